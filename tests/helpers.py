@@ -1,0 +1,129 @@
+"""Shared test scaffolding: turns a workload recipe into concrete seeded arrays and an
+oracle instance.  Inputs come from ``synth`` (structure + random values); edge weights and
+every expected value come from ``oracle`` only."""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+import oracle
+from synth import graphs, values
+from synth.configs import Workload, make_graph
+
+
+def to_bf16_grid(x: np.ndarray) -> np.ndarray:
+    """Nearest bf16-representable fp32 values (library rounding, used to make INPUTS exact in bf16)."""
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16).to(torch.float32).numpy()
+
+
+@dataclass
+class Problem:
+    w: Workload
+    row_ptr: np.ndarray
+    col: np.ndarray
+    val: np.ndarray
+    chunk_ptr: np.ndarray
+    dims: List[int]
+    W: List[np.ndarray]
+    b: List[np.ndarray]
+    x0: np.ndarray
+    hist: List[np.ndarray]
+    grad_out: np.ndarray
+    order: np.ndarray
+    h0: Optional[np.ndarray] = None
+    a: float = 0.0
+    beta: Optional[np.ndarray] = None
+    quant: bool = False
+    level0_f32: bool = False
+
+    @property
+    def n(self):
+        return self.row_ptr.shape[0] - 1
+
+    @property
+    def L(self):
+        return len(self.dims) - 1
+
+    def new_oracle(self, f64: bool = False) -> "oracle.OracleStage":
+        st = oracle.OracleStage(self.row_ptr, self.col,
+                                self.val if not f64 else oracle.gcn_norm(self.row_ptr, self.col, f64=True),
+                                self.chunk_ptr, self.dims, self.W, self.b,
+                                variant=self.w.variant, a=self.a, beta=self.beta, h0=self.h0,
+                                quant=self.quant and not f64, level0_f32=self.level0_f32, f64=f64)
+        st.cur[0][...] = self.x0
+        for j in range(self.L):
+            st.hist[j][...] = self.hist[j]
+        return st
+
+
+def gcnii_beta(first_layer: int, n_layers: int) -> np.ndarray:
+    """beta_l = ln(0.5 / l + 1), l = global 1-based layer index (benchmark definition)."""
+    return np.array([math.log(0.5 / l + 1.0) for l in range(first_layer, first_layer + n_layers)], dtype=np.float64)
+
+
+def make_problem(w: Workload, *, graph=None, chunk_ptr=None, order=None, bias_std: float = 0.1,
+                 first_stage: Optional[bool] = None, shuffle: bool = True, noise_std: float = 0.01) -> Problem:
+    row_ptr, col = graph if graph is not None else make_graph(w)
+    n = row_ptr.shape[0] - 1
+    val = oracle.gcn_norm(row_ptr, col)
+    if chunk_ptr is None:
+        chunk_ptr = graphs.equal_chunks(n, w.n_chunks)
+    K = chunk_ptr.shape[0] - 1
+    dims = list(w.dims)
+    L = len(dims) - 1
+    quant = w.dtype == "bf16"
+    if first_stage is None:
+        first_stage = w.variant == "gcn"
+    g = to_bf16_grid if quant else (lambda x: x)
+    g0 = (lambda x: x) if (w.level0_f32 or not quant) else to_bf16_grid
+    W = [g(values.glorot_uniform(w.seed, 100 + j, dims[j], dims[j + 1])) for j in range(L)]
+    if w.variant == "gcn":
+        b = [values.normal(w.seed, 200 + j, (dims[j + 1],), bias_std) if bias_std > 0
+             else np.zeros(dims[j + 1], np.float32) for j in range(L)]
+        x0 = g0(values.normal(w.seed, 1, (n, dims[0])))
+        h0, a, beta = None, 0.0, None
+    else:
+        b = [np.zeros(dims[j + 1], np.float32) for j in range(L)]
+        x0 = g0(values.half_normal(w.seed, 1, (n, dims[0])))
+        h0 = g(values.normal(w.seed, 2, (n, dims[0])))
+        a, beta = w.gcnii_alpha, gcnii_beta(w.gcnii_first_layer, L)
+    grad_out = g(values.normal(w.seed, 3, (n, dims[-1])))
+    if order is None:
+        order = values.permutation(w.seed, 4, K) if shuffle else np.arange(K, dtype=np.int32)
+    # historical buffers: a clean full-graph pass (one chunk => no staleness) plus N(0, noise_std^2)
+    clean = oracle.OracleStage(row_ptr, col, val, np.array([0, n], dtype=np.int64), dims, W, b,
+                               variant=w.variant, a=a, beta=beta, h0=h0, quant=quant, level0_f32=w.level0_f32)
+    clean.cur[0][...] = x0
+    clean.forward_pass([0])
+    hist = []
+    for j in range(L):
+        if j == 0 and first_stage:
+            hist.append(x0.copy())
+        else:
+            hj = clean.cur[j] + values.normal(w.seed, 300 + j, (n, dims[j]), noise_std)
+            hist.append(g0(hj) if j == 0 else g(hj))
+    return Problem(w, row_ptr, col, val, np.asarray(chunk_ptr, dtype=np.int64), dims, W, b, x0, hist, grad_out,
+                   np.asarray(order, dtype=np.int32), h0=h0, a=a, beta=beta, quant=quant,
+                   level0_f32=w.level0_f32 and quant)
+
+
+def run_oracle(p: Problem, need_input_grad: bool = True, f64: bool = False):
+    st = p.new_oracle(f64=f64)
+    st.forward_pass(p.order)
+    st.backward_pass(p.grad_out, need_input_grad)
+    return st
+
+
+def max_rel(x: np.ndarray, ref: np.ndarray) -> float:
+    """Per-tensor error measure used by every floating-point parity check:
+    max |x - ref| / max |ref| (relative error is undefined at the zeros ReLU produces)."""
+    ref = np.asarray(ref, dtype=np.float64)
+    x = np.asarray(x, dtype=np.float64)
+    denom = float(np.max(np.abs(ref))) if ref.size else 1.0
+    if denom == 0.0:
+        denom = 1.0
+    return float(np.max(np.abs(x - ref))) / denom if ref.size else 0.0
