@@ -1,0 +1,184 @@
+/*
+ * gnnstage — one pipeline stage of chunk-based pipelined full-graph GNN training on one
+ * MI355X (gfx950).  C ABI; no C++ or framework types cross this boundary.
+ *
+ * The stage owns L consecutive GNN layers and sweeps the whole graph chunk by chunk
+ * (Algorithm 1 of the paper, the loops over k, l and v in C_k).  For every destination
+ * row v of the chunk it aggregates the CSR neighbours u through the normalised adjacency,
+ * reading the CURRENT level-(l-1) row of u when u's chunk has already been started in this
+ * pass and the HISTORICAL row otherwise (Section 3.3), then applies the layer's dense
+ * update.  The backward pass walks the chunks in the reverse order and drops the gradient
+ * that would flow back from a not-yet-processed vertex (Section 3.4, third technique).
+ *
+ * Level j (0 <= j <= L) is the embedding after j of the stage's layers; level 0 is the
+ * stage input.  d_j = dims[j] is its width.  All matrices are dense row-major with
+ * leading dimension equal to their width.
+ *
+ * Pointers are tagged HOST or DEVICE below.  Everything the descriptor points to stays
+ * owned by the caller; DEVICE buffers must outlive the handle, HOST arrays are copied by
+ * gnnstage_create and may be freed afterwards.  The library allocates no device memory:
+ * all of its own device state lives in the caller-provided workspace.
+ *
+ * Every function returns GNNSTAGE_OK (0) or a negative GNNSTAGE_E* code and never throws
+ * or aborts; gnnstage_last_error gives a message for the last failure.
+ */
+#ifndef GNNSTAGE_H
+#define GNNSTAGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gnnstage gnnstage_t; /* opaque, owned by the library */
+
+enum {
+  GNNSTAGE_OK = 0,
+  GNNSTAGE_EINVAL = -1,  /* null pointer, bad shape / dtype / variant, malformed CSR or chunks */
+  GNNSTAGE_ERANGE = -2,  /* chunk id outside [0, n_chunks) */
+  GNNSTAGE_EORDER = -3,  /* call sequence violates the pass protocol (see below) */
+  GNNSTAGE_ENOMEM = -4,  /* workspace smaller than gnnstage_workspace_size() */
+  GNNSTAGE_EHIP = -5,    /* a HIP runtime call failed */
+  GNNSTAGE_ENOTSUP = -6  /* sizes beyond what the index packing supports */
+};
+
+enum { GNNSTAGE_GCN = 0, GNNSTAGE_GCNII = 1 };
+enum { GNNSTAGE_F32 = 0, GNNSTAGE_BF16 = 1 };
+
+/*
+ * Stage descriptor (the inputs of Algorithm 1 for one GPU: graph, chunks, the layers
+ * assigned to this GPU and their weights, plus the embedding buffers).
+ *
+ * variant GNNSTAGE_GCN   (Section 2.1):  z_v = sum_u A_vu src(u);  h'_v = ReLU(z_v W + b)
+ * variant GNNSTAGE_GCNII (benchmark definition; the paper only cites the model):
+ *     p_v = (1-alpha) z_v + alpha h0_v ;  h'_v = ReLU((1-beta_l) p_v + beta_l p_v W)
+ *     (all widths equal, no bias).
+ *
+ * dtype GNNSTAGE_F32 : levels, weights, gradients rows are fp32; fp32 arithmetic.
+ * dtype GNNSTAGE_BF16: levels, weights, gradient rows are bf16 (bias and all accumulators
+ *     fp32; products on the bf16 matrix cores with fp32 accumulation).  With level0_f32 != 0
+ *     level 0 (cur[0], hist[0], grad_in) is fp32 instead (a first stage fed with raw features).
+ */
+typedef struct {
+  /* graph: CSR of A_hat INCLUDING self-loops; row v lists the sources u of edges u->v (any
+   * order inside a row, no symmetry assumed).  HOST. */
+  int64_t n_vertices;
+  int64_t nnz;
+  const int64_t *row_ptr; /* HOST, n_vertices + 1 */
+  const int32_t *col_idx; /* HOST, nnz */
+  const float *edge_val;  /* HOST, nnz; NULL => 1/sqrt(D_v D_u), D = row length (Section 2.1) */
+  /* chunks: chunk c = vertex ids [chunk_ptr[c], chunk_ptr[c+1]); empty chunks allowed */
+  int32_t n_chunks;
+  const int64_t *chunk_ptr; /* HOST, n_chunks + 1, chunk_ptr[0] = 0, last = n_vertices */
+  /* layers */
+  int32_t n_layers;
+  const int32_t *dims; /* HOST, n_layers + 1 */
+  int32_t variant;
+  float alpha;       /* GCNII initial-residual weight */
+  const float *beta; /* HOST, n_layers; GCNII only (NULL for GCN) */
+  int32_t dtype;
+  int32_t level0_f32;
+  /* HOST arrays of DEVICE pointers */
+  void *const *W;      /* n_layers; W[j] is d_j x d_{j+1}; read when a pass starts (forward) and
+                          at each backward call; must not change inside a pass */
+  void *const *bias;   /* n_layers fp32 vectors d_{j+1}; GCN only (NULL for GCNII) */
+  void *const *cur;    /* n_layers + 1; n x d_j.  The caller fills level-0 rows of chunk c before
+                          stage_forward_chunk(c); the library writes rows of c at levels 1..L */
+  void *const *hist;   /* n_layers (levels 0..L-1); hist[0] may alias cur[0] (first stage) */
+  const void *h0;      /* DEVICE n x d, GCNII only */
+  float *const *dW;    /* n_layers fp32 d_j x d_{j+1}; "+=" over the backward calls; caller zeroes */
+  float *const *dbias; /* n_layers fp32 d_{j+1}; "+="; GCN only */
+  void *grad_in;       /* DEVICE n x d_0 (level-0 dtype); rows of chunk c written by its backward
+                          call; used only when need_input_grad != 0 */
+  float *grad_h0;      /* DEVICE fp32 n x d, "+="; GCNII only */
+  int32_t need_input_grad;
+  void *workspace;     /* DEVICE, 256-byte aligned, >= gnnstage_workspace_size() bytes */
+  size_t workspace_bytes;
+} gnnstage_desc;
+
+/* Device bytes the stage needs inside desc->workspace (graph tables, transposed index,
+ * launch schedule, saved aggregations for backward, gradient rows).  Host-only computation;
+ * returns 0 when the descriptor's sizes are invalid.  Reads row_ptr, col_idx, chunk_ptr and
+ * dims; no other pointer field is dereferenced. */
+size_t gnnstage_workspace_size(const gnnstage_desc *desc);
+
+/* Validates the descriptor, builds the transposed (CSC) index and the launch schedule on the
+ * host, uploads them into the workspace and synchronises.  *out is NULL on failure. */
+int gnnstage_create(const gnnstage_desc *desc, gnnstage_t **out);
+
+/*
+ * Forward work of one chunk: Algorithm 1, the body of the loop over k for this GPU's layers.
+ * pos_in_pass is the position of the chunk in this pass's processing order: 0 starts a new
+ * pass (V_processed <- empty) and the following calls must use 1, 2, ... with every chunk at
+ * most once (any permutation: Section 3.4 chunk shuffling).  The chunk counts as processed
+ * for its own aggregation.  Asynchronous on hip_stream (a hipStream_t; NULL = default stream).
+ * Errors: ERANGE (chunk id), EORDER (pos out of sequence, chunk seen twice).
+ */
+int stage_forward_chunk(gnnstage_t *st, int32_t chunk_id, int32_t pos_in_pass, void *hip_stream);
+
+/*
+ * Backward work of one chunk.  grad_out_rows: DEVICE, rows of the chunk at level L,
+ * (chunk rows) x d_L, level dtype.  Chunks must come in exactly the reverse of the forward
+ * order of a completed forward pass (otherwise EORDER): then a vertex is "processed" in the
+ * backward pass exactly when it read current values in the forward pass, and the zero rule of
+ * Section 3.4 yields the gradient of the chunked forward with history held constant.
+ * Accumulates dW, dbias (and grad_h0), writes grad_in rows of the chunk when requested.
+ */
+int stage_backward_chunk(gnnstage_t *st, int32_t chunk_id, const void *grad_out_rows, void *hip_stream);
+
+/* hist[j] <- cur[j] for j < L, all rows (Section 3.4, second technique: when to call it, i.e.
+ * the refresh period, is caller policy).  Levels whose hist pointer aliases cur are skipped. */
+int update_history(gnnstage_t *st, void *hip_stream);
+
+/* Synchronises the device and frees the handle (the workspace stays with the caller). */
+int gnnstage_destroy(gnnstage_t *st);
+
+/* Message for the last error on this handle (or, with NULL, of the last failed create). */
+const char *gnnstage_last_error(const gnnstage_t *st);
+
+/*
+ * Diagnostics for bit-exact tests of the V_processed bookkeeping (Section 3.3): for every row
+ * of the chunk, the number of neighbours that WOULD be read from the current buffers if the
+ * chunk were aggregated now (processed set as it stands, the chunk itself included).  Pure
+ * host computation on the library's own packed tables.  out: HOST, chunk rows.
+ */
+int gnnstage_debug_select_counts(gnnstage_t *st, int32_t chunk_id, int32_t *out);
+
+/*
+ * Host-only planning helpers (no GPU needed), exported so that the integer bookkeeping can be
+ * checked on a CPU: the transposed index (column u -> rows v ascending, with the position of
+ * each entry in the CSR arrays) and the packed column words (vertex id | chunk id << vbits).
+ */
+int gnnstage_plan_transpose(int64_t n, const int64_t *row_ptr, const int32_t *col_idx,
+                            int64_t *t_ptr, int32_t *t_row, int64_t *t_edge);
+int gnnstage_plan_pack(int64_t n, int64_t nnz, const int32_t *idx, int32_t n_chunks,
+                       const int64_t *chunk_ptr, uint32_t *packed, int32_t *vbits);
+/* Launch schedule of one aggregation over rows [row_begin, row_end): every row with at most
+ * split_edges entries is one task, longer rows are cut into pieces of split_edges.  Returns the
+ * number of tasks (or a negative code); with non-NULL arrays also fills them (capacity checked).
+ * task_row: row id; task_e0: first entry; task_ne: entry count; task_slot: -1 for a whole row,
+ * else the index of the fp32 partial-sum slot the piece writes. */
+int64_t gnnstage_plan_tasks(const int64_t *ptr, int64_t row_begin, int64_t row_end, int32_t split_edges,
+                            int64_t capacity, int32_t *task_row, int64_t *task_e0, int32_t *task_ne,
+                            int32_t *task_slot, int64_t *n_slots);
+
+/*
+ * Per-kernel timing with HIP events on the launch stream.  kind: 0 forward aggregation,
+ * 1 forward transform, 2 backward transposed aggregation, 3 input-gradient GEMM,
+ * 4 weight-gradient GEMM (+bias gradient), 5 history copy, 6 other (masks, weight staging).
+ * gnnstage_profile_read synchronises, then returns summed milliseconds and launch count.
+ */
+enum { GNNSTAGE_NKINDS = 7 };
+int gnnstage_profile_enable(gnnstage_t *st, int32_t on);
+int gnnstage_profile_read(gnnstage_t *st, int32_t kind, double *ms, int64_t *launches);
+int gnnstage_profile_reset(gnnstage_t *st);
+
+/* Library version, e.g. 100 = 0.1.0 */
+int gnnstage_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GNNSTAGE_H */

@@ -1,0 +1,10 @@
+"""gnnstage: one pipeline stage of chunk-based pipelined GNN training on one MI355X.
+
+The work is done by hand-written HIP kernels in ``libgnnstage.so`` (C ABI declared in
+``include/gnnstage.h``); this package only marshals arguments.  There is no CPU fallback:
+importing :mod:`binding` raises if the library has not been built.
+"""
+from .binding import (  # noqa: F401
+    GNNSTAGE_BF16, GNNSTAGE_F32, GNNSTAGE_GCN, GNNSTAGE_GCNII, GnnStage, GnnStageError, KIND_NAMES,
+    gnnstage_plan_pack, gnnstage_plan_tasks, gnnstage_plan_transpose, gnnstage_version, lib,
+)

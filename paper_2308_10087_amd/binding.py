@@ -1,0 +1,265 @@
+"""ctypes binding of libgnnstage.so: same names as the C ABI, argument marshalling only.
+
+PyTorch supplies device memory and the stream handle; no arithmetic of the method happens
+in Python.  ``GnnStage`` keeps the tensors a stage points at alive and forwards each call.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libgnnstage.so")
+
+GNNSTAGE_GCN, GNNSTAGE_GCNII = 0, 1
+GNNSTAGE_F32, GNNSTAGE_BF16 = 0, 1
+KIND_NAMES = ["spmm_fwd", "gemm_fwd", "spmm_bwd", "gemm_dgrad", "gemm_wgrad", "history_copy", "other"]
+_ERRORS = {-1: "EINVAL", -2: "ERANGE", -3: "EORDER", -4: "ENOMEM", -5: "EHIP", -6: "ENOTSUP"}
+
+
+class GnnStageError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"gnnstage error {_ERRORS.get(code, code)}: {msg}")
+        self.code = code
+
+
+class gnnstage_desc(C.Structure):
+    _fields_ = [
+        ("n_vertices", C.c_int64), ("nnz", C.c_int64),
+        ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("edge_val", C.c_void_p),
+        ("n_chunks", C.c_int32), ("chunk_ptr", C.c_void_p),
+        ("n_layers", C.c_int32), ("dims", C.c_void_p),
+        ("variant", C.c_int32), ("alpha", C.c_float), ("beta", C.c_void_p),
+        ("dtype", C.c_int32), ("level0_f32", C.c_int32),
+        ("W", C.c_void_p), ("bias", C.c_void_p), ("cur", C.c_void_p), ("hist", C.c_void_p),
+        ("h0", C.c_void_p), ("dW", C.c_void_p), ("dbias", C.c_void_p),
+        ("grad_in", C.c_void_p), ("grad_h0", C.c_void_p), ("need_input_grad", C.c_int32),
+        ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+    ]
+
+
+def _load():
+    # The process must hold ONE HIP runtime.  PyTorch ships its own libamdhip64; importing torch
+    # first makes the dynamic loader resolve this library's libamdhip64.so.7 dependency to the copy
+    # that is already loaded, so both share the device context and the streams.
+    import torch  # noqa: F401
+
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2308_10087_amd.build` "
+            "(there is no CPU fallback for the stage kernels)")
+    lib = C.CDLL(_LIB_PATH)
+    lib.gnnstage_version.restype = C.c_int
+    lib.gnnstage_workspace_size.restype = C.c_size_t
+    lib.gnnstage_workspace_size.argtypes = [C.POINTER(gnnstage_desc)]
+    lib.gnnstage_create.restype = C.c_int
+    lib.gnnstage_create.argtypes = [C.POINTER(gnnstage_desc), C.POINTER(C.c_void_p)]
+    lib.stage_forward_chunk.restype = C.c_int
+    lib.stage_forward_chunk.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+    lib.stage_backward_chunk.restype = C.c_int
+    lib.stage_backward_chunk.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.update_history.restype = C.c_int
+    lib.update_history.argtypes = [C.c_void_p, C.c_void_p]
+    lib.gnnstage_destroy.restype = C.c_int
+    lib.gnnstage_destroy.argtypes = [C.c_void_p]
+    lib.gnnstage_last_error.restype = C.c_char_p
+    lib.gnnstage_last_error.argtypes = [C.c_void_p]
+    lib.gnnstage_debug_select_counts.restype = C.c_int
+    lib.gnnstage_debug_select_counts.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+    lib.gnnstage_plan_transpose.restype = C.c_int
+    lib.gnnstage_plan_transpose.argtypes = [C.c_int64] + [C.c_void_p] * 5
+    lib.gnnstage_plan_pack.restype = C.c_int
+    lib.gnnstage_plan_pack.argtypes = [C.c_int64, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                       C.POINTER(C.c_int32)]
+    lib.gnnstage_plan_tasks.restype = C.c_int64
+    lib.gnnstage_plan_tasks.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_void_p, C.POINTER(C.c_int64)]
+    lib.gnnstage_profile_enable.restype = C.c_int
+    lib.gnnstage_profile_enable.argtypes = [C.c_void_p, C.c_int32]
+    lib.gnnstage_profile_read.restype = C.c_int
+    lib.gnnstage_profile_read.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    lib.gnnstage_profile_reset.restype = C.c_int
+    lib.gnnstage_profile_reset.argtypes = [C.c_void_p]
+    return lib
+
+
+lib = _load()
+
+
+def gnnstage_version() -> int:
+    return int(lib.gnnstage_version())
+
+
+# ---- host-only planning helpers (no GPU needed) -----------------------------------------
+def gnnstage_plan_transpose(row_ptr: np.ndarray, col_idx: np.ndarray):
+    row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int64)
+    col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
+    n, nnz = row_ptr.shape[0] - 1, col_idx.shape[0]
+    t_ptr = np.zeros(n + 1, dtype=np.int64)
+    t_row = np.zeros(nnz, dtype=np.int32)
+    t_edge = np.zeros(nnz, dtype=np.int64)
+    rc = lib.gnnstage_plan_transpose(n, row_ptr.ctypes.data, col_idx.ctypes.data, t_ptr.ctypes.data,
+                                     t_row.ctypes.data, t_edge.ctypes.data)
+    if rc != 0:
+        raise GnnStageError(rc, "gnnstage_plan_transpose")
+    return t_ptr, t_row, t_edge
+
+
+def gnnstage_plan_pack(n: int, idx: np.ndarray, chunk_ptr: np.ndarray):
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    chunk_ptr = np.ascontiguousarray(chunk_ptr, dtype=np.int64)
+    packed = np.zeros(idx.shape[0], dtype=np.uint32)
+    vbits = C.c_int32(0)
+    rc = lib.gnnstage_plan_pack(n, idx.shape[0], idx.ctypes.data, chunk_ptr.shape[0] - 1, chunk_ptr.ctypes.data,
+                                packed.ctypes.data, C.byref(vbits))
+    if rc != 0:
+        raise GnnStageError(rc, "gnnstage_plan_pack")
+    return packed, int(vbits.value)
+
+
+def gnnstage_plan_tasks(ptr: np.ndarray, row_begin: int, row_end: int, split_edges: int):
+    ptr = np.ascontiguousarray(ptr, dtype=np.int64)
+    ns = C.c_int64(0)
+    n = lib.gnnstage_plan_tasks(ptr.ctypes.data, row_begin, row_end, split_edges, 0, None, None, None, None, C.byref(ns))
+    if n < 0:
+        raise GnnStageError(int(n), "gnnstage_plan_tasks")
+    row, e0 = np.zeros(n, np.int32), np.zeros(n, np.int64)
+    ne, slot = np.zeros(n, np.int32), np.zeros(n, np.int32)
+    got = lib.gnnstage_plan_tasks(ptr.ctypes.data, row_begin, row_end, split_edges, n, row.ctypes.data, e0.ctypes.data,
+                                  ne.ctypes.data, slot.ctypes.data, C.byref(ns))
+    if got != n:
+        raise GnnStageError(int(got), "gnnstage_plan_tasks")
+    return row, e0, ne, slot, int(ns.value)
+
+
+def _ptrs(tensors: Sequence) -> "C.Array":
+    arr = (C.c_void_p * max(len(tensors), 1))()
+    for i, t in enumerate(tensors):
+        arr[i] = None if t is None else t.data_ptr()
+    return arr
+
+
+class GnnStage:
+    """A stage handle plus the tensors it points at.
+
+    ``cur`` / ``hist`` / ``W`` / ``bias`` / ``dW`` / ``dbias`` are lists of CUDA(HIP) tensors owned by
+    the caller; the workspace is allocated here with ``torch.empty`` (device memory only).
+    """
+
+    def __init__(self, row_ptr, col_idx, chunk_ptr, dims, *, W, cur, hist, dW, bias=None, dbias=None,
+                 edge_val=None, variant=GNNSTAGE_GCN, alpha=0.0, beta=None, h0=None, grad_h0=None,
+                 dtype=GNNSTAGE_F32, level0_f32=False, grad_in=None, device="cuda:0"):
+        import torch
+
+        self._torch = torch
+        self.row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int64)
+        self.col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
+        self.chunk_ptr = np.ascontiguousarray(chunk_ptr, dtype=np.int64)
+        self.dims = np.ascontiguousarray(dims, dtype=np.int32)
+        self.edge_val = None if edge_val is None else np.ascontiguousarray(edge_val, dtype=np.float32)
+        self.beta = None if beta is None else np.ascontiguousarray(beta, dtype=np.float32)
+        self.n, self.nnz = self.row_ptr.shape[0] - 1, self.col_idx.shape[0]
+        self.K, self.L = self.chunk_ptr.shape[0] - 1, self.dims.shape[0] - 1
+        self.W, self.cur, self.hist, self.dW = list(W), list(cur), list(hist), list(dW)
+        self.bias = None if bias is None else list(bias)
+        self.dbias = None if dbias is None else list(dbias)
+        self.h0, self.grad_h0, self.grad_in = h0, grad_h0, grad_in
+        self._keep = [_ptrs(self.W), _ptrs(self.cur), _ptrs(self.hist), _ptrs(self.dW),
+                      None if self.bias is None else _ptrs(self.bias),
+                      None if self.dbias is None else _ptrs(self.dbias)]
+        d = gnnstage_desc()
+        d.n_vertices, d.nnz = self.n, self.nnz
+        d.row_ptr, d.col_idx = self.row_ptr.ctypes.data, self.col_idx.ctypes.data
+        d.edge_val = None if self.edge_val is None else self.edge_val.ctypes.data
+        d.n_chunks, d.chunk_ptr = self.K, self.chunk_ptr.ctypes.data
+        d.n_layers, d.dims = self.L, self.dims.ctypes.data
+        d.variant, d.alpha = int(variant), float(alpha)
+        d.beta = None if self.beta is None else self.beta.ctypes.data
+        d.dtype, d.level0_f32 = int(dtype), int(bool(level0_f32))
+        vp = lambda a: None if a is None else C.cast(a, C.c_void_p)
+        d.W, d.cur, d.hist, d.dW = vp(self._keep[0]), vp(self._keep[1]), vp(self._keep[2]), vp(self._keep[3])
+        d.bias, d.dbias = vp(self._keep[4]), vp(self._keep[5])
+        d.h0 = None if h0 is None else h0.data_ptr()
+        d.grad_h0 = None if grad_h0 is None else grad_h0.data_ptr()
+        d.grad_in = None if grad_in is None else grad_in.data_ptr()
+        d.need_input_grad = int(grad_in is not None)
+        size = int(lib.gnnstage_workspace_size(C.byref(d)))
+        if size == 0:
+            raise GnnStageError(-1, lib.gnnstage_last_error(None).decode())
+        self.workspace_bytes = size
+        self.workspace = torch.empty(size, dtype=torch.uint8, device=device)
+        d.workspace, d.workspace_bytes = self.workspace.data_ptr(), size
+        self._desc = d
+        h = C.c_void_p(None)
+        rc = lib.gnnstage_create(C.byref(d), C.byref(h))
+        if rc != 0:
+            raise GnnStageError(rc, lib.gnnstage_last_error(None).decode())
+        self._h = h
+
+    # -- same names as the C ABI -------------------------------------------------------------
+    def _check(self, rc: int):
+        if rc != 0:
+            raise GnnStageError(rc, lib.gnnstage_last_error(self._h).decode())
+
+    def _stream(self, stream):
+        if stream is None:
+            stream = self._torch.cuda.current_stream()
+        return C.c_void_p(stream.cuda_stream)
+
+    def stage_forward_chunk(self, chunk_id: int, pos_in_pass: int, stream=None) -> None:
+        self._check(lib.stage_forward_chunk(self._h, int(chunk_id), int(pos_in_pass), self._stream(stream)))
+
+    def stage_backward_chunk(self, chunk_id: int, grad_out_rows, stream=None) -> None:
+        ptr = None if grad_out_rows is None else grad_out_rows.data_ptr()
+        self._check(lib.stage_backward_chunk(self._h, int(chunk_id), ptr, self._stream(stream)))
+
+    def update_history(self, stream=None) -> None:
+        self._check(lib.update_history(self._h, self._stream(stream)))
+
+    def gnnstage_debug_select_counts(self, chunk_id: int) -> np.ndarray:
+        rows = max(int(self.chunk_ptr[chunk_id + 1] - self.chunk_ptr[chunk_id]), 0) if 0 <= chunk_id < self.K else 0
+        out = np.zeros(max(rows, 1), dtype=np.int32)
+        self._check(lib.gnnstage_debug_select_counts(self._h, int(chunk_id), out.ctypes.data))
+        return out[:rows]
+
+    def gnnstage_profile_enable(self, on: bool) -> None:
+        self._check(lib.gnnstage_profile_enable(self._h, int(on)))
+
+    def gnnstage_profile_reset(self) -> None:
+        self._check(lib.gnnstage_profile_reset(self._h))
+
+    def gnnstage_profile_read(self) -> dict:
+        out = {}
+        for kind, name in enumerate(KIND_NAMES):
+            ms, n = C.c_double(0), C.c_int64(0)
+            self._check(lib.gnnstage_profile_read(self._h, kind, C.byref(ms), C.byref(n)))
+            out[name] = (float(ms.value), int(n.value))
+        return out
+
+    def gnnstage_destroy(self) -> None:
+        if getattr(self, "_h", None) is not None and self._h.value is not None:
+            rc = lib.gnnstage_destroy(self._h)
+            self._h = C.c_void_p(None)
+            if rc != 0:
+                raise GnnStageError(rc, "gnnstage_destroy")
+
+    def __del__(self):
+        try:
+            self.gnnstage_destroy()
+        except Exception:
+            pass
+
+    # -- conveniences built only from the calls above ----------------------------------------
+    def rows(self, k: int) -> slice:
+        return slice(int(self.chunk_ptr[k]), int(self.chunk_ptr[k + 1]))
+
+    def forward_pass(self, order, stream=None) -> None:
+        for pos, k in enumerate(order):
+            self.stage_forward_chunk(int(k), pos, stream)
+
+    def backward_pass(self, order, grad_out, stream=None) -> None:
+        for k in reversed(list(order)):
+            self.stage_backward_chunk(int(k), grad_out[self.rows(int(k))], stream)

@@ -1,0 +1,121 @@
+// Shared declarations of the gnnstage HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __bf16 bf16_t;
+
+// Which chunks count as processed (Section 3.3, V_processed), one bit per chunk id.
+// Passed by value as a kernel argument; supports up to 256 chunks.
+struct ChunkMask {
+  uint64_t w[4];
+};
+constexpr int kMaxChunks = 256;
+
+__host__ __device__ inline bool mask_test(const ChunkMask &m, uint32_t c) {
+  return (m.w[(c >> 6) & 3] >> (c & 63)) & 1ull;
+}
+
+// ---- aggregation (SpMM with current/history select) ---------------------------------
+enum SpmmEpilogue : int {
+  SPMM_PLAIN = 0,  // out = acc
+  SPMM_MIX = 1,    // out = s_acc * acc + s_aux * aux[row]      (GCNII initial residual)
+  SPMM_MASK = 2    // out = aux[row] > 0 ? acc : 0              (ReLU derivative on the way back)
+};
+
+struct SpmmArgs {
+  // sparse structure: packed index words (vertex | chunk << vbits) and weights
+  const uint32_t *pidx;
+  const float *val;
+  // launch schedule
+  const int32_t *task_row;
+  const int64_t *task_e0;
+  const int32_t *task_ne;
+  const int32_t *task_slot;
+  int64_t n_tasks;
+  // long rows: pieces summed by the reduce kernel
+  const int32_t *lr_row;
+  const int32_t *lr_slot0;
+  const int32_t *lr_nslots;
+  int64_t n_long;
+  float *partial;  // [n_slots][d] fp32
+  // gathered operand: rows of width d, leading dimension src_ld
+  const void *src_sel;    // read when the neighbour's chunk is in the mask
+  const void *src_unsel;  // read otherwise; nullptr => the entry contributes zero
+  int32_t d;
+  int32_t src_ld;
+  int32_t vbits;
+  ChunkMask mask;
+  // output rows: out[(row - out_row0) * out_ld + c], c < d; columns [d, out_ld) get zeros
+  void *out;
+  int32_t out_ld;
+  int64_t out_row0;
+  // epilogue
+  int32_t epilogue;
+  const void *aux;  // indexed by absolute row, leading dimension aux_ld, same dtype as src
+  int32_t aux_ld;
+  float s_acc, s_aux;
+};
+
+enum DType : int { DT_F32 = 0, DT_BF16 = 1 };
+
+// src dtype -> out dtype; returns hipError_t as int
+int launch_spmm(const SpmmArgs &a, int src_dtype, int out_dtype, hipStream_t s);
+
+// ---- dense transforms -------------------------------------------------------------------
+enum GemmEpilogue : int {
+  EPI_FWD_GCN = 0,    // out = ReLU(acc + bias[n])
+  EPI_FWD_GCNII = 1,  // out = ReLU((1-beta) aux[m][n] + beta acc)
+  EPI_DGRAD_GCN = 2,  // out = acc
+  EPI_DGRAD_GCNII = 3 // dp = (1-beta) aux[m][n] + beta acc; out = (1-alpha) dp; h0grad[m][n] += alpha dp
+};
+
+// C[M x N] = A[M x Kp] . Bt[N x Kp]^T  (both operands K-contiguous, zero padded to Kp, Kp % 8 == 0)
+struct GemmNtArgs {
+  const void *A;
+  int32_t lda;
+  const void *Bt;
+  int32_t ldb;
+  int32_t M, N, Kp;
+  int32_t epilogue;
+  const float *bias;
+  const void *aux;  // compute dtype
+  int32_t aux_ld;
+  float alpha, beta;
+  float *h0grad;  // fp32, pre-offset to the first row
+  int32_t h0_ld;
+  void *out;
+  int32_t out_ld;
+};
+int launch_gemm_nt(const GemmNtArgs &a, int compute_dtype, int out_dtype, hipStream_t s);
+
+// dW[I x O] += scale * A[M x I]^T . B[M x O]   (reduction over the M rows of the chunk)
+struct GemmTnArgs {
+  const void *A;
+  int32_t lda;
+  const void *B;
+  int32_t ldb;
+  int32_t M, I, O;
+  float scale;
+  float *dW;       // fp32 [I][O]
+  float *partial;  // fp32 scratch [splits][I][O]
+  int32_t max_splits;
+  float *dbias;          // optional: dbias[O] += column sums of B
+  float *bias_partial;   // fp32 scratch [splits][O]
+};
+int launch_gemm_tn(const GemmTnArgs &a, int compute_dtype, hipStream_t s);
+
+// ---- small kernels ------------------------------------------------------------------------
+// Wt[N][Kp] (transposed) and Wn[K][Np] (plain) zero-padded copies of W[K][N] in the compute dtype
+int launch_stage_weights(const void *W, int w_dtype, int K, int N, void *Wt, int Kp, void *Wn, int Np,
+                         hipStream_t s);
+// dY[m][c] = level[m][c] > 0 ? g[m][c] : 0 for c < d, zeros up to out_ld
+int launch_relu_mask(const void *g, const void *level, int dtype, int64_t M, int d, void *out, int out_ld,
+                     hipStream_t s);
+int launch_copy(const void *src, void *dst, size_t bytes, hipStream_t s);
+int launch_fill_zero(void *dst, size_t bytes, hipStream_t s);
+// symmetric normalisation weights from row lengths: val[e] = 1/sqrt(len(row) * len(other))
+int launch_gcn_norm(const int64_t *ptr, const uint32_t *pidx, int vbits, const int64_t *len_ptr, int64_t n,
+                    float *val, hipStream_t s);
+
+static inline int round_up(int x, int m) { return (x + m - 1) / m * m; }

@@ -1,0 +1,743 @@
+// C-ABI entry points of the stage library: descriptor validation, workspace layout, host
+// planning at create time, and the per-chunk launch sequences (Algorithm 1's inner loops and
+// the matching backward pass).  All device work is issued on the caller's stream.
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <algorithm>
+#include <string>
+#include <vector>
+
+#include "../../include/gnnstage.h"
+#include "common.h"
+
+namespace {
+
+constexpr int kMaxSplits = 64;
+constexpr size_t kAlign = 256;
+
+std::string g_create_error;
+
+int split_edges_setting() {
+  const char *e = getenv("GNNSTAGE_SPLIT_EDGES");
+  if (e) {
+    const int v = atoi(e);
+    if (v >= 64) return v;
+  }
+  return 2048;
+}
+
+struct TaskList {
+  int64_t n_tasks = 0, n_long = 0, n_slots = 0;
+  int32_t *task_row = nullptr;
+  int64_t *task_e0 = nullptr;
+  int32_t *task_ne = nullptr;
+  int32_t *task_slot = nullptr;
+  int32_t *lr_row = nullptr, *lr_slot0 = nullptr, *lr_nslots = nullptr;
+};
+
+// Sizes that depend only on row lengths: number of tasks / long rows / slots of every chunk.
+struct PlanCounts {
+  std::vector<int64_t> tasks, longs, slots;
+  int64_t total_tasks = 0, total_longs = 0, max_slots = 0;
+};
+
+PlanCounts count_plan(const int64_t *ptr, const std::vector<int64_t> &chunk_ptr, int split) {
+  PlanCounts pc;
+  const int K = (int)chunk_ptr.size() - 1;
+  pc.tasks.assign(K, 0);
+  pc.longs.assign(K, 0);
+  pc.slots.assign(K, 0);
+  for (int c = 0; c < K; ++c) {
+    for (int64_t r = chunk_ptr[c]; r < chunk_ptr[c + 1]; ++r) {
+      const int64_t len = ptr[r + 1] - ptr[r];
+      if (len > split) {
+        const int64_t pieces = (len + split - 1) / split;
+        pc.tasks[c] += pieces;
+        pc.slots[c] += pieces;
+        pc.longs[c] += 1;
+      } else {
+        pc.tasks[c] += 1;
+      }
+    }
+    pc.total_tasks += pc.tasks[c];
+    pc.total_longs += pc.longs[c];
+    if (pc.slots[c] > pc.max_slots) pc.max_slots = pc.slots[c];
+  }
+  return pc;
+}
+
+struct Bump {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    const size_t at = off;
+    off += (bytes + kAlign - 1) / kAlign * kAlign;
+    return at;
+  }
+};
+
+struct Layout {
+  size_t row_ptr, pcol, val, t_ptr, prow, tval;
+  size_t f_task_row, f_task_e0, f_task_ne, f_task_slot, f_lr_row, f_lr_slot0, f_lr_n;
+  size_t b_task_row, b_task_e0, b_task_ne, b_task_slot, b_lr_row, b_lr_slot0, b_lr_n;
+  size_t partial;
+  std::vector<size_t> Z, dZ, Wt, Wn;
+  size_t G[2];
+  size_t gemm_partial, bias_partial;
+  size_t total;
+};
+
+struct Shape {
+  int64_t n = 0, nnz = 0;
+  int K = 0, L = 0;
+  std::vector<int64_t> chunk_ptr;
+  std::vector<int> dims, ld;
+  int dtype = 0, level0_f32 = 0, variant = 0, need_input_grad = 0;
+  int elt() const { return dtype == GNNSTAGE_BF16 ? 2 : 4; }
+  int64_t max_rows() const {
+    int64_t m = 0;
+    for (int c = 0; c < K; ++c) m = std::max<int64_t>(m, chunk_ptr[c + 1] - chunk_ptr[c]);
+    return m;
+  }
+};
+
+bool read_shape(const gnnstage_desc *d, Shape &s, std::string &err) {
+  if (!d) { err = "descriptor is NULL"; return false; }
+  if (d->n_vertices <= 0 || d->nnz < 0) { err = "n_vertices must be positive and nnz non-negative"; return false; }
+  if (!d->row_ptr || !d->chunk_ptr || !d->dims) { err = "row_ptr, chunk_ptr and dims must not be NULL"; return false; }
+  if (d->n_chunks <= 0 || d->n_chunks > kMaxChunks) { err = "n_chunks must be in [1, 256]"; return false; }
+  if (d->n_layers <= 0 || d->n_layers > 1024) { err = "n_layers must be in [1, 1024]"; return false; }
+  if (d->dtype != GNNSTAGE_F32 && d->dtype != GNNSTAGE_BF16) { err = "unknown dtype"; return false; }
+  if (d->variant != GNNSTAGE_GCN && d->variant != GNNSTAGE_GCNII) { err = "unknown variant"; return false; }
+  s.n = d->n_vertices;
+  s.nnz = d->nnz;
+  s.K = d->n_chunks;
+  s.L = d->n_layers;
+  s.dtype = d->dtype;
+  s.level0_f32 = (d->dtype == GNNSTAGE_BF16 && d->level0_f32) ? 1 : 0;
+  s.variant = d->variant;
+  s.need_input_grad = d->need_input_grad ? 1 : 0;
+  s.chunk_ptr.assign(d->chunk_ptr, d->chunk_ptr + s.K + 1);
+  if (s.chunk_ptr[0] != 0 || s.chunk_ptr[s.K] != s.n) { err = "chunk_ptr must start at 0 and end at n_vertices"; return false; }
+  for (int c = 0; c < s.K; ++c)
+    if (s.chunk_ptr[c] > s.chunk_ptr[c + 1]) { err = "chunk_ptr must be non-decreasing"; return false; }
+  s.dims.assign(d->dims, d->dims + s.L + 1);
+  s.ld.resize(s.L + 1);
+  for (int j = 0; j <= s.L; ++j) {
+    if (s.dims[j] <= 0 || s.dims[j] > (1 << 20)) { err = "every level width must be in [1, 2^20]"; return false; }
+    if (s.dtype == GNNSTAGE_BF16 && (s.dims[j] & 1) && !(j == 0 && s.level0_f32)) {
+      err = "bf16 levels need an even width";
+      return false;
+    }
+    s.ld[j] = round_up(s.dims[j], 8);
+  }
+  if (s.variant == GNNSTAGE_GCNII) {
+    for (int j = 1; j <= s.L; ++j)
+      if (s.dims[j] != s.dims[0]) { err = "GCNII needs equal widths at every level"; return false; }
+    if (s.level0_f32) { err = "GCNII does not take an fp32 level 0"; return false; }
+  }
+  if (d->row_ptr[0] != 0 || d->row_ptr[s.n] != s.nnz) { err = "row_ptr must start at 0 and end at nnz"; return false; }
+  for (int64_t v = 0; v < s.n; ++v)
+    if (d->row_ptr[v] > d->row_ptr[v + 1]) { err = "row_ptr must be non-decreasing"; return false; }
+  return true;
+}
+
+// column occupancy of the transposed index without building it
+std::vector<int64_t> transposed_ptr(const gnnstage_desc *d, const Shape &s, std::string &err) {
+  std::vector<int64_t> t((size_t)s.n + 1, 0);
+  if (s.nnz > 0 && !d->col_idx) { err = "col_idx is NULL"; return {}; }
+  for (int64_t e = 0; e < s.nnz; ++e) {
+    const int64_t u = d->col_idx[e];
+    if (u < 0 || u >= s.n) { err = "col_idx entry out of range"; return {}; }
+    t[(size_t)u + 1]++;
+  }
+  for (int64_t i = 0; i < s.n; ++i) t[i + 1] += t[i];
+  return t;
+}
+
+Layout make_layout(const Shape &s, const PlanCounts &f, const PlanCounts &b) {
+  Layout l;
+  Bump w;
+  l.row_ptr = w.take(sizeof(int64_t) * (s.n + 1));
+  l.pcol = w.take(sizeof(uint32_t) * s.nnz);
+  l.val = w.take(sizeof(float) * s.nnz);
+  l.t_ptr = w.take(sizeof(int64_t) * (s.n + 1));
+  l.prow = w.take(sizeof(uint32_t) * s.nnz);
+  l.tval = w.take(sizeof(float) * s.nnz);
+  l.f_task_row = w.take(sizeof(int32_t) * f.total_tasks);
+  l.f_task_e0 = w.take(sizeof(int64_t) * f.total_tasks);
+  l.f_task_ne = w.take(sizeof(int32_t) * f.total_tasks);
+  l.f_task_slot = w.take(sizeof(int32_t) * f.total_tasks);
+  l.f_lr_row = w.take(sizeof(int32_t) * f.total_longs);
+  l.f_lr_slot0 = w.take(sizeof(int32_t) * f.total_longs);
+  l.f_lr_n = w.take(sizeof(int32_t) * f.total_longs);
+  l.b_task_row = w.take(sizeof(int32_t) * b.total_tasks);
+  l.b_task_e0 = w.take(sizeof(int64_t) * b.total_tasks);
+  l.b_task_ne = w.take(sizeof(int32_t) * b.total_tasks);
+  l.b_task_slot = w.take(sizeof(int32_t) * b.total_tasks);
+  l.b_lr_row = w.take(sizeof(int32_t) * b.total_longs);
+  l.b_lr_slot0 = w.take(sizeof(int32_t) * b.total_longs);
+  l.b_lr_n = w.take(sizeof(int32_t) * b.total_longs);
+  int max_d = 0, max_ld = 0;
+  size_t max_io = 0;
+  for (int j = 0; j <= s.L; ++j) {
+    max_d = std::max(max_d, s.dims[j]);
+    max_ld = std::max(max_ld, s.ld[j]);
+  }
+  for (int j = 0; j < s.L; ++j) max_io = std::max(max_io, (size_t)s.dims[j] * s.dims[j + 1]);
+  l.partial = w.take(sizeof(float) * (size_t)std::max(f.max_slots, b.max_slots) * max_d);
+  const size_t elt = s.elt();
+  l.Z.resize(s.L);
+  l.dZ.resize(s.L);
+  l.Wt.resize(s.L);
+  l.Wn.resize(s.L);
+  for (int j = 0; j < s.L; ++j) l.Z[j] = w.take((size_t)s.n * s.ld[j] * elt);
+  for (int j = 0; j < s.L; ++j) l.dZ[j] = (j == 0 && !s.need_input_grad) ? 0 : w.take((size_t)s.n * s.ld[j] * elt);
+  for (int j = 0; j < s.L; ++j) {
+    l.Wt[j] = w.take((size_t)s.dims[j + 1] * s.ld[j] * elt);
+    l.Wn[j] = w.take((size_t)s.dims[j] * s.ld[j + 1] * elt);
+  }
+  l.G[0] = w.take((size_t)s.max_rows() * max_ld * elt);
+  l.G[1] = w.take((size_t)s.max_rows() * max_ld * elt);
+  l.gemm_partial = w.take(sizeof(float) * kMaxSplits * max_io);
+  l.bias_partial = w.take(sizeof(float) * kMaxSplits * max_d);
+  l.total = w.off;
+  return l;
+}
+
+struct Profiler {
+  bool on = false;
+  struct Rec { int kind; hipEvent_t a, b; };
+  std::vector<Rec> recs;
+  std::vector<hipEvent_t> free_events;
+  double ms[GNNSTAGE_NKINDS] = {0};
+  int64_t launches[GNNSTAGE_NKINDS] = {0};
+  hipEvent_t get() {
+    if (!free_events.empty()) {
+      hipEvent_t e = free_events.back();
+      free_events.pop_back();
+      return e;
+    }
+    hipEvent_t e = nullptr;
+    (void)hipEventCreate(&e);
+    return e;
+  }
+  void collect() {
+    for (auto &r : recs) {
+      float t = 0.f;
+      if (hipEventElapsedTime(&t, r.a, r.b) == hipSuccess) {
+        ms[r.kind] += t;
+        launches[r.kind] += 1;
+      }
+      free_events.push_back(r.a);
+      free_events.push_back(r.b);
+    }
+    recs.clear();
+  }
+  void destroy() {
+    collect();
+    for (auto e : free_events) (void)hipEventDestroy(e);
+    free_events.clear();
+  }
+};
+
+}  // namespace
+
+struct gnnstage {
+  Shape s;
+  Layout lay;
+  int vbits = 0, split = 0;
+  float alpha = 0.f;
+  std::vector<float> beta;
+  // caller-owned device buffers
+  std::vector<void *> W, bias, cur, hist;
+  std::vector<float *> dW, dbias;
+  const void *h0 = nullptr;
+  void *grad_in = nullptr;
+  float *grad_h0 = nullptr;
+  char *ws = nullptr;
+  // host copies for the diagnostics
+  std::vector<int64_t> h_row_ptr;
+  std::vector<uint32_t> h_pcol;
+  // schedules
+  std::vector<TaskList> ftasks, btasks;
+  // pass state (Section 3.3: V_processed, and its backward twin)
+  std::vector<int32_t> order;
+  ChunkMask fmask{}, bmask{};
+  int n_bwd = 0;
+  std::string err;
+  Profiler prof;
+
+  template <typename T>
+  T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
+  int level_dtype(int j) const { return (j == 0 && s.level0_f32) ? DT_F32 : (s.dtype == GNNSTAGE_BF16 ? DT_BF16 : DT_F32); }
+  int cdtype() const { return s.dtype == GNNSTAGE_BF16 ? DT_BF16 : DT_F32; }
+  size_t level_elt(int j) const { return level_dtype(j) == DT_BF16 ? 2 : 4; }
+};
+
+namespace {
+
+int fail(gnnstage *st, int code, const std::string &msg) {
+  if (st) st->err = msg; else g_create_error = msg;
+  return code;
+}
+
+struct Timed {
+  gnnstage *st;
+  hipStream_t s;
+  int kind;
+  hipEvent_t a = nullptr, b = nullptr;
+  Timed(gnnstage *st_, hipStream_t s_, int kind_) : st(st_), s(s_), kind(kind_) {
+    if (st->prof.on) {
+      a = st->prof.get();
+      b = st->prof.get();
+      (void)hipEventRecord(a, s);
+    }
+  }
+  ~Timed() {
+    if (st->prof.on) {
+      (void)hipEventRecord(b, s);
+      st->prof.recs.push_back({kind, a, b});
+    }
+  }
+};
+
+#define HIP_TRY(st, expr)                                                                            \
+  do {                                                                                               \
+    const int e_ = (int)(expr);                                                                      \
+    if (e_ != 0)                                                                                     \
+      return fail(st, GNNSTAGE_EHIP, std::string(#expr) + ": " + hipGetErrorString((hipError_t)e_)); \
+  } while (0)
+
+void mask_set(ChunkMask &m, int c) { m.w[c >> 6] |= 1ull << (c & 63); }
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+SpmmArgs base_spmm(const gnnstage *st, bool transposed, int chunk) {
+  SpmmArgs a{};
+  const TaskList &t = transposed ? st->btasks[chunk] : st->ftasks[chunk];
+  a.pidx = st->at<uint32_t>(transposed ? st->lay.prow : st->lay.pcol);
+  a.val = st->at<float>(transposed ? st->lay.tval : st->lay.val);
+  a.task_row = t.task_row;
+  a.task_e0 = t.task_e0;
+  a.task_ne = t.task_ne;
+  a.task_slot = t.task_slot;
+  a.n_tasks = t.n_tasks;
+  a.lr_row = t.lr_row;
+  a.lr_slot0 = t.lr_slot0;
+  a.lr_nslots = t.lr_nslots;
+  a.n_long = t.n_long;
+  a.partial = st->at<float>(st->lay.partial);
+  a.vbits = st->vbits;
+  a.mask = transposed ? st->bmask : st->fmask;
+  return a;
+}
+
+}  // namespace
+
+extern "C" int gnnstage_version(void) { return 100; }
+
+extern "C" const char *gnnstage_last_error(const gnnstage_t *st) { return st ? st->err.c_str() : g_create_error.c_str(); }
+
+extern "C" size_t gnnstage_workspace_size(const gnnstage_desc *desc) {
+  Shape s;
+  std::string err;
+  if (!read_shape(desc, s, err)) {
+    g_create_error = err;
+    return 0;
+  }
+  std::vector<int64_t> tptr = transposed_ptr(desc, s, err);
+  if (tptr.empty()) {
+    g_create_error = err;
+    return 0;
+  }
+  const int split = split_edges_setting();
+  const PlanCounts f = count_plan(desc->row_ptr, s.chunk_ptr, split);
+  const PlanCounts b = count_plan(tptr.data(), s.chunk_ptr, split);
+  return make_layout(s, f, b).total;
+}
+
+extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
+  if (!out) return fail(nullptr, GNNSTAGE_EINVAL, "out is NULL");
+  *out = nullptr;
+  Shape s;
+  std::string err;
+  if (!read_shape(d, s, err)) return fail(nullptr, GNNSTAGE_EINVAL, err);
+  if (!d->W || !d->cur || !d->hist) return fail(nullptr, GNNSTAGE_EINVAL, "W, cur and hist must not be NULL");
+  if (!d->dW) return fail(nullptr, GNNSTAGE_EINVAL, "dW must not be NULL");
+  if (s.variant == GNNSTAGE_GCN && (!d->bias || !d->dbias)) return fail(nullptr, GNNSTAGE_EINVAL, "GCN needs bias and dbias");
+  if (s.variant == GNNSTAGE_GCNII && (!d->beta || !d->h0)) return fail(nullptr, GNNSTAGE_EINVAL, "GCNII needs beta and h0");
+  if (s.need_input_grad && !d->grad_in) return fail(nullptr, GNNSTAGE_EINVAL, "need_input_grad set but grad_in is NULL");
+  if (!d->workspace || (reinterpret_cast<uintptr_t>(d->workspace) & (kAlign - 1)))
+    return fail(nullptr, GNNSTAGE_EINVAL, "workspace must be a 256-byte aligned device pointer");
+  for (int j = 0; j <= s.L; ++j) {
+    if (!d->cur[j] || !aligned16(d->cur[j])) return fail(nullptr, GNNSTAGE_EINVAL, "cur[j] NULL or not 16-byte aligned");
+    if (j < s.L) {
+      if (!d->hist[j] || !aligned16(d->hist[j])) return fail(nullptr, GNNSTAGE_EINVAL, "hist[j] NULL or not 16-byte aligned");
+      if (!d->W[j] || !d->dW[j]) return fail(nullptr, GNNSTAGE_EINVAL, "W[j] / dW[j] NULL");
+      if (s.variant == GNNSTAGE_GCN && (!d->bias[j] || !d->dbias[j])) return fail(nullptr, GNNSTAGE_EINVAL, "bias[j] / dbias[j] NULL");
+    }
+  }
+  if ((d->h0 && !aligned16(d->h0)) || (d->grad_in && !aligned16(d->grad_in)))
+    return fail(nullptr, GNNSTAGE_EINVAL, "h0 / grad_in not 16-byte aligned");
+
+  // ---- host planning -------------------------------------------------------------------
+  std::vector<int64_t> t_ptr((size_t)s.n + 1);
+  std::vector<int32_t> t_row((size_t)s.nnz);
+  std::vector<int64_t> t_edge;
+  if (d->edge_val) t_edge.resize((size_t)s.nnz);
+  int rc = gnnstage_plan_transpose(s.n, d->row_ptr, d->col_idx, t_ptr.data(), t_row.data(),
+                                   d->edge_val ? t_edge.data() : nullptr);
+  if (rc != GNNSTAGE_OK) return fail(nullptr, rc, "col_idx is NULL or has an entry outside [0, n_vertices)");
+  int vbits = 0;
+  std::vector<uint32_t> pcol((size_t)s.nnz), prow((size_t)s.nnz);
+  rc = gnnstage_plan_pack(s.n, s.nnz, d->col_idx, s.K, s.chunk_ptr.data(), pcol.data(), &vbits);
+  if (rc == GNNSTAGE_ENOTSUP)
+    return fail(nullptr, rc, "vertex-id bits + chunk-id bits exceed the 32-bit packed index word");
+  if (rc != GNNSTAGE_OK) return fail(nullptr, rc, "cannot pack column indices");
+  rc = gnnstage_plan_pack(s.n, s.nnz, t_row.data(), s.K, s.chunk_ptr.data(), prow.data(), &vbits);
+  if (rc != GNNSTAGE_OK) return fail(nullptr, rc, "cannot pack row indices");
+
+  const int split = split_edges_setting();
+  const PlanCounts fc = count_plan(d->row_ptr, s.chunk_ptr, split);
+  const PlanCounts bc = count_plan(t_ptr.data(), s.chunk_ptr, split);
+  Layout lay = make_layout(s, fc, bc);
+  if (d->workspace_bytes < lay.total) {
+    char buf[160];
+    snprintf(buf, sizeof buf, "workspace too small: %zu bytes given, %zu needed", d->workspace_bytes, lay.total);
+    return fail(nullptr, GNNSTAGE_ENOMEM, buf);
+  }
+
+  gnnstage *st = new gnnstage();
+  st->s = s;
+  st->lay = lay;
+  st->vbits = vbits;
+  st->split = split;
+  st->alpha = d->alpha;
+  if (d->beta) st->beta.assign(d->beta, d->beta + s.L); else st->beta.assign(s.L, 0.f);
+  st->W.assign(d->W, d->W + s.L);
+  st->cur.assign(d->cur, d->cur + s.L + 1);
+  st->hist.assign(d->hist, d->hist + s.L);
+  st->dW.assign(d->dW, d->dW + s.L);
+  if (d->bias) st->bias.assign(d->bias, d->bias + s.L); else st->bias.assign(s.L, nullptr);
+  if (d->dbias) st->dbias.assign(d->dbias, d->dbias + s.L); else st->dbias.assign(s.L, nullptr);
+  st->h0 = d->h0;
+  st->grad_in = d->grad_in;
+  st->grad_h0 = d->grad_h0;
+  st->ws = static_cast<char *>(d->workspace);
+  st->h_row_ptr.assign(d->row_ptr, d->row_ptr + s.n + 1);
+  st->h_pcol = pcol;
+
+  // schedules: build on the host chunk by chunk, upload into the preallocated arrays
+  auto build = [&](const int64_t *ptr, const PlanCounts &pc, bool transposed, std::vector<TaskList> &lists) -> int {
+    lists.resize(s.K);
+    int64_t t_off = 0, l_off = 0;
+    for (int c = 0; c < s.K; ++c) {
+      TaskList &tl = lists[c];
+      tl.n_tasks = pc.tasks[c];
+      tl.n_long = pc.longs[c];
+      tl.n_slots = pc.slots[c];
+      tl.task_row = st->at<int32_t>(transposed ? lay.b_task_row : lay.f_task_row) + t_off;
+      tl.task_e0 = st->at<int64_t>(transposed ? lay.b_task_e0 : lay.f_task_e0) + t_off;
+      tl.task_ne = st->at<int32_t>(transposed ? lay.b_task_ne : lay.f_task_ne) + t_off;
+      tl.task_slot = st->at<int32_t>(transposed ? lay.b_task_slot : lay.f_task_slot) + t_off;
+      tl.lr_row = st->at<int32_t>(transposed ? lay.b_lr_row : lay.f_lr_row) + l_off;
+      tl.lr_slot0 = st->at<int32_t>(transposed ? lay.b_lr_slot0 : lay.f_lr_slot0) + l_off;
+      tl.lr_nslots = st->at<int32_t>(transposed ? lay.b_lr_n : lay.f_lr_n) + l_off;
+      t_off += tl.n_tasks;
+      l_off += tl.n_long;
+      if (tl.n_tasks == 0) continue;
+      std::vector<int32_t> row(tl.n_tasks), ne(tl.n_tasks), slot(tl.n_tasks);
+      std::vector<int64_t> e0(tl.n_tasks);
+      int64_t ns = 0;
+      const int64_t got = gnnstage_plan_tasks(ptr, s.chunk_ptr[c], s.chunk_ptr[c + 1], split, tl.n_tasks, row.data(),
+                                              e0.data(), ne.data(), slot.data(), &ns);
+      if (got != tl.n_tasks || ns != tl.n_slots) return GNNSTAGE_EINVAL;
+      std::vector<int32_t> lrow, lslot0, ln;
+      for (int64_t t = 0; t < tl.n_tasks && slot[t] >= 0; ++t) {
+        if (lrow.empty() || lrow.back() != row[t]) {
+          lrow.push_back(row[t]);
+          lslot0.push_back(slot[t]);
+          ln.push_back(0);
+        }
+        ln.back() += 1;
+      }
+      if ((int64_t)lrow.size() != tl.n_long) return GNNSTAGE_EINVAL;
+      if (hipMemcpy(tl.task_row, row.data(), sizeof(int32_t) * tl.n_tasks, hipMemcpyHostToDevice) != hipSuccess ||
+          hipMemcpy(tl.task_e0, e0.data(), sizeof(int64_t) * tl.n_tasks, hipMemcpyHostToDevice) != hipSuccess ||
+          hipMemcpy(tl.task_ne, ne.data(), sizeof(int32_t) * tl.n_tasks, hipMemcpyHostToDevice) != hipSuccess ||
+          hipMemcpy(tl.task_slot, slot.data(), sizeof(int32_t) * tl.n_tasks, hipMemcpyHostToDevice) != hipSuccess)
+        return GNNSTAGE_EHIP;
+      if (tl.n_long > 0 &&
+          (hipMemcpy(tl.lr_row, lrow.data(), sizeof(int32_t) * tl.n_long, hipMemcpyHostToDevice) != hipSuccess ||
+           hipMemcpy(tl.lr_slot0, lslot0.data(), sizeof(int32_t) * tl.n_long, hipMemcpyHostToDevice) != hipSuccess ||
+           hipMemcpy(tl.lr_nslots, ln.data(), sizeof(int32_t) * tl.n_long, hipMemcpyHostToDevice) != hipSuccess))
+        return GNNSTAGE_EHIP;
+    }
+    return GNNSTAGE_OK;
+  };
+
+  auto bail = [&](int code, const std::string &msg) {
+    delete st;
+    return fail(nullptr, code, msg);
+  };
+  if (hipMemcpy(st->at<int64_t>(lay.row_ptr), d->row_ptr, sizeof(int64_t) * (s.n + 1), hipMemcpyHostToDevice) != hipSuccess ||
+      hipMemcpy(st->at<int64_t>(lay.t_ptr), t_ptr.data(), sizeof(int64_t) * (s.n + 1), hipMemcpyHostToDevice) != hipSuccess ||
+      hipMemcpy(st->at<uint32_t>(lay.pcol), pcol.data(), sizeof(uint32_t) * s.nnz, hipMemcpyHostToDevice) != hipSuccess ||
+      hipMemcpy(st->at<uint32_t>(lay.prow), prow.data(), sizeof(uint32_t) * s.nnz, hipMemcpyHostToDevice) != hipSuccess)
+    return bail(GNNSTAGE_EHIP, std::string("uploading the graph failed: ") + hipGetErrorString(hipGetLastError()));
+  if (d->edge_val) {
+    std::vector<float> tval((size_t)s.nnz);
+    for (int64_t p = 0; p < s.nnz; ++p) tval[(size_t)p] = d->edge_val[t_edge[(size_t)p]];
+    if (hipMemcpy(st->at<float>(lay.val), d->edge_val, sizeof(float) * s.nnz, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(st->at<float>(lay.tval), tval.data(), sizeof(float) * s.nnz, hipMemcpyHostToDevice) != hipSuccess)
+      return bail(GNNSTAGE_EHIP, "uploading edge values failed");
+  } else {
+    // Section 2.1 weights from the row lengths of A + I, for the CSR entries and for their transposed copies
+    const int64_t *rp = st->at<int64_t>(lay.row_ptr);
+    if (launch_gcn_norm(rp, st->at<uint32_t>(lay.pcol), vbits, rp, s.n, st->at<float>(lay.val), nullptr) != 0 ||
+        launch_gcn_norm(st->at<int64_t>(lay.t_ptr), st->at<uint32_t>(lay.prow), vbits, rp, s.n, st->at<float>(lay.tval), nullptr) != 0)
+      return bail(GNNSTAGE_EHIP, "normalisation kernel launch failed");
+  }
+  rc = build(d->row_ptr, fc, false, st->ftasks);
+  if (rc == GNNSTAGE_OK) rc = build(t_ptr.data(), bc, true, st->btasks);
+  if (rc != GNNSTAGE_OK) return bail(rc, "building the launch schedule failed");
+  if (hipDeviceSynchronize() != hipSuccess) return bail(GNNSTAGE_EHIP, "device synchronisation failed after create");
+  *out = st;
+  return GNNSTAGE_OK;
+}
+
+extern "C" int gnnstage_destroy(gnnstage_t *st) {
+  if (!st) return GNNSTAGE_EINVAL;
+  const hipError_t e = hipDeviceSynchronize();
+  st->prof.destroy();
+  delete st;
+  return e == hipSuccess ? GNNSTAGE_OK : GNNSTAGE_EHIP;
+}
+
+extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void *hip_stream) {
+  if (!st) return GNNSTAGE_EINVAL;
+  const Shape &s = st->s;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (k < 0 || k >= s.K) return fail(st, GNNSTAGE_ERANGE, "chunk id out of range");
+  if (pos == 0) {  // a new pass: V_processed <- empty
+    st->order.clear();
+    st->fmask = ChunkMask{};
+    st->bmask = ChunkMask{};
+    st->n_bwd = 0;
+    Timed t(st, stream, 6);
+    for (int j = 0; j < s.L; ++j)
+      HIP_TRY(st, launch_stage_weights(st->W[j], st->cdtype(), s.dims[j], s.dims[j + 1], st->at<char>(st->lay.Wt[j]), s.ld[j],
+                                       st->at<char>(st->lay.Wn[j]), s.ld[j + 1], stream));
+  }
+  if (pos != (int32_t)st->order.size()) return fail(st, GNNSTAGE_EORDER, "pos_in_pass does not continue the current pass");
+  if (mask_test(st->fmask, (uint32_t)k)) return fail(st, GNNSTAGE_EORDER, "chunk already processed in this pass");
+  st->order.push_back(k);
+  mask_set(st->fmask, k);  // C_k joins V_processed before its layers run
+
+  const int64_t row0 = s.chunk_ptr[k], M = s.chunk_ptr[k + 1] - row0;
+  if (M == 0) return GNNSTAGE_OK;
+  const int cd = st->cdtype();
+  const size_t celt = s.elt();
+  for (int j = 0; j < s.L; ++j) {
+    char *Zj = st->at<char>(st->lay.Z[j]);
+    {
+      Timed t(st, stream, 0);
+      SpmmArgs a = base_spmm(st, false, k);
+      a.src_sel = st->cur[j];
+      a.src_unsel = st->hist[j];
+      a.d = s.dims[j];
+      a.src_ld = s.dims[j];
+      a.out = Zj;
+      a.out_ld = s.ld[j];
+      a.out_row0 = 0;
+      if (s.variant == GNNSTAGE_GCNII) {
+        a.epilogue = SPMM_MIX;
+        a.aux = st->h0;
+        a.aux_ld = s.dims[j];
+        a.s_acc = 1.f - st->alpha;
+        a.s_aux = st->alpha;
+      } else {
+        a.epilogue = SPMM_PLAIN;
+      }
+      HIP_TRY(st, launch_spmm(a, st->level_dtype(j), cd, stream));
+    }
+    {
+      Timed t(st, stream, 1);
+      GemmNtArgs g{};
+      g.A = Zj + (size_t)row0 * s.ld[j] * celt;
+      g.lda = s.ld[j];
+      g.Bt = st->at<char>(st->lay.Wt[j]);
+      g.ldb = s.ld[j];
+      g.M = (int)M;
+      g.N = s.dims[j + 1];
+      g.Kp = s.ld[j];
+      if (s.variant == GNNSTAGE_GCNII) {
+        g.epilogue = EPI_FWD_GCNII;
+        g.aux = g.A;
+        g.aux_ld = s.ld[j];
+        g.beta = st->beta[j];
+      } else {
+        g.epilogue = EPI_FWD_GCN;
+        g.bias = static_cast<const float *>(st->bias[j]);
+      }
+      g.out = static_cast<char *>(st->cur[j + 1]) + (size_t)row0 * s.dims[j + 1] * celt;
+      g.out_ld = s.dims[j + 1];
+      HIP_TRY(st, launch_gemm_nt(g, cd, cd, stream));
+    }
+  }
+  return GNNSTAGE_OK;
+}
+
+extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_out_rows, void *hip_stream) {
+  if (!st) return GNNSTAGE_EINVAL;
+  const Shape &s = st->s;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (k < 0 || k >= s.K) return fail(st, GNNSTAGE_ERANGE, "chunk id out of range");
+  if ((int)st->order.size() != s.K) return fail(st, GNNSTAGE_EORDER, "backward before the forward pass covered every chunk");
+  if (st->n_bwd >= s.K) return fail(st, GNNSTAGE_EORDER, "backward pass already complete");
+  if (st->order[s.K - 1 - st->n_bwd] != k) return fail(st, GNNSTAGE_EORDER, "backward must walk the chunks in reverse forward order");
+  const int64_t row0 = s.chunk_ptr[k], M = s.chunk_ptr[k + 1] - row0;
+  if (M > 0 && !grad_out_rows) return fail(st, GNNSTAGE_EINVAL, "grad_out_rows is NULL");
+  st->n_bwd += 1;
+  mask_set(st->bmask, k);
+  if (M == 0) return GNNSTAGE_OK;
+
+  const int cd = st->cdtype();
+  const size_t celt = s.elt();
+  char *G[2] = {st->at<char>(st->lay.G[0]), st->at<char>(st->lay.G[1])};
+  int gi = 0;
+  {
+    Timed t(st, stream, 6);
+    const char *top = static_cast<const char *>(st->cur[s.L]) + (size_t)row0 * s.dims[s.L] * celt;
+    HIP_TRY(st, launch_relu_mask(grad_out_rows, top, cd, M, s.dims[s.L], G[gi], s.ld[s.L], stream));
+  }
+  for (int j = s.L - 1; j >= 0; --j) {
+    const char *dY = G[gi];
+    const char *Zrows = st->at<char>(st->lay.Z[j]) + (size_t)row0 * s.ld[j] * celt;
+    {
+      Timed t(st, stream, 4);
+      GemmTnArgs w{};
+      w.A = Zrows;
+      w.lda = s.ld[j];
+      w.B = dY;
+      w.ldb = s.ld[j + 1];
+      w.M = (int)M;
+      w.I = s.dims[j];
+      w.O = s.dims[j + 1];
+      w.scale = s.variant == GNNSTAGE_GCNII ? st->beta[j] : 1.f;
+      w.dW = st->dW[j];
+      w.partial = st->at<float>(st->lay.gemm_partial);
+      w.max_splits = kMaxSplits;
+      w.dbias = s.variant == GNNSTAGE_GCN ? st->dbias[j] : nullptr;
+      w.bias_partial = st->at<float>(st->lay.bias_partial);
+      HIP_TRY(st, launch_gemm_tn(w, cd, stream));
+    }
+    if (j == 0 && !s.need_input_grad) break;
+    char *dZj = st->at<char>(st->lay.dZ[j]);
+    {
+      Timed t(st, stream, 3);
+      GemmNtArgs g{};
+      g.A = dY;
+      g.lda = s.ld[j + 1];
+      g.Bt = st->at<char>(st->lay.Wn[j]);
+      g.ldb = s.ld[j + 1];
+      g.M = (int)M;
+      g.N = s.dims[j];
+      g.Kp = s.ld[j + 1];
+      if (s.variant == GNNSTAGE_GCNII) {
+        g.epilogue = EPI_DGRAD_GCNII;
+        g.aux = dY;
+        g.aux_ld = s.ld[j + 1];
+        g.alpha = st->alpha;
+        g.beta = st->beta[j];
+        g.h0grad = st->grad_h0 ? st->grad_h0 + (size_t)row0 * s.dims[j] : nullptr;
+        g.h0_ld = s.dims[j];
+      } else {
+        g.epilogue = EPI_DGRAD_GCN;
+      }
+      g.out = dZj + (size_t)row0 * s.ld[j] * celt;
+      g.out_ld = s.ld[j];
+      HIP_TRY(st, launch_gemm_nt(g, cd, cd, stream));
+    }
+    {
+      Timed t(st, stream, 2);
+      SpmmArgs a = base_spmm(st, true, k);
+      a.src_sel = dZj;
+      a.src_unsel = nullptr;  // Section 3.4: nothing flows back from unprocessed vertices
+      a.d = s.dims[j];
+      a.src_ld = s.ld[j];
+      if (j > 0) {
+        a.out = G[gi ^ 1];
+        a.out_ld = s.ld[j];
+        a.out_row0 = row0;
+        a.epilogue = SPMM_MASK;
+        a.aux = st->cur[j];
+        a.aux_ld = s.dims[j];
+        HIP_TRY(st, launch_spmm(a, cd, cd, stream));
+      } else {
+        a.out = st->grad_in;
+        a.out_ld = s.dims[0];
+        a.out_row0 = 0;
+        a.epilogue = SPMM_PLAIN;
+        HIP_TRY(st, launch_spmm(a, cd, st->level_dtype(0), stream));
+      }
+    }
+    gi ^= 1;
+  }
+  return GNNSTAGE_OK;
+}
+
+extern "C" int update_history(gnnstage_t *st, void *hip_stream) {
+  if (!st) return GNNSTAGE_EINVAL;
+  const Shape &s = st->s;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  Timed t(st, stream, 5);
+  for (int j = 0; j < s.L; ++j) {
+    if (st->hist[j] == st->cur[j]) continue;
+    HIP_TRY(st, launch_copy(st->cur[j], st->hist[j], (size_t)s.n * s.dims[j] * st->level_elt(j), stream));
+  }
+  return GNNSTAGE_OK;
+}
+
+extern "C" int gnnstage_debug_select_counts(gnnstage_t *st, int32_t k, int32_t *out) {
+  if (!st || !out) return GNNSTAGE_EINVAL;
+  const Shape &s = st->s;
+  if (k < 0 || k >= s.K) return fail(st, GNNSTAGE_ERANGE, "chunk id out of range");
+  ChunkMask m = st->fmask;
+  mask_set(m, k);
+  const uint32_t vb = (uint32_t)st->vbits;
+  for (int64_t v = s.chunk_ptr[k]; v < s.chunk_ptr[k + 1]; ++v) {
+    int32_t c = 0;
+    for (int64_t e = st->h_row_ptr[v]; e < st->h_row_ptr[v + 1]; ++e) c += mask_test(m, st->h_pcol[(size_t)e] >> vb) ? 1 : 0;
+    out[v - s.chunk_ptr[k]] = c;
+  }
+  return GNNSTAGE_OK;
+}
+
+extern "C" int gnnstage_profile_enable(gnnstage_t *st, int32_t on) {
+  if (!st) return GNNSTAGE_EINVAL;
+  st->prof.on = on != 0;
+  return GNNSTAGE_OK;
+}
+
+extern "C" int gnnstage_profile_read(gnnstage_t *st, int32_t kind, double *ms, int64_t *launches) {
+  if (!st || kind < 0 || kind >= GNNSTAGE_NKINDS) return GNNSTAGE_EINVAL;
+  if (hipDeviceSynchronize() != hipSuccess) return fail(st, GNNSTAGE_EHIP, "device synchronisation failed");
+  st->prof.collect();
+  if (ms) *ms = st->prof.ms[kind];
+  if (launches) *launches = st->prof.launches[kind];
+  return GNNSTAGE_OK;
+}
+
+extern "C" int gnnstage_profile_reset(gnnstage_t *st) {
+  if (!st) return GNNSTAGE_EINVAL;
+  if (hipDeviceSynchronize() != hipSuccess) return fail(st, GNNSTAGE_EHIP, "device synchronisation failed");
+  st->prof.collect();
+  for (int i = 0; i < GNNSTAGE_NKINDS; ++i) {
+    st->prof.ms[i] = 0;
+    st->prof.launches[i] = 0;
+  }
+  return GNNSTAGE_OK;
+}

@@ -1,0 +1,133 @@
+// Small kernels around the two hot operations: weight staging, the ReLU-derivative mask on
+// the upstream gradient, the history copy (Section 3.4, second technique), zero fill, and the
+// symmetric normalisation weights of Section 2.1.
+#include "common.h"
+
+namespace {
+
+__device__ inline float to_f32(float x) { return x; }
+__device__ inline float to_f32(bf16_t x) { return (float)x; }
+template <typename T>
+__device__ inline T from_f32(float x);
+template <>
+__device__ inline float from_f32<float>(float x) { return x; }
+template <>
+__device__ inline bf16_t from_f32<bf16_t>(float x) { return (bf16_t)x; }
+
+// Wt[n][k] = W[k][n] (k < K, else 0; row stride Kp) and Wn[k][n] = W[k][n] (n < N, else 0; row stride Np)
+template <typename Tw, typename Tc>
+__global__ __launch_bounds__(256) void stage_weights_kernel(const Tw *W, int K, int N, Tc *Wt, int Kp, Tc *Wn, int Np) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx < N * Kp) {
+    const int n = idx / Kp, k = idx % Kp;
+    Wt[idx] = from_f32<Tc>(k < K ? to_f32(W[(size_t)k * N + n]) : 0.f);
+  }
+  if (idx < K * Np) {
+    const int k = idx / Np, n = idx % Np;
+    Wn[idx] = from_f32<Tc>(n < N ? to_f32(W[(size_t)k * N + n]) : 0.f);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void relu_mask_kernel(const T *g, const T *level, int64_t M, int d, T *out, int out_ld) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= M * out_ld) return;
+  const int64_t m = idx / out_ld;
+  const int c = (int)(idx % out_ld);
+  float r = 0.f;
+  if (c < d && to_f32(level[m * d + c]) > 0.f) r = to_f32(g[m * d + c]);
+  out[idx] = from_f32<T>(r);
+}
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// grid-stride 16-byte copy with a byte tail
+__global__ __launch_bounds__(256) void copy_kernel(const u32x4 *src, u32x4 *dst, size_t n16, const uint8_t *tsrc,
+                                                   uint8_t *tdst, int tail) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+  if (blockIdx.x == 0 && (int)threadIdx.x < tail) tdst[threadIdx.x] = tsrc[threadIdx.x];
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(u32x4 *dst, size_t n16, uint8_t *tdst, int tail) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  const u32x4 z = {0u, 0u, 0u, 0u};
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = z;
+  if (blockIdx.x == 0 && (int)threadIdx.x < tail) tdst[threadIdx.x] = 0;
+}
+
+// One wave per sparse row: val[e] = 1 / sqrt(len(row) * len(other endpoint)), lengths taken from
+// len_ptr (the CSR row pointer of A + I), computed in fp64 and rounded once to fp32.
+__global__ __launch_bounds__(256) void gcn_norm_kernel(const int64_t *ptr, const uint32_t *pidx, int vbits,
+                                                       const int64_t *len_ptr, int64_t n, float *val) {
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= n) return;
+  const int lane = threadIdx.x & 63;
+  const uint32_t vmask = (1u << vbits) - 1u;
+  const double dv = (double)(len_ptr[row + 1] - len_ptr[row]);
+  for (int64_t e = ptr[row] + lane; e < ptr[row + 1]; e += 64) {
+    const int64_t u = pidx[e] & vmask;
+    const double du = (double)(len_ptr[u + 1] - len_ptr[u]);
+    val[e] = (float)(1.0 / sqrt(dv * du));
+  }
+}
+
+}  // namespace
+
+int launch_stage_weights(const void *W, int w_dtype, int K, int N, void *Wt, int Kp, void *Wn, int Np, hipStream_t s) {
+  const int total = (N * Kp > K * Np) ? N * Kp : K * Np;
+  dim3 grid((total + 255) / 256);
+  if (w_dtype == DT_BF16)
+    hipLaunchKernelGGL((stage_weights_kernel<bf16_t, bf16_t>), grid, dim3(256), 0, s, static_cast<const bf16_t *>(W), K, N,
+                       static_cast<bf16_t *>(Wt), Kp, static_cast<bf16_t *>(Wn), Np);
+  else
+    hipLaunchKernelGGL((stage_weights_kernel<float, float>), grid, dim3(256), 0, s, static_cast<const float *>(W), K, N,
+                       static_cast<float *>(Wt), Kp, static_cast<float *>(Wn), Np);
+  return (int)hipGetLastError();
+}
+
+int launch_relu_mask(const void *g, const void *level, int dtype, int64_t M, int d, void *out, int out_ld, hipStream_t s) {
+  if (M <= 0) return hipSuccess;
+  const int64_t total = M * out_ld;
+  dim3 grid((unsigned)((total + 255) / 256));
+  if (dtype == DT_BF16)
+    hipLaunchKernelGGL(relu_mask_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(g),
+                       static_cast<const bf16_t *>(level), M, d, static_cast<bf16_t *>(out), out_ld);
+  else
+    hipLaunchKernelGGL(relu_mask_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(g),
+                       static_cast<const float *>(level), M, d, static_cast<float *>(out), out_ld);
+  return (int)hipGetLastError();
+}
+
+static unsigned stream_grid(size_t n16) {
+  size_t blocks = (n16 + 255) / 256;
+  if (blocks > 256 * 16) blocks = 256 * 16;  // 16 blocks per CU, grid-stride beyond that
+  if (blocks == 0) blocks = 1;
+  return (unsigned)blocks;
+}
+
+int launch_copy(const void *src, void *dst, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  const size_t n16 = bytes / 16;
+  const int tail = (int)(bytes % 16);
+  hipLaunchKernelGGL(copy_kernel, dim3(stream_grid(n16)), dim3(256), 0, s, static_cast<const u32x4 *>(src),
+                     static_cast<u32x4 *>(dst), n16, static_cast<const uint8_t *>(src) + n16 * 16,
+                     static_cast<uint8_t *>(dst) + n16 * 16, tail);
+  return (int)hipGetLastError();
+}
+
+int launch_fill_zero(void *dst, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  const size_t n16 = bytes / 16;
+  const int tail = (int)(bytes % 16);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(stream_grid(n16)), dim3(256), 0, s, static_cast<u32x4 *>(dst), n16,
+                     static_cast<uint8_t *>(dst) + n16 * 16, tail);
+  return (int)hipGetLastError();
+}
+
+int launch_gcn_norm(const int64_t *ptr, const uint32_t *pidx, int vbits, const int64_t *len_ptr, int64_t n, float *val,
+                    hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(gcn_norm_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, s, ptr, pidx, vbits, len_ptr, n, val);
+  return (int)hipGetLastError();
+}

@@ -1,0 +1,56 @@
+"""Runs a Problem through the HIP library (via the C ABI binding) and brings results back as numpy."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2308_10087_amd as g
+
+
+def _dev(x: np.ndarray, dtype, device):
+    return torch.from_numpy(np.ascontiguousarray(x)).to(device=device, dtype=dtype).contiguous()
+
+
+class GpuRun:
+    def __init__(self, p, *, need_input_grad=True, edge_val="given", device="cuda:0"):
+        self.p = p
+        self.device = device
+        bf = p.quant
+        sdt = torch.bfloat16 if bf else torch.float32
+        l0 = torch.float32 if (p.level0_f32 or not bf) else torch.bfloat16
+        L, n = p.L, p.n
+        self.sdt, self.l0 = sdt, l0
+        self.W = [_dev(p.W[j], sdt, device) for j in range(L)]
+        gcn = p.w.variant == "gcn"
+        self.bias = [_dev(p.b[j], torch.float32, device) for j in range(L)] if gcn else None
+        self.cur = [_dev(p.x0, l0, device)] + [torch.zeros((n, p.dims[j]), dtype=sdt, device=device) for j in range(1, L + 1)]
+        self.hist = [_dev(p.hist[j], l0 if j == 0 else sdt, device) for j in range(L)]
+        self.dW = [torch.zeros((p.dims[j], p.dims[j + 1]), dtype=torch.float32, device=device) for j in range(L)]
+        self.dbias = [torch.zeros(p.dims[j + 1], dtype=torch.float32, device=device) for j in range(L)] if gcn else None
+        self.h0 = None if gcn else _dev(p.h0, sdt, device)
+        self.grad_h0 = None if gcn else torch.zeros((n, p.dims[0]), dtype=torch.float32, device=device)
+        self.grad_in = torch.zeros((n, p.dims[0]), dtype=l0, device=device) if need_input_grad else None
+        self.grad_out = _dev(p.grad_out, sdt, device)
+        self.stage = g.GnnStage(
+            p.row_ptr, p.col, p.chunk_ptr, p.dims, W=self.W, cur=self.cur, hist=self.hist, dW=self.dW,
+            bias=self.bias, dbias=self.dbias, edge_val=(p.val if edge_val == "given" else None),
+            variant=g.GNNSTAGE_GCN if gcn else g.GNNSTAGE_GCNII, alpha=p.a,
+            beta=None if gcn else p.beta.astype(np.float32), h0=self.h0, grad_h0=self.grad_h0,
+            dtype=g.GNNSTAGE_BF16 if bf else g.GNNSTAGE_F32, level0_f32=p.level0_f32, grad_in=self.grad_in,
+            device=device)
+
+    def forward(self, order=None):
+        self.stage.forward_pass(self.p.order if order is None else order)
+
+    def backward(self, order=None):
+        self.stage.backward_pass(self.p.order if order is None else order, self.grad_out)
+
+    def run(self):
+        self.forward()
+        self.backward()
+        torch.cuda.synchronize()
+        return self
+
+    @staticmethod
+    def np(t):
+        return t.detach().to(torch.float32).cpu().numpy()
