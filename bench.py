@@ -1,0 +1,268 @@
+#!/usr/bin/env python3
+"""Benchmark of one pipeline stage on one MI355X.
+
+A step = one epoch's work of the stage: forward over all chunks (shuffled order), backward over
+the chunks in reverse, then update_history.  The workload is configuration 1 of the benchmark
+definition (Reddit-shaped R-MAT graph, 4 GCN layers 602->256x4, bf16 transforms, 8 chunks); inputs
+are synthetic and resident in HBM before the timed region.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def pair_counts(row_ptr, col, chunk_ptr):
+    """E[k][c] = entries of chunk k's rows whose column lies in chunk c; D[k][c] = distinct columns among them."""
+    K = len(chunk_ptr) - 1
+    n = len(row_ptr) - 1
+    E = np.zeros((K, K), dtype=np.int64)
+    D = np.zeros((K, K), dtype=np.int64)
+    for k in range(K):
+        cols = col[row_ptr[chunk_ptr[k]]:row_ptr[chunk_ptr[k + 1]]]
+        mark = np.zeros(n, dtype=bool)
+        mark[cols] = True
+        cnt = np.bincount(np.searchsorted(chunk_ptr, cols, side="right") - 1, minlength=K)
+        E[k] = cnt[:K]
+        D[k] = np.add.reduceat(mark.astype(np.int64), chunk_ptr[:-1].clip(max=n - 1))[:K]
+        for c in range(K):  # reduceat misreads empty ranges
+            if chunk_ptr[c] == chunk_ptr[c + 1]:
+                D[k, c] = 0
+    return E, D
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c1")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-rows", type=int, default=131072)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one pipeline stage on ONE GPU; this build has no multi-GPU path (--gpus must be 1)")
+
+    import torch
+    import paper_2308_10087_amd as g
+    from synth import values
+    from synth.configs import CONFIGS, make_graph
+    from synth.graphs import degree_stats, equal_chunks
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    w = CONFIGS[args.workload]
+    t0 = time.time()
+    row_ptr, col = make_graph(w)
+    n, nnz = len(row_ptr) - 1, int(row_ptr[-1])
+    chunk_ptr = equal_chunks(n, w.n_chunks)
+    K, L, dims = w.n_chunks, w.n_layers, list(w.dims)
+    stats = degree_stats(row_ptr)
+    log(f"[bench] graph {w.name}: {stats} built in {time.time() - t0:.1f}s")
+
+    bf = w.dtype == "bf16"
+    sdt = torch.bfloat16 if bf else torch.float32
+    l0 = torch.float32 if (w.level0_f32 or not bf) else torch.bfloat16
+    gcn = w.variant == "gcn"
+    x0_np = values.normal(w.seed, 1, (n, dims[0])) if gcn else values.half_normal(w.seed, 1, (n, dims[0]))
+    W = [torch.from_numpy(values.glorot_uniform(w.seed, 100 + j, dims[j], dims[j + 1])).to(dev, sdt) for j in range(L)]
+    bias = [torch.zeros(dims[j + 1], device=dev) for j in range(L)] if gcn else None
+    cur = [torch.from_numpy(x0_np).to(dev, l0)] + [torch.zeros((n, dims[j]), dtype=sdt, device=dev) for j in range(1, L + 1)]
+    first_stage = gcn
+    hist = [cur[0] if first_stage else cur[0].clone()] + [torch.zeros((n, dims[j]), dtype=sdt, device=dev) for j in range(1, L)]
+    dW = [torch.zeros((dims[j], dims[j + 1]), device=dev) for j in range(L)]
+    dbias = [torch.zeros(dims[j + 1], device=dev) for j in range(L)] if gcn else None
+    h0 = None if gcn else torch.from_numpy(values.normal(w.seed, 2, (n, dims[0]))).to(dev, sdt)
+    grad_h0 = None if gcn else torch.zeros((n, dims[0]), device=dev)
+    grad_in = None if first_stage else torch.zeros((n, dims[0]), dtype=l0, device=dev)
+    grad_out = torch.from_numpy(values.normal(w.seed, 3, (n, dims[-1]))).to(dev, sdt)
+    beta = None
+    if not gcn:
+        import math
+        beta = np.array([math.log(0.5 / l + 1.0) for l in range(w.gcnii_first_layer, w.gcnii_first_layer + L)], np.float32)
+    t1 = time.time()
+    st = g.GnnStage(row_ptr, col, chunk_ptr, dims, W=W, cur=cur, hist=hist, dW=dW, bias=bias, dbias=dbias,
+                    variant=g.GNNSTAGE_GCN if gcn else g.GNNSTAGE_GCNII, alpha=w.gcnii_alpha, beta=beta, h0=h0,
+                    grad_h0=grad_h0, dtype=g.GNNSTAGE_BF16 if bf else g.GNNSTAGE_F32, level0_f32=w.level0_f32,
+                    grad_in=grad_in, device=dev)
+    log(f"[bench] gnnstage_create: {time.time() - t1:.1f}s, workspace {st.workspace_bytes / 2**30:.2f} GiB")
+
+    def one_step(step_idx: int):
+        order = values.permutation(w.seed, 1000 + step_idx, K)
+        for t in dW:
+            t.zero_()
+        if dbias:
+            for t in dbias:
+                t.zero_()
+        if grad_h0 is not None:
+            grad_h0.zero_()
+        st.forward_pass(order)
+        st.backward_pass(order, grad_out)
+        st.update_history()
+        return order
+
+    # historical buffers: one untimed epoch from zero history, refresh, then N(0, 0.01^2) noise
+    one_step(-1)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed)
+    for j in range(L):
+        if hist[j].data_ptr() != cur[j].data_ptr():
+            hist[j].add_((0.01 * torch.randn(hist[j].shape, generator=gen, device=dev)).to(hist[j].dtype))
+    for i in range(args.warmup):
+        one_step(i)
+    torch.cuda.synchronize()
+
+    st.gnnstage_profile_reset()
+    st.gnnstage_profile_enable(True)
+    orders = []
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        orders.append(one_step(args.warmup + i))
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    st.gnnstage_profile_enable(False)
+    prof_all = st.gnnstage_profile_read(-1)
+    prof_layer = [st.gnnstage_profile_read(j) for j in range(L)]
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = L * nnz / (elapsed / args.steps)
+
+    # ---- roofline of the dominant kernel -------------------------------------------------
+    # The aggregation kernel instance that gathers rows of the hidden width serves forward layers
+    # 1..L-1 and backward layers 1..L-1 (one instantiation, same launch shape), so they are one group.
+    E, D = pair_counts(row_ptr, col, chunk_ptr)
+    rows = np.diff(chunk_ptr)
+    elt = 2 if bf else 4
+    groups = {}
+
+    def add(group, nbytes, ms, launches):
+        gr = groups.setdefault(group, [0.0, 0.0, 0])
+        gr[0] += nbytes
+        gr[1] += ms
+        gr[2] += launches
+
+    for j in range(L):
+        e_in = 4 if (j == 0 and l0 == torch.float32) else elt
+        name_f = f"spmm d={dims[j]} in={'f32' if e_in == 4 else 'bf16'}"
+        fwd_bytes = 0.0
+        for _ in orders:
+            for k in range(K):
+                # every entry's index + weight, the row pointers, each distinct source row once, the output rows
+                fwd_bytes += E[k].sum() * 8 + 8 * (rows[k] + 1) + D[k].sum() * dims[j] * e_in + rows[k] * dims[j] * elt
+        add(name_f, fwd_bytes, *prof_layer[j]["spmm_fwd"])
+        if j == 0 and grad_in is None:
+            continue
+        e_src = elt
+        name_b = f"spmm d={dims[j]} in={'f32' if e_src == 4 else 'bf16'}"
+        bwd_bytes = 0.0
+        for order in orders:
+            done = np.zeros(K, dtype=bool)
+            for k in reversed(list(order)):
+                done[k] = True
+                # symmetric graph: the transposed rows of chunk k have the same pair counts
+                bwd_bytes += E[k].sum() * 8 + 8 * (rows[k] + 1) + D[k][done].sum() * dims[j] * e_src
+                bwd_bytes += rows[k] * dims[j] * elt * (2 if j > 0 else 1)  # output rows (+ level rows for the mask)
+        add(name_b, bwd_bytes, *prof_layer[j]["spmm_bwd"])
+    dom = max(groups.items(), key=lambda kv: kv[1][1])
+    dom_name, (dom_bytes, dom_ms, dom_launches) = dom
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get(w.name, {}).get(dom_name)
+    roofline = {
+        "bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+        "algorithmic_bytes_per_launch": round(dom_bytes / max(dom_launches, 1)),
+        "avg_launch_ms": round(dom_ms / max(dom_launches, 1), 4), "launches": dom_launches,
+        "gather_GBps": round(sum(
+            (E.sum() * dims[j] * (4 if (j == 0 and l0 == torch.float32) else elt)) for j in range(L)) * len(orders) / 1e9 /
+            max(sum(prof_layer[j]["spmm_fwd"][0] for j in range(L)) * 1e-3, 1e-9), 1),
+    }
+    kernels_ms = {k: round(v[0] / args.steps, 3) for k, v in prof_all.items()}
+
+    # ---- CPU baseline: the oracle on a bounded sample ---------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w, row_ptr, col, x0_np, dims, args.cpu_sample_rows)
+
+    out = {
+        "metric": "layer-stage fwd+bwd edges/sec per MI355X", "value": value, "unit": "edges/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if bf else "f32", "data": "synthetic",
+        "config": {"workload": f"configs[{args.workload[1:]}] {w.name}: R-MAT n={n} nnz={nnz} dims={dims} chunks={K} "
+                               f"{w.variant} {'bf16 levels, fp32 level 0' if w.level0_f32 else w.dtype}",
+                   "max_degree": stats["max_degree"], "step": "forward all chunks + backward all chunks + update_history"},
+        "kernel_ms_per_step": kernels_ms,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(w, row_ptr, col, x0_np, dims, sample_rows):
+    """Times the CPU oracle (as it stands) on the first `sample_rows` destination rows of the same
+    workload: all layers, forward + backward, half of the remaining vertices marked processed."""
+    import oracle
+    from synth import values
+
+    n = len(row_ptr) - 1
+    L = len(dims) - 1
+    s = min(sample_rows, n // 2)
+    chunk_ptr = np.array([0, s, (s + n) // 2, n], dtype=np.int64)
+    t0 = time.time()
+    val = oracle.gcn_norm(row_ptr, col)
+    gcn = w.variant == "gcn"
+    quant = w.dtype == "bf16"
+    Wn = [values.glorot_uniform(w.seed, 100 + j, dims[j], dims[j + 1]) for j in range(L)]
+    beta = None
+    if not gcn:
+        import math
+        beta = np.array([math.log(0.5 / l + 1.0) for l in range(w.gcnii_first_layer, w.gcnii_first_layer + L)])
+    h0 = None if gcn else values.normal(w.seed, 2, (n, dims[0]))
+    st = oracle.OracleStage(row_ptr, col, val, chunk_ptr, dims, Wn, None, variant=w.variant, a=w.gcnii_alpha,
+                            beta=beta, h0=h0, quant=quant, level0_f32=w.level0_f32)
+    st.cur[0][...] = x0_np
+    st.hist[0][...] = x0_np
+    for j in range(1, L):
+        # values only need a realistic range here (this leg is timed, not compared)
+        st.hist[j][...] = values.half_normal(w.seed, 400 + j, (n, dims[j]))
+        st.cur[j][...] = st.hist[j]
+    log(f"[bench] oracle set-up {time.time() - t0:.1f}s")
+    edges = int(row_ptr[s] - row_ptr[0])
+    gout = values.normal(w.seed, 3, (s, dims[-1]))
+    st.begin_pass()
+    st.processed[2] = 1   # half of the other vertices count as already processed (read from cur)
+    t1 = time.perf_counter()
+    st.lib.oracle_forward_chunk(__import__("ctypes").byref(st._cs), 0)
+    t_f = time.perf_counter() - t1
+    st.bprocessed[2] = 1
+    t2 = time.perf_counter()
+    st.lib.oracle_backward_chunk(__import__("ctypes").byref(st._cs), 0, np.ascontiguousarray(gout).ctypes.data, 1)
+    t_b = time.perf_counter() - t2
+    total = t_f + t_b
+    return {"value": L * edges / total, "unit": "edges/s", "cores": oracle.max_threads(), "kind": "oracle",
+            "sample": f"first {s} destination rows ({edges} entries) of the same graph, all {L} layers, forward "
+                      f"{t_f:.2f}s + backward {t_b:.2f}s, half of the other vertices marked processed",
+            "seconds": round(total, 2)}
+
+
+if __name__ == "__main__":
+    main()

@@ -167,12 +167,14 @@ int64_t gnnstage_plan_tasks(const int64_t *ptr, int64_t row_begin, int64_t row_e
 /*
  * Per-kernel timing with HIP events on the launch stream.  kind: 0 forward aggregation,
  * 1 forward transform, 2 backward transposed aggregation, 3 input-gradient GEMM,
- * 4 weight-gradient GEMM (+bias gradient), 5 history copy, 6 other (masks, weight staging).
- * gnnstage_profile_read synchronises, then returns summed milliseconds and launch count.
+ * 4 weight-gradient GEMM (+bias gradient), 5 history copy, 6 other (masks, weight staging),
+ * 7 long-row reduce of an aggregation.  gnnstage_profile_read synchronises the device, then
+ * returns summed milliseconds and launch count of that kind for one layer (0 <= layer < L) or,
+ * with layer < 0, over all layers.
  */
-enum { GNNSTAGE_NKINDS = 7 };
+enum { GNNSTAGE_NKINDS = 8 };
 int gnnstage_profile_enable(gnnstage_t *st, int32_t on);
-int gnnstage_profile_read(gnnstage_t *st, int32_t kind, double *ms, int64_t *launches);
+int gnnstage_profile_read(gnnstage_t *st, int32_t kind, int32_t layer, double *ms, int64_t *launches);
 int gnnstage_profile_reset(gnnstage_t *st);
 
 /* Library version, e.g. 100 = 0.1.0 */

@@ -16,7 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libgnnstage.so")
 
 GNNSTAGE_GCN, GNNSTAGE_GCNII = 0, 1
 GNNSTAGE_F32, GNNSTAGE_BF16 = 0, 1
-KIND_NAMES = ["spmm_fwd", "gemm_fwd", "spmm_bwd", "gemm_dgrad", "gemm_wgrad", "history_copy", "other"]
+KIND_NAMES = ["spmm_fwd", "gemm_fwd", "spmm_bwd", "gemm_dgrad", "gemm_wgrad", "history_copy", "other", "spmm_reduce"]
 _ERRORS = {-1: "EINVAL", -2: "ERANGE", -3: "EORDER", -4: "ENOMEM", -5: "EHIP", -6: "ENOTSUP"}
 
 
@@ -80,7 +80,7 @@ def _load():
     lib.gnnstage_profile_enable.restype = C.c_int
     lib.gnnstage_profile_enable.argtypes = [C.c_void_p, C.c_int32]
     lib.gnnstage_profile_read.restype = C.c_int
-    lib.gnnstage_profile_read.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    lib.gnnstage_profile_read.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     lib.gnnstage_profile_reset.restype = C.c_int
     lib.gnnstage_profile_reset.argtypes = [C.c_void_p]
     return lib
@@ -231,11 +231,12 @@ class GnnStage:
     def gnnstage_profile_reset(self) -> None:
         self._check(lib.gnnstage_profile_reset(self._h))
 
-    def gnnstage_profile_read(self) -> dict:
+    def gnnstage_profile_read(self, layer: int = -1) -> dict:
+        """{kernel kind: (milliseconds, launches)} for one layer, or summed over layers (layer < 0)."""
         out = {}
         for kind, name in enumerate(KIND_NAMES):
             ms, n = C.c_double(0), C.c_int64(0)
-            self._check(lib.gnnstage_profile_read(self._h, kind, C.byref(ms), C.byref(n)))
+            self._check(lib.gnnstage_profile_read(self._h, kind, int(layer), C.byref(ms), C.byref(n)))
             out[name] = (float(ms.value), int(n.value))
         return out
 

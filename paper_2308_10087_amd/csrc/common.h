@@ -59,8 +59,10 @@ struct SpmmArgs {
 
 enum DType : int { DT_F32 = 0, DT_BF16 = 1 };
 
-// src dtype -> out dtype; returns hipError_t as int
+// src dtype -> out dtype; returns hipError_t as int.  launch_spmm runs the per-task kernel,
+// launch_spmm_reduce adds the pieces of long rows (needed whenever a.n_long > 0).
 int launch_spmm(const SpmmArgs &a, int src_dtype, int out_dtype, hipStream_t s);
+int launch_spmm_reduce(const SpmmArgs &a, int src_dtype, int out_dtype, hipStream_t s);
 
 // ---- dense transforms -------------------------------------------------------------------
 enum GemmEpilogue : int {

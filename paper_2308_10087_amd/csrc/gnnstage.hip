@@ -208,11 +208,17 @@ Layout make_layout(const Shape &s, const PlanCounts &f, const PlanCounts &b) {
 
 struct Profiler {
   bool on = false;
-  struct Rec { int kind; hipEvent_t a, b; };
+  int n_layers = 0;  // slot n_layers collects launches that belong to no layer
+  struct Rec { int kind, layer; hipEvent_t a, b; };
   std::vector<Rec> recs;
   std::vector<hipEvent_t> free_events;
-  double ms[GNNSTAGE_NKINDS] = {0};
-  int64_t launches[GNNSTAGE_NKINDS] = {0};
+  std::vector<double> ms;          // [kind][layer]
+  std::vector<int64_t> launches;   // [kind][layer]
+  void init(int L) {
+    n_layers = L;
+    ms.assign((size_t)GNNSTAGE_NKINDS * (L + 1), 0.0);
+    launches.assign((size_t)GNNSTAGE_NKINDS * (L + 1), 0);
+  }
   hipEvent_t get() {
     if (!free_events.empty()) {
       hipEvent_t e = free_events.back();
@@ -227,8 +233,8 @@ struct Profiler {
     for (auto &r : recs) {
       float t = 0.f;
       if (hipEventElapsedTime(&t, r.a, r.b) == hipSuccess) {
-        ms[r.kind] += t;
-        launches[r.kind] += 1;
+        ms[(size_t)r.kind * (n_layers + 1) + r.layer] += t;
+        launches[(size_t)r.kind * (n_layers + 1) + r.layer] += 1;
       }
       free_events.push_back(r.a);
       free_events.push_back(r.b);
@@ -286,9 +292,10 @@ int fail(gnnstage *st, int code, const std::string &msg) {
 struct Timed {
   gnnstage *st;
   hipStream_t s;
-  int kind;
+  int kind, layer;
   hipEvent_t a = nullptr, b = nullptr;
-  Timed(gnnstage *st_, hipStream_t s_, int kind_) : st(st_), s(s_), kind(kind_) {
+  Timed(gnnstage *st_, hipStream_t s_, int kind_, int layer_ = -1)
+      : st(st_), s(s_), kind(kind_), layer(layer_ < 0 ? st_->prof.n_layers : layer_) {
     if (st->prof.on) {
       a = st->prof.get();
       b = st->prof.get();
@@ -298,7 +305,7 @@ struct Timed {
   ~Timed() {
     if (st->prof.on) {
       (void)hipEventRecord(b, s);
-      st->prof.recs.push_back({kind, a, b});
+      st->prof.recs.push_back({kind, layer, a, b});
     }
   }
 };
@@ -332,6 +339,20 @@ SpmmArgs base_spmm(const gnnstage *st, bool transposed, int chunk) {
   a.vbits = st->vbits;
   a.mask = transposed ? st->bmask : st->fmask;
   return a;
+}
+
+// aggregation kernel and (when the chunk has long rows) the reduce of their pieces, timed apart
+int run_spmm(gnnstage *st, const SpmmArgs &a, int src_dtype, int out_dtype, hipStream_t stream, int kind, int layer) {
+  {
+    Timed t(st, stream, kind, layer);
+    const int e = launch_spmm(a, src_dtype, out_dtype, stream);
+    if (e != 0) return e;
+  }
+  if (a.n_long > 0 && a.n_tasks > 0) {
+    Timed t(st, stream, 7, layer);
+    return launch_spmm_reduce(a, src_dtype, out_dtype, stream);
+  }
+  return 0;
 }
 
 }  // namespace
@@ -426,6 +447,7 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
   st->grad_in = d->grad_in;
   st->grad_h0 = d->grad_h0;
   st->ws = static_cast<char *>(d->workspace);
+  st->prof.init(s.L);
   st->h_row_ptr.assign(d->row_ptr, d->row_ptr + s.n + 1);
   st->h_pcol = pcol;
 
@@ -543,7 +565,6 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
   for (int j = 0; j < s.L; ++j) {
     char *Zj = st->at<char>(st->lay.Z[j]);
     {
-      Timed t(st, stream, 0);
       SpmmArgs a = base_spmm(st, false, k);
       a.src_sel = st->cur[j];
       a.src_unsel = st->hist[j];
@@ -561,10 +582,10 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
       } else {
         a.epilogue = SPMM_PLAIN;
       }
-      HIP_TRY(st, launch_spmm(a, st->level_dtype(j), cd, stream));
+      HIP_TRY(st, run_spmm(st, a, st->level_dtype(j), cd, stream, 0, j));
     }
     {
-      Timed t(st, stream, 1);
+      Timed t(st, stream, 1, j);
       GemmNtArgs g{};
       g.A = Zj + (size_t)row0 * s.ld[j] * celt;
       g.lda = s.ld[j];
@@ -617,7 +638,7 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
     const char *dY = G[gi];
     const char *Zrows = st->at<char>(st->lay.Z[j]) + (size_t)row0 * s.ld[j] * celt;
     {
-      Timed t(st, stream, 4);
+      Timed t(st, stream, 4, j);
       GemmTnArgs w{};
       w.A = Zrows;
       w.lda = s.ld[j];
@@ -637,7 +658,7 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
     if (j == 0 && !s.need_input_grad) break;
     char *dZj = st->at<char>(st->lay.dZ[j]);
     {
-      Timed t(st, stream, 3);
+      Timed t(st, stream, 3, j);
       GemmNtArgs g{};
       g.A = dY;
       g.lda = s.ld[j + 1];
@@ -662,7 +683,6 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
       HIP_TRY(st, launch_gemm_nt(g, cd, cd, stream));
     }
     {
-      Timed t(st, stream, 2);
       SpmmArgs a = base_spmm(st, true, k);
       a.src_sel = dZj;
       a.src_unsel = nullptr;  // Section 3.4: nothing flows back from unprocessed vertices
@@ -675,13 +695,13 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
         a.epilogue = SPMM_MASK;
         a.aux = st->cur[j];
         a.aux_ld = s.dims[j];
-        HIP_TRY(st, launch_spmm(a, cd, cd, stream));
+        HIP_TRY(st, run_spmm(st, a, cd, cd, stream, 2, j));
       } else {
         a.out = st->grad_in;
         a.out_ld = s.dims[0];
         a.out_row0 = 0;
         a.epilogue = SPMM_PLAIN;
-        HIP_TRY(st, launch_spmm(a, cd, st->level_dtype(0), stream));
+        HIP_TRY(st, run_spmm(st, a, cd, st->level_dtype(0), stream, 2, j));
       }
     }
     gi ^= 1;
@@ -722,12 +742,20 @@ extern "C" int gnnstage_profile_enable(gnnstage_t *st, int32_t on) {
   return GNNSTAGE_OK;
 }
 
-extern "C" int gnnstage_profile_read(gnnstage_t *st, int32_t kind, double *ms, int64_t *launches) {
-  if (!st || kind < 0 || kind >= GNNSTAGE_NKINDS) return GNNSTAGE_EINVAL;
+extern "C" int gnnstage_profile_read(gnnstage_t *st, int32_t kind, int32_t layer, double *ms, int64_t *launches) {
+  if (!st || kind < 0 || kind >= GNNSTAGE_NKINDS || layer >= st->s.L) return GNNSTAGE_EINVAL;
   if (hipDeviceSynchronize() != hipSuccess) return fail(st, GNNSTAGE_EHIP, "device synchronisation failed");
   st->prof.collect();
-  if (ms) *ms = st->prof.ms[kind];
-  if (launches) *launches = st->prof.launches[kind];
+  double t = 0;
+  int64_t n = 0;
+  const int L1 = st->s.L + 1;
+  for (int j = 0; j < L1; ++j) {
+    if (layer >= 0 && j != layer) continue;
+    t += st->prof.ms[(size_t)kind * L1 + j];
+    n += st->prof.launches[(size_t)kind * L1 + j];
+  }
+  if (ms) *ms = t;
+  if (launches) *launches = n;
   return GNNSTAGE_OK;
 }
 
@@ -735,9 +763,6 @@ extern "C" int gnnstage_profile_reset(gnnstage_t *st) {
   if (!st) return GNNSTAGE_EINVAL;
   if (hipDeviceSynchronize() != hipSuccess) return fail(st, GNNSTAGE_EHIP, "device synchronisation failed");
   st->prof.collect();
-  for (int i = 0; i < GNNSTAGE_NKINDS; ++i) {
-    st->prof.ms[i] = 0;
-    st->prof.launches[i] = 0;
-  }
+  st->prof.init(st->s.L);
   return GNNSTAGE_OK;
 }

@@ -205,8 +205,7 @@ const Shape *shapes_f32(int *n) {
 
 }  // namespace
 
-int launch_spmm(const SpmmArgs &a, int src_dtype, int out_dtype, hipStream_t s) {
-  if (a.n_tasks <= 0) return hipSuccess;
+static const Shape *pick_shape(const SpmmArgs &a, int src_dtype, int out_dtype) {
   int n = 0;
   const Shape *tab;
   if (src_dtype == DT_BF16)
@@ -222,7 +221,7 @@ int launch_spmm(const SpmmArgs &a, int src_dtype, int out_dtype, hipStream_t s) 
     for (int k = 0; k < 4; ++k) ok = ok && (lds[k] % tab[i].vec == 0);
     if (ok && tab[i].vec > best_vec) best_vec = tab[i].vec;
   }
-  if (best_vec == 0) return hipErrorInvalidValue;  // bf16 rows of odd width are rejected at create time
+  if (best_vec == 0) return nullptr;  // bf16 rows of odd width are rejected at create time
   const int nvec = a.d / best_vec;
   for (int i = 0; i < n; ++i) {  // smallest tile that covers the row, else the widest tile
     if (tab[i].vec != best_vec) continue;
@@ -234,14 +233,23 @@ int launch_spmm(const SpmmArgs &a, int src_dtype, int out_dtype, hipStream_t s) 
       if ((bc < nvec && cover > bc) || (cover >= nvec && cover < bc)) best = &tab[i];
     }
   }
+  return best;
+}
+
+int launch_spmm(const SpmmArgs &a, int src_dtype, int out_dtype, hipStream_t s) {
+  if (a.n_tasks <= 0) return hipSuccess;
+  const Shape *best = pick_shape(a, src_dtype, out_dtype);
+  if (!best) return hipErrorInvalidValue;
   const int tile_w = best->lpr * best->nv * best->vec;
   dim3 grid((unsigned)((a.n_tasks + 3) / 4), (unsigned)((a.d + tile_w - 1) / tile_w));
   hipLaunchKernelGGL(best->main, grid, dim3(256), 0, s, a);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return (int)e;
-  if (a.n_long > 0) {
-    hipLaunchKernelGGL(best->reduce, dim3((unsigned)a.n_long), dim3(256), 0, s, a);
-    e = hipGetLastError();
-  }
-  return (int)e;
+  return (int)hipGetLastError();
+}
+
+int launch_spmm_reduce(const SpmmArgs &a, int src_dtype, int out_dtype, hipStream_t s) {
+  if (a.n_long <= 0) return hipSuccess;
+  const Shape *best = pick_shape(a, src_dtype, out_dtype);
+  if (!best) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(best->reduce, dim3((unsigned)a.n_long), dim3(256), 0, s, a);
+  return (int)hipGetLastError();
 }
