@@ -143,43 +143,51 @@ def main():
     value = L * nnz / (elapsed / args.steps)
 
     # ---- roofline of the dominant kernel -------------------------------------------------
-    # The aggregation kernel instance that gathers rows of the hidden width serves forward layers
-    # 1..L-1 and backward layers 1..L-1 (one instantiation, same launch shape), so they are one group.
+    # Aggregation launches are grouped by the rows they gather (width, element type): one kernel
+    # instantiation and launch shape per group, the same grouping rocprofv3 shows by kernel name.
+    # Algorithmic bytes of a launch over chunk k: every entry's packed index + weight (8 B), the chunk's
+    # row pointers, each DISTINCT gathered source row once, the output rows (+ the level rows a masking
+    # epilogue reads).  Backward launches gather only entries whose reader chunk is already processed.
     E, D = pair_counts(row_ptr, col, chunk_ptr)
     rows = np.diff(chunk_ptr)
     elt = 2 if bf else 4
+    tf = [st.gnnstage_layer_order(j) for j in range(L)]
+    shared0 = hist[0].data_ptr() == cur[0].data_ptr()
     groups = {}
 
-    def add(group, nbytes, ms, launches):
-        gr = groups.setdefault(group, [0.0, 0.0, 0])
+    def add(group, nbytes, gather, ms, launches):
+        gr = groups.setdefault(group, [0.0, 0.0, 0.0, 0])
         gr[0] += nbytes
-        gr[1] += ms
-        gr[2] += launches
+        gr[1] += gather
+        gr[2] += ms
+        gr[3] += launches
 
+    def gname(d, e):
+        return f"spmm gather width {d} {'f32' if e == 4 else 'bf16'}"
+
+    struct = [E[k].sum() * 8 + 8 * (rows[k] + 1) for k in range(K)]
     for j in range(L):
-        e_in = 4 if (j == 0 and l0 == torch.float32) else elt
-        name_f = f"spmm d={dims[j]} in={'f32' if e_in == 4 else 'bf16'}"
-        fwd_bytes = 0.0
-        for _ in orders:
-            for k in range(K):
-                # every entry's index + weight, the row pointers, each distinct source row once, the output rows
-                fwd_bytes += E[k].sum() * 8 + 8 * (rows[k] + 1) + D[k].sum() * dims[j] * e_in + rows[k] * dims[j] * elt
-        add(name_f, fwd_bytes, *prof_layer[j]["spmm_fwd"])
-        if j == 0 and grad_in is None:
-            continue
-        e_src = elt
-        name_b = f"spmm d={dims[j]} in={'f32' if e_src == 4 else 'bf16'}"
-        bwd_bytes = 0.0
+        lvl_e = 4 if (j == 0 and l0 == torch.float32) else elt
+        dg, eg = (dims[j + 1], elt) if tf[j] else (dims[j], lvl_e)       # what the forward gathers
+        fb = sum(struct[k] + D[k].sum() * dg * eg + rows[k] * (dims[j + 1] if tf[j] else dims[j]) * elt
+                 for k in range(K)) * len(orders)
+        add(gname(dg, eg), fb, E.sum() * dg * eg * len(orders), *prof_layer[j]["spmm_fwd"])
+        db_, eb = (dims[j + 1], elt) if tf[j] else (dims[j], elt)        # what the backward gathers
+        bb = gb = 0.0
+        masked = (j > 0 or grad_in is not None) and not (tf[j] and j == 0 and shared0 and grad_in is None)
         for order in orders:
             done = np.zeros(K, dtype=bool)
             for k in reversed(list(order)):
                 done[k] = True
-                # symmetric graph: the transposed rows of chunk k have the same pair counts
-                bwd_bytes += E[k].sum() * 8 + 8 * (rows[k] + 1) + D[k][done].sum() * dims[j] * e_src
-                bwd_bytes += rows[k] * dims[j] * elt * (2 if j > 0 else 1)  # output rows (+ level rows for the mask)
-        add(name_b, bwd_bytes, *prof_layer[j]["spmm_bwd"])
-    dom = max(groups.items(), key=lambda kv: kv[1][1])
-    dom_name, (dom_bytes, dom_ms, dom_launches) = dom
+                if masked:
+                    bb += struct[k] + D[k][done].sum() * db_ * eb + rows[k] * db_ * elt * (2 if (j > 0 and not tf[j]) else 1)
+                    gb += E[k][done].sum() * db_ * eb
+            if tf[j]:  # end-of-pass unmasked transposed aggregation of a transform-first layer
+                bb += sum(struct[k] + D[k].sum() * db_ * eb + rows[k] * db_ * elt for k in range(K))
+                gb += E.sum() * db_ * eb
+        if prof_layer[j]["spmm_bwd"][1] > 0:
+            add(gname(db_, eb), bb, gb, *prof_layer[j]["spmm_bwd"])
+    dom_name, (dom_bytes, dom_gather, dom_ms, dom_launches) = max(groups.items(), key=lambda kv: kv[1][2])
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
@@ -191,9 +199,9 @@ def main():
         "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
         "algorithmic_bytes_per_launch": round(dom_bytes / max(dom_launches, 1)),
         "avg_launch_ms": round(dom_ms / max(dom_launches, 1), 4), "launches": dom_launches,
-        "gather_GBps": round(sum(
-            (E.sum() * dims[j] * (4 if (j == 0 and l0 == torch.float32) else elt)) for j in range(L)) * len(orders) / 1e9 /
-            max(sum(prof_layer[j]["spmm_fwd"][0] for j in range(L)) * 1e-3, 1e-9), 1),
+        "gathered_bytes_per_launch": round(dom_gather / max(dom_launches, 1)),
+        "gather_GBps": round(dom_gather / max(dom_ms * 1e-3, 1e-12) / 1e9, 1),
+        "layer_order": ["transform-first" if t else "aggregate-first" for t in tf],
     }
     kernels_ms = {k: round(v[0] / args.steps, 3) for k, v in prof_all.items()}
 

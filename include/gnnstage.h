@@ -147,6 +147,14 @@ const char *gnnstage_last_error(const gnnstage_t *st);
 int gnnstage_debug_select_counts(gnnstage_t *st, int32_t chunk_id, int32_t *out);
 
 /*
+ * Order in which layer j (0 <= j < L) applies its two steps: 0 = aggregate, then transform (the order
+ * Algorithm 1 prints); 1 = transform, then aggregate.  Both compute A_hat H W with the same per-edge
+ * current/history choice; the library transforms first when that narrows the rows the aggregation
+ * gathers (d_{j+1} * element size < d_j * element size), GCN layers only.  Negative on error.
+ */
+int gnnstage_layer_order(const gnnstage_t *st, int32_t layer);
+
+/*
  * Host-only planning helpers (no GPU needed), exported so that the integer bookkeeping can be
  * checked on a CPU: the transposed index (column u -> rows v ascending, with the position of
  * each entry in the CSR arrays) and the packed column words (vertex id | chunk id << vbits).

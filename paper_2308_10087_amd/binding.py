@@ -77,6 +77,8 @@ def _load():
     lib.gnnstage_plan_tasks.restype = C.c_int64
     lib.gnnstage_plan_tasks.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_void_p, C.POINTER(C.c_int64)]
+    lib.gnnstage_layer_order.restype = C.c_int
+    lib.gnnstage_layer_order.argtypes = [C.c_void_p, C.c_int32]
     lib.gnnstage_profile_enable.restype = C.c_int
     lib.gnnstage_profile_enable.argtypes = [C.c_void_p, C.c_int32]
     lib.gnnstage_profile_read.restype = C.c_int
@@ -224,6 +226,12 @@ class GnnStage:
         out = np.zeros(max(rows, 1), dtype=np.int32)
         self._check(lib.gnnstage_debug_select_counts(self._h, int(chunk_id), out.ctypes.data))
         return out[:rows]
+
+    def gnnstage_layer_order(self, layer: int) -> int:
+        rc = lib.gnnstage_layer_order(self._h, int(layer))
+        if rc < 0:
+            raise GnnStageError(rc, "gnnstage_layer_order")
+        return rc
 
     def gnnstage_profile_enable(self, on: bool) -> None:
         self._check(lib.gnnstage_profile_enable(self._h, int(on)))

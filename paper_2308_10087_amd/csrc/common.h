@@ -18,9 +18,10 @@ __host__ __device__ inline bool mask_test(const ChunkMask &m, uint32_t c) {
 
 // ---- aggregation (SpMM with current/history select) ---------------------------------
 enum SpmmEpilogue : int {
-  SPMM_PLAIN = 0,  // out = acc
-  SPMM_MIX = 1,    // out = s_acc * acc + s_aux * aux[row]      (GCNII initial residual)
-  SPMM_MASK = 2    // out = aux[row] > 0 ? acc : 0              (ReLU derivative on the way back)
+  SPMM_PLAIN = 0,     // out = acc
+  SPMM_MIX = 1,       // out = s_acc * acc + s_aux * aux[row]      (GCNII initial residual)
+  SPMM_MASK = 2,      // out = aux[row] > 0 ? acc : 0              (ReLU derivative on the way back)
+  SPMM_BIAS_RELU = 3  // out = max(acc + bias[c], 0)               (transform-first layers)
 };
 
 struct SpmmArgs {
@@ -55,6 +56,7 @@ struct SpmmArgs {
   const void *aux;  // indexed by absolute row, leading dimension aux_ld, same dtype as src
   int32_t aux_ld;
   float s_acc, s_aux;
+  const float *bias;  // SPMM_BIAS_RELU
 };
 
 enum DType : int { DT_F32 = 0, DT_BF16 = 1 };
@@ -66,34 +68,43 @@ int launch_spmm_reduce(const SpmmArgs &a, int src_dtype, int out_dtype, hipStrea
 
 // ---- dense transforms -------------------------------------------------------------------
 enum GemmEpilogue : int {
-  EPI_FWD_GCN = 0,    // out = ReLU(acc + bias[n])
-  EPI_FWD_GCNII = 1,  // out = ReLU((1-beta) aux[m][n] + beta acc)
-  EPI_DGRAD_GCN = 2,  // out = acc
-  EPI_DGRAD_GCNII = 3 // dp = (1-beta) aux[m][n] + beta acc; out = (1-alpha) dp; h0grad[m][n] += alpha dp
+  EPI_FWD_GCN = 0,     // out = ReLU(acc + bias[n])
+  EPI_FWD_GCNII = 1,   // out = ReLU((1-beta) aux[m][n] + beta acc)
+  EPI_PLAIN = 2,       // out = acc
+  EPI_DGRAD_GCNII = 3, // dp = (1-beta) aux[m][n] + beta acc; out = (1-alpha) dp; h0grad[m][n] += alpha dp
+  EPI_MASK = 4         // out = aux[m][n] > 0 ? acc : 0
 };
 
-// C[M x N] = A[M x Kp] . Bt[N x Kp]^T  (both operands K-contiguous, zero padded to Kp, Kp % 8 == 0)
+// C[M x N] = A[M x K] . Bt[N x Kp]^T.  Bt is an internal buffer: K-contiguous rows, zero padded to Kp,
+// Kp % 8 == 0, compute dtype.  A is either such a padded buffer too, or any row-major matrix of fp32 or
+// bf16 elements with K valid columns (read with bounds checks).
 struct GemmNtArgs {
   const void *A;
+  int32_t a_dtype;
   int32_t lda;
   const void *Bt;
   int32_t ldb;
-  int32_t M, N, Kp;
+  int32_t M, N, K, Kp;
   int32_t epilogue;
   const float *bias;
-  const void *aux;  // compute dtype
+  const void *aux;
+  int32_t aux_dtype;
   int32_t aux_ld;
   float alpha, beta;
   float *h0grad;  // fp32, pre-offset to the first row
   int32_t h0_ld;
   void *out;
+  int32_t out_dtype;
   int32_t out_ld;
+  int32_t out_pad;  // columns [N, out_pad) of every output row are written as zeros (0: none)
 };
-int launch_gemm_nt(const GemmNtArgs &a, int compute_dtype, int out_dtype, hipStream_t s);
+int launch_gemm_nt(const GemmNtArgs &a, int compute_dtype, hipStream_t s);
 
-// dW[I x O] += scale * A[M x I]^T . B[M x O]   (reduction over the M rows of the chunk)
+// dW[I x O] += scale * A[M x I]^T . B[M x O]   (reduction over the M rows of the chunk).
+// B is an internal padded buffer in the compute dtype; A as for the NT product.
 struct GemmTnArgs {
   const void *A;
+  int32_t a_dtype;
   int32_t lda;
   const void *B;
   int32_t ldb;
@@ -102,10 +113,11 @@ struct GemmTnArgs {
   float *dW;       // fp32 [I][O]
   float *partial;  // fp32 scratch [splits][I][O]
   int32_t max_splits;
-  float *dbias;          // optional: dbias[O] += column sums of B
-  float *bias_partial;   // fp32 scratch [splits][O]
 };
 int launch_gemm_tn(const GemmTnArgs &a, int compute_dtype, hipStream_t s);
+// dst[o] += sum over the M rows of B[.][o]; partial: fp32 scratch [max_splits][O]
+int launch_colsum_add(const void *B, int dtype, int ldb, int M, int O, float *partial, int max_splits, float *dst,
+                      hipStream_t s);
 
 // ---- small kernels ------------------------------------------------------------------------
 // Wt[N][Kp] (transposed) and Wn[K][Np] (plain) zero-padded copies of W[K][N] in the compute dtype

@@ -1,11 +1,14 @@
 // Dense transforms of the stage (the UPDATE line of Algorithm 1 and its gradients).
 //
-//   NT:  C[M x N]  = A[M x Kp] . Bt[N x Kp]^T     forward transform and input gradient
+//   NT:  C[M x N]  = A[M x K] . Bt[N x Kp]^T      forward transform and input gradient
 //   TN:  dW[I x O] += s * A[M x I]^T . B[M x O]    weight gradient (reduction over chunk rows)
 //
 // bf16 operands go through the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32
 // accumulation); the fp32 variants are plain LDS-tiled FMA kernels used by the fp32 stage.
 // Bias / ReLU / GCNII residual terms are applied in the epilogue on the fp32 accumulators.
+// Bt and B always live in the library's zero-padded internal buffers (16-byte aligned rows);
+// A may also be a caller-owned level buffer of any width and of fp32 or bf16 type, in which case
+// it is read element-wise with bounds checks and converted while it is staged into LDS.
 #include "common.h"
 
 namespace {
@@ -16,15 +19,18 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 __device__ inline float to_f32(float x) { return x; }
 __device__ inline float to_f32(bf16_t x) { return (float)x; }
-template <typename T>
-__device__ inline T from_f32(float x);
-template <>
-__device__ inline float from_f32<float>(float x) { return x; }
-template <>
-__device__ inline bf16_t from_f32<bf16_t>(float x) { return (bf16_t)x; }
 
-// One output element of an NT product: epilogue + store.  T is both the dtype of aux and of out.
-template <typename T>
+__device__ inline float load_f32(const void *p, int dtype, size_t idx) {
+  return dtype == DT_BF16 ? (float)static_cast<const bf16_t *>(p)[idx] : static_cast<const float *>(p)[idx];
+}
+__device__ inline void store_f32(void *p, int dtype, size_t idx, float v) {
+  if (dtype == DT_BF16)
+    static_cast<bf16_t *>(p)[idx] = (bf16_t)v;
+  else
+    static_cast<float *>(p)[idx] = v;
+}
+
+// One output element of an NT product: epilogue + store.
 __device__ inline void epilogue_store(const GemmNtArgs &a, int m, int n, float acc) {
   float r;
   switch (a.epilogue) {
@@ -34,38 +40,59 @@ __device__ inline void epilogue_store(const GemmNtArgs &a, int m, int n, float a
       break;
     }
     case EPI_FWD_GCNII: {
-      const float p = to_f32(static_cast<const T *>(a.aux)[(size_t)m * a.aux_ld + n]);
+      const float p = load_f32(a.aux, a.aux_dtype, (size_t)m * a.aux_ld + n);
       r = (1.f - a.beta) * p + a.beta * acc;
       r = r > 0.f ? r : 0.f;
       break;
     }
-    case EPI_DGRAD_GCN: {
+    case EPI_PLAIN: {
       r = acc;
       break;
     }
+    case EPI_MASK: {
+      r = load_f32(a.aux, a.aux_dtype, (size_t)m * a.aux_ld + n) > 0.f ? acc : 0.f;
+      break;
+    }
     default: {  // EPI_DGRAD_GCNII
-      const float dy = to_f32(static_cast<const T *>(a.aux)[(size_t)m * a.aux_ld + n]);
+      const float dy = load_f32(a.aux, a.aux_dtype, (size_t)m * a.aux_ld + n);
       const float dp = (1.f - a.beta) * dy + a.beta * acc;
       r = (1.f - a.alpha) * dp;
       if (a.h0grad) a.h0grad[(size_t)m * a.h0_ld + n] += a.alpha * dp;
       break;
     }
   }
-  static_cast<T *>(a.out)[(size_t)m * a.out_ld + n] = from_f32<T>(r);
+  store_f32(a.out, a.out_dtype, (size_t)m * a.out_ld + n, r);
+}
+
+// 8 consecutive elements of row `r` starting at column `c` as bf16; columns >= cols read as zero.
+template <typename T, bool VEC>
+__device__ inline bf16x8 load8_bf16(const T *base, size_t ld, int r, int c, int cols) {
+  bf16x8 out = {0, 0, 0, 0, 0, 0, 0, 0};
+  if constexpr (VEC) {
+    if (c < cols) out = *reinterpret_cast<const bf16x8 *>(base + (size_t)r * ld + c);
+  } else {
+    const T *p = base + (size_t)r * ld + c;
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+      if (c + t < cols) out[t] = (bf16_t)to_f32(p[t]);
+  }
+  return out;
 }
 
 // ------------------------------------------------------------------------------------ bf16 NT
 constexpr int BM = 128, BN = 128, BK = 32;
 constexpr int LDS_K = 40;  // padded K stride (elements): 80-byte rows keep 16-byte fragment reads conflict-free
 
+template <typename TA, bool VEC>
 __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmNtArgs a) {
   __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * LDS_K];
   __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * LDS_K];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
   const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
-  const bf16_t *A = static_cast<const bf16_t *>(a.A);
+  const TA *A = static_cast<const TA *>(a.A);
   const bf16_t *Bt = static_cast<const bf16_t *>(a.Bt);
+  const int a_cols = VEC ? a.Kp : a.K;  // padded operands are valid (zero) up to Kp
 
   f32x16 acc[2][2];
 #pragma unroll
@@ -81,7 +108,7 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmNtArgs a) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int vid = tid + 256 * i, r = vid >> 2, k = k0 + (vid & 3) * 8;
-      ra[i] = (m0 + r < a.M && k < a.Kp) ? *reinterpret_cast<const bf16x8 *>(A + (size_t)(m0 + r) * a.lda + k) : zero8;
+      ra[i] = (m0 + r < a.M) ? load8_bf16<TA, VEC>(A, (size_t)a.lda, m0 + r, k, a_cols) : zero8;
       rb[i] = (n0 + r < a.N && k < a.Kp) ? *reinterpret_cast<const bf16x8 *>(Bt + (size_t)(n0 + r) * a.ldb + k) : zero8;
     }
   };
@@ -131,7 +158,10 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmNtArgs a) {
       for (int t = 0; t < 16; ++t) {
         const int m = m0 + wm + i * 32 + 8 * (t >> 2) + 4 * (lane >> 5) + (t & 3);
         const int n = n0 + wn + j * 32 + (lane & 31);
-        if (m < a.M && n < a.N) epilogue_store<bf16_t>(a, m, n, acc[i][j][t]);
+        if (m < a.M && n < a.N)
+          epilogue_store(a, m, n, acc[i][j][t]);
+        else if (m < a.M && n < a.out_pad)
+          store_f32(a.out, a.out_dtype, (size_t)m * a.out_ld + n, 0.f);
       }
 }
 
@@ -139,6 +169,7 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmNtArgs a) {
 constexpr int TR = 32;      // reduction rows per step
 constexpr int LDS_C = 136;  // padded column stride of the row-major LDS tiles
 
+template <typename TA, bool VEC>
 __global__ __launch_bounds__(256) void gemm_tn_bf16_kernel(const GemmTnArgs a, int rows_per_split) {
   __shared__ __attribute__((aligned(16))) bf16_t As[TR * LDS_C];
   __shared__ __attribute__((aligned(16))) bf16_t Bs[TR * LDS_C];
@@ -147,9 +178,10 @@ __global__ __launch_bounds__(256) void gemm_tn_bf16_kernel(const GemmTnArgs a, i
   const int wi = (wave >> 1) * 64, wo = (wave & 1) * 64;
   const int r_begin = blockIdx.z * rows_per_split;
   const int r_end = min(a.M, r_begin + rows_per_split);
-  const bf16_t *A = static_cast<const bf16_t *>(a.A);
+  const TA *A = static_cast<const TA *>(a.A);
   const bf16_t *B = static_cast<const bf16_t *>(a.B);
   const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  const int a_cols = VEC ? a.lda : a.I;
 
   f32x16 acc[2][2];
 #pragma unroll
@@ -165,7 +197,7 @@ __global__ __launch_bounds__(256) void gemm_tn_bf16_kernel(const GemmTnArgs a, i
     for (int i = 0; i < 2; ++i) {
       const int vid = tid + 256 * i, r = vid >> 4, c = (vid & 15) * 8;
       const bool rv = r0 + r < r_end;
-      ra[i] = (rv && i0 + c < a.lda) ? *reinterpret_cast<const bf16x8 *>(A + (size_t)(r0 + r) * a.lda + i0 + c) : zero8;
+      ra[i] = rv ? load8_bf16<TA, VEC>(A, (size_t)a.lda, r0 + r, i0 + c, a_cols) : zero8;
       rb[i] = (rv && o0 + c < a.ldb) ? *reinterpret_cast<const bf16x8 *>(B + (size_t)(r0 + r) * a.ldb + o0 + c) : zero8;
     }
     __syncthreads();  // previous step's fragment reads are done
@@ -209,6 +241,7 @@ __global__ __launch_bounds__(256) void gemm_tn_bf16_kernel(const GemmTnArgs a, i
 }
 
 // ------------------------------------------------------------------------------------ fp32 NT
+template <bool VEC>
 __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmNtArgs a) {
   constexpr int T = 64, KB = 16;
   __shared__ float As[KB][T + 4];
@@ -221,7 +254,16 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmNtArgs a) {
   const int lr = tid >> 2, lk = (tid & 3) * 4;
   for (int k0 = 0; k0 < a.Kp; k0 += KB) {
     f32x4 va = {0.f, 0.f, 0.f, 0.f}, vb = {0.f, 0.f, 0.f, 0.f};
-    if (m0 + lr < a.M && k0 + lk < a.Kp) va = *reinterpret_cast<const f32x4 *>(A + (size_t)(m0 + lr) * a.lda + k0 + lk);
+    if (m0 + lr < a.M) {
+      const float *p = A + (size_t)(m0 + lr) * a.lda + k0 + lk;
+      if constexpr (VEC) {
+        if (k0 + lk < a.Kp) va = *reinterpret_cast<const f32x4 *>(p);
+      } else {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+          if (k0 + lk + t < a.K) va[t] = p[t];
+      }
+    }
     if (n0 + lr < a.N && k0 + lk < a.Kp) vb = *reinterpret_cast<const f32x4 *>(Bt + (size_t)(n0 + lr) * a.ldb + k0 + lk);
     __syncthreads();
 #pragma unroll
@@ -249,11 +291,15 @@ __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmNtArgs a) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
-      if (m < a.M && n < a.N) epilogue_store<float>(a, m, n, acc[i][j]);
+      if (m < a.M && n < a.N)
+        epilogue_store(a, m, n, acc[i][j]);
+      else if (m < a.M && n < a.out_pad)
+        store_f32(a.out, a.out_dtype, (size_t)m * a.out_ld + n, 0.f);
     }
 }
 
 // ------------------------------------------------------------------------------------ fp32 TN
+template <bool VEC>
 __global__ __launch_bounds__(256) void gemm_tn_f32_kernel(const GemmTnArgs a, int rows_per_split) {
   constexpr int T = 64, RB = 16;
   __shared__ float As[RB][T + 4];
@@ -268,8 +314,17 @@ __global__ __launch_bounds__(256) void gemm_tn_f32_kernel(const GemmTnArgs a, in
   const int lr = tid >> 4, lc = (tid & 15) * 4;
   for (int r0 = r_begin; r0 < r_end; r0 += RB) {
     f32x4 va = {0.f, 0.f, 0.f, 0.f}, vb = {0.f, 0.f, 0.f, 0.f};
-    if (r0 + lr < r_end && i0 + lc < a.lda) va = *reinterpret_cast<const f32x4 *>(A + (size_t)(r0 + lr) * a.lda + i0 + lc);
-    if (r0 + lr < r_end && o0 + lc < a.ldb) vb = *reinterpret_cast<const f32x4 *>(B + (size_t)(r0 + lr) * a.ldb + o0 + lc);
+    if (r0 + lr < r_end) {
+      const float *p = A + (size_t)(r0 + lr) * a.lda + i0 + lc;
+      if constexpr (VEC) {
+        if (i0 + lc < a.lda) va = *reinterpret_cast<const f32x4 *>(p);
+      } else {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+          if (i0 + lc + t < a.I) va[t] = p[t];
+      }
+      if (o0 + lc < a.ldb) vb = *reinterpret_cast<const f32x4 *>(B + (size_t)(r0 + lr) * a.ldb + o0 + lc);
+    }
     __syncthreads();
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
@@ -311,29 +366,44 @@ __global__ __launch_bounds__(256) void reduce_add_kernel(const float *partial, i
   dst[e] += scale * s;
 }
 
-// partial[split][o] = sum of B[r][o] over the split's rows
+// partial[split][o] = sum of B[r][o] over the split's rows: 64 columns x 4 row phases per block
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_kernel(const T *B, int ldb, int M, int O, int rows_per_split, float *partial) {
-  const int o = blockIdx.x * 256 + threadIdx.x;
-  if (o >= O) return;
+  __shared__ float red[4][64];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int o = blockIdx.x * 64 + tx;
   const int r_begin = blockIdx.y * rows_per_split;
   const int r_end = min(M, r_begin + rows_per_split);
   float s = 0.f;
-  for (int r = r_begin; r < r_end; ++r) s += to_f32(B[(size_t)r * ldb + o]);
-  partial[(size_t)blockIdx.y * O + o] = s;
+  if (o < O)
+    for (int r = r_begin + ty; r < r_end; r += 4) s += to_f32(B[(size_t)r * ldb + o]);
+  red[ty][tx] = s;
+  __syncthreads();
+  if (ty == 0 && o < O) partial[(size_t)blockIdx.y * O + o] = (red[0][tx] + red[1][tx]) + (red[2][tx] + red[3][tx]);
 }
+
+bool vec_ok(const void *p, int ld, int mult) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0 && ld % mult == 0; }
 
 }  // namespace
 
-int launch_gemm_nt(const GemmNtArgs &a, int compute_dtype, int out_dtype, hipStream_t s) {
+int launch_gemm_nt(const GemmNtArgs &a, int compute_dtype, hipStream_t s) {
   if (a.M <= 0 || a.N <= 0) return hipSuccess;
-  if (compute_dtype != out_dtype) return hipErrorInvalidValue;
   if (compute_dtype == DT_BF16) {
     dim3 grid((a.M + BM - 1) / BM, (a.N + BN - 1) / BN);
-    hipLaunchKernelGGL(gemm_nt_bf16_kernel, grid, dim3(256), 0, s, a);
+    const bool vec = a.a_dtype == DT_BF16 && vec_ok(a.A, a.lda, 8) && a.lda >= a.Kp;
+    if (a.a_dtype == DT_F32)
+      hipLaunchKernelGGL((gemm_nt_bf16_kernel<float, false>), grid, dim3(256), 0, s, a);
+    else if (vec)
+      hipLaunchKernelGGL((gemm_nt_bf16_kernel<bf16_t, true>), grid, dim3(256), 0, s, a);
+    else
+      hipLaunchKernelGGL((gemm_nt_bf16_kernel<bf16_t, false>), grid, dim3(256), 0, s, a);
   } else {
+    if (a.a_dtype != DT_F32) return hipErrorInvalidValue;
     dim3 grid((a.M + 63) / 64, (a.N + 63) / 64);
-    hipLaunchKernelGGL(gemm_nt_f32_kernel, grid, dim3(256), 0, s, a);
+    if (vec_ok(a.A, a.lda, 4) && a.lda >= a.Kp)
+      hipLaunchKernelGGL(gemm_nt_f32_kernel<true>, grid, dim3(256), 0, s, a);
+    else
+      hipLaunchKernelGGL(gemm_nt_f32_kernel<false>, grid, dim3(256), 0, s, a);
   }
   return (int)hipGetLastError();
 }
@@ -350,30 +420,42 @@ int launch_gemm_tn(const GemmTnArgs &a, int compute_dtype, hipStream_t s) {
   rows_per = (rows_per + step - 1) / step * step;
   splits = (a.M + rows_per - 1) / rows_per;
   dim3 grid(ti, to, splits);
-  if (compute_dtype == DT_BF16)
-    hipLaunchKernelGGL(gemm_tn_bf16_kernel, grid, dim3(256), 0, s, a, rows_per);
-  else
-    hipLaunchKernelGGL(gemm_tn_f32_kernel, grid, dim3(256), 0, s, a, rows_per);
+  if (compute_dtype == DT_BF16) {
+    if (a.a_dtype == DT_F32)
+      hipLaunchKernelGGL((gemm_tn_bf16_kernel<float, false>), grid, dim3(256), 0, s, a, rows_per);
+    else if (vec_ok(a.A, a.lda, 8))
+      hipLaunchKernelGGL((gemm_tn_bf16_kernel<bf16_t, true>), grid, dim3(256), 0, s, a, rows_per);
+    else
+      hipLaunchKernelGGL((gemm_tn_bf16_kernel<bf16_t, false>), grid, dim3(256), 0, s, a, rows_per);
+  } else {
+    if (a.a_dtype != DT_F32) return hipErrorInvalidValue;
+    if (vec_ok(a.A, a.lda, 4))
+      hipLaunchKernelGGL(gemm_tn_f32_kernel<true>, grid, dim3(256), 0, s, a, rows_per);
+    else
+      hipLaunchKernelGGL(gemm_tn_f32_kernel<false>, grid, dim3(256), 0, s, a, rows_per);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return (int)e;
   const size_t count = (size_t)a.I * a.O;
   hipLaunchKernelGGL(reduce_add_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, a.partial, splits, count,
                      a.scale, a.dW);
-  e = hipGetLastError();
+  return (int)hipGetLastError();
+}
+
+int launch_colsum_add(const void *B, int dtype, int ldb, int M, int O, float *partial, int max_splits, float *dst,
+                      hipStream_t s) {
+  if (M <= 0 || O <= 0) return hipSuccess;
+  int splits = (M + 255) / 256;
+  if (splits > max_splits) splits = max_splits;
+  const int rows_per = (M + splits - 1) / splits;
+  splits = (M + rows_per - 1) / rows_per;
+  dim3 grid((O + 63) / 64, splits);
+  if (dtype == DT_BF16)
+    hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(B), ldb, M, O, rows_per, partial);
+  else
+    hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(B), ldb, M, O, rows_per, partial);
+  hipError_t e = hipGetLastError();
   if (e != hipSuccess) return (int)e;
-  if (a.dbias != nullptr) {
-    dim3 g2((a.O + 255) / 256, splits);
-    if (compute_dtype == DT_BF16)
-      hipLaunchKernelGGL(colsum_kernel<bf16_t>, g2, dim3(256), 0, s, static_cast<const bf16_t *>(a.B), a.ldb, a.M, a.O,
-                         rows_per, a.bias_partial);
-    else
-      hipLaunchKernelGGL(colsum_kernel<float>, g2, dim3(256), 0, s, static_cast<const float *>(a.B), a.ldb, a.M, a.O,
-                         rows_per, a.bias_partial);
-    e = hipGetLastError();
-    if (e != hipSuccess) return (int)e;
-    hipLaunchKernelGGL(reduce_add_kernel, dim3((unsigned)((a.O + 255) / 256)), dim3(256), 0, s, a.bias_partial, splits,
-                       (size_t)a.O, 1.0f, a.dbias);
-    e = hipGetLastError();
-  }
-  return (int)e;
+  hipLaunchKernelGGL(reduce_add_kernel, dim3((unsigned)((O + 255) / 256)), dim3(256), 0, s, partial, splits, (size_t)O, 1.0f, dst);
+  return (int)hipGetLastError();
 }

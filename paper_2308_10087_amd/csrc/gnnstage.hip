@@ -82,7 +82,7 @@ struct Layout {
   size_t f_task_row, f_task_e0, f_task_ne, f_task_slot, f_lr_row, f_lr_slot0, f_lr_n;
   size_t b_task_row, b_task_e0, b_task_ne, b_task_slot, b_lr_row, b_lr_slot0, b_lr_n;
   size_t partial;
-  std::vector<size_t> Z, dZ, Wt, Wn;
+  std::vector<size_t> Z, dZ, Wt, Wn, Tc, Th;
   size_t G[2];
   size_t gemm_partial, bias_partial;
   size_t total;
@@ -93,8 +93,10 @@ struct Shape {
   int K = 0, L = 0;
   std::vector<int64_t> chunk_ptr;
   std::vector<int> dims, ld;
+  std::vector<char> tf;  // per layer: 1 = transform first (gather rows of width d_{j+1}), 0 = aggregate first
   int dtype = 0, level0_f32 = 0, variant = 0, need_input_grad = 0;
   int elt() const { return dtype == GNNSTAGE_BF16 ? 2 : 4; }
+  int level_elt(int j) const { return (j == 0 && level0_f32) ? 4 : elt(); }
   int64_t max_rows() const {
     int64_t m = 0;
     for (int c = 0; c < K; ++c) m = std::max<int64_t>(m, chunk_ptr[c + 1] - chunk_ptr[c]);
@@ -136,6 +138,17 @@ bool read_shape(const gnnstage_desc *d, Shape &s, std::string &err) {
     for (int j = 1; j <= s.L; ++j)
       if (s.dims[j] != s.dims[0]) { err = "GCNII needs equal widths at every level"; return false; }
     if (s.level0_f32) { err = "GCNII does not take an fp32 level 0"; return false; }
+  }
+  // Layer order.  (A_hat H) W == A_hat (H W) and the select is per edge, so a GCN layer may apply W
+  // before the aggregation; that pays when it narrows the rows the gather has to move.
+  const char *ord = getenv("GNNSTAGE_ORDER");
+  s.tf.assign(s.L, 0);
+  for (int j = 0; j < s.L; ++j) {
+    if (s.variant != GNNSTAGE_GCN) continue;
+    const bool narrower = (size_t)s.dims[j + 1] * s.elt() < (size_t)s.dims[j] * s.level_elt(j);
+    s.tf[j] = narrower ? 1 : 0;
+    if (ord && !strcmp(ord, "aggregate")) s.tf[j] = 0;
+    if (ord && !strcmp(ord, "transform")) s.tf[j] = 1;
   }
   if (d->row_ptr[0] != 0 || d->row_ptr[s.n] != s.nnz) { err = "row_ptr must start at 0 and end at nnz"; return false; }
   for (int64_t v = 0; v < s.n; ++v)
@@ -192,8 +205,20 @@ Layout make_layout(const Shape &s, const PlanCounts &f, const PlanCounts &b) {
   l.dZ.resize(s.L);
   l.Wt.resize(s.L);
   l.Wn.resize(s.L);
-  for (int j = 0; j < s.L; ++j) l.Z[j] = w.take((size_t)s.n * s.ld[j] * elt);
-  for (int j = 0; j < s.L; ++j) l.dZ[j] = (j == 0 && !s.need_input_grad) ? 0 : w.take((size_t)s.n * s.ld[j] * elt);
+  l.Tc.assign(s.L, 0);
+  l.Th.assign(s.L, 0);
+  for (int j = 0; j < s.L; ++j) {
+    if (s.tf[j]) {
+      // transform-first layer: transformed current / historical rows, and the masked upstream gradient
+      l.Z[j] = 0;
+      l.Tc[j] = w.take((size_t)s.n * s.ld[j + 1] * elt);
+      l.Th[j] = w.take((size_t)s.n * s.ld[j + 1] * elt);
+      l.dZ[j] = w.take((size_t)s.n * s.ld[j + 1] * elt);
+    } else {
+      l.Z[j] = w.take((size_t)s.n * s.ld[j] * elt);
+      l.dZ[j] = (j == 0 && !s.need_input_grad) ? 0 : w.take((size_t)s.n * s.ld[j] * elt);
+    }
+  }
   for (int j = 0; j < s.L; ++j) {
     l.Wt[j] = w.take((size_t)s.dims[j + 1] * s.ld[j] * elt);
     l.Wn[j] = w.take((size_t)s.dims[j] * s.ld[j + 1] * elt);
@@ -353,6 +378,50 @@ int run_spmm(gnnstage *st, const SpmmArgs &a, int src_dtype, int out_dtype, hipS
     return launch_spmm_reduce(a, src_dtype, out_dtype, stream);
   }
   return 0;
+}
+
+// After the last backward call of a pass: the history-side weight gradient of every transform-first
+// layer, dW += hist^T (A_hat^T dY), chunk by chunk through the gradient scratch rows.
+int finish_transform_first(gnnstage *st, hipStream_t stream) {
+  const Shape &s = st->s;
+  const int cd = st->cdtype();
+  ChunkMask all{};
+  for (int c = 0; c < s.K; ++c) mask_set(all, c);
+  char *dT = st->at<char>(st->lay.G[0]);
+  for (int j = 0; j < s.L; ++j) {
+    if (!s.tf[j]) continue;
+    for (int c = 0; c < s.K; ++c) {
+      const int64_t row0 = s.chunk_ptr[c], M = s.chunk_ptr[c + 1] - row0;
+      if (M == 0) continue;
+      SpmmArgs a = base_spmm(st, true, c);
+      a.mask = all;
+      a.src_sel = st->at<char>(st->lay.dZ[j]);
+      a.src_unsel = nullptr;
+      a.d = s.dims[j + 1];
+      a.src_ld = s.ld[j + 1];
+      a.out = dT;
+      a.out_ld = s.ld[j + 1];
+      a.out_row0 = row0;
+      a.epilogue = SPMM_PLAIN;
+      HIP_TRY(st, run_spmm(st, a, cd, cd, stream, 2, j));
+      Timed t(st, stream, 4, j);
+      GemmTnArgs w{};
+      w.A = static_cast<const char *>(st->hist[j]) + (size_t)row0 * s.dims[j] * st->level_elt(j);
+      w.a_dtype = st->level_dtype(j);
+      w.lda = s.dims[j];
+      w.B = dT;
+      w.ldb = s.ld[j + 1];
+      w.M = (int)M;
+      w.I = s.dims[j];
+      w.O = s.dims[j + 1];
+      w.scale = 1.f;
+      w.dW = st->dW[j];
+      w.partial = st->at<float>(st->lay.gemm_partial);
+      w.max_splits = kMaxSplits;
+      HIP_TRY(st, launch_gemm_tn(w, cd, stream));
+    }
+  }
+  return GNNSTAGE_OK;
 }
 
 }  // namespace
@@ -543,15 +612,39 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
   const Shape &s = st->s;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (k < 0 || k >= s.K) return fail(st, GNNSTAGE_ERANGE, "chunk id out of range");
+  const int cd = st->cdtype();
+  const size_t celt = s.elt();
   if (pos == 0) {  // a new pass: V_processed <- empty
     st->order.clear();
     st->fmask = ChunkMask{};
     st->bmask = ChunkMask{};
     st->n_bwd = 0;
-    Timed t(st, stream, 6);
-    for (int j = 0; j < s.L; ++j)
-      HIP_TRY(st, launch_stage_weights(st->W[j], st->cdtype(), s.dims[j], s.dims[j + 1], st->at<char>(st->lay.Wt[j]), s.ld[j],
-                                       st->at<char>(st->lay.Wn[j]), s.ld[j + 1], stream));
+    {
+      Timed t(st, stream, 6);
+      for (int j = 0; j < s.L; ++j)
+        HIP_TRY(st, launch_stage_weights(st->W[j], cd, s.dims[j], s.dims[j + 1], st->at<char>(st->lay.Wt[j]), s.ld[j],
+                                         st->at<char>(st->lay.Wn[j]), s.ld[j + 1], stream));
+    }
+    // transform-first layers: the historical rows are constants of the pass, transform them once
+    for (int j = 0; j < s.L; ++j) {
+      if (!s.tf[j]) continue;
+      Timed t(st, stream, 1, j);
+      GemmNtArgs g{};
+      g.A = st->hist[j];
+      g.a_dtype = st->level_dtype(j);
+      g.lda = s.dims[j];
+      g.Bt = st->at<char>(st->lay.Wt[j]);
+      g.ldb = s.ld[j];
+      g.M = (int)s.n;
+      g.N = s.dims[j + 1];
+      g.K = s.dims[j];
+      g.Kp = s.ld[j];
+      g.epilogue = EPI_PLAIN;
+      g.out = st->at<char>(st->lay.Th[j]);
+      g.out_dtype = cd;
+      g.out_ld = s.ld[j + 1];
+      HIP_TRY(st, launch_gemm_nt(g, cd, stream));
+    }
   }
   if (pos != (int32_t)st->order.size()) return fail(st, GNNSTAGE_EORDER, "pos_in_pass does not continue the current pass");
   if (mask_test(st->fmask, (uint32_t)k)) return fail(st, GNNSTAGE_EORDER, "chunk already processed in this pass");
@@ -560,9 +653,43 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
 
   const int64_t row0 = s.chunk_ptr[k], M = s.chunk_ptr[k + 1] - row0;
   if (M == 0) return GNNSTAGE_OK;
-  const int cd = st->cdtype();
-  const size_t celt = s.elt();
   for (int j = 0; j < s.L; ++j) {
+    if (s.tf[j]) {
+      // transform the chunk's current rows, then aggregate transformed rows (current or historical)
+      const bool shared = st->hist[j] == st->cur[j];  // level never changes: one transformed table serves both
+      char *Th = st->at<char>(st->lay.Th[j]);
+      char *Tc = shared ? Th : st->at<char>(st->lay.Tc[j]);
+      if (!shared) {
+        Timed t(st, stream, 1, j);
+        GemmNtArgs g{};
+        g.A = static_cast<const char *>(st->cur[j]) + (size_t)row0 * s.dims[j] * st->level_elt(j);
+        g.a_dtype = st->level_dtype(j);
+        g.lda = s.dims[j];
+        g.Bt = st->at<char>(st->lay.Wt[j]);
+        g.ldb = s.ld[j];
+        g.M = (int)M;
+        g.N = s.dims[j + 1];
+        g.K = s.dims[j];
+        g.Kp = s.ld[j];
+        g.epilogue = EPI_PLAIN;
+        g.out = Tc + (size_t)row0 * s.ld[j + 1] * celt;
+        g.out_dtype = cd;
+        g.out_ld = s.ld[j + 1];
+        HIP_TRY(st, launch_gemm_nt(g, cd, stream));
+      }
+      SpmmArgs a = base_spmm(st, false, k);
+      a.src_sel = Tc;
+      a.src_unsel = Th;
+      a.d = s.dims[j + 1];
+      a.src_ld = s.ld[j + 1];
+      a.out = st->cur[j + 1];
+      a.out_ld = s.dims[j + 1];
+      a.out_row0 = 0;
+      a.epilogue = SPMM_BIAS_RELU;
+      a.bias = static_cast<const float *>(st->bias[j]);
+      HIP_TRY(st, run_spmm(st, a, cd, cd, stream, 0, j));
+      continue;
+    }
     char *Zj = st->at<char>(st->lay.Z[j]);
     {
       SpmmArgs a = base_spmm(st, false, k);
@@ -588,15 +715,18 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
       Timed t(st, stream, 1, j);
       GemmNtArgs g{};
       g.A = Zj + (size_t)row0 * s.ld[j] * celt;
+      g.a_dtype = cd;
       g.lda = s.ld[j];
       g.Bt = st->at<char>(st->lay.Wt[j]);
       g.ldb = s.ld[j];
       g.M = (int)M;
       g.N = s.dims[j + 1];
+      g.K = s.dims[j];
       g.Kp = s.ld[j];
       if (s.variant == GNNSTAGE_GCNII) {
         g.epilogue = EPI_FWD_GCNII;
         g.aux = g.A;
+        g.aux_dtype = cd;
         g.aux_ld = s.ld[j];
         g.beta = st->beta[j];
       } else {
@@ -604,8 +734,9 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
         g.bias = static_cast<const float *>(st->bias[j]);
       }
       g.out = static_cast<char *>(st->cur[j + 1]) + (size_t)row0 * s.dims[j + 1] * celt;
+      g.out_dtype = cd;
       g.out_ld = s.dims[j + 1];
-      HIP_TRY(st, launch_gemm_nt(g, cd, cd, stream));
+      HIP_TRY(st, launch_gemm_nt(g, cd, stream));
     }
   }
   return GNNSTAGE_OK;
@@ -628,19 +759,108 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
   const int cd = st->cdtype();
   const size_t celt = s.elt();
   char *G[2] = {st->at<char>(st->lay.G[0]), st->at<char>(st->lay.G[1])};
+  float *gemm_partial = st->at<float>(st->lay.gemm_partial);
+  float *bias_partial = st->at<float>(st->lay.bias_partial);
   int gi = 0;
   {
     Timed t(st, stream, 6);
     const char *top = static_cast<const char *>(st->cur[s.L]) + (size_t)row0 * s.dims[s.L] * celt;
     HIP_TRY(st, launch_relu_mask(grad_out_rows, top, cd, M, s.dims[s.L], G[gi], s.ld[s.L], stream));
   }
+  // invariant at the top of every iteration: G[gi] holds dY_j = dL/d(pre-activation of layer j) for the
+  // rows of the chunk, [M x ld_{j+1}], zero in the padding columns
   for (int j = s.L - 1; j >= 0; --j) {
     const char *dY = G[gi];
+    if (s.variant == GNNSTAGE_GCN) {
+      Timed t(st, stream, 4, j);
+      HIP_TRY(st, launch_colsum_add(dY, cd, s.ld[j + 1], (int)M, s.dims[j + 1], bias_partial, kMaxSplits, st->dbias[j], stream));
+    }
+    const bool need_prev = j > 0 || s.need_input_grad;
+    if (s.tf[j]) {
+      // Layer computed as A_hat (H W).  With T = H W:  dL/dW = cur^T dT_cur + hist^T dT_hist, where
+      // dT_cur[u] sums A_vu dY[v] over the readers v that saw u's CURRENT row (exactly the vertices
+      // already processed in this backward pass) and dT_hist over the readers that saw its history.
+      // dT_cur + dT_hist is the unmasked transposed aggregation, known only when every chunk's dY is:
+      //   dW += (cur - hist)[C_k]^T dT_cur[C_k]   here, per chunk,
+      //   dW += hist^T (A_hat^T dY)                after the last chunk (finish_transform_first).
+      const bool shared = st->hist[j] == st->cur[j];
+      char *dYfull = st->at<char>(st->lay.dZ[j]);
+      {
+        Timed t(st, stream, 6);
+        HIP_TRY(st, launch_copy(dY, dYfull + (size_t)row0 * s.ld[j + 1] * celt, (size_t)M * s.ld[j + 1] * celt, stream));
+      }
+      if (shared && !need_prev) continue;  // nothing else depends on dT_cur; G[gi] is not needed below
+      char *dT = G[gi ^ 1];
+      {
+        SpmmArgs a = base_spmm(st, true, k);
+        a.src_sel = dYfull;
+        a.src_unsel = nullptr;  // Section 3.4: nothing flows back from unprocessed vertices
+        a.d = s.dims[j + 1];
+        a.src_ld = s.ld[j + 1];
+        a.out = dT;
+        a.out_ld = s.ld[j + 1];
+        a.out_row0 = row0;
+        a.epilogue = SPMM_PLAIN;
+        HIP_TRY(st, run_spmm(st, a, cd, cd, stream, 2, j));
+      }
+      if (!shared) {
+        Timed t(st, stream, 4, j);
+        GemmTnArgs w{};
+        w.a_dtype = st->level_dtype(j);
+        w.lda = s.dims[j];
+        w.B = dT;
+        w.ldb = s.ld[j + 1];
+        w.M = (int)M;
+        w.I = s.dims[j];
+        w.O = s.dims[j + 1];
+        w.dW = st->dW[j];
+        w.partial = gemm_partial;
+        w.max_splits = kMaxSplits;
+        w.A = static_cast<const char *>(st->cur[j]) + (size_t)row0 * s.dims[j] * st->level_elt(j);
+        w.scale = 1.f;
+        HIP_TRY(st, launch_gemm_tn(w, cd, stream));
+        w.A = static_cast<const char *>(st->hist[j]) + (size_t)row0 * s.dims[j] * st->level_elt(j);
+        w.scale = -1.f;
+        HIP_TRY(st, launch_gemm_tn(w, cd, stream));
+      }
+      if (!need_prev) continue;
+      {
+        Timed t(st, stream, 3, j);
+        GemmNtArgs g{};
+        g.A = dT;
+        g.a_dtype = cd;
+        g.lda = s.ld[j + 1];
+        g.Bt = st->at<char>(st->lay.Wn[j]);
+        g.ldb = s.ld[j + 1];
+        g.M = (int)M;
+        g.N = s.dims[j];
+        g.K = s.dims[j + 1];
+        g.Kp = s.ld[j + 1];
+        if (j > 0) {
+          g.epilogue = EPI_MASK;
+          g.aux = static_cast<const char *>(st->cur[j]) + (size_t)row0 * s.dims[j] * celt;
+          g.aux_dtype = cd;
+          g.aux_ld = s.dims[j];
+          g.out = G[gi];  // dY_j is dead by now
+          g.out_dtype = cd;
+          g.out_ld = s.ld[j];
+          g.out_pad = s.ld[j];
+        } else {
+          g.epilogue = EPI_PLAIN;
+          g.out = static_cast<char *>(st->grad_in) + (size_t)row0 * s.dims[0] * st->level_elt(0);
+          g.out_dtype = st->level_dtype(0);
+          g.out_ld = s.dims[0];
+        }
+        HIP_TRY(st, launch_gemm_nt(g, cd, stream));
+      }
+      continue;  // the next dY sits in G[gi] again
+    }
     const char *Zrows = st->at<char>(st->lay.Z[j]) + (size_t)row0 * s.ld[j] * celt;
     {
       Timed t(st, stream, 4, j);
       GemmTnArgs w{};
       w.A = Zrows;
+      w.a_dtype = cd;
       w.lda = s.ld[j];
       w.B = dY;
       w.ldb = s.ld[j + 1];
@@ -649,38 +869,40 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
       w.O = s.dims[j + 1];
       w.scale = s.variant == GNNSTAGE_GCNII ? st->beta[j] : 1.f;
       w.dW = st->dW[j];
-      w.partial = st->at<float>(st->lay.gemm_partial);
+      w.partial = gemm_partial;
       w.max_splits = kMaxSplits;
-      w.dbias = s.variant == GNNSTAGE_GCN ? st->dbias[j] : nullptr;
-      w.bias_partial = st->at<float>(st->lay.bias_partial);
       HIP_TRY(st, launch_gemm_tn(w, cd, stream));
     }
-    if (j == 0 && !s.need_input_grad) break;
+    if (!need_prev) break;
     char *dZj = st->at<char>(st->lay.dZ[j]);
     {
       Timed t(st, stream, 3, j);
       GemmNtArgs g{};
       g.A = dY;
+      g.a_dtype = cd;
       g.lda = s.ld[j + 1];
       g.Bt = st->at<char>(st->lay.Wn[j]);
       g.ldb = s.ld[j + 1];
       g.M = (int)M;
       g.N = s.dims[j];
+      g.K = s.dims[j + 1];
       g.Kp = s.ld[j + 1];
       if (s.variant == GNNSTAGE_GCNII) {
         g.epilogue = EPI_DGRAD_GCNII;
         g.aux = dY;
+        g.aux_dtype = cd;
         g.aux_ld = s.ld[j + 1];
         g.alpha = st->alpha;
         g.beta = st->beta[j];
         g.h0grad = st->grad_h0 ? st->grad_h0 + (size_t)row0 * s.dims[j] : nullptr;
         g.h0_ld = s.dims[j];
       } else {
-        g.epilogue = EPI_DGRAD_GCN;
+        g.epilogue = EPI_PLAIN;
       }
       g.out = dZj + (size_t)row0 * s.ld[j] * celt;
+      g.out_dtype = cd;
       g.out_ld = s.ld[j];
-      HIP_TRY(st, launch_gemm_nt(g, cd, cd, stream));
+      HIP_TRY(st, launch_gemm_nt(g, cd, stream));
     }
     {
       SpmmArgs a = base_spmm(st, true, k);
@@ -706,6 +928,7 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
     }
     gi ^= 1;
   }
+  if (st->n_bwd == s.K) return finish_transform_first(st, stream);
   return GNNSTAGE_OK;
 }
 
@@ -734,6 +957,11 @@ extern "C" int gnnstage_debug_select_counts(gnnstage_t *st, int32_t k, int32_t *
     out[v - s.chunk_ptr[k]] = c;
   }
   return GNNSTAGE_OK;
+}
+
+extern "C" int gnnstage_layer_order(const gnnstage_t *st, int32_t layer) {
+  if (!st || layer < 0 || layer >= st->s.L) return GNNSTAGE_EINVAL;
+  return st->s.tf[layer] ? 1 : 0;
 }
 
 extern "C" int gnnstage_profile_enable(gnnstage_t *st, int32_t on) {

@@ -36,6 +36,12 @@ __device__ inline void finish_cols(const SpmmArgs &a, int64_t row, int c, const 
   if (a.epilogue == SPMM_PLAIN) {
 #pragma unroll
     for (int t = 0; t < VEC; ++t) r[t] = acc[t];
+  } else if (a.epilogue == SPMM_BIAS_RELU) {
+#pragma unroll
+    for (int t = 0; t < VEC; ++t) {
+      const float y = acc[t] + a.bias[c + t];
+      r[t] = y > 0.f ? y : 0.f;
+    }
   } else {
     const Pack<Tin, VEC> x = *reinterpret_cast<const Pack<Tin, VEC> *>(
         static_cast<const Tin *>(a.aux) + (size_t)row * a.aux_ld + c);
@@ -213,7 +219,8 @@ static const Shape *pick_shape(const SpmmArgs &a, int src_dtype, int out_dtype) 
   else
     tab = out_dtype == DT_BF16 ? shapes_f32<bf16_t>(&n) : shapes_f32<float>(&n);
   // widest vector that divides every leading dimension involved
-  const int lds[4] = {a.d, a.src_ld, a.out_ld, a.epilogue == SPMM_PLAIN ? a.d : a.aux_ld};
+  const bool has_aux = a.epilogue == SPMM_MIX || a.epilogue == SPMM_MASK;
+  const int lds[4] = {a.d, a.src_ld, a.out_ld, has_aux ? a.aux_ld : a.d};
   const Shape *best = nullptr;
   int best_vec = 0;
   for (int i = 0; i < n; ++i) {

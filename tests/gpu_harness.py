@@ -12,7 +12,7 @@ def _dev(x: np.ndarray, dtype, device):
 
 
 class GpuRun:
-    def __init__(self, p, *, need_input_grad=True, edge_val="given", device="cuda:0"):
+    def __init__(self, p, *, need_input_grad=True, edge_val="given", alias_hist0=False, device="cuda:0"):
         self.p = p
         self.device = device
         bf = p.quant
@@ -25,6 +25,8 @@ class GpuRun:
         self.bias = [_dev(p.b[j], torch.float32, device) for j in range(L)] if gcn else None
         self.cur = [_dev(p.x0, l0, device)] + [torch.zeros((n, p.dims[j]), dtype=sdt, device=device) for j in range(1, L + 1)]
         self.hist = [_dev(p.hist[j], l0 if j == 0 else sdt, device) for j in range(L)]
+        if alias_hist0:  # a first stage: level 0 never changes, so history IS the current buffer
+            self.hist[0] = self.cur[0]
         self.dW = [torch.zeros((p.dims[j], p.dims[j + 1]), dtype=torch.float32, device=device) for j in range(L)]
         self.dbias = [torch.zeros(p.dims[j + 1], dtype=torch.float32, device=device) for j in range(L)] if gcn else None
         self.h0 = None if gcn else _dev(p.h0, sdt, device)

@@ -1,0 +1,157 @@
+"""CPU-only checks of the library boundary and its host-side integer bookkeeping:
+the shared library loads and exports every function the header declares, the transposed index is
+the exact transpose, packed index words decode to (vertex, chunk), the launch schedule partitions
+the entries, and descriptor validation reports errors without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from synth import graphs
+from synth.configs import CONFIGS, make_graph
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _lib():
+    import paper_2308_10087_amd as g
+    return g
+
+
+def test_library_exports_every_declared_symbol():
+    g = _lib()
+    header = open(os.path.join(ROOT, "include", "gnnstage.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = re.findall(r"\b([a-z_][a-z0-9_]*)\s*\(", header)
+    declared = sorted({n for n in names if n.startswith(("gnnstage_", "stage_", "update_history"))})
+    assert {"gnnstage_create", "stage_forward_chunk", "stage_backward_chunk", "update_history",
+            "gnnstage_destroy"} <= set(declared)
+    for name in declared:
+        assert hasattr(g.lib, name), name
+    assert g.gnnstage_version() >= 100
+
+
+def test_transposed_index_is_the_exact_transpose():
+    g = _lib()
+    rng = np.random.default_rng(1)
+    n = 300
+    row_ptr, col = graphs.from_directed_pairs(n, rng.integers(0, n, 4000), rng.integers(0, n, 4000))
+    t_ptr, t_row, t_edge = g.gnnstage_plan_transpose(row_ptr, col)
+    # same as the oracle's own transposition (independent code)
+    st = oracle.OracleStage(row_ptr, col, np.ones(len(col), np.float32), [0, n], [1, 1], [np.ones((1, 1), np.float32)])
+    assert np.array_equal(t_ptr, st.t_ptr) and np.array_equal(t_row, st.t_row) and np.array_equal(t_edge, st.t_edge)
+    # transposing the transpose gives the CSR back
+    b_ptr, b_row, _ = g.gnnstage_plan_transpose(t_ptr, t_row)
+    assert np.array_equal(b_ptr, row_ptr) and np.array_equal(b_row, col)
+    # every entry points back at itself
+    rows_of_edge = np.repeat(np.arange(n), np.diff(row_ptr))
+    assert np.array_equal(rows_of_edge[t_edge], t_row)
+    assert np.array_equal(col[t_edge], np.repeat(np.arange(n), np.diff(t_ptr)))
+    with pytest.raises(g.GnnStageError):
+        g.gnnstage_plan_transpose(np.array([0, 1]), np.array([5]))  # column out of range
+
+
+@pytest.mark.parametrize("n,k", [(1000, 7), (5, 1), (70000, 200)])
+def test_packed_words_decode_to_vertex_and_chunk(n, k):
+    g = _lib()
+    rng = np.random.default_rng(2)
+    idx = rng.integers(0, n, 5000).astype(np.int32)
+    chunk_ptr = graphs.ragged_chunks(n, k, 3) if k > 1 else np.array([0, n])
+    packed, vbits = g.gnnstage_plan_pack(n, idx, chunk_ptr)
+    assert (1 << vbits) >= n
+    assert np.array_equal(packed & ((1 << vbits) - 1), idx.astype(np.uint32))
+    want_chunk = np.searchsorted(chunk_ptr, idx, side="right") - 1
+    assert np.array_equal(packed >> vbits, want_chunk.astype(np.uint32))
+
+
+def test_packing_refuses_sizes_beyond_32_bits():
+    g = _lib()
+    vb = C.c_int32(0)
+    cp = np.array([0] + [1 << 27] * 255 + [1 << 28], dtype=np.int64)
+    rc = g.lib.gnnstage_plan_pack(1 << 28, 0, None, 256, cp.ctypes.data, None, C.byref(vb))
+    assert rc == -6  # 28 vertex bits + 8 chunk bits > 32
+
+
+@pytest.mark.parametrize("split", [64, 500, 1 << 20])
+def test_launch_schedule_partitions_the_entries(split):
+    g = _lib()
+    w = CONFIGS["c4_s"]
+    row_ptr, col = make_graph(w)
+    n = len(row_ptr) - 1
+    chunk_ptr = graphs.equal_chunks(n, 5)
+    covered = np.zeros(row_ptr[-1], dtype=np.int32)
+    for c in range(5):
+        row, e0, ne, slot, n_slots = g.gnnstage_plan_tasks(row_ptr, int(chunk_ptr[c]), int(chunk_ptr[c + 1]), split)
+        assert np.all(ne <= split) and np.all(ne >= 0)
+        assert np.all((row >= chunk_ptr[c]) & (row < chunk_ptr[c + 1]))
+        for r, a, m in zip(row, e0, ne):
+            assert row_ptr[r] <= a and a + m <= row_ptr[r + 1]
+            covered[a:a + m] += 1
+        deg = np.diff(row_ptr)[chunk_ptr[c]:chunk_ptr[c + 1]]
+        long_rows = np.flatnonzero(deg > split) + chunk_ptr[c]
+        # whole rows carry slot -1 and appear once; long rows are cut into consecutive slots, listed first
+        whole = row[slot < 0]
+        assert len(np.unique(whole)) == len(whole) == (deg <= split).sum()
+        pieces = slot[slot >= 0]
+        assert np.array_equal(pieces, np.arange(n_slots))
+        assert np.all(slot[:len(pieces)] >= 0)
+        assert set(row[slot >= 0].tolist()) == set(long_rows.tolist())
+        assert n_slots == int(np.ceil(deg[deg > split] / split).sum())
+    assert np.all(covered == 1)  # every entry belongs to exactly one task
+
+
+def _desc(g, **over):
+    n = 6
+    row_ptr = np.array([0, 1, 2, 3, 4, 5, 6], dtype=np.int64)
+    col = np.arange(6, dtype=np.int32)
+    chunk_ptr = np.array([0, 3, 6], dtype=np.int64)
+    dims = np.array([4, 4], dtype=np.int32)
+    d = g.binding.gnnstage_desc()
+    d.n_vertices, d.nnz = n, 6
+    d.row_ptr, d.col_idx = row_ptr.ctypes.data, col.ctypes.data
+    d.n_chunks, d.chunk_ptr = 2, chunk_ptr.ctypes.data
+    d.n_layers, d.dims = 1, dims.ctypes.data
+    keep = [row_ptr, col, chunk_ptr, dims]
+    for k, v in over.items():
+        setattr(d, k, v)
+    return d, keep
+
+
+def test_workspace_size_and_validation_without_a_gpu():
+    g = _lib()
+    d, keep = _desc(g)
+    size = g.lib.gnnstage_workspace_size(C.byref(d))
+    assert size > 0 and size % 256 == 0
+    bad, keep2 = _desc(g, n_chunks=0)
+    assert g.lib.gnnstage_workspace_size(C.byref(bad)) == 0
+    assert b"n_chunks" in g.lib.gnnstage_last_error(None)
+    bad, keep3 = _desc(g, dtype=7)
+    assert g.lib.gnnstage_workspace_size(C.byref(bad)) == 0
+    # create() rejects a descriptor with missing buffers before any device call
+    h = C.c_void_p(None)
+    assert g.lib.gnnstage_create(C.byref(d), C.byref(h)) == -1 and h.value is None
+    assert g.lib.gnnstage_create(None, C.byref(h)) == -1
+    assert g.lib.stage_forward_chunk(None, 0, 0, None) == -1
+    assert g.lib.update_history(None, None) == -1
+    assert g.lib.gnnstage_destroy(None) == -1
+
+
+def test_generated_graphs_are_symmetric_sorted_and_reproducible():
+    w = CONFIGS["c3_s"]
+    a_ptr, a_col = make_graph(w)
+    b_ptr, b_col = make_graph(w)
+    assert np.array_equal(a_ptr, b_ptr) and np.array_equal(a_col, b_col)
+    g = _lib()
+    t_ptr, t_row, _ = g.gnnstage_plan_transpose(a_ptr, a_col)
+    assert np.array_equal(t_ptr, a_ptr) and np.array_equal(t_row, a_col)  # symmetric
+    n = len(a_ptr) - 1
+    rows = np.repeat(np.arange(n), np.diff(a_ptr))
+    key = rows.astype(np.int64) * n + a_col
+    assert np.all(np.diff(key) > 0)  # sorted, no duplicates
+    assert np.all(a_col[a_ptr[:-1] + np.searchsorted(a_col[a_ptr[0]:], 0) * 0] >= 0)
+    has_loop = np.zeros(n, dtype=bool)
+    has_loop[rows[rows == a_col]] = True
+    assert has_loop.all()
