@@ -11,6 +11,8 @@
 // flight per instruction.  Entry metadata (packed index, weight) is loaded 64 entries at a
 // time, one per lane, and broadcast through lane permutes; when unselected entries are
 // dropped they are first compacted inside the wave so that no bandwidth is spent on them.
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace {
@@ -74,10 +76,14 @@ __global__ __launch_bounds__(256) void spmm_kernel(const SpmmArgs a) {
   if (task >= a.n_tasks) return;  // whole wave leaves together
   const int grp = lane / LPR, lig = lane % LPR;
   const int col0 = blockIdx.y * TILE_W + lig * VEC;
-  const int64_t row = a.task_row[task];
-  const int64_t e0 = a.task_e0[task];
-  const int ne = a.task_ne[task];
-  const int slot = a.task_slot[task];
+  // task fields are the same for the whole wave: keep them in scalar registers, so that every loop
+  // bound below is provably wave-uniform (the lane permutes need all lanes in step)
+  const int64_t row = __builtin_amdgcn_readfirstlane(a.task_row[task]);
+  const int64_t e0_raw = a.task_e0[task];
+  const int64_t e0 = ((int64_t)__builtin_amdgcn_readfirstlane((int)(e0_raw >> 32)) << 32) |
+                     (uint32_t)__builtin_amdgcn_readfirstlane((int)(e0_raw & 0xffffffff));
+  const int ne = __builtin_amdgcn_readfirstlane(a.task_ne[task]);
+  const int slot = __builtin_amdgcn_readfirstlane(a.task_slot[task]);
   const uint32_t vmask = (1u << a.vbits) - 1u;
   const bool drop_unsel = a.src_unsel == nullptr;
   const Tin *src_sel = static_cast<const Tin *>(a.src_sel);
@@ -111,7 +117,7 @@ __global__ __launch_bounds__(256) void spmm_kernel(const SpmmArgs a) {
       const int dest = keep ? rk : nk + (lane - rk);
       info = (uint32_t)__builtin_amdgcn_ds_permute(dest << 2, (int)info);
       w = __int_as_float(__builtin_amdgcn_ds_permute(dest << 2, __float_as_int(w)));
-      n = nk;
+      n = __builtin_amdgcn_readfirstlane(nk);
     }
     for (int i = 0; i < n; i += G) {
       const int idx = i + grp;
@@ -175,6 +181,156 @@ __global__ __launch_bounds__(256) void spmm_reduce_kernel(const SpmmArgs a) {
     finish_cols<Tin, Tout, VEC>(a, row, c, acc);
   }
   if (threadIdx.x < 64) zero_pad_cols<Tout>(a, row, threadIdx.x);
+}
+
+// ---- bf16 sources: the weighted row sum on the matrix cores ---------------------------------
+// A gathered 16-byte piece (8 consecutive bf16 columns of one neighbour row) is exactly one lane's
+// A-operand fragment of v_mfma_f32_16x16x32_bf16: lane l supplies A[m = l%16][k = 8*(l/16) .. +8].
+// Reading m as "8-column block" and k as (neighbour slot g = l/16, column t inside the block), the
+// B operand  B[8g + t][n] = w_g * [t == n % 8]  turns the instruction into
+//     D[m][n] += sum_g w_g * X[u_g][8m + n % 8]
+// i.e. four neighbours (one per 16-lane group) times a 128-column tile are scaled by their edge
+// weights and accumulated in fp32 with no bf16->fp32 conversion and no vector FMA.  Columns n < 8 of B
+// carry the upper bf16 half of the fp32 weight, columns n >= 8 the remainder, and the two halves of D
+// are added at the end, so the weight keeps 16 mantissa bits.  (A non-finite input value also poisons
+// the other 7 columns of its 8-column block, since 0 * inf = nan inside the dot product.)
+typedef bf16_t bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+template <typename Tout, int NT>
+__global__ __launch_bounds__(256) void spmm_mfma_kernel(const SpmmArgs a) {
+  constexpr int TILE_W = NT * 128;
+  __shared__ float rowbuf[4][TILE_W];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t task = (int64_t)blockIdx.x * 4 + wave;
+  if (task >= a.n_tasks) return;  // whole wave leaves together (no block-wide barrier below)
+  const int g = lane >> 4, lig = lane & 15;
+  const int tile0 = blockIdx.y * TILE_W;
+  // task fields are the same for the whole wave: keep them in scalar registers.  The matrix
+  // instruction ignores the execution mask and the lane permutes need every lane in step, so all
+  // control flow around them must be provably wave-uniform.
+  const int64_t row = __builtin_amdgcn_readfirstlane(a.task_row[task]);
+  const int64_t e0_raw = a.task_e0[task];
+  const int64_t e0 = ((int64_t)__builtin_amdgcn_readfirstlane((int)(e0_raw >> 32)) << 32) |
+                     (uint32_t)__builtin_amdgcn_readfirstlane((int)(e0_raw & 0xffffffff));
+  const int ne = __builtin_amdgcn_readfirstlane(a.task_ne[task]);
+  const int slot = __builtin_amdgcn_readfirstlane(a.task_slot[task]);
+  const uint32_t vmask = (1u << a.vbits) - 1u;
+  const bool drop_unsel = a.src_unsel == nullptr;
+  const bf16_t *src_sel = static_cast<const bf16_t *>(a.src_sel);
+  const bf16_t *src_unsel = static_cast<const bf16_t *>(a.src_unsel);
+  const int d = a.d;
+  const size_t ld = (size_t)a.src_ld;
+  const int pos = lig & 7;            // which element of the 8-column block this lane's B column picks
+  const bool lo_part = lig >= 8;      // B columns 8..15 carry the low half of the weight
+
+  f32x4_t acc[NT];
+#pragma unroll
+  for (int h = 0; h < NT; ++h) acc[h] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  const bf16x8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+
+  // entry metadata of the first batch; later batches are fetched one batch ahead
+  uint32_t pc_next = 0;
+  float w_next = 0.f;
+  if (lane < ne) {
+    pc_next = a.pidx[e0 + lane];
+    w_next = a.val[e0 + lane];
+  }
+  for (int base = 0; base < ne; base += 64) {
+    int n = ne - base < 64 ? ne - base : 64;
+    const uint32_t pc = pc_next;
+    float w = w_next;
+    if (base + 64 + lane < ne) {
+      pc_next = a.pidx[e0 + base + 64 + lane];
+      w_next = a.val[e0 + base + 64 + lane];
+    }
+    uint32_t info = 0;
+    bool keep = false;
+    if (lane < n) {
+      const bool sel = mask_test(a.mask, pc >> a.vbits);
+      keep = sel || !drop_unsel;
+      info = (pc & vmask) | (sel ? 0x80000000u : 0u);
+    } else {
+      w = 0.f;
+    }
+    if (drop_unsel) {
+      const uint64_t bal = __ballot(keep);
+      const int nk = __popcll(bal);
+      const int rk = __popcll(bal & ((1ull << lane) - 1ull));
+      const int dest = keep ? rk : nk + (lane - rk);
+      info = (uint32_t)__builtin_amdgcn_ds_permute(dest << 2, (int)info);
+      w = __int_as_float(__builtin_amdgcn_ds_permute(dest << 2, __float_as_int(w)));
+      n = __builtin_amdgcn_readfirstlane(nk);
+    }
+    // 16 entries per step: all gathers of the step are issued before the first product needs its data
+    for (int i = 0; i < n; i += 16) {
+      bf16x8_t x[4][NT];
+      bf16x8_t bfrag[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (i + 4 * u < n) {  // wave-uniform
+          const int idx = i + 4 * u + g;
+          const int from = idx < n ? idx : i;  // past the end: a valid row with weight 0
+          const uint32_t inf = (uint32_t)__shfl((int)info, from);
+          float ww = __shfl(w, from);
+          if (idx >= n) ww = 0.f;
+          // split the fp32 weight into two bf16 halves and place this lane's half at element `pos`
+          const bf16_t whi = (bf16_t)ww;
+          const bf16_t wlo = (bf16_t)(ww - (float)whi);
+          const bf16_t part = lo_part ? wlo : whi;
+          const uint32_t bits = (uint32_t)__builtin_bit_cast(uint16_t, part) << ((pos & 1) * 16);
+          u32x4_t bw;
+          bw[0] = (pos >> 1) == 0 ? bits : 0u;
+          bw[1] = (pos >> 1) == 1 ? bits : 0u;
+          bw[2] = (pos >> 1) == 2 ? bits : 0u;
+          bw[3] = (pos >> 1) == 3 ? bits : 0u;
+          bfrag[u] = __builtin_bit_cast(bf16x8_t, bw);
+          const bf16_t *rowp = ((inf >> 31) ? src_sel : src_unsel) + (size_t)(inf & 0x7fffffffu) * ld + tile0 + lig * 8;
+#pragma unroll
+          for (int h = 0; h < NT; ++h)
+            x[u][h] = (tile0 + h * 128 + lig * 8 < d) ? *reinterpret_cast<const bf16x8_t *>(rowp + h * 128) : zero8;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (i + 4 * u < n) {
+#pragma unroll
+          for (int h = 0; h < NT; ++h) acc[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[u][h], bfrag[u], acc[h], 0, 0, 0);
+        }
+      }
+    }
+  }
+  // D layout: element i of lane l is D[m = 4*(l/16) + i][n = l%16]; column = 8m + n%8, halves n<8 / n>=8
+#pragma unroll
+  for (int h = 0; h < NT; ++h)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float v = acc[h][i] + __shfl_xor(acc[h][i], 8);
+      if (!lo_part) rowbuf[wave][h * 128 + (4 * g + i) * 8 + pos] = v;
+    }
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the wave's own LDS writes have landed
+  // natural layout again: lane q owns 8 consecutive columns
+#pragma unroll
+  for (int r = 0; r < (NT * 16 + 63) / 64; ++r) {
+    const int q = lane + 64 * r;
+    const int c = tile0 + q * 8;
+    if (q < NT * 16 && c < d) {
+      float v[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) v[t] = rowbuf[wave][q * 8 + t];
+      if (slot >= 0) {
+        Pack<float, 8> o;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) o.v[t] = v[t];
+        *reinterpret_cast<Pack<float, 8> *>(a.partial + (size_t)slot * d + c) = o;
+      } else {
+        finish_cols<bf16_t, Tout, 8>(a, row, c, v);
+      }
+    }
+  }
+  if (slot < 0 && blockIdx.y == 0) zero_pad_cols<Tout>(a, row, lane);
 }
 
 typedef void (*spmm_fn)(const SpmmArgs);
@@ -243,8 +399,28 @@ static const Shape *pick_shape(const SpmmArgs &a, int src_dtype, int out_dtype) 
   return best;
 }
 
+static bool mfma_path(const SpmmArgs &a, int src_dtype) {
+  static const bool off = getenv("GNNSTAGE_SPMM_VALU") != nullptr;  // measurement switch
+  const bool has_aux = a.epilogue == SPMM_MIX || a.epilogue == SPMM_MASK;
+  return !off && src_dtype == DT_BF16 && a.d % 8 == 0 && a.src_ld % 8 == 0 && a.out_ld % 8 == 0 &&
+         (!has_aux || a.aux_ld % 8 == 0);
+}
+
+template <typename Tout>
+static int launch_mfma(const SpmmArgs &a, hipStream_t s) {
+  const unsigned gx = (unsigned)((a.n_tasks + 3) / 4);
+  if (a.d <= 128)
+    hipLaunchKernelGGL((spmm_mfma_kernel<Tout, 1>), dim3(gx, 1), dim3(256), 0, s, a);
+  else if (a.d <= 256)
+    hipLaunchKernelGGL((spmm_mfma_kernel<Tout, 2>), dim3(gx, 1), dim3(256), 0, s, a);
+  else
+    hipLaunchKernelGGL((spmm_mfma_kernel<Tout, 4>), dim3(gx, (unsigned)((a.d + 511) / 512)), dim3(256), 0, s, a);
+  return (int)hipGetLastError();
+}
+
 int launch_spmm(const SpmmArgs &a, int src_dtype, int out_dtype, hipStream_t s) {
   if (a.n_tasks <= 0) return hipSuccess;
+  if (mfma_path(a, src_dtype)) return out_dtype == DT_BF16 ? launch_mfma<bf16_t>(a, s) : launch_mfma<float>(a, s);
   const Shape *best = pick_shape(a, src_dtype, out_dtype);
   if (!best) return hipErrorInvalidValue;
   const int tile_w = best->lpr * best->nv * best->vec;
