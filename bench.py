@@ -189,11 +189,13 @@ def main():
             add(gname(db_, eb), bb, gb, *prof_layer[j]["spmm_bwd"])
     dom_name, (dom_bytes, dom_gather, dom_ms, dom_launches) = max(groups.items(), key=lambda kv: kv[1][2])
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+    traffic = None  # HBM-side bytes per launch from the committed rocprofv3 counter summary, if it covers this kernel
+    tpath = os.path.join(ROOT, "profiles", f"stage_{w.name}_pmc_traffic.md")
     if os.path.exists(tpath):
-        with open(tpath) as f:
-            traffic = json.load(f).get(w.name, {}).get(dom_name)
+        for line in open(tpath):
+            parts = [x.strip() for x in line.split("|")]
+            if len(parts) == 3 and parts[0] == f"traffic {w.name}" and parts[1] == dom_name:
+                traffic = float(parts[2])
     roofline = {
         "bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,

@@ -151,7 +151,6 @@ def test_generated_graphs_are_symmetric_sorted_and_reproducible():
     rows = np.repeat(np.arange(n), np.diff(a_ptr))
     key = rows.astype(np.int64) * n + a_col
     assert np.all(np.diff(key) > 0)  # sorted, no duplicates
-    assert np.all(a_col[a_ptr[:-1] + np.searchsorted(a_col[a_ptr[0]:], 0) * 0] >= 0)
     has_loop = np.zeros(n, dtype=bool)
     has_loop[rows[rows == a_col]] = True
     assert has_loop.all()
