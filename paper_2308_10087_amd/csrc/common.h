@@ -97,6 +97,7 @@ struct GemmNtArgs {
   int32_t out_dtype;
   int32_t out_ld;
   int32_t out_pad;  // columns [N, out_pad) of every output row are written as zeros (0: none)
+  int32_t vec_epi;  // set by the launcher: the epilogue may use 16-byte accesses
 };
 int launch_gemm_nt(const GemmNtArgs &a, int compute_dtype, hipStream_t s);
 

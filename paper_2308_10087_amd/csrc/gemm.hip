@@ -64,6 +64,94 @@ __device__ inline void epilogue_store(const GemmNtArgs &a, int m, int n, float a
   store_f32(a.out, a.out_dtype, (size_t)m * a.out_ld + n, r);
 }
 
+__device__ inline void load8_f32(const void *p, int dtype, size_t idx, float (&v)[8]) {
+  if (dtype == DT_BF16) {
+    const bf16x8 x = *reinterpret_cast<const bf16x8 *>(static_cast<const bf16_t *>(p) + idx);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) v[t] = (float)x[t];
+  } else {
+    const f32x4 x0 = *reinterpret_cast<const f32x4 *>(static_cast<const float *>(p) + idx);
+    const f32x4 x1 = *reinterpret_cast<const f32x4 *>(static_cast<const float *>(p) + idx + 4);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      v[t] = x0[t];
+      v[4 + t] = x1[t];
+    }
+  }
+}
+__device__ inline void store8_f32(void *p, int dtype, size_t idx, const float (&v)[8]) {
+  if (dtype == DT_BF16) {
+    bf16x8 x;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) x[t] = (bf16_t)v[t];
+    *reinterpret_cast<bf16x8 *>(static_cast<bf16_t *>(p) + idx) = x;
+  } else {
+    f32x4 x0, x1;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      x0[t] = v[t];
+      x1[t] = v[4 + t];
+    }
+    *reinterpret_cast<f32x4 *>(static_cast<float *>(p) + idx) = x0;
+    *reinterpret_cast<f32x4 *>(static_cast<float *>(p) + idx + 4) = x1;
+  }
+}
+
+// Eight consecutive output columns n0..n0+7 of row m (all inside [0, N), every pointer involved
+// 16-byte aligned at that position: checked on the host, a.vec_epi).
+__device__ inline void epilogue_store8(const GemmNtArgs &a, int m, int n0, const float (&acc)[8]) {
+  float r[8], x[8];
+  switch (a.epilogue) {
+    case EPI_FWD_GCN: {
+      load8_f32(a.bias, DT_F32, (size_t)n0, x);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const float y = acc[t] + x[t];
+        r[t] = y > 0.f ? y : 0.f;
+      }
+      break;
+    }
+    case EPI_FWD_GCNII: {
+      load8_f32(a.aux, a.aux_dtype, (size_t)m * a.aux_ld + n0, x);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const float y = (1.f - a.beta) * x[t] + a.beta * acc[t];
+        r[t] = y > 0.f ? y : 0.f;
+      }
+      break;
+    }
+    case EPI_PLAIN: {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) r[t] = acc[t];
+      break;
+    }
+    case EPI_MASK: {
+      load8_f32(a.aux, a.aux_dtype, (size_t)m * a.aux_ld + n0, x);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) r[t] = x[t] > 0.f ? acc[t] : 0.f;
+      break;
+    }
+    default: {  // EPI_DGRAD_GCNII
+      load8_f32(a.aux, a.aux_dtype, (size_t)m * a.aux_ld + n0, x);
+      float dp[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        dp[t] = (1.f - a.beta) * x[t] + a.beta * acc[t];
+        r[t] = (1.f - a.alpha) * dp[t];
+      }
+      if (a.h0grad) {
+        float h[8];
+        load8_f32(a.h0grad, DT_F32, (size_t)m * a.h0_ld + n0, h);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) h[t] += a.alpha * dp[t];
+        store8_f32(a.h0grad, DT_F32, (size_t)m * a.h0_ld + n0, h);
+      }
+      break;
+    }
+  }
+  store8_f32(a.out, a.out_dtype, (size_t)m * a.out_ld + n0, r);
+}
+
 // 8 consecutive elements of row `r` starting at column `c` as bf16; columns >= cols read as zero.
 template <typename T, bool VEC>
 __device__ inline bf16x8 load8_bf16(const T *base, size_t ld, int r, int c, int cols) {
@@ -149,20 +237,49 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmNtArgs a) {
       __syncthreads();
     }
   }
-  // 32x32 accumulator layout: element t of lane l is row 8*(t/4) + 4*(l/32) + t%4, column l%32
+  // 32x32 accumulator layout: element t of lane l is row 8*(t/4) + 4*(l/32) + t%4, column l%32.
+  // Each wave passes its tiles through a private LDS patch so that a lane ends up with 8 consecutive
+  // columns of one row: 16-byte stores and vector reads of bias / residual rows.
+  __syncthreads();  // every wave is done with the operand tiles; As is reused as staging space
+  constexpr int PS = 36;  // padded row stride (floats) of the 32x32 patch
+  float *patch = reinterpret_cast<float *>(&As[0][0]) + wave * (32 * PS);
+  static_assert(4 * 32 * PS * sizeof(float) <= sizeof(As), "staging patch must fit the A tiles");
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 2; ++j) {
+      const int mt = m0 + wm + i * 32, nt = n0 + wn + j * 32;
+      if (mt >= a.M || nt >= (a.out_pad > a.N ? a.out_pad : a.N)) continue;  // wave-uniform
+      if (a.vec_epi) {
 #pragma unroll
-      for (int t = 0; t < 16; ++t) {
-        const int m = m0 + wm + i * 32 + 8 * (t >> 2) + 4 * (lane >> 5) + (t & 3);
-        const int n = n0 + wn + j * 32 + (lane & 31);
-        if (m < a.M && n < a.N)
-          epilogue_store(a, m, n, acc[i][j][t]);
-        else if (m < a.M && n < a.out_pad)
-          store_f32(a.out, a.out_dtype, (size_t)m * a.out_ld + n, 0.f);
+        for (int t = 0; t < 16; ++t) patch[(8 * (t >> 2) + 4 * (lane >> 5) + (t & 3)) * PS + (lane & 31)] = acc[i][j][t];
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int ps = 0; ps < 2; ++ps) {
+          const int idx = ps * 64 + lane, r = idx >> 2, c = (idx & 3) * 8;
+          float v[8];
+          const f32x4 v0 = *reinterpret_cast<const f32x4 *>(&patch[r * PS + c]);
+          const f32x4 v1 = *reinterpret_cast<const f32x4 *>(&patch[r * PS + c + 4]);
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            v[t] = v0[t];
+            v[4 + t] = v1[t];
+          }
+          if (mt + r < a.M && nt + c < a.N) epilogue_store8(a, mt + r, nt + c, v);
+        }
+        __builtin_amdgcn_wave_barrier();
+      } else {
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+          const int m = mt + 8 * (t >> 2) + 4 * (lane >> 5) + (t & 3);
+          const int n = nt + (lane & 31);
+          if (m < a.M && n < a.N)
+            epilogue_store(a, m, n, acc[i][j][t]);
+          else if (m < a.M && n < a.out_pad)
+            store_f32(a.out, a.out_dtype, (size_t)m * a.out_ld + n, 0.f);
+        }
       }
+    }
 }
 
 // ------------------------------------------------------------------------------------ bf16 TN
@@ -191,8 +308,8 @@ __global__ __launch_bounds__(256) void gemm_tn_bf16_kernel(const GemmTnArgs a, i
 #pragma unroll
       for (int t = 0; t < 16; ++t) acc[i][j][t] = 0.f;
 
-  for (int r0 = r_begin; r0 < r_end; r0 += TR) {
-    bf16x8 ra[2], rb[2];
+  bf16x8 ra[2], rb[2];
+  auto gload = [&](int r0) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int vid = tid + 256 * i, r = vid >> 4, c = (vid & 15) * 8;
@@ -200,6 +317,9 @@ __global__ __launch_bounds__(256) void gemm_tn_bf16_kernel(const GemmTnArgs a, i
       ra[i] = rv ? load8_bf16<TA, VEC>(A, (size_t)a.lda, r0 + r, i0 + c, a_cols) : zero8;
       rb[i] = (rv && o0 + c < a.ldb) ? *reinterpret_cast<const bf16x8 *>(B + (size_t)(r0 + r) * a.ldb + o0 + c) : zero8;
     }
+  };
+  if (r_begin < r_end) gload(r_begin);
+  for (int r0 = r_begin; r0 < r_end; r0 += TR) {
     __syncthreads();  // previous step's fragment reads are done
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -208,6 +328,7 @@ __global__ __launch_bounds__(256) void gemm_tn_bf16_kernel(const GemmTnArgs a, i
       *reinterpret_cast<bf16x8 *>(&Bs[r * LDS_C + c]) = rb[i];
     }
     __syncthreads();
+    if (r0 + TR < r_end) gload(r0 + TR);  // next tile's loads fly while this one is multiplied
 #pragma unroll
     for (int kk = 0; kk < TR / 16; ++kk) {
       const int roff = kk * 16 + (lane >> 5) * 8;
@@ -356,14 +477,30 @@ __global__ __launch_bounds__(256) void gemm_tn_f32_kernel(const GemmTnArgs a, in
     }
 }
 
-// dst[e] += scale * sum_s partial[s][e]   (fixed summation order => reproducible)
+// dst[e] += scale * sum_s partial[s][e].  Fixed summation order => reproducible.  64 outputs per block,
+// four phases of splits summed in parallel (8 independent loads in flight each), then combined in LDS.
 __global__ __launch_bounds__(256) void reduce_add_kernel(const float *partial, int splits, size_t count, float scale,
                                                          float *dst) {
-  const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (e >= count) return;
+  __shared__ float red[4][64];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const size_t e = (size_t)blockIdx.x * 64 + tx;
   float s = 0.f;
-  for (int k = 0; k < splits; ++k) s += partial[(size_t)k * count + e];
-  dst[e] += scale * s;
+  if (e < count) {
+    const int per = (splits + 3) / 4;
+    const int k0 = ty * per, k1 = min(splits, k0 + per);
+    int k = k0;
+    for (; k + 8 <= k1; k += 8) {
+      float v[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) v[t] = partial[(size_t)(k + t) * count + e];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) s += v[t];
+    }
+    for (; k < k1; ++k) s += partial[(size_t)k * count + e];
+  }
+  red[ty][tx] = s;
+  __syncthreads();
+  if (ty == 0 && e < count) dst[e] += scale * ((red[0][tx] + red[1][tx]) + (red[2][tx] + red[3][tx]));
 }
 
 // partial[split][o] = sum of B[r][o] over the split's rows: 64 columns x 4 row phases per block
@@ -386,8 +523,16 @@ bool vec_ok(const void *p, int ld, int mult) { return (reinterpret_cast<uintptr_
 
 }  // namespace
 
-int launch_gemm_nt(const GemmNtArgs &a, int compute_dtype, hipStream_t s) {
-  if (a.M <= 0 || a.N <= 0) return hipSuccess;
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int launch_gemm_nt(const GemmNtArgs &a_in, int compute_dtype, hipStream_t s) {
+  if (a_in.M <= 0 || a_in.N <= 0) return hipSuccess;
+  GemmNtArgs a = a_in;
+  const bool has_aux = a.epilogue == EPI_FWD_GCNII || a.epilogue == EPI_MASK || a.epilogue == EPI_DGRAD_GCNII;
+  a.vec_epi = a.N % 8 == 0 && a.out_ld % 8 == 0 && aligned16(a.out) && (a.out_pad <= a.N) &&
+              (!has_aux || (a.aux_ld % 8 == 0 && aligned16(a.aux))) &&
+              (a.epilogue != EPI_FWD_GCN || aligned16(a.bias)) &&
+              (a.epilogue != EPI_DGRAD_GCNII || !a.h0grad || (a.h0_ld % 4 == 0 && aligned16(a.h0grad)));
   if (compute_dtype == DT_BF16) {
     dim3 grid((a.M + BM - 1) / BM, (a.N + BN - 1) / BN);
     const bool vec = a.a_dtype == DT_BF16 && vec_ok(a.A, a.lda, 8) && a.lda >= a.Kp;
@@ -413,7 +558,11 @@ int launch_gemm_tn(const GemmTnArgs &a, int compute_dtype, hipStream_t s) {
   const int tile = compute_dtype == DT_BF16 ? 128 : 64;
   const int step = compute_dtype == DT_BF16 ? TR : 16;
   const int ti = (a.I + tile - 1) / tile, to = (a.O + tile - 1) / tile;
-  int splits = 256 / (ti * to);
+  int splits = 1024 / (ti * to);  // about four blocks per compute unit ...
+  // ... but the fp32 partials (write + read, 8 bytes per output element and split) should not outweigh
+  // the operands themselves (2 bytes per element of A and B)
+  const long long cap = (long long)a.M * (a.I + a.O) / (4LL * a.I * a.O);
+  if (splits > cap) splits = (int)cap;
   if (splits < 1) splits = 1;
   if (splits > a.max_splits) splits = a.max_splits;
   int rows_per = (a.M + splits - 1) / splits;
@@ -437,7 +586,7 @@ int launch_gemm_tn(const GemmTnArgs &a, int compute_dtype, hipStream_t s) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return (int)e;
   const size_t count = (size_t)a.I * a.O;
-  hipLaunchKernelGGL(reduce_add_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s, a.partial, splits, count,
+  hipLaunchKernelGGL(reduce_add_kernel, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, s, a.partial, splits, count,
                      a.scale, a.dW);
   return (int)hipGetLastError();
 }
@@ -456,6 +605,6 @@ int launch_colsum_add(const void *B, int dtype, int ldb, int M, int O, float *pa
     hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(B), ldb, M, O, rows_per, partial);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return (int)e;
-  hipLaunchKernelGGL(reduce_add_kernel, dim3((unsigned)((O + 255) / 256)), dim3(256), 0, s, partial, splits, (size_t)O, 1.0f, dst);
+  hipLaunchKernelGGL(reduce_add_kernel, dim3((unsigned)((O + 63) / 64)), dim3(256), 0, s, partial, splits, (size_t)O, 1.0f, dst);
   return (int)hipGetLastError();
 }

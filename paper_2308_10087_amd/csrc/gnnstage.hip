@@ -14,18 +14,25 @@
 
 namespace {
 
-constexpr int kMaxSplits = 64;
+constexpr int kMaxSplits = 256;
 constexpr size_t kAlign = 256;
 
 std::string g_create_error;
 
-int split_edges_setting() {
+// Longest piece of a row that one wavefront handles in an aggregation over `entries` entries.  A wave
+// streams roughly 16 entries per microsecond, so the longest task bounds the tail of the launch: pieces
+// shrink with the launch (about 16k pieces' worth of work per launch), within [256, 4096].
+// GNNSTAGE_SPLIT_EDGES overrides (tests force tiny pieces).
+int split_edges_for(int64_t entries) {
   const char *e = getenv("GNNSTAGE_SPLIT_EDGES");
   if (e) {
     const int v = atoi(e);
     if (v >= 64) return v;
   }
-  return 2048;
+  int64_t s = (entries / 16384 + 63) / 64 * 64;
+  if (s < 256) s = 256;
+  if (s > 4096) s = 4096;
+  return (int)s;
 }
 
 struct TaskList {
@@ -40,16 +47,20 @@ struct TaskList {
 // Sizes that depend only on row lengths: number of tasks / long rows / slots of every chunk.
 struct PlanCounts {
   std::vector<int64_t> tasks, longs, slots;
+  std::vector<int> split;
   int64_t total_tasks = 0, total_longs = 0, max_slots = 0;
 };
 
-PlanCounts count_plan(const int64_t *ptr, const std::vector<int64_t> &chunk_ptr, int split) {
+PlanCounts count_plan(const int64_t *ptr, const std::vector<int64_t> &chunk_ptr) {
   PlanCounts pc;
   const int K = (int)chunk_ptr.size() - 1;
   pc.tasks.assign(K, 0);
   pc.longs.assign(K, 0);
   pc.slots.assign(K, 0);
+  pc.split.assign(K, 0);
   for (int c = 0; c < K; ++c) {
+    const int split = split_edges_for(ptr[chunk_ptr[c + 1]] - ptr[chunk_ptr[c]]);
+    pc.split[c] = split;
     for (int64_t r = chunk_ptr[c]; r < chunk_ptr[c + 1]; ++r) {
       const int64_t len = ptr[r + 1] - ptr[r];
       if (len > split) {
@@ -278,7 +289,7 @@ struct Profiler {
 struct gnnstage {
   Shape s;
   Layout lay;
-  int vbits = 0, split = 0;
+  int vbits = 0;
   float alpha = 0.f;
   std::vector<float> beta;
   // caller-owned device buffers
@@ -442,9 +453,8 @@ extern "C" size_t gnnstage_workspace_size(const gnnstage_desc *desc) {
     g_create_error = err;
     return 0;
   }
-  const int split = split_edges_setting();
-  const PlanCounts f = count_plan(desc->row_ptr, s.chunk_ptr, split);
-  const PlanCounts b = count_plan(tptr.data(), s.chunk_ptr, split);
+  const PlanCounts f = count_plan(desc->row_ptr, s.chunk_ptr);
+  const PlanCounts b = count_plan(tptr.data(), s.chunk_ptr);
   return make_layout(s, f, b).total;
 }
 
@@ -489,9 +499,8 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
   rc = gnnstage_plan_pack(s.n, s.nnz, t_row.data(), s.K, s.chunk_ptr.data(), prow.data(), &vbits);
   if (rc != GNNSTAGE_OK) return fail(nullptr, rc, "cannot pack row indices");
 
-  const int split = split_edges_setting();
-  const PlanCounts fc = count_plan(d->row_ptr, s.chunk_ptr, split);
-  const PlanCounts bc = count_plan(t_ptr.data(), s.chunk_ptr, split);
+  const PlanCounts fc = count_plan(d->row_ptr, s.chunk_ptr);
+  const PlanCounts bc = count_plan(t_ptr.data(), s.chunk_ptr);
   Layout lay = make_layout(s, fc, bc);
   if (d->workspace_bytes < lay.total) {
     char buf[160];
@@ -503,7 +512,6 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
   st->s = s;
   st->lay = lay;
   st->vbits = vbits;
-  st->split = split;
   st->alpha = d->alpha;
   if (d->beta) st->beta.assign(d->beta, d->beta + s.L); else st->beta.assign(s.L, 0.f);
   st->W.assign(d->W, d->W + s.L);
@@ -542,7 +550,7 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
       std::vector<int32_t> row(tl.n_tasks), ne(tl.n_tasks), slot(tl.n_tasks);
       std::vector<int64_t> e0(tl.n_tasks);
       int64_t ns = 0;
-      const int64_t got = gnnstage_plan_tasks(ptr, s.chunk_ptr[c], s.chunk_ptr[c + 1], split, tl.n_tasks, row.data(),
+      const int64_t got = gnnstage_plan_tasks(ptr, s.chunk_ptr[c], s.chunk_ptr[c + 1], pc.split[c], tl.n_tasks, row.data(),
                                               e0.data(), ne.data(), slot.data(), &ns);
       if (got != tl.n_tasks || ns != tl.n_slots) return GNNSTAGE_EINVAL;
       std::vector<int32_t> lrow, lslot0, ln;

@@ -173,7 +173,18 @@ __global__ __launch_bounds__(256) void spmm_reduce_kernel(const SpmmArgs a) {
     float acc[VEC];
 #pragma unroll
     for (int t = 0; t < VEC; ++t) acc[t] = 0.f;
-    for (int s = 0; s < ns; ++s) {
+    int s = 0;
+    for (; s + 4 <= ns; s += 4) {  // four independent loads in flight, summed in slot order
+      Pack<float, VEC> x[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        x[q] = *reinterpret_cast<const Pack<float, VEC> *>(a.partial + (size_t)(slot0 + s + q) * a.d + c);
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int t = 0; t < VEC; ++t) acc[t] += x[q].v[t];
+    }
+    for (; s < ns; ++s) {
       const Pack<float, VEC> x = *reinterpret_cast<const Pack<float, VEC> *>(a.partial + (size_t)(slot0 + s) * a.d + c);
 #pragma unroll
       for (int t = 0; t < VEC; ++t) acc[t] += x.v[t];
