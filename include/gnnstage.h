@@ -163,12 +163,17 @@ int gnnstage_plan_transpose(int64_t n, const int64_t *row_ptr, const int32_t *co
                             int64_t *t_ptr, int32_t *t_row, int64_t *t_edge);
 int gnnstage_plan_pack(int64_t n, int64_t nnz, const int32_t *idx, int32_t n_chunks,
                        const int64_t *chunk_ptr, uint32_t *packed, int32_t *vbits);
-/* Launch schedule of one aggregation over rows [row_begin, row_end): every row with at most
- * split_edges entries is one task, longer rows are cut into pieces of split_edges.  Returns the
- * number of tasks (or a negative code); with non-NULL arrays also fills them (capacity checked).
- * task_row: row id; task_e0: first entry; task_ne: entry count; task_slot: -1 for a whole row,
- * else the index of the fp32 partial-sum slot the piece writes. */
-int64_t gnnstage_plan_tasks(const int64_t *ptr, int64_t row_begin, int64_t row_end, int32_t split_edges,
+/* Launch schedule of one aggregation over rows [row_begin, row_end) of a sparse index (ptr, idx).
+ * A task is what one wavefront does.  Rows with at most split_edges entries are one task each
+ * (task_slot = -1).  Longer rows are cut into pieces of at most split_edges entries; with n_classes > 1
+ * rows of at least class_min_row entries are first cut where the source id changes its range class
+ * (class = source * n_classes / n_vertices), so that each piece gathers from one slice of the source
+ * table.  Every piece carries the index of the fp32 partial-sum slot it writes (consecutive per row).
+ * Tasks are emitted in groups of four (one workgroup): group g prefers pieces of class g % n_classes,
+ * cut rows come before whole rows.  Returns the number of tasks (or a negative code); with non-NULL
+ * arrays also fills them (capacity checked).  idx may be NULL when n_classes == 1. */
+int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, int64_t n_vertices, int64_t row_begin,
+                            int64_t row_end, int32_t split_edges, int32_t n_classes, int32_t class_min_row,
                             int64_t capacity, int32_t *task_row, int64_t *task_e0, int32_t *task_ne,
                             int32_t *task_slot, int64_t *n_slots);
 

@@ -176,7 +176,12 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmNtArgs a) {
   __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * LDS_K];
   __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * LDS_K];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+  // Workgroups go round-robin over the 8 XCDs (each with its own L2).  The column tiles that share a
+  // block of A rows are given consecutive slots on ONE XCD, so A is fetched into that L2 once.
+  const int nt = (a.N + BN - 1) / BN;
+  const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+  const int m0 = ((q / nt) * 8 + xcd) * BM, n0 = (q % nt) * BN;
+  if (m0 >= a.M) return;  // padding slots of the last group of 8 row tiles
   const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
   const TA *A = static_cast<const TA *>(a.A);
   const bf16_t *Bt = static_cast<const bf16_t *>(a.Bt);
@@ -287,13 +292,18 @@ constexpr int TR = 32;      // reduction rows per step
 constexpr int LDS_C = 136;  // padded column stride of the row-major LDS tiles
 
 template <typename TA, bool VEC>
-__global__ __launch_bounds__(256) void gemm_tn_bf16_kernel(const GemmTnArgs a, int rows_per_split) {
+__global__ __launch_bounds__(256) void gemm_tn_bf16_kernel(const GemmTnArgs a, int rows_per_split, int splits) {
   __shared__ __attribute__((aligned(16))) bf16_t As[TR * LDS_C];
   __shared__ __attribute__((aligned(16))) bf16_t Bs[TR * LDS_C];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int i0 = blockIdx.x * 128, o0 = blockIdx.y * 128;
+  // XCD-aware order: the output tiles that read the same rows of A and B sit on one XCD (one L2)
+  const int ti = (a.I + 127) / 128, tiles = ti * ((a.O + 127) / 128);
+  const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+  const int tile = q % tiles, split = (q / tiles) * 8 + xcd;
+  if (split >= splits) return;
+  const int i0 = (tile % ti) * 128, o0 = (tile / ti) * 128;
   const int wi = (wave >> 1) * 64, wo = (wave & 1) * 64;
-  const int r_begin = blockIdx.z * rows_per_split;
+  const int r_begin = split * rows_per_split;
   const int r_end = min(a.M, r_begin + rows_per_split);
   const TA *A = static_cast<const TA *>(a.A);
   const bf16_t *B = static_cast<const bf16_t *>(a.B);
@@ -348,7 +358,7 @@ __global__ __launch_bounds__(256) void gemm_tn_bf16_kernel(const GemmTnArgs a, i
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
   }
-  float *P = a.partial + (size_t)blockIdx.z * a.I * a.O;
+  float *P = a.partial + (size_t)split * a.I * a.O;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -534,7 +544,8 @@ int launch_gemm_nt(const GemmNtArgs &a_in, int compute_dtype, hipStream_t s) {
               (a.epilogue != EPI_FWD_GCN || aligned16(a.bias)) &&
               (a.epilogue != EPI_DGRAD_GCNII || !a.h0grad || (a.h0_ld % 4 == 0 && aligned16(a.h0grad)));
   if (compute_dtype == DT_BF16) {
-    dim3 grid((a.M + BM - 1) / BM, (a.N + BN - 1) / BN);
+    const int mt = (a.M + BM - 1) / BM, ntiles = (a.N + BN - 1) / BN;
+    dim3 grid((unsigned)(((mt + 7) / 8) * 8 * ntiles));
     const bool vec = a.a_dtype == DT_BF16 && vec_ok(a.A, a.lda, 8) && a.lda >= a.Kp;
     if (a.a_dtype == DT_F32)
       hipLaunchKernelGGL((gemm_nt_bf16_kernel<float, false>), grid, dim3(256), 0, s, a);
@@ -570,12 +581,13 @@ int launch_gemm_tn(const GemmTnArgs &a, int compute_dtype, hipStream_t s) {
   splits = (a.M + rows_per - 1) / rows_per;
   dim3 grid(ti, to, splits);
   if (compute_dtype == DT_BF16) {
+    dim3 g1((unsigned)(((splits + 7) / 8) * 8 * ti * to));
     if (a.a_dtype == DT_F32)
-      hipLaunchKernelGGL((gemm_tn_bf16_kernel<float, false>), grid, dim3(256), 0, s, a, rows_per);
+      hipLaunchKernelGGL((gemm_tn_bf16_kernel<float, false>), g1, dim3(256), 0, s, a, rows_per, splits);
     else if (vec_ok(a.A, a.lda, 8))
-      hipLaunchKernelGGL((gemm_tn_bf16_kernel<bf16_t, true>), grid, dim3(256), 0, s, a, rows_per);
+      hipLaunchKernelGGL((gemm_tn_bf16_kernel<bf16_t, true>), g1, dim3(256), 0, s, a, rows_per, splits);
     else
-      hipLaunchKernelGGL((gemm_tn_bf16_kernel<bf16_t, false>), grid, dim3(256), 0, s, a, rows_per);
+      hipLaunchKernelGGL((gemm_tn_bf16_kernel<bf16_t, false>), g1, dim3(256), 0, s, a, rows_per, splits);
   } else {
     if (a.a_dtype != DT_F32) return hipErrorInvalidValue;
     if (vec_ok(a.A, a.lda, 4))

@@ -7,6 +7,7 @@
 
 #include <algorithm>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "../../include/gnnstage.h"
@@ -35,6 +36,24 @@ int split_edges_for(int64_t entries) {
   return (int)s;
 }
 
+int xcd_classes_setting() {
+  const char *e = getenv("GNNSTAGE_XCD_CLASSES");
+  if (e) {
+    const int v = atoi(e);
+    if (v >= 1 && v <= 64) return v;
+  }
+  return 8;  // one source-id range per XCD
+}
+
+int class_min_row_setting() {
+  const char *e = getenv("GNNSTAGE_CLASS_MIN_ROW");
+  if (e) {
+    const int v = atoi(e);
+    if (v >= 1) return v;
+  }
+  return 256;
+}
+
 struct TaskList {
   int64_t n_tasks = 0, n_long = 0, n_slots = 0;
   int32_t *task_row = nullptr;
@@ -51,9 +70,12 @@ struct PlanCounts {
   int64_t total_tasks = 0, total_longs = 0, max_slots = 0;
 };
 
+// Upper bounds (from row lengths alone) on tasks / cut rows / slots of every chunk: a row cut by
+// source class adds at most one extra piece per class.
 PlanCounts count_plan(const int64_t *ptr, const std::vector<int64_t> &chunk_ptr) {
   PlanCounts pc;
   const int K = (int)chunk_ptr.size() - 1;
+  const int classes = xcd_classes_setting(), min_row = class_min_row_setting();
   pc.tasks.assign(K, 0);
   pc.longs.assign(K, 0);
   pc.slots.assign(K, 0);
@@ -63,8 +85,9 @@ PlanCounts count_plan(const int64_t *ptr, const std::vector<int64_t> &chunk_ptr)
     pc.split[c] = split;
     for (int64_t r = chunk_ptr[c]; r < chunk_ptr[c + 1]; ++r) {
       const int64_t len = ptr[r + 1] - ptr[r];
-      if (len > split) {
-        const int64_t pieces = (len + split - 1) / split;
+      const bool by_src = classes > 1 && len >= min_row;
+      if (by_src || len > split) {
+        const int64_t pieces = (len + split - 1) / split + (by_src ? classes : 0);
         pc.tasks[c] += pieces;
         pc.slots[c] += pieces;
         pc.longs[c] += 1;
@@ -529,14 +552,13 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
   st->h_pcol = pcol;
 
   // schedules: build on the host chunk by chunk, upload into the preallocated arrays
-  auto build = [&](const int64_t *ptr, const PlanCounts &pc, bool transposed, std::vector<TaskList> &lists) -> int {
+  const int classes = xcd_classes_setting(), min_row = class_min_row_setting();
+  auto build = [&](const int64_t *ptr, const int32_t *idx, const PlanCounts &pc, bool transposed,
+                   std::vector<TaskList> &lists) -> int {
     lists.resize(s.K);
     int64_t t_off = 0, l_off = 0;
     for (int c = 0; c < s.K; ++c) {
       TaskList &tl = lists[c];
-      tl.n_tasks = pc.tasks[c];
-      tl.n_long = pc.longs[c];
-      tl.n_slots = pc.slots[c];
       tl.task_row = st->at<int32_t>(transposed ? lay.b_task_row : lay.f_task_row) + t_off;
       tl.task_e0 = st->at<int64_t>(transposed ? lay.b_task_e0 : lay.f_task_e0) + t_off;
       tl.task_ne = st->at<int32_t>(transposed ? lay.b_task_ne : lay.f_task_ne) + t_off;
@@ -544,29 +566,39 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
       tl.lr_row = st->at<int32_t>(transposed ? lay.b_lr_row : lay.f_lr_row) + l_off;
       tl.lr_slot0 = st->at<int32_t>(transposed ? lay.b_lr_slot0 : lay.f_lr_slot0) + l_off;
       tl.lr_nslots = st->at<int32_t>(transposed ? lay.b_lr_n : lay.f_lr_n) + l_off;
-      t_off += tl.n_tasks;
-      l_off += tl.n_long;
-      if (tl.n_tasks == 0) continue;
-      std::vector<int32_t> row(tl.n_tasks), ne(tl.n_tasks), slot(tl.n_tasks);
-      std::vector<int64_t> e0(tl.n_tasks);
+      t_off += pc.tasks[c];  // the arrays were sized from the upper bounds
+      l_off += pc.longs[c];
+      const int64_t cap = pc.tasks[c];
+      if (cap == 0) continue;
+      std::vector<int32_t> row(cap), ne(cap), slot(cap);
+      std::vector<int64_t> e0(cap);
       int64_t ns = 0;
-      const int64_t got = gnnstage_plan_tasks(ptr, s.chunk_ptr[c], s.chunk_ptr[c + 1], pc.split[c], tl.n_tasks, row.data(),
-                                              e0.data(), ne.data(), slot.data(), &ns);
-      if (got != tl.n_tasks || ns != tl.n_slots) return GNNSTAGE_EINVAL;
+      const int64_t got = gnnstage_plan_tasks(ptr, idx, s.n, s.chunk_ptr[c], s.chunk_ptr[c + 1], pc.split[c], classes,
+                                              min_row, cap, row.data(), e0.data(), ne.data(), slot.data(), &ns);
+      if (got < 0 || got > cap || ns > pc.slots[c]) return GNNSTAGE_EINVAL;
+      tl.n_tasks = got;
+      tl.n_slots = ns;
+      // cut rows: their slots are consecutive, so sorting the pieces by slot groups them by row
+      std::vector<std::pair<int32_t, int32_t>> sr;
+      for (int64_t t = 0; t < got; ++t)
+        if (slot[t] >= 0) sr.emplace_back(slot[t], row[t]);
+      std::sort(sr.begin(), sr.end());
       std::vector<int32_t> lrow, lslot0, ln;
-      for (int64_t t = 0; t < tl.n_tasks && slot[t] >= 0; ++t) {
-        if (lrow.empty() || lrow.back() != row[t]) {
-          lrow.push_back(row[t]);
-          lslot0.push_back(slot[t]);
+      for (const auto &p : sr) {
+        if (lrow.empty() || lrow.back() != p.second) {
+          lrow.push_back(p.second);
+          lslot0.push_back(p.first);
           ln.push_back(0);
         }
         ln.back() += 1;
       }
-      if ((int64_t)lrow.size() != tl.n_long) return GNNSTAGE_EINVAL;
-      if (hipMemcpy(tl.task_row, row.data(), sizeof(int32_t) * tl.n_tasks, hipMemcpyHostToDevice) != hipSuccess ||
-          hipMemcpy(tl.task_e0, e0.data(), sizeof(int64_t) * tl.n_tasks, hipMemcpyHostToDevice) != hipSuccess ||
-          hipMemcpy(tl.task_ne, ne.data(), sizeof(int32_t) * tl.n_tasks, hipMemcpyHostToDevice) != hipSuccess ||
-          hipMemcpy(tl.task_slot, slot.data(), sizeof(int32_t) * tl.n_tasks, hipMemcpyHostToDevice) != hipSuccess)
+      tl.n_long = (int64_t)lrow.size();
+      if (tl.n_long > pc.longs[c]) return GNNSTAGE_EINVAL;
+      if (got > 0 &&
+          (hipMemcpy(tl.task_row, row.data(), sizeof(int32_t) * got, hipMemcpyHostToDevice) != hipSuccess ||
+           hipMemcpy(tl.task_e0, e0.data(), sizeof(int64_t) * got, hipMemcpyHostToDevice) != hipSuccess ||
+           hipMemcpy(tl.task_ne, ne.data(), sizeof(int32_t) * got, hipMemcpyHostToDevice) != hipSuccess ||
+           hipMemcpy(tl.task_slot, slot.data(), sizeof(int32_t) * got, hipMemcpyHostToDevice) != hipSuccess))
         return GNNSTAGE_EHIP;
       if (tl.n_long > 0 &&
           (hipMemcpy(tl.lr_row, lrow.data(), sizeof(int32_t) * tl.n_long, hipMemcpyHostToDevice) != hipSuccess ||
@@ -599,8 +631,8 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
         launch_gcn_norm(st->at<int64_t>(lay.t_ptr), st->at<uint32_t>(lay.prow), vbits, rp, s.n, st->at<float>(lay.tval), nullptr) != 0)
       return bail(GNNSTAGE_EHIP, "normalisation kernel launch failed");
   }
-  rc = build(d->row_ptr, fc, false, st->ftasks);
-  if (rc == GNNSTAGE_OK) rc = build(t_ptr.data(), bc, true, st->btasks);
+  rc = build(d->row_ptr, d->col_idx, fc, false, st->ftasks);
+  if (rc == GNNSTAGE_OK) rc = build(t_ptr.data(), t_row.data(), bc, true, st->btasks);
   if (rc != GNNSTAGE_OK) return bail(rc, "building the launch schedule failed");
   if (hipDeviceSynchronize() != hipSuccess) return bail(GNNSTAGE_EHIP, "device synchronisation failed after create");
   *out = st;

@@ -59,41 +59,107 @@ extern "C" int gnnstage_plan_pack(int64_t n, int64_t nnz, const int32_t *idx, in
   return GNNSTAGE_OK;
 }
 
-extern "C" int64_t gnnstage_plan_tasks(const int64_t *ptr, int64_t row_begin, int64_t row_end, int32_t split_edges,
+namespace {
+struct Task {
+  int32_t row;
+  int64_t e0;
+  int32_t ne;
+  int32_t slot;
+};
+}  // namespace
+
+extern "C" int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, int64_t n_vertices, int64_t row_begin,
+                                       int64_t row_end, int32_t split_edges, int32_t n_classes, int32_t class_min_row,
                                        int64_t capacity, int32_t *task_row, int64_t *task_e0, int32_t *task_ne,
                                        int32_t *task_slot, int64_t *n_slots_out) {
-  if (!ptr || row_begin > row_end || split_edges <= 0) return GNNSTAGE_EINVAL;
-  const bool fill = task_row && task_e0 && task_ne && task_slot;
-  int64_t t = 0, slots = 0;
-  // pass 1: pieces of long rows first, so that the biggest tasks start early
-  for (int64_t r = row_begin; r < row_end; ++r) {
-    const int64_t len = ptr[r + 1] - ptr[r];
-    if (len <= split_edges) continue;
-    for (int64_t off = 0; off < len; off += split_edges) {
-      if (fill) {
-        if (t >= capacity) return GNNSTAGE_ENOMEM;
-        task_row[t] = (int32_t)r;
-        task_e0[t] = ptr[r] + off;
-        task_ne[t] = (int32_t)(len - off < split_edges ? len - off : split_edges);
-        task_slot[t] = (int32_t)slots;
-      }
-      ++t;
+  if (!ptr || row_begin > row_end || split_edges <= 0 || n_classes < 1 || n_classes > 64 || n_vertices <= 0)
+    return GNNSTAGE_EINVAL;
+  const bool classes = n_classes > 1 && idx != nullptr;
+  std::vector<std::vector<Task>> by_class(classes ? n_classes : 1);
+  std::vector<Task> pieces, whole;  // pieces without a class, whole rows
+  int64_t slots = 0;
+  auto cut = [&](std::vector<Task> &q, int64_t r, int64_t b, int64_t e) {
+    for (int64_t off = b; off < e; off += split_edges) {
+      const int64_t m = e - off < split_edges ? e - off : split_edges;
+      q.push_back(Task{(int32_t)r, off, (int32_t)m, (int32_t)slots});
       ++slots;
     }
-  }
-  // pass 2: every other row is one task (empty rows included: they still write zeros)
+  };
   for (int64_t r = row_begin; r < row_end; ++r) {
-    const int64_t len = ptr[r + 1] - ptr[r];
-    if (len > split_edges) continue;
-    if (fill) {
-      if (t >= capacity) return GNNSTAGE_ENOMEM;
-      task_row[t] = (int32_t)r;
-      task_e0[t] = ptr[r];
-      task_ne[t] = (int32_t)len;
-      task_slot[t] = -1;
+    const int64_t b = ptr[r], e = ptr[r + 1], len = e - b;
+    const bool by_src = classes && len >= class_min_row;
+    if (!by_src && len <= split_edges) {  // empty rows included: they still write zeros
+      whole.push_back(Task{(int32_t)r, b, (int32_t)len, -1});
+      continue;
     }
-    ++t;
+    if (!by_src) {
+      cut(pieces, r, b, e);
+      continue;
+    }
+    // maximal runs of entries whose source falls in the same id range (contiguous when the row is sorted);
+    // a row whose columns are so unsorted that it has more runs than classes is cut without classes
+    int64_t runs = 1;
+    for (int64_t x = b + 1; x < e && runs <= n_classes; ++x)
+      if ((int64_t)idx[x] * n_classes / n_vertices != (int64_t)idx[x - 1] * n_classes / n_vertices) ++runs;
+    if (runs > n_classes) {
+      cut(pieces, r, b, e);
+      continue;
+    }
+    int64_t s0 = b;
+    while (s0 < e) {
+      const int64_t cls = (int64_t)idx[s0] * n_classes / n_vertices;
+      int64_t s1 = s0 + 1;
+      while (s1 < e && (int64_t)idx[s1] * n_classes / n_vertices == cls) ++s1;
+      cut(by_class[(size_t)cls], r, s0, s1);
+      s0 = s1;
+    }
   }
+  // Emission: groups of 4 tasks (one workgroup); group g prefers class g % n_classes, so that a class is
+  // served by the workgroups of one XCD (workgroups are dealt round-robin to the XCDs) and that XCD's L2
+  // only ever sees 1/n_classes of the gathered table.  Cut rows first (longest work), whole rows last.
+  std::vector<Task> out;
+  out.reserve(pieces.size() + whole.size() + (size_t)slots);
+  std::vector<size_t> head(by_class.size(), 0);
+  size_t ph = 0, wh = 0;
+  auto class_left = [&]() {
+    for (size_t c = 0; c < by_class.size(); ++c)
+      if (head[c] < by_class[c].size()) return true;
+    return false;
+  };
+  int64_t group = 0;
+  while (class_left() || ph < pieces.size()) {
+    const size_t pref = classes ? (size_t)(group % n_classes) : 0;
+    for (int k = 0; k < 4; ++k) {
+      if (head[pref] < by_class[pref].size()) {
+        out.push_back(by_class[pref][head[pref]++]);
+      } else if (ph < pieces.size()) {
+        out.push_back(pieces[ph++]);
+      } else {
+        size_t best = by_class.size();
+        size_t most = 0;
+        for (size_t c = 0; c < by_class.size(); ++c)
+          if (by_class[c].size() - head[c] > most) {
+            most = by_class[c].size() - head[c];
+            best = c;
+          }
+        if (best == by_class.size()) break;
+        out.push_back(by_class[best][head[best]++]);
+      }
+    }
+    ++group;
+  }
+  for (; wh < whole.size(); ++wh) out.push_back(whole[wh]);
+
+  const int64_t t = (int64_t)out.size();
   if (n_slots_out) *n_slots_out = slots;
+  if (task_row && task_e0 && task_ne && task_slot) {
+    if (t > capacity) return GNNSTAGE_ENOMEM;
+    for (int64_t i = 0; i < t; ++i) {
+      task_row[i] = out[(size_t)i].row;
+      task_e0[i] = out[(size_t)i].e0;
+      task_ne[i] = out[(size_t)i].ne;
+      task_slot[i] = out[(size_t)i].slot;
+    }
+  }
   return t;
 }

@@ -75,31 +75,48 @@ def test_packing_refuses_sizes_beyond_32_bits():
     assert rc == -6  # 28 vertex bits + 8 chunk bits > 32
 
 
-@pytest.mark.parametrize("split", [64, 500, 1 << 20])
-def test_launch_schedule_partitions_the_entries(split):
+@pytest.mark.parametrize("split,classes", [(64, 1), (500, 1), (1 << 20, 1), (64, 8), (300, 8), (1 << 20, 3)])
+def test_launch_schedule_partitions_the_entries(split, classes):
     g = _lib()
     w = CONFIGS["c4_s"]
     row_ptr, col = make_graph(w)
     n = len(row_ptr) - 1
     chunk_ptr = graphs.equal_chunks(n, 5)
     covered = np.zeros(row_ptr[-1], dtype=np.int32)
+    min_row = 100
     for c in range(5):
-        row, e0, ne, slot, n_slots = g.gnnstage_plan_tasks(row_ptr, int(chunk_ptr[c]), int(chunk_ptr[c + 1]), split)
+        row, e0, ne, slot, n_slots = g.gnnstage_plan_tasks(row_ptr, int(chunk_ptr[c]), int(chunk_ptr[c + 1]), split,
+                                                           idx=col, n_vertices=n, n_classes=classes, class_min_row=min_row)
         assert np.all(ne <= split) and np.all(ne >= 0)
         assert np.all((row >= chunk_ptr[c]) & (row < chunk_ptr[c + 1]))
         for r, a, m in zip(row, e0, ne):
             assert row_ptr[r] <= a and a + m <= row_ptr[r + 1]
             covered[a:a + m] += 1
         deg = np.diff(row_ptr)[chunk_ptr[c]:chunk_ptr[c + 1]]
-        long_rows = np.flatnonzero(deg > split) + chunk_ptr[c]
-        # whole rows carry slot -1 and appear once; long rows are cut into consecutive slots, listed first
+        is_cut = (deg > split) | ((classes > 1) & (deg >= min_row))
+        cut_rows = np.flatnonzero(is_cut) + chunk_ptr[c]
+        # whole rows carry slot -1 and appear once, after every piece of the cut rows
         whole = row[slot < 0]
-        assert len(np.unique(whole)) == len(whole) == (deg <= split).sum()
-        pieces = slot[slot >= 0]
+        assert len(np.unique(whole)) == len(whole) == (~is_cut).sum()
+        pieces = np.sort(slot[slot >= 0])
         assert np.array_equal(pieces, np.arange(n_slots))
         assert np.all(slot[:len(pieces)] >= 0)
-        assert set(row[slot >= 0].tolist()) == set(long_rows.tolist())
-        assert n_slots == int(np.ceil(deg[deg > split] / split).sum())
+        assert set(row[slot >= 0].tolist()) == set(cut_rows.tolist())
+        # slots of one row are consecutive (the reduce kernel sums slot0 .. slot0 + count - 1)
+        order = np.argsort(slot[slot >= 0])
+        rows_by_slot = row[slot >= 0][order]
+        assert np.all(np.diff(rows_by_slot) >= 0) or len(np.unique(rows_by_slot)) == (np.diff(rows_by_slot) != 0).sum() + 1
+        if classes > 1:
+            # every piece of a class-cut row gathers from a single source-id range
+            for r, a, m, sl in zip(row, e0, ne, slot):
+                if sl >= 0 and deg[r - chunk_ptr[c]] >= min_row and m > 0:
+                    cls = col[a:a + m].astype(np.int64) * classes // n
+                    assert cls.min() == cls.max()
+            # workgroup g (tasks 4g .. 4g+3) prefers class g % classes while that class has pieces left
+            k = len(pieces)
+            grp_cls = [int(col[e0[i]]) * classes // n for i in range(0, min(k, 4 * classes * 3), 4)
+                       if deg[row[i] - chunk_ptr[c]] >= min_row]
+            assert grp_cls[:classes] == list(range(classes))[:len(grp_cls)] or k < 4 * classes
     assert np.all(covered == 1)  # every entry belongs to exactly one task
 
 
