@@ -77,7 +77,7 @@ def _load():
     lib.gnnstage_plan_tasks.restype = C.c_int64
     lib.gnnstage_plan_tasks.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_int32,
                                         C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
-                                        C.POINTER(C.c_int64)]
+                                        C.POINTER(C.c_int64), C.c_void_p, C.c_void_p]
     lib.gnnstage_layer_order.restype = C.c_int
     lib.gnnstage_layer_order.argtypes = [C.c_void_p, C.c_int32]
     lib.gnnstage_profile_enable.restype = C.c_int
@@ -124,7 +124,7 @@ def gnnstage_plan_pack(n: int, idx: np.ndarray, chunk_ptr: np.ndarray):
 
 
 def gnnstage_plan_tasks(ptr: np.ndarray, row_begin: int, row_end: int, split_edges: int, idx=None,
-                        n_vertices: int = 0, n_classes: int = 1, class_min_row: int = 0):
+                        n_vertices: int = 0, n_classes: int = 1, class_min_row: int = 0, return_classes: bool = False):
     ptr = np.ascontiguousarray(ptr, dtype=np.int64)
     if idx is not None:
         idx = np.ascontiguousarray(idx, dtype=np.int32)
@@ -132,15 +132,20 @@ def gnnstage_plan_tasks(ptr: np.ndarray, row_begin: int, row_end: int, split_edg
     nv = n_vertices if n_vertices > 0 else ptr.shape[0] - 1
     ns = C.c_int64(0)
     n = lib.gnnstage_plan_tasks(ptr.ctypes.data, ip, nv, row_begin, row_end, split_edges, n_classes, class_min_row,
-                                0, None, None, None, None, C.byref(ns))
+                                0, None, None, None, None, C.byref(ns), None, None)
     if n < 0:
         raise GnnStageError(int(n), "gnnstage_plan_tasks")
     row, e0 = np.zeros(n, np.int32), np.zeros(n, np.int64)
     ne, slot = np.zeros(n, np.int32), np.zeros(n, np.int32)
+    class_off = np.zeros(n_classes + 1, np.int64)
+    slot_class = np.zeros(max(int(ns.value), 1), np.uint8)
     got = lib.gnnstage_plan_tasks(ptr.ctypes.data, ip, nv, row_begin, row_end, split_edges, n_classes, class_min_row,
-                                  n, row.ctypes.data, e0.ctypes.data, ne.ctypes.data, slot.ctypes.data, C.byref(ns))
+                                  n, row.ctypes.data, e0.ctypes.data, ne.ctypes.data, slot.ctypes.data, C.byref(ns),
+                                  class_off.ctypes.data, slot_class.ctypes.data)
     if got != n:
         raise GnnStageError(int(got), "gnnstage_plan_tasks")
+    if return_classes:
+        return row, e0, ne, slot, int(ns.value), class_off, slot_class[:int(ns.value)]
     return row, e0, ne, slot, int(ns.value)
 
 

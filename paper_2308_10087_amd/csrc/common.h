@@ -34,6 +34,16 @@ struct SpmmArgs {
   const int32_t *task_ne;
   const int32_t *task_slot;
   int64_t n_tasks;
+  // XCD-aware serving order.  Tasks [0, tail_task0) are pieces grouped by source-id class (class c at
+  // cls_task0[c], cls_ntasks[c] of them); workgroups are dealt round-robin to the 8 XCDs, and XCD x
+  // (workgroups with index % 8 == x) serves class xcd_cls[x], taking the groups of four tasks
+  // xcd_first[x], xcd_first[x] + xcd_stride[x], ...  Workgroups from n_class_blocks on serve the tail.
+  int32_t cls_task0[8], cls_ntasks[8];
+  int32_t xcd_cls[8], xcd_first[8], xcd_stride[8];
+  int32_t n_class_blocks;
+  int64_t tail_task0;
+  const uint8_t *slot_class;  // class of every partial slot (255: none); pieces of inactive classes are not run
+  uint32_t active_classes;
   // long rows: pieces summed by the reduce kernel
   const int32_t *lr_row;
   const int32_t *lr_slot0;
@@ -58,6 +68,19 @@ struct SpmmArgs {
   float s_acc, s_aux;
   const float *bias;  // SPMM_BIAS_RELU
 };
+
+// which task the wave `wave` of workgroup `b` runs (-1: none)
+__device__ inline int64_t spmm_task_index(const SpmmArgs &a, unsigned b, int wave) {
+  if (b < (unsigned)a.n_class_blocks) {
+    const int x = b & 7, j = b >> 3;
+    const int cls = a.xcd_cls[x];
+    if (cls < 0) return -1;
+    const int64_t t = ((int64_t)j * a.xcd_stride[x] + a.xcd_first[x]) * 4 + wave;
+    return t < a.cls_ntasks[cls] ? a.cls_task0[cls] + t : -1;
+  }
+  const int64_t t = a.tail_task0 + (int64_t)(b - a.n_class_blocks) * 4 + wave;
+  return t < a.n_tasks ? t : -1;
+}
 
 enum DType : int { DT_F32 = 0, DT_BF16 = 1 };
 

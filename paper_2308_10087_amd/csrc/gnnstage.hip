@@ -36,13 +36,14 @@ int split_edges_for(int64_t entries) {
   return (int)s;
 }
 
-int xcd_classes_setting() {
+// Source-id classes (one per XCD) pay when one class's slice of the gathered table has a chance to
+// live in an XCD's L2 and the memory-side cache; for tables far beyond that they only add partial sums.
+// GNNSTAGE_XCD_CLASSES=1 switches them off, =8 forces them on.
+int xcd_classes_setting(int64_t table_bytes) {
   const char *e = getenv("GNNSTAGE_XCD_CLASSES");
-  if (e) {
-    const int v = atoi(e);
-    if (v >= 1 && v <= 64) return v;
-  }
-  return 8;  // one source-id range per XCD
+  if (e && atoi(e) == 1) return 1;
+  if (e && atoi(e) == 8) return 8;
+  return table_bytes <= (int64_t)256 << 20 ? 8 : 1;
 }
 
 int class_min_row_setting() {
@@ -61,21 +62,25 @@ struct TaskList {
   int32_t *task_ne = nullptr;
   int32_t *task_slot = nullptr;
   int32_t *lr_row = nullptr, *lr_slot0 = nullptr, *lr_nslots = nullptr;
+  // class sections of the task list (class c = tasks [cls_off[c], cls_off[c+1]); tail from cls_off[8])
+  int64_t cls_off[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+  uint8_t *slot_class = nullptr;
 };
 
 // Sizes that depend only on row lengths: number of tasks / long rows / slots of every chunk.
 struct PlanCounts {
   std::vector<int64_t> tasks, longs, slots;
   std::vector<int> split;
+  int64_t total_slots = 0;
   int64_t total_tasks = 0, total_longs = 0, max_slots = 0;
 };
 
 // Upper bounds (from row lengths alone) on tasks / cut rows / slots of every chunk: a row cut by
 // source class adds at most one extra piece per class.
-PlanCounts count_plan(const int64_t *ptr, const std::vector<int64_t> &chunk_ptr) {
+PlanCounts count_plan(const int64_t *ptr, const std::vector<int64_t> &chunk_ptr, int classes) {
   PlanCounts pc;
   const int K = (int)chunk_ptr.size() - 1;
-  const int classes = xcd_classes_setting(), min_row = class_min_row_setting();
+  const int min_row = class_min_row_setting();
   pc.tasks.assign(K, 0);
   pc.longs.assign(K, 0);
   pc.slots.assign(K, 0);
@@ -97,6 +102,7 @@ PlanCounts count_plan(const int64_t *ptr, const std::vector<int64_t> &chunk_ptr)
     }
     pc.total_tasks += pc.tasks[c];
     pc.total_longs += pc.longs[c];
+    pc.total_slots += pc.slots[c];
     if (pc.slots[c] > pc.max_slots) pc.max_slots = pc.slots[c];
   }
   return pc;
@@ -115,6 +121,7 @@ struct Layout {
   size_t row_ptr, pcol, val, t_ptr, prow, tval;
   size_t f_task_row, f_task_e0, f_task_ne, f_task_slot, f_lr_row, f_lr_slot0, f_lr_n;
   size_t b_task_row, b_task_e0, b_task_ne, b_task_slot, b_lr_row, b_lr_slot0, b_lr_n;
+  size_t f_slot_class, b_slot_class;
   size_t partial;
   std::vector<size_t> Z, dZ, Wt, Wn, Tc, Th;
   size_t G[2];
@@ -131,6 +138,14 @@ struct Shape {
   int dtype = 0, level0_f32 = 0, variant = 0, need_input_grad = 0;
   int elt() const { return dtype == GNNSTAGE_BF16 ? 2 : 4; }
   int level_elt(int j) const { return (j == 0 && level0_f32) ? 4 : elt(); }
+  // source classes for the aggregation schedule, decided by the widest bf16/fp32 table that is gathered
+  int classes() const {
+    int64_t widest = 0;  // bytes of the widest row any aggregation of the stage gathers
+    for (int j = 0; j < L; ++j)
+      widest = std::max<int64_t>(widest, tf[j] ? (int64_t)dims[j + 1] * elt()
+                                               : std::max<int64_t>((int64_t)dims[j] * level_elt(j), (int64_t)dims[j] * elt()));
+    return xcd_classes_setting(n * widest);
+  }
   int64_t max_rows() const {
     int64_t m = 0;
     for (int c = 0; c < K; ++c) m = std::max<int64_t>(m, chunk_ptr[c + 1] - chunk_ptr[c]);
@@ -226,6 +241,8 @@ Layout make_layout(const Shape &s, const PlanCounts &f, const PlanCounts &b) {
   l.b_lr_row = w.take(sizeof(int32_t) * b.total_longs);
   l.b_lr_slot0 = w.take(sizeof(int32_t) * b.total_longs);
   l.b_lr_n = w.take(sizeof(int32_t) * b.total_longs);
+  l.f_slot_class = w.take((size_t)f.total_slots);
+  l.b_slot_class = w.take((size_t)b.total_slots);
   int max_d = 0, max_ld = 0;
   size_t max_io = 0;
   for (int j = 0; j <= s.L; ++j) {
@@ -327,6 +344,7 @@ struct gnnstage {
   std::vector<uint32_t> h_pcol;
   // schedules
   std::vector<TaskList> ftasks, btasks;
+  ChunkMask cls_chunks[8] = {};  // chunks that overlap the id range of each source class
   // pass state (Section 3.3: V_processed, and its backward twin)
   std::vector<int32_t> order;
   ChunkMask fmask{}, bmask{};
@@ -380,6 +398,57 @@ void mask_set(ChunkMask &m, int c) { m.w[c >> 6] |= 1ull << (c & 63); }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// XCD assignment of the class sections for one launch.  `drop` = the launch skips unselected entries:
+// a class none of whose chunks is in the mask has no work and is not served at all; the 8 XCDs are shared
+// out among the remaining classes in proportion to their (estimated) work, every class at least one.
+void assign_xcds(const gnnstage *st, const TaskList &t, const ChunkMask &mask, bool drop, SpmmArgs &a) {
+  a.tail_task0 = t.cls_off[8];
+  a.slot_class = t.slot_class;
+  a.active_classes = 0;
+  a.n_class_blocks = 0;
+  double w[8];
+  int share[8], n_active = 0;
+  for (int q = 0; q < 8; ++q) {
+    a.cls_task0[q] = (int32_t)t.cls_off[q];
+    a.cls_ntasks[q] = (int32_t)(t.cls_off[q + 1] - t.cls_off[q]);
+    a.xcd_cls[q] = -1;
+    a.xcd_first[q] = 0;
+    a.xcd_stride[q] = 1;
+    int tot = 0, on = 0;
+    for (int c = 0; c < st->s.K; ++c)
+      if (mask_test(st->cls_chunks[q], c)) {
+        ++tot;
+        on += mask_test(mask, c) ? 1 : 0;
+      }
+    const double frac = drop ? (tot ? (double)on / tot : 0.0) : 1.0;
+    w[q] = a.cls_ntasks[q] * frac;
+    share[q] = 0;
+    if (a.cls_ntasks[q] > 0 && frac > 0.0) {
+      a.active_classes |= 1u << q;
+      share[q] = 1;
+      ++n_active;
+    }
+  }
+  if (n_active == 0) return;
+  for (int left = 8 - n_active; left > 0; --left) {
+    int best = -1;
+    for (int q = 0; q < 8; ++q)
+      if (share[q] > 0 && (best < 0 || w[q] / share[q] > w[best] / share[best])) best = q;
+    share[best] += 1;
+  }
+  int x = 0, max_rounds = 0;
+  for (int q = 0; q < 8; ++q) {
+    const int groups = (a.cls_ntasks[q] + 3) / 4;
+    for (int i = 0; i < share[q]; ++i, ++x) {
+      a.xcd_cls[x] = q;
+      a.xcd_first[x] = i;
+      a.xcd_stride[x] = share[q];
+      max_rounds = std::max(max_rounds, (groups - i + share[q] - 1) / share[q]);
+    }
+  }
+  a.n_class_blocks = 8 * max_rounds;
+}
+
 SpmmArgs base_spmm(const gnnstage *st, bool transposed, int chunk) {
   SpmmArgs a{};
   const TaskList &t = transposed ? st->btasks[chunk] : st->ftasks[chunk];
@@ -397,6 +466,7 @@ SpmmArgs base_spmm(const gnnstage *st, bool transposed, int chunk) {
   a.partial = st->at<float>(st->lay.partial);
   a.vbits = st->vbits;
   a.mask = transposed ? st->bmask : st->fmask;
+  assign_xcds(st, t, a.mask, transposed, a);  // every transposed launch drops unselected entries
   return a;
 }
 
@@ -429,6 +499,7 @@ int finish_transform_first(gnnstage *st, hipStream_t stream) {
       if (M == 0) continue;
       SpmmArgs a = base_spmm(st, true, c);
       a.mask = all;
+      assign_xcds(st, st->btasks[c], all, true, a);
       a.src_sel = st->at<char>(st->lay.dZ[j]);
       a.src_unsel = nullptr;
       a.d = s.dims[j + 1];
@@ -476,8 +547,8 @@ extern "C" size_t gnnstage_workspace_size(const gnnstage_desc *desc) {
     g_create_error = err;
     return 0;
   }
-  const PlanCounts f = count_plan(desc->row_ptr, s.chunk_ptr);
-  const PlanCounts b = count_plan(tptr.data(), s.chunk_ptr);
+  const PlanCounts f = count_plan(desc->row_ptr, s.chunk_ptr, s.classes());
+  const PlanCounts b = count_plan(tptr.data(), s.chunk_ptr, s.classes());
   return make_layout(s, f, b).total;
 }
 
@@ -522,8 +593,8 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
   rc = gnnstage_plan_pack(s.n, s.nnz, t_row.data(), s.K, s.chunk_ptr.data(), prow.data(), &vbits);
   if (rc != GNNSTAGE_OK) return fail(nullptr, rc, "cannot pack row indices");
 
-  const PlanCounts fc = count_plan(d->row_ptr, s.chunk_ptr);
-  const PlanCounts bc = count_plan(t_ptr.data(), s.chunk_ptr);
+  const PlanCounts fc = count_plan(d->row_ptr, s.chunk_ptr, s.classes());
+  const PlanCounts bc = count_plan(t_ptr.data(), s.chunk_ptr, s.classes());
   Layout lay = make_layout(s, fc, bc);
   if (d->workspace_bytes < lay.total) {
     char buf[160];
@@ -548,17 +619,24 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
   st->grad_h0 = d->grad_h0;
   st->ws = static_cast<char *>(d->workspace);
   st->prof.init(s.L);
+  for (int q = 0; q < 8; ++q)
+    for (int c = 0; c < s.K; ++c) {
+      const int64_t lo = (q * s.n + 7) / 8, hi = ((q + 1) * s.n + 7) / 8;  // ids u with u * 8 / n == q
+      if (s.chunk_ptr[c] < hi && s.chunk_ptr[c + 1] > lo) mask_set(st->cls_chunks[q], c);
+    }
   st->h_row_ptr.assign(d->row_ptr, d->row_ptr + s.n + 1);
   st->h_pcol = pcol;
 
   // schedules: build on the host chunk by chunk, upload into the preallocated arrays
-  const int classes = xcd_classes_setting(), min_row = class_min_row_setting();
+  const int classes = s.classes(), min_row = class_min_row_setting();
   auto build = [&](const int64_t *ptr, const int32_t *idx, const PlanCounts &pc, bool transposed,
                    std::vector<TaskList> &lists) -> int {
     lists.resize(s.K);
-    int64_t t_off = 0, l_off = 0;
+    int64_t t_off = 0, l_off = 0, s_off = 0;
     for (int c = 0; c < s.K; ++c) {
       TaskList &tl = lists[c];
+      tl.slot_class = st->at<uint8_t>(transposed ? lay.b_slot_class : lay.f_slot_class) + s_off;
+      s_off += pc.slots[c];
       tl.task_row = st->at<int32_t>(transposed ? lay.b_task_row : lay.f_task_row) + t_off;
       tl.task_e0 = st->at<int64_t>(transposed ? lay.b_task_e0 : lay.f_task_e0) + t_off;
       tl.task_ne = st->at<int32_t>(transposed ? lay.b_task_ne : lay.f_task_ne) + t_off;
@@ -573,9 +651,19 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
       std::vector<int32_t> row(cap), ne(cap), slot(cap);
       std::vector<int64_t> e0(cap);
       int64_t ns = 0;
+      std::vector<int64_t> coff(classes + 1, 0);
+      std::vector<uint8_t> sclass((size_t)std::max<int64_t>(pc.slots[c], 1), 255);
       const int64_t got = gnnstage_plan_tasks(ptr, idx, s.n, s.chunk_ptr[c], s.chunk_ptr[c + 1], pc.split[c], classes,
-                                              min_row, cap, row.data(), e0.data(), ne.data(), slot.data(), &ns);
+                                              min_row, cap, row.data(), e0.data(), ne.data(), slot.data(), &ns,
+                                              coff.data(), sclass.data());
       if (got < 0 || got > cap || ns > pc.slots[c]) return GNNSTAGE_EINVAL;
+      if (classes == 8) {
+        for (int q = 0; q <= 8; ++q) tl.cls_off[q] = coff[q];
+      } else {  // no class sections: everything is tail
+        for (int q = 0; q <= 8; ++q) tl.cls_off[q] = 0;
+      }
+      if (ns > 0 && hipMemcpy(tl.slot_class, sclass.data(), (size_t)ns, hipMemcpyHostToDevice) != hipSuccess)
+        return GNNSTAGE_EHIP;
       tl.n_tasks = got;
       tl.n_slots = ns;
       // cut rows: their slots are consecutive, so sorting the pieces by slot groups them by row

@@ -71,7 +71,8 @@ struct Task {
 extern "C" int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, int64_t n_vertices, int64_t row_begin,
                                        int64_t row_end, int32_t split_edges, int32_t n_classes, int32_t class_min_row,
                                        int64_t capacity, int32_t *task_row, int64_t *task_e0, int32_t *task_ne,
-                                       int32_t *task_slot, int64_t *n_slots_out) {
+                                       int32_t *task_slot, int64_t *n_slots_out, int64_t *class_off,
+                                       uint8_t *slot_class) {
   if (!ptr || row_begin > row_end || split_edges <= 0 || n_classes < 1 || n_classes > 64 || n_vertices <= 0)
     return GNNSTAGE_EINVAL;
   const bool classes = n_classes > 1 && idx != nullptr;
@@ -114,41 +115,24 @@ extern "C" int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, i
       s0 = s1;
     }
   }
-  // Emission: groups of 4 tasks (one workgroup); group g prefers class g % n_classes, so that a class is
-  // served by the workgroups of one XCD (workgroups are dealt round-robin to the XCDs) and that XCD's L2
-  // only ever sees 1/n_classes of the gathered table.  Cut rows first (longest work), whole rows last.
+  // Emission, class-major: [class 0 pieces] ... [class C-1 pieces] [other pieces] [whole rows].  Which
+  // workgroups serve which class is decided at launch time (one class per XCD when all are active).
   std::vector<Task> out;
   out.reserve(pieces.size() + whole.size() + (size_t)slots);
-  std::vector<size_t> head(by_class.size(), 0);
-  size_t ph = 0, wh = 0;
-  auto class_left = [&]() {
-    for (size_t c = 0; c < by_class.size(); ++c)
-      if (head[c] < by_class[c].size()) return true;
-    return false;
-  };
-  int64_t group = 0;
-  while (class_left() || ph < pieces.size()) {
-    const size_t pref = classes ? (size_t)(group % n_classes) : 0;
-    for (int k = 0; k < 4; ++k) {
-      if (head[pref] < by_class[pref].size()) {
-        out.push_back(by_class[pref][head[pref]++]);
-      } else if (ph < pieces.size()) {
-        out.push_back(pieces[ph++]);
-      } else {
-        size_t best = by_class.size();
-        size_t most = 0;
-        for (size_t c = 0; c < by_class.size(); ++c)
-          if (by_class[c].size() - head[c] > most) {
-            most = by_class[c].size() - head[c];
-            best = c;
-          }
-        if (best == by_class.size()) break;
-        out.push_back(by_class[best][head[best]++]);
-      }
-    }
-    ++group;
+  for (size_t c = 0; c < by_class.size(); ++c) {
+    if (class_off) class_off[c] = (int64_t)out.size();
+    out.insert(out.end(), by_class[c].begin(), by_class[c].end());
+    if (slot_class)
+      for (const Task &t : by_class[c]) slot_class[t.slot] = (uint8_t)(classes ? c : 255);
   }
-  for (; wh < whole.size(); ++wh) out.push_back(whole[wh]);
+  if (class_off) {
+    for (int c = (int)by_class.size(); c <= n_classes; ++c) class_off[c] = (int64_t)out.size();
+    if (!classes) class_off[0] = 0, class_off[n_classes] = 0;  // no class section at all
+  }
+  if (slot_class)
+    for (const Task &t : pieces) slot_class[t.slot] = 255;
+  out.insert(out.end(), pieces.begin(), pieces.end());
+  out.insert(out.end(), whole.begin(), whole.end());
 
   const int64_t t = (int64_t)out.size();
   if (n_slots_out) *n_slots_out = slots;

@@ -72,8 +72,8 @@ __global__ __launch_bounds__(256) void spmm_kernel(const SpmmArgs a) {
   constexpr int G = 64 / LPR;
   constexpr int TILE_W = LPR * NV * VEC;
   const int lane = threadIdx.x & 63;
-  const int64_t task = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (task >= a.n_tasks) return;  // whole wave leaves together
+  const int64_t task = spmm_task_index(a, blockIdx.x, threadIdx.x >> 6);
+  if (task < 0) return;  // whole wave leaves together
   const int grp = lane / LPR, lig = lane % LPR;
   const int col0 = blockIdx.y * TILE_W + lig * VEC;
   // task fields are the same for the whole wave: keep them in scalar registers, so that every loop
@@ -163,33 +163,45 @@ __global__ __launch_bounds__(256) void spmm_kernel(const SpmmArgs a) {
   }
 }
 
-// Sums the pieces of every long row in slot order, then applies the epilogue.
+// Sums the pieces of every cut row, then applies the epilogue.  One workgroup per row: 8 phases x 32
+// column vectors; phase p adds the slots p, p+8, p+16, ... (hub rows have hundreds of pieces), then the 8
+// phase sums are added in order.  The order is fixed, so results are reproducible.
 template <typename Tin, typename Tout, int VEC>
 __global__ __launch_bounds__(256) void spmm_reduce_kernel(const SpmmArgs a) {
+  __shared__ float red[8][32][VEC];
   const int64_t i = blockIdx.x;
+  const int ph = threadIdx.x >> 5, cv = threadIdx.x & 31;
   const int64_t row = a.lr_row[i];
   const int slot0 = a.lr_slot0[i], ns = a.lr_nslots[i];
-  for (int c = threadIdx.x * VEC; c < a.d; c += blockDim.x * VEC) {
+  // pieces of classes that were not run in this launch (all their entries unselected) hold stale data
+  const bool check = a.slot_class != nullptr && a.active_classes != 0xffu;
+  for (int c0 = 0; c0 < a.d; c0 += 32 * VEC) {
+    const int c = c0 + cv * VEC;
     float acc[VEC];
 #pragma unroll
     for (int t = 0; t < VEC; ++t) acc[t] = 0.f;
-    int s = 0;
-    for (; s + 4 <= ns; s += 4) {  // four independent loads in flight, summed in slot order
-      Pack<float, VEC> x[4];
+    if (c < a.d) {
+      for (int s = ph; s < ns; s += 8) {
+        if (check) {
+          const uint32_t sc = a.slot_class[slot0 + s];
+          if (sc < 32u && !((a.active_classes >> sc) & 1u)) continue;
+        }
+        const Pack<float, VEC> x = *reinterpret_cast<const Pack<float, VEC> *>(a.partial + (size_t)(slot0 + s) * a.d + c);
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        x[q] = *reinterpret_cast<const Pack<float, VEC> *>(a.partial + (size_t)(slot0 + s + q) * a.d + c);
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int t = 0; t < VEC; ++t) acc[t] += x[q].v[t];
+        for (int t = 0; t < VEC; ++t) acc[t] += x.v[t];
+      }
     }
-    for (; s < ns; ++s) {
-      const Pack<float, VEC> x = *reinterpret_cast<const Pack<float, VEC> *>(a.partial + (size_t)(slot0 + s) * a.d + c);
 #pragma unroll
-      for (int t = 0; t < VEC; ++t) acc[t] += x.v[t];
+    for (int t = 0; t < VEC; ++t) red[ph][cv][t] = acc[t];
+    __syncthreads();
+    if (ph == 0 && c < a.d) {
+#pragma unroll
+      for (int p = 1; p < 8; ++p)
+#pragma unroll
+        for (int t = 0; t < VEC; ++t) acc[t] += red[p][cv][t];
+      finish_cols<Tin, Tout, VEC>(a, row, c, acc);
     }
-    finish_cols<Tin, Tout, VEC>(a, row, c, acc);
+    __syncthreads();
   }
   if (threadIdx.x < 64) zero_pad_cols<Tout>(a, row, threadIdx.x);
 }
@@ -214,8 +226,8 @@ __global__ __launch_bounds__(256) void spmm_mfma_kernel(const SpmmArgs a) {
   constexpr int TILE_W = NT * 128;
   __shared__ float rowbuf[4][TILE_W];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t task = (int64_t)blockIdx.x * 4 + wave;
-  if (task >= a.n_tasks) return;  // whole wave leaves together (no block-wide barrier below)
+  const int64_t task = spmm_task_index(a, blockIdx.x, wave);
+  if (task < 0) return;  // whole wave leaves together (no block-wide barrier below)
   const int g = lane >> 4, lig = lane & 15;
   const int tile0 = blockIdx.y * TILE_W;
   // task fields are the same for the whole wave: keep them in scalar registers.  The matrix
@@ -419,7 +431,8 @@ static bool mfma_path(const SpmmArgs &a, int src_dtype) {
 
 template <typename Tout>
 static int launch_mfma(const SpmmArgs &a, hipStream_t s) {
-  const unsigned gx = (unsigned)((a.n_tasks + 3) / 4);
+  const unsigned gx = (unsigned)(a.n_class_blocks + (a.n_tasks - a.tail_task0 + 3) / 4);
+  if (gx == 0) return hipSuccess;  // only class pieces, none of them active
   if (a.d <= 128)
     hipLaunchKernelGGL((spmm_mfma_kernel<Tout, 1>), dim3(gx, 1), dim3(256), 0, s, a);
   else if (a.d <= 256)
@@ -435,7 +448,8 @@ int launch_spmm(const SpmmArgs &a, int src_dtype, int out_dtype, hipStream_t s) 
   const Shape *best = pick_shape(a, src_dtype, out_dtype);
   if (!best) return hipErrorInvalidValue;
   const int tile_w = best->lpr * best->nv * best->vec;
-  dim3 grid((unsigned)((a.n_tasks + 3) / 4), (unsigned)((a.d + tile_w - 1) / tile_w));
+  dim3 grid((unsigned)(a.n_class_blocks + (a.n_tasks - a.tail_task0 + 3) / 4), (unsigned)((a.d + tile_w - 1) / tile_w));
+  if (grid.x == 0) return hipSuccess;
   hipLaunchKernelGGL(best->main, grid, dim3(256), 0, s, a);
   return (int)hipGetLastError();
 }

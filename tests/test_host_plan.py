@@ -85,8 +85,9 @@ def test_launch_schedule_partitions_the_entries(split, classes):
     covered = np.zeros(row_ptr[-1], dtype=np.int32)
     min_row = 100
     for c in range(5):
-        row, e0, ne, slot, n_slots = g.gnnstage_plan_tasks(row_ptr, int(chunk_ptr[c]), int(chunk_ptr[c + 1]), split,
-                                                           idx=col, n_vertices=n, n_classes=classes, class_min_row=min_row)
+        row, e0, ne, slot, n_slots, class_off, slot_class = g.gnnstage_plan_tasks(
+            row_ptr, int(chunk_ptr[c]), int(chunk_ptr[c + 1]), split, idx=col, n_vertices=n, n_classes=classes,
+            class_min_row=min_row, return_classes=True)
         assert np.all(ne <= split) and np.all(ne >= 0)
         assert np.all((row >= chunk_ptr[c]) & (row < chunk_ptr[c + 1]))
         for r, a, m in zip(row, e0, ne):
@@ -106,17 +107,17 @@ def test_launch_schedule_partitions_the_entries(split, classes):
         order = np.argsort(slot[slot >= 0])
         rows_by_slot = row[slot >= 0][order]
         assert np.all(np.diff(rows_by_slot) >= 0) or len(np.unique(rows_by_slot)) == (np.diff(rows_by_slot) != 0).sum() + 1
+        assert np.all(np.diff(class_off) >= 0) and class_off[0] == 0
         if classes > 1:
-            # every piece of a class-cut row gathers from a single source-id range
-            for r, a, m, sl in zip(row, e0, ne, slot):
-                if sl >= 0 and deg[r - chunk_ptr[c]] >= min_row and m > 0:
-                    cls = col[a:a + m].astype(np.int64) * classes // n
-                    assert cls.min() == cls.max()
-            # workgroup g (tasks 4g .. 4g+3) prefers class g % classes while that class has pieces left
-            k = len(pieces)
-            grp_cls = [int(col[e0[i]]) * classes // n for i in range(0, min(k, 4 * classes * 3), 4)
-                       if deg[row[i] - chunk_ptr[c]] >= min_row]
-            assert grp_cls[:classes] == list(range(classes))[:len(grp_cls)] or k < 4 * classes
+            # class-major sections: section q holds exactly the pieces that gather from source-id range q
+            for q in range(classes):
+                for i in range(class_off[q], class_off[q + 1]):
+                    cls = col[e0[i]:e0[i] + ne[i]].astype(np.int64) * classes // n
+                    assert ne[i] > 0 and cls.min() == cls.max() == q and slot_class[slot[i]] == q
+            tail = slice(class_off[classes], len(row))
+            assert np.all(slot_class[slot[tail][slot[tail] >= 0]] == 255)
+        else:
+            assert class_off[classes] == 0 and np.all(slot_class == 255)
     assert np.all(covered == 1)  # every entry belongs to exactly one task
 
 
