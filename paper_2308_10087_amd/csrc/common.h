@@ -35,11 +35,12 @@ struct SpmmArgs {
   const int32_t *task_slot;
   int64_t n_tasks;
   // XCD-aware serving order.  Tasks [0, tail_task0) are pieces grouped by source-id class (class c at
-  // cls_task0[c], cls_ntasks[c] of them); workgroups are dealt round-robin to the 8 XCDs, and XCD x
-  // (workgroups with index % 8 == x) serves class xcd_cls[x], taking the groups of four tasks
-  // xcd_first[x], xcd_first[x] + xcd_stride[x], ...  Workgroups from n_class_blocks on serve the tail.
+  // cls_task0[c], cls_ntasks[c] of them).  Workgroups are dealt round-robin to the 8 XCDs; XCD x
+  // (workgroups with index % 8 == x) serves up to 8 segments, segment s being the groups of four tasks
+  // seg_g0[x][s] .. seg_g0[x][s] + seg_cnt[x][s] - 1 of class seg_cls[x][s].  Workgroups from
+  // n_class_blocks on serve the tail.
   int32_t cls_task0[8], cls_ntasks[8];
-  int32_t xcd_cls[8], xcd_first[8], xcd_stride[8];
+  int32_t seg_cls[8][8], seg_g0[8][8], seg_cnt[8][8];
   int32_t n_class_blocks;
   int64_t tail_task0;
   const uint8_t *slot_class;  // class of every partial slot (255: none); pieces of inactive classes are not run
@@ -72,11 +73,19 @@ struct SpmmArgs {
 // which task the wave `wave` of workgroup `b` runs (-1: none)
 __device__ inline int64_t spmm_task_index(const SpmmArgs &a, unsigned b, int wave) {
   if (b < (unsigned)a.n_class_blocks) {
-    const int x = b & 7, j = b >> 3;
-    const int cls = a.xcd_cls[x];
-    if (cls < 0) return -1;
-    const int64_t t = ((int64_t)j * a.xcd_stride[x] + a.xcd_first[x]) * 4 + wave;
-    return t < a.cls_ntasks[cls] ? a.cls_task0[cls] + t : -1;
+    const int x = b & 7;
+    int j = b >> 3;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const int cnt = a.seg_cnt[x][s];
+      if (j < cnt) {
+        const int cls = a.seg_cls[x][s];
+        const int64_t t = ((int64_t)a.seg_g0[x][s] + j) * 4 + wave;
+        return t < a.cls_ntasks[cls] ? a.cls_task0[cls] + t : -1;
+      }
+      j -= cnt;
+    }
+    return -1;
   }
   const int64_t t = a.tail_task0 + (int64_t)(b - a.n_class_blocks) * 4 + wave;
   return t < a.n_tasks ? t : -1;

@@ -9,6 +9,8 @@
 // Bt and B always live in the library's zero-padded internal buffers (16-byte aligned rows);
 // A may also be a caller-owned level buffer of any width and of fp32 or bf16 type, in which case
 // it is read element-wise with bounds checks and converted while it is staged into LDS.
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace {
@@ -529,6 +531,48 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T *B, int ldb, int M,
   if (ty == 0 && o < O) partial[(size_t)blockIdx.y * O + o] = (red[0][tx] + red[1][tx]) + (red[2][tx] + red[3][tx]);
 }
 
+// Same sums with 16-byte loads of 8 bf16 columns: 32 column vectors x 8 row phases per block, two rows
+// in flight per thread.  Needs ldb % 8 == 0 and a 16-byte aligned base (the library's padded buffers).
+__global__ __launch_bounds__(256) void colsum_bf16_vec_kernel(const bf16_t *B, int ldb, int M, int O, int rows_per_split,
+                                                              float *partial) {
+  __shared__ float red[8][32][8];
+  const int cv = threadIdx.x & 31, ph = threadIdx.x >> 5;
+  const int o = (blockIdx.x * 32 + cv) * 8;
+  const int r_begin = blockIdx.y * rows_per_split;
+  const int r_end = min(M, r_begin + rows_per_split);
+  float s[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) s[t] = 0.f;
+  if (o < ldb) {
+    int r = r_begin + ph;
+    for (; r + 8 < r_end; r += 16) {
+      const bf16x8 x0 = *reinterpret_cast<const bf16x8 *>(B + (size_t)r * ldb + o);
+      const bf16x8 x1 = *reinterpret_cast<const bf16x8 *>(B + (size_t)(r + 8) * ldb + o);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) s[t] += (float)x0[t];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) s[t] += (float)x1[t];
+    }
+    for (; r < r_end; r += 8) {
+      const bf16x8 x0 = *reinterpret_cast<const bf16x8 *>(B + (size_t)r * ldb + o);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) s[t] += (float)x0[t];
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < 8; ++t) red[ph][cv][t] = s[t];
+  __syncthreads();
+  if (ph == 0 && o < ldb) {
+#pragma unroll
+    for (int p = 1; p < 8; ++p)
+#pragma unroll
+      for (int t = 0; t < 8; ++t) s[t] += red[p][cv][t];
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+      if (o + t < O) partial[(size_t)blockIdx.y * O + o + t] = s[t];
+  }
+}
+
 bool vec_ok(const void *p, int ld, int mult) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0 && ld % mult == 0; }
 
 }  // namespace
@@ -611,7 +655,10 @@ int launch_colsum_add(const void *B, int dtype, int ldb, int M, int O, float *pa
   const int rows_per = (M + splits - 1) / splits;
   splits = (M + rows_per - 1) / rows_per;
   dim3 grid((O + 63) / 64, splits);
-  if (dtype == DT_BF16)
+  if (dtype == DT_BF16 && vec_ok(B, ldb, 8))
+    hipLaunchKernelGGL(colsum_bf16_vec_kernel, dim3((ldb / 8 + 31) / 32, splits), dim3(256), 0, s,
+                       static_cast<const bf16_t *>(B), ldb, M, O, rows_per, partial);
+  else if (dtype == DT_BF16)
     hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(B), ldb, M, O, rows_per, partial);
   else
     hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(B), ldb, M, O, rows_per, partial);

@@ -399,54 +399,48 @@ void mask_set(ChunkMask &m, int c) { m.w[c >> 6] |= 1ull << (c & 63); }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // XCD assignment of the class sections for one launch.  `drop` = the launch skips unselected entries:
-// a class none of whose chunks is in the mask has no work and is not served at all; the 8 XCDs are shared
-// out among the remaining classes in proportion to their (estimated) work, every class at least one.
+// a class none of whose chunks is in the mask has no work and is not served at all.  The groups of the
+// active classes are dealt to the 8 XCDs like water into buckets: equal shares, a class being split
+// between neighbouring XCDs where a share boundary falls inside it.
 void assign_xcds(const gnnstage *st, const TaskList &t, const ChunkMask &mask, bool drop, SpmmArgs &a) {
   a.tail_task0 = t.cls_off[8];
   a.slot_class = t.slot_class;
   a.active_classes = 0;
   a.n_class_blocks = 0;
-  double w[8];
-  int share[8], n_active = 0;
+  int groups[8];
+  int64_t total = 0;
   for (int q = 0; q < 8; ++q) {
     a.cls_task0[q] = (int32_t)t.cls_off[q];
     a.cls_ntasks[q] = (int32_t)(t.cls_off[q + 1] - t.cls_off[q]);
-    a.xcd_cls[q] = -1;
-    a.xcd_first[q] = 0;
-    a.xcd_stride[q] = 1;
-    int tot = 0, on = 0;
-    for (int c = 0; c < st->s.K; ++c)
-      if (mask_test(st->cls_chunks[q], c)) {
-        ++tot;
-        on += mask_test(mask, c) ? 1 : 0;
-      }
-    const double frac = drop ? (tot ? (double)on / tot : 0.0) : 1.0;
-    w[q] = a.cls_ntasks[q] * frac;
-    share[q] = 0;
-    if (a.cls_ntasks[q] > 0 && frac > 0.0) {
-      a.active_classes |= 1u << q;
-      share[q] = 1;
-      ++n_active;
-    }
+    for (int sgm = 0; sgm < 8; ++sgm) a.seg_cls[q][sgm] = a.seg_g0[q][sgm] = a.seg_cnt[q][sgm] = 0;
+    bool on = !drop;
+    for (int c = 0; c < st->s.K && !on; ++c) on = mask_test(st->cls_chunks[q], c) && mask_test(mask, c);
+    groups[q] = (on && a.cls_ntasks[q] > 0) ? (a.cls_ntasks[q] + 3) / 4 : 0;
+    if (groups[q] > 0) a.active_classes |= 1u << q;
+    total += groups[q];
   }
-  if (n_active == 0) return;
-  for (int left = 8 - n_active; left > 0; --left) {
-    int best = -1;
-    for (int q = 0; q < 8; ++q)
-      if (share[q] > 0 && (best < 0 || w[q] / share[q] > w[best] / share[best])) best = q;
-    share[best] += 1;
-  }
-  int x = 0, max_rounds = 0;
+  if (total == 0) return;
+  const int quota = (int)((total + 7) / 8);
+  int x = 0, used = 0, nseg = 0, most = 0;
   for (int q = 0; q < 8; ++q) {
-    const int groups = (a.cls_ntasks[q] + 3) / 4;
-    for (int i = 0; i < share[q]; ++i, ++x) {
-      a.xcd_cls[x] = q;
-      a.xcd_first[x] = i;
-      a.xcd_stride[x] = share[q];
-      max_rounds = std::max(max_rounds, (groups - i + share[q] - 1) / share[q]);
+    int g = 0;
+    while (g < groups[q]) {
+      if (used == quota) {
+        ++x;
+        used = 0;
+        nseg = 0;
+      }
+      const int take = std::min(groups[q] - g, quota - used);
+      a.seg_cls[x][nseg] = q;
+      a.seg_g0[x][nseg] = g;
+      a.seg_cnt[x][nseg] = take;
+      ++nseg;  // at most 8 classes => at most 8 segments per XCD
+      g += take;
+      used += take;
+      most = std::max(most, used);
     }
   }
-  a.n_class_blocks = 8 * max_rounds;
+  a.n_class_blocks = 8 * most;
 }
 
 SpmmArgs base_spmm(const gnnstage *st, bool transposed, int chunk) {
