@@ -11,6 +11,8 @@ struct ChunkMask {
   uint64_t w[4];
 };
 constexpr int kMaxChunks = 256;
+constexpr int kMaxClasses = 32;  // source-id classes of the aggregation schedule (a 32-bit activity mask)
+constexpr int kMaxSegs = 12;     // class segments one XCD may serve in a launch
 
 __host__ __device__ inline bool mask_test(const ChunkMask &m, uint32_t c) {
   return (m.w[(c >> 6) & 3] >> (c & 63)) & 1ull;
@@ -36,15 +38,16 @@ struct SpmmArgs {
   int64_t n_tasks;
   // XCD-aware serving order.  Tasks [0, tail_task0) are pieces grouped by source-id class (class c at
   // cls_task0[c], cls_ntasks[c] of them).  Workgroups are dealt round-robin to the 8 XCDs; XCD x
-  // (workgroups with index % 8 == x) serves up to 8 segments, segment s being the groups of four tasks
+  // (workgroups with index % 8 == x) serves up to kMaxSegs segments, segment s being the groups of four tasks
   // seg_g0[x][s] .. seg_g0[x][s] + seg_cnt[x][s] - 1 of class seg_cls[x][s].  Workgroups from
   // n_class_blocks on serve the tail.
-  int32_t cls_task0[8], cls_ntasks[8];
-  int32_t seg_cls[8][8], seg_g0[8][8], seg_cnt[8][8];
+  int32_t cls_task0[kMaxClasses], cls_ntasks[kMaxClasses];
+  int32_t seg_cls[8][kMaxSegs], seg_g0[8][kMaxSegs], seg_cnt[8][kMaxSegs];
   int32_t n_class_blocks;
   int64_t tail_task0;
   const uint8_t *slot_class;  // class of every partial slot (255: none); pieces of inactive classes are not run
   uint32_t active_classes;
+  int32_t all_classes_active;
   // long rows: pieces summed by the reduce kernel
   const int32_t *lr_row;
   const int32_t *lr_slot0;
@@ -76,7 +79,7 @@ __device__ inline int64_t spmm_task_index(const SpmmArgs &a, unsigned b, int wav
     const int x = b & 7;
     int j = b >> 3;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
+    for (int s = 0; s < kMaxSegs; ++s) {
       const int cnt = a.seg_cnt[x][s];
       if (j < cnt) {
         const int cls = a.seg_cls[x][s];

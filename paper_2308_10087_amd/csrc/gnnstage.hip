@@ -41,8 +41,10 @@ int split_edges_for(int64_t entries) {
 // GNNSTAGE_XCD_CLASSES=1 switches them off, =8 forces them on.
 int xcd_classes_setting(int64_t table_bytes) {
   const char *e = getenv("GNNSTAGE_XCD_CLASSES");
-  if (e && atoi(e) == 1) return 1;
-  if (e && atoi(e) == 8) return 8;
+  if (e) {
+    const int v = atoi(e);
+    if (v >= 1 && v <= kMaxClasses) return v;
+  }
   return table_bytes <= (int64_t)256 << 20 ? 8 : 1;
 }
 
@@ -63,7 +65,8 @@ struct TaskList {
   int32_t *task_slot = nullptr;
   int32_t *lr_row = nullptr, *lr_slot0 = nullptr, *lr_nslots = nullptr;
   // class sections of the task list (class c = tasks [cls_off[c], cls_off[c+1]); tail from cls_off[8])
-  int64_t cls_off[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+  int n_classes = 0;                      // 0: no class sections
+  int64_t cls_off[kMaxClasses + 1] = {};  // tail starts at cls_off[n_classes]
   uint8_t *slot_class = nullptr;
 };
 
@@ -344,7 +347,8 @@ struct gnnstage {
   std::vector<uint32_t> h_pcol;
   // schedules
   std::vector<TaskList> ftasks, btasks;
-  ChunkMask cls_chunks[8] = {};  // chunks that overlap the id range of each source class
+  int n_classes = 1;
+  ChunkMask cls_chunks[kMaxClasses] = {};  // chunks that overlap the id range of each source class
   // pass state (Section 3.3: V_processed, and its backward twin)
   std::vector<int32_t> order;
   ChunkMask fmask{}, bmask{};
@@ -403,41 +407,69 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // active classes are dealt to the 8 XCDs like water into buckets: equal shares, a class being split
 // between neighbouring XCDs where a share boundary falls inside it.
 void assign_xcds(const gnnstage *st, const TaskList &t, const ChunkMask &mask, bool drop, SpmmArgs &a) {
-  a.tail_task0 = t.cls_off[8];
+  const int C = t.n_classes;
+  a.tail_task0 = t.cls_off[C];
   a.slot_class = t.slot_class;
   a.active_classes = 0;
+  a.all_classes_active = 1;
   a.n_class_blocks = 0;
-  int groups[8];
+  int groups[kMaxClasses];
   int64_t total = 0;
-  for (int q = 0; q < 8; ++q) {
+  for (int x = 0; x < 8; ++x)
+    for (int sgm = 0; sgm < kMaxSegs; ++sgm) a.seg_cls[x][sgm] = a.seg_g0[x][sgm] = a.seg_cnt[x][sgm] = 0;
+  for (int q = 0; q < kMaxClasses; ++q) {
+    a.cls_task0[q] = a.cls_ntasks[q] = 0;
+    groups[q] = 0;
+    if (q >= C) continue;
     a.cls_task0[q] = (int32_t)t.cls_off[q];
     a.cls_ntasks[q] = (int32_t)(t.cls_off[q + 1] - t.cls_off[q]);
-    for (int sgm = 0; sgm < 8; ++sgm) a.seg_cls[q][sgm] = a.seg_g0[q][sgm] = a.seg_cnt[q][sgm] = 0;
     bool on = !drop;
     for (int c = 0; c < st->s.K && !on; ++c) on = mask_test(st->cls_chunks[q], c) && mask_test(mask, c);
+    if (!on) a.all_classes_active = 0;
     groups[q] = (on && a.cls_ntasks[q] > 0) ? (a.cls_ntasks[q] + 3) / 4 : 0;
-    if (groups[q] > 0) a.active_classes |= 1u << q;
+    if (on) a.active_classes |= 1u << q;
     total += groups[q];
   }
   if (total == 0) return;
   const int quota = (int)((total + 7) / 8);
   int x = 0, used = 0, nseg = 0, most = 0;
-  for (int q = 0; q < 8; ++q) {
+  bool fits = true;
+  for (int q = 0; q < C && fits; ++q) {
     int g = 0;
     while (g < groups[q]) {
-      if (used == quota) {
+      if (x < 7 && (used == quota || nseg == kMaxSegs)) {
         ++x;
         used = 0;
         nseg = 0;
       }
-      const int take = std::min(groups[q] - g, quota - used);
+      if (nseg == kMaxSegs) {  // many tiny classes left for the last XCD
+        fits = false;
+        break;
+      }
+      const int take = x < 7 ? std::min(groups[q] - g, quota - used) : groups[q] - g;
       a.seg_cls[x][nseg] = q;
       a.seg_g0[x][nseg] = g;
       a.seg_cnt[x][nseg] = take;
-      ++nseg;  // at most 8 classes => at most 8 segments per XCD
+      ++nseg;
       g += take;
       used += take;
       most = std::max(most, used);
+    }
+  }
+  if (!fits) {  // fallback that always fits: class q goes whole to XCD q % 8 (at most 4 segments each)
+    most = 0;
+    int cnt[8] = {0, 0, 0, 0, 0, 0, 0, 0}, load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int xx = 0; xx < 8; ++xx)
+      for (int sgm = 0; sgm < kMaxSegs; ++sgm) a.seg_cls[xx][sgm] = a.seg_g0[xx][sgm] = a.seg_cnt[xx][sgm] = 0;
+    for (int q = 0; q < C; ++q) {
+      if (groups[q] == 0) continue;
+      const int xx = q & 7;
+      a.seg_cls[xx][cnt[xx]] = q;
+      a.seg_g0[xx][cnt[xx]] = 0;
+      a.seg_cnt[xx][cnt[xx]] = groups[q];
+      ++cnt[xx];
+      load[xx] += groups[q];
+      most = std::max(most, load[xx]);
     }
   }
   a.n_class_blocks = 8 * most;
@@ -613,9 +645,11 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
   st->grad_h0 = d->grad_h0;
   st->ws = static_cast<char *>(d->workspace);
   st->prof.init(s.L);
-  for (int q = 0; q < 8; ++q)
+  st->n_classes = s.classes();
+  for (int q = 0; q < st->n_classes; ++q)
     for (int c = 0; c < s.K; ++c) {
-      const int64_t lo = (q * s.n + 7) / 8, hi = ((q + 1) * s.n + 7) / 8;  // ids u with u * 8 / n == q
+      const int64_t C = st->n_classes;
+      const int64_t lo = (q * s.n + C - 1) / C, hi = ((q + 1) * s.n + C - 1) / C;  // ids u with u * C / n == q
       if (s.chunk_ptr[c] < hi && s.chunk_ptr[c + 1] > lo) mask_set(st->cls_chunks[q], c);
     }
   st->h_row_ptr.assign(d->row_ptr, d->row_ptr + s.n + 1);
@@ -651,11 +685,8 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
                                               min_row, cap, row.data(), e0.data(), ne.data(), slot.data(), &ns,
                                               coff.data(), sclass.data());
       if (got < 0 || got > cap || ns > pc.slots[c]) return GNNSTAGE_EINVAL;
-      if (classes == 8) {
-        for (int q = 0; q <= 8; ++q) tl.cls_off[q] = coff[q];
-      } else {  // no class sections: everything is tail
-        for (int q = 0; q <= 8; ++q) tl.cls_off[q] = 0;
-      }
+      tl.n_classes = classes > 1 ? classes : 0;
+      for (int q = 0; q <= tl.n_classes; ++q) tl.cls_off[q] = coff[q];
       if (ns > 0 && hipMemcpy(tl.slot_class, sclass.data(), (size_t)ns, hipMemcpyHostToDevice) != hipSuccess)
         return GNNSTAGE_EHIP;
       tl.n_tasks = got;

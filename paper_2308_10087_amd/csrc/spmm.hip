@@ -174,7 +174,7 @@ __global__ __launch_bounds__(256) void spmm_reduce_kernel(const SpmmArgs a) {
   const int64_t row = a.lr_row[i];
   const int slot0 = a.lr_slot0[i], ns = a.lr_nslots[i];
   // pieces of classes that were not run in this launch (all their entries unselected) hold stale data
-  const bool check = a.slot_class != nullptr && a.active_classes != 0xffu;
+  const bool check = a.slot_class != nullptr && a.all_classes_active == 0;
   for (int c0 = 0; c0 < a.d; c0 += 32 * VEC) {
     const int c = c0 + cv * VEC;
     float acc[VEC];
@@ -221,7 +221,7 @@ typedef bf16_t bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-template <typename Tout, int NT>
+template <typename Tout, int NT, int U>
 __global__ __launch_bounds__(256) void spmm_mfma_kernel(const SpmmArgs a) {
   constexpr int TILE_W = NT * 128;
   __shared__ float rowbuf[4][TILE_W];
@@ -286,29 +286,26 @@ __global__ __launch_bounds__(256) void spmm_mfma_kernel(const SpmmArgs a) {
       w = __int_as_float(__builtin_amdgcn_ds_permute(dest << 2, __float_as_int(w)));
       n = __builtin_amdgcn_readfirstlane(nk);
     }
-    // 16 entries per step: all gathers of the step are issued before the first product needs its data
-    for (int i = 0; i < n; i += 16) {
-      bf16x8_t x[4][NT];
-      bf16x8_t bfrag[4];
+    // U*4 entries per step: all gathers of the step are issued before the first product needs its data.
+    // What bounds this kernel is the number of bytes in flight per compute unit, i.e. the share of the
+    // register file that holds gathered rows: a step keeps U*NT 16-byte pieces per lane pending, and the
+    // weight operand is kept as one packed word per neighbour and expanded only when it is multiplied.
+    for (int i = 0; i < n; i += 4 * U) {
+      bf16x8_t x[U][NT];
+      uint32_t wbits[U];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < U; ++u) {
         if (i + 4 * u < n) {  // wave-uniform
           const int idx = i + 4 * u + g;
           const int from = idx < n ? idx : i;  // past the end: a valid row with weight 0
           const uint32_t inf = (uint32_t)__shfl((int)info, from);
           float ww = __shfl(w, from);
           if (idx >= n) ww = 0.f;
-          // split the fp32 weight into two bf16 halves and place this lane's half at element `pos`
+          // split the fp32 weight into two bf16 halves; this lane's half goes to element `pos` of B
           const bf16_t whi = (bf16_t)ww;
           const bf16_t wlo = (bf16_t)(ww - (float)whi);
           const bf16_t part = lo_part ? wlo : whi;
-          const uint32_t bits = (uint32_t)__builtin_bit_cast(uint16_t, part) << ((pos & 1) * 16);
-          u32x4_t bw;
-          bw[0] = (pos >> 1) == 0 ? bits : 0u;
-          bw[1] = (pos >> 1) == 1 ? bits : 0u;
-          bw[2] = (pos >> 1) == 2 ? bits : 0u;
-          bw[3] = (pos >> 1) == 3 ? bits : 0u;
-          bfrag[u] = __builtin_bit_cast(bf16x8_t, bw);
+          wbits[u] = (uint32_t)__builtin_bit_cast(uint16_t, part) << ((pos & 1) * 16);
           const bf16_t *rowp = ((inf >> 31) ? src_sel : src_unsel) + (size_t)(inf & 0x7fffffffu) * ld + tile0 + lig * 8;
 #pragma unroll
           for (int h = 0; h < NT; ++h)
@@ -316,10 +313,16 @@ __global__ __launch_bounds__(256) void spmm_mfma_kernel(const SpmmArgs a) {
         }
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < U; ++u) {
         if (i + 4 * u < n) {
+          u32x4_t bw;
+          bw[0] = (pos >> 1) == 0 ? wbits[u] : 0u;
+          bw[1] = (pos >> 1) == 1 ? wbits[u] : 0u;
+          bw[2] = (pos >> 1) == 2 ? wbits[u] : 0u;
+          bw[3] = (pos >> 1) == 3 ? wbits[u] : 0u;
+          const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, bw);
 #pragma unroll
-          for (int h = 0; h < NT; ++h) acc[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[u][h], bfrag[u], acc[h], 0, 0, 0);
+          for (int h = 0; h < NT; ++h) acc[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[u][h], bfrag, acc[h], 0, 0, 0);
         }
       }
     }
@@ -433,12 +436,22 @@ template <typename Tout>
 static int launch_mfma(const SpmmArgs &a, hipStream_t s) {
   const unsigned gx = (unsigned)(a.n_class_blocks + (a.n_tasks - a.tail_task0 + 3) / 4);
   if (gx == 0) return hipSuccess;  // only class pieces, none of them active
-  if (a.d <= 128)
-    hipLaunchKernelGGL((spmm_mfma_kernel<Tout, 1>), dim3(gx, 1), dim3(256), 0, s, a);
-  else if (a.d <= 256)
-    hipLaunchKernelGGL((spmm_mfma_kernel<Tout, 2>), dim3(gx, 1), dim3(256), 0, s, a);
-  else
-    hipLaunchKernelGGL((spmm_mfma_kernel<Tout, 4>), dim3(gx, (unsigned)((a.d + 511) / 512)), dim3(256), 0, s, a);
+  static const int unroll = getenv("GNNSTAGE_SPMM_UNROLL") ? atoi(getenv("GNNSTAGE_SPMM_UNROLL")) : 4;
+  if (a.d <= 128) {
+    if (unroll >= 8)
+      hipLaunchKernelGGL((spmm_mfma_kernel<Tout, 1, 8>), dim3(gx, 1), dim3(256), 0, s, a);
+    else if (unroll >= 4)
+      hipLaunchKernelGGL((spmm_mfma_kernel<Tout, 1, 4>), dim3(gx, 1), dim3(256), 0, s, a);
+    else
+      hipLaunchKernelGGL((spmm_mfma_kernel<Tout, 1, 2>), dim3(gx, 1), dim3(256), 0, s, a);
+  } else if (a.d <= 256) {
+    if (unroll >= 4)
+      hipLaunchKernelGGL((spmm_mfma_kernel<Tout, 2, 4>), dim3(gx, 1), dim3(256), 0, s, a);
+    else
+      hipLaunchKernelGGL((spmm_mfma_kernel<Tout, 2, 2>), dim3(gx, 1), dim3(256), 0, s, a);
+  } else {
+    hipLaunchKernelGGL((spmm_mfma_kernel<Tout, 4, 4>), dim3(gx, (unsigned)((a.d + 511) / 512)), dim3(256), 0, s, a);
+  }
   return (int)hipGetLastError();
 }
 

@@ -153,6 +153,40 @@ def test_bf16_odd_shapes(dims, variant):
     _parity(p, TOL_BF16)
 
 
+@pytest.mark.parametrize("classes,min_row,split", [(8, 4, 64), (32, 16, 128), (5, 2, 4096), (1, 1, 64)])
+@pytest.mark.parametrize("name", ["c2_s", "c3_s"])
+def test_source_class_schedules(monkeypatch, classes, min_row, split, name):
+    """The aggregation schedule cuts rows by source-id class and deals the classes to the XCDs at launch
+    time (classes whose chunks are all unprocessed are skipped in the backward).  Force many classes,
+    tiny rows into the class path and small pieces, with ragged chunks that straddle class boundaries."""
+    monkeypatch.setenv("GNNSTAGE_XCD_CLASSES", str(classes))
+    monkeypatch.setenv("GNNSTAGE_CLASS_MIN_ROW", str(min_row))
+    monkeypatch.setenv("GNNSTAGE_SPLIT_EDGES", str(split))
+    w = CONFIGS[name]
+    row_ptr, col = __import__("synth").make_graph(w)
+    n = len(row_ptr) - 1
+    p = make_problem(w, graph=(row_ptr, col), chunk_ptr=graphs.ragged_chunks(n, w.n_chunks, 17), bias_std=0.05)
+    _parity(p, TOL_BF16)
+
+
+def test_source_class_schedule_fp32_probe(monkeypatch):
+    """Exact-integer check of the class path: unit weights, ones, W = I (see the indicator probes below)."""
+    monkeypatch.setenv("GNNSTAGE_XCD_CLASSES", "8")
+    monkeypatch.setenv("GNNSTAGE_CLASS_MIN_ROW", "4")
+    monkeypatch.setenv("GNNSTAGE_SPLIT_EDGES", "64")
+    w = small(n=1200, k=6, dims=(8, 8), deg=10.0, seed=33)
+    p = make_problem(w, chunk_ptr=graphs.ragged_chunks(1200, 6, 5), bias_std=0.0)
+    p.val = np.ones_like(p.val)
+    p.W = [np.eye(8, dtype=np.float32)]
+    p.x0 = np.ones_like(p.x0)
+    p.hist = [np.zeros_like(p.hist[0])]
+    p.grad_out = np.ones_like(p.grad_out)
+    ref = run_oracle(p)
+    run = _gpu(p).run()
+    assert np.array_equal(run.np(run.cur[1]), ref.cur[1])
+    assert np.array_equal(run.np(run.grad_in), ref.grad_in)
+
+
 @pytest.mark.parametrize("order_mode", ["aggregate", "transform"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_both_layer_orders(monkeypatch, order_mode, dtype):
