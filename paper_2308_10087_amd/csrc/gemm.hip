@@ -289,6 +289,139 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmNtArgs a) {
     }
 }
 
+// ------------------------------------------------------------- bf16 NT, weight-stationary and persistent
+// For the widths of this stage (K, N <= 256) the product streams A in and C out and is HBM-bound; what
+// decides its speed is how many bytes of A are in flight, not arithmetic.  Each wave keeps its 64-column
+// panel of Bt in registers for the whole kernel (as ready-made MFMA fragments), workgroups are persistent
+// and walk over row tiles, and the loads of the next A tile are in flight while the current one is
+// multiplied and stored.  WN = column panels per workgroup (4: N <= 256 with 64-row tiles, 2: N <= 128
+// with 128-row tiles); KS = number of 16-wide k-steps held (Kp <= 16 * KS).
+template <int WN, int KS>
+__global__ __launch_bounds__(256, 2) void gemm_nt_bf16_ws_kernel(const GemmNtArgs a) {
+  constexpr int WR = 4 / WN, TM = 64 * WR;  // row groups, rows per tile
+  constexpr int LDK = KS * 16 + 8;          // LDS row stride (elements): conflict-free 16-byte fragment reads
+  constexpr int NV = TM * (KS * 2) / 256;   // 16-byte vectors of an A tile per thread
+  constexpr int PS = 36;                    // padded row stride (floats) of a 16x32 staging patch
+  extern __shared__ __attribute__((aligned(16))) unsigned char ws_smem[];
+  bf16_t *As = reinterpret_cast<bf16_t *>(ws_smem);                                 // [2][TM * LDK]
+  float *patches = reinterpret_cast<float *>(ws_smem + (size_t)2 * TM * LDK * 2);  // [4][16 * PS]
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int rg = wave / WN, cp = wave % WN;
+  const bf16_t *A = static_cast<const bf16_t *>(a.A);
+  const bf16_t *Bt = static_cast<const bf16_t *>(a.Bt);
+  const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  const int kl = (lane >> 5) * 8;
+  const int n_wave = cp * 64;
+
+  // this wave's panel of Bt as MFMA B fragments: [k-step][column sub-tile]
+  bf16x8 bfr[KS][2];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int n = n_wave + j * 32 + (lane & 31), k = ks * 16 + kl;
+      bfr[ks][j] = (n < a.N && k < a.Kp) ? *reinterpret_cast<const bf16x8 *>(Bt + (size_t)n * a.ldb + k) : zero8;
+    }
+
+  const int n_tiles = (a.M + TM - 1) / TM;
+  bf16x8 stage[NV];
+  auto gload = [&](int tile) {
+    const int m0 = tile * TM;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int vid = tid + 256 * i, r = vid / (KS * 2), k = (vid % (KS * 2)) * 8;
+      stage[i] = (m0 + r < a.M && k < a.Kp) ? *reinterpret_cast<const bf16x8 *>(A + (size_t)(m0 + r) * a.lda + k) : zero8;
+    }
+  };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int vid = tid + 256 * i, r = vid / (KS * 2), k = (vid % (KS * 2)) * 8;
+      *reinterpret_cast<bf16x8 *>(&As[buf * TM * LDK + r * LDK + k]) = stage[i];
+    }
+  };
+
+  int tile = blockIdx.x;
+  if (tile >= n_tiles) return;
+  gload(tile);
+  sstore(0);
+  __syncthreads();
+  float *patch = patches + wave * (16 * PS);
+  int buf = 0;
+  for (; tile < n_tiles; tile += gridDim.x, buf ^= 1) {
+    const int next = tile + gridDim.x;
+    if (next < n_tiles) gload(next);  // in flight during the products and the stores below
+    const bf16_t *At = As + buf * TM * LDK + (rg * 64) * LDK;
+    const int m_wave = tile * TM + rg * 64;
+    // the wave's 64x64 block, one 32x32 sub-tile at a time (few accumulator registers: the Bt panel
+    // already takes KS*8), each written out through the wave's private LDS patch in two 16-row halves
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        f32x16 acc;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) acc[t] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const bf16x8 fa = *reinterpret_cast<const bf16x8 *>(&At[(i * 32 + (lane & 31)) * LDK + ks * 16 + kl]);
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, bfr[ks][j], acc, 0, 0, 0);
+        }
+        const int mt = m_wave + i * 32, ntc = n_wave + j * 32;
+        if (mt >= a.M || ntc >= (a.out_pad > a.N ? a.out_pad : a.N)) continue;  // wave-uniform
+        if (a.vec_epi) {
+#pragma unroll
+          for (int hf = 0; hf < 2; ++hf) {  // accumulator elements 8*hf .. 8*hf+7 are rows 16*hf .. 16*hf+15
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+              patch[(8 * (t >> 2) + 4 * (lane >> 5) + (t & 3)) * PS + (lane & 31)] = acc[8 * hf + t];
+            __builtin_amdgcn_wave_barrier();
+            const int r = lane >> 2, c = (lane & 3) * 8;
+            float v[8];
+            const f32x4 v0 = *reinterpret_cast<const f32x4 *>(&patch[r * PS + c]);
+            const f32x4 v1 = *reinterpret_cast<const f32x4 *>(&patch[r * PS + c + 4]);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+              v[t] = v0[t];
+              v[4 + t] = v1[t];
+            }
+            if (mt + 16 * hf + r < a.M && ntc + c < a.N) epilogue_store8(a, mt + 16 * hf + r, ntc + c, v);
+            __builtin_amdgcn_wave_barrier();
+          }
+        } else {
+#pragma unroll
+          for (int t = 0; t < 16; ++t) {
+            const int m = mt + 8 * (t >> 2) + 4 * (lane >> 5) + (t & 3);
+            const int n = ntc + (lane & 31);
+            if (m < a.M && n < a.N)
+              epilogue_store(a, m, n, acc[t]);
+            else if (m < a.M && n < a.out_pad)
+              store_f32(a.out, a.out_dtype, (size_t)m * a.out_ld + n, 0.f);
+          }
+        }
+      }
+    __syncthreads();  // every wave is done reading this A tile
+    if (next < n_tiles) sstore(buf ^ 1);
+    __syncthreads();
+  }
+}
+
+template <int WN, int KS>
+static int launch_ws(const GemmNtArgs &a, hipStream_t s) {
+  constexpr int TM = 64 * (4 / WN), LDK = KS * 16 + 8;
+  const size_t smem = (size_t)2 * TM * LDK * sizeof(bf16_t) + (size_t)4 * 16 * 36 * sizeof(float);
+  static bool attr_done = false;
+  if (!attr_done) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_nt_bf16_ws_kernel<WN, KS>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    attr_done = true;
+  }
+  const int n_tiles = (a.M + TM - 1) / TM;
+  const int blocks = n_tiles < 512 ? n_tiles : 512;  // two persistent workgroups per compute unit
+  hipLaunchKernelGGL((gemm_nt_bf16_ws_kernel<WN, KS>), dim3(blocks), dim3(256), smem, s, a);
+  return (int)hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------ bf16 TN
 constexpr int TR = 32;      // reduction rows per step
 constexpr int LDS_C = 136;  // padded column stride of the row-major LDS tiles
@@ -593,7 +726,15 @@ int launch_gemm_nt(const GemmNtArgs &a_in, int compute_dtype, hipStream_t s) {
     const bool vec = a.a_dtype == DT_BF16 && vec_ok(a.A, a.lda, 8) && a.lda >= a.Kp;
     if (a.a_dtype == DT_F32)
       hipLaunchKernelGGL((gemm_nt_bf16_kernel<float, false>), grid, dim3(256), 0, s, a);
-    else if (vec)
+    else if (vec && vec_ok(a.Bt, a.ldb, 8) && a.Kp <= 256 && a.N <= 256 && a.M >= 65536 &&
+             !getenv("GNNSTAGE_GEMM_TILED")) {
+      // long operands: persistent weight-stationary kernel (needs a few row tiles per workgroup to pay
+      // for loading its panel of Bt into registers)
+      if (a.N <= 128 && a.Kp <= 128) return launch_ws<2, 8>(a, s);
+      if (a.N <= 128) return launch_ws<2, 16>(a, s);
+      if (a.Kp <= 128) return launch_ws<4, 8>(a, s);
+      return launch_ws<4, 16>(a, s);
+    } else if (vec)
       hipLaunchKernelGGL((gemm_nt_bf16_kernel<bf16_t, true>), grid, dim3(256), 0, s, a);
     else
       hipLaunchKernelGGL((gemm_nt_bf16_kernel<bf16_t, false>), grid, dim3(256), 0, s, a);
