@@ -169,6 +169,14 @@ def test_source_class_schedules(monkeypatch, classes, min_row, split, name):
     _parity(p, TOL_BF16)
 
 
+@pytest.mark.parametrize("name", ["c1_s", "c2_s", "c3_s", "c4_s"])
+def test_persistent_gemm_on_small_inputs(monkeypatch, name):
+    """The weight-stationary persistent GEMM normally serves only long operands; force it everywhere."""
+    monkeypatch.setenv("GNNSTAGE_GEMM_WS_MIN_ROWS", "1")
+    p = make_problem(CONFIGS[name], bias_std=0.05)
+    _parity(p, TOL_BF16)
+
+
 def test_source_class_schedule_fp32_probe(monkeypatch):
     """Exact-integer check of the class path: unit weights, ones, W = I (see the indicator probes below)."""
     monkeypatch.setenv("GNNSTAGE_XCD_CLASSES", "8")
