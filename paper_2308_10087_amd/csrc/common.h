@@ -149,6 +149,8 @@ struct GemmTnArgs {
   float *dW;       // fp32 [I][O]
   float *partial;  // fp32 scratch [splits][I][O]
   int32_t max_splits;
+  float *dbias;         // optional (bf16 product only): dbias[o] += column sums of B, fused into the product
+  float *bias_partial;  // fp32 scratch [splits][O]
 };
 int launch_gemm_tn(const GemmTnArgs &a, int compute_dtype, hipStream_t s);
 // dst[o] += sum over the M rows of B[.][o]; partial: fp32 scratch [max_splits][O]

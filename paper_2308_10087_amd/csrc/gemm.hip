@@ -429,7 +429,7 @@ static int launch_ws(const GemmNtArgs &a, hipStream_t s) {
 }
 
 // ------------------------------------------------------------------------------------ bf16 TN
-constexpr int TR = 32;      // reduction rows per step
+constexpr int TR = 64;      // reduction rows per step (two 16 KB operand tiles in flight per workgroup)
 constexpr int LDS_C = 136;  // padded column stride of the row-major LDS tiles
 
 template <typename TA, bool VEC>
@@ -459,10 +459,20 @@ __global__ __launch_bounds__(256) void gemm_tn_bf16_kernel(const GemmTnArgs a, i
 #pragma unroll
       for (int t = 0; t < 16; ++t) acc[i][j][t] = 0.f;
 
-  bf16x8 ra[2], rb[2];
+  // bias gradient on the side: a product with an all-ones A fragment leaves the column sums of the B
+  // tile in every row of its result; done by the waves that own the first rows of the first row tile
+  const bool do_bias = a.bias_partial != nullptr && i0 == 0 && wi == 0;
+  const bf16x8 ones8 = {(bf16_t)1.f, (bf16_t)1.f, (bf16_t)1.f, (bf16_t)1.f, (bf16_t)1.f, (bf16_t)1.f, (bf16_t)1.f, (bf16_t)1.f};
+  f32x16 accb[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int t = 0; t < 16; ++t) accb[j][t] = 0.f;
+  constexpr int NVT = TR * 16 / 256;  // 16-byte vectors per thread and operand tile
+  bf16x8 ra[NVT], rb[NVT];
   auto gload = [&](int r0) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < NVT; ++i) {
       const int vid = tid + 256 * i, r = vid >> 4, c = (vid & 15) * 8;
       const bool rv = r0 + r < r_end;
       ra[i] = rv ? load8_bf16<TA, VEC>(A, (size_t)a.lda, r0 + r, i0 + c, a_cols) : zero8;
@@ -473,7 +483,7 @@ __global__ __launch_bounds__(256) void gemm_tn_bf16_kernel(const GemmTnArgs a, i
   for (int r0 = r_begin; r0 < r_end; r0 += TR) {
     __syncthreads();  // previous step's fragment reads are done
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < NVT; ++i) {
       const int vid = tid + 256 * i, r = vid >> 4, c = (vid & 15) * 8;
       *reinterpret_cast<bf16x8 *>(&As[r * LDS_C + c]) = ra[i];
       *reinterpret_cast<bf16x8 *>(&Bs[r * LDS_C + c]) = rb[i];
@@ -497,6 +507,17 @@ __global__ __launch_bounds__(256) void gemm_tn_bf16_kernel(const GemmTnArgs a, i
 #pragma unroll
         for (int j = 0; j < 2; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+      if (do_bias) {  // wave-uniform
+#pragma unroll
+        for (int j = 0; j < 2; ++j) accb[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones8, fb[j], accb[j], 0, 0, 0);
+      }
+    }
+  }
+  if (do_bias && lane < 32) {  // element 0 of lanes 0..31 is row 0 of the result: the column sums
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int oo = o0 + wo + j * 32 + lane;
+      if (oo < a.O) a.bias_partial[(size_t)split * a.O + oo] = accb[j][0];
     }
   }
   float *P = a.partial + (size_t)split * a.I * a.O;
@@ -790,7 +811,15 @@ int launch_gemm_tn(const GemmTnArgs &a, int compute_dtype, hipStream_t s) {
   const size_t count = (size_t)a.I * a.O;
   hipLaunchKernelGGL(reduce_add_kernel, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, s, a.partial, splits, count,
                      a.scale, a.dW);
-  return (int)hipGetLastError();
+  e = hipGetLastError();
+  if (e != hipSuccess) return (int)e;
+  if (a.dbias != nullptr) {
+    if (compute_dtype != DT_BF16) return hipErrorInvalidValue;  // the fp32 stage sums columns separately
+    hipLaunchKernelGGL(reduce_add_kernel, dim3((unsigned)((a.O + 63) / 64)), dim3(256), 0, s, a.bias_partial, splits,
+                       (size_t)a.O, 1.0f, a.dbias);
+    e = hipGetLastError();
+  }
+  return (int)e;
 }
 
 int launch_colsum_add(const void *B, int dtype, int ldb, int M, int O, float *partial, int max_splits, float *dst,

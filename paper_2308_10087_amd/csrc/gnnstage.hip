@@ -924,7 +924,10 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
   // rows of the chunk, [M x ld_{j+1}], zero in the padding columns
   for (int j = s.L - 1; j >= 0; --j) {
     const char *dY = G[gi];
-    if (s.variant == GNNSTAGE_GCN) {
+    // bias gradient = column sums of dY: fused into the weight-gradient product where that product reads dY
+    // (aggregate-first layers of the bf16 stage), a kernel of its own otherwise
+    const bool fuse_bias = s.variant == GNNSTAGE_GCN && !s.tf[j] && cd == DT_BF16;
+    if (s.variant == GNNSTAGE_GCN && !fuse_bias) {
       Timed t(st, stream, 4, j);
       HIP_TRY(st, launch_colsum_add(dY, cd, s.ld[j + 1], (int)M, s.dims[j + 1], bias_partial, kMaxSplits, st->dbias[j], stream));
     }
@@ -1024,6 +1027,10 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
       w.dW = st->dW[j];
       w.partial = gemm_partial;
       w.max_splits = kMaxSplits;
+      if (fuse_bias) {
+        w.dbias = st->dbias[j];
+        w.bias_partial = bias_partial;
+      }
       HIP_TRY(st, launch_gemm_tn(w, cd, stream));
     }
     if (!need_prev) break;
