@@ -5,12 +5,13 @@
 // One wavefront per task.  A task is a whole sparse row, or a piece of a long row (power-law
 // hubs are cut so that no wave owns more than a fixed number of entries; the pieces write
 // fp32 partial sums that a second small kernel adds in a fixed order, so results do not
-// depend on scheduling).  Inside a wave the 64 lanes form G = 64/LPR groups of LPR lanes;
-// each group gathers one neighbour row per step with 16-byte loads (LPR * 16 B covers the
-// row), so a 512-byte bf16 row of width 256 is one half-wave load and two neighbours are in
-// flight per instruction.  Entry metadata (packed index, weight) is loaded 64 entries at a
-// time, one per lane, and broadcast through lane permutes; when unselected entries are
-// dropped they are first compacted inside the wave so that no bandwidth is spent on them.
+// depend on scheduling).  Two kernels share that schedule:
+//  * spmm_kernel, the vector-ALU form for fp32 rows and odd widths: the 64 lanes form G = 64/LPR
+//    groups of LPR lanes, each group gathers one neighbour row per step with 16/8/4-byte loads;
+//    entry metadata (packed index, weight) is loaded 64 entries at a time, one per lane, and
+//    broadcast through lane permutes; dropped entries are first compacted inside the wave.
+//  * spmm_ring_kernel, for bf16 rows whose width is a multiple of 8: entries become address
+//    records in a wave-private LDS ring and the weighted sum runs on the matrix cores.
 #include <stdlib.h>
 
 #include "common.h"
@@ -49,7 +50,10 @@ __device__ inline void finish_cols(const SpmmArgs &a, int64_t row, int c, const 
         static_cast<const Tin *>(a.aux) + (size_t)row * a.aux_ld + c);
     if (a.epilogue == SPMM_MIX) {
 #pragma unroll
-      for (int t = 0; t < VEC; ++t) r[t] = a.s_acc * acc[t] + a.s_aux * to_f32(x.v[t]);
+      // one rounding for the dominant (1 - alpha) term: with rows on the bf16 grid the exact mix often sits
+      // exactly half-way between two bf16 values, and rounding the large product separately would push all
+      // of those ties the same way
+      for (int t = 0; t < VEC; ++t) r[t] = __builtin_fmaf(a.s_acc, acc[t], a.s_aux * to_f32(x.v[t]));
     } else {
 #pragma unroll
       for (int t = 0; t < VEC; ++t) r[t] = to_f32(x.v[t]) > 0.f ? acc[t] : 0.f;
@@ -220,19 +224,34 @@ __global__ __launch_bounds__(256) void spmm_reduce_kernel(const SpmmArgs a) {
 typedef bf16_t bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) bf16x8_t global_bf16x8_t;  // a load through it is a global load
 
-template <typename Tout, int NT, int U>
-__global__ __launch_bounds__(256) void spmm_mfma_kernel(const SpmmArgs a) {
+// Entry metadata is turned, once per entry, into a 16-byte record {row address, packed weight halves}
+// and appended to a wave-private ring in LDS; unselected entries of a backward launch are simply not
+// appended, so the gather loop sees one dense stream of kept entries across the 64-entry metadata
+// batches.  A wave alternates between two phases.  Phase A turns KB batches of metadata (loaded during
+// the previous phase B) into records.  Phase B gathers: it works in steps of four records (one per
+// 16-lane group) and owns U register slots; slot u holds the pieces of step s with s % U == u.  In the
+// steady loop every slot is multiplied into the accumulators and immediately refilled with the loads of
+// step s + U, unconditionally, so the number of younger loads at every wait is a compile-time constant
+// and U - 1 steps of gathers stay in flight while one is consumed.  Per step the vector ALU only adds
+// the lane offset to the record's address and expands the weight (one byte permute, four selects).
+template <typename Tout, int NT, int U, bool FULL>
+__global__ __launch_bounds__(256, (NT * U <= 8) ? 7 : 1) void spmm_ring_kernel(const SpmmArgs a) {
   constexpr int TILE_W = NT * 128;
-  __shared__ float rowbuf[4][TILE_W];
+  constexpr int KB = 2;    // metadata batches per phase
+  constexpr int R = 256;   // ring capacity in records: a phase appends at most 64 * KB, fewer than 8 * U are left over
+  static_assert(TILE_W * sizeof(float) <= R * sizeof(u32x4_t), "the output row reuses the ring's memory");
+  static_assert((U & (U - 1)) == 0 && U <= 8, "slot count");
+  __shared__ u32x4_t ring_all[4][R];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t task = spmm_task_index(a, blockIdx.x, wave);
   if (task < 0) return;  // whole wave leaves together (no block-wide barrier below)
+  u32x4_t *ring = ring_all[wave];
   const int g = lane >> 4, lig = lane & 15;
   const int tile0 = blockIdx.y * TILE_W;
-  // task fields are the same for the whole wave: keep them in scalar registers.  The matrix
-  // instruction ignores the execution mask and the lane permutes need every lane in step, so all
-  // control flow around them must be provably wave-uniform.
+  // Task fields are the same for the whole wave: keep them in scalar registers.  The matrix instruction
+  // ignores the execution mask, so all control flow around it must be provably wave-uniform.
   const int64_t row = __builtin_amdgcn_readfirstlane(a.task_row[task]);
   const int64_t e0_raw = a.task_e0[task];
   const int64_t e0 = ((int64_t)__builtin_amdgcn_readfirstlane((int)(e0_raw >> 32)) << 32) |
@@ -241,102 +260,161 @@ __global__ __launch_bounds__(256) void spmm_mfma_kernel(const SpmmArgs a) {
   const int slot = __builtin_amdgcn_readfirstlane(a.task_slot[task]);
   const uint32_t vmask = (1u << a.vbits) - 1u;
   const bool drop_unsel = a.src_unsel == nullptr;
-  const bf16_t *src_sel = static_cast<const bf16_t *>(a.src_sel);
-  const bf16_t *src_unsel = static_cast<const bf16_t *>(a.src_unsel);
+  const char *base_sel = static_cast<const char *>(a.src_sel) + (size_t)tile0 * 2;
+  const char *base_unsel = drop_unsel ? base_sel : static_cast<const char *>(a.src_unsel) + (size_t)tile0 * 2;
   const int d = a.d;
-  const size_t ld = (size_t)a.src_ld;
-  const int pos = lig & 7;            // which element of the 8-column block this lane's B column picks
-  const bool lo_part = lig >= 8;      // B columns 8..15 carry the low half of the weight
+  const uint32_t row_bytes = (uint32_t)a.src_ld * 2u;
+  const uint32_t lane_off = (uint32_t)lig * 16u;
+  const int pos = lig & 7;        // which element of the 8-column block this lane's B column picks
+  const bool lo_part = lig >= 8;  // B columns 8..15 carry the low half of the weight
+  // byte selector that moves this lane's weight half (bytes 0-1 or 2-3 of the packed word) into the
+  // bf16 element `pos & 1` of a B operand word and zeroes the other element
+  const uint32_t b0 = lo_part ? 2u : 0u;
+  const uint32_t selw = (pos & 1) ? (((b0 + 1u) << 24) | (b0 << 16) | 0x0c0cu) : (0x0c0c0000u | ((b0 + 1u) << 8) | b0);
+  const int wword = pos >> 1;
+  const uint64_t mask0 = a.mask.w[0], mask1 = a.mask.w[1], mask2 = a.mask.w[2], mask3 = a.mask.w[3];
 
   f32x4_t acc[NT];
 #pragma unroll
   for (int h = 0; h < NT; ++h) acc[h] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   const bf16x8_t zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  bf16x8_t x[U][NT];
+  uint32_t wk[U];
+  uint64_t rec_addr = 0;  // record of the next step to issue, read one step ahead
+  uint32_t rec_w = 0;
 
-  // entry metadata of the first batch; later batches are fetched one batch ahead
-  uint32_t pc_next = 0;
-  float w_next = 0.f;
-  if (lane < ne) {
-    pc_next = a.pidx[e0 + lane];
-    w_next = a.val[e0 + lane];
-  }
-  for (int base = 0; base < ne; base += 64) {
-    int n = ne - base < 64 ? ne - base : 64;
-    const uint32_t pc = pc_next;
-    float w = w_next;
-    if (base + 64 + lane < ne) {
-      pc_next = a.pidx[e0 + base + 64 + lane];
-      w_next = a.val[e0 + base + 64 + lane];
+  auto read_record = [&](int step) {
+    const uint32_t *rec = reinterpret_cast<const uint32_t *>(&ring[((step << 2) + g) & (R - 1)]);
+    rec_addr = *reinterpret_cast<const uint64_t *>(rec);
+    rec_w = rec[2];
+  };
+  // gathers of step `step` into slot u; the record was read before, the following one is requested now
+  // (past the last appended record this reads stale ring memory that nobody uses)
+  auto issue = [&](int step, int u) {
+    const global_bf16x8_t *p = reinterpret_cast<const global_bf16x8_t *>(rec_addr + lane_off);
+    wk[u] = rec_w;
+#pragma unroll
+    for (int h = 0; h < NT; ++h) x[u][h] = (FULL || tile0 + h * 128 + lig * 8 < d) ? p[h * 16] : zero8;
+    read_record(step + 1);
+    // keep the slots in program order: the wait in front of a slot's product then only covers that slot's
+    // own loads and leaves the younger gathers in flight
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto consume = [&](int u) {
+    const uint32_t wbits = __builtin_amdgcn_perm(0u, wk[u], selw);
+    u32x4_t bw;
+    bw[0] = wword == 0 ? wbits : 0u;
+    bw[1] = wword == 1 ? wbits : 0u;
+    bw[2] = wword == 2 ? wbits : 0u;
+    bw[3] = wword == 3 ? wbits : 0u;
+    const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, bw);
+#pragma unroll
+    for (int h = 0; h < NT; ++h) acc[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[u][h], bfrag, acc[h], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  const int nb = (ne + 63) >> 6;  // metadata batches
+  int bprod = 0;                  // batches turned into records so far
+  int produced = 0;               // records appended so far
+  int issued = 0;                 // steps whose gathers have been issued (and, between phases, multiplied)
+  uint32_t pad_lo = 0, pad_hi = 0;  // address of some kept row, for the zero-weight records that fill the last step
+
+  uint32_t pcs[KB];
+  float ws[KB];
+  auto prefetch = [&](int b0) {  // clamped index: lanes past the end re-read the last entry and are not kept
+#pragma unroll
+    for (int k = 0; k < KB; ++k) {
+      int i = ((b0 + k) << 6) + lane;
+      i = i < ne ? i : ne - 1;
+      pcs[k] = a.pidx[e0 + i];
+      ws[k] = a.val[e0 + i];
     }
-    uint32_t info = 0;
-    bool keep = false;
-    if (lane < n) {
-      const bool sel = mask_test(a.mask, pc >> a.vbits);
-      keep = sel || !drop_unsel;
-      info = (pc & vmask) | (sel ? 0x80000000u : 0u);
-    } else {
-      w = 0.f;
-    }
-    if (drop_unsel) {
+  };
+  if (ne > 0) prefetch(0);
+  while (bprod < nb) {
+    // ---- phase A: KB batches of metadata become records
+#pragma unroll
+    for (int k = 0; k < KB; ++k) {
+      const int nraw = ne - ((bprod + k) << 6);  // entries left from this batch on (may be <= 0)
+      const uint32_t pc = pcs[k];
+      const float w = ws[k];
+      // the chunk's bit of the processed mask, picked with register selects (no indexed access)
+      const uint32_t ci = pc >> a.vbits;
+      const uint64_t mlo = (ci & 64u) ? mask1 : mask0, mhi = (ci & 64u) ? mask3 : mask2;
+      const bool sel = ((((ci & 128u) ? mhi : mlo) >> (ci & 63u)) & 1ull) != 0;
+      const bool keep = lane < nraw && (sel || !drop_unsel);
+      const uint64_t addr = reinterpret_cast<uint64_t>(sel ? base_sel : base_unsel) + (uint64_t)(pc & vmask) * row_bytes;
+      const bf16_t whi = (bf16_t)w;
+      const bf16_t wlo = (bf16_t)(w - (float)whi);
+      const uint32_t wpk = (uint32_t)__builtin_bit_cast(uint16_t, whi) | ((uint32_t)__builtin_bit_cast(uint16_t, wlo) << 16);
       const uint64_t bal = __ballot(keep);
-      const int nk = __popcll(bal);
-      const int rk = __popcll(bal & ((1ull << lane) - 1ull));
-      const int dest = keep ? rk : nk + (lane - rk);
-      info = (uint32_t)__builtin_amdgcn_ds_permute(dest << 2, (int)info);
-      w = __int_as_float(__builtin_amdgcn_ds_permute(dest << 2, __float_as_int(w)));
-      n = __builtin_amdgcn_readfirstlane(nk);
+      const int nk = __builtin_amdgcn_readfirstlane(__popcll(bal));
+      const int rk = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+      if (keep) ring[(produced + rk) & (R - 1)] = u32x4_t{(uint32_t)addr, (uint32_t)(addr >> 32), wpk, 0u};
+      if (nk > 0) {
+        const int first = __builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)bal) - 1);
+        pad_lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)addr, first);
+        pad_hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(addr >> 32), first);
+      }
+      produced += nk;
     }
-    // U*4 entries per step: all gathers of the step are issued before the first product needs its data.
-    // What bounds this kernel is the number of bytes in flight per compute unit, i.e. the share of the
-    // register file that holds gathered rows: a step keeps U*NT 16-byte pieces per lane pending, and the
-    // weight operand is kept as one packed word per neighbour and expanded only when it is multiplied.
-    for (int i = 0; i < n; i += 4 * U) {
-      bf16x8_t x[U][NT];
-      uint32_t wbits[U];
+    bprod += KB;
+    const bool final = bprod >= nb;
+    if (!final) prefetch(bprod);  // lands while this phase's gathers run
+    if (final) {  // complete the last step with zero-weight records that point at a row of the sum
+      const int padn = (-produced) & 3;
+      if (lane < padn) ring[(produced + lane) & (R - 1)] = u32x4_t{pad_lo, pad_hi, 0u, 0u};
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int avail = final ? (produced + 3) >> 2 : produced >> 2;  // steps that may be issued
+    const int count = avail - issued;
+    if (!final && count < 2 * U) continue;  // too few kept entries for a steady loop: collect more first
+    // ---- phase B: steps issued .. avail - 1
+    read_record(issued);
+    int k = 0;
+    if (count >= 2 * U) {
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        if (i + 4 * u < n) {  // wave-uniform
-          const int idx = i + 4 * u + g;
-          const int from = idx < n ? idx : i;  // past the end: a valid row with weight 0
-          const uint32_t inf = (uint32_t)__shfl((int)info, from);
-          float ww = __shfl(w, from);
-          if (idx >= n) ww = 0.f;
-          // split the fp32 weight into two bf16 halves; this lane's half goes to element `pos` of B
-          const bf16_t whi = (bf16_t)ww;
-          const bf16_t wlo = (bf16_t)(ww - (float)whi);
-          const bf16_t part = lo_part ? wlo : whi;
-          wbits[u] = (uint32_t)__builtin_bit_cast(uint16_t, part) << ((pos & 1) * 16);
-          const bf16_t *rowp = ((inf >> 31) ? src_sel : src_unsel) + (size_t)(inf & 0x7fffffffu) * ld + tile0 + lig * 8;
+      for (int u = 0; u < U; ++u) issue(issued + u, u);
+      for (; k + 2 * U <= count; k += U) {
 #pragma unroll
-          for (int h = 0; h < NT; ++h)
-            x[u][h] = (tile0 + h * 128 + lig * 8 < d) ? *reinterpret_cast<const bf16x8_t *>(rowp + h * 128) : zero8;
+        for (int u = 0; u < U; ++u) {
+          consume(u);
+          issue(issued + k + U + u, u);
         }
       }
+    } else {
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        if (i + 4 * u < n) {
-          u32x4_t bw;
-          bw[0] = (pos >> 1) == 0 ? wbits[u] : 0u;
-          bw[1] = (pos >> 1) == 1 ? wbits[u] : 0u;
-          bw[2] = (pos >> 1) == 2 ? wbits[u] : 0u;
-          bw[3] = (pos >> 1) == 3 ? wbits[u] : 0u;
-          const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, bw);
-#pragma unroll
-          for (int h = 0; h < NT; ++h) acc[h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x[u][h], bfrag, acc[h], 0, 0, 0);
-        }
-      }
+      for (int u = 0; u < U; ++u)
+        if (u < count) issue(issued + u, u);
     }
+    // steps k .. k + U - 1 (those below count) are in their slots; fewer than U further steps remain
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (k + u < count) consume(u);
+      if (k + U + u < count) issue(issued + k + U + u, u);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (k + U + u < count) consume(u);
+    issued = avail;
   }
   // D layout: element i of lane l is D[m = 4*(l/16) + i][n = l%16]; column = 8m + n%8, halves n<8 / n>=8
+  float *rowbuf = reinterpret_cast<float *>(ring);  // every record has been read: the ring's memory is free
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
 #pragma unroll
   for (int h = 0; h < NT; ++h)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const float v = acc[h][i] + __shfl_xor(acc[h][i], 8);
-      if (!lo_part) rowbuf[wave][h * 128 + (4 * g + i) * 8 + pos] = v;
+      if (!lo_part) rowbuf[h * 128 + (4 * g + i) * 8 + pos] = v;
     }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the wave's own LDS writes have landed
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   // natural layout again: lane q owns 8 consecutive columns
 #pragma unroll
   for (int r = 0; r < (NT * 16 + 63) / 64; ++r) {
@@ -345,7 +423,7 @@ __global__ __launch_bounds__(256) void spmm_mfma_kernel(const SpmmArgs a) {
     if (q < NT * 16 && c < d) {
       float v[8];
 #pragma unroll
-      for (int t = 0; t < 8; ++t) v[t] = rowbuf[wave][q * 8 + t];
+      for (int t = 0; t < 8; ++t) v[t] = rowbuf[q * 8 + t];
       if (slot >= 0) {
         Pack<float, 8> o;
 #pragma unroll
@@ -432,26 +510,39 @@ static bool mfma_path(const SpmmArgs &a, int src_dtype) {
          (!has_aux || a.aux_ld % 8 == 0);
 }
 
+template <typename Tout, int NT>
+static void launch_ring(const SpmmArgs &a, hipStream_t s, dim3 grid, int unroll) {
+  const bool full = a.d == NT * 128;
+  if (unroll >= 8) {
+    if (full) hipLaunchKernelGGL((spmm_ring_kernel<Tout, NT, 8, true>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((spmm_ring_kernel<Tout, NT, 8, false>), grid, dim3(256), 0, s, a);
+  } else if (unroll >= 4) {
+    if (full) hipLaunchKernelGGL((spmm_ring_kernel<Tout, NT, 4, true>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((spmm_ring_kernel<Tout, NT, 4, false>), grid, dim3(256), 0, s, a);
+  } else {
+    if (full) hipLaunchKernelGGL((spmm_ring_kernel<Tout, NT, 2, true>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((spmm_ring_kernel<Tout, NT, 2, false>), grid, dim3(256), 0, s, a);
+  }
+}
+
+// Gather slots per wave.  Two slots leave room for eight waves per SIMD, which measured best on every
+// workload; GNNSTAGE_SPMM_UNROLL = 4 or 8 trades waves for deeper per-wave queues (tests run all three).
+static int ring_slots() {
+  const char *e = getenv("GNNSTAGE_SPMM_UNROLL");
+  return e ? atoi(e) : 2;
+}
+
 template <typename Tout>
 static int launch_mfma(const SpmmArgs &a, hipStream_t s) {
   const unsigned gx = (unsigned)(a.n_class_blocks + (a.n_tasks - a.tail_task0 + 3) / 4);
   if (gx == 0) return hipSuccess;  // only class pieces, none of them active
-  static const int unroll = getenv("GNNSTAGE_SPMM_UNROLL") ? atoi(getenv("GNNSTAGE_SPMM_UNROLL")) : 4;
-  if (a.d <= 128) {
-    if (unroll >= 8)
-      hipLaunchKernelGGL((spmm_mfma_kernel<Tout, 1, 8>), dim3(gx, 1), dim3(256), 0, s, a);
-    else if (unroll >= 4)
-      hipLaunchKernelGGL((spmm_mfma_kernel<Tout, 1, 4>), dim3(gx, 1), dim3(256), 0, s, a);
-    else
-      hipLaunchKernelGGL((spmm_mfma_kernel<Tout, 1, 2>), dim3(gx, 1), dim3(256), 0, s, a);
-  } else if (a.d <= 256) {
-    if (unroll >= 4)
-      hipLaunchKernelGGL((spmm_mfma_kernel<Tout, 2, 4>), dim3(gx, 1), dim3(256), 0, s, a);
-    else
-      hipLaunchKernelGGL((spmm_mfma_kernel<Tout, 2, 2>), dim3(gx, 1), dim3(256), 0, s, a);
-  } else {
-    hipLaunchKernelGGL((spmm_mfma_kernel<Tout, 4, 4>), dim3(gx, (unsigned)((a.d + 511) / 512)), dim3(256), 0, s, a);
-  }
+  const int unroll = ring_slots();
+  if (a.d <= 128)
+    launch_ring<Tout, 1>(a, s, dim3(gx, 1), unroll);
+  else if (a.d <= 256)
+    launch_ring<Tout, 2>(a, s, dim3(gx, 1), unroll);
+  else
+    launch_ring<Tout, 4>(a, s, dim3(gx, (unsigned)((a.d + 511) / 512)), unroll >= 8 ? 4 : 2);
   return (int)hipGetLastError();
 }
 

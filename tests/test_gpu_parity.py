@@ -169,6 +169,16 @@ def test_source_class_schedules(monkeypatch, classes, min_row, split, name):
     _parity(p, TOL_BF16)
 
 
+@pytest.mark.parametrize("slots", [4, 8])
+@pytest.mark.parametrize("name", ["c1_s", "c3_s"])
+def test_deeper_gather_queues(monkeypatch, slots, name):
+    """The matrix-core aggregation normally keeps two gather slots per wave; run its 4- and 8-slot forms
+    (other steady-loop lengths, other tails) against the same oracle."""
+    monkeypatch.setenv("GNNSTAGE_SPMM_UNROLL", str(slots))
+    p = make_problem(CONFIGS[name], bias_std=0.05)
+    _parity(p, TOL_BF16)
+
+
 @pytest.mark.parametrize("name", ["c1_s", "c2_s", "c3_s", "c4_s"])
 def test_persistent_gemm_on_small_inputs(monkeypatch, name):
     """The weight-stationary persistent GEMM normally serves only long operands; force it everywhere."""
@@ -243,6 +253,30 @@ def test_indicator_probe_counts_selected_neighbours(roles):
         got = run.np(run.cur[1][rows])
         expect = want if roles == "cur1_hist0" else deg[rows] - want
         assert np.array_equal(got, np.repeat(expect[:, None], 8, axis=1).astype(np.float32))
+
+
+@pytest.mark.parametrize("d,deg,wbits,xmax", [(128, 9.0, 12, 4), (256, 9.0, 12, 4), (256, 200.0, 12, 4),
+                                              (512, 70.0, 12, 4), (256, 9.0, 16, 2), (128, 30.0, 16, 2)])
+def test_bf16_aggregation_is_exact_on_exactly_summable_inputs(d, deg, wbits, xmax):
+    """Edge weights with 12 or 16 significant bits (more than one bf16 holds), rows of small integers, W = I,
+    b = 0: every product and every partial sum is exact in fp32, so level 1 and the input gradient are the
+    bf16 rounding of the exact sum - bit for bit.  Fails if the matrix-core aggregation loses the low half
+    of a weight, drops or repeats an entry, or reads a row from the wrong buffer.  Rows of 200 entries
+    span several metadata batches."""
+    n = 1500
+    w = small(n=n, k=5, dims=(d, d), dtype="bf16", deg=deg, seed=41)
+    p = make_problem(w, chunk_ptr=graphs.ragged_chunks(n, 5, 11), bias_std=0.0)
+    rng = np.random.default_rng(7)
+    p.val = (rng.integers(1 << (wbits - 1), 1 << wbits, size=p.val.shape) / float(1 << (wbits - 1))).astype(np.float32)
+    p.W = [np.eye(d, dtype=np.float32)]
+    p.x0 = rng.integers(0, xmax, size=p.x0.shape).astype(np.float32)
+    p.hist = [rng.integers(0, xmax, size=p.hist[0].shape).astype(np.float32)]
+    p.grad_out = rng.integers(-1, 2, size=p.grad_out.shape).astype(np.float32)
+    ref = run_oracle(p)
+    run = _gpu(p).run()
+    assert np.array_equal(run.np(run.cur[1]), ref.cur[1])
+    assert np.array_equal(run.np(run.grad_in), ref.grad_in)
+    assert len(np.unique(ref.cur[1])) > 50
 
 
 def test_backward_mask_probe_counts_processed_readers():
