@@ -18,6 +18,8 @@ namespace {
 typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef bf16_t bf16x2 __attribute__((ext_vector_type(2)));
 
 __device__ inline float to_f32(float x) { return x; }
 __device__ inline float to_f32(bf16_t x) { return (float)x; }
@@ -173,7 +175,10 @@ __device__ inline bf16x8 load8_bf16(const T *base, size_t ld, int r, int c, int 
 constexpr int BM = 128, BN = 128, BK = 32;
 constexpr int LDS_K = 40;  // padded K stride (elements): 80-byte rows keep 16-byte fragment reads conflict-free
 
-template <typename TA, bool VEC>
+// PAIR: A is an fp32 matrix with an even leading dimension and an 8-byte aligned base.  A tile row is then
+// 32 floats = one 128-byte line, read by 16 lanes as float pairs (four whole rows per wave instruction,
+// fully coalesced) instead of eight scalars per lane.
+template <typename TA, bool VEC, bool PAIR = false>
 __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmNtArgs a) {
   __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * LDS_K];
   __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * LDS_K];
@@ -198,20 +203,44 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmNtArgs a) {
       for (int t = 0; t < 16; ++t) acc[i][j][t] = 0.f;
 
   bf16x8 ra[2], rb[2];
+  f32x2 rp[PAIR ? 8 : 1];
   const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
   auto gload = [&](int k0) {
+    if constexpr (PAIR) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int r = (tid >> 4) + 16 * i, k = k0 + 2 * (tid & 15);
+        f32x2 v = {0.f, 0.f};
+        if (m0 + r < a.M) {
+          const float *p = reinterpret_cast<const float *>(A) + (size_t)(m0 + r) * a.lda + k;
+          if (k + 1 < a.K)
+            v = *reinterpret_cast<const f32x2 *>(p);
+          else if (k < a.K)
+            v[0] = p[0];
+        }
+        rp[i] = v;
+      }
+    }
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int vid = tid + 256 * i, r = vid >> 2, k = k0 + (vid & 3) * 8;
-      ra[i] = (m0 + r < a.M) ? load8_bf16<TA, VEC>(A, (size_t)a.lda, m0 + r, k, a_cols) : zero8;
+      if constexpr (!PAIR) ra[i] = (m0 + r < a.M) ? load8_bf16<TA, VEC>(A, (size_t)a.lda, m0 + r, k, a_cols) : zero8;
       rb[i] = (n0 + r < a.N && k < a.Kp) ? *reinterpret_cast<const bf16x8 *>(Bt + (size_t)(n0 + r) * a.ldb + k) : zero8;
     }
   };
   auto sstore = [&](int buf) {
+    if constexpr (PAIR) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int r = (tid >> 4) + 16 * i;
+        const bf16x2 v = {(bf16_t)rp[i][0], (bf16_t)rp[i][1]};
+        *reinterpret_cast<bf16x2 *>(&As[buf][r * LDS_K + 2 * (tid & 15)]) = v;
+      }
+    }
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int vid = tid + 256 * i, r = vid >> 2, kv = vid & 3;
-      *reinterpret_cast<bf16x8 *>(&As[buf][r * LDS_K + kv * 8]) = ra[i];
+      if constexpr (!PAIR) *reinterpret_cast<bf16x8 *>(&As[buf][r * LDS_K + kv * 8]) = ra[i];
       *reinterpret_cast<bf16x8 *>(&Bs[buf][r * LDS_K + kv * 8]) = rb[i];
     }
   };
@@ -432,7 +461,9 @@ static int launch_ws(const GemmNtArgs &a, hipStream_t s) {
 constexpr int TR = 64;      // reduction rows per step (two 16 KB operand tiles in flight per workgroup)
 constexpr int LDS_C = 136;  // padded column stride of the row-major LDS tiles
 
-template <typename TA, bool VEC>
+// PAIR: fp32 A with an even leading dimension and an 8-byte aligned base; a tile row (128 floats) is read by
+// one wave instruction as 64 float pairs.
+template <typename TA, bool VEC, bool PAIR = false>
 __global__ __launch_bounds__(256) void gemm_tn_bf16_kernel(const GemmTnArgs a, int rows_per_split, int splits) {
   __shared__ __attribute__((aligned(16))) bf16_t As[TR * LDS_C];
   __shared__ __attribute__((aligned(16))) bf16_t Bs[TR * LDS_C];
@@ -470,22 +501,46 @@ __global__ __launch_bounds__(256) void gemm_tn_bf16_kernel(const GemmTnArgs a, i
     for (int t = 0; t < 16; ++t) accb[j][t] = 0.f;
   constexpr int NVT = TR * 16 / 256;  // 16-byte vectors per thread and operand tile
   bf16x8 ra[NVT], rb[NVT];
+  constexpr int NPR = TR / 4;  // rows per wave and tile in the pair layout
+  f32x2 rp[PAIR ? NPR : 1];
   auto gload = [&](int r0) {
+    if constexpr (PAIR) {
+#pragma unroll
+      for (int i = 0; i < NPR; ++i) {
+        const int r = wave + 4 * i, c = i0 + 2 * lane;
+        f32x2 v = {0.f, 0.f};
+        if (r0 + r < r_end) {
+          const float *p = reinterpret_cast<const float *>(A) + (size_t)(r0 + r) * a.lda + c;
+          if (c + 1 < a.I)
+            v = *reinterpret_cast<const f32x2 *>(p);
+          else if (c < a.I)
+            v[0] = p[0];
+        }
+        rp[i] = v;
+      }
+    }
 #pragma unroll
     for (int i = 0; i < NVT; ++i) {
       const int vid = tid + 256 * i, r = vid >> 4, c = (vid & 15) * 8;
       const bool rv = r0 + r < r_end;
-      ra[i] = rv ? load8_bf16<TA, VEC>(A, (size_t)a.lda, r0 + r, i0 + c, a_cols) : zero8;
+      if constexpr (!PAIR) ra[i] = rv ? load8_bf16<TA, VEC>(A, (size_t)a.lda, r0 + r, i0 + c, a_cols) : zero8;
       rb[i] = (rv && o0 + c < a.ldb) ? *reinterpret_cast<const bf16x8 *>(B + (size_t)(r0 + r) * a.ldb + o0 + c) : zero8;
     }
   };
   if (r_begin < r_end) gload(r_begin);
   for (int r0 = r_begin; r0 < r_end; r0 += TR) {
     __syncthreads();  // previous step's fragment reads are done
+    if constexpr (PAIR) {
+#pragma unroll
+      for (int i = 0; i < NPR; ++i) {
+        const bf16x2 v = {(bf16_t)rp[i][0], (bf16_t)rp[i][1]};
+        *reinterpret_cast<bf16x2 *>(&As[(wave + 4 * i) * LDS_C + 2 * lane]) = v;
+      }
+    }
 #pragma unroll
     for (int i = 0; i < NVT; ++i) {
       const int vid = tid + 256 * i, r = vid >> 4, c = (vid & 15) * 8;
-      *reinterpret_cast<bf16x8 *>(&As[r * LDS_C + c]) = ra[i];
+      if constexpr (!PAIR) *reinterpret_cast<bf16x8 *>(&As[r * LDS_C + c]) = ra[i];
       *reinterpret_cast<bf16x8 *>(&Bs[r * LDS_C + c]) = rb[i];
     }
     __syncthreads();
@@ -738,6 +793,7 @@ bool vec_ok(const void *p, int ld, int mult) { return (reinterpret_cast<uintptr_
 }  // namespace
 
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static bool pair_ok(const void *p, int ld) { return (reinterpret_cast<uintptr_t>(p) & 7u) == 0 && ld % 2 == 0; }
 
 int launch_gemm_nt(const GemmNtArgs &a_in, int compute_dtype, hipStream_t s) {
   if (a_in.M <= 0 || a_in.N <= 0) return hipSuccess;
@@ -751,7 +807,9 @@ int launch_gemm_nt(const GemmNtArgs &a_in, int compute_dtype, hipStream_t s) {
     const int mt = (a.M + BM - 1) / BM, ntiles = (a.N + BN - 1) / BN;
     dim3 grid((unsigned)(((mt + 7) / 8) * 8 * ntiles));
     const bool vec = a.a_dtype == DT_BF16 && vec_ok(a.A, a.lda, 8) && a.lda >= a.Kp;
-    if (a.a_dtype == DT_F32)
+    if (a.a_dtype == DT_F32 && pair_ok(a.A, a.lda))
+      hipLaunchKernelGGL((gemm_nt_bf16_kernel<float, false, true>), grid, dim3(256), 0, s, a);
+    else if (a.a_dtype == DT_F32)
       hipLaunchKernelGGL((gemm_nt_bf16_kernel<float, false>), grid, dim3(256), 0, s, a);
     else if (vec && vec_ok(a.Bt, a.ldb, 8) && a.Kp <= 256 && a.N <= 256 && a.M >= ws_min_rows()) {
       // long operands: persistent weight-stationary kernel (needs a few row tiles per workgroup to pay
@@ -793,7 +851,9 @@ int launch_gemm_tn(const GemmTnArgs &a, int compute_dtype, hipStream_t s) {
   dim3 grid(ti, to, splits);
   if (compute_dtype == DT_BF16) {
     dim3 g1((unsigned)(((splits + 7) / 8) * 8 * ti * to));
-    if (a.a_dtype == DT_F32)
+    if (a.a_dtype == DT_F32 && pair_ok(a.A, a.lda))
+      hipLaunchKernelGGL((gemm_tn_bf16_kernel<float, false, true>), g1, dim3(256), 0, s, a, rows_per, splits);
+    else if (a.a_dtype == DT_F32)
       hipLaunchKernelGGL((gemm_tn_bf16_kernel<float, false>), g1, dim3(256), 0, s, a, rows_per, splits);
     else if (vec_ok(a.A, a.lda, 8))
       hipLaunchKernelGGL((gemm_tn_bf16_kernel<bf16_t, true>), g1, dim3(256), 0, s, a, rows_per, splits);

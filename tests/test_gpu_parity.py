@@ -216,11 +216,12 @@ def test_both_layer_orders(monkeypatch, order_mode, dtype):
     _parity(p, TOL_F32 if dtype == "f32" else TOL_BF16)
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_first_stage_with_aliased_history(dtype):
+@pytest.mark.parametrize("dtype,d0", [("f32", 200), ("bf16", 200), ("bf16", 201), ("bf16", 602)])
+def test_first_stage_with_aliased_history(dtype, d0):
     """hist[0] is the very same buffer as cur[0]; the wide first layer runs transform-first and shares
-    one transformed table between current and historical reads."""
-    w = small(n=900, k=4, dims=(200, 32, 32), dtype=dtype, deg=8.0, seed=13, level0_f32=(dtype == "bf16"))
+    one transformed table between current and historical reads.  In the bf16 stage the fp32 features are
+    read as float pairs when their width is even (602: with a ragged last k-tile), element-wise when odd."""
+    w = small(n=900, k=4, dims=(d0, 32, 32), dtype=dtype, deg=8.0, seed=13, level0_f32=(dtype == "bf16"))
     p = make_problem(w, first_stage=True)
     _parity(p, TOL_F32 if dtype == "f32" else TOL_BF16, need_input_grad=False, alias_hist0=True)
     _parity(p, TOL_F32 if dtype == "f32" else TOL_BF16, need_input_grad=True, alias_hist0=True)
