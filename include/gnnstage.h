@@ -167,7 +167,8 @@ int gnnstage_plan_pack(int64_t n, int64_t nnz, const int32_t *idx, int32_t n_chu
  * A task is what one wavefront does.  Rows with at most split_edges entries are one task each
  * (task_slot = -1).  Longer rows are cut into pieces of at most split_edges entries; with n_classes > 1
  * rows of at least class_min_row entries are first cut where the source id changes its range class
- * (class = source * n_classes / n_vertices), so that each piece gathers from one slice of the source
+ * (class q = source ids [class_lo[q], class_lo[q + 1]), n_classes + 1 ascending bounds from 0 to n_vertices;
+ * class_lo == NULL means equal id ranges), so that each piece gathers from one slice of the source
  * table.  Every piece carries the index of the fp32 partial-sum slot it writes (consecutive per row).
  * Tasks are emitted class-major: the pieces of class 0, ..., class n_classes-1, then pieces without a
  * class, then whole rows; class_off (n_classes + 1 entries, may be NULL) receives where each class
@@ -175,9 +176,10 @@ int gnnstage_plan_pack(int64_t n, int64_t nnz, const int32_t *idx, int32_t n_chu
  * may be NULL) the class of every slot (255 = none).  Returns the number of tasks (or a negative code);
  * with non-NULL task arrays also fills them (capacity checked).  idx may be NULL when n_classes == 1. */
 int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, int64_t n_vertices, int64_t row_begin,
-                            int64_t row_end, int32_t split_edges, int32_t n_classes, int32_t class_min_row,
-                            int64_t capacity, int32_t *task_row, int64_t *task_e0, int32_t *task_ne,
-                            int32_t *task_slot, int64_t *n_slots, int64_t *class_off, uint8_t *slot_class);
+                            int64_t row_end, int32_t split_edges, int32_t n_classes, const int64_t *class_lo,
+                            int32_t class_min_row, int64_t capacity, int32_t *task_row, int64_t *task_e0,
+                            int32_t *task_ne, int32_t *task_slot, int64_t *n_slots, int64_t *class_off,
+                            uint8_t *slot_class);
 
 /*
  * Per-kernel timing with HIP events on the launch stream.  kind: 0 forward aggregation,

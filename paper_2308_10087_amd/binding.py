@@ -76,7 +76,7 @@ def _load():
                                        C.POINTER(C.c_int32)]
     lib.gnnstage_plan_tasks.restype = C.c_int64
     lib.gnnstage_plan_tasks.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_int32,
-                                        C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.POINTER(C.c_int64), C.c_void_p, C.c_void_p]
     lib.gnnstage_layer_order.restype = C.c_int
     lib.gnnstage_layer_order.argtypes = [C.c_void_p, C.c_int32]
@@ -124,14 +124,19 @@ def gnnstage_plan_pack(n: int, idx: np.ndarray, chunk_ptr: np.ndarray):
 
 
 def gnnstage_plan_tasks(ptr: np.ndarray, row_begin: int, row_end: int, split_edges: int, idx=None,
-                        n_vertices: int = 0, n_classes: int = 1, class_min_row: int = 0, return_classes: bool = False):
+                        n_vertices: int = 0, n_classes: int = 1, class_min_row: int = 0, return_classes: bool = False,
+                        class_lo=None):
     ptr = np.ascontiguousarray(ptr, dtype=np.int64)
+    if class_lo is not None:
+        class_lo = np.ascontiguousarray(class_lo, dtype=np.int64)
+        assert class_lo.shape[0] == n_classes + 1
+    lo = None if class_lo is None else class_lo.ctypes.data
     if idx is not None:
         idx = np.ascontiguousarray(idx, dtype=np.int32)
     ip = None if idx is None else idx.ctypes.data
     nv = n_vertices if n_vertices > 0 else ptr.shape[0] - 1
     ns = C.c_int64(0)
-    n = lib.gnnstage_plan_tasks(ptr.ctypes.data, ip, nv, row_begin, row_end, split_edges, n_classes, class_min_row,
+    n = lib.gnnstage_plan_tasks(ptr.ctypes.data, ip, nv, row_begin, row_end, split_edges, n_classes, lo, class_min_row,
                                 0, None, None, None, None, C.byref(ns), None, None)
     if n < 0:
         raise GnnStageError(int(n), "gnnstage_plan_tasks")
@@ -139,8 +144,8 @@ def gnnstage_plan_tasks(ptr: np.ndarray, row_begin: int, row_end: int, split_edg
     ne, slot = np.zeros(n, np.int32), np.zeros(n, np.int32)
     class_off = np.zeros(n_classes + 1, np.int64)
     slot_class = np.zeros(max(int(ns.value), 1), np.uint8)
-    got = lib.gnnstage_plan_tasks(ptr.ctypes.data, ip, nv, row_begin, row_end, split_edges, n_classes, class_min_row,
-                                  n, row.ctypes.data, e0.ctypes.data, ne.ctypes.data, slot.ctypes.data, C.byref(ns),
+    got = lib.gnnstage_plan_tasks(ptr.ctypes.data, ip, nv, row_begin, row_end, split_edges, n_classes, lo,
+                                  class_min_row, n, row.ctypes.data, e0.ctypes.data, ne.ctypes.data, slot.ctypes.data, C.byref(ns),
                                   class_off.ctypes.data, slot_class.ctypes.data)
     if got != n:
         raise GnnStageError(int(got), "gnnstage_plan_tasks")

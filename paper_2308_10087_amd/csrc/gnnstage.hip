@@ -57,6 +57,24 @@ int class_min_row_setting() {
   return 256;
 }
 
+// Lower bounds of the source-id classes: equal id ranges, except that a bound moves onto a chunk boundary
+// that lies within a quarter of a class width of it.  Chunks that line up with classes (equal chunks, a
+// multiple of the class count) then never straddle two classes, and a backward launch touches exactly the
+// classes of its processed chunks.
+std::vector<int64_t> class_bounds(int64_t n, int classes, const std::vector<int64_t> &chunk_ptr) {
+  std::vector<int64_t> lo((size_t)classes + 1);
+  for (int q = 0; q <= classes; ++q) lo[(size_t)q] = ((int64_t)q * n + classes - 1) / classes;
+  const int64_t tol = n / (4 * (int64_t)classes);
+  for (int q = 1; q < classes; ++q) {
+    int64_t best = -1;
+    for (const int64_t cb : chunk_ptr)
+      if (std::llabs(cb - lo[(size_t)q]) <= tol && (best < 0 || std::llabs(cb - lo[(size_t)q]) < std::llabs(best - lo[(size_t)q])))
+        best = cb;
+    if (best > 0 && best < n) lo[(size_t)q] = best;
+  }
+  return lo;
+}
+
 struct TaskList {
   int64_t n_tasks = 0, n_long = 0, n_slots = 0;
   int32_t *task_row = nullptr;
@@ -68,6 +86,9 @@ struct TaskList {
   int n_classes = 0;                      // 0: no class sections
   int64_t cls_off[kMaxClasses + 1] = {};  // tail starts at cls_off[n_classes]
   uint8_t *slot_class = nullptr;
+  // entries of every class section by the chunk of the gathered vertex ([class * K + chunk]): what a launch
+  // that drops unselected entries really gathers from each class
+  std::vector<int64_t> cls_chunk_entries;
 };
 
 // Sizes that depend only on row lengths: number of tasks / long rows / slots of every chunk.
@@ -348,7 +369,6 @@ struct gnnstage {
   // schedules
   std::vector<TaskList> ftasks, btasks;
   int n_classes = 1;
-  ChunkMask cls_chunks[kMaxClasses] = {};  // chunks that overlap the id range of each source class
   // pass state (Section 3.3: V_processed, and its backward twin)
   std::vector<int32_t> order;
   ChunkMask fmask{}, bmask{};
@@ -403,62 +423,80 @@ void mask_set(ChunkMask &m, int c) { m.w[c >> 6] |= 1ull << (c & 63); }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // XCD assignment of the class sections for one launch.  `drop` = the launch skips unselected entries:
-// a class none of whose chunks is in the mask has no work and is not served at all.  The groups of the
-// active classes are dealt to the 8 XCDs like water into buckets: equal shares, a class being split
-// between neighbouring XCDs where a share boundary falls inside it.
+// a class with no entry from a chunk in the mask has no work and is not served at all.  Every class gets
+// a cost (a fixed part per task, one unit per gathered entry, a small part per entry that is read and
+// dropped), and the groups of the active classes are dealt to the 8 XCDs like water into buckets of equal
+// cost, a class being split between neighbouring XCDs where a bucket boundary falls inside it.
 void assign_xcds(const gnnstage *st, const TaskList &t, const ChunkMask &mask, bool drop, SpmmArgs &a) {
-  const int C = t.n_classes;
+  const int C = t.n_classes, K = st->s.K;
   a.tail_task0 = t.cls_off[C];
   a.slot_class = t.slot_class;
   a.active_classes = 0;
   a.all_classes_active = 1;
   a.n_class_blocks = 0;
   int groups[kMaxClasses];
-  int64_t total = 0;
+  double unit[kMaxClasses];  // cost of one group of four tasks
+  double total = 0;
   for (int x = 0; x < 8; ++x)
     for (int sgm = 0; sgm < kMaxSegs; ++sgm) a.seg_cls[x][sgm] = a.seg_g0[x][sgm] = a.seg_cnt[x][sgm] = 0;
   for (int q = 0; q < kMaxClasses; ++q) {
     a.cls_task0[q] = a.cls_ntasks[q] = 0;
     groups[q] = 0;
+    unit[q] = 0;
     if (q >= C) continue;
     a.cls_task0[q] = (int32_t)t.cls_off[q];
     a.cls_ntasks[q] = (int32_t)(t.cls_off[q + 1] - t.cls_off[q]);
-    bool on = !drop;
-    for (int c = 0; c < st->s.K && !on; ++c) on = mask_test(st->cls_chunks[q], c) && mask_test(mask, c);
+    int64_t kept = 0, all = 0;
+    for (int c = 0; c < K; ++c) {
+      const int64_t e = t.cls_chunk_entries[(size_t)q * K + c];
+      all += e;
+      if (!drop || mask_test(mask, c)) kept += e;
+    }
+    const bool on = a.cls_ntasks[q] > 0 && kept > 0;
     if (!on) a.all_classes_active = 0;
-    groups[q] = (on && a.cls_ntasks[q] > 0) ? (a.cls_ntasks[q] + 3) / 4 : 0;
-    if (on) a.active_classes |= 1u << q;
-    total += groups[q];
+    if (!on) continue;
+    a.active_classes |= 1u << q;
+    groups[q] = (a.cls_ntasks[q] + 3) / 4;
+    const double cost = 32.0 * a.cls_ntasks[q] + (double)kept + 0.125 * (double)(all - kept);
+    unit[q] = cost / groups[q];
+    total += cost;
   }
   if (total == 0) return;
-  const int quota = (int)((total + 7) / 8);
-  int x = 0, used = 0, nseg = 0, most = 0;
+  const double quota = total / 8;
+  int x = 0, nseg = 0, most = 0, load = 0;
+  double used = 0;
   bool fits = true;
   for (int q = 0; q < C && fits; ++q) {
     int g = 0;
     while (g < groups[q]) {
-      if (x < 7 && (used == quota || nseg == kMaxSegs)) {
+      if (x < 7 && (used >= quota - 0.5 * unit[q] || nseg == kMaxSegs)) {
         ++x;
         used = 0;
         nseg = 0;
+        load = 0;
       }
       if (nseg == kMaxSegs) {  // many tiny classes left for the last XCD
         fits = false;
         break;
       }
-      const int take = x < 7 ? std::min(groups[q] - g, quota - used) : groups[q] - g;
+      int take = groups[q] - g;
+      if (x < 7) {
+        const int room = (int)((quota - used) / unit[q] + 0.5);
+        take = std::min(take, std::max(room, 1));
+      }
       a.seg_cls[x][nseg] = q;
       a.seg_g0[x][nseg] = g;
       a.seg_cnt[x][nseg] = take;
       ++nseg;
       g += take;
-      used += take;
-      most = std::max(most, used);
+      used += take * unit[q];
+      load += take;
+      most = std::max(most, load);
     }
   }
   if (!fits) {  // fallback that always fits: class q goes whole to XCD q % 8 (at most 4 segments each)
     most = 0;
-    int cnt[8] = {0, 0, 0, 0, 0, 0, 0, 0}, load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    int cnt[8] = {0, 0, 0, 0, 0, 0, 0, 0}, ld[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     for (int xx = 0; xx < 8; ++xx)
       for (int sgm = 0; sgm < kMaxSegs; ++sgm) a.seg_cls[xx][sgm] = a.seg_g0[xx][sgm] = a.seg_cnt[xx][sgm] = 0;
     for (int q = 0; q < C; ++q) {
@@ -468,8 +506,8 @@ void assign_xcds(const gnnstage *st, const TaskList &t, const ChunkMask &mask, b
       a.seg_g0[xx][cnt[xx]] = 0;
       a.seg_cnt[xx][cnt[xx]] = groups[q];
       ++cnt[xx];
-      load[xx] += groups[q];
-      most = std::max(most, load[xx]);
+      ld[xx] += groups[q];
+      most = std::max(most, ld[xx]);
     }
   }
   a.n_class_blocks = 8 * most;
@@ -646,19 +684,14 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
   st->ws = static_cast<char *>(d->workspace);
   st->prof.init(s.L);
   st->n_classes = s.classes();
-  for (int q = 0; q < st->n_classes; ++q)
-    for (int c = 0; c < s.K; ++c) {
-      const int64_t C = st->n_classes;
-      const int64_t lo = (q * s.n + C - 1) / C, hi = ((q + 1) * s.n + C - 1) / C;  // ids u with u * C / n == q
-      if (s.chunk_ptr[c] < hi && s.chunk_ptr[c + 1] > lo) mask_set(st->cls_chunks[q], c);
-    }
+  const std::vector<int64_t> cls_lo = class_bounds(s.n, st->n_classes, s.chunk_ptr);
   st->h_row_ptr.assign(d->row_ptr, d->row_ptr + s.n + 1);
   st->h_pcol = pcol;
 
   // schedules: build on the host chunk by chunk, upload into the preallocated arrays
   const int classes = s.classes(), min_row = class_min_row_setting();
-  auto build = [&](const int64_t *ptr, const int32_t *idx, const PlanCounts &pc, bool transposed,
-                   std::vector<TaskList> &lists) -> int {
+  auto build = [&](const int64_t *ptr, const int32_t *idx, const uint32_t *packed, const PlanCounts &pc,
+                   bool transposed, std::vector<TaskList> &lists) -> int {
     lists.resize(s.K);
     int64_t t_off = 0, l_off = 0, s_off = 0;
     for (int c = 0; c < s.K; ++c) {
@@ -682,11 +715,15 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
       std::vector<int64_t> coff(classes + 1, 0);
       std::vector<uint8_t> sclass((size_t)std::max<int64_t>(pc.slots[c], 1), 255);
       const int64_t got = gnnstage_plan_tasks(ptr, idx, s.n, s.chunk_ptr[c], s.chunk_ptr[c + 1], pc.split[c], classes,
-                                              min_row, cap, row.data(), e0.data(), ne.data(), slot.data(), &ns,
-                                              coff.data(), sclass.data());
+                                              cls_lo.data(), min_row, cap, row.data(), e0.data(), ne.data(),
+                                              slot.data(), &ns, coff.data(), sclass.data());
       if (got < 0 || got > cap || ns > pc.slots[c]) return GNNSTAGE_EINVAL;
       tl.n_classes = classes > 1 ? classes : 0;
       for (int q = 0; q <= tl.n_classes; ++q) tl.cls_off[q] = coff[q];
+      tl.cls_chunk_entries.assign((size_t)tl.n_classes * s.K, 0);
+      for (int q = 0; q < tl.n_classes; ++q)
+        for (int64_t t = coff[q]; t < coff[q + 1]; ++t)
+          for (int64_t e = e0[t]; e < e0[t] + ne[t]; ++e) tl.cls_chunk_entries[(size_t)q * s.K + (packed[e] >> vbits)] += 1;
       if (ns > 0 && hipMemcpy(tl.slot_class, sclass.data(), (size_t)ns, hipMemcpyHostToDevice) != hipSuccess)
         return GNNSTAGE_EHIP;
       tl.n_tasks = got;
@@ -744,8 +781,8 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
         launch_gcn_norm(st->at<int64_t>(lay.t_ptr), st->at<uint32_t>(lay.prow), vbits, rp, s.n, st->at<float>(lay.tval), nullptr) != 0)
       return bail(GNNSTAGE_EHIP, "normalisation kernel launch failed");
   }
-  rc = build(d->row_ptr, d->col_idx, fc, false, st->ftasks);
-  if (rc == GNNSTAGE_OK) rc = build(t_ptr.data(), t_row.data(), bc, true, st->btasks);
+  rc = build(d->row_ptr, d->col_idx, pcol.data(), fc, false, st->ftasks);
+  if (rc == GNNSTAGE_OK) rc = build(t_ptr.data(), t_row.data(), prow.data(), bc, true, st->btasks);
   if (rc != GNNSTAGE_OK) return bail(rc, "building the launch schedule failed");
   if (hipDeviceSynchronize() != hipSuccess) return bail(GNNSTAGE_EHIP, "device synchronisation failed after create");
   *out = st;

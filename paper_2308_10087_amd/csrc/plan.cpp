@@ -69,13 +69,28 @@ struct Task {
 }  // namespace
 
 extern "C" int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, int64_t n_vertices, int64_t row_begin,
-                                       int64_t row_end, int32_t split_edges, int32_t n_classes, int32_t class_min_row,
-                                       int64_t capacity, int32_t *task_row, int64_t *task_e0, int32_t *task_ne,
-                                       int32_t *task_slot, int64_t *n_slots_out, int64_t *class_off,
-                                       uint8_t *slot_class) {
+                                       int64_t row_end, int32_t split_edges, int32_t n_classes,
+                                       const int64_t *class_lo, int32_t class_min_row, int64_t capacity,
+                                       int32_t *task_row, int64_t *task_e0, int32_t *task_ne, int32_t *task_slot,
+                                       int64_t *n_slots_out, int64_t *class_off, uint8_t *slot_class) {
   if (!ptr || row_begin > row_end || split_edges <= 0 || n_classes < 1 || n_classes > 64 || n_vertices <= 0)
     return GNNSTAGE_EINVAL;
   const bool classes = n_classes > 1 && idx != nullptr;
+  // class q = source ids [lo[q], lo[q + 1]); without explicit bounds: equal id ranges
+  std::vector<int64_t> lo((size_t)n_classes + 1);
+  for (int q = 0; q <= n_classes; ++q)
+    lo[(size_t)q] = class_lo ? class_lo[q] : ((int64_t)q * n_vertices + n_classes - 1) / n_classes;
+  if (lo[0] != 0 || lo[(size_t)n_classes] != n_vertices) return GNNSTAGE_EINVAL;
+  for (int q = 0; q < n_classes; ++q)
+    if (lo[(size_t)q] > lo[(size_t)q + 1]) return GNNSTAGE_EINVAL;
+  auto cls_of = [&](int64_t u) {  // last q with lo[q] <= u
+    int a = 0, b = n_classes;
+    while (b - a > 1) {
+      const int m = (a + b) / 2;
+      if (lo[(size_t)m] <= u) a = m; else b = m;
+    }
+    return (int64_t)a;
+  };
   std::vector<std::vector<Task>> by_class(classes ? n_classes : 1);
   std::vector<Task> pieces, whole;  // pieces without a class, whole rows
   int64_t slots = 0;
@@ -99,18 +114,21 @@ extern "C" int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, i
     }
     // maximal runs of entries whose source falls in the same id range (contiguous when the row is sorted);
     // a row whose columns are so unsorted that it has more runs than classes is cut without classes
-    int64_t runs = 1;
-    for (int64_t x = b + 1; x < e && runs <= n_classes; ++x)
-      if ((int64_t)idx[x] * n_classes / n_vertices != (int64_t)idx[x - 1] * n_classes / n_vertices) ++runs;
+    int64_t runs = 1, prev = cls_of(idx[b]);
+    for (int64_t x = b + 1; x < e && runs <= n_classes; ++x) {
+      const int64_t q = (idx[x] >= lo[(size_t)prev] && idx[x] < lo[(size_t)prev + 1]) ? prev : cls_of(idx[x]);
+      if (q != prev) ++runs;
+      prev = q;
+    }
     if (runs > n_classes) {
       cut(pieces, r, b, e);
       continue;
     }
     int64_t s0 = b;
     while (s0 < e) {
-      const int64_t cls = (int64_t)idx[s0] * n_classes / n_vertices;
+      const int64_t cls = cls_of(idx[s0]);
       int64_t s1 = s0 + 1;
-      while (s1 < e && (int64_t)idx[s1] * n_classes / n_vertices == cls) ++s1;
+      while (s1 < e && idx[s1] >= lo[(size_t)cls] && idx[s1] < lo[(size_t)cls + 1]) ++s1;
       cut(by_class[(size_t)cls], r, s0, s1);
       s0 = s1;
     }

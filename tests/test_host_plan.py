@@ -121,6 +121,29 @@ def test_launch_schedule_partitions_the_entries(split, classes):
     assert np.all(covered == 1)  # every entry belongs to exactly one task
 
 
+def test_launch_schedule_with_explicit_class_bounds():
+    """Class sections follow the given id bounds (here: uneven ones), not equal id ranges."""
+    g = _lib()
+    w = CONFIGS["c3_s"]
+    row_ptr, col = make_graph(w)
+    n = len(row_ptr) - 1
+    lo = np.array([0, n // 10, n // 2, n // 2 + 7, n], dtype=np.int64)
+    row, e0, ne, slot, n_slots, class_off, slot_class = g.gnnstage_plan_tasks(
+        row_ptr, 0, n, 128, idx=col, n_vertices=n, n_classes=4, class_min_row=8, return_classes=True, class_lo=lo)
+    covered = np.zeros(row_ptr[-1], dtype=np.int32)
+    for r, a, m in zip(row, e0, ne):
+        covered[a:a + m] += 1
+    assert np.all(covered == 1)
+    assert class_off[4] > 0
+    for q in range(4):
+        for i in range(class_off[q], class_off[q + 1]):
+            u = col[e0[i]:e0[i] + ne[i]]
+            assert ne[i] > 0 and u.min() >= lo[q] and u.max() < lo[q + 1] and slot_class[slot[i]] == q
+    with pytest.raises(g.GnnStageError):
+        g.gnnstage_plan_tasks(row_ptr, 0, n, 128, idx=col, n_vertices=n, n_classes=4, class_min_row=8,
+                              class_lo=np.array([0, 5, 3, 9, n]))  # not ascending
+
+
 def _desc(g, **over):
     n = 6
     row_ptr = np.array([0, 1, 2, 3, 4, 5, 6], dtype=np.int64)
