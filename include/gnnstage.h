@@ -181,6 +181,27 @@ int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, int64_t n_ve
                             int32_t *task_ne, int32_t *task_slot, int64_t *n_slots, int64_t *class_off,
                             uint8_t *slot_class);
 
+/* Dense-block plan of one aggregation direction (host only).  Power-law graphs keep most of their
+ * entries in a small, dense corner once rows and columns are ordered by degree: inside every chunk the
+ * rows are ordered by length, the vertices of every chunk by how often they occur as a column, and the
+ * matrix is cut into blocks of 128 rows x 64 columns in those orders.  Blocks with at least min_nnz
+ * entries are multiplied as dense tiles on the matrix cores; their entries leave the sparse index (the
+ * "remainder", same rows, same column order).  If fewer than min_share of all entries fall into such
+ * blocks the plan stays inactive (every array below empty).  gnnstage_dense_plan_get returns the length
+ * of one array of the plan and a pointer to it (valid until destroy):
+ *   0 rem_ptr (int64, n+1)   1 rem_idx (int32)   2 rem_orig (int64, position in the original index)
+ *   3 row_perm (int32, n: rows of chunk k in [chunk_ptr[k], chunk_ptr[k+1]), longest first)
+ *   4 cb_off (int64, K+1: column blocks of chunk c)   5 colslot_vertex (int32, 64 per column block, -1 = padding)
+ *   6 chunk_blk_off (int64, K+1: dense blocks whose rows are in chunk k)   7 blk_rb (int32, row block in its chunk)
+ *   8 blk_cb (int32, column block)   9 blk_e0 (int64, n_blocks+1)   10 ent_pos (uint16, row_in_block << 8 | col_in_block)
+ *   11 ent_orig (int64, position in the original index)                                                  */
+typedef struct gnnstage_dense_plan gnnstage_dense_plan;
+int gnnstage_dense_plan_create(const int64_t *ptr, const int32_t *idx, int64_t n_vertices, int32_t n_chunks,
+                               const int64_t *chunk_ptr, int32_t min_nnz, double min_share,
+                               gnnstage_dense_plan **out);
+int64_t gnnstage_dense_plan_get(const gnnstage_dense_plan *plan, int32_t what, const void **data);
+int gnnstage_dense_plan_destroy(gnnstage_dense_plan *plan);
+
 /*
  * Per-kernel timing with HIP events on the launch stream.  kind: 0 forward aggregation,
  * 1 forward transform, 2 backward transposed aggregation, 3 input-gradient GEMM,

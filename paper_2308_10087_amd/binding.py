@@ -78,6 +78,13 @@ def _load():
     lib.gnnstage_plan_tasks.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_int32,
                                         C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.POINTER(C.c_int64), C.c_void_p, C.c_void_p]
+    lib.gnnstage_dense_plan_create.restype = C.c_int
+    lib.gnnstage_dense_plan_create.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32,
+                                               C.c_double, C.POINTER(C.c_void_p)]
+    lib.gnnstage_dense_plan_get.restype = C.c_int64
+    lib.gnnstage_dense_plan_get.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_void_p)]
+    lib.gnnstage_dense_plan_destroy.restype = C.c_int
+    lib.gnnstage_dense_plan_destroy.argtypes = [C.c_void_p]
     lib.gnnstage_layer_order.restype = C.c_int
     lib.gnnstage_layer_order.argtypes = [C.c_void_p, C.c_int32]
     lib.gnnstage_profile_enable.restype = C.c_int
@@ -152,6 +159,39 @@ def gnnstage_plan_tasks(ptr: np.ndarray, row_begin: int, row_end: int, split_edg
     if return_classes:
         return row, e0, ne, slot, int(ns.value), class_off, slot_class[:int(ns.value)]
     return row, e0, ne, slot, int(ns.value)
+
+
+_DENSE_FIELDS = [("rem_ptr", np.int64), ("rem_idx", np.int32), ("rem_orig", np.int64), ("row_perm", np.int32),
+                 ("cb_off", np.int64), ("colslot_vertex", np.int32), ("chunk_blk_off", np.int64), ("blk_rb", np.int32),
+                 ("blk_cb", np.int32), ("blk_e0", np.int64), ("ent_pos", np.uint16), ("ent_orig", np.int64)]
+
+
+def gnnstage_dense_plan(ptr: np.ndarray, idx: np.ndarray, chunk_ptr: np.ndarray, min_nnz: int, min_share: float) -> dict:
+    """Dense-block plan of one aggregation direction as a dict of numpy arrays (copies); every array is
+    empty when the plan is inactive."""
+    ptr = np.ascontiguousarray(ptr, dtype=np.int64)
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    chunk_ptr = np.ascontiguousarray(chunk_ptr, dtype=np.int64)
+    h = C.c_void_p(None)
+    rc = lib.gnnstage_dense_plan_create(ptr.ctypes.data, idx.ctypes.data, ptr.shape[0] - 1, chunk_ptr.shape[0] - 1,
+                                        chunk_ptr.ctypes.data, int(min_nnz), float(min_share), C.byref(h))
+    if rc != 0:
+        raise GnnStageError(rc, "gnnstage_dense_plan_create")
+    out = {}
+    try:
+        for what, (name, dt) in enumerate(_DENSE_FIELDS):
+            data = C.c_void_p(None)
+            cnt = lib.gnnstage_dense_plan_get(h, what, C.byref(data))
+            if cnt < 0:
+                raise GnnStageError(int(cnt), "gnnstage_dense_plan_get")
+            if cnt == 0:
+                out[name] = np.zeros(0, dt)
+            else:
+                buf = (C.c_char * (cnt * np.dtype(dt).itemsize)).from_address(data.value)
+                out[name] = np.frombuffer(buf, dtype=dt).copy()
+    finally:
+        lib.gnnstage_dense_plan_destroy(h)
+    return out
 
 
 def _ptrs(tensors: Sequence) -> "C.Array":

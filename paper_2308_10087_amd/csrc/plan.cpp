@@ -4,7 +4,11 @@
 
 #include <vector>
 
+#include <algorithm>
+#include <numeric>
+
 #include "../../include/gnnstage.h"
+#include "plan.h"
 
 extern "C" int gnnstage_plan_transpose(int64_t n, const int64_t *row_ptr, const int32_t *col_idx, int64_t *t_ptr,
                                        int32_t *t_row, int64_t *t_edge) {
@@ -164,4 +168,172 @@ extern "C" int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, i
     }
   }
   return t;
+}
+
+// ---- dense blocks ------------------------------------------------------------------------------
+bool build_dense_plan(const int64_t *ptr, const int32_t *idx, int64_t n, int K, const int64_t *chunk_ptr,
+                      int min_nnz, double min_share, DensePlan &out) {
+  constexpr int RB = DensePlan::RB, CB = DensePlan::CB;
+  out = DensePlan();
+  out.n = n;
+  out.K = K;
+  out.nnz = ptr[n];
+  const int64_t nnz = out.nnz;
+  if (nnz == 0 || min_nnz <= 0) return true;
+  // how often every vertex occurs as a column
+  std::vector<int64_t> col_count((size_t)n, 0);
+  for (int64_t e = 0; e < nnz; ++e) {
+    const int64_t u = idx[e];
+    if (u < 0 || u >= n) return false;
+    col_count[(size_t)u]++;
+  }
+  // column slots: chunk by chunk, most frequent column first
+  std::vector<int64_t> cb_off((size_t)K + 1, 0);
+  for (int c = 0; c < K; ++c) cb_off[(size_t)c + 1] = cb_off[(size_t)c] + (chunk_ptr[c + 1] - chunk_ptr[c] + CB - 1) / CB;
+  const int64_t n_cb = cb_off[(size_t)K];
+  std::vector<int32_t> colslot_vertex((size_t)(n_cb * CB), -1);
+  std::vector<int64_t> slot_of((size_t)n);
+  std::vector<int32_t> order;
+  for (int c = 0; c < K; ++c) {
+    const int64_t a = chunk_ptr[c], b = chunk_ptr[c + 1];
+    order.resize((size_t)(b - a));
+    std::iota(order.begin(), order.end(), (int32_t)a);
+    std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return col_count[(size_t)x] > col_count[(size_t)y]; });
+    for (int64_t i = 0; i < b - a; ++i) {
+      const int64_t slot = cb_off[(size_t)c] * CB + i;
+      colslot_vertex[(size_t)slot] = order[(size_t)i];
+      slot_of[(size_t)order[(size_t)i]] = slot;
+    }
+  }
+  // rows of every chunk, longest first
+  std::vector<int32_t> row_perm((size_t)n);
+  std::vector<int64_t> rpos((size_t)n);  // position of a row inside its chunk
+  for (int c = 0; c < K; ++c) {
+    const int64_t a = chunk_ptr[c], b = chunk_ptr[c + 1];
+    std::iota(row_perm.begin() + a, row_perm.begin() + b, (int32_t)a);
+    std::stable_sort(row_perm.begin() + a, row_perm.begin() + b,
+                     [&](int32_t x, int32_t y) { return ptr[x + 1] - ptr[x] > ptr[y + 1] - ptr[y]; });
+    for (int64_t i = a; i < b; ++i) rpos[(size_t)row_perm[(size_t)i]] = i - a;
+  }
+  // pass 1: entries per block, chunk by chunk; blocks that reach min_nnz are dense
+  std::vector<int64_t> chunk_blk_off((size_t)K + 1, 0);
+  std::vector<int32_t> blk_rb, blk_cb;
+  std::vector<int64_t> blk_cnt;
+  std::vector<int32_t> counter;
+  int64_t dense_entries = 0;
+  for (int c = 0; c < K; ++c) {
+    const int64_t a = chunk_ptr[c], b = chunk_ptr[c + 1];
+    const int64_t n_rb = (b - a + RB - 1) / RB;
+    chunk_blk_off[(size_t)c + 1] = chunk_blk_off[(size_t)c];
+    if (n_rb == 0) continue;
+    if (n_rb * n_cb > ((int64_t)1 << 26)) return true;  // block grid too large to count: no dense path (plan stays inactive)
+    counter.assign((size_t)(n_rb * n_cb), 0);
+    for (int64_t r = a; r < b; ++r) {
+      const int64_t base = (rpos[(size_t)r] / RB) * n_cb;
+      for (int64_t e = ptr[r]; e < ptr[r + 1]; ++e) counter[(size_t)(base + slot_of[(size_t)idx[e]] / CB)]++;
+    }
+    for (int64_t k = 0; k < n_rb * n_cb; ++k)
+      if (counter[(size_t)k] >= min_nnz) {
+        blk_rb.push_back((int32_t)(k / n_cb));
+        blk_cb.push_back((int32_t)(k % n_cb));
+        blk_cnt.push_back(counter[(size_t)k]);
+        dense_entries += counter[(size_t)k];
+      }
+    chunk_blk_off[(size_t)c + 1] = (int64_t)blk_rb.size();
+  }
+  if (blk_rb.empty() || (double)dense_entries < min_share * (double)nnz) return true;
+  // pass 2: split the entries
+  const int64_t nb = (int64_t)blk_rb.size();
+  out.active = true;
+  out.blk_e0.assign((size_t)nb + 1, 0);
+  for (int64_t i = 0; i < nb; ++i) out.blk_e0[(size_t)i + 1] = out.blk_e0[(size_t)i] + blk_cnt[(size_t)i];
+  out.ent_pos.resize((size_t)dense_entries);
+  out.ent_orig.resize((size_t)dense_entries);
+  out.rem_ptr.assign((size_t)n + 1, 0);
+  out.rem_idx.reserve((size_t)(nnz - dense_entries));
+  out.rem_orig.reserve((size_t)(nnz - dense_entries));
+  std::vector<int64_t> cursor(out.blk_e0.begin(), out.blk_e0.end() - 1);
+  std::vector<int64_t> block_of;  // block index + 1 per (row block, column block) of the current chunk
+  for (int c = 0; c < K; ++c) {
+    const int64_t a = chunk_ptr[c], b = chunk_ptr[c + 1];
+    const int64_t n_rb = (b - a + RB - 1) / RB;
+    block_of.assign((size_t)(n_rb * n_cb), 0);
+    for (int64_t i = chunk_blk_off[(size_t)c]; i < chunk_blk_off[(size_t)c + 1]; ++i)
+      block_of[(size_t)((int64_t)blk_rb[(size_t)i] * n_cb + blk_cb[(size_t)i])] = i + 1;
+    for (int64_t r = a; r < b; ++r) {
+      const int64_t rb = rpos[(size_t)r] / RB, rl = rpos[(size_t)r] % RB;
+      for (int64_t e = ptr[r]; e < ptr[r + 1]; ++e) {
+        const int64_t slot = slot_of[(size_t)idx[e]];
+        const int64_t bi = block_of[(size_t)(rb * n_cb + slot / CB)];
+        if (bi > 0) {
+          const int64_t at = cursor[(size_t)(bi - 1)]++;
+          out.ent_pos[(size_t)at] = (uint16_t)((rl << 8) | (slot % CB));
+          out.ent_orig[(size_t)at] = e;
+        } else {
+          out.rem_idx.push_back(idx[e]);
+          out.rem_orig.push_back(e);
+        }
+      }
+      out.rem_ptr[(size_t)r + 1] = (int64_t)out.rem_idx.size();
+    }
+  }
+  out.row_perm.swap(row_perm);
+  out.cb_off.swap(cb_off);
+  out.colslot_vertex.swap(colslot_vertex);
+  out.chunk_blk_off.swap(chunk_blk_off);
+  out.blk_rb.swap(blk_rb);
+  out.blk_cb.swap(blk_cb);
+  return true;
+}
+
+struct gnnstage_dense_plan {
+  DensePlan p;
+};
+
+extern "C" int gnnstage_dense_plan_create(const int64_t *ptr, const int32_t *idx, int64_t n_vertices, int32_t n_chunks,
+                                          const int64_t *chunk_ptr, int32_t min_nnz, double min_share,
+                                          gnnstage_dense_plan **out) {
+  if (!ptr || !chunk_ptr || !out || n_vertices <= 0 || n_chunks <= 0 || (ptr[n_vertices] > 0 && !idx)) return GNNSTAGE_EINVAL;
+  if (chunk_ptr[0] != 0 || chunk_ptr[n_chunks] != n_vertices) return GNNSTAGE_EINVAL;
+  for (int c = 0; c < n_chunks; ++c)
+    if (chunk_ptr[c] > chunk_ptr[c + 1]) return GNNSTAGE_EINVAL;
+  gnnstage_dense_plan *h = new gnnstage_dense_plan();
+  if (!build_dense_plan(ptr, idx, n_vertices, n_chunks, chunk_ptr, min_nnz, min_share, h->p)) {
+    delete h;
+    return GNNSTAGE_EINVAL;
+  }
+  *out = h;
+  return GNNSTAGE_OK;
+}
+
+extern "C" int64_t gnnstage_dense_plan_get(const gnnstage_dense_plan *h, int32_t what, const void **data) {
+  if (!h || !data) return GNNSTAGE_EINVAL;
+  const DensePlan &p = h->p;
+#define GIVE(v)                 \
+  do {                          \
+    *data = (v).data();         \
+    return (int64_t)(v).size(); \
+  } while (0)
+  switch (what) {
+    case 0: GIVE(p.rem_ptr);
+    case 1: GIVE(p.rem_idx);
+    case 2: GIVE(p.rem_orig);
+    case 3: GIVE(p.row_perm);
+    case 4: GIVE(p.cb_off);
+    case 5: GIVE(p.colslot_vertex);
+    case 6: GIVE(p.chunk_blk_off);
+    case 7: GIVE(p.blk_rb);
+    case 8: GIVE(p.blk_cb);
+    case 9: GIVE(p.blk_e0);
+    case 10: GIVE(p.ent_pos);
+    case 11: GIVE(p.ent_orig);
+    default: return GNNSTAGE_EINVAL;
+  }
+#undef GIVE
+}
+
+extern "C" int gnnstage_dense_plan_destroy(gnnstage_dense_plan *h) {
+  if (!h) return GNNSTAGE_EINVAL;
+  delete h;
+  return GNNSTAGE_OK;
 }

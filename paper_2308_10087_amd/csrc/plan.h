@@ -1,0 +1,38 @@
+// Host-side plans shared between plan.cpp (which builds them) and the stage (which uploads them).
+#pragma once
+#include <stdint.h>
+
+#include <vector>
+
+// Dense-block plan of one aggregation direction (a sparse index ptr/idx over n vertices, rows grouped
+// into K chunks).  Inside a chunk the rows are ordered by length, the vertices of every chunk are
+// ordered by how often they occur as a column, and the matrix is cut into RB x CB blocks in those
+// orders.  Blocks with at least min_nnz entries are "dense": their entries leave the sparse index and
+// are multiplied on the matrix cores as small dense products; everything else stays in the remainder.
+struct DensePlan {
+  static constexpr int RB = 128, CB = 64;
+  int64_t n = 0, nnz = 0;
+  int K = 0;
+  bool active = false;  // false: no dense blocks, the remainder is the whole index (arrays below empty)
+  // remainder (same rows, same column order inside a row)
+  std::vector<int64_t> rem_ptr;    // n + 1
+  std::vector<int32_t> rem_idx;    // column of every remainder entry
+  std::vector<int64_t> rem_orig;   // its position in the original index
+  // orders
+  std::vector<int32_t> row_perm;        // n: chunk k occupies [chunk_ptr[k], chunk_ptr[k+1]), longest row first
+  std::vector<int64_t> cb_off;          // K + 1: column blocks of chunk c are [cb_off[c], cb_off[c+1])
+  std::vector<int32_t> colslot_vertex;  // cb_off[K] * CB: vertex in every column slot, -1 = padding
+  // dense blocks, sorted by (row chunk, row block, column block)
+  std::vector<int64_t> chunk_blk_off;   // K + 1: blocks whose rows are in chunk k
+  std::vector<int32_t> blk_rb;          // row block inside its chunk (rows row_perm[chunk_ptr[k] + RB*rb ...])
+  std::vector<int32_t> blk_cb;          // column block (global numbering, see cb_off)
+  std::vector<int64_t> blk_e0;          // n_blocks + 1: entries of a block
+  std::vector<uint16_t> ent_pos;        // (row inside the block) << 8 | column inside the block
+  std::vector<int64_t> ent_orig;        // position in the original index
+  int64_t n_blocks() const { return (int64_t)blk_rb.size(); }
+};
+
+// min_share: the plan is only activated when at least this share of all entries falls into dense blocks.
+// Returns false on invalid input (an index entry outside [0, n)).
+bool build_dense_plan(const int64_t *ptr, const int32_t *idx, int64_t n, int K, const int64_t *chunk_ptr,
+                      int min_nnz, double min_share, DensePlan &out);

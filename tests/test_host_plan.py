@@ -144,6 +144,58 @@ def test_launch_schedule_with_explicit_class_bounds():
                               class_lo=np.array([0, 5, 3, 9, n]))  # not ascending
 
 
+@pytest.mark.parametrize("name,min_nnz", [("c1_s", 40), ("c3_s", 12), ("c0", 3)])
+def test_dense_plan_partitions_the_entries(name, min_nnz):
+    """Dense blocks + remainder hold every entry exactly once, at the right (row, column); rows and columns
+    of a block come from one chunk each; every dense block reaches the threshold."""
+    g = _lib()
+    w = CONFIGS[name]
+    row_ptr, col = make_graph(w)
+    n = len(row_ptr) - 1
+    chunk_ptr = graphs.ragged_chunks(n, 5, 3)
+    d = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, min_nnz, 0.0)
+    assert len(d["blk_rb"]) > 0, "threshold too high for this graph: nothing to check"
+    rows_of_entry = np.repeat(np.arange(n), np.diff(row_ptr))
+    seen = np.zeros(row_ptr[-1], dtype=np.int32)
+    # remainder: same rows, original order, columns unchanged
+    seen[d["rem_orig"]] += 1
+    assert np.array_equal(d["rem_idx"], col[d["rem_orig"]])
+    assert np.array_equal(np.repeat(np.arange(n), np.diff(d["rem_ptr"])), rows_of_entry[d["rem_orig"]])
+    assert np.all(np.diff(d["rem_orig"]) > 0)
+    # orders are permutations inside every chunk, sorted by length / column frequency
+    col_count = np.bincount(col, minlength=n)
+    for c in range(5):
+        a, b = chunk_ptr[c], chunk_ptr[c + 1]
+        rp = d["row_perm"][a:b]
+        assert np.array_equal(np.sort(rp), np.arange(a, b))
+        assert np.all(np.diff(np.diff(row_ptr)[rp]) <= 0)
+        slots = d["colslot_vertex"][d["cb_off"][c] * 64:d["cb_off"][c + 1] * 64]
+        real = slots[slots >= 0]
+        assert np.array_equal(np.sort(real), np.arange(a, b)) and np.all(slots[len(real):] == -1)
+        assert np.all(np.diff(col_count[real]) <= 0)
+    # dense entries decode to their original (row, column)
+    for k in range(5):
+        for bi in range(d["chunk_blk_off"][k], d["chunk_blk_off"][k + 1]):
+            e0, e1 = d["blk_e0"][bi], d["blk_e0"][bi + 1]
+            assert e1 - e0 >= min_nnz
+            pos = d["ent_pos"][e0:e1].astype(np.int64)
+            r = d["row_perm"][chunk_ptr[k] + 128 * d["blk_rb"][bi] + (pos >> 8)]
+            u = d["colslot_vertex"][64 * d["blk_cb"][bi] + (pos & 255)]
+            orig = d["ent_orig"][e0:e1]
+            assert np.all((pos & 255) < 64) and np.all((pos >> 8) < 128)
+            assert np.array_equal(r, rows_of_entry[orig]) and np.array_equal(u, col[orig])
+            seen[orig] += 1
+    assert np.all(seen == 1)
+    # blocks are sorted by (row chunk, row block, column block)
+    for k in range(5):
+        s0, s1 = d["chunk_blk_off"][k], d["chunk_blk_off"][k + 1]
+        key = d["blk_rb"][s0:s1].astype(np.int64) * (1 << 32) + d["blk_cb"][s0:s1]
+        assert np.all(np.diff(key) > 0)
+    # an unreachable share leaves the plan inactive
+    off = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, min_nnz, 1.1)
+    assert all(len(v) == 0 for v in off.values())
+
+
 def _desc(g, **over):
     n = 6
     row_ptr = np.array([0, 1, 2, 3, 4, 5, 6], dtype=np.int64)
