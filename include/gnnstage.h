@@ -154,6 +154,10 @@ int gnnstage_debug_select_counts(gnnstage_t *st, int32_t chunk_id, int32_t *out)
  */
 int gnnstage_layer_order(const gnnstage_t *st, int32_t layer);
 
+/* Diagnostics: how many entries of the (transposed != 0: transposed) index are multiplied as dense blocks
+ * (see gnnstage_dense_plan_create below); 0 when the stage does not use them. */
+int64_t gnnstage_dense_entries(const gnnstage_t *st, int32_t transposed);
+
 /*
  * Host-only planning helpers (no GPU needed), exported so that the integer bookkeeping can be
  * checked on a CPU: the transposed index (column u -> rows v ascending, with the position of
@@ -170,6 +174,8 @@ int gnnstage_plan_pack(int64_t n, int64_t nnz, const int32_t *idx, int32_t n_chu
  * (class q = source ids [class_lo[q], class_lo[q + 1]), n_classes + 1 ascending bounds from 0 to n_vertices;
  * class_lo == NULL means equal id ranges), so that each piece gathers from one slice of the source
  * table.  Every piece carries the index of the fp32 partial-sum slot it writes (consecutive per row).
+ * force_slot (one byte per vertex, may be NULL) marks rows whose sum has parts outside this index: such a row
+ * always writes partial sums (never the finished row), and gets no task at all when it is empty here.
  * Tasks are emitted class-major: the pieces of class 0, ..., class n_classes-1, then pieces without a
  * class, then whole rows; class_off (n_classes + 1 entries, may be NULL) receives where each class
  * section starts (the last entry is the start of the class-less tail) and slot_class (one byte per slot,
@@ -177,9 +183,9 @@ int gnnstage_plan_pack(int64_t n, int64_t nnz, const int32_t *idx, int32_t n_chu
  * with non-NULL task arrays also fills them (capacity checked).  idx may be NULL when n_classes == 1. */
 int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, int64_t n_vertices, int64_t row_begin,
                             int64_t row_end, int32_t split_edges, int32_t n_classes, const int64_t *class_lo,
-                            int32_t class_min_row, int64_t capacity, int32_t *task_row, int64_t *task_e0,
-                            int32_t *task_ne, int32_t *task_slot, int64_t *n_slots, int64_t *class_off,
-                            uint8_t *slot_class);
+                            int32_t class_min_row, const uint8_t *force_slot, int64_t capacity, int32_t *task_row,
+                            int64_t *task_e0, int32_t *task_ne, int32_t *task_slot, int64_t *n_slots,
+                            int64_t *class_off, uint8_t *slot_class);
 
 /* Dense-block plan of one aggregation direction (host only).  Power-law graphs keep most of their
  * entries in a small, dense corner once rows and columns are ordered by degree: inside every chunk the

@@ -76,7 +76,7 @@ def _load():
                                        C.POINTER(C.c_int32)]
     lib.gnnstage_plan_tasks.restype = C.c_int64
     lib.gnnstage_plan_tasks.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_int32,
-                                        C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.POINTER(C.c_int64), C.c_void_p, C.c_void_p]
     lib.gnnstage_dense_plan_create.restype = C.c_int
     lib.gnnstage_dense_plan_create.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32,
@@ -85,6 +85,8 @@ def _load():
     lib.gnnstage_dense_plan_get.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_void_p)]
     lib.gnnstage_dense_plan_destroy.restype = C.c_int
     lib.gnnstage_dense_plan_destroy.argtypes = [C.c_void_p]
+    lib.gnnstage_dense_entries.restype = C.c_int64
+    lib.gnnstage_dense_entries.argtypes = [C.c_void_p, C.c_int32]
     lib.gnnstage_layer_order.restype = C.c_int
     lib.gnnstage_layer_order.argtypes = [C.c_void_p, C.c_int32]
     lib.gnnstage_profile_enable.restype = C.c_int
@@ -132,8 +134,12 @@ def gnnstage_plan_pack(n: int, idx: np.ndarray, chunk_ptr: np.ndarray):
 
 def gnnstage_plan_tasks(ptr: np.ndarray, row_begin: int, row_end: int, split_edges: int, idx=None,
                         n_vertices: int = 0, n_classes: int = 1, class_min_row: int = 0, return_classes: bool = False,
-                        class_lo=None):
+                        class_lo=None, force_slot=None):
     ptr = np.ascontiguousarray(ptr, dtype=np.int64)
+    if force_slot is not None:
+        force_slot = np.ascontiguousarray(force_slot, dtype=np.uint8)
+        assert force_slot.shape[0] == ptr.shape[0] - 1
+    fs = None if force_slot is None else force_slot.ctypes.data
     if class_lo is not None:
         class_lo = np.ascontiguousarray(class_lo, dtype=np.int64)
         assert class_lo.shape[0] == n_classes + 1
@@ -144,7 +150,7 @@ def gnnstage_plan_tasks(ptr: np.ndarray, row_begin: int, row_end: int, split_edg
     nv = n_vertices if n_vertices > 0 else ptr.shape[0] - 1
     ns = C.c_int64(0)
     n = lib.gnnstage_plan_tasks(ptr.ctypes.data, ip, nv, row_begin, row_end, split_edges, n_classes, lo, class_min_row,
-                                0, None, None, None, None, C.byref(ns), None, None)
+                                fs, 0, None, None, None, None, C.byref(ns), None, None)
     if n < 0:
         raise GnnStageError(int(n), "gnnstage_plan_tasks")
     row, e0 = np.zeros(n, np.int32), np.zeros(n, np.int64)
@@ -152,7 +158,7 @@ def gnnstage_plan_tasks(ptr: np.ndarray, row_begin: int, row_end: int, split_edg
     class_off = np.zeros(n_classes + 1, np.int64)
     slot_class = np.zeros(max(int(ns.value), 1), np.uint8)
     got = lib.gnnstage_plan_tasks(ptr.ctypes.data, ip, nv, row_begin, row_end, split_edges, n_classes, lo,
-                                  class_min_row, n, row.ctypes.data, e0.ctypes.data, ne.ctypes.data, slot.ctypes.data, C.byref(ns),
+                                  class_min_row, fs, n, row.ctypes.data, e0.ctypes.data, ne.ctypes.data, slot.ctypes.data, C.byref(ns),
                                   class_off.ctypes.data, slot_class.ctypes.data)
     if got != n:
         raise GnnStageError(int(got), "gnnstage_plan_tasks")
@@ -289,6 +295,9 @@ class GnnStage:
         if rc < 0:
             raise GnnStageError(rc, "gnnstage_layer_order")
         return rc
+
+    def gnnstage_dense_entries(self, transposed: bool = False) -> int:
+        return int(lib.gnnstage_dense_entries(self._h, int(transposed)))
 
     def gnnstage_profile_enable(self, on: bool) -> None:
         self._check(lib.gnnstage_profile_enable(self._h, int(on)))

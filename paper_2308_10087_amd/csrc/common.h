@@ -54,6 +54,14 @@ struct SpmmArgs {
   const int32_t *lr_nslots;
   int64_t n_long;
   float *partial;  // [n_slots][d] fp32
+  // dense-block partial sums of a cut row: rows lr_dense0[i] + 128 * g (g < lr_ndense[i]) of dense_partial,
+  // one per item of the row's row block; lr_item0[i] is the first of those items (for the activity test)
+  const int32_t *lr_dense0;
+  const int32_t *lr_ndense;
+  const int32_t *lr_item0;
+  const ChunkMask *item_chunks;
+  const float *dense_partial;
+  int32_t drop_unselected;  // the launch skips unselected entries: items without a chunk in the mask were not run
   // gathered operand: rows of width d, leading dimension src_ld
   const void *src_sel;    // read when the neighbour's chunk is in the mask
   const void *src_unsel;  // read otherwise; nullptr => the entry contributes zero
@@ -93,6 +101,40 @@ __device__ inline int64_t spmm_task_index(const SpmmArgs &a, unsigned b, int wav
   const int64_t t = a.tail_task0 + (int64_t)(b - a.n_class_blocks) * 4 + wave;
   return t < a.n_tasks ? t : -1;
 }
+
+// ---- dense blocks of an aggregation (bf16 rows of width 128 or 256) ---------------------------
+// After ordering rows and columns by degree, the blocks that hold many entries are multiplied as dense
+// 128 x 64 tiles on the matrix cores; the sparse kernels above only see the remaining entries.  An item
+// is a run of blocks of one row block; it leaves a 128 x d fp32 tile of partial sums that the reduce
+// kernel adds to the rows' sparse pieces.
+constexpr int kDenseRB = 128, kDenseCB = 64;
+constexpr int kDenseMaxItemBlocks = 32;  // blocks one workgroup multiplies before it writes its partial tile
+struct DenseArgs {
+  const int32_t *item_rb;         // row block (inside the chunk) of every item of this launch
+  const int64_t *item_b0;         // its first block
+  const int32_t *item_nb;         // and how many
+  const ChunkMask *item_chunks;   // chunks its blocks' columns come from
+  int32_t n_items;
+  const int32_t *blk_cb;          // column block of every block: column slots 64 * cb ...
+  const bf16_t *tiles;            // per block two row-major 128 x 64 weight tiles: nearest bf16, then the remainder's bf16
+  // weights of the form s(row) * s(column) instead (bits != nullptr): per block 256 words of pattern bits
+  // (word t: row t / 2, columns 32 * (t % 2) ..), s per column slot (0 = padding) and per row position of the chunk
+  const uint32_t *bits;
+  const float *colscale;
+  const float *rowscale;          // [row blocks of the chunk * 128], zero past the chunk's last row
+  const uint32_t *colslot;        // vertex | chunk << vbits of every column slot, 0xffffffff = padding
+  const void *src_sel;            // rows of vertices whose chunk is in the mask
+  const void *src_unsel;          // rows of the others; nullptr => they contribute zero
+  int32_t d, src_ld, vbits;
+  ChunkMask mask;
+  float *partial;                 // [n_items][128][d]
+};
+int launch_spmm_dense(const DenseArgs &a, hipStream_t s);
+// Writes the weight tiles of n_blocks blocks (cleared by the caller) from their entry lists: entries
+// [blk_e0[b], blk_e0[b + 1]) of block b, position = row << 8 | column (0xffff = padding), weight as two bf16
+// halves (nearest bf16 in the low half of the word, the remainder's bf16 in the high half).
+int launch_dense_expand(const int64_t *blk_e0, const uint16_t *ent_pos, const uint32_t *ent_w, void *tiles, int64_t n_blocks,
+                        hipStream_t s);
 
 enum DType : int { DT_F32 = 0, DT_BF16 = 1 };
 

@@ -1,0 +1,391 @@
+// Dense blocks of the neighbour aggregation on the matrix cores (Algorithm 1, the AGGREGATE line, for
+// the part of a power-law graph that is dense once rows and columns are ordered by degree).
+//
+// Every dense block is kept in memory as two 128 x 64 bf16 tiles: the nearest bf16 of every weight and
+// the bf16 of the remainder (weights keep 16 mantissa bits, as in the sparse kernel); an expand kernel
+// writes them once from the block's entry list when the stage is created.
+//
+// One workgroup per (item, 128-column half of the rows' width).  An item owns the 128 x 128 fp32
+// accumulator tile of one row block (in registers) and walks over its dense blocks.  For every block it
+//   * copies the two weight tiles to LDS (16-byte pieces, rows padded to 144 bytes),
+//   * loads the 64 source rows of the block's column slots (current or historical buffer by the
+//     source's chunk, Section 3.3; zero for padding slots and for unselected sources of a backward
+//     launch, Section 3.4) and stores them to LDS with consecutive source pairs interleaved, which makes
+//     the k-contiguous B fragments of v_mfma_f32_32x32x16_bf16 four 4-byte reads,
+//   * multiplies: acc += W_hi . H + W_lo . H.
+// The loads of the next block are issued before the current one is multiplied.  Blocks whose columns
+// all come from an unselected chunk are skipped in a backward launch, items with no selected block leave
+// without writing (the reduce kernel applies the same test).
+#include "common.h"
+
+namespace {
+
+typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int A_PITCH = 72;  // bf16 elements per weight-tile row in LDS: 144 bytes keep 16-byte fragment reads conflict-free
+constexpr int DH = 128;      // columns one workgroup owns
+constexpr int TILE_ELEMS = kDenseRB * kDenseCB;  // one weight tile in memory (row-major, no padding)
+
+__device__ inline bool masks_meet(const ChunkMask &x, const ChunkMask &y) {
+  return ((x.w[0] & y.w[0]) | (x.w[1] & y.w[1]) | (x.w[2] & y.w[2]) | (x.w[3] & y.w[3])) != 0;
+}
+
+// tiles[b] (cleared beforehand) <- entries of block b; one workgroup per block
+__global__ __launch_bounds__(256) void dense_expand_kernel(const int64_t *blk_e0, const uint16_t *ent_pos,
+                                                          const uint32_t *ent_w, uint16_t *tiles) {
+  const int64_t b = blockIdx.x;
+  uint16_t *hi = tiles + (size_t)b * 2 * TILE_ELEMS, *lo = hi + TILE_ELEMS;
+  for (int64_t e = blk_e0[b] + threadIdx.x; e < blk_e0[b + 1]; e += 256) {
+    const uint32_t pos = ent_pos[e], w = ent_w[e];
+    if (pos == 0xffffu) continue;  // padding of the entry list
+    const int at = (int)(pos >> 8) * kDenseCB + (int)(pos & 255u);
+    hi[at] = (uint16_t)(w & 0xffffu);
+    lo[at] = (uint16_t)(w >> 16);
+  }
+}
+
+__global__ __launch_bounds__(256, 2) void spmm_dense_kernel(const DenseArgs a) {
+  constexpr int NI = 2;              // 32-column tiles per wave (a wave owns 64 x 64 of the 128 x 128 tile)
+  constexpr int GROUPS = DH / 8;     // 16-byte pieces per source half-row
+  constexpr int SETS = 64 / GROUPS;  // source pairs one wave instruction covers
+  constexpr int PPL = 8 / SETS;      // source pairs per lane (a wave stages 8 of the 32 pairs)
+  extern __shared__ __attribute__((aligned(16))) unsigned char dense_smem[];
+  bf16_t *A_hi = reinterpret_cast<bf16_t *>(dense_smem);
+  bf16_t *A_lo = A_hi + kDenseRB * A_PITCH;
+  uint32_t *Hp = reinterpret_cast<uint32_t *>(A_lo + kDenseRB * A_PITCH);  // [32 source pairs][DH] interleaved pairs
+  uint32_t *ids = Hp + 32 * DH;                                           // [blocks of the item][64] column slots
+  int32_t *m_cb = reinterpret_cast<int32_t *>(ids + kDenseMaxItemBlocks * kDenseCB);
+
+  const int item = blockIdx.x;
+  const int col0 = blockIdx.y * DH;
+  const bool drop = a.src_unsel == nullptr;
+  if (drop && !masks_meet(a.item_chunks[item], a.mask)) return;  // whole workgroup
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  const uint32_t vmask = (1u << a.vbits) - 1u;
+  const int64_t b0 = a.item_b0[item];
+  const int nb = a.item_nb[item];
+  const bf16_t *src_sel = static_cast<const bf16_t *>(a.src_sel) + col0;
+  const bf16_t *src_unsel = drop ? nullptr : static_cast<const bf16_t *>(a.src_unsel) + col0;
+  const size_t ld = (size_t)a.src_ld;
+
+  // the item's column slots go to LDS once, so that all loads of a block can be issued at once
+  if (tid < nb) m_cb[tid] = a.blk_cb[b0 + tid];
+  __syncthreads();
+  for (int i = tid; i < nb * kDenseCB; i += 256) ids[i] = a.colslot[(int64_t)m_cb[i >> 6] * kDenseCB + (i & 63)];
+  __syncthreads();
+
+  f32x16 acc[2][NI];
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int t = 0; t < 16; ++t) acc[mi][ni][t] = 0.f;
+
+  const int ng = lane % GROUPS, set = lane / GROUPS;
+  // registers that carry one block from its loads to LDS: the source rows of this wave's 8 pairs and this
+  // thread's 16-byte pieces of the two weight tiles
+  u32x4 x0[PPL], x1[PPL], th[4], tl[4];
+  auto next_active = [&](int bi) {  // wave-uniform: slot 0 of a block is never padding
+    while (bi < nb && drop && !mask_test(a.mask, ids[bi * kDenseCB] >> a.vbits)) ++bi;
+    return bi;
+  };
+  auto issue = [&](int bi) {
+    const u32x4 *tile = reinterpret_cast<const u32x4 *>(a.tiles + (size_t)(b0 + bi) * 2 * TILE_ELEMS);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      th[j] = tile[tid + 256 * j];
+      tl[j] = tile[TILE_ELEMS / 8 + tid + 256 * j];
+    }
+#pragma unroll
+    for (int j = 0; j < PPL; ++j) {
+      const int kp = wave * 8 + j * SETS + set;
+      const uint32_t pc0 = ids[bi * kDenseCB + 2 * kp], pc1 = ids[bi * kDenseCB + 2 * kp + 1];
+      x0[j] = u32x4{0u, 0u, 0u, 0u};
+      x1[j] = u32x4{0u, 0u, 0u, 0u};
+      if (pc0 != 0xffffffffu) {
+        const bool sel = mask_test(a.mask, pc0 >> a.vbits);
+        if (sel || !drop) x0[j] = *reinterpret_cast<const u32x4 *>((sel ? src_sel : src_unsel) + (size_t)(pc0 & vmask) * ld + ng * 8);
+      }
+      if (pc1 != 0xffffffffu) {
+        const bool sel = mask_test(a.mask, pc1 >> a.vbits);
+        if (sel || !drop) x1[j] = *reinterpret_cast<const u32x4 *>((sel ? src_sel : src_unsel) + (size_t)(pc1 & vmask) * ld + ng * 8);
+      }
+    }
+  };
+
+  int cur = next_active(0);
+  if (cur < nb) issue(cur);
+  while (cur < nb) {
+    const int nxt = next_active(cur + 1);
+    __syncthreads();  // the previous block's fragment reads are done
+    // weight tiles: piece i covers row i / 8, columns 8 * (i % 8) ..
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int i = tid + 256 * j;
+      const int at = (i >> 3) * A_PITCH + (i & 7) * 8;
+      *reinterpret_cast<u32x4 *>(A_hi + at) = th[j];
+      *reinterpret_cast<u32x4 *>(A_lo + at) = tl[j];
+    }
+    // source rows: word n of pair kp holds (row 2kp, row 2kp+1) at column n
+#pragma unroll
+    for (int j = 0; j < PPL; ++j) {
+      const int kp = wave * 8 + j * SETS + set;
+      u32x4 lo4, hi4;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        lo4[2 * q] = __builtin_amdgcn_perm(x1[j][q], x0[j][q], 0x05040100u);      // column 2q of this lane's eight
+        lo4[2 * q + 1] = __builtin_amdgcn_perm(x1[j][q], x0[j][q], 0x07060302u);  // column 2q + 1
+        hi4[2 * q] = __builtin_amdgcn_perm(x1[j][q + 2], x0[j][q + 2], 0x05040100u);
+        hi4[2 * q + 1] = __builtin_amdgcn_perm(x1[j][q + 2], x0[j][q + 2], 0x07060302u);
+      }
+      u32x4 *dst = reinterpret_cast<u32x4 *>(Hp + (size_t)kp * DH + ng * 8);
+      dst[0] = lo4;
+      dst[1] = hi4;
+    }
+    __syncthreads();  // weights and source rows are in place
+    if (nxt < nb) issue(nxt);  // the next block's loads fly while this one is multiplied
+#pragma unroll
+    for (int ks = 0; ks < kDenseCB / 16; ++ks) {
+      bf16x8 fh[2], fl[2], fb[NI];
+      const int koff = ks * 16 + (lane >> 5) * 8;
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi) {
+        fh[mi] = *reinterpret_cast<const bf16x8 *>(&A_hi[(wm + mi * 32 + (lane & 31)) * A_PITCH + koff]);
+        fl[mi] = *reinterpret_cast<const bf16x8 *>(&A_lo[(wm + mi * 32 + (lane & 31)) * A_PITCH + koff]);
+      }
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni) {
+        u32x4 w4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w4[j] = Hp[(size_t)(ks * 8 + (lane >> 5) * 4 + j) * DH + wn + ni * 32 + (lane & 31)];
+        fb[ni] = __builtin_bit_cast(bf16x8, w4);
+      }
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fh[mi], fb[ni], acc[mi][ni], 0, 0, 0);
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fl[mi], fb[ni], acc[mi][ni], 0, 0, 0);
+    }
+    cur = nxt;
+  }
+  // 32x32 accumulator layout: element t of lane l is row 8*(t/4) + 4*(l/32) + t%4, column l%32
+  float *P = a.partial + (size_t)item * kDenseRB * a.d + col0;
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int t = 0; t < 16; ++t) {
+        const int r = wm + mi * 32 + 8 * (t >> 2) + 4 * (lane >> 5) + (t & 3);
+        P[(size_t)r * a.d + wn + ni * 32 + (lane & 31)] = acc[mi][ni][t];
+      }
+}
+
+// The same product for weights of the form w(v, u) = s(v) * s(u) (the normalisation of Section 2.1 computed
+// by the library itself): a block is then a 0/1 pattern (kept as 128 x 64 bits), the source rows are scaled
+// by s(u) while they are staged - in fp32, split into the nearest bf16 and the bf16 of the remainder - and
+// the accumulator rows are scaled by s(v) at the end:  out[v] = s(v) * sum_u P(v, u) * (s(u) h(u)).
+__global__ __launch_bounds__(256, 2) void spmm_dense_r1_kernel(const DenseArgs a) {
+  constexpr int NI = 2;
+  constexpr int GROUPS = DH / 8;
+  constexpr int SETS = 64 / GROUPS;
+  constexpr int PPL = 8 / SETS;
+  extern __shared__ __attribute__((aligned(16))) unsigned char dense_smem[];
+  bf16_t *A01 = reinterpret_cast<bf16_t *>(dense_smem);                    // [128][A_PITCH] zeros and ones
+  uint32_t *Hh = reinterpret_cast<uint32_t *>(A01 + kDenseRB * A_PITCH);  // [32 source pairs][DH], upper parts
+  uint32_t *Hl = Hh + 32 * DH;                                            // lower parts
+  uint32_t *ids = Hl + 32 * DH;                                           // [blocks of the item][64] column slots
+  int32_t *m_cb = reinterpret_cast<int32_t *>(ids + kDenseMaxItemBlocks * kDenseCB);
+
+  const int item = blockIdx.x;
+  const int col0 = blockIdx.y * DH;
+  const bool drop = a.src_unsel == nullptr;
+  if (drop && !masks_meet(a.item_chunks[item], a.mask)) return;  // whole workgroup
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  const uint32_t vmask = (1u << a.vbits) - 1u;
+  const int64_t b0 = a.item_b0[item];
+  const int nb = a.item_nb[item];
+  const bf16_t *src_sel = static_cast<const bf16_t *>(a.src_sel) + col0;
+  const bf16_t *src_unsel = drop ? nullptr : static_cast<const bf16_t *>(a.src_unsel) + col0;
+  const size_t ld = (size_t)a.src_ld;
+
+  if (tid < nb) m_cb[tid] = a.blk_cb[b0 + tid];
+  __syncthreads();
+  for (int i = tid; i < nb * kDenseCB; i += 256) ids[i] = a.colslot[(int64_t)m_cb[i >> 6] * kDenseCB + (i & 63)];
+  __syncthreads();
+
+  f32x16 acc[2][NI];
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int t = 0; t < 16; ++t) acc[mi][ni][t] = 0.f;
+
+  const int ng = lane % GROUPS, set = lane / GROUPS;
+  u32x4 x0[PPL], x1[PPL];
+  float s0[PPL], s1[PPL];
+  uint32_t bits = 0;  // this thread's 32 cells of the pattern: row tid / 2, columns 32 * (tid % 2) ..
+  auto next_active = [&](int bi) {
+    while (bi < nb && drop && !mask_test(a.mask, ids[bi * kDenseCB] >> a.vbits)) ++bi;
+    return bi;
+  };
+  auto issue = [&](int bi) {
+    bits = a.bits[(size_t)(b0 + bi) * 256 + tid];
+    const int64_t slot0 = (int64_t)m_cb[bi] * kDenseCB;
+#pragma unroll
+    for (int j = 0; j < PPL; ++j) {
+      const int kp = wave * 8 + j * SETS + set;
+      const uint32_t pc0 = ids[bi * kDenseCB + 2 * kp], pc1 = ids[bi * kDenseCB + 2 * kp + 1];
+      x0[j] = u32x4{0u, 0u, 0u, 0u};
+      x1[j] = u32x4{0u, 0u, 0u, 0u};
+      s0[j] = a.colscale[slot0 + 2 * kp];
+      s1[j] = a.colscale[slot0 + 2 * kp + 1];
+      if (pc0 != 0xffffffffu) {
+        const bool sel = mask_test(a.mask, pc0 >> a.vbits);
+        if (sel || !drop) x0[j] = *reinterpret_cast<const u32x4 *>((sel ? src_sel : src_unsel) + (size_t)(pc0 & vmask) * ld + ng * 8);
+      }
+      if (pc1 != 0xffffffffu) {
+        const bool sel = mask_test(a.mask, pc1 >> a.vbits);
+        if (sel || !drop) x1[j] = *reinterpret_cast<const u32x4 *>((sel ? src_sel : src_unsel) + (size_t)(pc1 & vmask) * ld + ng * 8);
+      }
+    }
+  };
+  // (hi, lo) bf16 parts of s * x for one bf16 element taken from the low or high half of a word
+  auto scaled = [](uint32_t word, bool high, float sc, uint32_t &hi, uint32_t &lo) {
+    const float f = __uint_as_float(high ? (word & 0xffff0000u) : (word << 16)) * sc;
+    const bf16_t h = (bf16_t)f;
+    const bf16_t l = (bf16_t)(f - (float)h);
+    hi = __builtin_bit_cast(uint16_t, h);
+    lo = __builtin_bit_cast(uint16_t, l);
+  };
+
+  int cur = next_active(0);
+  if (cur < nb) issue(cur);
+  while (cur < nb) {
+    const int nxt = next_active(cur + 1);
+    __syncthreads();  // the previous block's fragment reads are done
+    {  // pattern: 32 cells -> 32 bf16 (1.0 = 0x3f80)
+      u32x4 *dst = reinterpret_cast<u32x4 *>(A01 + (tid >> 1) * A_PITCH + (tid & 1) * 32);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        u32x4 w;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const uint32_t two = (bits >> (8 * q + 2 * t)) & 3u;
+          w[t] = ((two & 1u) ? 0x3f80u : 0u) | ((two & 2u) ? 0x3f800000u : 0u);
+        }
+        dst[q] = w;
+      }
+    }
+    // source rows, scaled: word n of pair kp holds (row 2kp, row 2kp+1) at column n
+#pragma unroll
+    for (int j = 0; j < PPL; ++j) {
+      const int kp = wave * 8 + j * SETS + set;
+      u32x4 h4[2], l4[2];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {  // word q of the 16-byte piece: columns 2q and 2q + 1
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          uint32_t ah, al, bh, bl;
+          scaled(x0[j][q], e == 1, s0[j], ah, al);
+          scaled(x1[j][q], e == 1, s1[j], bh, bl);
+          h4[q >> 1][(q & 1) * 2 + e] = ah | (bh << 16);
+          l4[q >> 1][(q & 1) * 2 + e] = al | (bl << 16);
+        }
+      }
+      u32x4 *dh = reinterpret_cast<u32x4 *>(Hh + (size_t)kp * DH + ng * 8);
+      u32x4 *dl = reinterpret_cast<u32x4 *>(Hl + (size_t)kp * DH + ng * 8);
+      dh[0] = h4[0];
+      dh[1] = h4[1];
+      dl[0] = l4[0];
+      dl[1] = l4[1];
+    }
+    __syncthreads();  // pattern and source rows are in place
+    if (nxt < nb) issue(nxt);  // the next block's loads fly while this one is multiplied
+#pragma unroll
+    for (int ks = 0; ks < kDenseCB / 16; ++ks) {
+      bf16x8 fa[2], fbh[NI], fbl[NI];
+      const int koff = ks * 16 + (lane >> 5) * 8;
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi) fa[mi] = *reinterpret_cast<const bf16x8 *>(&A01[(wm + mi * 32 + (lane & 31)) * A_PITCH + koff]);
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni) {
+        u32x4 wh, wl;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const size_t at = (size_t)(ks * 8 + (lane >> 5) * 4 + j) * DH + wn + ni * 32 + (lane & 31);
+          wh[j] = Hh[at];
+          wl[j] = Hl[at];
+        }
+        fbh[ni] = __builtin_bit_cast(bf16x8, wh);
+        fbl[ni] = __builtin_bit_cast(bf16x8, wl);
+      }
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fbh[ni], acc[mi][ni], 0, 0, 0);
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fbl[ni], acc[mi][ni], 0, 0, 0);
+    }
+    cur = nxt;
+  }
+  float *P = a.partial + (size_t)item * kDenseRB * a.d + col0;
+  const float *rs = a.rowscale + (size_t)a.item_rb[item] * kDenseRB;  // zero past the last row of the chunk
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int t = 0; t < 16; ++t) {
+        const int r = wm + mi * 32 + 8 * (t >> 2) + 4 * (lane >> 5) + (t & 3);
+        P[(size_t)r * a.d + wn + ni * 32 + (lane & 31)] = acc[mi][ni][t] * rs[r];
+      }
+}
+
+}  // namespace
+
+int launch_spmm_dense(const DenseArgs &a, hipStream_t s) {
+  if (a.n_items <= 0) return hipSuccess;
+  if (a.d != 128 && a.d != 256) return hipErrorInvalidValue;
+  const size_t smem = (size_t)2 * kDenseRB * A_PITCH * sizeof(bf16_t) + (size_t)32 * DH * sizeof(uint32_t) +
+                      (size_t)kDenseMaxItemBlocks * kDenseCB * sizeof(uint32_t) + kDenseMaxItemBlocks * sizeof(int32_t);
+  static bool attr_done = false;
+  if (!attr_done) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(spmm_dense_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)smem);
+    attr_done = true;
+  }
+  if (a.bits) {
+    const size_t smem1 = (size_t)kDenseRB * A_PITCH * sizeof(bf16_t) + (size_t)2 * 32 * DH * sizeof(uint32_t) +
+                         (size_t)kDenseMaxItemBlocks * kDenseCB * sizeof(uint32_t) + kDenseMaxItemBlocks * sizeof(int32_t);
+    static bool attr1_done = false;
+    if (!attr1_done) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(spmm_dense_r1_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)smem1);
+      attr1_done = true;
+    }
+    hipLaunchKernelGGL(spmm_dense_r1_kernel, dim3((unsigned)a.n_items, (unsigned)(a.d / DH)), dim3(256), smem1, s, a);
+    return (int)hipGetLastError();
+  }
+  hipLaunchKernelGGL(spmm_dense_kernel, dim3((unsigned)a.n_items, (unsigned)(a.d / DH)), dim3(256), smem, s, a);
+  return (int)hipGetLastError();
+}
+
+int launch_dense_expand(const int64_t *blk_e0, const uint16_t *ent_pos, const uint32_t *ent_w, void *tiles, int64_t n_blocks,
+                        hipStream_t s) {
+  if (n_blocks <= 0) return hipSuccess;
+  hipLaunchKernelGGL(dense_expand_kernel, dim3((unsigned)n_blocks), dim3(256), 0, s, blk_e0, ent_pos, ent_w,
+                     static_cast<uint16_t *>(tiles));
+  return (int)hipGetLastError();
+}

@@ -12,6 +12,7 @@
 
 #include "../../include/gnnstage.h"
 #include "common.h"
+#include "plan.h"
 
 namespace {
 
@@ -75,6 +76,25 @@ std::vector<int64_t> class_bounds(int64_t n, int classes, const std::vector<int6
   return lo;
 }
 
+// Dense blocks: switched on for bf16 stages whose aggregations all gather rows of width 128 or 256.
+// GNNSTAGE_DENSE=0 switches them off; GNNSTAGE_DENSE_MIN_NNZ (entries a 128 x 64 block needs, default 5 %
+// of its cells) and GNNSTAGE_DENSE_MIN_SHARE (share of all entries that must fall into such blocks,
+// default 0.2) let tests force them on small graphs.
+bool dense_enabled() {
+  const char *e = getenv("GNNSTAGE_DENSE");
+  return !(e && atoi(e) == 0);
+}
+int dense_min_nnz() {
+  const char *e = getenv("GNNSTAGE_DENSE_MIN_NNZ");
+  if (e && atoi(e) >= 1) return atoi(e);
+  return kDenseRB * kDenseCB / 20;
+}
+double dense_min_share() {
+  const char *e = getenv("GNNSTAGE_DENSE_MIN_SHARE");
+  return e ? atof(e) : 0.2;
+}
+constexpr int kDenseItemBlocks = kDenseMaxItemBlocks;
+
 struct TaskList {
   int64_t n_tasks = 0, n_long = 0, n_slots = 0;
   int32_t *task_row = nullptr;
@@ -89,6 +109,10 @@ struct TaskList {
   // entries of every class section by the chunk of the gathered vertex ([class * K + chunk]): what a launch
   // that drops unselected entries really gathers from each class
   std::vector<int64_t> cls_chunk_entries;
+  // dense-block parts of the cut rows and the items of this chunk (dense plan active only)
+  int32_t *lr_dense0 = nullptr, *lr_ndense = nullptr, *lr_item0 = nullptr;
+  int64_t item0 = 0;  // first item of the chunk in the direction's item arrays
+  int n_items = 0;
 };
 
 // Sizes that depend only on row lengths: number of tasks / long rows / slots of every chunk.
@@ -101,7 +125,8 @@ struct PlanCounts {
 
 // Upper bounds (from row lengths alone) on tasks / cut rows / slots of every chunk: a row cut by
 // source class adds at most one extra piece per class.
-PlanCounts count_plan(const int64_t *ptr, const std::vector<int64_t> &chunk_ptr, int classes) {
+PlanCounts count_plan(const int64_t *ptr, const std::vector<int64_t> &chunk_ptr, int classes,
+                      const uint8_t *force = nullptr) {
   PlanCounts pc;
   const int K = (int)chunk_ptr.size() - 1;
   const int min_row = class_min_row_setting();
@@ -115,7 +140,7 @@ PlanCounts count_plan(const int64_t *ptr, const std::vector<int64_t> &chunk_ptr,
     for (int64_t r = chunk_ptr[c]; r < chunk_ptr[c + 1]; ++r) {
       const int64_t len = ptr[r + 1] - ptr[r];
       const bool by_src = classes > 1 && len >= min_row;
-      if (by_src || len > split) {
+      if (by_src || len > split || (force && force[r])) {
         const int64_t pieces = (len + split - 1) / split + (by_src ? classes : 0);
         pc.tasks[c] += pieces;
         pc.slots[c] += pieces;
@@ -132,6 +157,78 @@ PlanCounts count_plan(const int64_t *ptr, const std::vector<int64_t> &chunk_ptr,
   return pc;
 }
 
+// Everything the host plans for one aggregation direction before anything is uploaded.
+struct HostDir {
+  DensePlan dp;
+  const int64_t *ptr = nullptr;   // the index the sparse kernels see: the original one, or the dense plan's remainder
+  const int32_t *idx = nullptr;
+  int64_t nnz = 0;
+  std::vector<uint8_t> force;     // rows with dense parts (they always write partial sums)
+  PlanCounts pc;
+  std::vector<int32_t> item_rb, item_nb;
+  std::vector<int64_t> item_b0;
+  std::vector<ChunkMask> item_chunks;
+  std::vector<int64_t> chunk_item_off;  // K + 1
+  std::vector<int64_t> rowscale_off;    // K + 1: chunk k owns 128 scale slots per row block
+  int64_t max_items = 0;
+  bool dense() const { return dp.active; }
+  int64_t padded_entries() const {  // entry lists padded to multiples of eight (16-byte loads)
+    int64_t t = 0;
+    for (int64_t b = 0; b < dp.n_blocks(); ++b) t += (dp.blk_e0[(size_t)b + 1] - dp.blk_e0[(size_t)b] + 7) / 8 * 8;
+    return t;
+  }
+  const uint8_t *force_ptr() const { return dp.active ? force.data() : nullptr; }
+};
+
+void host_mask_set(ChunkMask &m, int c) { m.w[c >> 6] |= 1ull << (c & 63); }
+
+bool make_host_dir(const int64_t *ptr, const int32_t *idx, int64_t n, const std::vector<int64_t> &chunk_ptr,
+                   int classes, bool try_dense, HostDir &h) {
+  const int K = (int)chunk_ptr.size() - 1;
+  h.ptr = ptr;
+  h.idx = idx;
+  h.nnz = ptr[n];
+  h.chunk_item_off.assign((size_t)K + 1, 0);
+  h.rowscale_off.assign((size_t)K + 1, 0);
+  for (int k = 0; k < K; ++k)
+    h.rowscale_off[(size_t)k + 1] = h.rowscale_off[(size_t)k] + (chunk_ptr[(size_t)k + 1] - chunk_ptr[(size_t)k] + kDenseRB - 1) / kDenseRB * kDenseRB;
+  if (try_dense && !build_dense_plan(ptr, idx, n, K, chunk_ptr.data(), dense_min_nnz(), dense_min_share(), h.dp)) return false;
+  if (h.dp.active) {
+    const DensePlan &dp = h.dp;
+    h.ptr = dp.rem_ptr.data();
+    h.idx = dp.rem_idx.data();
+    h.nnz = (int64_t)dp.rem_idx.size();
+    h.force.assign((size_t)n, 0);
+    std::vector<int> chunk_of_cb((size_t)dp.cb_off[(size_t)K]);
+    for (int c = 0; c < K; ++c)
+      for (int64_t b = dp.cb_off[(size_t)c]; b < dp.cb_off[(size_t)c + 1]; ++b) chunk_of_cb[(size_t)b] = c;
+    for (int k = 0; k < K; ++k) {
+      int64_t b = dp.chunk_blk_off[(size_t)k];
+      const int64_t b_end = dp.chunk_blk_off[(size_t)k + 1];
+      while (b < b_end) {  // runs of blocks of one row block, at most kDenseItemBlocks each
+        int64_t e = b;
+        ChunkMask m{};
+        while (e < b_end && dp.blk_rb[(size_t)e] == dp.blk_rb[(size_t)b] && e - b < kDenseItemBlocks) {
+          host_mask_set(m, chunk_of_cb[(size_t)dp.blk_cb[(size_t)e]]);
+          ++e;
+        }
+        h.item_rb.push_back(dp.blk_rb[(size_t)b]);
+        h.item_b0.push_back(b);
+        h.item_nb.push_back((int32_t)(e - b));
+        h.item_chunks.push_back(m);
+        const int64_t r0 = chunk_ptr[(size_t)k] + (int64_t)dp.blk_rb[(size_t)b] * kDenseRB;
+        for (int64_t r = r0; r < std::min<int64_t>(r0 + kDenseRB, chunk_ptr[(size_t)k + 1]); ++r)
+          h.force[(size_t)dp.row_perm[(size_t)r]] = 1;
+        b = e;
+      }
+      h.chunk_item_off[(size_t)k + 1] = (int64_t)h.item_rb.size();
+      h.max_items = std::max(h.max_items, h.chunk_item_off[(size_t)k + 1] - h.chunk_item_off[(size_t)k]);
+    }
+  }
+  h.pc = count_plan(h.ptr, chunk_ptr, classes, h.force_ptr());
+  return true;
+}
+
 struct Bump {
   size_t off = 0;
   size_t take(size_t bytes) {
@@ -146,6 +243,13 @@ struct Layout {
   size_t f_task_row, f_task_e0, f_task_ne, f_task_slot, f_lr_row, f_lr_slot0, f_lr_n;
   size_t b_task_row, b_task_e0, b_task_ne, b_task_slot, b_lr_row, b_lr_slot0, b_lr_n;
   size_t f_slot_class, b_slot_class;
+  size_t rem_ptr[2];  // row pointers of the remainder index per direction (dense plan active), else unused
+  // dense plan per direction (0 forward, 1 transposed)
+  size_t d_blk_cb[2], d_blk_e0[2], d_ent_pos[2], d_ent_w[2], d_colslot[2], d_tiles[2];
+  size_t d_bits[2], d_colscale[2], d_rowscale[2];  // weights of the form s(row) * s(column): patterns and scales
+  size_t d_item_rb[2], d_item_b0[2], d_item_nb[2], d_item_chunks[2];
+  size_t d_lr_dense0[2], d_lr_ndense[2], d_lr_item0[2];
+  size_t dense_partial;
   size_t partial;
   std::vector<size_t> Z, dZ, Wt, Wn, Tc, Th;
   size_t G[2];
@@ -169,6 +273,17 @@ struct Shape {
       widest = std::max<int64_t>(widest, tf[j] ? (int64_t)dims[j + 1] * elt()
                                                : std::max<int64_t>((int64_t)dims[j] * level_elt(j), (int64_t)dims[j] * elt()));
     return xcd_classes_setting(n * widest);
+  }
+  // dense blocks serve the matrix-core aggregation only: every aggregation of the stage must gather bf16 rows
+  // of width 128 or 256
+  bool dense_ok() const {
+    if (dtype != GNNSTAGE_BF16 || !dense_enabled()) return false;
+    for (int j = 0; j < L; ++j) {
+      const int wdt = tf[j] ? dims[j + 1] : dims[j];
+      if (wdt != 128 && wdt != 256) return false;
+      if (!tf[j] && j == 0 && level0_f32) return false;
+    }
+    return true;
   }
   int64_t max_rows() const {
     int64_t m = 0;
@@ -242,15 +357,42 @@ std::vector<int64_t> transposed_ptr(const gnnstage_desc *d, const Shape &s, std:
   return t;
 }
 
-Layout make_layout(const Shape &s, const PlanCounts &f, const PlanCounts &b) {
+Layout make_layout(const Shape &s, const HostDir &hf, const HostDir &hb, bool rank1) {
+  const PlanCounts &f = hf.pc, &b = hb.pc;
   Layout l;
   Bump w;
   l.row_ptr = w.take(sizeof(int64_t) * (s.n + 1));
-  l.pcol = w.take(sizeof(uint32_t) * s.nnz);
-  l.val = w.take(sizeof(float) * s.nnz);
+  l.pcol = w.take(sizeof(uint32_t) * hf.nnz);
+  l.val = w.take(sizeof(float) * hf.nnz);
   l.t_ptr = w.take(sizeof(int64_t) * (s.n + 1));
-  l.prow = w.take(sizeof(uint32_t) * s.nnz);
-  l.tval = w.take(sizeof(float) * s.nnz);
+  l.prow = w.take(sizeof(uint32_t) * hb.nnz);
+  l.tval = w.take(sizeof(float) * hb.nnz);
+  int64_t max_items = 0;
+  for (int dir = 0; dir < 2; ++dir) {
+    const HostDir &h = dir ? hb : hf;
+    const bool on = h.dense();
+    const size_t nb = on ? (size_t)h.dp.n_blocks() : 0, ne = on ? (size_t)h.padded_entries() : 0;
+    const size_t ni = h.item_rb.size(), nl = on ? (size_t)h.pc.total_longs : 0;
+    l.rem_ptr[dir] = w.take(on ? sizeof(int64_t) * (s.n + 1) : 0);
+    l.d_blk_cb[dir] = w.take(sizeof(int32_t) * nb);
+    l.d_blk_e0[dir] = w.take(on ? sizeof(int64_t) * (nb + 1) : 0);
+    l.d_ent_pos[dir] = w.take(rank1 ? 0 : sizeof(uint16_t) * ne);
+    l.d_ent_w[dir] = w.take(rank1 ? 0 : sizeof(uint32_t) * ne);
+    l.d_colslot[dir] = w.take(on ? sizeof(uint32_t) * h.dp.colslot_vertex.size() : 0);
+    l.d_tiles[dir] = w.take(rank1 ? 0 : sizeof(uint16_t) * nb * 2 * kDenseRB * kDenseCB);
+    l.d_bits[dir] = w.take(rank1 ? sizeof(uint32_t) * nb * 256 : 0);
+    l.d_colscale[dir] = w.take(on && rank1 ? sizeof(float) * h.dp.colslot_vertex.size() : 0);
+    l.d_rowscale[dir] = w.take(on && rank1 ? sizeof(float) * (size_t)h.rowscale_off.back() : 0);
+    l.d_item_rb[dir] = w.take(sizeof(int32_t) * ni);
+    l.d_item_b0[dir] = w.take(sizeof(int64_t) * ni);
+    l.d_item_nb[dir] = w.take(sizeof(int32_t) * ni);
+    l.d_item_chunks[dir] = w.take(sizeof(ChunkMask) * ni);
+    l.d_lr_dense0[dir] = w.take(sizeof(int32_t) * nl);
+    l.d_lr_ndense[dir] = w.take(sizeof(int32_t) * nl);
+    l.d_lr_item0[dir] = w.take(sizeof(int32_t) * nl);
+    max_items = std::max(max_items, h.max_items);
+  }
+  l.dense_partial = w.take(sizeof(float) * (size_t)max_items * kDenseRB * 256);
   l.f_task_row = w.take(sizeof(int32_t) * f.total_tasks);
   l.f_task_e0 = w.take(sizeof(int64_t) * f.total_tasks);
   l.f_task_ne = w.take(sizeof(int32_t) * f.total_tasks);
@@ -368,6 +510,10 @@ struct gnnstage {
   std::vector<uint32_t> h_pcol;
   // schedules
   std::vector<TaskList> ftasks, btasks;
+  bool dense_on[2] = {false, false};  // dense blocks per direction (0 forward, 1 transposed)
+  int64_t dense_entries[2] = {0, 0};  // entries that live in dense blocks
+  bool dense_rank1 = false;           // their weights are kept as pattern bits and row / column scales
+  std::vector<int64_t> rowscale_off[2];
   int n_classes = 1;
   // pass state (Section 3.3: V_processed, and its backward twin)
   std::vector<int32_t> order;
@@ -530,19 +676,61 @@ SpmmArgs base_spmm(const gnnstage *st, bool transposed, int chunk) {
   a.partial = st->at<float>(st->lay.partial);
   a.vbits = st->vbits;
   a.mask = transposed ? st->bmask : st->fmask;
+  const int dir = transposed ? 1 : 0;
+  if (st->dense_on[dir]) {
+    a.lr_dense0 = t.lr_dense0;
+    a.lr_ndense = t.lr_ndense;
+    a.lr_item0 = t.lr_item0;
+    a.item_chunks = st->at<ChunkMask>(st->lay.d_item_chunks[dir]) + t.item0;
+    a.dense_partial = st->at<float>(st->lay.dense_partial);
+  }
   assign_xcds(st, t, a.mask, transposed, a);  // every transposed launch drops unselected entries
   return a;
 }
 
 // aggregation kernel and (when the chunk has long rows) the reduce of their pieces, timed apart
-int run_spmm(gnnstage *st, const SpmmArgs &a, int src_dtype, int out_dtype, hipStream_t stream, int kind, int layer) {
+// (with dense blocks: their kernel first, timed together with the sparse kernel)
+int run_spmm(gnnstage *st, const SpmmArgs &a_in, bool transposed, int chunk, int src_dtype, int out_dtype,
+             hipStream_t stream, int kind, int layer) {
+  SpmmArgs a = a_in;
+  a.drop_unselected = a.src_unsel == nullptr ? 1 : 0;
+  const int dir = transposed ? 1 : 0;
+  const TaskList &t = transposed ? st->btasks[chunk] : st->ftasks[chunk];
   {
-    Timed t(st, stream, kind, layer);
+    Timed tm(st, stream, kind, layer);
+    if (st->dense_on[dir] && t.n_items > 0) {
+      if (src_dtype != DT_BF16 || (a.d != 128 && a.d != 256) || a.src_ld != a.d) return hipErrorInvalidValue;
+      const Layout &lay = st->lay;
+      DenseArgs da{};
+      da.item_rb = st->at<int32_t>(lay.d_item_rb[dir]) + t.item0;
+      da.item_b0 = st->at<int64_t>(lay.d_item_b0[dir]) + t.item0;
+      da.item_nb = st->at<int32_t>(lay.d_item_nb[dir]) + t.item0;
+      da.item_chunks = st->at<ChunkMask>(lay.d_item_chunks[dir]) + t.item0;
+      da.n_items = t.n_items;
+      da.blk_cb = st->at<int32_t>(lay.d_blk_cb[dir]);
+      if (st->dense_rank1) {
+        da.bits = st->at<uint32_t>(lay.d_bits[dir]);
+        da.colscale = st->at<float>(lay.d_colscale[dir]);
+        da.rowscale = st->at<float>(lay.d_rowscale[dir]) + st->rowscale_off[dir][(size_t)chunk];
+      } else {
+        da.tiles = st->at<bf16_t>(lay.d_tiles[dir]);
+      }
+      da.colslot = st->at<uint32_t>(lay.d_colslot[dir]);
+      da.src_sel = a.src_sel;
+      da.src_unsel = a.src_unsel;
+      da.d = a.d;
+      da.src_ld = a.src_ld;
+      da.vbits = a.vbits;
+      da.mask = a.mask;
+      da.partial = st->at<float>(lay.dense_partial);
+      const int e = launch_spmm_dense(da, stream);
+      if (e != 0) return e;
+    }
     const int e = launch_spmm(a, src_dtype, out_dtype, stream);
     if (e != 0) return e;
   }
-  if (a.n_long > 0 && a.n_tasks > 0) {
-    Timed t(st, stream, 7, layer);
+  if (a.n_long > 0) {
+    Timed tm(st, stream, 7, layer);
     return launch_spmm_reduce(a, src_dtype, out_dtype, stream);
   }
   return 0;
@@ -572,7 +760,7 @@ int finish_transform_first(gnnstage *st, hipStream_t stream) {
       a.out_ld = s.ld[j + 1];
       a.out_row0 = row0;
       a.epilogue = SPMM_PLAIN;
-      HIP_TRY(st, run_spmm(st, a, cd, cd, stream, 2, j));
+      HIP_TRY(st, run_spmm(st, a, true, c, cd, cd, stream, 2, j));
       Timed t(st, stream, 4, j);
       GemmTnArgs w{};
       w.A = static_cast<const char *>(st->hist[j]) + (size_t)row0 * s.dims[j] * st->level_elt(j);
@@ -597,7 +785,56 @@ int finish_transform_first(gnnstage *st, hipStream_t stream) {
 
 extern "C" int gnnstage_version(void) { return 100; }
 
+extern "C" int64_t gnnstage_dense_entries(const gnnstage_t *st, int32_t transposed) {
+  if (!st) return GNNSTAGE_EINVAL;
+  return st->dense_entries[transposed ? 1 : 0];
+}
+
 extern "C" const char *gnnstage_last_error(const gnnstage_t *st) { return st ? st->err.c_str() : g_create_error.c_str(); }
+
+namespace {
+// transposed index and the per-direction plans: what both the size query and create need
+struct HostPlan {
+  std::vector<int64_t> t_ptr, t_edge;
+  std::vector<int32_t> t_row;
+  HostDir f, b;
+};
+
+int make_host_plan(const gnnstage_desc *d, const Shape &s, bool want_edge, HostPlan &hp, std::string &err) {
+  if (s.nnz > 0 && !d->col_idx) {
+    err = "col_idx is NULL";
+    return GNNSTAGE_EINVAL;
+  }
+  hp.t_ptr.assign((size_t)s.n + 1, 0);
+  hp.t_row.resize((size_t)s.nnz);
+  if (want_edge) hp.t_edge.resize((size_t)s.nnz);
+  if (gnnstage_plan_transpose(s.n, d->row_ptr, d->col_idx, hp.t_ptr.data(), hp.t_row.data(),
+                              want_edge ? hp.t_edge.data() : nullptr) != GNNSTAGE_OK) {
+    err = "col_idx is NULL or has an entry outside [0, n_vertices)";
+    return GNNSTAGE_EINVAL;
+  }
+  const bool dense = s.dense_ok();
+  if (!make_host_dir(d->row_ptr, d->col_idx, s.n, s.chunk_ptr, s.classes(), dense, hp.f) ||
+      !make_host_dir(hp.t_ptr.data(), hp.t_row.data(), s.n, s.chunk_ptr, s.classes(), dense, hp.b)) {
+    err = "cannot plan the aggregation";
+    return GNNSTAGE_EINVAL;
+  }
+  return GNNSTAGE_OK;
+}
+
+uint16_t bf16_bits_rne(float f) {  // finite inputs: round to nearest even, as the device conversion does
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+float bf16_bits_to_f32(uint16_t h) {
+  const uint32_t u = (uint32_t)h << 16;
+  float f;
+  memcpy(&f, &u, 4);
+  return f;
+}
+}  // namespace
 
 extern "C" size_t gnnstage_workspace_size(const gnnstage_desc *desc) {
   Shape s;
@@ -606,14 +843,12 @@ extern "C" size_t gnnstage_workspace_size(const gnnstage_desc *desc) {
     g_create_error = err;
     return 0;
   }
-  std::vector<int64_t> tptr = transposed_ptr(desc, s, err);
-  if (tptr.empty()) {
+  HostPlan hp;
+  if (make_host_plan(desc, s, false, hp, err) != GNNSTAGE_OK) {
     g_create_error = err;
     return 0;
   }
-  const PlanCounts f = count_plan(desc->row_ptr, s.chunk_ptr, s.classes());
-  const PlanCounts b = count_plan(tptr.data(), s.chunk_ptr, s.classes());
-  return make_layout(s, f, b).total;
+  return make_layout(s, hp.f, hp.b, desc->edge_val == nullptr).total;
 }
 
 extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
@@ -641,25 +876,21 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
     return fail(nullptr, GNNSTAGE_EINVAL, "h0 / grad_in not 16-byte aligned");
 
   // ---- host planning -------------------------------------------------------------------
-  std::vector<int64_t> t_ptr((size_t)s.n + 1);
-  std::vector<int32_t> t_row((size_t)s.nnz);
-  std::vector<int64_t> t_edge;
-  if (d->edge_val) t_edge.resize((size_t)s.nnz);
-  int rc = gnnstage_plan_transpose(s.n, d->row_ptr, d->col_idx, t_ptr.data(), t_row.data(),
-                                   d->edge_val ? t_edge.data() : nullptr);
-  if (rc != GNNSTAGE_OK) return fail(nullptr, rc, "col_idx is NULL or has an entry outside [0, n_vertices)");
+  HostPlan hp;
+  int rc = make_host_plan(d, s, d->edge_val != nullptr, hp, err);
+  if (rc != GNNSTAGE_OK) return fail(nullptr, rc, err);
+  const std::vector<int64_t> &t_ptr = hp.t_ptr, &t_edge = hp.t_edge;
   int vbits = 0;
-  std::vector<uint32_t> pcol((size_t)s.nnz), prow((size_t)s.nnz);
-  rc = gnnstage_plan_pack(s.n, s.nnz, d->col_idx, s.K, s.chunk_ptr.data(), pcol.data(), &vbits);
+  std::vector<uint32_t> pcol((size_t)hp.f.nnz), prow((size_t)hp.b.nnz);
+  rc = gnnstage_plan_pack(s.n, hp.f.nnz, hp.f.idx, s.K, s.chunk_ptr.data(), pcol.data(), &vbits);
   if (rc == GNNSTAGE_ENOTSUP)
     return fail(nullptr, rc, "vertex-id bits + chunk-id bits exceed the 32-bit packed index word");
   if (rc != GNNSTAGE_OK) return fail(nullptr, rc, "cannot pack column indices");
-  rc = gnnstage_plan_pack(s.n, s.nnz, t_row.data(), s.K, s.chunk_ptr.data(), prow.data(), &vbits);
+  rc = gnnstage_plan_pack(s.n, hp.b.nnz, hp.b.idx, s.K, s.chunk_ptr.data(), prow.data(), &vbits);
   if (rc != GNNSTAGE_OK) return fail(nullptr, rc, "cannot pack row indices");
 
-  const PlanCounts fc = count_plan(d->row_ptr, s.chunk_ptr, s.classes());
-  const PlanCounts bc = count_plan(t_ptr.data(), s.chunk_ptr, s.classes());
-  Layout lay = make_layout(s, fc, bc);
+  const bool rank1 = d->edge_val == nullptr;  // the library computes w(v, u) = s(v) s(u) itself
+  Layout lay = make_layout(s, hp.f, hp.b, rank1);
   if (d->workspace_bytes < lay.total) {
     char buf[160];
     snprintf(buf, sizeof buf, "workspace too small: %zu bytes given, %zu needed", d->workspace_bytes, lay.total);
@@ -686,12 +917,23 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
   st->n_classes = s.classes();
   const std::vector<int64_t> cls_lo = class_bounds(s.n, st->n_classes, s.chunk_ptr);
   st->h_row_ptr.assign(d->row_ptr, d->row_ptr + s.n + 1);
-  st->h_pcol = pcol;
+  if (hp.f.dense()) {  // the diagnostics walk the whole index, not the remainder
+    st->h_pcol.resize((size_t)s.nnz);
+    if (gnnstage_plan_pack(s.n, s.nnz, d->col_idx, s.K, s.chunk_ptr.data(), st->h_pcol.data(), &vbits) != GNNSTAGE_OK) {
+      delete st;
+      return fail(nullptr, GNNSTAGE_EINVAL, "cannot pack column indices");
+    }
+  } else {
+    st->h_pcol = pcol;
+  }
 
   // schedules: build on the host chunk by chunk, upload into the preallocated arrays
   const int classes = s.classes(), min_row = class_min_row_setting();
-  auto build = [&](const int64_t *ptr, const int32_t *idx, const uint32_t *packed, const PlanCounts &pc,
-                   bool transposed, std::vector<TaskList> &lists) -> int {
+  auto build = [&](const HostDir &h, const uint32_t *packed, bool transposed, std::vector<TaskList> &lists) -> int {
+    const int64_t *ptr = h.ptr;
+    const int32_t *idx = h.idx;
+    const PlanCounts &pc = h.pc;
+    const int dir = transposed ? 1 : 0;
     lists.resize(s.K);
     int64_t t_off = 0, l_off = 0, s_off = 0;
     for (int c = 0; c < s.K; ++c) {
@@ -705,18 +947,25 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
       tl.lr_row = st->at<int32_t>(transposed ? lay.b_lr_row : lay.f_lr_row) + l_off;
       tl.lr_slot0 = st->at<int32_t>(transposed ? lay.b_lr_slot0 : lay.f_lr_slot0) + l_off;
       tl.lr_nslots = st->at<int32_t>(transposed ? lay.b_lr_n : lay.f_lr_n) + l_off;
+      if (h.dense()) {
+        tl.lr_dense0 = st->at<int32_t>(lay.d_lr_dense0[dir]) + l_off;
+        tl.lr_ndense = st->at<int32_t>(lay.d_lr_ndense[dir]) + l_off;
+        tl.lr_item0 = st->at<int32_t>(lay.d_lr_item0[dir]) + l_off;
+        tl.item0 = h.chunk_item_off[(size_t)c];
+        tl.n_items = (int)(h.chunk_item_off[(size_t)c + 1] - h.chunk_item_off[(size_t)c]);
+      }
       t_off += pc.tasks[c];  // the arrays were sized from the upper bounds
       l_off += pc.longs[c];
       const int64_t cap = pc.tasks[c];
-      if (cap == 0) continue;
-      std::vector<int32_t> row(cap), ne(cap), slot(cap);
-      std::vector<int64_t> e0(cap);
+      if (cap == 0 && tl.n_items == 0) continue;
+      std::vector<int32_t> row((size_t)std::max<int64_t>(cap, 1)), ne((size_t)std::max<int64_t>(cap, 1)), slot((size_t)std::max<int64_t>(cap, 1));
+      std::vector<int64_t> e0((size_t)std::max<int64_t>(cap, 1));
       int64_t ns = 0;
       std::vector<int64_t> coff(classes + 1, 0);
       std::vector<uint8_t> sclass((size_t)std::max<int64_t>(pc.slots[c], 1), 255);
       const int64_t got = gnnstage_plan_tasks(ptr, idx, s.n, s.chunk_ptr[c], s.chunk_ptr[c + 1], pc.split[c], classes,
-                                              cls_lo.data(), min_row, cap, row.data(), e0.data(), ne.data(),
-                                              slot.data(), &ns, coff.data(), sclass.data());
+                                              cls_lo.data(), min_row, h.force_ptr(), cap, row.data(), e0.data(),
+                                              ne.data(), slot.data(), &ns, coff.data(), sclass.data());
       if (got < 0 || got > cap || ns > pc.slots[c]) return GNNSTAGE_EINVAL;
       tl.n_classes = classes > 1 ? classes : 0;
       for (int q = 0; q <= tl.n_classes; ++q) tl.cls_off[q] = coff[q];
@@ -742,8 +991,44 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
         }
         ln.back() += 1;
       }
+      // rows of dense row blocks: their dense partial rows join the pieces (a row without any piece is added)
+      std::vector<int32_t> ldense0(lrow.size(), 0), lndense(lrow.size(), 0), litem0(lrow.size(), 0);
+      if (tl.n_items > 0) {
+        std::vector<int32_t> where((size_t)(s.chunk_ptr[c + 1] - s.chunk_ptr[c]), -1);
+        for (size_t i = 0; i < lrow.size(); ++i) where[(size_t)(lrow[i] - s.chunk_ptr[c])] = (int32_t)i;
+        int64_t it = tl.item0;
+        const int64_t it_end = tl.item0 + tl.n_items;
+        while (it < it_end) {
+          int64_t it2 = it;
+          while (it2 < it_end && h.item_rb[(size_t)it2] == h.item_rb[(size_t)it]) ++it2;
+          const int64_t p0 = (int64_t)h.item_rb[(size_t)it] * kDenseRB;
+          const int64_t p1 = std::min<int64_t>(p0 + kDenseRB, s.chunk_ptr[c + 1] - s.chunk_ptr[c]);
+          for (int64_t pp = p0; pp < p1; ++pp) {
+            const int32_t r = h.dp.row_perm[(size_t)(s.chunk_ptr[c] + pp)];
+            int32_t at = where[(size_t)(r - s.chunk_ptr[c])];
+            if (at < 0) {
+              at = (int32_t)lrow.size();
+              lrow.push_back(r);
+              lslot0.push_back(0);
+              ln.push_back(0);
+              ldense0.push_back(0);
+              lndense.push_back(0);
+              litem0.push_back(0);
+            }
+            ldense0[(size_t)at] = (int32_t)((it - tl.item0) * kDenseRB + (pp - p0));
+            lndense[(size_t)at] = (int32_t)(it2 - it);
+            litem0[(size_t)at] = (int32_t)(it - tl.item0);
+          }
+          it = it2;
+        }
+      }
       tl.n_long = (int64_t)lrow.size();
       if (tl.n_long > pc.longs[c]) return GNNSTAGE_EINVAL;
+      if (h.dense() && tl.n_long > 0 &&
+          (hipMemcpy(tl.lr_dense0, ldense0.data(), sizeof(int32_t) * tl.n_long, hipMemcpyHostToDevice) != hipSuccess ||
+           hipMemcpy(tl.lr_ndense, lndense.data(), sizeof(int32_t) * tl.n_long, hipMemcpyHostToDevice) != hipSuccess ||
+           hipMemcpy(tl.lr_item0, litem0.data(), sizeof(int32_t) * tl.n_long, hipMemcpyHostToDevice) != hipSuccess))
+        return GNNSTAGE_EHIP;
       if (got > 0 &&
           (hipMemcpy(tl.task_row, row.data(), sizeof(int32_t) * got, hipMemcpyHostToDevice) != hipSuccess ||
            hipMemcpy(tl.task_e0, e0.data(), sizeof(int64_t) * got, hipMemcpyHostToDevice) != hipSuccess ||
@@ -765,24 +1050,105 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
   };
   if (hipMemcpy(st->at<int64_t>(lay.row_ptr), d->row_ptr, sizeof(int64_t) * (s.n + 1), hipMemcpyHostToDevice) != hipSuccess ||
       hipMemcpy(st->at<int64_t>(lay.t_ptr), t_ptr.data(), sizeof(int64_t) * (s.n + 1), hipMemcpyHostToDevice) != hipSuccess ||
-      hipMemcpy(st->at<uint32_t>(lay.pcol), pcol.data(), sizeof(uint32_t) * s.nnz, hipMemcpyHostToDevice) != hipSuccess ||
-      hipMemcpy(st->at<uint32_t>(lay.prow), prow.data(), sizeof(uint32_t) * s.nnz, hipMemcpyHostToDevice) != hipSuccess)
+      (hp.f.nnz > 0 && hipMemcpy(st->at<uint32_t>(lay.pcol), pcol.data(), sizeof(uint32_t) * hp.f.nnz, hipMemcpyHostToDevice) != hipSuccess) ||
+      (hp.b.nnz > 0 && hipMemcpy(st->at<uint32_t>(lay.prow), prow.data(), sizeof(uint32_t) * hp.b.nnz, hipMemcpyHostToDevice) != hipSuccess))
     return bail(GNNSTAGE_EHIP, std::string("uploading the graph failed: ") + hipGetErrorString(hipGetLastError()));
+  for (int dir = 0; dir < 2; ++dir) {  // dense plans
+    const HostDir &h = dir ? hp.b : hp.f;
+    if (!h.dense()) continue;
+    const DensePlan &dp = h.dp;
+    const size_t nb = (size_t)dp.n_blocks(), ne = dp.ent_pos.size(), ni = h.item_rb.size();  // ne: real entries, without padding
+    std::vector<uint32_t> colslot(dp.colslot_vertex.size());
+    std::vector<int32_t> chunk_of((size_t)s.n);
+    for (int c = 0; c < s.K; ++c)
+      for (int64_t v = s.chunk_ptr[c]; v < s.chunk_ptr[c + 1]; ++v) chunk_of[(size_t)v] = c;
+    for (size_t i = 0; i < colslot.size(); ++i) {
+      const int32_t v = dp.colslot_vertex[i];
+      colslot[i] = v < 0 ? 0xffffffffu : ((uint32_t)v | ((uint32_t)chunk_of[(size_t)v] << vbits));
+    }
+    if (hipMemcpy(st->at<int64_t>(lay.rem_ptr[dir]), dp.rem_ptr.data(), sizeof(int64_t) * (s.n + 1), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(st->at<int32_t>(lay.d_blk_cb[dir]), dp.blk_cb.data(), sizeof(int32_t) * nb, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(st->at<uint32_t>(lay.d_colslot[dir]), colslot.data(), sizeof(uint32_t) * colslot.size(), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(st->at<int32_t>(lay.d_item_rb[dir]), h.item_rb.data(), sizeof(int32_t) * ni, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(st->at<int64_t>(lay.d_item_b0[dir]), h.item_b0.data(), sizeof(int64_t) * ni, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(st->at<int32_t>(lay.d_item_nb[dir]), h.item_nb.data(), sizeof(int32_t) * ni, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(st->at<ChunkMask>(lay.d_item_chunks[dir]), h.item_chunks.data(), sizeof(ChunkMask) * ni, hipMemcpyHostToDevice) != hipSuccess)
+      return bail(GNNSTAGE_EHIP, std::string("uploading the dense blocks failed: ") + hipGetErrorString(hipGetLastError()));
+    if (rank1) {
+      // patterns and the two scale vectors; s(v) = 1 / sqrt(row length of v in A + I)
+      auto scale_of = [&](int64_t v) { return (float)(1.0 / sqrt((double)(d->row_ptr[v + 1] - d->row_ptr[v]))); };
+      std::vector<uint32_t> bits(nb * 256, 0u);
+      for (size_t b = 0; b < nb; ++b)
+        for (int64_t e = dp.blk_e0[b]; e < dp.blk_e0[b + 1]; ++e) {
+          const uint32_t pos = dp.ent_pos[(size_t)e], r = pos >> 8, c = pos & 255u;
+          bits[b * 256 + r * 2 + (c >> 5)] |= 1u << (c & 31u);
+        }
+      std::vector<float> colscale(colslot.size(), 0.f), rowscale((size_t)h.rowscale_off.back(), 0.f);
+      for (size_t i = 0; i < colslot.size(); ++i)
+        if (dp.colslot_vertex[i] >= 0) colscale[i] = scale_of(dp.colslot_vertex[i]);
+      for (int k = 0; k < s.K; ++k)
+        for (int64_t pp = 0; pp < s.chunk_ptr[k + 1] - s.chunk_ptr[k]; ++pp)
+          rowscale[(size_t)(h.rowscale_off[(size_t)k] + pp)] = scale_of(dp.row_perm[(size_t)(s.chunk_ptr[k] + pp)]);
+      if (hipMemcpy(st->at<uint32_t>(lay.d_bits[dir]), bits.data(), sizeof(uint32_t) * bits.size(), hipMemcpyHostToDevice) != hipSuccess ||
+          hipMemcpy(st->at<float>(lay.d_colscale[dir]), colscale.data(), sizeof(float) * colscale.size(), hipMemcpyHostToDevice) != hipSuccess ||
+          hipMemcpy(st->at<float>(lay.d_rowscale[dir]), rowscale.data(), sizeof(float) * rowscale.size(), hipMemcpyHostToDevice) != hipSuccess)
+        return bail(GNNSTAGE_EHIP, "uploading the dense patterns failed");
+      st->rowscale_off[dir] = h.rowscale_off;
+    } else {
+      const size_t ne_pad = (size_t)h.padded_entries();
+      std::vector<uint32_t> ent_w(ne_pad, 0u);
+      std::vector<uint16_t> ent_pos(ne_pad, (uint16_t)0xffff);
+      std::vector<int64_t> blk_e0(nb + 1, 0);
+      for (int k = 0; k < s.K; ++k)
+        for (int64_t b = dp.chunk_blk_off[(size_t)k]; b < dp.chunk_blk_off[(size_t)k + 1]; ++b) {
+          int64_t at = blk_e0[(size_t)b];
+          for (int64_t e = dp.blk_e0[(size_t)b]; e < dp.blk_e0[(size_t)b + 1]; ++e, ++at) {
+            const uint32_t pos = dp.ent_pos[(size_t)e];
+            const int64_t e_csr = dir ? t_edge[(size_t)dp.ent_orig[(size_t)e]] : dp.ent_orig[(size_t)e];
+            const float wgt = d->edge_val[e_csr];
+            const uint16_t hi = bf16_bits_rne(wgt), lo = bf16_bits_rne(wgt - bf16_bits_to_f32(hi));
+            ent_w[(size_t)at] = (uint32_t)hi | ((uint32_t)lo << 16);
+            ent_pos[(size_t)at] = (uint16_t)pos;
+          }
+          blk_e0[(size_t)b + 1] = (at + 7) / 8 * 8;
+        }
+      if (hipMemcpy(st->at<int64_t>(lay.d_blk_e0[dir]), blk_e0.data(), sizeof(int64_t) * (nb + 1), hipMemcpyHostToDevice) != hipSuccess ||
+          hipMemcpy(st->at<uint16_t>(lay.d_ent_pos[dir]), ent_pos.data(), sizeof(uint16_t) * ne_pad, hipMemcpyHostToDevice) != hipSuccess ||
+          hipMemcpy(st->at<uint32_t>(lay.d_ent_w[dir]), ent_w.data(), sizeof(uint32_t) * ne_pad, hipMemcpyHostToDevice) != hipSuccess)
+        return bail(GNNSTAGE_EHIP, "uploading the dense entries failed");
+      if (launch_fill_zero(st->at<char>(lay.d_tiles[dir]), sizeof(uint16_t) * nb * 2 * kDenseRB * kDenseCB, nullptr) != 0 ||
+          launch_dense_expand(st->at<int64_t>(lay.d_blk_e0[dir]), st->at<uint16_t>(lay.d_ent_pos[dir]),
+                              st->at<uint32_t>(lay.d_ent_w[dir]), st->at<char>(lay.d_tiles[dir]), (int64_t)nb, nullptr) != 0)
+        return bail(GNNSTAGE_EHIP, "expanding the dense blocks failed");
+    }
+    st->dense_rank1 = rank1;
+    st->dense_on[dir] = true;
+    st->dense_entries[dir] = (int64_t)ne;
+  }
   if (d->edge_val) {
-    std::vector<float> tval((size_t)s.nnz);
-    for (int64_t p = 0; p < s.nnz; ++p) tval[(size_t)p] = d->edge_val[t_edge[(size_t)p]];
-    if (hipMemcpy(st->at<float>(lay.val), d->edge_val, sizeof(float) * s.nnz, hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(st->at<float>(lay.tval), tval.data(), sizeof(float) * s.nnz, hipMemcpyHostToDevice) != hipSuccess)
+    std::vector<float> fval, tval((size_t)hp.b.nnz);
+    const float *fv = d->edge_val;
+    if (hp.f.dense()) {
+      fval.resize((size_t)hp.f.nnz);
+      for (int64_t i = 0; i < hp.f.nnz; ++i) fval[(size_t)i] = d->edge_val[hp.f.dp.rem_orig[(size_t)i]];
+      fv = fval.data();
+    }
+    for (int64_t i = 0; i < hp.b.nnz; ++i)
+      tval[(size_t)i] = d->edge_val[t_edge[(size_t)(hp.b.dense() ? hp.b.dp.rem_orig[(size_t)i] : i)]];
+    if ((hp.f.nnz > 0 && hipMemcpy(st->at<float>(lay.val), fv, sizeof(float) * hp.f.nnz, hipMemcpyHostToDevice) != hipSuccess) ||
+        (hp.b.nnz > 0 && hipMemcpy(st->at<float>(lay.tval), tval.data(), sizeof(float) * hp.b.nnz, hipMemcpyHostToDevice) != hipSuccess))
       return bail(GNNSTAGE_EHIP, "uploading edge values failed");
   } else {
-    // Section 2.1 weights from the row lengths of A + I, for the CSR entries and for their transposed copies
+    // Section 2.1 weights from the row lengths of A + I, for the (remaining) CSR entries and for their transposed copies
     const int64_t *rp = st->at<int64_t>(lay.row_ptr);
-    if (launch_gcn_norm(rp, st->at<uint32_t>(lay.pcol), vbits, rp, s.n, st->at<float>(lay.val), nullptr) != 0 ||
-        launch_gcn_norm(st->at<int64_t>(lay.t_ptr), st->at<uint32_t>(lay.prow), vbits, rp, s.n, st->at<float>(lay.tval), nullptr) != 0)
+    const int64_t *fp = hp.f.dense() ? st->at<int64_t>(lay.rem_ptr[0]) : rp;
+    const int64_t *bp = hp.b.dense() ? st->at<int64_t>(lay.rem_ptr[1]) : st->at<int64_t>(lay.t_ptr);
+    if (launch_gcn_norm(fp, st->at<uint32_t>(lay.pcol), vbits, rp, s.n, st->at<float>(lay.val), nullptr) != 0 ||
+        launch_gcn_norm(bp, st->at<uint32_t>(lay.prow), vbits, rp, s.n, st->at<float>(lay.tval), nullptr) != 0)
       return bail(GNNSTAGE_EHIP, "normalisation kernel launch failed");
   }
-  rc = build(d->row_ptr, d->col_idx, pcol.data(), fc, false, st->ftasks);
-  if (rc == GNNSTAGE_OK) rc = build(t_ptr.data(), t_row.data(), prow.data(), bc, true, st->btasks);
+  rc = build(hp.f, pcol.data(), false, st->ftasks);
+  if (rc == GNNSTAGE_OK) rc = build(hp.b, prow.data(), true, st->btasks);
   if (rc != GNNSTAGE_OK) return bail(rc, "building the launch schedule failed");
   if (hipDeviceSynchronize() != hipSuccess) return bail(GNNSTAGE_EHIP, "device synchronisation failed after create");
   *out = st;
@@ -877,7 +1243,7 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
       a.out_row0 = 0;
       a.epilogue = SPMM_BIAS_RELU;
       a.bias = static_cast<const float *>(st->bias[j]);
-      HIP_TRY(st, run_spmm(st, a, cd, cd, stream, 0, j));
+      HIP_TRY(st, run_spmm(st, a, false, k, cd, cd, stream, 0, j));
       continue;
     }
     char *Zj = st->at<char>(st->lay.Z[j]);
@@ -899,7 +1265,7 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
       } else {
         a.epilogue = SPMM_PLAIN;
       }
-      HIP_TRY(st, run_spmm(st, a, st->level_dtype(j), cd, stream, 0, j));
+      HIP_TRY(st, run_spmm(st, a, false, k, st->level_dtype(j), cd, stream, 0, j));
     }
     {
       Timed t(st, stream, 1, j);
@@ -994,7 +1360,7 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
         a.out_ld = s.ld[j + 1];
         a.out_row0 = row0;
         a.epilogue = SPMM_PLAIN;
-        HIP_TRY(st, run_spmm(st, a, cd, cd, stream, 2, j));
+        HIP_TRY(st, run_spmm(st, a, true, k, cd, cd, stream, 2, j));
       }
       if (!shared) {
         Timed t(st, stream, 4, j);
@@ -1114,13 +1480,13 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
         a.epilogue = SPMM_MASK;
         a.aux = st->cur[j];
         a.aux_ld = s.dims[j];
-        HIP_TRY(st, run_spmm(st, a, cd, cd, stream, 2, j));
+        HIP_TRY(st, run_spmm(st, a, true, k, cd, cd, stream, 2, j));
       } else {
         a.out = st->grad_in;
         a.out_ld = s.dims[0];
         a.out_row0 = 0;
         a.epilogue = SPMM_PLAIN;
-        HIP_TRY(st, run_spmm(st, a, cd, st->level_dtype(0), stream, 2, j));
+        HIP_TRY(st, run_spmm(st, a, true, k, cd, st->level_dtype(0), stream, 2, j));
       }
     }
     gi ^= 1;

@@ -74,9 +74,10 @@ struct Task {
 
 extern "C" int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, int64_t n_vertices, int64_t row_begin,
                                        int64_t row_end, int32_t split_edges, int32_t n_classes,
-                                       const int64_t *class_lo, int32_t class_min_row, int64_t capacity,
-                                       int32_t *task_row, int64_t *task_e0, int32_t *task_ne, int32_t *task_slot,
-                                       int64_t *n_slots_out, int64_t *class_off, uint8_t *slot_class) {
+                                       const int64_t *class_lo, int32_t class_min_row, const uint8_t *force_slot,
+                                       int64_t capacity, int32_t *task_row, int64_t *task_e0, int32_t *task_ne,
+                                       int32_t *task_slot, int64_t *n_slots_out, int64_t *class_off,
+                                       uint8_t *slot_class) {
   if (!ptr || row_begin > row_end || split_edges <= 0 || n_classes < 1 || n_classes > 64 || n_vertices <= 0)
     return GNNSTAGE_EINVAL;
   const bool classes = n_classes > 1 && idx != nullptr;
@@ -108,7 +109,9 @@ extern "C" int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, i
   for (int64_t r = row_begin; r < row_end; ++r) {
     const int64_t b = ptr[r], e = ptr[r + 1], len = e - b;
     const bool by_src = classes && len >= class_min_row;
-    if (!by_src && len <= split_edges) {  // empty rows included: they still write zeros
+    const bool forced = force_slot && force_slot[r];  // the row's sum has further parts: no task may finish it
+    if (forced && len == 0) continue;
+    if (!by_src && len <= split_edges && !forced) {  // empty rows included: they still write zeros
       whole.push_back(Task{(int32_t)r, b, (int32_t)len, -1});
       continue;
     }

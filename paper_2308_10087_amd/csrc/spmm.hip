@@ -177,6 +177,8 @@ __global__ __launch_bounds__(256) void spmm_reduce_kernel(const SpmmArgs a) {
   const int ph = threadIdx.x >> 5, cv = threadIdx.x & 31;
   const int64_t row = a.lr_row[i];
   const int slot0 = a.lr_slot0[i], ns = a.lr_nslots[i];
+  const int nd = a.lr_ndense ? a.lr_ndense[i] : 0;
+  const int dense0 = nd > 0 ? a.lr_dense0[i] : 0, item0 = nd > 0 ? a.lr_item0[i] : 0;
   // pieces of classes that were not run in this launch (all their entries unselected) hold stale data
   const bool check = a.slot_class != nullptr && a.all_classes_active == 0;
   for (int c0 = 0; c0 < a.d; c0 += 32 * VEC) {
@@ -191,6 +193,17 @@ __global__ __launch_bounds__(256) void spmm_reduce_kernel(const SpmmArgs a) {
           if (sc < 32u && !((a.active_classes >> sc) & 1u)) continue;
         }
         const Pack<float, VEC> x = *reinterpret_cast<const Pack<float, VEC> *>(a.partial + (size_t)(slot0 + s) * a.d + c);
+#pragma unroll
+        for (int t = 0; t < VEC; ++t) acc[t] += x.v[t];
+      }
+      // the row's parts from dense blocks: one partial row per item of its row block
+      for (int g = ph; g < nd; g += 8) {
+        if (a.drop_unselected) {  // an item without a selected chunk was not run
+          const ChunkMask &m = a.item_chunks[item0 + g];
+          if (((m.w[0] & a.mask.w[0]) | (m.w[1] & a.mask.w[1]) | (m.w[2] & a.mask.w[2]) | (m.w[3] & a.mask.w[3])) == 0) continue;
+        }
+        const Pack<float, VEC> x =
+            *reinterpret_cast<const Pack<float, VEC> *>(a.dense_partial + ((size_t)dense0 + (size_t)g * kDenseRB) * a.d + c);
 #pragma unroll
         for (int t = 0; t < VEC; ++t) acc[t] += x.v[t];
       }

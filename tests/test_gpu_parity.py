@@ -179,6 +179,43 @@ def test_deeper_gather_queues(monkeypatch, slots, name):
     _parity(p, TOL_BF16)
 
 
+@pytest.mark.parametrize("weights", ["given", "computed"])
+@pytest.mark.parametrize("min_nnz,classes", [(6, 1), (24, 8), (2, 1)])
+@pytest.mark.parametrize("name", ["c1_s", "c2_s", "c3_s"])
+def test_dense_blocks_forced_on_small_graphs(monkeypatch, min_nnz, classes, name, weights):
+    """Blocks of the degree-ordered matrix with enough entries are multiplied as dense tiles on the matrix
+    cores, the rest stays sparse; force that split on the shrunk graphs (tiny thresholds, with and without
+    source classes, ragged chunks), forward and backward, against the one oracle.  With weights given by
+    the caller a block is a pair of bf16 weight tiles; when the library computes the normalisation itself
+    (w = s(v) s(u)) it is a bit pattern and the scales move to the source rows and the result rows."""
+    monkeypatch.setenv("GNNSTAGE_DENSE_MIN_NNZ", str(min_nnz))
+    monkeypatch.setenv("GNNSTAGE_DENSE_MIN_SHARE", "0")
+    monkeypatch.setenv("GNNSTAGE_XCD_CLASSES", str(classes))
+    monkeypatch.setenv("GNNSTAGE_CLASS_MIN_ROW", "16")
+    w = CONFIGS[name]
+    row_ptr, col = __import__("synth").make_graph(w)
+    n = len(row_ptr) - 1
+    p = make_problem(w, graph=(row_ptr, col), chunk_ptr=graphs.ragged_chunks(n, w.n_chunks, 23), bias_std=0.05)
+    probe = _gpu(p, edge_val=weights)
+    assert probe.stage.gnnstage_dense_entries(False) > 0 and probe.stage.gnnstage_dense_entries(True) > 0
+    _parity(p, TOL_BF16, edge_val=weights)
+
+
+def test_dense_blocks_switched_off_give_the_same_levels(monkeypatch):
+    """The split into dense blocks and sparse remainder only regroups the same sum."""
+    p = make_problem(CONFIGS["c1_s"], bias_std=0.05)
+    monkeypatch.setenv("GNNSTAGE_DENSE_MIN_NNZ", "6")
+    monkeypatch.setenv("GNNSTAGE_DENSE_MIN_SHARE", "0")
+    a = _gpu(p)
+    a.forward()
+    monkeypatch.setenv("GNNSTAGE_DENSE", "0")
+    b = _gpu(p)
+    b.forward()
+    torch.cuda.synchronize()
+    for j in range(1, p.L + 1):
+        assert max_rel(a.np(a.cur[j]), b.np(b.cur[j])) <= 1e-2
+
+
 @pytest.mark.parametrize("name", ["c1_s", "c2_s", "c3_s", "c4_s"])
 def test_persistent_gemm_on_small_inputs(monkeypatch, name):
     """The weight-stationary persistent GEMM normally serves only long operands; force it everywhere."""
@@ -275,6 +312,8 @@ def test_bf16_aggregation_is_exact_on_exactly_summable_inputs(d, deg, wbits, xma
     p.grad_out = rng.integers(-1, 2, size=p.grad_out.shape).astype(np.float32)
     ref = run_oracle(p)
     run = _gpu(p).run()
+    # the denser graphs take the dense-block path (rows of width 128 or 256 only)
+    assert (run.stage.gnnstage_dense_entries(False) > 0) == (deg >= 70.0 and d in (128, 256))
     assert np.array_equal(run.np(run.cur[1]), ref.cur[1])
     assert np.array_equal(run.np(run.grad_in), ref.grad_in)
     assert len(np.unique(ref.cur[1])) > 50
