@@ -14,8 +14,11 @@ constexpr int kMaxChunks = 256;
 constexpr int kMaxClasses = 32;  // source-id classes of the aggregation schedule (a 32-bit activity mask)
 constexpr int kMaxSegs = 12;     // class segments one XCD may serve in a launch
 
+// The word is picked with selects, not with an indexed access: a kernel that holds the mask as an argument
+// would otherwise fetch the word from memory and wait for it (and for every other load in flight).
 __host__ __device__ inline bool mask_test(const ChunkMask &m, uint32_t c) {
-  return (m.w[(c >> 6) & 3] >> (c & 63)) & 1ull;
+  const uint64_t lo = (c & 64u) ? m.w[1] : m.w[0], hi = (c & 64u) ? m.w[3] : m.w[2];
+  return (((c & 128u) ? hi : lo) >> (c & 63u)) & 1ull;
 }
 
 // ---- aggregation (SpMM with current/history select) ---------------------------------

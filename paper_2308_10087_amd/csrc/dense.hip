@@ -189,20 +189,27 @@ __global__ __launch_bounds__(256, 2) void spmm_dense_kernel(const DenseArgs a) {
 }
 
 // The same product for weights of the form w(v, u) = s(v) * s(u) (the normalisation of Section 2.1 computed
-// by the library itself): a block is then a 0/1 pattern (kept as 128 x 64 bits), the source rows are scaled
-// by s(u) while they are staged - in fp32, split into the nearest bf16 and the bf16 of the remainder - and
-// the accumulator rows are scaled by s(v) at the end:  out[v] = s(v) * sum_u P(v, u) * (s(u) h(u)).
+// by the library itself).  A block is then a 0/1 pattern, kept as 128 x 64 bits; the weight tiles are made
+// in LDS from the pattern and the 64 column scales (each split into the nearest bf16 and the bf16 of the
+// remainder), and the accumulator rows are scaled by s(v) at the end:
+//     out[v] = s(v) * sum_u P(v, u) * s(u) * h(u).
+// Per item everything that does not depend on the block's data is resolved once: the column slots become
+// (vertex | selected << 31), padding slots and - in a backward launch - unselected sources become 0xffffffff
+// (their rows count as zero), and the column scales of all its blocks sit in LDS as ready-made bf16 pairs.
 __global__ __launch_bounds__(256, 2) void spmm_dense_r1_kernel(const DenseArgs a) {
   constexpr int NI = 2;
   constexpr int GROUPS = DH / 8;
   constexpr int SETS = 64 / GROUPS;
   constexpr int PPL = 8 / SETS;
+  constexpr int S = 3;  // blocks whose loads are in flight (register slots)
   extern __shared__ __attribute__((aligned(16))) unsigned char dense_smem[];
-  bf16_t *A01 = reinterpret_cast<bf16_t *>(dense_smem);                    // [128][A_PITCH] zeros and ones
-  uint32_t *Hh = reinterpret_cast<uint32_t *>(A01 + kDenseRB * A_PITCH);  // [32 source pairs][DH], upper parts
-  uint32_t *Hl = Hh + 32 * DH;                                            // lower parts
-  uint32_t *ids = Hl + 32 * DH;                                           // [blocks of the item][64] column slots
-  int32_t *m_cb = reinterpret_cast<int32_t *>(ids + kDenseMaxItemBlocks * kDenseCB);
+  bf16_t *A_hi = reinterpret_cast<bf16_t *>(dense_smem);                   // [128][A_PITCH]
+  bf16_t *A_lo = A_hi + kDenseRB * A_PITCH;
+  uint32_t *Hp = reinterpret_cast<uint32_t *>(A_lo + kDenseRB * A_PITCH);  // [32 source pairs][DH] interleaved pairs
+  uint32_t *ids = Hp + 32 * DH;                                           // [blocks][64] resolved column slots
+  uint32_t *cs = ids + kDenseMaxItemBlocks * kDenseCB;                    // [blocks][32 column pairs][2]: upper parts, lower parts
+  int32_t *m_cb = reinterpret_cast<int32_t *>(cs + kDenseMaxItemBlocks * kDenseCB);
+  int32_t *act = m_cb + kDenseMaxItemBlocks;                              // the item's selected blocks, in order
 
   const int item = blockIdx.x;
   const int col0 = blockIdx.y * DH;
@@ -214,13 +221,44 @@ __global__ __launch_bounds__(256, 2) void spmm_dense_r1_kernel(const DenseArgs a
   const int64_t b0 = a.item_b0[item];
   const int nb = a.item_nb[item];
   const bf16_t *src_sel = static_cast<const bf16_t *>(a.src_sel) + col0;
-  const bf16_t *src_unsel = drop ? nullptr : static_cast<const bf16_t *>(a.src_unsel) + col0;
+  const bf16_t *src_unsel = drop ? src_sel : static_cast<const bf16_t *>(a.src_unsel) + col0;
   const size_t ld = (size_t)a.src_ld;
 
   if (tid < nb) m_cb[tid] = a.blk_cb[b0 + tid];
   __syncthreads();
-  for (int i = tid; i < nb * kDenseCB; i += 256) ids[i] = a.colslot[(int64_t)m_cb[i >> 6] * kDenseCB + (i & 63)];
+  for (int i = tid; i < nb * kDenseCB; i += 256) {
+    const int64_t slot = (int64_t)m_cb[i >> 6] * kDenseCB + (i & 63);
+    const uint32_t pc = a.colslot[slot];
+    uint32_t id = 0xffffffffu;
+    if (pc != 0xffffffffu) {
+      const bool sel = mask_test(a.mask, pc >> a.vbits);
+      if (sel || !drop) id = (pc & vmask) | (sel ? 0x80000000u : 0u);
+    }
+    ids[i] = id;
+  }
+  for (int i = tid; i < nb * (kDenseCB / 2); i += 256) {  // column pair (2i, 2i + 1) of a block
+    const int64_t slot = (int64_t)m_cb[i >> 5] * kDenseCB + 2 * (i & 31);
+    uint32_t part[2][2];  // [column of the pair][upper, lower]
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      const float sc = a.colscale[slot + c];  // zero for padding slots
+      const bf16_t h = (bf16_t)sc;
+      const bf16_t l = (bf16_t)(sc - (float)h);
+      part[c][0] = __builtin_bit_cast(uint16_t, h);
+      part[c][1] = __builtin_bit_cast(uint16_t, l);
+    }
+    cs[2 * i] = part[0][0] | (part[1][0] << 16);
+    cs[2 * i + 1] = part[0][1] | (part[1][1] << 16);
+  }
   __syncthreads();
+  if (wave == 0) {  // a block whose first slot resolved to "zero row" in a backward launch has no selected source
+    const bool on = lane < nb && (!drop || ids[(lane < nb ? lane : 0) * kDenseCB] != 0xffffffffu);
+    const uint64_t bal = __ballot(on);
+    if (on) act[__popcll(bal & ((1ull << lane) - 1ull))] = lane;
+    if (lane == 0) act[kDenseMaxItemBlocks] = __popcll(bal);
+  }
+  __syncthreads();
+  const int na = act[kDenseMaxItemBlocks];
 
   f32x16 acc[2][NI];
 #pragma unroll
@@ -231,114 +269,128 @@ __global__ __launch_bounds__(256, 2) void spmm_dense_r1_kernel(const DenseArgs a
       for (int t = 0; t < 16; ++t) acc[mi][ni][t] = 0.f;
 
   const int ng = lane % GROUPS, set = lane / GROUPS;
-  u32x4 x0[PPL], x1[PPL];
-  float s0[PPL], s1[PPL];
-  uint32_t bits = 0;  // this thread's 32 cells of the pattern: row tid / 2, columns 32 * (tid % 2) ..
-  auto next_active = [&](int bi) {
-    while (bi < nb && drop && !mask_test(a.mask, ids[bi * kDenseCB] >> a.vbits)) ++bi;
-    return bi;
-  };
-  auto issue = [&](int bi) {
-    bits = a.bits[(size_t)(b0 + bi) * 256 + tid];
-    const int64_t slot0 = (int64_t)m_cb[bi] * kDenseCB;
+  // register slots: slot u carries the active block i with i % S == u from its loads to LDS.  Every load is
+  // unconditional (a zero row reads row 0 and is cleared afterwards), so the number of younger loads at every
+  // wait is a compile-time constant.
+  u32x4 x0[S][PPL], x1[S][PPL];
+  uint32_t bits[S];  // this thread's 32 cells of the pattern: row tid / 2, columns 32 * (tid % 2) ..
+  uint32_t zero[S];  // bit 2j / 2j+1: row 0 / 1 of pair j counts as zero
+  auto issue = [&](int bi, int u) {
+    bits[u] = a.bits[(size_t)(b0 + bi) * 256 + tid];
+    zero[u] = 0u;
 #pragma unroll
     for (int j = 0; j < PPL; ++j) {
       const int kp = wave * 8 + j * SETS + set;
-      const uint32_t pc0 = ids[bi * kDenseCB + 2 * kp], pc1 = ids[bi * kDenseCB + 2 * kp + 1];
-      x0[j] = u32x4{0u, 0u, 0u, 0u};
-      x1[j] = u32x4{0u, 0u, 0u, 0u};
-      s0[j] = a.colscale[slot0 + 2 * kp];
-      s1[j] = a.colscale[slot0 + 2 * kp + 1];
-      if (pc0 != 0xffffffffu) {
-        const bool sel = mask_test(a.mask, pc0 >> a.vbits);
-        if (sel || !drop) x0[j] = *reinterpret_cast<const u32x4 *>((sel ? src_sel : src_unsel) + (size_t)(pc0 & vmask) * ld + ng * 8);
-      }
-      if (pc1 != 0xffffffffu) {
-        const bool sel = mask_test(a.mask, pc1 >> a.vbits);
-        if (sel || !drop) x1[j] = *reinterpret_cast<const u32x4 *>((sel ? src_sel : src_unsel) + (size_t)(pc1 & vmask) * ld + ng * 8);
-      }
+      const uint32_t i0 = ids[bi * kDenseCB + 2 * kp], i1 = ids[bi * kDenseCB + 2 * kp + 1];
+      const bool z0 = i0 == 0xffffffffu, z1 = i1 == 0xffffffffu;
+      zero[u] |= (z0 ? 1u : 0u) << (2 * j) | (z1 ? 2u : 0u) << (2 * j);
+      x0[u][j] = *reinterpret_cast<const u32x4 *>(((i0 >> 31) && !z0 ? src_sel : src_unsel) + (size_t)(z0 ? 0u : (i0 & 0x7fffffffu)) * ld + ng * 8);
+      x1[u][j] = *reinterpret_cast<const u32x4 *>(((i1 >> 31) && !z1 ? src_sel : src_unsel) + (size_t)(z1 ? 0u : (i1 & 0x7fffffffu)) * ld + ng * 8);
     }
+    __builtin_amdgcn_sched_barrier(0);  // keep the slots' loads in program order (the waits count younger loads)
   };
-  // (hi, lo) bf16 parts of s * x for one bf16 element taken from the low or high half of a word
-  auto scaled = [](uint32_t word, bool high, float sc, uint32_t &hi, uint32_t &lo) {
-    const float f = __uint_as_float(high ? (word & 0xffff0000u) : (word << 16)) * sc;
-    const bf16_t h = (bf16_t)f;
-    const bf16_t l = (bf16_t)(f - (float)h);
-    hi = __builtin_bit_cast(uint16_t, h);
-    lo = __builtin_bit_cast(uint16_t, l);
-  };
-
-  int cur = next_active(0);
-  if (cur < nb) issue(cur);
-  while (cur < nb) {
-    const int nxt = next_active(cur + 1);
+  auto consume = [&](int bi, int u) {
     __syncthreads();  // the previous block's fragment reads are done
-    {  // pattern: 32 cells -> 32 bf16 (1.0 = 0x3f80)
-      u32x4 *dst = reinterpret_cast<u32x4 *>(A01 + (tid >> 1) * A_PITCH + (tid & 1) * 32);
+    {  // weight tiles from the pattern: cell (r, c) = bit ? scale part of column c : 0
+      const uint32_t w = bits[u];
+      const u32x4 *cp = reinterpret_cast<const u32x4 *>(cs + (size_t)bi * kDenseCB + (tid & 1) * 32);
+      u32x4 *dh = reinterpret_cast<u32x4 *>(A_hi + (tid >> 1) * A_PITCH + (tid & 1) * 32);
+      u32x4 *dl = reinterpret_cast<u32x4 *>(A_lo + (tid >> 1) * A_PITCH + (tid & 1) * 32);
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        u32x4 w;
+      for (int q = 0; q < 4; ++q) {  // 8 columns = 4 pairs
+        const u32x4 c0 = cp[2 * q], c1 = cp[2 * q + 1];  // pairs 4q, 4q+1 | 4q+2, 4q+3: (upper, lower) each
+        u32x4 vh, vl;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-          const uint32_t two = (bits >> (8 * q + 2 * t)) & 3u;
-          w[t] = ((two & 1u) ? 0x3f80u : 0u) | ((two & 2u) ? 0x3f800000u : 0u);
+          const int m0 = __builtin_amdgcn_sbfe(w, 8 * q + 2 * t, 1), m1 = __builtin_amdgcn_sbfe(w, 8 * q + 2 * t + 1, 1);
+          const uint32_t mask = ((uint32_t)m0 & 0xffffu) | ((uint32_t)m1 & 0xffff0000u);
+          const uint32_t up = t < 2 ? c0[2 * t] : c1[2 * (t - 2)], lw = t < 2 ? c0[2 * t + 1] : c1[2 * (t - 2) + 1];
+          vh[t] = up & mask;
+          vl[t] = lw & mask;
         }
-        dst[q] = w;
+        dh[q] = vh;
+        dl[q] = vl;
       }
     }
-    // source rows, scaled: word n of pair kp holds (row 2kp, row 2kp+1) at column n
+    // source rows: word n of pair kp holds (row 2kp, row 2kp+1) at column n
 #pragma unroll
     for (int j = 0; j < PPL; ++j) {
       const int kp = wave * 8 + j * SETS + set;
-      u32x4 h4[2], l4[2];
+      const bool z0 = (zero[u] >> (2 * j)) & 1u, z1 = (zero[u] >> (2 * j)) & 2u;
+      u32x4 lo4, hi4;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {  // word q of the 16-byte piece: columns 2q and 2q + 1
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          uint32_t ah, al, bh, bl;
-          scaled(x0[j][q], e == 1, s0[j], ah, al);
-          scaled(x1[j][q], e == 1, s1[j], bh, bl);
-          h4[q >> 1][(q & 1) * 2 + e] = ah | (bh << 16);
-          l4[q >> 1][(q & 1) * 2 + e] = al | (bl << 16);
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t p0 = z0 ? 0u : x0[u][j][q], p1 = z1 ? 0u : x1[u][j][q];
+        const uint32_t even = __builtin_amdgcn_perm(p1, p0, 0x05040100u), odd = __builtin_amdgcn_perm(p1, p0, 0x07060302u);
+        if (q < 2) {
+          lo4[2 * q] = even;
+          lo4[2 * q + 1] = odd;
+        } else {
+          hi4[2 * (q - 2)] = even;
+          hi4[2 * (q - 2) + 1] = odd;
         }
       }
-      u32x4 *dh = reinterpret_cast<u32x4 *>(Hh + (size_t)kp * DH + ng * 8);
-      u32x4 *dl = reinterpret_cast<u32x4 *>(Hl + (size_t)kp * DH + ng * 8);
-      dh[0] = h4[0];
-      dh[1] = h4[1];
-      dl[0] = l4[0];
-      dl[1] = l4[1];
+      u32x4 *dst = reinterpret_cast<u32x4 *>(Hp + (size_t)kp * DH + ng * 8);
+      dst[0] = lo4;
+      dst[1] = hi4;
     }
-    __syncthreads();  // pattern and source rows are in place
-    if (nxt < nb) issue(nxt);  // the next block's loads fly while this one is multiplied
+    __syncthreads();  // weights and source rows are in place
+  };
+  auto multiply = [&]() {
 #pragma unroll
     for (int ks = 0; ks < kDenseCB / 16; ++ks) {
-      bf16x8 fa[2], fbh[NI], fbl[NI];
+      bf16x8 fh[2], fl[2], fb[NI];
       const int koff = ks * 16 + (lane >> 5) * 8;
 #pragma unroll
-      for (int mi = 0; mi < 2; ++mi) fa[mi] = *reinterpret_cast<const bf16x8 *>(&A01[(wm + mi * 32 + (lane & 31)) * A_PITCH + koff]);
+      for (int mi = 0; mi < 2; ++mi) {
+        fh[mi] = *reinterpret_cast<const bf16x8 *>(&A_hi[(wm + mi * 32 + (lane & 31)) * A_PITCH + koff]);
+        fl[mi] = *reinterpret_cast<const bf16x8 *>(&A_lo[(wm + mi * 32 + (lane & 31)) * A_PITCH + koff]);
+      }
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni) {
-        u32x4 wh, wl;
+        u32x4 w4;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const size_t at = (size_t)(ks * 8 + (lane >> 5) * 4 + j) * DH + wn + ni * 32 + (lane & 31);
-          wh[j] = Hh[at];
-          wl[j] = Hl[at];
-        }
-        fbh[ni] = __builtin_bit_cast(bf16x8, wh);
-        fbl[ni] = __builtin_bit_cast(bf16x8, wl);
+        for (int j = 0; j < 4; ++j) w4[j] = Hp[(size_t)(ks * 8 + (lane >> 5) * 4 + j) * DH + wn + ni * 32 + (lane & 31)];
+        fb[ni] = __builtin_bit_cast(bf16x8, w4);
       }
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fbh[ni], acc[mi][ni], 0, 0, 0);
+        for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fh[mi], fb[ni], acc[mi][ni], 0, 0, 0);
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fbl[ni], acc[mi][ni], 0, 0, 0);
+        for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fl[mi], fb[ni], acc[mi][ni], 0, 0, 0);
     }
-    cur = nxt;
+  };
+
+  // prologue, steady groups of S blocks (every refill unconditional), tail
+  int i = 0;
+  if (na >= 2 * S) {
+#pragma unroll
+    for (int u = 0; u < S; ++u) issue(act[u], u);
+    for (; i + 2 * S <= na; i += S) {
+#pragma unroll
+      for (int u = 0; u < S; ++u) {
+        consume(act[i + u], u);
+        issue(act[i + S + u], u);
+        multiply();
+      }
+    }
+  } else {
+#pragma unroll
+    for (int u = 0; u < S; ++u)
+      if (u < na) issue(act[u], u);
+  }
+  for (; i < na; i += S) {
+#pragma unroll
+    for (int u = 0; u < S; ++u) {
+      if (i + u < na) {
+        consume(act[i + u], u);
+        if (i + S + u < na) issue(act[i + S + u], u);
+        multiply();
+      }
+    }
   }
   float *P = a.partial + (size_t)item * kDenseRB * a.d + col0;
   const float *rs = a.rowscale + (size_t)a.item_rb[item] * kDenseRB;  // zero past the last row of the chunk
@@ -367,8 +419,8 @@ int launch_spmm_dense(const DenseArgs &a, hipStream_t s) {
     attr_done = true;
   }
   if (a.bits) {
-    const size_t smem1 = (size_t)kDenseRB * A_PITCH * sizeof(bf16_t) + (size_t)2 * 32 * DH * sizeof(uint32_t) +
-                         (size_t)kDenseMaxItemBlocks * kDenseCB * sizeof(uint32_t) + kDenseMaxItemBlocks * sizeof(int32_t);
+    const size_t smem1 = (size_t)2 * kDenseRB * A_PITCH * sizeof(bf16_t) + (size_t)32 * DH * sizeof(uint32_t) +
+                         (size_t)2 * kDenseMaxItemBlocks * kDenseCB * sizeof(uint32_t) + (2 * kDenseMaxItemBlocks + 1) * sizeof(int32_t);
     static bool attr1_done = false;
     if (!attr1_done) {
       (void)hipFuncSetAttribute(reinterpret_cast<const void *>(spmm_dense_r1_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
