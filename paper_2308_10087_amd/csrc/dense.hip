@@ -296,9 +296,12 @@ __global__ __launch_bounds__(256, 2) void spmm_dense_r1_kernel(const DenseArgs a
       const u32x4 *cp = reinterpret_cast<const u32x4 *>(cs + (size_t)bi * kDenseCB + (tid & 1) * 32);
       u32x4 *dh = reinterpret_cast<u32x4 *>(A_hi + (tid >> 1) * A_PITCH + (tid & 1) * 32);
       u32x4 *dl = reinterpret_cast<u32x4 *>(A_lo + (tid >> 1) * A_PITCH + (tid & 1) * 32);
+      u32x4 cw[8];  // all reads first: one LDS latency instead of four
+#pragma unroll
+      for (int q = 0; q < 8; ++q) cw[q] = cp[q];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {  // 8 columns = 4 pairs
-        const u32x4 c0 = cp[2 * q], c1 = cp[2 * q + 1];  // pairs 4q, 4q+1 | 4q+2, 4q+3: (upper, lower) each
+        const u32x4 c0 = cw[2 * q], c1 = cw[2 * q + 1];  // pairs 4q, 4q+1 | 4q+2, 4q+3: (upper, lower) each
         u32x4 vh, vl;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -336,31 +339,37 @@ __global__ __launch_bounds__(256, 2) void spmm_dense_r1_kernel(const DenseArgs a
     }
     __syncthreads();  // weights and source rows are in place
   };
+  // fragments of the next k-step are read from LDS while the current one is multiplied
   auto multiply = [&]() {
-#pragma unroll
-    for (int ks = 0; ks < kDenseCB / 16; ++ks) {
-      bf16x8 fh[2], fl[2], fb[NI];
+    bf16x8 fh[2][2], fl[2][2], fb[2][NI];
+    auto frags = [&](int ks, int f) {
       const int koff = ks * 16 + (lane >> 5) * 8;
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi) {
-        fh[mi] = *reinterpret_cast<const bf16x8 *>(&A_hi[(wm + mi * 32 + (lane & 31)) * A_PITCH + koff]);
-        fl[mi] = *reinterpret_cast<const bf16x8 *>(&A_lo[(wm + mi * 32 + (lane & 31)) * A_PITCH + koff]);
+        fh[f][mi] = *reinterpret_cast<const bf16x8 *>(&A_hi[(wm + mi * 32 + (lane & 31)) * A_PITCH + koff]);
+        fl[f][mi] = *reinterpret_cast<const bf16x8 *>(&A_lo[(wm + mi * 32 + (lane & 31)) * A_PITCH + koff]);
       }
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni) {
         u32x4 w4;
 #pragma unroll
         for (int j = 0; j < 4; ++j) w4[j] = Hp[(size_t)(ks * 8 + (lane >> 5) * 4 + j) * DH + wn + ni * 32 + (lane & 31)];
-        fb[ni] = __builtin_bit_cast(bf16x8, w4);
+        fb[f][ni] = __builtin_bit_cast(bf16x8, w4);
       }
+    };
+    frags(0, 0);
+#pragma unroll
+    for (int ks = 0; ks < kDenseCB / 16; ++ks) {
+      const int f = ks & 1;
+      if (ks + 1 < kDenseCB / 16) frags(ks + 1, f ^ 1);
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fh[mi], fb[ni], acc[mi][ni], 0, 0, 0);
+        for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fh[f][mi], fb[f][ni], acc[mi][ni], 0, 0, 0);
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fl[mi], fb[ni], acc[mi][ni], 0, 0, 0);
+        for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fl[f][mi], fb[f][ni], acc[mi][ni], 0, 0, 0);
     }
   };
 

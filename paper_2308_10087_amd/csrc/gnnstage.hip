@@ -78,8 +78,8 @@ std::vector<int64_t> class_bounds(int64_t n, int classes, const std::vector<int6
 
 // Dense blocks: switched on for bf16 stages whose aggregations all gather rows of width 128 or 256.
 // GNNSTAGE_DENSE=0 switches them off; GNNSTAGE_DENSE_MIN_NNZ (entries a 128 x 64 block needs, default 5 %
-// of its cells) and GNNSTAGE_DENSE_MIN_SHARE (share of all entries that must fall into such blocks,
-// default 0.2) let tests force them on small graphs.
+// of its cells), GNNSTAGE_DENSE_MIN_SHARE (share of all entries that must fall into such blocks,
+// default 0.2) and GNNSTAGE_DENSE_MIN_ENTRIES (see below) let tests force them on small graphs.
 bool dense_enabled() {
   const char *e = getenv("GNNSTAGE_DENSE");
   return !(e && atoi(e) == 0);
@@ -92,6 +92,13 @@ int dense_min_nnz() {
 double dense_min_share() {
   const char *e = getenv("GNNSTAGE_DENSE_MIN_SHARE");
   return e ? atof(e) : 0.2;
+}
+// A dense launch has a fixed cost (its longest item runs 32 blocks one after the other, some tens of
+// microseconds); it only pays when it takes a lot of entries off the sparse kernel: at least this many per
+// chunk on average (GNNSTAGE_DENSE_MIN_ENTRIES; the sparse kernel gathers about 40 entries per nanosecond).
+double dense_min_entries_per_chunk() {
+  const char *e = getenv("GNNSTAGE_DENSE_MIN_ENTRIES");
+  return e ? atof(e) : 2e6;
 }
 constexpr int kDenseItemBlocks = kDenseMaxItemBlocks;
 
@@ -192,7 +199,12 @@ bool make_host_dir(const int64_t *ptr, const int32_t *idx, int64_t n, const std:
   h.rowscale_off.assign((size_t)K + 1, 0);
   for (int k = 0; k < K; ++k)
     h.rowscale_off[(size_t)k + 1] = h.rowscale_off[(size_t)k] + (chunk_ptr[(size_t)k + 1] - chunk_ptr[(size_t)k] + kDenseRB - 1) / kDenseRB * kDenseRB;
-  if (try_dense && !build_dense_plan(ptr, idx, n, K, chunk_ptr.data(), dense_min_nnz(), dense_min_share(), h.dp)) return false;
+  if (try_dense) {
+    // share of all entries that must be dense: the relative threshold, or the absolute one if that asks for more
+    const double nnz = (double)ptr[n];
+    const double share = std::max(dense_min_share(), nnz > 0 ? dense_min_entries_per_chunk() * K / nnz : 0.0);
+    if (!build_dense_plan(ptr, idx, n, K, chunk_ptr.data(), dense_min_nnz(), share, h.dp)) return false;
+  }
   if (h.dp.active) {
     const DensePlan &dp = h.dp;
     h.ptr = dp.rem_ptr.data();

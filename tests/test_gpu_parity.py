@@ -190,6 +190,7 @@ def test_dense_blocks_forced_on_small_graphs(monkeypatch, min_nnz, classes, name
     (w = s(v) s(u)) it is a bit pattern and the scales move to the source rows and the result rows."""
     monkeypatch.setenv("GNNSTAGE_DENSE_MIN_NNZ", str(min_nnz))
     monkeypatch.setenv("GNNSTAGE_DENSE_MIN_SHARE", "0")
+    monkeypatch.setenv("GNNSTAGE_DENSE_MIN_ENTRIES", "0")
     monkeypatch.setenv("GNNSTAGE_XCD_CLASSES", str(classes))
     monkeypatch.setenv("GNNSTAGE_CLASS_MIN_ROW", "16")
     w = CONFIGS[name]
@@ -206,6 +207,7 @@ def test_dense_blocks_switched_off_give_the_same_levels(monkeypatch):
     p = make_problem(CONFIGS["c1_s"], bias_std=0.05)
     monkeypatch.setenv("GNNSTAGE_DENSE_MIN_NNZ", "6")
     monkeypatch.setenv("GNNSTAGE_DENSE_MIN_SHARE", "0")
+    monkeypatch.setenv("GNNSTAGE_DENSE_MIN_ENTRIES", "0")
     a = _gpu(p)
     a.forward()
     monkeypatch.setenv("GNNSTAGE_DENSE", "0")
@@ -295,12 +297,13 @@ def test_indicator_probe_counts_selected_neighbours(roles):
 
 @pytest.mark.parametrize("d,deg,wbits,xmax", [(128, 9.0, 12, 4), (256, 9.0, 12, 4), (256, 200.0, 12, 4),
                                               (512, 70.0, 12, 4), (256, 9.0, 16, 2), (128, 30.0, 16, 2)])
-def test_bf16_aggregation_is_exact_on_exactly_summable_inputs(d, deg, wbits, xmax):
+def test_bf16_aggregation_is_exact_on_exactly_summable_inputs(monkeypatch, d, deg, wbits, xmax):
     """Edge weights with 12 or 16 significant bits (more than one bf16 holds), rows of small integers, W = I,
     b = 0: every product and every partial sum is exact in fp32, so level 1 and the input gradient are the
     bf16 rounding of the exact sum - bit for bit.  Fails if the matrix-core aggregation loses the low half
     of a weight, drops or repeats an entry, or reads a row from the wrong buffer.  Rows of 200 entries
     span several metadata batches."""
+    monkeypatch.setenv("GNNSTAGE_DENSE_MIN_ENTRIES", "0")  # small graph: let its dense blocks (if any) be used
     n = 1500
     w = small(n=n, k=5, dims=(d, d), dtype="bf16", deg=deg, seed=41)
     p = make_problem(w, chunk_ptr=graphs.ragged_chunks(n, 5, 11), bias_std=0.0)
