@@ -55,7 +55,7 @@ int class_min_row_setting() {
     const int v = atoi(e);
     if (v >= 1) return v;
   }
-  return 256;
+  return 128;  // measured: shorter rows than this cost more in partial sums than their locality gains
 }
 
 // Lower bounds of the source-id classes: equal id ranges, except that a bound moves onto a chunk boundary
