@@ -266,6 +266,24 @@ def test_first_stage_with_aliased_history(dtype, d0):
     _parity(p, TOL_F32 if dtype == "f32" else TOL_BF16, need_input_grad=True, alias_hist0=True)
 
 
+def test_full_size_c1_in_the_benchmark_configuration():
+    """configs[1] at full size, exactly as bench.py runs it (first stage: history of level 0 is the feature
+    buffer itself, no input gradient, library-computed weights, dense blocks + source classes active): every
+    level and every weight gradient against the oracle.  About a minute of oracle time on 16 host threads."""
+    p = make_problem(CONFIGS["c1"], bias_std=0.05)
+    probe = _gpu(p, need_input_grad=False, alias_hist0=True, edge_val="computed")
+    assert probe.stage.gnnstage_dense_entries(False) > 10_000_000 and probe.stage.gnnstage_dense_entries(True) > 10_000_000
+    del probe
+    torch.cuda.empty_cache()
+    _parity(p, TOL_BF16, need_input_grad=False, alias_hist0=True, edge_val="computed")
+
+
+def test_full_size_c3_gcnii_stage():
+    """configs[3] at full size: 16 GCNII layers over the 169k-vertex power-law graph, bf16."""
+    p = make_problem(CONFIGS["c3"], bias_std=0.0)
+    _parity(p, TOL_BF16)
+
+
 # ----------------------------------------------------------------------------- select mask, bit-exact
 @pytest.mark.parametrize("roles", ["cur1_hist0", "cur0_hist1"])
 def test_indicator_probe_counts_selected_neighbours(roles):
