@@ -66,7 +66,8 @@ def gcnii_beta(first_layer: int, n_layers: int) -> np.ndarray:
 
 
 def make_problem(w: Workload, *, graph=None, chunk_ptr=None, order=None, bias_std: float = 0.1,
-                 first_stage: Optional[bool] = None, shuffle: bool = True, noise_std: float = 0.01) -> Problem:
+                 first_stage: Optional[bool] = None, shuffle: bool = True, noise_std: float = 0.01,
+                 history: str = "clean") -> Problem:
     row_ptr, col = graph if graph is not None else make_graph(w)
     n = row_ptr.shape[0] - 1
     val = oracle.gcn_norm(row_ptr, col)
@@ -94,15 +95,21 @@ def make_problem(w: Workload, *, graph=None, chunk_ptr=None, order=None, bias_st
     grad_out = g(values.normal(w.seed, 3, (n, dims[-1])))
     if order is None:
         order = values.permutation(w.seed, 4, K) if shuffle else np.arange(K, dtype=np.int32)
-    # historical buffers: a clean full-graph pass (one chunk => no staleness) plus N(0, noise_std^2)
-    clean = oracle.OracleStage(row_ptr, col, val, np.array([0, n], dtype=np.int64), dims, W, b,
-                               variant=w.variant, a=a, beta=beta, h0=h0, quant=quant, level0_f32=w.level0_f32)
-    clean.cur[0][...] = x0
-    clean.forward_pass([0])
+    # historical buffers: a clean full-graph pass (one chunk => no staleness) plus N(0, noise_std^2);
+    # history="random" skips the pass (full-size graphs): |N(0,1)| rows, like post-ReLU embeddings
+    clean = None
+    if history == "clean":
+        clean = oracle.OracleStage(row_ptr, col, val, np.array([0, n], dtype=np.int64), dims, W, b,
+                                   variant=w.variant, a=a, beta=beta, h0=h0, quant=quant, level0_f32=w.level0_f32)
+        clean.cur[0][...] = x0
+        clean.forward_pass([0])
     hist = []
     for j in range(L):
         if j == 0 and first_stage:
             hist.append(x0.copy())
+        elif clean is None:
+            hj = values.half_normal(w.seed, 300 + j, (n, dims[j]))
+            hist.append(g0(hj) if j == 0 else g(hj))
         else:
             hj = clean.cur[j] + values.normal(w.seed, 300 + j, (n, dims[j]), noise_std)
             hist.append(g0(hj) if j == 0 else g(hj))

@@ -284,6 +284,30 @@ def test_full_size_c3_gcnii_stage():
     _parity(p, TOL_BF16)
 
 
+def test_full_size_c2_first_chunks_of_a_pass():
+    """configs[2] at full size (2.45 M vertices, 16 chunks, 8 layers of width 128, no source classes: the
+    gathered table is beyond the memory-side cache): the first two chunks of a forward pass, every level of
+    their rows against the oracle.  The second chunk reads the first one's current rows, everything else
+    comes from (random) history.  The backward pass needs a complete forward pass on both sides and is left
+    to the shrunk configuration."""
+    p = make_problem(CONFIGS["c2"], bias_std=0.05, history="random")
+    order = [int(k) for k in p.order[:2]]
+    st = p.new_oracle()
+    st.forward_pass(order)
+    run = _gpu(p, need_input_grad=False, alias_hist0=True, edge_val="computed")
+    run.forward(order)
+    torch.cuda.synchronize()
+    for k in order:
+        rows = st.rows(k)
+        for j in range(1, p.L + 1):
+            a, b = run.np(run.cur[j][rows]), st.cur[j][rows]
+            assert max_rel(a, b) <= TOL_BF16, (k, j, max_rel(a, b))
+            flips = (a > 0) != (b > 0)
+            assert flips.mean() <= 1e-2
+            if flips.any():
+                assert np.maximum(np.abs(a[flips]), np.abs(b[flips])).max() <= TOL_BF16 * np.abs(b).max()
+
+
 # ----------------------------------------------------------------------------- select mask, bit-exact
 @pytest.mark.parametrize("roles", ["cur1_hist0", "cur0_hist1"])
 def test_indicator_probe_counts_selected_neighbours(roles):
