@@ -356,19 +356,6 @@ bool read_shape(const gnnstage_desc *d, Shape &s, std::string &err) {
   return true;
 }
 
-// column occupancy of the transposed index without building it
-std::vector<int64_t> transposed_ptr(const gnnstage_desc *d, const Shape &s, std::string &err) {
-  std::vector<int64_t> t((size_t)s.n + 1, 0);
-  if (s.nnz > 0 && !d->col_idx) { err = "col_idx is NULL"; return {}; }
-  for (int64_t e = 0; e < s.nnz; ++e) {
-    const int64_t u = d->col_idx[e];
-    if (u < 0 || u >= s.n) { err = "col_idx entry out of range"; return {}; }
-    t[(size_t)u + 1]++;
-  }
-  for (int64_t i = 0; i < s.n; ++i) t[i + 1] += t[i];
-  return t;
-}
-
 Layout make_layout(const Shape &s, const HostDir &hf, const HostDir &hb, bool rank1) {
   const PlanCounts &f = hf.pc, &b = hb.pc;
   Layout l;
