@@ -125,6 +125,7 @@ struct DenseArgs {
   const uint32_t *bits;
   const float *colscale;
   const float *rowscale;          // [row blocks of the chunk * 128], zero past the chunk's last row
+  const void *zero_row;           // at least 512 bytes of zeros, 16-byte aligned
   const uint32_t *colslot;        // vertex | chunk << vbits of every column slot, 0xffffffff = padding
   const void *src_sel;            // rows of vertices whose chunk is in the mask
   const void *src_unsel;          // rows of the others; nullptr => they contribute zero

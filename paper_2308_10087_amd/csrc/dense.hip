@@ -223,6 +223,7 @@ __global__ __launch_bounds__(256, 2) void spmm_dense_r1_kernel(const DenseArgs a
   const bf16_t *src_sel = static_cast<const bf16_t *>(a.src_sel) + col0;
   const bf16_t *src_unsel = drop ? src_sel : static_cast<const bf16_t *>(a.src_unsel) + col0;
   const size_t ld = (size_t)a.src_ld;
+  const bf16_t *zrow = static_cast<const bf16_t *>(a.zero_row);  // 128 zeros are enough for any column half
 
   if (tid < nb) m_cb[tid] = a.blk_cb[b0 + tid];
   __syncthreads();
@@ -270,22 +271,21 @@ __global__ __launch_bounds__(256, 2) void spmm_dense_r1_kernel(const DenseArgs a
 
   const int ng = lane % GROUPS, set = lane / GROUPS;
   // register slots: slot u carries the active block i with i % S == u from its loads to LDS.  Every load is
-  // unconditional (a zero row reads row 0 and is cleared afterwards), so the number of younger loads at every
+  // unconditional (a zero row reads a row of zeros), so the number of younger loads at every
   // wait is a compile-time constant.
   u32x4 x0[S][PPL], x1[S][PPL];
   uint32_t bits[S];  // this thread's 32 cells of the pattern: row tid / 2, columns 32 * (tid % 2) ..
-  uint32_t zero[S];  // bit 2j / 2j+1: row 0 / 1 of pair j counts as zero
   auto issue = [&](int bi, int u) {
     bits[u] = a.bits[(size_t)(b0 + bi) * 256 + tid];
-    zero[u] = 0u;
 #pragma unroll
     for (int j = 0; j < PPL; ++j) {
       const int kp = wave * 8 + j * SETS + set;
       const uint32_t i0 = ids[bi * kDenseCB + 2 * kp], i1 = ids[bi * kDenseCB + 2 * kp + 1];
-      const bool z0 = i0 == 0xffffffffu, z1 = i1 == 0xffffffffu;
-      zero[u] |= (z0 ? 1u : 0u) << (2 * j) | (z1 ? 2u : 0u) << (2 * j);
-      x0[u][j] = *reinterpret_cast<const u32x4 *>(((i0 >> 31) && !z0 ? src_sel : src_unsel) + (size_t)(z0 ? 0u : (i0 & 0x7fffffffu)) * ld + ng * 8);
-      x1[u][j] = *reinterpret_cast<const u32x4 *>(((i1 >> 31) && !z1 ? src_sel : src_unsel) + (size_t)(z1 ? 0u : (i1 & 0x7fffffffu)) * ld + ng * 8);
+      const bool z0 = i0 == 0xffffffffu, z1 = i1 == 0xffffffffu;  // zero rows are read from a row of zeros
+      const bf16_t *r0 = z0 ? zrow : ((i0 >> 31) ? src_sel : src_unsel) + (size_t)(i0 & 0x7fffffffu) * ld;
+      const bf16_t *r1 = z1 ? zrow : ((i1 >> 31) ? src_sel : src_unsel) + (size_t)(i1 & 0x7fffffffu) * ld;
+      x0[u][j] = *reinterpret_cast<const u32x4 *>(r0 + ng * 8);
+      x1[u][j] = *reinterpret_cast<const u32x4 *>(r1 + ng * 8);
     }
     __builtin_amdgcn_sched_barrier(0);  // keep the slots' loads in program order (the waits count younger loads)
   };
@@ -319,11 +319,10 @@ __global__ __launch_bounds__(256, 2) void spmm_dense_r1_kernel(const DenseArgs a
 #pragma unroll
     for (int j = 0; j < PPL; ++j) {
       const int kp = wave * 8 + j * SETS + set;
-      const bool z0 = (zero[u] >> (2 * j)) & 1u, z1 = (zero[u] >> (2 * j)) & 2u;
       u32x4 lo4, hi4;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const uint32_t p0 = z0 ? 0u : x0[u][j][q], p1 = z1 ? 0u : x1[u][j][q];
+        const uint32_t p0 = x0[u][j][q], p1 = x1[u][j][q];
         const uint32_t even = __builtin_amdgcn_perm(p1, p0, 0x05040100u), odd = __builtin_amdgcn_perm(p1, p0, 0x07060302u);
         if (q < 2) {
           lo4[2 * q] = even;

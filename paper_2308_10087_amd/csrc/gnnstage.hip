@@ -261,7 +261,7 @@ struct Layout {
   size_t d_bits[2], d_colscale[2], d_rowscale[2];  // weights of the form s(row) * s(column): patterns and scales
   size_t d_item_rb[2], d_item_b0[2], d_item_nb[2], d_item_chunks[2];
   size_t d_lr_dense0[2], d_lr_ndense[2], d_lr_item0[2];
-  size_t dense_partial;
+  size_t dense_partial, zero_row;
   size_t partial;
   std::vector<size_t> Z, dZ, Wt, Wn, Tc, Th;
   size_t G[2];
@@ -392,6 +392,7 @@ Layout make_layout(const Shape &s, const HostDir &hf, const HostDir &hb, bool ra
     max_items = std::max(max_items, h.max_items);
   }
   l.dense_partial = w.take(sizeof(float) * (size_t)max_items * kDenseRB * 256);
+  l.zero_row = w.take(max_items > 0 ? 512 : 0);
   l.f_task_row = w.take(sizeof(int32_t) * f.total_tasks);
   l.f_task_e0 = w.take(sizeof(int64_t) * f.total_tasks);
   l.f_task_ne = w.take(sizeof(int32_t) * f.total_tasks);
@@ -711,6 +712,7 @@ int run_spmm(gnnstage *st, const SpmmArgs &a_in, bool transposed, int chunk, int
         da.bits = st->at<uint32_t>(lay.d_bits[dir]);
         da.colscale = st->at<float>(lay.d_colscale[dir]);
         da.rowscale = st->at<float>(lay.d_rowscale[dir]) + st->rowscale_off[dir][(size_t)chunk];
+        da.zero_row = st->at<char>(lay.zero_row);
       } else {
         da.tiles = st->at<bf16_t>(lay.d_tiles[dir]);
       }
@@ -1121,6 +1123,7 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
         return bail(GNNSTAGE_EHIP, "expanding the dense blocks failed");
     }
     st->dense_rank1 = rank1;
+    if (launch_fill_zero(st->at<char>(lay.zero_row), 512, nullptr) != 0) return bail(GNNSTAGE_EHIP, "clearing the zero row failed");
     st->dense_on[dir] = true;
     st->dense_entries[dir] = (int64_t)ne;
   }
