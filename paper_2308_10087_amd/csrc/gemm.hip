@@ -20,6 +20,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef bf16_t bf16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ inline float to_f32(float x) { return x; }
 __device__ inline float to_f32(bf16_t x) { return (float)x; }
@@ -459,14 +461,31 @@ static int launch_ws(const GemmNtArgs &a, hipStream_t s) {
 
 // ------------------------------------------------------------------------------------ bf16 TN
 constexpr int TR = 64;      // reduction rows per step (two 16 KB operand tiles in flight per workgroup)
-constexpr int LDS_C = 136;  // padded column stride of the row-major LDS tiles
+constexpr int LDS_P = 132;  // padded stride, in words, of one row pair of an LDS tile
+
+// Both operands of the TN product are read along the reduction index (rows of A and of B), which is the slow
+// index of their row-major tiles.  The LDS tiles therefore hold ROW PAIRS: word [p][c] is (row 2p, row 2p+1) of
+// column c, so that the eight reduction elements of a matrix-core fragment are four 32-bit reads down one column.
+__device__ __forceinline__ void store_row_pair(uint32_t *dst, const bf16x8 &even, const bf16x8 &odd) {
+  const u32x4 x = __builtin_bit_cast(u32x4, even), y = __builtin_bit_cast(u32x4, odd);
+  u32x4 lo, hi;
+#pragma unroll
+  for (int w = 0; w < 2; ++w) {
+    lo[2 * w] = __builtin_amdgcn_perm(y[w], x[w], 0x05040100u);
+    lo[2 * w + 1] = __builtin_amdgcn_perm(y[w], x[w], 0x07060302u);
+    hi[2 * w] = __builtin_amdgcn_perm(y[w + 2], x[w + 2], 0x05040100u);
+    hi[2 * w + 1] = __builtin_amdgcn_perm(y[w + 2], x[w + 2], 0x07060302u);
+  }
+  *reinterpret_cast<u32x4 *>(dst) = lo;
+  *reinterpret_cast<u32x4 *>(dst + 4) = hi;
+}
 
 // PAIR: fp32 A with an even leading dimension and an 8-byte aligned base; a tile row (128 floats) is read by
 // one wave instruction as 64 float pairs.
 template <typename TA, bool VEC, bool PAIR = false>
 __global__ __launch_bounds__(256) void gemm_tn_bf16_kernel(const GemmTnArgs a, int rows_per_split, int splits) {
-  __shared__ __attribute__((aligned(16))) bf16_t As[TR * LDS_C];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[TR * LDS_C];
+  __shared__ __attribute__((aligned(16))) uint32_t As[TR / 2 * LDS_P];
+  __shared__ __attribute__((aligned(16))) uint32_t Bs[TR / 2 * LDS_P];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   // XCD-aware order: the output tiles that read the same rows of A and B sit on one XCD (one L2)
   const int ti = (a.I + 127) / 128, tiles = ti * ((a.O + 127) / 128);
@@ -507,7 +526,7 @@ __global__ __launch_bounds__(256) void gemm_tn_bf16_kernel(const GemmTnArgs a, i
     if constexpr (PAIR) {
 #pragma unroll
       for (int i = 0; i < NPR; ++i) {
-        const int r = wave + 4 * i, c = i0 + 2 * lane;
+        const int r = 2 * (wave + 4 * (i >> 1)) + (i & 1), c = i0 + 2 * lane;
         f32x2 v = {0.f, 0.f};
         if (r0 + r < r_end) {
           const float *p = reinterpret_cast<const float *>(A) + (size_t)(r0 + r) * a.lda + c;
@@ -521,7 +540,7 @@ __global__ __launch_bounds__(256) void gemm_tn_bf16_kernel(const GemmTnArgs a, i
     }
 #pragma unroll
     for (int i = 0; i < NVT; ++i) {
-      const int vid = tid + 256 * i, r = vid >> 4, c = (vid & 15) * 8;
+      const int r = 2 * ((tid >> 4) + 16 * (i >> 1)) + (i & 1), c = (tid & 15) * 8;  // slots 2h, 2h+1: one row pair
       const bool rv = r0 + r < r_end;
       if constexpr (!PAIR) ra[i] = rv ? load8_bf16<TA, VEC>(A, (size_t)a.lda, r0 + r, i0 + c, a_cols) : zero8;
       rb[i] = (rv && o0 + c < a.ldb) ? *reinterpret_cast<const bf16x8 *>(B + (size_t)(r0 + r) * a.ldb + o0 + c) : zero8;
@@ -532,31 +551,39 @@ __global__ __launch_bounds__(256) void gemm_tn_bf16_kernel(const GemmTnArgs a, i
     __syncthreads();  // previous step's fragment reads are done
     if constexpr (PAIR) {
 #pragma unroll
-      for (int i = 0; i < NPR; ++i) {
-        const bf16x2 v = {(bf16_t)rp[i][0], (bf16_t)rp[i][1]};
-        *reinterpret_cast<bf16x2 *>(&As[(wave + 4 * i) * LDS_C + 2 * lane]) = v;
+      for (int h = 0; h < NPR / 2; ++h) {
+        const bf16x2 c0 = {(bf16_t)rp[2 * h][0], (bf16_t)rp[2 * h + 1][0]};
+        const bf16x2 c1 = {(bf16_t)rp[2 * h][1], (bf16_t)rp[2 * h + 1][1]};
+        const u32x2 v = {__builtin_bit_cast(uint32_t, c0), __builtin_bit_cast(uint32_t, c1)};
+        *reinterpret_cast<u32x2 *>(&As[(wave + 4 * h) * LDS_P + 2 * lane]) = v;
       }
     }
 #pragma unroll
-    for (int i = 0; i < NVT; ++i) {
-      const int vid = tid + 256 * i, r = vid >> 4, c = (vid & 15) * 8;
-      if constexpr (!PAIR) *reinterpret_cast<bf16x8 *>(&As[r * LDS_C + c]) = ra[i];
-      *reinterpret_cast<bf16x8 *>(&Bs[r * LDS_C + c]) = rb[i];
+    for (int h = 0; h < NVT / 2; ++h) {
+      const int p = (tid >> 4) + 16 * h, c = (tid & 15) * 8;
+      if constexpr (!PAIR) store_row_pair(&As[p * LDS_P + c], ra[2 * h], ra[2 * h + 1]);
+      store_row_pair(&Bs[p * LDS_P + c], rb[2 * h], rb[2 * h + 1]);
     }
     __syncthreads();
     if (r0 + TR < r_end) gload(r0 + TR);  // next tile's loads fly while this one is multiplied
 #pragma unroll
     for (int kk = 0; kk < TR / 16; ++kk) {
-      const int roff = kk * 16 + (lane >> 5) * 8;
+      const int poff = kk * 8 + (lane >> 5) * 4;  // first of the fragment's four row pairs
       bf16x8 fa[2], fb[2];
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < 2; ++i) {
+        u32x4 w;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) fa[i][t] = As[(roff + t) * LDS_C + wi + i * 32 + (lane & 31)];
+        for (int t = 0; t < 4; ++t) w[t] = As[(poff + t) * LDS_P + wi + i * 32 + (lane & 31)];
+        fa[i] = __builtin_bit_cast(bf16x8, w);
+      }
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < 2; ++j) {
+        u32x4 w;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) fb[j][t] = Bs[(roff + t) * LDS_C + wo + j * 32 + (lane & 31)];
+        for (int t = 0; t < 4; ++t) w[t] = Bs[(poff + t) * LDS_P + wo + j * 32 + (lane & 31)];
+        fb[j] = __builtin_bit_cast(bf16x8, w);
+      }
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
