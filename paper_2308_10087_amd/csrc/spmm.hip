@@ -32,9 +32,21 @@ __device__ inline float from_f32<float>(float x) { return x; }
 template <>
 __device__ inline bf16_t from_f32<bf16_t>(float x) { return (bf16_t)x; }
 
-// Applies the epilogue to VEC consecutive columns of one output row and stores them.
+// The row of the auxiliary matrix that the mixing and masking epilogues read (zeros for the others).
+template <typename Tin, int VEC>
+__device__ inline Pack<Tin, VEC> load_aux(const SpmmArgs &a, int64_t row, int c) {
+  if (a.epilogue == SPMM_MIX || a.epilogue == SPMM_MASK)
+    return *reinterpret_cast<const Pack<Tin, VEC> *>(static_cast<const Tin *>(a.aux) + (size_t)row * a.aux_ld + c);
+  Pack<Tin, VEC> z;
+#pragma unroll
+  for (int t = 0; t < VEC; ++t) z.v[t] = from_f32<Tin>(0.f);
+  return z;
+}
+
+// Applies the epilogue to VEC consecutive columns of one output row and stores them; x is load_aux of the
+// same columns (a caller with other loads in flight asks for it early).
 template <typename Tin, typename Tout, int VEC>
-__device__ inline void finish_cols(const SpmmArgs &a, int64_t row, int c, const float (&acc)[VEC]) {
+__device__ inline void finish_cols(const SpmmArgs &a, int64_t row, int c, const float (&acc)[VEC], const Pack<Tin, VEC> &x) {
   float r[VEC];
   if (a.epilogue == SPMM_PLAIN) {
 #pragma unroll
@@ -45,24 +57,25 @@ __device__ inline void finish_cols(const SpmmArgs &a, int64_t row, int c, const 
       const float y = acc[t] + a.bias[c + t];
       r[t] = y > 0.f ? y : 0.f;
     }
+  } else if (a.epilogue == SPMM_MIX) {
+#pragma unroll
+    // one rounding for the dominant (1 - alpha) term: with rows on the bf16 grid the exact mix often sits
+    // exactly half-way between two bf16 values, and rounding the large product separately would push all
+    // of those ties the same way
+    for (int t = 0; t < VEC; ++t) r[t] = __builtin_fmaf(a.s_acc, acc[t], a.s_aux * to_f32(x.v[t]));
   } else {
-    const Pack<Tin, VEC> x = *reinterpret_cast<const Pack<Tin, VEC> *>(
-        static_cast<const Tin *>(a.aux) + (size_t)row * a.aux_ld + c);
-    if (a.epilogue == SPMM_MIX) {
 #pragma unroll
-      // one rounding for the dominant (1 - alpha) term: with rows on the bf16 grid the exact mix often sits
-      // exactly half-way between two bf16 values, and rounding the large product separately would push all
-      // of those ties the same way
-      for (int t = 0; t < VEC; ++t) r[t] = __builtin_fmaf(a.s_acc, acc[t], a.s_aux * to_f32(x.v[t]));
-    } else {
-#pragma unroll
-      for (int t = 0; t < VEC; ++t) r[t] = to_f32(x.v[t]) > 0.f ? acc[t] : 0.f;
-    }
+    for (int t = 0; t < VEC; ++t) r[t] = to_f32(x.v[t]) > 0.f ? acc[t] : 0.f;
   }
   Pack<Tout, VEC> o;
 #pragma unroll
   for (int t = 0; t < VEC; ++t) o.v[t] = from_f32<Tout>(r[t]);
   *reinterpret_cast<Pack<Tout, VEC> *>(static_cast<Tout *>(a.out) + (size_t)(row - a.out_row0) * a.out_ld + c) = o;
+}
+
+template <typename Tin, typename Tout, int VEC>
+__device__ inline void finish_cols(const SpmmArgs &a, int64_t row, int c, const float (&acc)[VEC]) {
+  finish_cols<Tin, Tout, VEC>(a, row, c, acc, load_aux<Tin, VEC>(a, row, c));
 }
 
 template <typename Tout>
@@ -170,15 +183,20 @@ __global__ __launch_bounds__(256) void spmm_kernel(const SpmmArgs a) {
 // Sums the pieces of every cut row, then applies the epilogue.  One workgroup per row: 8 phases x 32
 // column vectors; phase p adds the slots p, p+8, p+16, ... (hub rows have hundreds of pieces), then the 8
 // phase sums are added in order.  The order is fixed, so results are reproducible.
+// A workgroup moves a few KB, so what it costs is its chain of dependent memory round trips.  There are
+// two: the row's header words, then everything else at once.  Pieces that may not count (a class or an item
+// that did not run in this launch holds stale sums) are loaded anyway, together with the word that says so,
+// and left out by a select; the epilogue's auxiliary row is asked for before the sums.
 template <typename Tin, typename Tout, int VEC>
 __global__ __launch_bounds__(256) void spmm_reduce_kernel(const SpmmArgs a) {
   __shared__ float red[8][32][VEC];
   const int64_t i = blockIdx.x;
   const int ph = threadIdx.x >> 5, cv = threadIdx.x & 31;
+  const bool dense = a.lr_ndense != nullptr;
   const int64_t row = a.lr_row[i];
   const int slot0 = a.lr_slot0[i], ns = a.lr_nslots[i];
-  const int nd = a.lr_ndense ? a.lr_ndense[i] : 0;
-  const int dense0 = nd > 0 ? a.lr_dense0[i] : 0, item0 = nd > 0 ? a.lr_item0[i] : 0;
+  const int nd = dense ? a.lr_ndense[i] : 0;
+  const int dense0 = dense ? a.lr_dense0[i] : 0, item0 = dense ? a.lr_item0[i] : 0;
   // pieces of classes that were not run in this launch (all their entries unselected) hold stale data
   const bool check = a.slot_class != nullptr && a.all_classes_active == 0;
   for (int c0 = 0; c0 < a.d; c0 += 32 * VEC) {
@@ -186,26 +204,27 @@ __global__ __launch_bounds__(256) void spmm_reduce_kernel(const SpmmArgs a) {
     float acc[VEC];
 #pragma unroll
     for (int t = 0; t < VEC; ++t) acc[t] = 0.f;
+    Pack<Tin, VEC> xa;
     if (c < a.d) {
+      if (ph == 0) xa = load_aux<Tin, VEC>(a, row, c);
       for (int s = ph; s < ns; s += 8) {
-        if (check) {
-          const uint32_t sc = a.slot_class[slot0 + s];
-          if (sc < 32u && !((a.active_classes >> sc) & 1u)) continue;
-        }
+        const uint32_t sc = check ? a.slot_class[slot0 + s] : 32u;
         const Pack<float, VEC> x = *reinterpret_cast<const Pack<float, VEC> *>(a.partial + (size_t)(slot0 + s) * a.d + c);
+        const bool use = sc >= 32u || ((a.active_classes >> sc) & 1u);
 #pragma unroll
-        for (int t = 0; t < VEC; ++t) acc[t] += x.v[t];
+        for (int t = 0; t < VEC; ++t) acc[t] += use ? x.v[t] : 0.f;
       }
       // the row's parts from dense blocks: one partial row per item of its row block
       for (int g = ph; g < nd; g += 8) {
+        bool use = true;
         if (a.drop_unselected) {  // an item without a selected chunk was not run
-          const ChunkMask &m = a.item_chunks[item0 + g];
-          if (((m.w[0] & a.mask.w[0]) | (m.w[1] & a.mask.w[1]) | (m.w[2] & a.mask.w[2]) | (m.w[3] & a.mask.w[3])) == 0) continue;
+          const ChunkMask m = a.item_chunks[item0 + g];
+          use = ((m.w[0] & a.mask.w[0]) | (m.w[1] & a.mask.w[1]) | (m.w[2] & a.mask.w[2]) | (m.w[3] & a.mask.w[3])) != 0;
         }
         const Pack<float, VEC> x =
             *reinterpret_cast<const Pack<float, VEC> *>(a.dense_partial + ((size_t)dense0 + (size_t)g * kDenseRB) * a.d + c);
 #pragma unroll
-        for (int t = 0; t < VEC; ++t) acc[t] += x.v[t];
+        for (int t = 0; t < VEC; ++t) acc[t] += use ? x.v[t] : 0.f;
       }
     }
 #pragma unroll
@@ -216,7 +235,7 @@ __global__ __launch_bounds__(256) void spmm_reduce_kernel(const SpmmArgs a) {
       for (int p = 1; p < 8; ++p)
 #pragma unroll
         for (int t = 0; t < VEC; ++t) acc[t] += red[p][cv][t];
-      finish_cols<Tin, Tout, VEC>(a, row, c, acc);
+      finish_cols<Tin, Tout, VEC>(a, row, c, acc, xa);
     }
     __syncthreads();
   }
