@@ -73,6 +73,30 @@ def erdos_renyi(n: int, avg_degree: float, seed: int):
     return from_undirected_pairs(n, iu, ju)
 
 
+def planted_partition(n: int, n_groups: int, deg_in: float, deg_out: float, seed: int):
+    """Planted-partition (stochastic block) graph: vertex v belongs to group ``group[v]`` (drawn uniformly);
+    every vertex draws about ``deg_in`` partners inside its group and ``deg_out`` anywhere.  Returns
+    ``(row_ptr, col, group)``; a synthetic node-classification task whose labels the structure reveals."""
+    rng = np.random.Generator(np.random.PCG64([seed, 77]))
+    group = rng.integers(0, n_groups, size=n).astype(np.int32)
+    order = np.argsort(group, kind="stable")
+    start = np.searchsorted(group[order], np.arange(n_groups + 1))
+    size = np.diff(start)
+    k_in = rng.poisson(deg_in / 2.0, size=n)
+    src_in = np.repeat(np.arange(n), k_in)
+    g = group[src_in]
+    pick = (rng.random(src_in.shape[0]) * size[g]).astype(np.int64)
+    dst_in = order[start[g] + np.minimum(pick, size[g] - 1)]
+    k_out = rng.poisson(deg_out / 2.0, size=n)
+    src_out = np.repeat(np.arange(n), k_out)
+    dst_out = rng.integers(0, n, size=src_out.shape[0])
+    iu = np.concatenate([src_in, src_out])
+    ju = np.concatenate([dst_in, dst_out])
+    keep = iu != ju
+    row_ptr, col = from_undirected_pairs(n, iu[keep], ju[keep])
+    return row_ptr, col, group
+
+
 def from_undirected_pairs(n: int, iu, ju):
     """Symmetric CSR with self-loops from a list of distinct undirected pairs."""
     iu = np.asarray(iu, dtype=np.int64)

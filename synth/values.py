@@ -33,3 +33,17 @@ def glorot_uniform(seed: int, stream: int, d_in: int, d_out: int) -> np.ndarray:
 def permutation(seed: int, stream: int, k: int) -> np.ndarray:
     """A chunk processing order (chunk shuffling, Section 3.4 technique 1)."""
     return _rng(seed, stream).permutation(k).astype(np.int32)
+
+
+def group_features(seed: int, stream: int, group: np.ndarray, d: int, signal: float) -> np.ndarray:
+    """fp32 features of a synthetic classification task: a fixed random +-1 pattern per group, scaled by
+    ``signal``, under N(0,1) noise."""
+    rng = _rng(seed, stream)
+    n_groups = int(group.max()) + 1
+    pattern = rng.integers(0, 2, size=(n_groups, d)).astype(np.float32) * 2.0 - 1.0
+    return (signal * pattern[group] + rng.standard_normal((group.shape[0], d), dtype=np.float32)).astype(np.float32)
+
+
+def bernoulli_mask(seed: int, stream: int, n: int, p: float) -> np.ndarray:
+    """uint8 [n], 1 with probability p (which vertices carry a training label)."""
+    return (_rng(seed, stream).random(n) < p).astype(np.uint8)

@@ -134,3 +134,63 @@ def max_rel(x: np.ndarray, ref: np.ndarray) -> float:
     if denom == 0.0:
         denom = 1.0
     return float(np.max(np.abs(x - ref))) / denom if ref.size else 0.0
+
+
+# ---------------------------------------------------------------- training loop (epoch driver) problems
+@dataclass
+class TrainProblem:
+    row_ptr: np.ndarray
+    col: np.ndarray
+    val: np.ndarray
+    chunk_ptr: np.ndarray
+    stage_dims: List[List[int]]      # one width list per stage; last width of a stage = first of the next
+    W: List[List[np.ndarray]]
+    b: List[List[np.ndarray]]
+    x0: np.ndarray
+    labels: np.ndarray
+    mask: Optional[np.ndarray]
+    head_W: np.ndarray
+    head_b: np.ndarray
+    quant: bool
+    n_classes: int
+
+    @property
+    def n(self):
+        return self.row_ptr.shape[0] - 1
+
+
+def make_train_problem(*, n=1500, n_classes=5, stage_dims=((24, 16, 16),), K=4, dtype="f32", seed=2308100900,
+                       deg_in=8.0, deg_out=2.0, signal=0.6, label_rate=0.5, ragged=False) -> TrainProblem:
+    """A synthetic node-classification task on a planted-partition graph (labels = planted groups)."""
+    row_ptr, col, group = graphs.planted_partition(n, n_classes, deg_in, deg_out, seed)
+    val = oracle.gcn_norm(row_ptr, col)
+    chunk_ptr = graphs.ragged_chunks(n, K, seed) if ragged else graphs.equal_chunks(n, K)
+    quant = dtype == "bf16"
+    stage_dims = [list(d) for d in stage_dims]
+    x0 = values.group_features(seed, 1, group, stage_dims[0][0], signal)
+    W, b, stream = [], [], 100
+    for dims in stage_dims:
+        W.append([values.glorot_uniform(seed, stream + j, dims[j], dims[j + 1]) for j in range(len(dims) - 1)])
+        b.append([np.zeros(dims[j + 1], np.float32) for j in range(len(dims) - 1)])
+        stream += 20
+    d_last = stage_dims[-1][-1]
+    head_W = values.glorot_uniform(seed, 900, d_last, n_classes)
+    head_b = np.zeros(n_classes, np.float32)
+    mask = values.bernoulli_mask(seed, 5, n, label_rate) if label_rate < 1.0 else None
+    return TrainProblem(row_ptr, col, val, np.asarray(chunk_ptr, np.int64), stage_dims, W, b, x0,
+                        group.astype(np.int32), mask, head_W, head_b, quant, n_classes)
+
+
+def new_oracle_trainer(tp: TrainProblem, f64: bool = False, **opt):
+    """Oracle stages (history starts at zero; the first stage's level-0 history is the features) + trainer."""
+    from oracle.train import OracleTrainer
+    stages = []
+    val = tp.val if not f64 else oracle.gcn_norm(tp.row_ptr, tp.col, f64=True)
+    for si, dims in enumerate(tp.stage_dims):
+        st = oracle.OracleStage(tp.row_ptr, tp.col, val, tp.chunk_ptr, dims, tp.W[si], tp.b[si],
+                                quant=tp.quant and not f64, level0_f32=(si == 0 and tp.quant and not f64), f64=f64)
+        if si == 0:
+            st.cur[0][...] = tp.x0
+            st.hist[0][...] = tp.x0
+        stages.append(st)
+    return OracleTrainer(stages, tp.head_W, tp.head_b, tp.labels, tp.mask, quant=tp.quant and not f64, **opt)
