@@ -154,6 +154,19 @@ int gnnstage_debug_select_counts(gnnstage_t *st, int32_t chunk_id, int32_t *out)
  */
 int gnnstage_layer_order(const gnnstage_t *st, int32_t layer);
 
+/* What the handle was created with (for code that chains stages: the training loop in gnntrain.h).
+ * gnnstage_query returns a shape value, index being the level for WIDTH and the chunk boundary for
+ * CHUNK_PTR (negative on error); gnnstage_buffer returns one of the caller's DEVICE buffers (cur[index],
+ * hist[index], or grad_in, which is NULL unless need_input_grad was set). */
+enum {
+  GNNSTAGE_Q_VERTICES = 0, GNNSTAGE_Q_CHUNKS = 1, GNNSTAGE_Q_LAYERS = 2, GNNSTAGE_Q_DTYPE = 3,
+  GNNSTAGE_Q_LEVEL0_F32 = 4, GNNSTAGE_Q_VARIANT = 5, GNNSTAGE_Q_NEED_INPUT_GRAD = 6, GNNSTAGE_Q_WIDTH = 7,
+  GNNSTAGE_Q_CHUNK_PTR = 8
+};
+enum { GNNSTAGE_B_CUR = 0, GNNSTAGE_B_HIST = 1, GNNSTAGE_B_GRAD_IN = 2 };
+int64_t gnnstage_query(const gnnstage_t *st, int32_t what, int32_t index);
+void *gnnstage_buffer(const gnnstage_t *st, int32_t which, int32_t index);
+
 /* Diagnostics: how many entries of the (transposed != 0: transposed) index are multiplied as dense blocks
  * (see gnnstage_dense_plan_create below); 0 when the stage does not use them. */
 int64_t gnnstage_dense_entries(const gnnstage_t *st, int32_t transposed);

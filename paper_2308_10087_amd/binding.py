@@ -41,6 +41,24 @@ class gnnstage_desc(C.Structure):
     ]
 
 
+class gnntrain_param(C.Structure):
+    _fields_ = [("master", C.c_void_p), ("compute", C.c_void_p), ("compute_dtype", C.c_int32),
+                ("grad", C.c_void_p), ("count", C.c_int64)]
+
+
+class gnntrain_desc(C.Structure):
+    _fields_ = [
+        ("n_stages", C.c_int32), ("stages", C.c_void_p),
+        ("n_classes", C.c_int32), ("head_W", C.c_void_p), ("head_b", C.c_void_p),
+        ("head_dW", C.c_void_p), ("head_db", C.c_void_p), ("labels", C.c_void_p), ("train_mask", C.c_void_p),
+        ("n_params", C.c_int32), ("params", C.c_void_p),
+        ("optimizer", C.c_int32), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+        ("weight_decay", C.c_float),
+        ("shuffle", C.c_int32), ("seed", C.c_uint64), ("alpha_hist", C.c_int32),
+        ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+    ]
+
+
 def _load():
     # The process must hold ONE HIP runtime.  PyTorch ships its own libamdhip64; importing torch
     # first makes the dynamic loader resolve this library's libamdhip64.so.7 dependency to the copy
@@ -95,6 +113,36 @@ def _load():
     lib.gnnstage_profile_read.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     lib.gnnstage_profile_reset.restype = C.c_int
     lib.gnnstage_profile_reset.argtypes = [C.c_void_p]
+    lib.gnnstage_query.restype = C.c_int64
+    lib.gnnstage_query.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+    lib.gnnstage_buffer.restype = C.c_void_p
+    lib.gnnstage_buffer.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+    # training loop (include/gnntrain.h)
+    lib.gnntrain_workspace_size.restype = C.c_size_t
+    lib.gnntrain_workspace_size.argtypes = [C.POINTER(gnntrain_desc)]
+    lib.gnntrain_create.restype = C.c_int
+    lib.gnntrain_create.argtypes = [C.POINTER(gnntrain_desc), C.POINTER(C.c_void_p)]
+    lib.gnntrain_epoch.restype = C.c_int
+    lib.gnntrain_epoch.argtypes = [C.c_void_p, C.c_int64, C.POINTER(C.c_float), C.c_void_p]
+    lib.gnntrain_last_order.restype = C.c_int
+    lib.gnntrain_last_order.argtypes = [C.c_void_p, C.c_void_p]
+    lib.gnntrain_destroy.restype = C.c_int
+    lib.gnntrain_destroy.argtypes = [C.c_void_p]
+    lib.gnntrain_last_error.restype = C.c_char_p
+    lib.gnntrain_last_error.argtypes = [C.c_void_p]
+    lib.gnntrain_chunk_order.restype = C.c_int
+    lib.gnntrain_chunk_order.argtypes = [C.c_uint64, C.c_int64, C.c_int32, C.c_int32, C.c_void_p]
+    lib.gnntrain_softmax_xent.restype = C.c_int
+    lib.gnntrain_softmax_xent.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
+                                          C.c_float, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.gnntrain_sum.restype = C.c_int
+    lib.gnntrain_sum.argtypes = [C.c_void_p, C.c_int64, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.gnntrain_adam_step.restype = C.c_int
+    lib.gnntrain_adam_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64,
+                                       C.c_float, C.c_float, C.c_float, C.c_float, C.c_float, C.c_int64, C.c_void_p]
+    lib.gnntrain_sgd_step.restype = C.c_int
+    lib.gnntrain_sgd_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_float,
+                                      C.c_void_p]
     return lib
 
 
@@ -338,3 +386,131 @@ class GnnStage:
     def backward_pass(self, order, grad_out, stream=None) -> None:
         for k in reversed(list(order)):
             self.stage_backward_chunk(int(k), grad_out[self.rows(int(k))], stream)
+
+
+# ---- training loop (include/gnntrain.h) -------------------------------------------------------
+GNNTRAIN_SGD, GNNTRAIN_ADAM = 0, 1
+
+
+def _cur_stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def gnntrain_chunk_order(seed: int, epoch: int, n_chunks: int, shuffle: bool = True) -> np.ndarray:
+    order = np.zeros(max(n_chunks, 1), dtype=np.int32)
+    rc = lib.gnntrain_chunk_order(int(seed), int(epoch), int(n_chunks), int(bool(shuffle)), order.ctypes.data)
+    if rc != 0:
+        raise GnnStageError(rc, "gnntrain_chunk_order")
+    return order[:n_chunks]
+
+
+def gnntrain_softmax_xent(logits, bias, labels, mask, n_classes: int, inv_n_train: float, dlogits, row_loss) -> None:
+    """logits: fp32 [rows, ld]; dlogits: fp32 or bf16 [rows, dl_ld]; labels int32 [rows]; mask uint8 [rows] or None."""
+    import torch
+    rows = logits.shape[0]
+    rc = lib.gnntrain_softmax_xent(
+        logits.data_ptr(), logits.stride(0) if rows else max(n_classes, 1), None if bias is None else bias.data_ptr(),
+        labels.data_ptr(), None if mask is None else mask.data_ptr(), rows, int(n_classes), float(inv_n_train),
+        dlogits.data_ptr(), GNNSTAGE_BF16 if dlogits.dtype == torch.bfloat16 else GNNSTAGE_F32,
+        dlogits.stride(0) if rows else max(n_classes, 1), row_loss.data_ptr(), _cur_stream())
+    if rc != 0:
+        raise GnnStageError(rc, "gnntrain_softmax_xent")
+
+
+def gnntrain_sum(x, scale: float, scratch, out) -> None:
+    rc = lib.gnntrain_sum(x.data_ptr(), x.numel(), float(scale), scratch.data_ptr(), out.data_ptr(), _cur_stream())
+    if rc != 0:
+        raise GnnStageError(rc, "gnntrain_sum")
+
+
+def _compute_args(compute):
+    import torch
+    if compute is None:
+        return None, GNNSTAGE_F32
+    return compute.data_ptr(), GNNSTAGE_BF16 if compute.dtype == torch.bfloat16 else GNNSTAGE_F32
+
+
+def gnntrain_adam_step(p, g, m, v, compute, lr, beta1, beta2, eps, weight_decay, t) -> None:
+    cp, cdt = _compute_args(compute)
+    rc = lib.gnntrain_adam_step(p.data_ptr(), g.data_ptr(), m.data_ptr(), v.data_ptr(), cp, cdt, p.numel(), float(lr),
+                                float(beta1), float(beta2), float(eps), float(weight_decay), int(t), _cur_stream())
+    if rc != 0:
+        raise GnnStageError(rc, "gnntrain_adam_step")
+
+
+def gnntrain_sgd_step(p, g, compute, lr, weight_decay) -> None:
+    cp, cdt = _compute_args(compute)
+    rc = lib.gnntrain_sgd_step(p.data_ptr(), g.data_ptr(), cp, cdt, p.numel(), float(lr), float(weight_decay), _cur_stream())
+    if rc != 0:
+        raise GnnStageError(rc, "gnntrain_sgd_step")
+
+
+class GnnTrainer:
+    """Handle of the epoch loop plus the tensors it points at.  ``params`` is a list of
+    ``(master fp32 tensor, compute tensor or None, grad fp32 tensor)``."""
+
+    def __init__(self, stages: Sequence["GnnStage"], *, head_W, head_b, head_dW, head_db, labels, train_mask, params,
+                 optimizer=GNNTRAIN_ADAM, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, shuffle=True,
+                 seed=0, alpha_hist=1, device="cuda:0"):
+        import torch
+
+        self._torch = torch
+        self.stages = list(stages)
+        self._tensors = [head_W, head_b, head_dW, head_db, labels, train_mask, params]
+        hs = (C.c_void_p * len(self.stages))(*[st._h for st in self.stages])
+        ps = (gnntrain_param * max(len(params), 1))()
+        for i, (master, compute, grad) in enumerate(params):
+            assert master.dtype == torch.float32 and grad.dtype == torch.float32 and master.numel() == grad.numel()
+            ps[i].master, ps[i].grad, ps[i].count = master.data_ptr(), grad.data_ptr(), master.numel()
+            ps[i].compute, ps[i].compute_dtype = _compute_args(compute)
+        self._keep = [hs, ps]
+        d = gnntrain_desc()
+        d.n_stages, d.stages = len(self.stages), C.cast(hs, C.c_void_p)
+        d.n_classes = int(head_b.numel())
+        d.head_W, d.head_b = head_W.data_ptr(), head_b.data_ptr()
+        d.head_dW, d.head_db = head_dW.data_ptr(), head_db.data_ptr()
+        d.labels = labels.data_ptr()
+        d.train_mask = None if train_mask is None else train_mask.data_ptr()
+        d.n_params, d.params = len(params), C.cast(ps, C.c_void_p)
+        d.optimizer, d.lr, d.beta1, d.beta2, d.eps = int(optimizer), float(lr), float(beta1), float(beta2), float(eps)
+        d.weight_decay = float(weight_decay)
+        d.shuffle, d.seed, d.alpha_hist = int(bool(shuffle)), int(seed), int(alpha_hist)
+        size = int(lib.gnntrain_workspace_size(C.byref(d)))
+        if size == 0:
+            raise GnnStageError(-1, "gnntrain_workspace_size: invalid descriptor")
+        self.workspace_bytes = size
+        self.workspace = torch.empty(size, dtype=torch.uint8, device=device)
+        d.workspace, d.workspace_bytes = self.workspace.data_ptr(), size
+        self._desc = d
+        h = C.c_void_p(None)
+        rc = lib.gnntrain_create(C.byref(d), C.byref(h))
+        if rc != 0:
+            raise GnnStageError(rc, lib.gnntrain_last_error(None).decode())
+        self._h = h
+        self.K = self.stages[0].K
+
+    def gnntrain_epoch(self, epoch: int, want_loss: bool = True):
+        loss = C.c_float(0.0)
+        rc = lib.gnntrain_epoch(self._h, int(epoch), C.byref(loss) if want_loss else None, _cur_stream())
+        if rc != 0:
+            raise GnnStageError(rc, lib.gnntrain_last_error(self._h).decode())
+        return float(loss.value) if want_loss else None
+
+    def gnntrain_last_order(self) -> np.ndarray:
+        order = np.zeros(self.K, dtype=np.int32)
+        rc = lib.gnntrain_last_order(self._h, order.ctypes.data)
+        if rc != 0:
+            raise GnnStageError(rc, "gnntrain_last_order")
+        return order
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib.gnntrain_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

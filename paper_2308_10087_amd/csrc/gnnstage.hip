@@ -1529,6 +1529,33 @@ extern "C" int gnnstage_layer_order(const gnnstage_t *st, int32_t layer) {
   return st->s.tf[layer] ? 1 : 0;
 }
 
+extern "C" int64_t gnnstage_query(const gnnstage_t *st, int32_t what, int32_t index) {
+  if (!st) return GNNSTAGE_EINVAL;
+  const Shape &s = st->s;
+  switch (what) {
+    case GNNSTAGE_Q_VERTICES: return s.n;
+    case GNNSTAGE_Q_CHUNKS: return s.K;
+    case GNNSTAGE_Q_LAYERS: return s.L;
+    case GNNSTAGE_Q_DTYPE: return s.dtype;
+    case GNNSTAGE_Q_LEVEL0_F32: return s.level0_f32;
+    case GNNSTAGE_Q_VARIANT: return s.variant;
+    case GNNSTAGE_Q_NEED_INPUT_GRAD: return s.need_input_grad;
+    case GNNSTAGE_Q_WIDTH: return (index >= 0 && index <= s.L) ? s.dims[(size_t)index] : GNNSTAGE_EINVAL;
+    case GNNSTAGE_Q_CHUNK_PTR: return (index >= 0 && index <= s.K) ? s.chunk_ptr[(size_t)index] : GNNSTAGE_EINVAL;
+    default: return GNNSTAGE_EINVAL;
+  }
+}
+
+extern "C" void *gnnstage_buffer(const gnnstage_t *st, int32_t which, int32_t index) {
+  if (!st) return nullptr;
+  switch (which) {
+    case GNNSTAGE_B_CUR: return (index >= 0 && index <= st->s.L) ? st->cur[(size_t)index] : nullptr;
+    case GNNSTAGE_B_HIST: return (index >= 0 && index < st->s.L) ? st->hist[(size_t)index] : nullptr;
+    case GNNSTAGE_B_GRAD_IN: return st->s.need_input_grad ? st->grad_in : nullptr;
+    default: return nullptr;
+  }
+}
+
 extern "C" int gnnstage_profile_enable(gnnstage_t *st, int32_t on) {
   if (!st) return GNNSTAGE_EINVAL;
   st->prof.on = on != 0;

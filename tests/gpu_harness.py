@@ -56,3 +56,68 @@ class GpuRun:
     @staticmethod
     def np(t):
         return t.detach().to(torch.float32).cpu().numpy()
+
+
+class GpuTrainRun:
+    """A TrainProblem on the GPU: chained stages, head, parameter list in the oracle trainer's order
+    (per stage all W then all biases, then the head's W and b)."""
+
+    def __init__(self, tp, device="cuda:0", chain=True, **opt):
+        self.tp = tp
+        bf = tp.quant
+        sdt = torch.bfloat16 if bf else torch.float32
+        self.sdt = sdt
+        n = tp.n
+        self.stages, self.params = [], []
+        self.W, self.bias, self.dW, self.dbias, self.cur, self.hist, self.grad_in = [], [], [], [], [], [], []
+        prev_top = None
+        for si, dims in enumerate(tp.stage_dims):
+            L = len(dims) - 1
+            first = si == 0
+            l0 = torch.float32 if (first and bf) else sdt
+            master_W = [_dev(tp.W[si][j], torch.float32, device) for j in range(L)]
+            W = [m.to(sdt) for m in master_W] if bf else master_W
+            bias = [_dev(tp.b[si][j], torch.float32, device) for j in range(L)]
+            level0 = _dev(tp.x0, l0, device) if first else (prev_top if chain else torch.zeros((n, dims[0]), dtype=sdt, device=device))
+            cur = [level0] + [torch.zeros((n, dims[j]), dtype=sdt, device=device) for j in range(1, L + 1)]
+            hist = [cur[0] if first else torch.zeros((n, dims[0]), dtype=sdt, device=device)] + \
+                   [torch.zeros((n, dims[j]), dtype=sdt, device=device) for j in range(1, L)]
+            dW = [torch.zeros((dims[j], dims[j + 1]), dtype=torch.float32, device=device) for j in range(L)]
+            dbias = [torch.zeros(dims[j + 1], dtype=torch.float32, device=device) for j in range(L)]
+            grad_in = None if first else torch.zeros((n, dims[0]), dtype=sdt, device=device)
+            st = g.GnnStage(tp.row_ptr, tp.col, tp.chunk_ptr, dims, W=W, cur=cur, hist=hist, dW=dW, bias=bias, dbias=dbias,
+                            edge_val=tp.val, dtype=g.GNNSTAGE_BF16 if bf else g.GNNSTAGE_F32, level0_f32=first and bf,
+                            grad_in=grad_in, device=device)
+            self.stages.append(st)
+            for j in range(L):
+                self.params.append((master_W[j], W[j] if bf else None, dW[j]))
+            for j in range(L):
+                self.params.append((bias[j], None, dbias[j]))
+            self.W.append(W); self.bias.append(bias); self.dW.append(dW); self.dbias.append(dbias)
+            self.cur.append(cur); self.hist.append(hist); self.grad_in.append(grad_in)
+            prev_top = cur[L]
+        d_top = tp.stage_dims[-1][-1]
+        self.head_master = _dev(tp.head_W, torch.float32, device)
+        self.head_W = self.head_master.to(sdt) if bf else self.head_master
+        self.head_b = _dev(tp.head_b, torch.float32, device)
+        self.head_dW = torch.zeros((d_top, tp.n_classes), dtype=torch.float32, device=device)
+        self.head_db = torch.zeros(tp.n_classes, dtype=torch.float32, device=device)
+        self.params.append((self.head_master, self.head_W if bf else None, self.head_dW))
+        self.params.append((self.head_b, None, self.head_db))
+        self.labels = torch.from_numpy(np.ascontiguousarray(tp.labels, dtype=np.int32)).to(device)
+        self.mask = None if tp.mask is None else torch.from_numpy(np.ascontiguousarray(tp.mask, dtype=np.uint8)).to(device)
+        o = dict(optimizer="adam", lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, shuffle=True, seed=0, alpha_hist=1)
+        o.update(opt)
+        o["optimizer"] = g.GNNTRAIN_ADAM if o["optimizer"] == "adam" else g.GNNTRAIN_SGD
+        self.trainer = g.GnnTrainer(self.stages, head_W=self.head_W, head_b=self.head_b, head_dW=self.head_dW,
+                                    head_db=self.head_db, labels=self.labels, train_mask=self.mask, params=self.params,
+                                    device=device, **o)
+
+    def epoch(self, t):
+        return self.trainer.gnntrain_epoch(t)
+
+    def grads(self):
+        return [GpuRun.np(p[2]) for p in self.params]
+
+    def master_values(self):
+        return [GpuRun.np(p[0]) for p in self.params]

@@ -23,15 +23,30 @@ def _lib():
 
 def test_library_exports_every_declared_symbol():
     g = _lib()
-    header = open(os.path.join(ROOT, "include", "gnnstage.h")).read()
+    import glob
+    headers = sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
+    assert [os.path.basename(h) for h in headers] == ["gnnstage.h", "gnntrain.h"]
+    header = "\n".join(open(h).read() for h in headers)
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = re.findall(r"\b([a-z_][a-z0-9_]*)\s*\(", header)
-    declared = sorted({n for n in names if n.startswith(("gnnstage_", "stage_", "update_history"))})
+    declared = sorted({n for n in names if n.startswith(("gnnstage_", "gnntrain_", "stage_", "update_history"))})
     assert {"gnnstage_create", "stage_forward_chunk", "stage_backward_chunk", "update_history",
-            "gnnstage_destroy"} <= set(declared)
+            "gnnstage_destroy", "gnntrain_create", "gnntrain_epoch", "gnntrain_chunk_order", "gnntrain_softmax_xent",
+            "gnntrain_adam_step", "gnntrain_sgd_step", "gnntrain_sum", "gnnstage_query", "gnnstage_buffer"} <= set(declared)
     for name in declared:
         assert hasattr(g.lib, name), name
     assert g.gnnstage_version() >= 100
+
+
+def test_chunk_order_matches_the_oracle_bit_for_bit():
+    """Section 3.4, technique 1: the library's host-side shuffle and the oracle's draw the same orders."""
+    from oracle.train import chunk_order
+    g = _lib()
+    for seed in (0, 1, 2308100900, (1 << 64) - 1, 0x9E3779B97F4A7C15):
+        for K in (1, 2, 7, 8, 32, 256):
+            for epoch in (0, 1, 2, 77, 10**6):
+                assert np.array_equal(g.gnntrain_chunk_order(seed, epoch, K), chunk_order(seed, epoch, K)), (seed, K, epoch)
+    assert np.array_equal(g.gnntrain_chunk_order(5, 3, 9, shuffle=False), np.arange(9))
 
 
 def test_transposed_index_is_the_exact_transpose():
