@@ -53,6 +53,8 @@ def main():
     ap.add_argument("--workload", default="c1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=131072)
+    ap.add_argument("--train-epochs", type=int, default=0,
+                    help="also time this many epochs of the whole training loop (head + Adam) around the same stage")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one pipeline stage on ONE GPU; this build has no multi-GPU path (--gpus must be 1)")
@@ -126,8 +128,11 @@ def main():
         one_step(i)
     torch.cuda.synchronize()
 
+    # Inside the timed region only the aggregation launches (the dominant kernel) carry HIP events: two
+    # event records per launch on the launch stream.  The per-kind breakdown of a whole step comes from two
+    # further, untimed steps with every kind switched on (events around ~350 launches cost ~1 ms per step).
     st.gnnstage_profile_reset()
-    st.gnnstage_profile_enable(True)
+    st.gnnstage_profile_select(["spmm_fwd", "spmm_bwd"])
     orders = []
     torch.cuda.synchronize()
     t_start = time.perf_counter()
@@ -136,8 +141,15 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     st.gnnstage_profile_enable(False)
-    prof_all = st.gnnstage_profile_read(-1)
     prof_layer = [st.gnnstage_profile_read(j) for j in range(L)]
+    st.gnnstage_profile_reset()
+    st.gnnstage_profile_enable(True)
+    n_extra = 2
+    for i in range(n_extra):
+        one_step(args.warmup + args.steps + i)
+    torch.cuda.synchronize()
+    st.gnnstage_profile_enable(False)
+    prof_all = st.gnnstage_profile_read(-1)
 
     ms_per_step = 1e3 * elapsed / args.steps
     value = L * nnz / (elapsed / args.steps)
@@ -205,7 +217,42 @@ def main():
         "gather_GBps": round(dom_gather / max(dom_ms * 1e-3, 1e-12) / 1e9, 1),
         "layer_order": ["transform-first" if t else "aggregate-first" for t in tf],
     }
-    kernels_ms = {k: round(v[0] / args.steps, 3) for k, v in prof_all.items()}
+    kernels_ms = {k: round(v[0] / n_extra, 3) for k, v in prof_all.items()}
+
+    # ---- gemm side of the metric: achieved rate of the dense products against the bf16 matrix-core peak
+    gemm_flops = 0.0
+    for j in range(L):
+        per = 2.0 * n * dims[j] * dims[j + 1]
+        gemm_flops += per * (3 if (j > 0 or not first_stage) else 2)  # forward, weight gradient, input gradient
+    gemm_ms = sum(prof_all[k][0] for k in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad")) / n_extra
+    gemm = {"tflops": round(gemm_flops / max(gemm_ms * 1e-3, 1e-12) / 1e12, 1), "ms_per_step": round(gemm_ms, 3),
+            "frac_of_mfma_peak": round(gemm_flops / max(gemm_ms * 1e-3, 1e-12) / (2.5e15 if bf else 157.3e12), 4),
+            "bound": "hbm (128 flop/B at width 256 against a machine balance of 312)"}
+
+    # ---- optional: epochs of the whole training loop around the same stage ------------------
+    trainer = None
+    if args.train_epochs > 0 and gcn:
+        n_classes = 41
+        labels = torch.from_numpy(values._rng(w.seed, 7).integers(0, n_classes, size=n).astype(np.int32)).to(dev)
+        master = [t.to(torch.float32) for t in W] if bf else W
+        head_master = torch.from_numpy(values.glorot_uniform(w.seed, 900, dims[-1], n_classes)).to(dev)
+        head_W = head_master.to(sdt) if bf else head_master
+        head_b = torch.zeros(n_classes, device=dev)
+        head_dW, head_db = torch.zeros((dims[-1], n_classes), device=dev), torch.zeros(n_classes, device=dev)
+        params = [(master[j], W[j] if bf else None, dW[j]) for j in range(L)] + [(bias[j], None, dbias[j]) for j in range(L)]
+        params += [(head_master, head_W if bf else None, head_dW), (head_b, None, head_db)]
+        tr = g.GnnTrainer([st], head_W=head_W, head_b=head_b, head_dW=head_dW, head_db=head_db, labels=labels,
+                          train_mask=None, params=params, optimizer=g.GNNTRAIN_ADAM, lr=1e-3, shuffle=True, seed=w.seed,
+                          alpha_hist=1, device=dev)
+        tr.gnntrain_epoch(0)
+        torch.cuda.synchronize()
+        t_tr = time.perf_counter()
+        for e in range(1, args.train_epochs + 1):
+            last_loss = tr.gnntrain_epoch(e, want_loss=(e == args.train_epochs))
+        torch.cuda.synchronize()
+        trainer = {"ms_per_epoch": round(1e3 * (time.perf_counter() - t_tr) / args.train_epochs, 3), "epochs": args.train_epochs,
+                   "head_classes": n_classes, "optimizer": "adam", "loss": last_loss,
+                   "step": "stage step + linear softmax cross-entropy head + Adam update of all weights"}
 
     # ---- CPU baseline: the oracle on a bounded sample ---------------------------------------
     cpu = None
@@ -221,9 +268,12 @@ def main():
                                f"{w.variant} {'bf16 levels, fp32 level 0' if w.level0_f32 else w.dtype}",
                    "max_degree": stats["max_degree"], "step": "forward all chunks + backward all chunks + update_history"},
         "kernel_ms_per_step": kernels_ms,
+        "gemm": gemm,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    if trainer is not None:
+        out["trainer"] = trainer
     print(json.dumps(out), flush=True)
 
 

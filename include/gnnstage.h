@@ -228,9 +228,13 @@ int gnnstage_dense_plan_destroy(gnnstage_dense_plan *plan);
  * 7 long-row reduce of an aggregation.  gnnstage_profile_read synchronises the device, then
  * returns summed milliseconds and launch count of that kind for one layer (0 <= layer < L) or,
  * with layer < 0, over all layers.
+ * gnnstage_profile_enable switches all kinds on or off; gnnstage_profile_select takes a bit mask of kinds
+ * (bit k = kind k), for callers that want the events of a few kinds only inside a timed region (every
+ * timed launch costs two event records on the stream).
  */
 enum { GNNSTAGE_NKINDS = 8 };
 int gnnstage_profile_enable(gnnstage_t *st, int32_t on);
+int gnnstage_profile_select(gnnstage_t *st, uint32_t kind_mask);
 int gnnstage_profile_read(gnnstage_t *st, int32_t kind, int32_t layer, double *ms, int64_t *launches);
 int gnnstage_profile_reset(gnnstage_t *st);
 

@@ -109,6 +109,8 @@ def _load():
     lib.gnnstage_layer_order.argtypes = [C.c_void_p, C.c_int32]
     lib.gnnstage_profile_enable.restype = C.c_int
     lib.gnnstage_profile_enable.argtypes = [C.c_void_p, C.c_int32]
+    lib.gnnstage_profile_select.restype = C.c_int
+    lib.gnnstage_profile_select.argtypes = [C.c_void_p, C.c_uint32]
     lib.gnnstage_profile_read.restype = C.c_int
     lib.gnnstage_profile_read.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     lib.gnnstage_profile_reset.restype = C.c_int
@@ -349,6 +351,13 @@ class GnnStage:
 
     def gnnstage_profile_enable(self, on: bool) -> None:
         self._check(lib.gnnstage_profile_enable(self._h, int(on)))
+
+    def gnnstage_profile_select(self, kinds) -> None:
+        """Time only the given kinds (names from KIND_NAMES)."""
+        mask = 0
+        for k in kinds:
+            mask |= 1 << KIND_NAMES.index(k)
+        self._check(lib.gnnstage_profile_select(self._h, mask))
 
     def gnnstage_profile_reset(self) -> None:
         self._check(lib.gnnstage_profile_reset(self._h))

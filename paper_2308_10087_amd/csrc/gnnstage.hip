@@ -449,7 +449,7 @@ Layout make_layout(const Shape &s, const HostDir &hf, const HostDir &hb, bool ra
 }
 
 struct Profiler {
-  bool on = false;
+  uint32_t kinds = 0;  // bit k set: launches of kind k are timed
   int n_layers = 0;  // slot n_layers collects launches that belong to no layer
   struct Rec { int kind, layer; hipEvent_t a, b; };
   std::vector<Rec> recs;
@@ -543,14 +543,14 @@ struct Timed {
   hipEvent_t a = nullptr, b = nullptr;
   Timed(gnnstage *st_, hipStream_t s_, int kind_, int layer_ = -1)
       : st(st_), s(s_), kind(kind_), layer(layer_ < 0 ? st_->prof.n_layers : layer_) {
-    if (st->prof.on) {
+    if ((st->prof.kinds >> kind) & 1u) {
       a = st->prof.get();
       b = st->prof.get();
       (void)hipEventRecord(a, s);
     }
   }
   ~Timed() {
-    if (st->prof.on) {
+    if (a != nullptr) {
       (void)hipEventRecord(b, s);
       st->prof.recs.push_back({kind, layer, a, b});
     }
@@ -1558,7 +1558,13 @@ extern "C" void *gnnstage_buffer(const gnnstage_t *st, int32_t which, int32_t in
 
 extern "C" int gnnstage_profile_enable(gnnstage_t *st, int32_t on) {
   if (!st) return GNNSTAGE_EINVAL;
-  st->prof.on = on != 0;
+  st->prof.kinds = on != 0 ? (1u << GNNSTAGE_NKINDS) - 1u : 0u;
+  return GNNSTAGE_OK;
+}
+
+extern "C" int gnnstage_profile_select(gnnstage_t *st, uint32_t kind_mask) {
+  if (!st || (kind_mask >> GNNSTAGE_NKINDS) != 0) return GNNSTAGE_EINVAL;
+  st->prof.kinds = kind_mask;
   return GNNSTAGE_OK;
 }
 
