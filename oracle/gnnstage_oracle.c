@@ -22,6 +22,11 @@
  *     historical buffers; when it is called is caller policy.
  *   - GCNII variant (formula from the benchmark definition, the paper only cites the
  *     model): p = (1-a) z + a h0 ;  h' = ReLU((1-beta) p + beta p W).
+ *   - GraphSage variant (Section 2.1, Equation 1: UPDATE takes both h_v of the previous
+ *     layer and z_v; the paper only cites the model, the form is Hamilton et al.'s with
+ *     the aggregator's weights given per edge, 1/|N(v)| for the mean aggregator):
+ *     h' = ReLU(h_v W_self + z_v W_neigh + b), W stored as [W_self ; W_neigh], 2 d_in x d_out.
+ *     v belongs to the chunk being computed, so h_v is its current row.
  *
  * Precision: arrays are fp32 storage, every sum runs in fp64.  With quant == 1 the
  * values the GPU path keeps in bf16 (saved aggregation, levels, gradient rows) are
@@ -65,19 +70,19 @@ typedef struct {
   /* stage */
   int32_t L;
   const int32_t *dims; /* L+1 */
-  int32_t variant;     /* 0 GCN, 1 GCNII */
+  int32_t variant;     /* 0 GCN, 1 GCNII, 2 GraphSage */
   double a;            /* GCNII initial-residual weight */
   const double *beta;  /* GCNII, L entries */
   int32_t quant;       /* 0: fp32 storage, 1: bf16 storage of levels >= 1, Z, dZ, g */
   int32_t level0_f32;  /* with quant: level 0 (and grad_in) stay fp32 */
-  real_t *const *W;     /* L arrays d_j x d_{j+1}, row-major */
-  real_t *const *b;     /* L arrays d_{j+1} (GCN only) */
+  real_t *const *W;     /* L arrays d_j x d_{j+1} (GraphSage: 2 d_j x d_{j+1}), row-major */
+  real_t *const *b;     /* L arrays d_{j+1} (GCN, GraphSage) */
   real_t *const *cur;   /* L+1 arrays n x d_j */
   real_t *const *hist;  /* L arrays n x d_j */
   const real_t *h0;     /* GCNII: n x d */
   real_t *const *Z;     /* saved aggregation (GCN) or mixed p (GCNII), L arrays n x d_j */
   real_t *const *dZ;    /* L arrays n x d_j */
-  double *const *dW;   /* L arrays d_j x d_{j+1}, accumulated (+=) */
+  double *const *dW;   /* L arrays shaped like W, accumulated (+=) */
   double *const *db;   /* L arrays d_{j+1}, accumulated (+=) */
   double *dH0;         /* GCNII: n x d accumulated (+=) */
   real_t *grad_in;      /* n x d_0 or NULL */
@@ -217,7 +222,7 @@ void oracle_forward_chunk(oracle_stage *s, int32_t k) {
           for (int32_t i = 0; i < din; ++i) z[i] += w * (double)hu[i];
         }
         real_t *zs = s->Z[j] + v * din;
-        if (s->variant == 0) {
+        if (s->variant != 1) {
           for (int32_t i = 0; i < din; ++i) zs[i] = store(s, z[i]);
         } else { /* GCNII initial residual */
           const real_t *h0 = s->h0 + v * din;
@@ -226,13 +231,22 @@ void oracle_forward_chunk(oracle_stage *s, int32_t k) {
         }
         /* UPDATE: fully connected layer on the stored aggregation */
         for (int32_t o = 0; o < dout; ++o) y[o] = 0.0;
+        const real_t *Wz = s->variant == 2 ? W + (int64_t)din * dout : W; /* GraphSage: the lower half */
         for (int32_t i = 0; i < din; ++i) {
           const double zi = (double)zs[i];
-          const real_t *wr = W + (int64_t)i * dout;
+          const real_t *wr = Wz + (int64_t)i * dout;
           for (int32_t o = 0; o < dout; ++o) y[o] += zi * (double)wr[o];
         }
+        if (s->variant == 2) { /* GraphSage: the vertex's own previous-level row through W_self */
+          const real_t *hv = cur + v * din;
+          for (int32_t i = 0; i < din; ++i) {
+            const double hi = (double)hv[i];
+            const real_t *wr = W + (int64_t)i * dout;
+            for (int32_t o = 0; o < dout; ++o) y[o] += hi * (double)wr[o];
+          }
+        }
         real_t *hn = s->cur[j + 1] + v * dout;
-        if (s->variant == 0) {
+        if (s->variant != 1) {
           const real_t *b = s->b[j];
           for (int32_t o = 0; o < dout; ++o) {
             double t = y[o] + (double)b[o];
@@ -268,7 +282,8 @@ void oracle_backward_chunk(oracle_stage *s, int32_t k, const real_t *grad_out, i
     for (int64_t r = 0; r < m; ++r)
       for (int32_t o = 0; o < dout; ++o)
         if (!(hn[(v0 + r) * dout + o] > (real_t)0)) g[r * dout + o] = (real_t)0;
-    const double wscale = s->variant == 0 ? 1.0 : s->beta[j];
+    const double wscale = s->variant == 1 ? s->beta[j] : 1.0;
+    const int64_t zoff = s->variant == 2 ? (int64_t)din * dout : 0; /* GraphSage: W_neigh is the lower half */
     /* weight gradient: dW[i][o] += scale * sum_v Zsaved[v][i] dy[v][o] */
 #pragma omp parallel for schedule(static)
     for (int32_t i = 0; i < din; ++i) {
@@ -278,10 +293,23 @@ void oracle_backward_chunk(oracle_stage *s, int32_t k, const real_t *grad_out, i
         const real_t *dy = g + r * dout;
         for (int32_t o = 0; o < dout; ++o) acc[o] += zi * (double)dy[o];
       }
-      for (int32_t o = 0; o < dout; ++o) s->dW[j][(int64_t)i * dout + o] += wscale * acc[o];
+      for (int32_t o = 0; o < dout; ++o) s->dW[j][zoff + (int64_t)i * dout + o] += wscale * acc[o];
       free(acc);
     }
-    if (s->variant == 0) { /* bias gradient */
+    if (s->variant == 2) { /* GraphSage: dW_self[i][o] += sum_v h_v[i] dy[v][o] */
+#pragma omp parallel for schedule(static)
+      for (int32_t i = 0; i < din; ++i) {
+        double *acc = (double *)calloc((size_t)dout, sizeof(double));
+        for (int64_t r = 0; r < m; ++r) {
+          const double hi = (double)s->cur[j][(v0 + r) * din + i];
+          const real_t *dy = g + r * dout;
+          for (int32_t o = 0; o < dout; ++o) acc[o] += hi * (double)dy[o];
+        }
+        for (int32_t o = 0; o < dout; ++o) s->dW[j][(int64_t)i * dout + o] += acc[o];
+        free(acc);
+      }
+    }
+    if (s->variant != 1) { /* bias gradient */
       for (int32_t o = 0; o < dout; ++o) {
         double acc = 0.0;
         for (int64_t r = 0; r < m; ++r) acc += (double)g[r * dout + o];
@@ -294,10 +322,10 @@ void oracle_backward_chunk(oracle_stage *s, int32_t k, const real_t *grad_out, i
       const real_t *dy = g + r * dout;
       real_t *dz = s->dZ[j] + (v0 + r) * din;
       for (int32_t i = 0; i < din; ++i) {
-        const real_t *wr = W + (int64_t)i * dout;
+        const real_t *wr = W + zoff + (int64_t)i * dout;
         double acc = 0.0;
         for (int32_t o = 0; o < dout; ++o) acc += (double)dy[o] * (double)wr[o];
-        if (s->variant == 0) {
+        if (s->variant != 1) {
           dz[i] = store(s, acc);
         } else {
           const double be = s->beta[j];
@@ -308,6 +336,20 @@ void oracle_backward_chunk(oracle_stage *s, int32_t k, const real_t *grad_out, i
       }
     }
     if (j == 0 && !need_input_grad) break;
+    /* GraphSage: the part of the gradient that reaches h_v directly, through W_self (kept in the scratch
+     * rows that receive the next g; v is in the chunk, so this is always a current row) */
+    if (s->variant == 2) {
+#pragma omp parallel for schedule(static)
+      for (int64_t r = 0; r < m; ++r) {
+        const real_t *dy = g + r * dout;
+        for (int32_t i = 0; i < din; ++i) {
+          const real_t *wr = W + (int64_t)i * dout;
+          double acc = 0.0;
+          for (int32_t o = 0; o < dout; ++o) acc += (double)dy[o] * (double)wr[o];
+          gn[r * din + i] = store(s, acc);
+        }
+      }
+    }
     /* transposed aggregation with the zero rule: u in C_k pulls from every v that
      * lists u as a neighbour AND whose chunk has been backward-processed */
 #pragma omp parallel
@@ -315,7 +357,7 @@ void oracle_backward_chunk(oracle_stage *s, int32_t k, const real_t *grad_out, i
       double *acc = (double *)malloc(sizeof(double) * (size_t)din);
 #pragma omp for schedule(dynamic, 16)
       for (int64_t u = v0; u < v1; ++u) {
-        for (int32_t i = 0; i < din; ++i) acc[i] = 0.0;
+        for (int32_t i = 0; i < din; ++i) acc[i] = s->variant == 2 ? (double)gn[(u - v0) * din + i] : 0.0;
         for (int64_t p = s->t_ptr[u]; p < s->t_ptr[u + 1]; ++p) {
           const int64_t v = s->t_row[p];
           if (!s->bprocessed[s->chunk_of[v]]) continue; /* technique 3: zeros */

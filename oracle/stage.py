@@ -117,14 +117,15 @@ class OracleStage:
         assert self.chunk_ptr[0] == 0 and self.chunk_ptr[-1] == n and np.all(np.diff(self.chunk_ptr) >= 0)
         self.dims = np.ascontiguousarray(dims, dtype=np.int32)
         self.L = L = self.dims.shape[0] - 1
-        self.variant = 0 if variant == "gcn" else 1
+        self.variant = {"gcn": 0, "gcnii": 1, "sage": 2}[variant]
         self.a = float(a)
         self.beta = np.ascontiguousarray(beta if beta is not None else np.zeros(L), dtype=np.float64)
         assert self.beta.shape[0] == L
         self.quant = bool(quant)
         self.level0_f32 = bool(level0_f32)
         d = [int(x) for x in self.dims]
-        self.W = [np.ascontiguousarray(W[j], dtype=rt).reshape(d[j], d[j + 1]) for j in range(L)]
+        wr = 2 if self.variant == 2 else 1  # GraphSage stacks [W_self ; W_neigh]
+        self.W = [np.ascontiguousarray(W[j], dtype=rt).reshape(wr * d[j], d[j + 1]) for j in range(L)]
         self.b = [np.ascontiguousarray(b[j] if b is not None else np.zeros(d[j + 1]), dtype=rt) for j in range(L)]
         self.cur = [np.zeros((n, d[j]), dtype=rt) for j in range(L + 1)]
         self.hist = [np.zeros((n, d[j]), dtype=rt) for j in range(L)]
@@ -133,7 +134,7 @@ class OracleStage:
             assert self.h0 is not None and all(x == d[0] for x in d)
         self.Z = [np.zeros((n, d[j]), dtype=rt) for j in range(L)]
         self.dZ = [np.zeros((n, d[j]), dtype=rt) for j in range(L)]
-        self.dW = [np.zeros((d[j], d[j + 1]), dtype=np.float64) for j in range(L)]
+        self.dW = [np.zeros((wr * d[j], d[j + 1]), dtype=np.float64) for j in range(L)]
         self.db = [np.zeros(d[j + 1], dtype=np.float64) for j in range(L)]
         self.dH0 = np.zeros((n, d[0]), dtype=np.float64) if self.variant == 1 else None
         self.grad_in = np.zeros((n, d[0]), dtype=rt)

@@ -15,6 +15,17 @@ from synth import graphs, values
 from synth.configs import Workload, make_graph
 
 
+def edge_weights(variant: str, row_ptr: np.ndarray, col: np.ndarray, f64: bool = False) -> np.ndarray:
+    """The aggregator's per-edge weights handed to oracle and library alike: the GCN normalisation of
+    Section 2.1 (from the oracle), or, for the GraphSage variant, the mean aggregator's 1 / |N(v)| on every
+    entry of row v (an input: a plain reciprocal of the row length)."""
+    if variant != "sage":
+        return oracle.gcn_norm(row_ptr, col, f64=f64)
+    deg = np.diff(row_ptr).astype(np.float64)
+    w = np.repeat(1.0 / np.maximum(deg, 1.0), np.diff(row_ptr))
+    return w if f64 else w.astype(np.float32)
+
+
 def to_bf16_grid(x: np.ndarray) -> np.ndarray:
     """Nearest bf16-representable fp32 values (library rounding, used to make INPUTS exact in bf16)."""
     return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16).to(torch.float32).numpy()
@@ -50,7 +61,7 @@ class Problem:
 
     def new_oracle(self, f64: bool = False) -> "oracle.OracleStage":
         st = oracle.OracleStage(self.row_ptr, self.col,
-                                self.val if not f64 else oracle.gcn_norm(self.row_ptr, self.col, f64=True),
+                                self.val if not f64 else edge_weights(self.w.variant, self.row_ptr, self.col, f64=True),
                                 self.chunk_ptr, self.dims, self.W, self.b,
                                 variant=self.w.variant, a=self.a, beta=self.beta, h0=self.h0,
                                 quant=self.quant and not f64, level0_f32=self.level0_f32, f64=f64)
@@ -70,7 +81,7 @@ def make_problem(w: Workload, *, graph=None, chunk_ptr=None, order=None, bias_st
                  history: str = "clean") -> Problem:
     row_ptr, col = graph if graph is not None else make_graph(w)
     n = row_ptr.shape[0] - 1
-    val = oracle.gcn_norm(row_ptr, col)
+    val = edge_weights(w.variant, row_ptr, col)
     if chunk_ptr is None:
         chunk_ptr = graphs.equal_chunks(n, w.n_chunks)
     K = chunk_ptr.shape[0] - 1
@@ -78,11 +89,13 @@ def make_problem(w: Workload, *, graph=None, chunk_ptr=None, order=None, bias_st
     L = len(dims) - 1
     quant = w.dtype == "bf16"
     if first_stage is None:
-        first_stage = w.variant == "gcn"
+        first_stage = w.variant in ("gcn", "sage")
     g = to_bf16_grid if quant else (lambda x: x)
     g0 = (lambda x: x) if (w.level0_f32 or not quant) else to_bf16_grid
     W = [g(values.glorot_uniform(w.seed, 100 + j, dims[j], dims[j + 1])) for j in range(L)]
-    if w.variant == "gcn":
+    if w.variant == "sage":  # [W_self ; W_neigh]
+        W = [np.concatenate([g(values.glorot_uniform(w.seed, 150 + j, dims[j], dims[j + 1])), W[j]], axis=0) for j in range(L)]
+    if w.variant in ("gcn", "sage"):
         b = [values.normal(w.seed, 200 + j, (dims[j + 1],), bias_std) if bias_std > 0
              else np.zeros(dims[j + 1], np.float32) for j in range(L)]
         x0 = g0(values.normal(w.seed, 1, (n, dims[0])))

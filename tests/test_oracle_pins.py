@@ -20,7 +20,7 @@ import oracle
 from synth import graphs, values
 from synth.configs import CONFIGS, Workload
 
-from helpers import gcnii_beta, make_problem, max_rel, run_oracle
+from helpers import edge_weights, gcnii_beta, make_problem, max_rel, run_oracle
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -45,6 +45,9 @@ def dense_full_graph_levels(A, x0, W, b, variant="gcn", a=0.0, beta=None, h0=Non
         z = A @ levels[-1]
         if variant == "gcn":
             y = z @ W[j].astype(np.float64) + b[j].astype(np.float64)
+        elif variant == "sage":
+            d = levels[-1].shape[1]
+            y = levels[-1] @ W[j][:d].astype(np.float64) + z @ W[j][d:].astype(np.float64) + b[j].astype(np.float64)
         else:
             p = (1 - a) * z + a * h0.astype(np.float64)
             y = (1 - beta[j]) * p + beta[j] * (p @ W[j].astype(np.float64))
@@ -77,6 +80,9 @@ def torch_dense_chunked(p, A, order, x0_t, W_t, b_t, h0_t=None):
                 z = z + A_t[rows, cols] @ src
             if p.w.variant == "gcn":
                 y = z @ W_t[j] + b_t[j]
+            elif p.w.variant == "sage":
+                d = p.dims[j]
+                y = cur_rows[j][k] @ W_t[j][:d] + z @ W_t[j][d:] + b_t[j]
             else:
                 pm = (1 - p.a) * z + p.a * h0_t[rows]
                 y = (1 - p.beta[j]) * pm + p.beta[j] * (pm @ W_t[j])
@@ -113,9 +119,9 @@ def test_norm_sqrt_degree_is_fixed_point():
 
 
 # ----------------------------------------------------------------------------- P1 / P2
-@pytest.mark.parametrize("variant", ["gcn", "gcnii"])
+@pytest.mark.parametrize("variant", ["gcn", "gcnii", "sage"])
 def test_p1_p2_one_chunk_equals_dense(variant):
-    dims = (5, 7, 6, 4) if variant == "gcn" else (6, 6, 6, 6)
+    dims = (5, 7, 6, 4) if variant != "gcnii" else (6, 6, 6, 6)
     w = tiny_workload(k=1, dims=dims, variant=variant)
     p = make_problem(w)
     # poison the history: with one chunk it must never be read
@@ -123,7 +129,7 @@ def test_p1_p2_one_chunk_equals_dense(variant):
         h[...] = 1e6
     st = p.new_oracle(f64=True)
     st.forward_pass([0])
-    A = dense_adj(p.row_ptr, p.col, oracle.gcn_norm(p.row_ptr, p.col, f64=True), p.n)
+    A = dense_adj(p.row_ptr, p.col, edge_weights(variant, p.row_ptr, p.col, f64=True), p.n)
     ref = dense_full_graph_levels(A, p.x0, p.W, p.b, variant, p.a, p.beta, p.h0)
     for j in range(1, p.L + 1):
         assert np.allclose(st.cur[j], ref[j], rtol=1e-12, atol=1e-12), j
@@ -211,9 +217,9 @@ def test_p5_hand_example():
 
 
 # ----------------------------------------------------------------------------- P6
-@pytest.mark.parametrize("variant", ["gcn", "gcnii"])
+@pytest.mark.parametrize("variant", ["gcn", "gcnii", "sage"])
 def test_p6_backward_is_the_gradient_of_the_chunked_forward(variant):
-    dims = (4, 6, 5, 3) if variant == "gcn" else (5, 5, 5, 5)
+    dims = (4, 6, 5, 3) if variant != "gcnii" else (5, 5, 5, 5)
     w = tiny_workload(n=29, k=4, dims=dims, variant=variant, seed=11)
     p = make_problem(w, chunk_ptr=graphs.ragged_chunks(29, 4, 3), first_stage=False, noise_std=0.3)
     st = p.new_oracle(f64=True)
@@ -221,7 +227,7 @@ def test_p6_backward_is_the_gradient_of_the_chunked_forward(variant):
     for dz in st.dZ:  # leftovers of an earlier epoch must be masked out by the zero rule
         dz[...] = 1e3
     st.backward_pass(p.grad_out)
-    A = dense_adj(p.row_ptr, p.col, oracle.gcn_norm(p.row_ptr, p.col, f64=True), p.n)
+    A = dense_adj(p.row_ptr, p.col, edge_weights(variant, p.row_ptr, p.col, f64=True), p.n)
 
     # (a) torch autograd on an independent dense formulation
     x0_t = torch.from_numpy(p.x0.astype(np.float64)).requires_grad_(True)
@@ -234,7 +240,7 @@ def test_p6_backward_is_the_gradient_of_the_chunked_forward(variant):
     loss.backward()
     for j in range(p.L):
         assert np.allclose(st.dW[j], W_t[j].grad.numpy(), rtol=1e-9, atol=1e-11), j
-        if variant == "gcn":
+        if variant != "gcnii":
             assert np.allclose(st.db[j], b_t[j].grad.numpy(), rtol=1e-9, atol=1e-11), j
     assert np.allclose(st.grad_in, x0_t.grad.numpy(), rtol=1e-9, atol=1e-11)
     if variant == "gcnii":
@@ -251,7 +257,7 @@ def test_p6_backward_is_the_gradient_of_the_chunked_forward(variant):
     eps = 1e-6
     for _ in range(6):
         j = int(rng.integers(p.L))
-        i, o = int(rng.integers(p.dims[j])), int(rng.integers(p.dims[j + 1]))
+        i, o = int(rng.integers(p.W[j].shape[0])), int(rng.integers(p.dims[j + 1]))
 
         def bump_w(s2, sgn, j=j, i=i, o=o):
             s2.W[j][i, o] += sgn * eps
@@ -311,6 +317,49 @@ def test_p7_gcnii_special_cases():
 
 
 # ----------------------------------------------------------------------------- bookkeeping
+def test_graphsage_special_cases():
+    """UPDATE(h_v, z_v) = ReLU(h_v W_self + z_v W_neigh + b) (Equation 1 takes both arguments).
+    W_self = 0 is the GCN update on the same edge weights; W_neigh = 0 is a plain MLP that neither the
+    graph nor the history can reach."""
+    w = tiny_workload(n=37, k=3, dims=(5, 6, 4), variant="sage", seed=5)
+    p = make_problem(w, first_stage=False, noise_std=0.3)
+    # (a) W_self = 0
+    pa = make_problem(w, first_stage=False, noise_std=0.3)
+    for j in range(pa.L):
+        pa.W[j][:pa.dims[j]] = 0.0
+    sa = run_oracle(pa)
+    gcn = oracle.OracleStage(pa.row_ptr, pa.col, pa.val, pa.chunk_ptr, pa.dims, [pa.W[j][pa.dims[j]:] for j in range(pa.L)], pa.b)
+    gcn.cur[0][...] = pa.x0
+    for j in range(pa.L):
+        gcn.hist[j][...] = pa.hist[j]
+    gcn.forward_pass(pa.order)
+    gcn.backward_pass(pa.grad_out)
+    for j in range(1, pa.L + 1):
+        assert np.array_equal(sa.cur[j], gcn.cur[j])
+    for j in range(pa.L):
+        assert np.array_equal(sa.dW[j][pa.dims[j]:], gcn.dW[j]) and np.array_equal(sa.db[j], gcn.db[j])
+    # the history those runs started from was made by a GraphSage pass, so it differs from zero
+    assert np.abs(sa.grad_in - gcn.grad_in).max() <= 1e-6 * np.abs(gcn.grad_in).max()
+    assert np.abs(sa.cur[pa.L]).max() > 0
+    # (b) W_neigh = 0: rows are independent of each other
+    pb = make_problem(w, first_stage=False, noise_std=0.3)
+    for j in range(pb.L):
+        pb.W[j][pb.dims[j]:] = 0.0
+    sb = run_oracle(pb)
+    h = pb.x0.astype(np.float64)
+    for j in range(pb.L):
+        h = np.maximum(h @ pb.W[j][:pb.dims[j]].astype(np.float64) + pb.b[j], 0.0)
+    assert max_rel(sb.cur[pb.L], h) < 2e-6
+    hist_free = make_problem(w, first_stage=False, noise_std=0.3)
+    for j in range(hist_free.L):
+        hist_free.W[j][hist_free.dims[j]:] = 0.0
+        hist_free.hist[j][...] = 123.0                     # no output may depend on the history
+    sc = run_oracle(hist_free)
+    assert np.array_equal(sc.cur[pb.L], sb.cur[pb.L]) and np.array_equal(sc.grad_in, sb.grad_in)
+    for j in range(pb.L):
+        assert np.array_equal(sc.dW[j][:pb.dims[j]], sb.dW[j][:pb.dims[j]])
+
+
 def test_transposed_index_round_trip_and_push_pull():
     rng = np.random.default_rng(3)
     n = 23
