@@ -44,7 +44,7 @@ enum {
   GNNSTAGE_ENOTSUP = -6  /* sizes beyond what the index packing supports */
 };
 
-enum { GNNSTAGE_GCN = 0, GNNSTAGE_GCNII = 1 };
+enum { GNNSTAGE_GCN = 0, GNNSTAGE_GCNII = 1, GNNSTAGE_SAGE = 2 };
 enum { GNNSTAGE_F32 = 0, GNNSTAGE_BF16 = 1 };
 
 /*
@@ -55,6 +55,11 @@ enum { GNNSTAGE_F32 = 0, GNNSTAGE_BF16 = 1 };
  * variant GNNSTAGE_GCNII (benchmark definition; the paper only cites the model):
  *     p_v = (1-alpha) z_v + alpha h0_v ;  h'_v = ReLU((1-beta_l) p_v + beta_l p_v W)
  *     (all widths equal, no bias).
+ * variant GNNSTAGE_SAGE  (Section 2.1, Equation 1: UPDATE takes h_v of the previous layer and z_v; the
+ *     paper only cites the model, the form is Hamilton et al.'s):
+ *     h'_v = ReLU(h_v W_self + z_v W_neigh + b), W[j] = [W_self ; W_neigh] stacked, 2 d_j x d_{j+1}
+ *     (dW[j] likewise).  v is in the chunk being computed, so h_v is its current row.  The aggregator's
+ *     weights are edge_val; edge_val == NULL means the mean aggregator, 1 / (length of row v).
  *
  * dtype GNNSTAGE_F32 : levels, weights, gradients rows are fp32; fp32 arithmetic.
  * dtype GNNSTAGE_BF16: levels, weights, gradient rows are bf16 (bias and all accumulators

@@ -14,7 +14,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libgnnstage.so")
 
-GNNSTAGE_GCN, GNNSTAGE_GCNII = 0, 1
+GNNSTAGE_GCN, GNNSTAGE_GCNII, GNNSTAGE_SAGE = 0, 1, 2
 GNNSTAGE_F32, GNNSTAGE_BF16 = 0, 1
 KIND_NAMES = ["spmm_fwd", "gemm_fwd", "spmm_bwd", "gemm_dgrad", "gemm_wgrad", "history_copy", "other", "spmm_reduce"]
 _ERRORS = {-1: "EINVAL", -2: "ERANGE", -3: "EORDER", -4: "ENOMEM", -5: "EHIP", -6: "ENOTSUP"}

@@ -26,8 +26,12 @@ enum SpmmEpilogue : int {
   SPMM_PLAIN = 0,     // out = acc
   SPMM_MIX = 1,       // out = s_acc * acc + s_aux * aux[row]      (GCNII initial residual)
   SPMM_MASK = 2,      // out = aux[row] > 0 ? acc : 0              (ReLU derivative on the way back)
-  SPMM_BIAS_RELU = 3  // out = max(acc + bias[c], 0)               (transform-first layers)
+  SPMM_BIAS_RELU = 3, // out = max(acc + bias[c], 0)               (transform-first layers)
+  SPMM_ADD = 4,       // out = acc + add[row - add_row0]           (GraphSage: the gradient through W_self joins)
+  SPMM_ADD_MASK = 5   // out = aux[row] > 0 ? acc + add[row - add_row0] : 0
 };
+__host__ __device__ inline bool spmm_reads_aux(int e) { return e == SPMM_MIX || e == SPMM_MASK || e == SPMM_ADD_MASK; }
+__host__ __device__ inline bool spmm_reads_add(int e) { return e == SPMM_ADD || e == SPMM_ADD_MASK; }
 
 struct SpmmArgs {
   // sparse structure: packed index words (vertex | chunk << vbits) and weights
@@ -82,6 +86,9 @@ struct SpmmArgs {
   int32_t aux_ld;
   float s_acc, s_aux;
   const float *bias;  // SPMM_BIAS_RELU
+  const void *add;    // SPMM_ADD / SPMM_ADD_MASK: rows indexed by row - add_row0, same dtype as src
+  int32_t add_ld;
+  int64_t add_row0;
 };
 
 // which task the wave `wave` of workgroup `b` runs (-1: none)
@@ -153,7 +160,8 @@ enum GemmEpilogue : int {
   EPI_FWD_GCNII = 1,   // out = ReLU((1-beta) aux[m][n] + beta acc)
   EPI_PLAIN = 2,       // out = acc
   EPI_DGRAD_GCNII = 3, // dp = (1-beta) aux[m][n] + beta acc; out = (1-alpha) dp; h0grad[m][n] += alpha dp
-  EPI_MASK = 4         // out = aux[m][n] > 0 ? acc : 0
+  EPI_MASK = 4,        // out = aux[m][n] > 0 ? acc : 0
+  EPI_FWD_ADD = 5      // out = ReLU(acc + bias[n] + aux[m][n])   (GraphSage: aux = h_v W_self)
 };
 
 // C[M x N] = A[M x K] . Bt[N x Kp]^T.  Bt is an internal buffer: K-contiguous rows, zero padded to Kp,

@@ -264,6 +264,8 @@ struct Layout {
   size_t dense_partial, zero_row;
   size_t partial;
   std::vector<size_t> Z, dZ, Wt, Wn, Tc, Th;
+  std::vector<size_t> Wt_self, Wn_self;  // GraphSage: staged copies of W_self (Wt / Wn then hold W_neigh)
+  size_t self_fwd = 0, self_bwd = 0;      // GraphSage: h_v W_self of a chunk (fp32), dY W_self^T of a chunk
   size_t G[2];
   size_t gemm_partial, bias_partial;
   size_t total;
@@ -276,6 +278,10 @@ struct Shape {
   std::vector<int> dims, ld;
   std::vector<char> tf;  // per layer: 1 = transform first (gather rows of width d_{j+1}), 0 = aggregate first
   int dtype = 0, level0_f32 = 0, variant = 0, need_input_grad = 0;
+  bool has_bias() const { return variant != GNNSTAGE_GCNII; }
+  bool sage() const { return variant == GNNSTAGE_SAGE; }
+  // elements of one weight matrix: GraphSage stacks [W_self ; W_neigh]
+  size_t w_half(int j) const { return (size_t)dims[j] * dims[j + 1]; }
   int elt() const { return dtype == GNNSTAGE_BF16 ? 2 : 4; }
   int level_elt(int j) const { return (j == 0 && level0_f32) ? 4 : elt(); }
   // source classes for the aggregation schedule, decided by the widest bf16/fp32 table that is gathered
@@ -311,7 +317,7 @@ bool read_shape(const gnnstage_desc *d, Shape &s, std::string &err) {
   if (d->n_chunks <= 0 || d->n_chunks > kMaxChunks) { err = "n_chunks must be in [1, 256]"; return false; }
   if (d->n_layers <= 0 || d->n_layers > 1024) { err = "n_layers must be in [1, 1024]"; return false; }
   if (d->dtype != GNNSTAGE_F32 && d->dtype != GNNSTAGE_BF16) { err = "unknown dtype"; return false; }
-  if (d->variant != GNNSTAGE_GCN && d->variant != GNNSTAGE_GCNII) { err = "unknown variant"; return false; }
+  if (d->variant != GNNSTAGE_GCN && d->variant != GNNSTAGE_GCNII && d->variant != GNNSTAGE_SAGE) { err = "unknown variant"; return false; }
   s.n = d->n_vertices;
   s.nnz = d->nnz;
   s.K = d->n_chunks;
@@ -439,6 +445,16 @@ Layout make_layout(const Shape &s, const HostDir &hf, const HostDir &hb, bool ra
   for (int j = 0; j < s.L; ++j) {
     l.Wt[j] = w.take((size_t)s.dims[j + 1] * s.ld[j] * elt);
     l.Wn[j] = w.take((size_t)s.dims[j] * s.ld[j + 1] * elt);
+  }
+  if (s.sage()) {
+    l.Wt_self.resize(s.L);
+    l.Wn_self.resize(s.L);
+    for (int j = 0; j < s.L; ++j) {
+      l.Wt_self[j] = w.take((size_t)s.dims[j + 1] * s.ld[j] * elt);
+      l.Wn_self[j] = w.take((size_t)s.dims[j] * s.ld[j + 1] * elt);
+    }
+    l.self_fwd = w.take(sizeof(float) * (size_t)s.max_rows() * max_ld);
+    l.self_bwd = w.take((size_t)s.max_rows() * max_ld * elt);
   }
   l.G[0] = w.take((size_t)s.max_rows() * max_ld * elt);
   l.G[1] = w.take((size_t)s.max_rows() * max_ld * elt);
@@ -849,7 +865,7 @@ extern "C" size_t gnnstage_workspace_size(const gnnstage_desc *desc) {
     g_create_error = err;
     return 0;
   }
-  return make_layout(s, hp.f, hp.b, desc->edge_val == nullptr).total;
+  return make_layout(s, hp.f, hp.b, desc->edge_val == nullptr && !s.sage()).total;
 }
 
 extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
@@ -858,9 +874,24 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
   Shape s;
   std::string err;
   if (!read_shape(d, s, err)) return fail(nullptr, GNNSTAGE_EINVAL, err);
+  // GraphSage without weights: the mean aggregator, 1 / |N(v)| on every entry of row v, handled from here on
+  // like weights the caller gave
+  std::vector<float> mean_val;
+  gnnstage_desc with_mean;
+  if (s.sage() && !d->edge_val && d->row_ptr) {
+    mean_val.resize((size_t)s.nnz);
+    for (int64_t v = 0; v < s.n; ++v) {
+      const int64_t e0 = d->row_ptr[v], e1 = d->row_ptr[v + 1];
+      if (e0 < 0 || e1 < e0 || e1 > s.nnz) return fail(nullptr, GNNSTAGE_EINVAL, "row_ptr is not a valid CSR pointer array");
+      for (int64_t e = e0; e < e1; ++e) mean_val[(size_t)e] = 1.f / (float)(e1 - e0);
+    }
+    with_mean = *d;
+    with_mean.edge_val = mean_val.data();
+    d = &with_mean;
+  }
   if (!d->W || !d->cur || !d->hist) return fail(nullptr, GNNSTAGE_EINVAL, "W, cur and hist must not be NULL");
   if (!d->dW) return fail(nullptr, GNNSTAGE_EINVAL, "dW must not be NULL");
-  if (s.variant == GNNSTAGE_GCN && (!d->bias || !d->dbias)) return fail(nullptr, GNNSTAGE_EINVAL, "GCN needs bias and dbias");
+  if (s.has_bias() && (!d->bias || !d->dbias)) return fail(nullptr, GNNSTAGE_EINVAL, "GCN and GraphSage need bias and dbias");
   if (s.variant == GNNSTAGE_GCNII && (!d->beta || !d->h0)) return fail(nullptr, GNNSTAGE_EINVAL, "GCNII needs beta and h0");
   if (s.need_input_grad && !d->grad_in) return fail(nullptr, GNNSTAGE_EINVAL, "need_input_grad set but grad_in is NULL");
   if (!d->workspace || (reinterpret_cast<uintptr_t>(d->workspace) & (kAlign - 1)))
@@ -870,7 +901,7 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
     if (j < s.L) {
       if (!d->hist[j] || !aligned16(d->hist[j])) return fail(nullptr, GNNSTAGE_EINVAL, "hist[j] NULL or not 16-byte aligned");
       if (!d->W[j] || !d->dW[j]) return fail(nullptr, GNNSTAGE_EINVAL, "W[j] / dW[j] NULL");
-      if (s.variant == GNNSTAGE_GCN && (!d->bias[j] || !d->dbias[j])) return fail(nullptr, GNNSTAGE_EINVAL, "bias[j] / dbias[j] NULL");
+      if (s.has_bias() && (!d->bias[j] || !d->dbias[j])) return fail(nullptr, GNNSTAGE_EINVAL, "bias[j] / dbias[j] NULL");
     }
   }
   if ((d->h0 && !aligned16(d->h0)) || (d->grad_in && !aligned16(d->grad_in)))
@@ -1179,9 +1210,15 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
     st->n_bwd = 0;
     {
       Timed t(st, stream, 6);
-      for (int j = 0; j < s.L; ++j)
-        HIP_TRY(st, launch_stage_weights(st->W[j], cd, s.dims[j], s.dims[j + 1], st->at<char>(st->lay.Wt[j]), s.ld[j],
+      for (int j = 0; j < s.L; ++j) {
+        // GraphSage: W[j] = [W_self ; W_neigh]; Wt / Wn take the half that multiplies the aggregation
+        const char *Wagg = static_cast<const char *>(st->W[j]) + (s.sage() ? s.w_half(j) * s.elt() : 0);
+        HIP_TRY(st, launch_stage_weights(Wagg, cd, s.dims[j], s.dims[j + 1], st->at<char>(st->lay.Wt[j]), s.ld[j],
                                          st->at<char>(st->lay.Wn[j]), s.ld[j + 1], stream));
+        if (s.sage())
+          HIP_TRY(st, launch_stage_weights(st->W[j], cd, s.dims[j], s.dims[j + 1], st->at<char>(st->lay.Wt_self[j]), s.ld[j],
+                                           st->at<char>(st->lay.Wn_self[j]), s.ld[j + 1], stream));
+      }
     }
     // transform-first layers: the historical rows are constants of the pass, transform them once
     for (int j = 0; j < s.L; ++j) {
@@ -1269,6 +1306,24 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
       }
       HIP_TRY(st, run_spmm(st, a, false, k, st->level_dtype(j), cd, stream, 0, j));
     }
+    if (s.sage()) {  // the vertex's own row through W_self, kept in fp32 until the layer's epilogue adds it
+      Timed t(st, stream, 1, j);
+      GemmNtArgs g{};
+      g.A = static_cast<const char *>(st->cur[j]) + (size_t)row0 * s.dims[j] * st->level_elt(j);
+      g.a_dtype = st->level_dtype(j);
+      g.lda = s.dims[j];
+      g.Bt = st->at<char>(st->lay.Wt_self[j]);
+      g.ldb = s.ld[j];
+      g.M = (int)M;
+      g.N = s.dims[j + 1];
+      g.K = s.dims[j];
+      g.Kp = s.ld[j];
+      g.epilogue = EPI_PLAIN;
+      g.out = st->at<float>(st->lay.self_fwd);
+      g.out_dtype = DT_F32;
+      g.out_ld = s.ld[j + 1];
+      HIP_TRY(st, launch_gemm_nt(g, cd, stream));
+    }
     {
       Timed t(st, stream, 1, j);
       GemmNtArgs g{};
@@ -1290,6 +1345,12 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
       } else {
         g.epilogue = EPI_FWD_GCN;
         g.bias = static_cast<const float *>(st->bias[j]);
+        if (s.sage()) {
+          g.epilogue = EPI_FWD_ADD;
+          g.aux = st->at<float>(st->lay.self_fwd);
+          g.aux_dtype = DT_F32;
+          g.aux_ld = s.ld[j + 1];
+        }
       }
       g.out = static_cast<char *>(st->cur[j + 1]) + (size_t)row0 * s.dims[j + 1] * celt;
       g.out_dtype = cd;
@@ -1331,8 +1392,8 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
     const char *dY = G[gi];
     // bias gradient = column sums of dY: fused into the weight-gradient product where that product reads dY
     // (aggregate-first layers of the bf16 stage), a kernel of its own otherwise
-    const bool fuse_bias = s.variant == GNNSTAGE_GCN && !s.tf[j] && cd == DT_BF16;
-    if (s.variant == GNNSTAGE_GCN && !fuse_bias) {
+    const bool fuse_bias = s.has_bias() && !s.tf[j] && cd == DT_BF16;
+    if (s.has_bias() && !fuse_bias) {
       Timed t(st, stream, 4, j);
       HIP_TRY(st, launch_colsum_add(dY, cd, s.ld[j + 1], (int)M, s.dims[j + 1], bias_partial, kMaxSplits, st->dbias[j], stream));
     }
@@ -1429,7 +1490,7 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
       w.I = s.dims[j];
       w.O = s.dims[j + 1];
       w.scale = s.variant == GNNSTAGE_GCNII ? st->beta[j] : 1.f;
-      w.dW = st->dW[j];
+      w.dW = st->dW[j] + (s.sage() ? s.w_half(j) : 0);  // GraphSage: W_neigh is the lower half
       w.partial = gemm_partial;
       w.max_splits = kMaxSplits;
       if (fuse_bias) {
@@ -1437,6 +1498,22 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
         w.bias_partial = bias_partial;
       }
       HIP_TRY(st, launch_gemm_tn(w, cd, stream));
+      if (s.sage()) {  // dW_self += h_v^T dY over the chunk's own (current) rows
+        GemmTnArgs ws{};
+        ws.A = static_cast<const char *>(st->cur[j]) + (size_t)row0 * s.dims[j] * st->level_elt(j);
+        ws.a_dtype = st->level_dtype(j);
+        ws.lda = s.dims[j];
+        ws.B = dY;
+        ws.ldb = s.ld[j + 1];
+        ws.M = (int)M;
+        ws.I = s.dims[j];
+        ws.O = s.dims[j + 1];
+        ws.scale = 1.f;
+        ws.dW = st->dW[j];
+        ws.partial = gemm_partial;
+        ws.max_splits = kMaxSplits;
+        HIP_TRY(st, launch_gemm_tn(ws, cd, stream));
+      }
     }
     if (!need_prev) break;
     char *dZj = st->at<char>(st->lay.dZ[j]);
@@ -1468,6 +1545,11 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
       g.out_dtype = cd;
       g.out_ld = s.ld[j];
       HIP_TRY(st, launch_gemm_nt(g, cd, stream));
+      if (s.sage()) {  // the gradient that reaches the chunk's own rows directly: dY W_self^T
+        g.Bt = st->at<char>(st->lay.Wn_self[j]);
+        g.out = st->at<char>(st->lay.self_bwd);
+        HIP_TRY(st, launch_gemm_nt(g, cd, stream));
+      }
     }
     {
       SpmmArgs a = base_spmm(st, true, k);
@@ -1475,11 +1557,16 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
       a.src_unsel = nullptr;  // Section 3.4: nothing flows back from unprocessed vertices
       a.d = s.dims[j];
       a.src_ld = s.ld[j];
+      if (s.sage()) {
+        a.add = st->at<char>(st->lay.self_bwd);
+        a.add_ld = s.ld[j];
+        a.add_row0 = row0;
+      }
       if (j > 0) {
         a.out = G[gi ^ 1];
         a.out_ld = s.ld[j];
         a.out_row0 = row0;
-        a.epilogue = SPMM_MASK;
+        a.epilogue = s.sage() ? SPMM_ADD_MASK : SPMM_MASK;
         a.aux = st->cur[j];
         a.aux_ld = s.dims[j];
         HIP_TRY(st, run_spmm(st, a, true, k, cd, cd, stream, 2, j));
@@ -1487,7 +1574,7 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
         a.out = st->grad_in;
         a.out_ld = s.dims[0];
         a.out_row0 = 0;
-        a.epilogue = SPMM_PLAIN;
+        a.epilogue = s.sage() ? SPMM_ADD : SPMM_PLAIN;
         HIP_TRY(st, run_spmm(st, a, true, k, cd, st->level_dtype(0), stream, 2, j));
       }
     }

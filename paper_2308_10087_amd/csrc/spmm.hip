@@ -35,7 +35,7 @@ __device__ inline bf16_t from_f32<bf16_t>(float x) { return (bf16_t)x; }
 // The row of the auxiliary matrix that the mixing and masking epilogues read (zeros for the others).
 template <typename Tin, int VEC>
 __device__ inline Pack<Tin, VEC> load_aux(const SpmmArgs &a, int64_t row, int c) {
-  if (a.epilogue == SPMM_MIX || a.epilogue == SPMM_MASK)
+  if (spmm_reads_aux(a.epilogue))
     return *reinterpret_cast<const Pack<Tin, VEC> *>(static_cast<const Tin *>(a.aux) + (size_t)row * a.aux_ld + c);
   Pack<Tin, VEC> z;
 #pragma unroll
@@ -56,6 +56,14 @@ __device__ inline void finish_cols(const SpmmArgs &a, int64_t row, int c, const 
     for (int t = 0; t < VEC; ++t) {
       const float y = acc[t] + a.bias[c + t];
       r[t] = y > 0.f ? y : 0.f;
+    }
+  } else if (spmm_reads_add(a.epilogue)) {
+    const Pack<Tin, VEC> y = *reinterpret_cast<const Pack<Tin, VEC> *>(
+        static_cast<const Tin *>(a.add) + (size_t)(row - a.add_row0) * a.add_ld + c);
+#pragma unroll
+    for (int t = 0; t < VEC; ++t) {
+      const float sum = acc[t] + to_f32(y.v[t]);
+      r[t] = (a.epilogue == SPMM_ADD || to_f32(x.v[t]) > 0.f) ? sum : 0.f;
     }
   } else if (a.epilogue == SPMM_MIX) {
 #pragma unroll
@@ -511,13 +519,13 @@ static const Shape *pick_shape(const SpmmArgs &a, int src_dtype, int out_dtype) 
   else
     tab = out_dtype == DT_BF16 ? shapes_f32<bf16_t>(&n) : shapes_f32<float>(&n);
   // widest vector that divides every leading dimension involved
-  const bool has_aux = a.epilogue == SPMM_MIX || a.epilogue == SPMM_MASK;
-  const int lds[4] = {a.d, a.src_ld, a.out_ld, has_aux ? a.aux_ld : a.d};
+  const bool has_aux = spmm_reads_aux(a.epilogue);
+  const int lds[5] = {a.d, a.src_ld, a.out_ld, has_aux ? a.aux_ld : a.d, spmm_reads_add(a.epilogue) ? a.add_ld : a.d};
   const Shape *best = nullptr;
   int best_vec = 0;
   for (int i = 0; i < n; ++i) {
     bool ok = true;
-    for (int k = 0; k < 4; ++k) ok = ok && (lds[k] % tab[i].vec == 0);
+    for (int k = 0; k < 5; ++k) ok = ok && (lds[k] % tab[i].vec == 0);
     if (ok && tab[i].vec > best_vec) best_vec = tab[i].vec;
   }
   if (best_vec == 0) return nullptr;  // bf16 rows of odd width are rejected at create time
@@ -537,9 +545,9 @@ static const Shape *pick_shape(const SpmmArgs &a, int src_dtype, int out_dtype) 
 
 static bool mfma_path(const SpmmArgs &a, int src_dtype) {
   static const bool off = getenv("GNNSTAGE_SPMM_VALU") != nullptr;  // measurement switch
-  const bool has_aux = a.epilogue == SPMM_MIX || a.epilogue == SPMM_MASK;
+  const bool has_aux = spmm_reads_aux(a.epilogue);
   return !off && src_dtype == DT_BF16 && a.d % 8 == 0 && a.src_ld % 8 == 0 && a.out_ld % 8 == 0 &&
-         (!has_aux || a.aux_ld % 8 == 0);
+         (!has_aux || a.aux_ld % 8 == 0) && (!spmm_reads_add(a.epilogue) || a.add_ld % 8 == 0);
 }
 
 template <typename Tout, int NT>

@@ -21,13 +21,13 @@ class GpuRun:
         L, n = p.L, p.n
         self.sdt, self.l0 = sdt, l0
         self.W = [_dev(p.W[j], sdt, device) for j in range(L)]
-        gcn = p.w.variant == "gcn"
+        gcn = p.w.variant in ("gcn", "sage")   # layers with a bias vector
         self.bias = [_dev(p.b[j], torch.float32, device) for j in range(L)] if gcn else None
         self.cur = [_dev(p.x0, l0, device)] + [torch.zeros((n, p.dims[j]), dtype=sdt, device=device) for j in range(1, L + 1)]
         self.hist = [_dev(p.hist[j], l0 if j == 0 else sdt, device) for j in range(L)]
         if alias_hist0:  # a first stage: level 0 never changes, so history IS the current buffer
             self.hist[0] = self.cur[0]
-        self.dW = [torch.zeros((p.dims[j], p.dims[j + 1]), dtype=torch.float32, device=device) for j in range(L)]
+        self.dW = [torch.zeros(p.W[j].shape, dtype=torch.float32, device=device) for j in range(L)]
         self.dbias = [torch.zeros(p.dims[j + 1], dtype=torch.float32, device=device) for j in range(L)] if gcn else None
         self.h0 = None if gcn else _dev(p.h0, sdt, device)
         self.grad_h0 = None if gcn else torch.zeros((n, p.dims[0]), dtype=torch.float32, device=device)
@@ -36,7 +36,7 @@ class GpuRun:
         self.stage = g.GnnStage(
             p.row_ptr, p.col, p.chunk_ptr, p.dims, W=self.W, cur=self.cur, hist=self.hist, dW=self.dW,
             bias=self.bias, dbias=self.dbias, edge_val=(p.val if edge_val == "given" else None),
-            variant=g.GNNSTAGE_GCN if gcn else g.GNNSTAGE_GCNII, alpha=p.a,
+            variant={"gcn": g.GNNSTAGE_GCN, "gcnii": g.GNNSTAGE_GCNII, "sage": g.GNNSTAGE_SAGE}[p.w.variant], alpha=p.a,
             beta=None if gcn else p.beta.astype(np.float32), h0=self.h0, grad_h0=self.grad_h0,
             dtype=g.GNNSTAGE_BF16 if bf else g.GNNSTAGE_F32, level0_f32=p.level0_f32, grad_in=self.grad_in,
             device=device)

@@ -63,7 +63,7 @@ def _compare(run, ref, p, tol, need_input_grad=True):
         worst[f"level{j}"] = max_rel(run.np(run.cur[j]), ref.cur[j])
     for j in range(p.L):
         worst[f"dW{j}"] = max_rel(run.np(run.dW[j]), ref.dW[j])
-        if p.w.variant == "gcn":
+        if p.w.variant in ("gcn", "sage"):
             worst[f"db{j}"] = max_rel(run.np(run.dbias[j]), ref.db[j])
     if need_input_grad:
         worst["grad_in"] = max_rel(run.np(run.grad_in), ref.grad_in)
@@ -432,3 +432,43 @@ def test_protocol_errors():
         s.stage_backward_chunk(1, run.grad_out[s.rows(1)])
     assert e.value.code == -3
     torch.cuda.synchronize()
+
+
+# ----------------------------------------------------------------------------- GraphSage variant
+@pytest.mark.parametrize("dims", [(24, 40, 16, 32), (7, 5, 3), (100, 128, 64)])
+def test_sage_fp32(dims):
+    w = small(dims=dims, n=911, k=6, variant="sage")
+    p = make_problem(w, chunk_ptr=graphs.ragged_chunks(911, 6, 4))
+    _parity(p, TOL_F32)
+    _parity(make_problem(w, first_stage=False, noise_std=0.3), TOL_F32)
+
+
+def test_sage_fp32_mean_aggregator_computed_by_the_library():
+    """edge_val == NULL with the GraphSage variant means the mean aggregator, 1 / (row length)."""
+    p = make_problem(small(variant="sage"))
+    a = _gpu(p, edge_val="given").run()
+    b = _gpu(p, edge_val="computed").run()
+    for j in range(1, p.L + 1):
+        assert torch.equal(a.cur[j], b.cur[j])
+    for j in range(p.L):
+        assert torch.equal(a.dW[j], b.dW[j])
+    assert torch.equal(a.grad_in, b.grad_in)
+
+
+@pytest.mark.parametrize("dims,level0_f32", [((64, 128, 128, 64), False), ((100, 128, 256), True), ((256, 256, 256), False)])
+def test_sage_bf16(dims, level0_f32):
+    w = Workload("sage_s", "rmat", 5003, 2308100890, list(dims), 6, variant="sage", dtype="bf16", level0_f32=level0_f32,
+                 n_candidates=60_000)
+    p = make_problem(w, first_stage=level0_f32)
+    _parity(p, TOL_BF16)
+
+
+def test_sage_bf16_dense_blocks(monkeypatch):
+    monkeypatch.setenv("GNNSTAGE_DENSE_MIN_ENTRIES", "0")
+    monkeypatch.setenv("GNNSTAGE_DENSE_MIN_NNZ", "64")
+    monkeypatch.setenv("GNNSTAGE_DENSE_MIN_SHARE", "0.05")
+    w = Workload("sage_d", "rmat", 6007, 2308100891, [128, 128, 128], 4, variant="sage", dtype="bf16", n_candidates=260_000)
+    p = make_problem(w, first_stage=False)
+    probe = _gpu(p)
+    assert probe.stage.gnnstage_dense_entries(False) > 0 and probe.stage.gnnstage_dense_entries(True) > 0
+    _parity(p, TOL_BF16)
