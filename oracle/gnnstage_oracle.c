@@ -27,6 +27,12 @@
  *     the aggregator's weights given per edge, 1/|N(v)| for the mean aggregator):
  *     h' = ReLU(h_v W_self + z_v W_neigh + b), W stored as [W_self ; W_neigh], 2 d_in x d_out.
  *     v belongs to the chunk being computed, so h_v is its current row.
+ *   - ResGCN+ variant (the paper only cites the model; the layer is DeepGCNs' pre-activation
+ *     residual block with a GCN convolution): r_u = ReLU(LayerNorm(h_u)), z_v = sum_u A_vu r_u,
+ *     h'_v = h_v + z_v W + b.  LayerNorm is over the features of one vertex,
+ *     gamma * (x - mean) / sqrt(var + eps) + beta with the biased variance.  The current-vs-historical
+ *     choice applies to h_u; the normalisation is this layer's own, so its parameters also receive
+ *     gradient through the historical rows (oracle_backward_finish).
  *
  * Precision: arrays are fp32 storage, every sum runs in fp64.  With quant == 1 the
  * values the GPU path keeps in bf16 (saved aggregation, levels, gradient rows) are
@@ -70,7 +76,7 @@ typedef struct {
   /* stage */
   int32_t L;
   const int32_t *dims; /* L+1 */
-  int32_t variant;     /* 0 GCN, 1 GCNII, 2 GraphSage */
+  int32_t variant;     /* 0 GCN, 1 GCNII, 2 GraphSage, 3 ResGCN+ */
   double a;            /* GCNII initial-residual weight */
   const double *beta;  /* GCNII, L entries */
   int32_t quant;       /* 0: fp32 storage, 1: bf16 storage of levels >= 1, Z, dZ, g */
@@ -89,6 +95,14 @@ typedef struct {
   uint8_t *processed;  /* K flags, forward */
   uint8_t *bprocessed; /* K flags, backward */
   real_t *g0, *g1;      /* scratch: max chunk rows x max d each */
+  /* ResGCN+ only */
+  real_t *const *ln_g;  /* L arrays d: LayerNorm scale */
+  real_t *const *ln_b;  /* L arrays d: LayerNorm shift */
+  double *const *d_ln_g; /* accumulated (+=) */
+  double *const *d_ln_b;
+  double ln_eps;
+  int32_t *fwd_pos;     /* K entries: position of every chunk in this pass's forward order */
+  int32_t n_fwd;
 } oracle_stage;
 
 void oracle_set_threads(int n) {
@@ -181,6 +195,56 @@ void oracle_build_transpose(int64_t n, const int64_t *row_ptr, const int32_t *co
 void oracle_begin_pass(oracle_stage *s) {
   memset(s->processed, 0, (size_t)s->K);
   memset(s->bprocessed, 0, (size_t)s->K);
+  s->n_fwd = 0;
+}
+
+/* LayerNorm statistics of one row: mean and 1/sqrt(biased variance + eps) */
+static void ln_stats(const real_t *x, int32_t d, double eps, double *mean, double *rstd) {
+  double m = 0.0;
+  for (int32_t i = 0; i < d; ++i) m += (double)x[i];
+  m /= d;
+  double var = 0.0;
+  for (int32_t i = 0; i < d; ++i) var += ((double)x[i] - m) * ((double)x[i] - m);
+  var /= d;
+  *mean = m;
+  *rstd = 1.0 / sqrt(var + eps);
+}
+
+/* r = ReLU(LayerNorm(x)), stored like every other row the GPU path keeps */
+static void ln_relu_row(const oracle_stage *s, int32_t j, const real_t *x, int32_t d, real_t *r) {
+  double mean, rstd;
+  ln_stats(x, d, s->ln_eps, &mean, &rstd);
+  for (int32_t i = 0; i < d; ++i) {
+    const double y = (double)s->ln_g[j][i] * (((double)x[i] - mean) * rstd) + (double)s->ln_b[j][i];
+    r[i] = store(s, y > 0.0 ? y : 0.0);
+  }
+}
+
+/* Backward of r = ReLU(LayerNorm(x)) for one row: dr -> dx (may be NULL), and the parameter gradients. */
+static void ln_relu_row_backward(const oracle_stage *s, int32_t j, const real_t *x, int32_t d, const double *dr,
+                                 double *dx, double *dg, double *db) {
+  double mean, rstd;
+  ln_stats(x, d, s->ln_eps, &mean, &rstd);
+  double m1 = 0.0, m2 = 0.0;
+  double *dxh = (double *)malloc(sizeof(double) * (size_t)d);
+  for (int32_t i = 0; i < d; ++i) {
+    const double xh = ((double)x[i] - mean) * rstd;
+    const double y = (double)s->ln_g[j][i] * xh + (double)s->ln_b[j][i];
+    const double dn = y > 0.0 ? dr[i] : 0.0; /* ReLU derivative, strict */
+    dg[i] += dn * xh;
+    db[i] += dn;
+    dxh[i] = dn * (double)s->ln_g[j][i];
+    m1 += dxh[i];
+    m2 += dxh[i] * xh;
+  }
+  m1 /= d;
+  m2 /= d;
+  if (dx)
+    for (int32_t i = 0; i < d; ++i) {
+      const double xh = ((double)x[i] - mean) * rstd;
+      dx[i] = rstd * (dxh[i] - m1 - xh * m2);
+    }
+  free(dxh);
 }
 
 /* Integer bookkeeping: how many neighbours of each row of chunk k would be read from
@@ -201,6 +265,7 @@ void oracle_select_counts(const oracle_stage *s, int32_t k, int32_t *out) {
  * The caller has already placed level-0 rows of C_k in cur[0]. */
 void oracle_forward_chunk(oracle_stage *s, int32_t k) {
   s->processed[k] = 1; /* V_processed <- V_processed U C_k, before the layers */
+  if (s->fwd_pos) s->fwd_pos[k] = s->n_fwd++;
   const int64_t v0 = s->chunk_ptr[k], v1 = s->chunk_ptr[k + 1];
   for (int32_t j = 0; j < s->L; ++j) {
     const int32_t din = s->dims[j], dout = s->dims[j + 1];
@@ -210,6 +275,7 @@ void oracle_forward_chunk(oracle_stage *s, int32_t k) {
     {
       double *z = (double *)malloc(sizeof(double) * (size_t)din);
       double *y = (double *)malloc(sizeof(double) * (size_t)dout);
+      real_t *ru = (real_t *)malloc(sizeof(real_t) * (size_t)din);
 #pragma omp for schedule(dynamic, 16)
       for (int64_t v = v0; v < v1; ++v) {
         /* AGGREGATE: processed neighbours -> current epoch, the rest -> history */
@@ -219,6 +285,10 @@ void oracle_forward_chunk(oracle_stage *s, int32_t k) {
           const real_t *src = s->processed[s->chunk_of[u]] ? cur : hist;
           const double w = (double)s->val[e];
           const real_t *hu = src + u * din;
+          if (s->variant == 3) { /* ResGCN+: the neighbour enters normalised and activated */
+            ln_relu_row(s, j, hu, din, ru);
+            hu = ru;
+          }
           for (int32_t i = 0; i < din; ++i) z[i] += w * (double)hu[i];
         }
         real_t *zs = s->Z[j] + v * din;
@@ -246,7 +316,11 @@ void oracle_forward_chunk(oracle_stage *s, int32_t k) {
           }
         }
         real_t *hn = s->cur[j + 1] + v * dout;
-        if (s->variant != 1) {
+        if (s->variant == 3) { /* ResGCN+: residual, no activation after the convolution */
+          const real_t *b = s->b[j];
+          const real_t *hv = cur + v * din;
+          for (int32_t o = 0; o < dout; ++o) hn[o] = store(s, (double)hv[o] + y[o] + (double)b[o]);
+        } else if (s->variant != 1) {
           const real_t *b = s->b[j];
           for (int32_t o = 0; o < dout; ++o) {
             double t = y[o] + (double)b[o];
@@ -262,6 +336,7 @@ void oracle_forward_chunk(oracle_stage *s, int32_t k) {
       }
       free(z);
       free(y);
+      free(ru);
     }
   }
 }
@@ -277,11 +352,13 @@ void oracle_backward_chunk(oracle_stage *s, int32_t k, const real_t *grad_out, i
     const int32_t din = s->dims[j], dout = s->dims[j + 1];
     const real_t *W = s->W[j];
     const real_t *hn = s->cur[j + 1];
-    /* dy = g where the layer's output is positive (ReLU derivative, strict) */
+    /* dy = g where the layer's output is positive (ReLU derivative, strict); ResGCN+ has no activation there */
+    if (s->variant != 3) {
 #pragma omp parallel for schedule(static)
-    for (int64_t r = 0; r < m; ++r)
-      for (int32_t o = 0; o < dout; ++o)
-        if (!(hn[(v0 + r) * dout + o] > (real_t)0)) g[r * dout + o] = (real_t)0;
+      for (int64_t r = 0; r < m; ++r)
+        for (int32_t o = 0; o < dout; ++o)
+          if (!(hn[(v0 + r) * dout + o] > (real_t)0)) g[r * dout + o] = (real_t)0;
+    }
     const double wscale = s->variant == 1 ? s->beta[j] : 1.0;
     const int64_t zoff = s->variant == 2 ? (int64_t)din * dout : 0; /* GraphSage: W_neigh is the lower half */
     /* weight gradient: dW[i][o] += scale * sum_v Zsaved[v][i] dy[v][o] */
@@ -335,7 +412,7 @@ void oracle_backward_chunk(oracle_stage *s, int32_t k, const real_t *grad_out, i
         }
       }
     }
-    if (j == 0 && !need_input_grad) break;
+    if (j == 0 && !need_input_grad && s->variant != 3) break; /* ResGCN+: LayerNorm's parameters still need it */
     /* GraphSage: the part of the gradient that reaches h_v directly, through W_self (kept in the scratch
      * rows that receive the next g; v is in the chunk, so this is always a current row) */
     if (s->variant == 2) {
@@ -365,9 +442,27 @@ void oracle_backward_chunk(oracle_stage *s, int32_t k, const real_t *grad_out, i
           const real_t *dz = s->dZ[j] + v * din;
           for (int32_t i = 0; i < din; ++i) acc[i] += w * (double)dz[i];
         }
+        if (s->variant == 3) {
+          /* acc is dL/dr_u over the readers that saw u's current row; stored like the GPU's gradient rows,
+           * then back through ReLU and LayerNorm of u's own row, plus the residual branch */
+          double *dr = (double *)malloc(sizeof(double) * (size_t)din * 2);
+          double *dx = dr + din;
+          for (int32_t i = 0; i < din; ++i) dr[i] = (double)store(s, acc[i]);
+          double *dg = (double *)calloc((size_t)din * 2, sizeof(double));
+          ln_relu_row_backward(s, j, s->cur[j] + u * din, din, dr, dx, dg, dg + din);
+#pragma omp critical
+          for (int32_t i = 0; i < din; ++i) {
+            s->d_ln_g[j][i] += dg[i];
+            s->d_ln_b[j][i] += dg[din + i];
+          }
+          for (int32_t i = 0; i < din; ++i) acc[i] = (double)g[(u - v0) * dout + i] + dx[i];
+          free(dg);
+          free(dr);
+        }
         if (j == 0) {
           real_t *out = s->grad_in + u * din;
-          for (int32_t i = 0; i < din; ++i) out[i] = store_level0(s, acc[i]);
+          if (need_input_grad)
+            for (int32_t i = 0; i < din; ++i) out[i] = store_level0(s, acc[i]);
         } else {
           real_t *out = gn + (u - v0) * din;
           for (int32_t i = 0; i < din; ++i) out[i] = store(s, acc[i]);
@@ -378,6 +473,32 @@ void oracle_backward_chunk(oracle_stage *s, int32_t k, const real_t *grad_out, i
     real_t *t = g;
     g = gn;
     gn = t;
+  }
+}
+
+/* ResGCN+ only, after the last backward chunk of a pass.  The historical rows are constants, but the
+ * LayerNorm applied to them is this layer's own: its parameters receive gradient through every edge that
+ * read u's historical row, i.e. whose reader's chunk came BEFORE u's chunk in the forward order. */
+void oracle_backward_finish(oracle_stage *s) {
+  if (s->variant != 3) return;
+  for (int32_t j = 0; j < s->L; ++j) {
+    const int32_t d = s->dims[j];
+    double *acc = (double *)malloc(sizeof(double) * (size_t)d * 2);
+    double *dr = acc + d;
+    for (int64_t u = 0; u < s->n; ++u) {
+      const int32_t pu = s->fwd_pos[s->chunk_of[u]];
+      for (int32_t i = 0; i < d; ++i) acc[i] = 0.0;
+      for (int64_t p = s->t_ptr[u]; p < s->t_ptr[u + 1]; ++p) {
+        const int64_t v = s->t_row[p];
+        if (s->fwd_pos[s->chunk_of[v]] >= pu) continue; /* that reader saw the current row */
+        const double w = (double)s->val[s->t_edge[p]];
+        const real_t *dz = s->dZ[j] + v * d;
+        for (int32_t i = 0; i < d; ++i) acc[i] += w * (double)dz[i];
+      }
+      for (int32_t i = 0; i < d; ++i) dr[i] = (double)store(s, acc[i]);
+      ln_relu_row_backward(s, j, s->hist[j] + u * d, d, dr, NULL, s->d_ln_g[j], s->d_ln_b[j]);
+    }
+    free(acc);
   }
 }
 

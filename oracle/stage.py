@@ -44,6 +44,8 @@ class _CStage(C.Structure):
         ("grad_in", C.c_void_p),
         ("processed", C.c_void_p), ("bprocessed", C.c_void_p),
         ("g0", C.c_void_p), ("g1", C.c_void_p),
+        ("ln_g", C.c_void_p), ("ln_b", C.c_void_p), ("d_ln_g", C.c_void_p), ("d_ln_b", C.c_void_p),
+        ("ln_eps", C.c_double), ("fwd_pos", C.c_void_p), ("n_fwd", C.c_int32),
     ]
 
 
@@ -60,6 +62,8 @@ def _lib(f64: bool):
         lib.oracle_forward_chunk.argtypes = [C.c_void_p, C.c_int32]
         lib.oracle_backward_chunk.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32]
         lib.oracle_update_history.argtypes = [C.c_void_p]
+        lib.oracle_backward_finish.argtypes = [C.c_void_p]
+        lib.oracle_backward_finish.restype = None
         lib.oracle_set_threads.argtypes = [C.c_int]
         lib.oracle_max_threads.restype = C.c_int
         for f in ("oracle_gcn_norm", "oracle_chunk_of", "oracle_build_transpose", "oracle_begin_pass",
@@ -102,7 +106,8 @@ class OracleStage:
     (``cur``, ``hist``, ``W``, ``b``, ``Z``, ``dZ``, ``dW``, ``db``, ``dH0``, ``grad_in``)."""
 
     def __init__(self, row_ptr, col, val, chunk_ptr, dims, W, b=None, *, variant="gcn", a=0.0,
-                 beta=None, h0=None, quant=False, level0_f32=False, f64=False):
+                 beta=None, h0=None, quant=False, level0_f32=False, f64=False, ln_gamma=None, ln_beta=None,
+                 ln_eps=1e-5):
         self.f64 = f64
         self.rt = rt = np.float64 if f64 else np.float32
         self.lib = _lib(f64)
@@ -117,7 +122,7 @@ class OracleStage:
         assert self.chunk_ptr[0] == 0 and self.chunk_ptr[-1] == n and np.all(np.diff(self.chunk_ptr) >= 0)
         self.dims = np.ascontiguousarray(dims, dtype=np.int32)
         self.L = L = self.dims.shape[0] - 1
-        self.variant = {"gcn": 0, "gcnii": 1, "sage": 2}[variant]
+        self.variant = {"gcn": 0, "gcnii": 1, "sage": 2, "resgcn": 3}[variant]
         self.a = float(a)
         self.beta = np.ascontiguousarray(beta if beta is not None else np.zeros(L), dtype=np.float64)
         assert self.beta.shape[0] == L
@@ -138,6 +143,15 @@ class OracleStage:
         self.db = [np.zeros(d[j + 1], dtype=np.float64) for j in range(L)]
         self.dH0 = np.zeros((n, d[0]), dtype=np.float64) if self.variant == 1 else None
         self.grad_in = np.zeros((n, d[0]), dtype=rt)
+        # ResGCN+: LayerNorm parameters of every layer and their gradients
+        self.ln_eps = float(ln_eps)
+        self.ln_g = [np.ascontiguousarray(ln_gamma[j] if ln_gamma is not None else np.ones(d[j]), dtype=rt) for j in range(L)]
+        self.ln_b = [np.ascontiguousarray(ln_beta[j] if ln_beta is not None else np.zeros(d[j]), dtype=rt) for j in range(L)]
+        self.d_ln_g = [np.zeros(d[j], dtype=np.float64) for j in range(L)]
+        self.d_ln_b = [np.zeros(d[j], dtype=np.float64) for j in range(L)]
+        self.fwd_pos = np.zeros(K, dtype=np.int32)
+        if self.variant == 3:
+            assert all(x == d[0] for x in d)
         self.processed = np.zeros(K, dtype=np.uint8)
         self.bprocessed = np.zeros(K, dtype=np.uint8)
         mrows = int(np.diff(self.chunk_ptr).max()) if K else 0
@@ -156,8 +170,9 @@ class OracleStage:
 
     def _refresh(self):
         """(Re)build the C struct; call after replacing any array object."""
-        self._keep = [_ptr_array(x) for x in (self.W, self.b, self.cur, self.hist, self.Z, self.dZ, self.dW, self.db)]
-        pw, pb, pc, ph, pz, pdz, pdw, pdb = self._keep
+        self._keep = [_ptr_array(x) for x in (self.W, self.b, self.cur, self.hist, self.Z, self.dZ, self.dW, self.db,
+                                              self.ln_g, self.ln_b, self.d_ln_g, self.d_ln_b)]
+        pw, pb, pc, ph, pz, pdz, pdw, pdb, plg, plb, pdlg, pdlb = self._keep
         cs = _CStage()
         cs.n = self.n
         cs.row_ptr, cs.col, cs.val = self.row_ptr.ctypes.data, self.col.ctypes.data, self.val.ctypes.data
@@ -174,6 +189,8 @@ class OracleStage:
         cs.grad_in = self.grad_in.ctypes.data
         cs.processed, cs.bprocessed = self.processed.ctypes.data, self.bprocessed.ctypes.data
         cs.g0, cs.g1 = self._g0.ctypes.data, self._g1.ctypes.data
+        cs.ln_g, cs.ln_b, cs.d_ln_g, cs.d_ln_b = vp(plg), vp(plb), vp(pdlg), vp(pdlb)
+        cs.ln_eps, cs.fwd_pos, cs.n_fwd = self.ln_eps, self.fwd_pos.ctypes.data, 0
         self._cs = cs
 
     # ---- Algorithm 1 driver pieces -------------------------------------------------
@@ -203,13 +220,15 @@ class OracleStage:
         g = np.ascontiguousarray(grad_out_rows, dtype=self.rt)
         assert g.shape == (int(self.chunk_ptr[k + 1] - self.chunk_ptr[k]), int(self.dims[-1]))
         self.lib.oracle_backward_chunk(C.byref(self._cs), int(k), g.ctypes.data, int(need_input_grad))
+        if self._bwd_done == self.K:  # ResGCN+: parameter gradients through the historical rows (no-op otherwise)
+            self.lib.oracle_backward_finish(C.byref(self._cs))
 
     def update_history(self) -> None:
         self.lib.oracle_update_history(C.byref(self._cs))
 
     # ---- conveniences ----------------------------------------------------------------
     def zero_grads(self) -> None:
-        for x in self.dW + self.db:
+        for x in self.dW + self.db + self.d_ln_g + self.d_ln_b:
             x[...] = 0
         if self.dH0 is not None:
             self.dH0[...] = 0

@@ -50,6 +50,8 @@ class Problem:
     beta: Optional[np.ndarray] = None
     quant: bool = False
     level0_f32: bool = False
+    ln_gamma: Optional[List[np.ndarray]] = None   # ResGCN+ only
+    ln_beta: Optional[List[np.ndarray]] = None
 
     @property
     def n(self):
@@ -64,7 +66,8 @@ class Problem:
                                 self.val if not f64 else edge_weights(self.w.variant, self.row_ptr, self.col, f64=True),
                                 self.chunk_ptr, self.dims, self.W, self.b,
                                 variant=self.w.variant, a=self.a, beta=self.beta, h0=self.h0,
-                                quant=self.quant and not f64, level0_f32=self.level0_f32, f64=f64)
+                                quant=self.quant and not f64, level0_f32=self.level0_f32, f64=f64,
+                                ln_gamma=self.ln_gamma, ln_beta=self.ln_beta)
         st.cur[0][...] = self.x0
         for j in range(self.L):
             st.hist[j][...] = self.hist[j]
@@ -89,13 +92,17 @@ def make_problem(w: Workload, *, graph=None, chunk_ptr=None, order=None, bias_st
     L = len(dims) - 1
     quant = w.dtype == "bf16"
     if first_stage is None:
-        first_stage = w.variant in ("gcn", "sage")
+        first_stage = w.variant in ("gcn", "sage", "resgcn")
     g = to_bf16_grid if quant else (lambda x: x)
     g0 = (lambda x: x) if (w.level0_f32 or not quant) else to_bf16_grid
     W = [g(values.glorot_uniform(w.seed, 100 + j, dims[j], dims[j + 1])) for j in range(L)]
     if w.variant == "sage":  # [W_self ; W_neigh]
         W = [np.concatenate([g(values.glorot_uniform(w.seed, 150 + j, dims[j], dims[j + 1])), W[j]], axis=0) for j in range(L)]
-    if w.variant in ("gcn", "sage"):
+    ln_gamma = ln_beta = None
+    if w.variant == "resgcn":  # LayerNorm parameters away from their trivial initial values
+        ln_gamma = [(1.0 + values.normal(w.seed, 400 + j, (dims[j],), 0.1)).astype(np.float32) for j in range(L)]
+        ln_beta = [values.normal(w.seed, 450 + j, (dims[j],), 0.1) for j in range(L)]
+    if w.variant in ("gcn", "sage", "resgcn"):
         b = [values.normal(w.seed, 200 + j, (dims[j + 1],), bias_std) if bias_std > 0
              else np.zeros(dims[j + 1], np.float32) for j in range(L)]
         x0 = g0(values.normal(w.seed, 1, (n, dims[0])))
@@ -113,7 +120,8 @@ def make_problem(w: Workload, *, graph=None, chunk_ptr=None, order=None, bias_st
     clean = None
     if history == "clean":
         clean = oracle.OracleStage(row_ptr, col, val, np.array([0, n], dtype=np.int64), dims, W, b,
-                                   variant=w.variant, a=a, beta=beta, h0=h0, quant=quant, level0_f32=w.level0_f32)
+                                   variant=w.variant, a=a, beta=beta, h0=h0, quant=quant, level0_f32=w.level0_f32,
+                                   ln_gamma=ln_gamma, ln_beta=ln_beta)
         clean.cur[0][...] = x0
         clean.forward_pass([0])
     hist = []
@@ -128,7 +136,7 @@ def make_problem(w: Workload, *, graph=None, chunk_ptr=None, order=None, bias_st
             hist.append(g0(hj) if j == 0 else g(hj))
     return Problem(w, row_ptr, col, val, np.asarray(chunk_ptr, dtype=np.int64), dims, W, b, x0, hist, grad_out,
                    np.asarray(order, dtype=np.int32), h0=h0, a=a, beta=beta, quant=quant,
-                   level0_f32=w.level0_f32 and quant)
+                   level0_f32=w.level0_f32 and quant, ln_gamma=ln_gamma, ln_beta=ln_beta)
 
 
 def run_oracle(p: Problem, need_input_grad: bool = True, f64: bool = False):

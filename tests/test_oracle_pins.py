@@ -39,9 +39,19 @@ def tiny_workload(n=41, k=3, dims=(5, 7, 6, 4), variant="gcn", seed=77):
                     gcnii_first_layer=3)
 
 
-def dense_full_graph_levels(A, x0, W, b, variant="gcn", a=0.0, beta=None, h0=None):
+def ln_relu_np(x, gamma, beta, eps=1e-5):
+    mu = x.mean(axis=1, keepdims=True)
+    var = ((x - mu) ** 2).mean(axis=1, keepdims=True)
+    return np.maximum(gamma * (x - mu) / np.sqrt(var + eps) + beta, 0.0)
+
+
+def dense_full_graph_levels(A, x0, W, b, variant="gcn", a=0.0, beta=None, h0=None, ln=None):
     levels = [x0.astype(np.float64)]
     for j in range(len(W)):
+        if variant == "resgcn":
+            r = ln_relu_np(levels[-1], ln[0][j].astype(np.float64), ln[1][j].astype(np.float64))
+            levels.append(levels[-1] + (A @ r) @ W[j].astype(np.float64) + b[j].astype(np.float64))
+            continue
         z = A @ levels[-1]
         if variant == "gcn":
             y = z @ W[j].astype(np.float64) + b[j].astype(np.float64)
@@ -55,7 +65,7 @@ def dense_full_graph_levels(A, x0, W, b, variant="gcn", a=0.0, beta=None, h0=Non
     return levels
 
 
-def torch_dense_chunked(p, A, order, x0_t, W_t, b_t, h0_t=None):
+def torch_dense_chunked(p, A, order, x0_t, W_t, b_t, h0_t=None, ln_t=None):
     """Independent dense formulation of Algorithm 1's forward for autograd: per chunk and
     layer, split the dense adjacency columns into processed / unprocessed blocks."""
     n, L, K = p.n, p.L, p.chunk_ptr.shape[0] - 1
@@ -77,12 +87,17 @@ def torch_dense_chunked(p, A, order, x0_t, W_t, b_t, h0_t=None):
             for c in range(K):
                 cols = slice(int(p.chunk_ptr[c]), int(p.chunk_ptr[c + 1]))
                 src = cur_rows[j][c] if c in done else hist[j][cols]
+                if p.w.variant == "resgcn":  # a library LayerNorm, then ReLU, on whichever row is read
+                    src = torch.relu(torch.nn.functional.layer_norm(src, (p.dims[j],), ln_t[0][j], ln_t[1][j], 1e-5))
                 z = z + A_t[rows, cols] @ src
             if p.w.variant == "gcn":
                 y = z @ W_t[j] + b_t[j]
             elif p.w.variant == "sage":
                 d = p.dims[j]
                 y = cur_rows[j][k] @ W_t[j][:d] + z @ W_t[j][d:] + b_t[j]
+            elif p.w.variant == "resgcn":
+                cur_rows[j + 1][k] = cur_rows[j][k] + z @ W_t[j] + b_t[j]
+                continue
             else:
                 pm = (1 - p.a) * z + p.a * h0_t[rows]
                 y = (1 - p.beta[j]) * pm + p.beta[j] * (pm @ W_t[j])
@@ -119,9 +134,9 @@ def test_norm_sqrt_degree_is_fixed_point():
 
 
 # ----------------------------------------------------------------------------- P1 / P2
-@pytest.mark.parametrize("variant", ["gcn", "gcnii", "sage"])
+@pytest.mark.parametrize("variant", ["gcn", "gcnii", "sage", "resgcn"])
 def test_p1_p2_one_chunk_equals_dense(variant):
-    dims = (5, 7, 6, 4) if variant != "gcnii" else (6, 6, 6, 6)
+    dims = (5, 7, 6, 4) if variant in ("gcn", "sage") else (6, 6, 6, 6)
     w = tiny_workload(k=1, dims=dims, variant=variant)
     p = make_problem(w)
     # poison the history: with one chunk it must never be read
@@ -130,7 +145,7 @@ def test_p1_p2_one_chunk_equals_dense(variant):
     st = p.new_oracle(f64=True)
     st.forward_pass([0])
     A = dense_adj(p.row_ptr, p.col, edge_weights(variant, p.row_ptr, p.col, f64=True), p.n)
-    ref = dense_full_graph_levels(A, p.x0, p.W, p.b, variant, p.a, p.beta, p.h0)
+    ref = dense_full_graph_levels(A, p.x0, p.W, p.b, variant, p.a, p.beta, p.h0, ln=(p.ln_gamma, p.ln_beta))
     for j in range(1, p.L + 1):
         assert np.allclose(st.cur[j], ref[j], rtol=1e-12, atol=1e-12), j
     # the fp32-storage build agrees to fp32 rounding
@@ -217,9 +232,9 @@ def test_p5_hand_example():
 
 
 # ----------------------------------------------------------------------------- P6
-@pytest.mark.parametrize("variant", ["gcn", "gcnii", "sage"])
+@pytest.mark.parametrize("variant", ["gcn", "gcnii", "sage", "resgcn"])
 def test_p6_backward_is_the_gradient_of_the_chunked_forward(variant):
-    dims = (4, 6, 5, 3) if variant != "gcnii" else (5, 5, 5, 5)
+    dims = (4, 6, 5, 3) if variant in ("gcn", "sage") else (5, 5, 5, 5)
     w = tiny_workload(n=29, k=4, dims=dims, variant=variant, seed=11)
     p = make_problem(w, chunk_ptr=graphs.ragged_chunks(29, 4, 3), first_stage=False, noise_std=0.3)
     st = p.new_oracle(f64=True)
@@ -234,7 +249,11 @@ def test_p6_backward_is_the_gradient_of_the_chunked_forward(variant):
     W_t = [torch.from_numpy(x.astype(np.float64)).requires_grad_(True) for x in p.W]
     b_t = [torch.from_numpy(x.astype(np.float64)).requires_grad_(True) for x in p.b]
     h0_t = None if p.h0 is None else torch.from_numpy(p.h0.astype(np.float64)).requires_grad_(True)
-    out = torch_dense_chunked(p, A, p.order, x0_t, W_t, b_t, h0_t)
+    ln_t = None
+    if variant == "resgcn":
+        ln_t = ([torch.from_numpy(x.astype(np.float64)).requires_grad_(True) for x in p.ln_gamma],
+                [torch.from_numpy(x.astype(np.float64)).requires_grad_(True) for x in p.ln_beta])
+    out = torch_dense_chunked(p, A, p.order, x0_t, W_t, b_t, h0_t, ln_t)
     assert np.allclose(out.detach().numpy(), st.cur[p.L], rtol=1e-11, atol=1e-12)
     loss = (out * torch.from_numpy(p.grad_out.astype(np.float64))).sum()
     loss.backward()
@@ -245,6 +264,10 @@ def test_p6_backward_is_the_gradient_of_the_chunked_forward(variant):
     assert np.allclose(st.grad_in, x0_t.grad.numpy(), rtol=1e-9, atol=1e-11)
     if variant == "gcnii":
         assert np.allclose(st.dH0, h0_t.grad.numpy(), rtol=1e-9, atol=1e-11)
+    if variant == "resgcn":  # LayerNorm's parameters, including what reaches them through the historical rows
+        for j in range(p.L):
+            assert np.allclose(st.d_ln_g[j], ln_t[0][j].grad.numpy(), rtol=1e-9, atol=1e-11), j
+            assert np.allclose(st.d_ln_b[j], ln_t[1][j].grad.numpy(), rtol=1e-9, atol=1e-11), j
 
     # (b) central finite differences on the oracle itself, history held constant
     def loss_of(mutate):
@@ -358,6 +381,26 @@ def test_graphsage_special_cases():
     assert np.array_equal(sc.cur[pb.L], sb.cur[pb.L]) and np.array_equal(sc.grad_in, sb.grad_in)
     for j in range(pb.L):
         assert np.array_equal(sc.dW[j][:pb.dims[j]], sb.dW[j][:pb.dims[j]])
+
+
+def test_resgcn_parameter_gradients_do_not_depend_on_asking_for_the_input_gradient():
+    """LayerNorm of layer 0 sits in front of the aggregation, so its parameters need the transposed
+    aggregation of layer 0 even when nobody wants the gradient of the stage input."""
+    w = tiny_workload(n=33, k=3, dims=(6, 6, 6), variant="resgcn", seed=9)
+    p = make_problem(w, first_stage=False, noise_std=0.3)
+    a = run_oracle(p, need_input_grad=True)
+    b = run_oracle(p, need_input_grad=False)
+    for j in range(p.L):
+        assert np.array_equal(a.d_ln_g[j], b.d_ln_g[j]) and np.array_equal(a.d_ln_b[j], b.d_ln_b[j])
+        assert np.array_equal(a.dW[j], b.dW[j]) and np.abs(a.d_ln_g[j]).max() > 0
+    assert np.abs(a.grad_in).max() > 0 and np.abs(b.grad_in).max() == 0
+    # identity-like special case: W = 0, b = 0 leaves every level equal to the input (pure residual)
+    for j in range(p.L):
+        p.W[j][...] = 0
+        p.b[j][...] = 0
+    c = run_oracle(p)
+    assert np.array_equal(c.cur[p.L], p.x0)
+    assert np.abs(c.grad_in - p.grad_out).max() <= 1e-6 * np.abs(p.grad_out).max()
 
 
 def test_transposed_index_round_trip_and_push_pull():
