@@ -44,7 +44,7 @@ enum {
   GNNSTAGE_ENOTSUP = -6  /* sizes beyond what the index packing supports */
 };
 
-enum { GNNSTAGE_GCN = 0, GNNSTAGE_GCNII = 1, GNNSTAGE_SAGE = 2 };
+enum { GNNSTAGE_GCN = 0, GNNSTAGE_GCNII = 1, GNNSTAGE_SAGE = 2, GNNSTAGE_RESGCN = 3 };
 enum { GNNSTAGE_F32 = 0, GNNSTAGE_BF16 = 1 };
 
 /*
@@ -60,6 +60,12 @@ enum { GNNSTAGE_F32 = 0, GNNSTAGE_BF16 = 1 };
  *     h'_v = ReLU(h_v W_self + z_v W_neigh + b), W[j] = [W_self ; W_neigh] stacked, 2 d_j x d_{j+1}
  *     (dW[j] likewise).  v is in the chunk being computed, so h_v is its current row.  The aggregator's
  *     weights are edge_val; edge_val == NULL means the mean aggregator, 1 / (length of row v).
+ * variant GNNSTAGE_RESGCN (the paper only cites the model; DeepGCNs' pre-activation residual block with a
+ *     GCN convolution):  r_u = ReLU(LayerNorm_j(h_u)),  z_v = sum_u A_vu r_u,  h'_v = h_v + z_v W + b.
+ *     LayerNorm over the features of one vertex, gamma * (x - mean) / sqrt(var + ln_eps) + beta with the biased
+ *     variance.  The current-vs-historical choice applies to h_u.  All widths equal (at most 1024), no fp32
+ *     level 0.  d_ln_gamma / d_ln_beta are complete after the last backward call of a pass: the normalisation
+ *     is the layer's own, so its parameters also receive gradient through the historical rows.
  *
  * dtype GNNSTAGE_F32 : levels, weights, gradients rows are fp32; fp32 arithmetic.
  * dtype GNNSTAGE_BF16: levels, weights, gradient rows are bf16 (bias and all accumulators
@@ -101,6 +107,12 @@ typedef struct {
   int32_t need_input_grad;
   void *workspace;     /* DEVICE, 256-byte aligned, >= gnnstage_workspace_size() bytes */
   size_t workspace_bytes;
+  /* GNNSTAGE_RESGCN only: HOST arrays (n_layers) of DEVICE fp32 vectors of width d_j */
+  void *const *ln_gamma;
+  void *const *ln_beta;
+  float *const *d_ln_gamma; /* "+=" over the backward calls; caller zeroes */
+  float *const *d_ln_beta;
+  float ln_eps;
 } gnnstage_desc;
 
 /* Device bytes the stage needs inside desc->workspace (graph tables, transposed index,

@@ -14,7 +14,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libgnnstage.so")
 
-GNNSTAGE_GCN, GNNSTAGE_GCNII, GNNSTAGE_SAGE = 0, 1, 2
+GNNSTAGE_GCN, GNNSTAGE_GCNII, GNNSTAGE_SAGE, GNNSTAGE_RESGCN = 0, 1, 2, 3
 GNNSTAGE_F32, GNNSTAGE_BF16 = 0, 1
 KIND_NAMES = ["spmm_fwd", "gemm_fwd", "spmm_bwd", "gemm_dgrad", "gemm_wgrad", "history_copy", "other", "spmm_reduce"]
 _ERRORS = {-1: "EINVAL", -2: "ERANGE", -3: "EORDER", -4: "ENOMEM", -5: "EHIP", -6: "ENOTSUP"}
@@ -38,6 +38,8 @@ class gnnstage_desc(C.Structure):
         ("h0", C.c_void_p), ("dW", C.c_void_p), ("dbias", C.c_void_p),
         ("grad_in", C.c_void_p), ("grad_h0", C.c_void_p), ("need_input_grad", C.c_int32),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+        ("ln_gamma", C.c_void_p), ("ln_beta", C.c_void_p), ("d_ln_gamma", C.c_void_p), ("d_ln_beta", C.c_void_p),
+        ("ln_eps", C.c_float),
     ]
 
 
@@ -266,7 +268,8 @@ class GnnStage:
 
     def __init__(self, row_ptr, col_idx, chunk_ptr, dims, *, W, cur, hist, dW, bias=None, dbias=None,
                  edge_val=None, variant=GNNSTAGE_GCN, alpha=0.0, beta=None, h0=None, grad_h0=None,
-                 dtype=GNNSTAGE_F32, level0_f32=False, grad_in=None, device="cuda:0"):
+                 dtype=GNNSTAGE_F32, level0_f32=False, grad_in=None, device="cuda:0", ln_gamma=None, ln_beta=None,
+                 d_ln_gamma=None, d_ln_beta=None, ln_eps=1e-5):
         import torch
 
         self._torch = torch
@@ -285,6 +288,8 @@ class GnnStage:
         self._keep = [_ptrs(self.W), _ptrs(self.cur), _ptrs(self.hist), _ptrs(self.dW),
                       None if self.bias is None else _ptrs(self.bias),
                       None if self.dbias is None else _ptrs(self.dbias)]
+        self.ln = [None if x is None else list(x) for x in (ln_gamma, ln_beta, d_ln_gamma, d_ln_beta)]
+        self._keep_ln = [None if x is None else _ptrs(x) for x in self.ln]
         d = gnnstage_desc()
         d.n_vertices, d.nnz = self.n, self.nnz
         d.row_ptr, d.col_idx = self.row_ptr.ctypes.data, self.col_idx.ctypes.data
@@ -301,6 +306,8 @@ class GnnStage:
         d.grad_h0 = None if grad_h0 is None else grad_h0.data_ptr()
         d.grad_in = None if grad_in is None else grad_in.data_ptr()
         d.need_input_grad = int(grad_in is not None)
+        d.ln_gamma, d.ln_beta, d.d_ln_gamma, d.d_ln_beta = (vp(x) for x in self._keep_ln)
+        d.ln_eps = float(ln_eps)
         size = int(lib.gnnstage_workspace_size(C.byref(d)))
         if size == 0:
             raise GnnStageError(-1, lib.gnnstage_last_error(None).decode())

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgnnstage.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-SOURCES = ["gnnstage.hip", "spmm.hip", "dense.hip", "gemm.hip", "misc.hip", "train.hip", "plan.cpp"]
+SOURCES = ["gnnstage.hip", "spmm.hip", "dense.hip", "gemm.hip", "misc.hip", "ln.hip", "train.hip", "plan.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed-fp32 VALU forms are switched off on purpose (build flags)
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -161,7 +161,8 @@ enum GemmEpilogue : int {
   EPI_PLAIN = 2,       // out = acc
   EPI_DGRAD_GCNII = 3, // dp = (1-beta) aux[m][n] + beta acc; out = (1-alpha) dp; h0grad[m][n] += alpha dp
   EPI_MASK = 4,        // out = aux[m][n] > 0 ? acc : 0
-  EPI_FWD_ADD = 5      // out = ReLU(acc + bias[n] + aux[m][n])   (GraphSage: aux = h_v W_self)
+  EPI_FWD_ADD = 5,     // out = ReLU(acc + bias[n] + aux[m][n])   (GraphSage: aux = h_v W_self)
+  EPI_RES = 6          // out = acc + bias[n] + aux[m][n]         (ResGCN+: aux = h_v, no activation)
 };
 
 // C[M x N] = A[M x K] . Bt[N x Kp]^T.  Bt is an internal buffer: K-contiguous rows, zero padded to Kp,
@@ -210,6 +211,21 @@ int launch_gemm_tn(const GemmTnArgs &a, int compute_dtype, hipStream_t s);
 // dst[o] += sum over the M rows of B[.][o]; partial: fp32 scratch [max_splits][O]
 int launch_colsum_add(const void *B, int dtype, int ldb, int M, int O, float *partial, int max_splits, float *dst,
                       hipStream_t s);
+
+// ---- LayerNorm + ReLU in front of the aggregation (ResGCN+ variant) -------------------------------
+constexpr int kLnMaxWidth = 1024;  // a row lives in the registers of one wavefront
+constexpr int kLnMaxWaves = 2048;  // wavefronts of one backward launch (size of the parameter-gradient scratch)
+// out[r][c] = ReLU(gamma[c] * (x[r][c] - mean_r) / sqrt(var_r + eps) + beta[c]), c < d; zeros up to out_ld
+int launch_ln_relu(const void *x, int x_dtype, int x_ld, const float *gamma, const float *beta, float eps, int64_t M, int d, void *out,
+                   int out_dtype, int out_ld, hipStream_t s);
+// Backward of the same for M rows: dr is the gradient of the activated rows.  out (may be NULL) receives the
+// gradient of x plus, when res is not NULL, the rows of res (the residual branch); dgamma / dbeta get "+=" of
+// the column sums in a fixed order (partial: fp32 scratch, kLnMaxWaves * 2 * d).
+int launch_ln_relu_backward(const void *x, int x_dtype, int x_ld, const float *gamma, const float *beta, float eps, const void *dr,
+                            int dr_dtype, int dr_ld, const void *res, int res_dtype, int res_ld, int64_t M, int d, void *out,
+                            int out_dtype, int out_ld, float *partial, float *dgamma, float *dbeta, hipStream_t s);
+// dst[r][c] = src[r][c] for c < d, zero for d <= c < dst_ld
+int launch_copy_rows(const void *src, int src_ld, void *dst, int dst_ld, int64_t M, int d, int dtype, hipStream_t s);
 
 // ---- small kernels ------------------------------------------------------------------------
 // Wt[N][Kp] (transposed) and Wn[K][Np] (plain) zero-padded copies of W[K][N] in the compute dtype

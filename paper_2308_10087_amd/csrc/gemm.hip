@@ -60,6 +60,10 @@ __device__ inline void epilogue_store(const GemmNtArgs &a, int m, int n, float a
       r = r > 0.f ? r : 0.f;
       break;
     }
+    case EPI_RES: {
+      r = acc + a.bias[n] + load_f32(a.aux, a.aux_dtype, (size_t)m * a.aux_ld + n);
+      break;
+    }
     case EPI_MASK: {
       r = load_f32(a.aux, a.aux_dtype, (size_t)m * a.aux_ld + n) > 0.f ? acc : 0.f;
       break;
@@ -136,14 +140,15 @@ __device__ inline void epilogue_store8(const GemmNtArgs &a, int m, int n0, const
       for (int t = 0; t < 8; ++t) r[t] = acc[t];
       break;
     }
-    case EPI_FWD_ADD: {
+    case EPI_FWD_ADD:
+    case EPI_RES: {
       float b8[8];
       load8_f32(a.bias, DT_F32, (size_t)n0, b8);
       load8_f32(a.aux, a.aux_dtype, (size_t)m * a.aux_ld + n0, x);
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
         const float y = acc[t] + b8[t] + x[t];
-        r[t] = y > 0.f ? y : 0.f;
+        r[t] = (a.epilogue == EPI_RES || y > 0.f) ? y : 0.f;
       }
       break;
     }
@@ -842,10 +847,10 @@ int launch_gemm_nt(const GemmNtArgs &a_in, int compute_dtype, hipStream_t s) {
   if (a_in.M <= 0 || a_in.N <= 0) return hipSuccess;
   GemmNtArgs a = a_in;
   const bool has_aux = a.epilogue == EPI_FWD_GCNII || a.epilogue == EPI_MASK || a.epilogue == EPI_DGRAD_GCNII ||
-                       a.epilogue == EPI_FWD_ADD;
+                       a.epilogue == EPI_FWD_ADD || a.epilogue == EPI_RES;
   a.vec_epi = a.N % 8 == 0 && a.out_ld % 8 == 0 && aligned16(a.out) && (a.out_pad <= a.N) &&
               (!has_aux || (a.aux_ld % 8 == 0 && aligned16(a.aux))) &&
-              ((a.epilogue != EPI_FWD_GCN && a.epilogue != EPI_FWD_ADD) || aligned16(a.bias)) &&
+              ((a.epilogue != EPI_FWD_GCN && a.epilogue != EPI_FWD_ADD && a.epilogue != EPI_RES) || aligned16(a.bias)) &&
               (a.epilogue != EPI_DGRAD_GCNII || !a.h0grad || (a.h0_ld % 4 == 0 && aligned16(a.h0grad)));
   if (compute_dtype == DT_BF16) {
     const int mt = (a.M + BM - 1) / BM, ntiles = (a.N + BN - 1) / BN;

@@ -266,6 +266,7 @@ struct Layout {
   std::vector<size_t> Z, dZ, Wt, Wn, Tc, Th;
   std::vector<size_t> Wt_self, Wn_self;  // GraphSage: staged copies of W_self (Wt / Wn then hold W_neigh)
   size_t self_fwd = 0, self_bwd = 0;      // GraphSage: h_v W_self of a chunk (fp32), dY W_self^T of a chunk
+  size_t res_dr = 0, ln_partial = 0;      // ResGCN+: gradient of the activated rows of a chunk; parameter-gradient scratch
   size_t G[2];
   size_t gemm_partial, bias_partial;
   size_t total;
@@ -280,6 +281,7 @@ struct Shape {
   int dtype = 0, level0_f32 = 0, variant = 0, need_input_grad = 0;
   bool has_bias() const { return variant != GNNSTAGE_GCNII; }
   bool sage() const { return variant == GNNSTAGE_SAGE; }
+  bool res() const { return variant == GNNSTAGE_RESGCN; }
   // elements of one weight matrix: GraphSage stacks [W_self ; W_neigh]
   size_t w_half(int j) const { return (size_t)dims[j] * dims[j + 1]; }
   int elt() const { return dtype == GNNSTAGE_BF16 ? 2 : 4; }
@@ -317,7 +319,11 @@ bool read_shape(const gnnstage_desc *d, Shape &s, std::string &err) {
   if (d->n_chunks <= 0 || d->n_chunks > kMaxChunks) { err = "n_chunks must be in [1, 256]"; return false; }
   if (d->n_layers <= 0 || d->n_layers > 1024) { err = "n_layers must be in [1, 1024]"; return false; }
   if (d->dtype != GNNSTAGE_F32 && d->dtype != GNNSTAGE_BF16) { err = "unknown dtype"; return false; }
-  if (d->variant != GNNSTAGE_GCN && d->variant != GNNSTAGE_GCNII && d->variant != GNNSTAGE_SAGE) { err = "unknown variant"; return false; }
+  if (d->variant != GNNSTAGE_GCN && d->variant != GNNSTAGE_GCNII && d->variant != GNNSTAGE_SAGE &&
+      d->variant != GNNSTAGE_RESGCN) {
+    err = "unknown variant";
+    return false;
+  }
   s.n = d->n_vertices;
   s.nnz = d->nnz;
   s.K = d->n_chunks;
@@ -340,10 +346,11 @@ bool read_shape(const gnnstage_desc *d, Shape &s, std::string &err) {
     }
     s.ld[j] = round_up(s.dims[j], 8);
   }
-  if (s.variant == GNNSTAGE_GCNII) {
+  if (s.variant == GNNSTAGE_GCNII || s.res()) {
     for (int j = 1; j <= s.L; ++j)
-      if (s.dims[j] != s.dims[0]) { err = "GCNII needs equal widths at every level"; return false; }
-    if (s.level0_f32) { err = "GCNII does not take an fp32 level 0"; return false; }
+      if (s.dims[j] != s.dims[0]) { err = "GCNII and ResGCN+ need equal widths at every level"; return false; }
+    if (s.level0_f32) { err = "GCNII and ResGCN+ do not take an fp32 level 0"; return false; }
+    if (s.res() && s.dims[0] > kLnMaxWidth) { err = "ResGCN+ rows are limited to 1024 columns"; return false; }
   }
   // Layer order.  (A_hat H) W == A_hat (H W) and the select is per edge, so a GCN layer may apply W
   // before the aggregation; that pays when it narrows the rows the gather has to move.
@@ -430,7 +437,19 @@ Layout make_layout(const Shape &s, const HostDir &hf, const HostDir &hb, bool ra
   l.Wn.resize(s.L);
   l.Tc.assign(s.L, 0);
   l.Th.assign(s.L, 0);
-  for (int j = 0; j < s.L; ++j) {
+  for (int j = 0; j < s.L && s.res(); ++j) {
+    // ResGCN+: ReLU(LayerNorm(.)) of the current and of the historical rows, the saved aggregation, and the
+    // gradient of the aggregation for ALL rows (the parameter gradient through historical rows needs it)
+    l.Tc[j] = w.take((size_t)s.n * s.ld[j] * elt);
+    l.Th[j] = w.take((size_t)s.n * s.ld[j] * elt);
+    l.Z[j] = w.take((size_t)s.n * s.ld[j] * elt);
+    l.dZ[j] = w.take((size_t)s.n * s.ld[j] * elt);
+  }
+  if (s.res()) {
+    l.res_dr = w.take((size_t)s.max_rows() * max_ld * elt);
+    l.ln_partial = w.take(sizeof(float) * (size_t)kLnMaxWaves * 2 * max_d);
+  }
+  for (int j = 0; j < s.L && !s.res(); ++j) {
     if (s.tf[j]) {
       // transform-first layer: transformed current / historical rows, and the masked upstream gradient
       l.Z[j] = 0;
@@ -518,6 +537,9 @@ struct gnnstage {
   std::vector<void *> W, bias, cur, hist;
   std::vector<float *> dW, dbias;
   const void *h0 = nullptr;
+  std::vector<const float *> ln_g, ln_b;  // ResGCN+: LayerNorm parameters and their gradients
+  std::vector<float *> d_ln_g, d_ln_b;
+  float ln_eps = 1e-5f;
   void *grad_in = nullptr;
   float *grad_h0 = nullptr;
   char *ws = nullptr;
@@ -798,6 +820,209 @@ int finish_transform_first(gnnstage *st, hipStream_t stream) {
   return GNNSTAGE_OK;
 }
 
+// ---- ResGCN+ (LayerNorm -> ReLU -> GCN convolution, plus the residual) ------------------------------------
+// Layer j: r_u = ReLU(LayerNorm_j(h_u)) on whichever row of u is read (current or historical),
+// z_v = sum_u A_vu r_u, h'_v = h_v + z_v W_j + b_j.  The activated rows are tables: Rh = f(hist[j]) once per
+// pass, Rc[C_k] = f(cur[j][C_k]) when the chunk is computed.
+int res_pass_start(gnnstage *st, hipStream_t stream) {
+  const Shape &s = st->s;
+  const int cd = st->cdtype();
+  for (int j = 0; j < s.L; ++j) {
+    Timed t(st, stream, 1, j);
+    HIP_TRY(st, launch_ln_relu(st->hist[j], st->level_dtype(j), s.dims[j], st->ln_g[j], st->ln_b[j], st->ln_eps, s.n, s.dims[j],
+                               st->at<char>(st->lay.Th[j]), cd, s.ld[j], stream));
+  }
+  return GNNSTAGE_OK;
+}
+
+int res_forward_chunk(gnnstage *st, int k, hipStream_t stream) {
+  const Shape &s = st->s;
+  const int cd = st->cdtype();
+  const size_t celt = s.elt();
+  const int64_t row0 = s.chunk_ptr[k], M = s.chunk_ptr[k + 1] - row0;
+  for (int j = 0; j < s.L; ++j) {
+    const bool shared = st->hist[j] == st->cur[j];  // the level never changes: one activated table serves both
+    char *Rh = st->at<char>(st->lay.Th[j]);
+    char *Rc = shared ? Rh : st->at<char>(st->lay.Tc[j]);
+    const char *xrows = static_cast<const char *>(st->cur[j]) + (size_t)row0 * s.dims[j] * st->level_elt(j);
+    if (!shared) {
+      Timed t(st, stream, 1, j);
+      HIP_TRY(st, launch_ln_relu(xrows, st->level_dtype(j), s.dims[j], st->ln_g[j], st->ln_b[j], st->ln_eps, M, s.dims[j],
+                                 Rc + (size_t)row0 * s.ld[j] * celt, cd, s.ld[j], stream));
+    }
+    char *Zj = st->at<char>(st->lay.Z[j]);
+    {
+      SpmmArgs a = base_spmm(st, false, k);
+      a.src_sel = Rc;
+      a.src_unsel = Rh;
+      a.d = s.dims[j];
+      a.src_ld = s.ld[j];
+      a.out = Zj;
+      a.out_ld = s.ld[j];
+      a.out_row0 = 0;
+      a.epilogue = SPMM_PLAIN;
+      HIP_TRY(st, run_spmm(st, a, false, k, cd, cd, stream, 0, j));
+    }
+    {
+      Timed t(st, stream, 1, j);
+      GemmNtArgs g{};
+      g.A = Zj + (size_t)row0 * s.ld[j] * celt;
+      g.a_dtype = cd;
+      g.lda = s.ld[j];
+      g.Bt = st->at<char>(st->lay.Wt[j]);
+      g.ldb = s.ld[j];
+      g.M = (int)M;
+      g.N = s.dims[j + 1];
+      g.K = s.dims[j];
+      g.Kp = s.ld[j];
+      g.epilogue = EPI_RES;
+      g.bias = static_cast<const float *>(st->bias[j]);
+      g.aux = xrows;
+      g.aux_dtype = st->level_dtype(j);
+      g.aux_ld = s.dims[j];
+      g.out = static_cast<char *>(st->cur[j + 1]) + (size_t)row0 * s.dims[j + 1] * celt;
+      g.out_dtype = cd;
+      g.out_ld = s.dims[j + 1];
+      HIP_TRY(st, launch_gemm_nt(g, cd, stream));
+    }
+  }
+  return GNNSTAGE_OK;
+}
+
+// After the last backward chunk: the LayerNorm of layer j was also applied to the historical rows, so its
+// parameters receive gradient through every edge whose reader saw the historical row of u: the readers whose
+// chunk came before u's chunk in the forward order.
+int res_backward_finish(gnnstage *st, hipStream_t stream) {
+  const Shape &s = st->s;
+  const int cd = st->cdtype();
+  const size_t celt = s.elt();
+  char *dR = st->at<char>(st->lay.res_dr);
+  ChunkMask earlier{};  // chunks in front of the current one, grown along the forward order
+  for (size_t pos = 0; pos < st->order.size(); ++pos) {
+    const int c = st->order[pos];
+    const int64_t row0 = s.chunk_ptr[c], M = s.chunk_ptr[c + 1] - row0;
+    if (pos > 0 && M > 0) {
+      for (int j = 0; j < s.L; ++j) {
+        SpmmArgs a = base_spmm(st, true, c);
+        a.mask = earlier;
+        assign_xcds(st, st->btasks[c], earlier, true, a);
+        a.src_sel = st->at<char>(st->lay.dZ[j]);
+        a.src_unsel = nullptr;
+        a.d = s.dims[j];
+        a.src_ld = s.ld[j];
+        a.out = dR;
+        a.out_ld = s.ld[j];
+        a.out_row0 = row0;
+        a.epilogue = SPMM_PLAIN;
+        HIP_TRY(st, run_spmm(st, a, true, c, cd, cd, stream, 2, j));
+        Timed t(st, stream, 4, j);
+        const char *xrows = static_cast<const char *>(st->hist[j]) + (size_t)row0 * s.dims[j] * st->level_elt(j);
+        HIP_TRY(st, launch_ln_relu_backward(xrows, st->level_dtype(j), s.dims[j], st->ln_g[j], st->ln_b[j], st->ln_eps, dR, cd, s.ld[j],
+                                            nullptr, cd, 0, M, s.dims[j], nullptr, cd, 0, st->at<float>(st->lay.ln_partial),
+                                            st->d_ln_g[j], st->d_ln_b[j], stream));
+      }
+    }
+    mask_set(earlier, c);
+  }
+  return GNNSTAGE_OK;
+}
+
+int res_backward_chunk(gnnstage *st, int k, const void *grad_out_rows, hipStream_t stream) {
+  const Shape &s = st->s;
+  const int cd = st->cdtype();
+  const size_t celt = s.elt();
+  const int64_t row0 = s.chunk_ptr[k], M = s.chunk_ptr[k + 1] - row0;
+  char *G[2] = {st->at<char>(st->lay.G[0]), st->at<char>(st->lay.G[1])};
+  char *dR = st->at<char>(st->lay.res_dr);
+  float *gemm_partial = st->at<float>(st->lay.gemm_partial);
+  float *bias_partial = st->at<float>(st->lay.bias_partial);
+  int gi = 0;
+  if (M > 0) {
+    Timed t(st, stream, 6);  // no activation after the convolution: dY of the top layer is the upstream gradient
+    HIP_TRY(st, launch_copy_rows(grad_out_rows, s.dims[s.L], G[gi], s.ld[s.L], M, s.dims[s.L], cd, stream));
+  }
+  for (int j = s.L - 1; j >= 0 && M > 0; --j) {
+    const char *dY = G[gi];
+    const bool fuse_bias = cd == DT_BF16;
+    if (!fuse_bias) {
+      Timed t(st, stream, 4, j);
+      HIP_TRY(st, launch_colsum_add(dY, cd, s.ld[j + 1], (int)M, s.dims[j + 1], bias_partial, kMaxSplits, st->dbias[j], stream));
+    }
+    {
+      Timed t(st, stream, 4, j);
+      GemmTnArgs w{};
+      w.A = st->at<char>(st->lay.Z[j]) + (size_t)row0 * s.ld[j] * celt;
+      w.a_dtype = cd;
+      w.lda = s.ld[j];
+      w.B = dY;
+      w.ldb = s.ld[j + 1];
+      w.M = (int)M;
+      w.I = s.dims[j];
+      w.O = s.dims[j + 1];
+      w.scale = 1.f;
+      w.dW = st->dW[j];
+      w.partial = gemm_partial;
+      w.max_splits = kMaxSplits;
+      if (fuse_bias) {
+        w.dbias = st->dbias[j];
+        w.bias_partial = bias_partial;
+      }
+      HIP_TRY(st, launch_gemm_tn(w, cd, stream));
+    }
+    char *dZj = st->at<char>(st->lay.dZ[j]);
+    {
+      Timed t(st, stream, 3, j);
+      GemmNtArgs g{};
+      g.A = dY;
+      g.a_dtype = cd;
+      g.lda = s.ld[j + 1];
+      g.Bt = st->at<char>(st->lay.Wn[j]);
+      g.ldb = s.ld[j + 1];
+      g.M = (int)M;
+      g.N = s.dims[j];
+      g.K = s.dims[j + 1];
+      g.Kp = s.ld[j + 1];
+      g.epilogue = EPI_PLAIN;
+      g.out = dZj + (size_t)row0 * s.ld[j] * celt;
+      g.out_dtype = cd;
+      g.out_ld = s.ld[j];
+      HIP_TRY(st, launch_gemm_nt(g, cd, stream));
+    }
+    {
+      SpmmArgs a = base_spmm(st, true, k);
+      a.src_sel = dZj;
+      a.src_unsel = nullptr;  // Section 3.4: nothing flows back from unprocessed vertices
+      a.d = s.dims[j];
+      a.src_ld = s.ld[j];
+      a.out = dR;
+      a.out_ld = s.ld[j];
+      a.out_row0 = row0;
+      a.epilogue = SPMM_PLAIN;
+      HIP_TRY(st, run_spmm(st, a, true, k, cd, cd, stream, 2, j));
+    }
+    {
+      // back through ReLU and LayerNorm of the chunk's own (current) rows, plus the residual branch
+      Timed t(st, stream, 4, j);
+      const char *xrows = static_cast<const char *>(st->cur[j]) + (size_t)row0 * s.dims[j] * st->level_elt(j);
+      void *out = nullptr;
+      int out_ld = 0;
+      if (j > 0) {
+        out = G[gi ^ 1];
+        out_ld = s.ld[j];
+      } else if (s.need_input_grad) {
+        out = static_cast<char *>(st->grad_in) + (size_t)row0 * s.dims[0] * st->level_elt(0);
+        out_ld = s.dims[0];
+      }
+      HIP_TRY(st, launch_ln_relu_backward(xrows, st->level_dtype(j), s.dims[j], st->ln_g[j], st->ln_b[j], st->ln_eps, dR, cd, s.ld[j], dY,
+                                          cd, s.ld[j + 1], M, s.dims[j], out, st->level_dtype(j), out_ld,
+                                          st->at<float>(st->lay.ln_partial), st->d_ln_g[j], st->d_ln_b[j], stream));
+    }
+    gi ^= 1;
+  }
+  if (st->n_bwd == s.K) return res_backward_finish(st, stream);
+  return GNNSTAGE_OK;
+}
+
 }  // namespace
 
 extern "C" int gnnstage_version(void) { return 100; }
@@ -893,6 +1118,14 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
   if (!d->dW) return fail(nullptr, GNNSTAGE_EINVAL, "dW must not be NULL");
   if (s.has_bias() && (!d->bias || !d->dbias)) return fail(nullptr, GNNSTAGE_EINVAL, "GCN and GraphSage need bias and dbias");
   if (s.variant == GNNSTAGE_GCNII && (!d->beta || !d->h0)) return fail(nullptr, GNNSTAGE_EINVAL, "GCNII needs beta and h0");
+  if (s.res()) {
+    if (!d->ln_gamma || !d->ln_beta || !d->d_ln_gamma || !d->d_ln_beta)
+      return fail(nullptr, GNNSTAGE_EINVAL, "ResGCN+ needs ln_gamma, ln_beta and their gradient arrays");
+    for (int j = 0; j < s.L; ++j)
+      if (!d->ln_gamma[j] || !d->ln_beta[j] || !d->d_ln_gamma[j] || !d->d_ln_beta[j])
+        return fail(nullptr, GNNSTAGE_EINVAL, "a LayerNorm parameter pointer is NULL");
+    if (!(d->ln_eps > 0.f)) return fail(nullptr, GNNSTAGE_EINVAL, "ln_eps must be positive");
+  }
   if (s.need_input_grad && !d->grad_in) return fail(nullptr, GNNSTAGE_EINVAL, "need_input_grad set but grad_in is NULL");
   if (!d->workspace || (reinterpret_cast<uintptr_t>(d->workspace) & (kAlign - 1)))
     return fail(nullptr, GNNSTAGE_EINVAL, "workspace must be a 256-byte aligned device pointer");
@@ -934,6 +1167,15 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
   st->lay = lay;
   st->vbits = vbits;
   st->alpha = d->alpha;
+  if (s.res()) {
+    for (int j = 0; j < s.L; ++j) {
+      st->ln_g.push_back(static_cast<const float *>(d->ln_gamma[j]));
+      st->ln_b.push_back(static_cast<const float *>(d->ln_beta[j]));
+      st->d_ln_g.push_back(d->d_ln_gamma[j]);
+      st->d_ln_b.push_back(d->d_ln_beta[j]);
+    }
+    st->ln_eps = d->ln_eps;
+  }
   if (d->beta) st->beta.assign(d->beta, d->beta + s.L); else st->beta.assign(s.L, 0.f);
   st->W.assign(d->W, d->W + s.L);
   st->cur.assign(d->cur, d->cur + s.L + 1);
@@ -1220,6 +1462,10 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
                                            st->at<char>(st->lay.Wn_self[j]), s.ld[j + 1], stream));
       }
     }
+    if (s.res()) {
+      const int rc = res_pass_start(st, stream);
+      if (rc != GNNSTAGE_OK) return rc;
+    }
     // transform-first layers: the historical rows are constants of the pass, transform them once
     for (int j = 0; j < s.L; ++j) {
       if (!s.tf[j]) continue;
@@ -1248,6 +1494,7 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
 
   const int64_t row0 = s.chunk_ptr[k], M = s.chunk_ptr[k + 1] - row0;
   if (M == 0) return GNNSTAGE_OK;
+  if (s.res()) return res_forward_chunk(st, k, stream);
   for (int j = 0; j < s.L; ++j) {
     if (s.tf[j]) {
       // transform the chunk's current rows, then aggregate transformed rows (current or historical)
@@ -1373,6 +1620,7 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
   if (M > 0 && !grad_out_rows) return fail(st, GNNSTAGE_EINVAL, "grad_out_rows is NULL");
   st->n_bwd += 1;
   mask_set(st->bmask, k);
+  if (s.res()) return res_backward_chunk(st, k, grad_out_rows, stream);
   if (M == 0) return GNNSTAGE_OK;
 
   const int cd = st->cdtype();

@@ -1,0 +1,216 @@
+// Row-wise LayerNorm + ReLU in front of the aggregation (ResGCN+ variant), its backward, and a row copy
+// with padding.  One wavefront per vertex row; rows are strided over the launched wavefronts.
+//
+// LayerNorm over the d features of one vertex: y = gamma * (x - mean) / sqrt(var + eps) + beta with the
+// biased variance; the layer's input to the aggregation is r = ReLU(y).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+
+#include "common.h"
+
+namespace {
+
+__device__ inline float ld_elt(const void *p, int dtype, size_t i) {
+  return dtype == DT_BF16 ? (float)static_cast<const bf16_t *>(p)[i] : static_cast<const float *>(p)[i];
+}
+__device__ inline void st_elt(void *p, int dtype, size_t i, float v) {
+  if (dtype == DT_BF16)
+    static_cast<bf16_t *>(p)[i] = (bf16_t)v;
+  else
+    static_cast<float *>(p)[i] = v;
+}
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// NI = columns per lane (lane, lane + 64, ...): the row lives in registers between the passes
+template <int NI>
+__global__ __launch_bounds__(256) void ln_relu_kernel(const void *x, int x_dtype, int x_ld, const float *gamma, const float *beta,
+                                                      float eps, int64_t M, int d, void *out, int out_dtype, int out_ld) {
+  const int lane = threadIdx.x & 63;
+  const int64_t w0 = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6), nw = (int64_t)gridDim.x * 4;
+  for (int64_t r = w0; r < M; r += nw) {
+    float v[NI];
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int c = lane + 64 * i;
+      v[i] = c < d ? ld_elt(x, x_dtype, (size_t)r * x_ld + c) : 0.f;
+      sum += v[i];
+    }
+    const float mean = wave_sum(sum) / (float)d;
+    float sq = 0.f;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int c = lane + 64 * i;
+      const float t = c < d ? v[i] - mean : 0.f;
+      sq += t * t;
+    }
+    const float rstd = 1.f / sqrtf(wave_sum(sq) / (float)d + eps);
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int c = lane + 64 * i;
+      if (c < out_ld) {
+        float y = 0.f;
+        if (c < d) {
+          y = gamma[c] * ((v[i] - mean) * rstd) + beta[c];
+          y = y > 0.f ? y : 0.f;
+        }
+        st_elt(out, out_dtype, (size_t)r * out_ld + c, y);
+      }
+    }
+  }
+}
+
+// dr -> dx (+ res) for the rows of the launch; per-wavefront column sums of the parameter gradients go to
+// partial[wave][0][c] (gamma) and partial[wave][1][c] (beta), added up in wave order by ln_param_reduce_kernel.
+template <int NI>
+__global__ __launch_bounds__(256) void ln_relu_backward_kernel(const void *x, int x_dtype, int x_ld, const float *gamma,
+                                                               const float *beta, float eps, const void *dr, int dr_dtype, int dr_ld,
+                                                               const void *res, int res_dtype, int res_ld, int64_t M, int d,
+                                                               void *out, int out_dtype, int out_ld, float *partial) {
+  const int lane = threadIdx.x & 63;
+  const int64_t w0 = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6), nw = (int64_t)gridDim.x * 4;
+  float dg[NI], db[NI], gam[NI], bet[NI];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int c = lane + 64 * i;
+    dg[i] = db[i] = 0.f;
+    gam[i] = c < d ? gamma[c] : 0.f;
+    bet[i] = c < d ? beta[c] : 0.f;
+  }
+  for (int64_t r = w0; r < M; r += nw) {
+    float xh[NI], dxh[NI];
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int c = lane + 64 * i;
+      xh[i] = c < d ? ld_elt(x, x_dtype, (size_t)r * x_ld + c) : 0.f;
+      sum += xh[i];
+    }
+    const float mean = wave_sum(sum) / (float)d;
+    float sq = 0.f;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int c = lane + 64 * i;
+      xh[i] = c < d ? xh[i] - mean : 0.f;
+      sq += xh[i] * xh[i];
+    }
+    const float rstd = 1.f / sqrtf(wave_sum(sq) / (float)d + eps);
+    float m1 = 0.f, m2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int c = lane + 64 * i;
+      xh[i] *= rstd;
+      float dn = 0.f;
+      if (c < d) {
+        const float y = gam[i] * xh[i] + bet[i];
+        dn = y > 0.f ? ld_elt(dr, dr_dtype, (size_t)r * dr_ld + c) : 0.f;  // ReLU derivative, strict
+      }
+      dg[i] += dn * xh[i];
+      db[i] += dn;
+      dxh[i] = dn * gam[i];
+      m1 += dxh[i];
+      m2 += dxh[i] * xh[i];
+    }
+    m1 = wave_sum(m1) / (float)d;
+    m2 = wave_sum(m2) / (float)d;
+    if (out != nullptr) {
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        const int c = lane + 64 * i;
+        if (c < out_ld) {
+          float v = 0.f;
+          if (c < d) {
+            v = rstd * (dxh[i] - m1 - xh[i] * m2);
+            if (res != nullptr) v += ld_elt(res, res_dtype, (size_t)r * res_ld + c);
+          }
+          st_elt(out, out_dtype, (size_t)r * out_ld + c, v);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int c = lane + 64 * i;
+    if (c < d) {
+      partial[((size_t)w0 * 2 + 0) * d + c] = dg[i];
+      partial[((size_t)w0 * 2 + 1) * d + c] = db[i];
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void ln_param_reduce_kernel(const float *partial, int n_waves, int d, float *dgamma, float *dbeta) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= 2 * d) return;
+  const int which = idx / d, c = idx % d;
+  float s = 0.f;
+  for (int w = 0; w < n_waves; ++w) s += partial[((size_t)w * 2 + which) * d + c];
+  float *dst = which == 0 ? dgamma : dbeta;
+  dst[c] += s;
+}
+
+__global__ __launch_bounds__(256) void copy_rows_kernel(const void *src, int src_ld, void *dst, int dst_ld, int64_t M, int d, int dtype) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= M * dst_ld) return;
+  const int64_t r = idx / dst_ld;
+  const int c = (int)(idx % dst_ld);
+  st_elt(dst, dtype, (size_t)idx, c < d ? ld_elt(src, dtype, (size_t)r * src_ld + c) : 0.f);
+}
+
+int waves_for(int64_t M, int max_waves) {
+  int64_t w = (M + 3) / 4 * 4;  // whole workgroups
+  if (w > max_waves) w = max_waves / 4 * 4;
+  if (w < 4) w = 4;
+  return (int)w;
+}
+
+}  // namespace
+
+int launch_ln_relu(const void *x, int x_dtype, int x_ld, const float *gamma, const float *beta, float eps, int64_t M, int d, void *out,
+                   int out_dtype, int out_ld, hipStream_t s) {
+  if (M <= 0) return hipSuccess;
+  if (d > kLnMaxWidth || out_ld > kLnMaxWidth) return hipErrorInvalidValue;
+  const int ni = (std::max(d, out_ld) + 63) / 64;
+  dim3 grid((unsigned)(waves_for(M, 16384) / 4));
+#define LN_FWD(NI) hipLaunchKernelGGL(ln_relu_kernel<NI>, grid, dim3(256), 0, s, x, x_dtype, x_ld, gamma, beta, eps, M, d, out, out_dtype, out_ld)
+  if (ni <= 1) LN_FWD(1);
+  else if (ni <= 2) LN_FWD(2);
+  else if (ni <= 4) LN_FWD(4);
+  else if (ni <= 8) LN_FWD(8);
+  else LN_FWD(16);
+#undef LN_FWD
+  return (int)hipGetLastError();
+}
+
+int launch_ln_relu_backward(const void *x, int x_dtype, int x_ld, const float *gamma, const float *beta, float eps, const void *dr,
+                            int dr_dtype, int dr_ld, const void *res, int res_dtype, int res_ld, int64_t M, int d, void *out,
+                            int out_dtype, int out_ld, float *partial, float *dgamma, float *dbeta, hipStream_t s) {
+  if (M <= 0) return hipSuccess;
+  if (d > kLnMaxWidth || (out && out_ld > kLnMaxWidth)) return hipErrorInvalidValue;
+  const int ni = (std::max(d, out ? out_ld : d) + 63) / 64;
+  const int waves = waves_for(M, kLnMaxWaves);
+  dim3 grid((unsigned)(waves / 4));
+#define LN_BWD(NI)                                                                                                              \
+  hipLaunchKernelGGL(ln_relu_backward_kernel<NI>, grid, dim3(256), 0, s, x, x_dtype, x_ld, gamma, beta, eps, dr, dr_dtype, dr_ld, res, \
+                     res_dtype, res_ld, M, d, out, out_dtype, out_ld, partial)
+  if (ni <= 1) LN_BWD(1);
+  else if (ni <= 2) LN_BWD(2);
+  else if (ni <= 4) LN_BWD(4);
+  else if (ni <= 8) LN_BWD(8);
+  else LN_BWD(16);
+#undef LN_BWD
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return (int)e;
+  hipLaunchKernelGGL(ln_param_reduce_kernel, dim3((unsigned)((2 * d + 255) / 256)), dim3(256), 0, s, partial, waves, d, dgamma, dbeta);
+  return (int)hipGetLastError();
+}
+
+int launch_copy_rows(const void *src, int src_ld, void *dst, int dst_ld, int64_t M, int d, int dtype, hipStream_t s) {
+  if (M <= 0) return hipSuccess;
+  hipLaunchKernelGGL(copy_rows_kernel, dim3((unsigned)((M * dst_ld + 255) / 256)), dim3(256), 0, s, src, src_ld, dst, dst_ld, M, d, dtype);
+  return (int)hipGetLastError();
+}

@@ -21,7 +21,12 @@ class GpuRun:
         L, n = p.L, p.n
         self.sdt, self.l0 = sdt, l0
         self.W = [_dev(p.W[j], sdt, device) for j in range(L)]
-        gcn = p.w.variant in ("gcn", "sage")   # layers with a bias vector
+        gcn = p.w.variant in ("gcn", "sage", "resgcn")   # layers with a bias vector
+        res = p.w.variant == "resgcn"
+        self.ln_gamma = [_dev(x, torch.float32, device) for x in p.ln_gamma] if res else None
+        self.ln_beta = [_dev(x, torch.float32, device) for x in p.ln_beta] if res else None
+        self.d_ln_gamma = [torch.zeros(p.dims[j], dtype=torch.float32, device=device) for j in range(L)] if res else None
+        self.d_ln_beta = [torch.zeros(p.dims[j], dtype=torch.float32, device=device) for j in range(L)] if res else None
         self.bias = [_dev(p.b[j], torch.float32, device) for j in range(L)] if gcn else None
         self.cur = [_dev(p.x0, l0, device)] + [torch.zeros((n, p.dims[j]), dtype=sdt, device=device) for j in range(1, L + 1)]
         self.hist = [_dev(p.hist[j], l0 if j == 0 else sdt, device) for j in range(L)]
@@ -36,7 +41,9 @@ class GpuRun:
         self.stage = g.GnnStage(
             p.row_ptr, p.col, p.chunk_ptr, p.dims, W=self.W, cur=self.cur, hist=self.hist, dW=self.dW,
             bias=self.bias, dbias=self.dbias, edge_val=(p.val if edge_val == "given" else None),
-            variant={"gcn": g.GNNSTAGE_GCN, "gcnii": g.GNNSTAGE_GCNII, "sage": g.GNNSTAGE_SAGE}[p.w.variant], alpha=p.a,
+            variant={"gcn": g.GNNSTAGE_GCN, "gcnii": g.GNNSTAGE_GCNII, "sage": g.GNNSTAGE_SAGE,
+                     "resgcn": g.GNNSTAGE_RESGCN}[p.w.variant], alpha=p.a,
+            ln_gamma=self.ln_gamma, ln_beta=self.ln_beta, d_ln_gamma=self.d_ln_gamma, d_ln_beta=self.d_ln_beta,
             beta=None if gcn else p.beta.astype(np.float32), h0=self.h0, grad_h0=self.grad_h0,
             dtype=g.GNNSTAGE_BF16 if bf else g.GNNSTAGE_F32, level0_f32=p.level0_f32, grad_in=self.grad_in,
             device=device)

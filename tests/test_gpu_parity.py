@@ -63,8 +63,11 @@ def _compare(run, ref, p, tol, need_input_grad=True):
         worst[f"level{j}"] = max_rel(run.np(run.cur[j]), ref.cur[j])
     for j in range(p.L):
         worst[f"dW{j}"] = max_rel(run.np(run.dW[j]), ref.dW[j])
-        if p.w.variant in ("gcn", "sage"):
+        if p.w.variant in ("gcn", "sage", "resgcn"):
             worst[f"db{j}"] = max_rel(run.np(run.dbias[j]), ref.db[j])
+        if p.w.variant == "resgcn":
+            worst[f"dgamma{j}"] = max_rel(run.np(run.d_ln_gamma[j]), ref.d_ln_g[j])
+            worst[f"dbeta{j}"] = max_rel(run.np(run.d_ln_beta[j]), ref.d_ln_b[j])
     if need_input_grad:
         worst["grad_in"] = max_rel(run.np(run.grad_in), ref.grad_in)
     if p.w.variant == "gcnii":
@@ -468,6 +471,33 @@ def test_sage_bf16_dense_blocks(monkeypatch):
     monkeypatch.setenv("GNNSTAGE_DENSE_MIN_NNZ", "64")
     monkeypatch.setenv("GNNSTAGE_DENSE_MIN_SHARE", "0.05")
     w = Workload("sage_d", "rmat", 6007, 2308100891, [128, 128, 128], 4, variant="sage", dtype="bf16", n_candidates=260_000)
+    p = make_problem(w, first_stage=False)
+    probe = _gpu(p)
+    assert probe.stage.gnnstage_dense_entries(False) > 0 and probe.stage.gnnstage_dense_entries(True) > 0
+    _parity(p, TOL_BF16)
+
+
+# ----------------------------------------------------------------------------- ResGCN+ variant
+@pytest.mark.parametrize("d,L", [(24, 3), (7, 2), (64, 4), (200, 2)])
+def test_resgcn_fp32(d, L):
+    w = small(dims=(d,) * (L + 1), n=911, k=6, variant="resgcn")
+    _parity(make_problem(w, chunk_ptr=graphs.ragged_chunks(911, 6, 4)), TOL_F32)
+    _parity(make_problem(w, first_stage=False, noise_std=0.3), TOL_F32)
+    _parity(make_problem(w, first_stage=False, noise_std=0.3), TOL_F32, need_input_grad=False)
+
+
+@pytest.mark.parametrize("d,L", [(128, 3), (256, 2), (72, 4)])
+def test_resgcn_bf16(d, L):
+    w = Workload("res_s", "rmat", 5003, 2308100892, [d] * (L + 1), 6, variant="resgcn", dtype="bf16", n_candidates=60_000)
+    _parity(make_problem(w, first_stage=False), TOL_BF16)
+    _parity(make_problem(w), TOL_BF16)
+
+
+def test_resgcn_bf16_dense_blocks(monkeypatch):
+    monkeypatch.setenv("GNNSTAGE_DENSE_MIN_ENTRIES", "0")
+    monkeypatch.setenv("GNNSTAGE_DENSE_MIN_NNZ", "64")
+    monkeypatch.setenv("GNNSTAGE_DENSE_MIN_SHARE", "0.05")
+    w = Workload("res_d", "rmat", 6007, 2308100893, [128, 128, 128], 4, variant="resgcn", dtype="bf16", n_candidates=260_000)
     p = make_problem(w, first_stage=False)
     probe = _gpu(p)
     assert probe.stage.gnnstage_dense_entries(False) > 0 and probe.stage.gnnstage_dense_entries(True) > 0
