@@ -126,10 +126,17 @@ class OracleTrainer:
             for j in range(st.L):
                 self.master.append(np.array(st.W[j], dtype=np.float64))
                 self._targets.append((si, "W", j))
-            if st.variant == 0:
+            if st.variant != 1:  # every variant but GCNII has a bias vector per layer
                 for j in range(st.L):
                     self.master.append(np.array(st.b[j], dtype=np.float64))
                     self._targets.append((si, "b", j))
+            if st.variant == 3:  # ResGCN+: LayerNorm scale and shift of every layer
+                for j in range(st.L):
+                    self.master.append(np.array(st.ln_g[j], dtype=np.float64))
+                    self._targets.append((si, "ln_g", j))
+                for j in range(st.L):
+                    self.master.append(np.array(st.ln_b[j], dtype=np.float64))
+                    self._targets.append((si, "ln_b", j))
         self.master.append(np.array(head_W, dtype=np.float64))
         self._targets.append((None, "W", 0))
         self.master.append(np.array(head_b, dtype=np.float64))
@@ -154,7 +161,7 @@ class OracleTrainer:
                     self.head_b[...] = x
             else:
                 st = self.stages[si]
-                (st.W if kind == "W" else st.b)[j][...] = w.astype(st.rt)
+                {"W": st.W, "b": st.b, "ln_g": st.ln_g, "ln_b": st.ln_b}[kind][j][...] = w.astype(st.rt)
 
     def grads(self) -> List[np.ndarray]:
         out = []
@@ -163,7 +170,7 @@ class OracleTrainer:
                 out.append(self.head_dW if kind == "W" else self.head_db)
             else:
                 st = self.stages[si]
-                out.append((st.dW if kind == "W" else st.db)[j])
+                out.append({"W": st.dW, "b": st.db, "ln_g": st.d_ln_g, "ln_b": st.d_ln_b}[kind][j])
         return out
 
     def rows(self, k: int) -> slice:

@@ -81,7 +81,9 @@ class GpuTrainRun:
         for si, dims in enumerate(tp.stage_dims):
             L = len(dims) - 1
             first = si == 0
-            l0 = torch.float32 if (first and bf) else sdt
+            var = tp.variant(si)
+            res = var == "resgcn"
+            l0 = torch.float32 if (first and bf and not res) else sdt
             master_W = [_dev(tp.W[si][j], torch.float32, device) for j in range(L)]
             W = [m.to(sdt) for m in master_W] if bf else master_W
             bias = [_dev(tp.b[si][j], torch.float32, device) for j in range(L)]
@@ -89,17 +91,28 @@ class GpuTrainRun:
             cur = [level0] + [torch.zeros((n, dims[j]), dtype=sdt, device=device) for j in range(1, L + 1)]
             hist = [cur[0] if first else torch.zeros((n, dims[0]), dtype=sdt, device=device)] + \
                    [torch.zeros((n, dims[j]), dtype=sdt, device=device) for j in range(1, L)]
-            dW = [torch.zeros((dims[j], dims[j + 1]), dtype=torch.float32, device=device) for j in range(L)]
+            dW = [torch.zeros(tuple(tp.W[si][j].shape), dtype=torch.float32, device=device) for j in range(L)]
             dbias = [torch.zeros(dims[j + 1], dtype=torch.float32, device=device) for j in range(L)]
             grad_in = None if first else torch.zeros((n, dims[0]), dtype=sdt, device=device)
+            ln_g = [_dev(x, torch.float32, device) for x in tp.ln_gamma[si]] if res else None
+            ln_b = [_dev(x, torch.float32, device) for x in tp.ln_beta[si]] if res else None
+            d_ln_g = [torch.zeros(dims[j], dtype=torch.float32, device=device) for j in range(L)] if res else None
+            d_ln_b = [torch.zeros(dims[j], dtype=torch.float32, device=device) for j in range(L)] if res else None
             st = g.GnnStage(tp.row_ptr, tp.col, tp.chunk_ptr, dims, W=W, cur=cur, hist=hist, dW=dW, bias=bias, dbias=dbias,
-                            edge_val=tp.val, dtype=g.GNNSTAGE_BF16 if bf else g.GNNSTAGE_F32, level0_f32=first and bf,
-                            grad_in=grad_in, device=device)
+                            edge_val=tp.val, dtype=g.GNNSTAGE_BF16 if bf else g.GNNSTAGE_F32,
+                            level0_f32=first and bf and not res, grad_in=grad_in, device=device,
+                            variant={"gcn": g.GNNSTAGE_GCN, "sage": g.GNNSTAGE_SAGE, "resgcn": g.GNNSTAGE_RESGCN}[var],
+                            ln_gamma=ln_g, ln_beta=ln_b, d_ln_gamma=d_ln_g, d_ln_beta=d_ln_b)
             self.stages.append(st)
             for j in range(L):
                 self.params.append((master_W[j], W[j] if bf else None, dW[j]))
             for j in range(L):
                 self.params.append((bias[j], None, dbias[j]))
+            if res:
+                for j in range(L):
+                    self.params.append((ln_g[j], None, d_ln_g[j]))
+                for j in range(L):
+                    self.params.append((ln_b[j], None, d_ln_b[j]))
             self.W.append(W); self.bias.append(bias); self.dW.append(dW); self.dbias.append(dbias)
             self.cur.append(cur); self.hist.append(hist); self.grad_in.append(grad_in)
             prev_top = cur[L]

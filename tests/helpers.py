@@ -174,14 +174,20 @@ class TrainProblem:
     head_b: np.ndarray
     quant: bool
     n_classes: int
+    variants: Optional[List[str]] = None        # per stage: "gcn" (default), "sage", "resgcn"
+    ln_gamma: Optional[List[List[np.ndarray]]] = None
+    ln_beta: Optional[List[List[np.ndarray]]] = None
 
     @property
     def n(self):
         return self.row_ptr.shape[0] - 1
 
+    def variant(self, si: int) -> str:
+        return "gcn" if self.variants is None else self.variants[si]
+
 
 def make_train_problem(*, n=1500, n_classes=5, stage_dims=((24, 16, 16),), K=4, dtype="f32", seed=2308100900,
-                       deg_in=8.0, deg_out=2.0, signal=0.6, label_rate=0.5, ragged=False) -> TrainProblem:
+                       deg_in=8.0, deg_out=2.0, signal=0.6, label_rate=0.5, ragged=False, variants=None) -> TrainProblem:
     """A synthetic node-classification task on a planted-partition graph (labels = planted groups)."""
     row_ptr, col, group = graphs.planted_partition(n, n_classes, deg_in, deg_out, seed)
     val = oracle.gcn_norm(row_ptr, col)
@@ -190,16 +196,25 @@ def make_train_problem(*, n=1500, n_classes=5, stage_dims=((24, 16, 16),), K=4, 
     stage_dims = [list(d) for d in stage_dims]
     x0 = values.group_features(seed, 1, group, stage_dims[0][0], signal)
     W, b, stream = [], [], 100
-    for dims in stage_dims:
-        W.append([values.glorot_uniform(seed, stream + j, dims[j], dims[j + 1]) for j in range(len(dims) - 1)])
+    ln_gamma, ln_beta = [], []
+    for si, dims in enumerate(stage_dims):
+        var = "gcn" if variants is None else variants[si]
+        Ws = [values.glorot_uniform(seed, stream + j, dims[j], dims[j + 1]) for j in range(len(dims) - 1)]
+        if var == "sage":  # [W_self ; W_neigh]
+            Ws = [np.concatenate([values.glorot_uniform(seed, stream + 10 + j, dims[j], dims[j + 1]), Ws[j]], axis=0)
+                  for j in range(len(dims) - 1)]
+        W.append(Ws)
         b.append([np.zeros(dims[j + 1], np.float32) for j in range(len(dims) - 1)])
+        ln_gamma.append([np.ones(dims[j], np.float32) for j in range(len(dims) - 1)])
+        ln_beta.append([np.zeros(dims[j], np.float32) for j in range(len(dims) - 1)])
         stream += 20
     d_last = stage_dims[-1][-1]
     head_W = values.glorot_uniform(seed, 900, d_last, n_classes)
     head_b = np.zeros(n_classes, np.float32)
     mask = values.bernoulli_mask(seed, 5, n, label_rate) if label_rate < 1.0 else None
     return TrainProblem(row_ptr, col, val, np.asarray(chunk_ptr, np.int64), stage_dims, W, b, x0,
-                        group.astype(np.int32), mask, head_W, head_b, quant, n_classes)
+                        group.astype(np.int32), mask, head_W, head_b, quant, n_classes,
+                        variants=None if variants is None else list(variants), ln_gamma=ln_gamma, ln_beta=ln_beta)
 
 
 def new_oracle_trainer(tp: TrainProblem, f64: bool = False, **opt):
@@ -208,8 +223,11 @@ def new_oracle_trainer(tp: TrainProblem, f64: bool = False, **opt):
     stages = []
     val = tp.val if not f64 else oracle.gcn_norm(tp.row_ptr, tp.col, f64=True)
     for si, dims in enumerate(tp.stage_dims):
-        st = oracle.OracleStage(tp.row_ptr, tp.col, val, tp.chunk_ptr, dims, tp.W[si], tp.b[si],
-                                quant=tp.quant and not f64, level0_f32=(si == 0 and tp.quant and not f64), f64=f64)
+        var = tp.variant(si)
+        st = oracle.OracleStage(tp.row_ptr, tp.col, val, tp.chunk_ptr, dims, tp.W[si], tp.b[si], variant=var,
+                                quant=tp.quant and not f64,
+                                level0_f32=(si == 0 and tp.quant and not f64 and var != "resgcn"), f64=f64,
+                                ln_gamma=tp.ln_gamma[si], ln_beta=tp.ln_beta[si])
         if si == 0:
             st.cur[0][...] = tp.x0
             st.hist[0][...] = tp.x0

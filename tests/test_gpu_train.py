@@ -155,6 +155,22 @@ def test_one_sgd_epoch_fp32(stage_dims, ragged):
             assert torch.equal(st_hist[j], st_cur[j])
 
 
+@pytest.mark.parametrize("variants,stage_dims", [(("sage",), ((24, 16, 16),)), (("resgcn",), ((16, 16, 16),)),
+                                                 (("sage", "resgcn", "gcn"), ((24, 16), (16, 16, 16), (16, 8)))])
+def test_one_sgd_epoch_fp32_other_layer_types(variants, stage_dims):
+    """The loop is generic over the stages' layer types: GraphSage, ResGCN+ (LayerNorm parameters are
+    trained too) and a mix of all three in one model."""
+    tp = make_train_problem(n=1500, n_classes=5, stage_dims=stage_dims, K=4, ragged=True, variants=variants)
+    ref, run, out = _run_pair(tp, 3, optimizer="sgd", lr=0.05, shuffle=True, seed=11, alpha_hist=2)
+    for lg, lr_ in out:
+        assert abs(lg - lr_) <= 1e-4 * lr_
+    for a, b in zip(run.grads(), ref.grads()):
+        assert max_rel(a.reshape(b.shape), b) <= 1e-4
+    for a, b in zip(run.master_values(), ref.master):
+        assert max_rel(a.reshape(b.shape), b) <= 1e-4
+    assert out[-1][0] < out[0][0]
+
+
 @pytest.mark.parametrize("stage_dims", [((24, 16, 16),), ((24, 16), (16, 16, 8))])
 def test_one_sgd_epoch_bf16(stage_dims):
     """bf16 levels: the oracle rounds at the same points.  A pre-activation that sits within rounding noise of
