@@ -79,14 +79,19 @@ def main():
     bf = w.dtype == "bf16"
     sdt = torch.bfloat16 if bf else torch.float32
     l0 = torch.float32 if (w.level0_f32 or not bf) else torch.bfloat16
-    gcn = w.variant == "gcn"
+    gcn = w.variant != "gcnii"  # layer types with a bias vector and no GCNII inputs
+    sage, res = w.variant == "sage", w.variant == "resgcn"
     x0_np = values.normal(w.seed, 1, (n, dims[0])) if gcn else values.half_normal(w.seed, 1, (n, dims[0]))
-    W = [torch.from_numpy(values.glorot_uniform(w.seed, 100 + j, dims[j], dims[j + 1])).to(dev, sdt) for j in range(L)]
+    wrows = 2 if sage else 1  # GraphSage stacks [W_self ; W_neigh]
+    W = [torch.from_numpy(np.concatenate([values.glorot_uniform(w.seed, 100 + 50 * h + j, dims[j], dims[j + 1]) for h in range(wrows)]))
+         .to(dev, sdt) for j in range(L)]
     bias = [torch.zeros(dims[j + 1], device=dev) for j in range(L)] if gcn else None
     cur = [torch.from_numpy(x0_np).to(dev, l0)] + [torch.zeros((n, dims[j]), dtype=sdt, device=dev) for j in range(1, L + 1)]
-    first_stage = gcn
+    first_stage = (w.variant == "gcn") if w.first_stage is None else w.first_stage
+    ln = [[torch.ones(dims[j], device=dev) for j in range(L)], [torch.zeros(dims[j], device=dev) for j in range(L)],
+          [torch.zeros(dims[j], device=dev) for j in range(L)], [torch.zeros(dims[j], device=dev) for j in range(L)]] if res else [None] * 4
     hist = [cur[0] if first_stage else cur[0].clone()] + [torch.zeros((n, dims[j]), dtype=sdt, device=dev) for j in range(1, L)]
-    dW = [torch.zeros((dims[j], dims[j + 1]), device=dev) for j in range(L)]
+    dW = [torch.zeros((wrows * dims[j], dims[j + 1]), device=dev) for j in range(L)]
     dbias = [torch.zeros(dims[j + 1], device=dev) for j in range(L)] if gcn else None
     h0 = None if gcn else torch.from_numpy(values.normal(w.seed, 2, (n, dims[0]))).to(dev, sdt)
     grad_h0 = None if gcn else torch.zeros((n, dims[0]), device=dev)
@@ -98,9 +103,10 @@ def main():
         beta = np.array([math.log(0.5 / l + 1.0) for l in range(w.gcnii_first_layer, w.gcnii_first_layer + L)], np.float32)
     t1 = time.time()
     st = g.GnnStage(row_ptr, col, chunk_ptr, dims, W=W, cur=cur, hist=hist, dW=dW, bias=bias, dbias=dbias,
-                    variant=g.GNNSTAGE_GCN if gcn else g.GNNSTAGE_GCNII, alpha=w.gcnii_alpha, beta=beta, h0=h0,
+                    variant={"gcn": g.GNNSTAGE_GCN, "gcnii": g.GNNSTAGE_GCNII, "sage": g.GNNSTAGE_SAGE,
+                             "resgcn": g.GNNSTAGE_RESGCN}[w.variant], alpha=w.gcnii_alpha, beta=beta, h0=h0,
                     grad_h0=grad_h0, dtype=g.GNNSTAGE_BF16 if bf else g.GNNSTAGE_F32, level0_f32=w.level0_f32,
-                    grad_in=grad_in, device=dev)
+                    grad_in=grad_in, device=dev, ln_gamma=ln[0], ln_beta=ln[1], d_ln_gamma=ln[2], d_ln_beta=ln[3])
     log(f"[bench] gnnstage_create: {time.time() - t1:.1f}s, workspace {st.workspace_bytes / 2**30:.2f} GiB")
 
     def one_step(step_idx: int):
@@ -186,7 +192,7 @@ def main():
         add(gname(dg, eg), fb, E.sum() * dg * eg * len(orders), *prof_layer[j]["spmm_fwd"])
         db_, eb = (dims[j + 1], elt) if tf[j] else (dims[j], elt)        # what the backward gathers
         bb = gb = 0.0
-        masked = (j > 0 or grad_in is not None) and not (tf[j] and j == 0 and shared0 and grad_in is None)
+        masked = (j > 0 or grad_in is not None or res) and not (tf[j] and j == 0 and shared0 and grad_in is None)
         for order in orders:
             done = np.zeros(K, dtype=bool)
             for k in reversed(list(order)):
@@ -197,6 +203,13 @@ def main():
             if tf[j]:  # end-of-pass unmasked transposed aggregation of a transform-first layer
                 bb += sum(struct[k] + D[k].sum() * db_ * eb + rows[k] * db_ * elt for k in range(K))
                 gb += E.sum() * db_ * eb
+            if res:  # end-of-pass aggregations over the readers that saw historical rows (LayerNorm parameters)
+                earlier = np.zeros(K, dtype=bool)
+                for pos, k in enumerate(order):
+                    if pos > 0:
+                        bb += struct[k] + D[k][earlier].sum() * db_ * eb + rows[k] * db_ * elt
+                        gb += E[k][earlier].sum() * db_ * eb
+                    earlier[k] = True
         if prof_layer[j]["spmm_bwd"][1] > 0:
             add(gname(db_, eb), bb, gb, *prof_layer[j]["spmm_bwd"])
     dom_name, (dom_bytes, dom_gather, dom_ms, dom_launches) = max(groups.items(), key=lambda kv: kv[1][2])
@@ -231,7 +244,7 @@ def main():
 
     # ---- optional: epochs of the whole training loop around the same stage ------------------
     trainer = None
-    if args.train_epochs > 0 and gcn:
+    if args.train_epochs > 0 and w.variant == "gcn":
         n_classes = 41
         labels = torch.from_numpy(values._rng(w.seed, 7).integers(0, n_classes, size=n).astype(np.int32)).to(dev)
         master = [t.to(torch.float32) for t in W] if bf else W
@@ -256,7 +269,7 @@ def main():
 
     # ---- CPU baseline: the oracle on a bounded sample ---------------------------------------
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and w.variant in ("gcn", "gcnii"):
         cpu = cpu_baseline(w, row_ptr, col, x0_np, dims, args.cpu_sample_rows)
 
     out = {

@@ -214,13 +214,14 @@ int launch_colsum_add(const void *B, int dtype, int ldb, int M, int O, float *pa
 
 // ---- LayerNorm + ReLU in front of the aggregation (ResGCN+ variant) -------------------------------
 constexpr int kLnMaxWidth = 1024;  // a row lives in the registers of one wavefront
-constexpr int kLnMaxWaves = 2048;  // wavefronts of one backward launch (size of the parameter-gradient scratch)
+constexpr int kLnMaxWaves = 8192;  // wavefronts of one backward launch; the parameter-gradient scratch holds one
+                                   // 2 x d block of sums per workgroup of four
 // out[r][c] = ReLU(gamma[c] * (x[r][c] - mean_r) / sqrt(var_r + eps) + beta[c]), c < d; zeros up to out_ld
 int launch_ln_relu(const void *x, int x_dtype, int x_ld, const float *gamma, const float *beta, float eps, int64_t M, int d, void *out,
                    int out_dtype, int out_ld, hipStream_t s);
 // Backward of the same for M rows: dr is the gradient of the activated rows.  out (may be NULL) receives the
 // gradient of x plus, when res is not NULL, the rows of res (the residual branch); dgamma / dbeta get "+=" of
-// the column sums in a fixed order (partial: fp32 scratch, kLnMaxWaves * 2 * d).
+// the column sums in a fixed order (partial: fp32 scratch, kLnMaxWaves / 4 * 2 * d).
 int launch_ln_relu_backward(const void *x, int x_dtype, int x_ld, const float *gamma, const float *beta, float eps, const void *dr,
                             int dr_dtype, int dr_ld, const void *res, int res_dtype, int res_ld, int64_t M, int d, void *out,
                             int out_dtype, int out_ld, float *partial, float *dgamma, float *dbeta, hipStream_t s);

@@ -447,7 +447,7 @@ Layout make_layout(const Shape &s, const HostDir &hf, const HostDir &hb, bool ra
   }
   if (s.res()) {
     l.res_dr = w.take((size_t)s.max_rows() * max_ld * elt);
-    l.ln_partial = w.take(sizeof(float) * (size_t)kLnMaxWaves * 2 * max_d);
+    l.ln_partial = w.take(sizeof(float) * (size_t)(kLnMaxWaves / 4) * 2 * max_d);
   }
   for (int j = 0; j < s.L && !s.res(); ++j) {
     if (s.tf[j]) {

@@ -65,15 +65,17 @@ __global__ __launch_bounds__(256) void ln_relu_kernel(const void *x, int x_dtype
   }
 }
 
-// dr -> dx (+ res) for the rows of the launch; per-wavefront column sums of the parameter gradients go to
-// partial[wave][0][c] (gamma) and partial[wave][1][c] (beta), added up in wave order by ln_param_reduce_kernel.
+// dr -> dx (+ res) for the rows of the launch; the column sums of the parameter gradients are added over the
+// four wavefronts of a workgroup in LDS and go to partial[workgroup][0][c] (gamma) and partial[workgroup][1][c]
+// (beta); ln_param_reduce_kernel adds those in a fixed order.
 template <int NI>
 __global__ __launch_bounds__(256) void ln_relu_backward_kernel(const void *x, int x_dtype, int x_ld, const float *gamma,
                                                                const float *beta, float eps, const void *dr, int dr_dtype, int dr_ld,
                                                                const void *res, int res_dtype, int res_ld, int64_t M, int d,
                                                                void *out, int out_dtype, int out_ld, float *partial) {
-  const int lane = threadIdx.x & 63;
-  const int64_t w0 = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6), nw = (int64_t)gridDim.x * 4;
+  __shared__ float red[3][2][NI * 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t w0 = (int64_t)blockIdx.x * 4 + wave, nw = (int64_t)gridDim.x * 4;
   float dg[NI], db[NI], gam[NI], bet[NI];
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
@@ -133,24 +135,46 @@ __global__ __launch_bounds__(256) void ln_relu_backward_kernel(const void *x, in
       }
     }
   }
+  if (wave > 0) {
 #pragma unroll
-  for (int i = 0; i < NI; ++i) {
-    const int c = lane + 64 * i;
-    if (c < d) {
-      partial[((size_t)w0 * 2 + 0) * d + c] = dg[i];
-      partial[((size_t)w0 * 2 + 1) * d + c] = db[i];
+    for (int i = 0; i < NI; ++i) {
+      red[wave - 1][0][lane + 64 * i] = dg[i];
+      red[wave - 1][1][lane + 64 * i] = db[i];
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int c = lane + 64 * i;
+      if (c < d) {
+        partial[((size_t)blockIdx.x * 2 + 0) * d + c] = ((dg[i] + red[0][0][c]) + red[1][0][c]) + red[2][0][c];
+        partial[((size_t)blockIdx.x * 2 + 1) * d + c] = ((db[i] + red[0][1][c]) + red[1][1][c]) + red[2][1][c];
+      }
     }
   }
 }
 
-__global__ __launch_bounds__(256) void ln_param_reduce_kernel(const float *partial, int n_waves, int d, float *dgamma, float *dbeta) {
-  const int idx = blockIdx.x * 256 + threadIdx.x;
-  if (idx >= 2 * d) return;
-  const int which = idx / d, c = idx % d;
+// One workgroup per 64 entries of the 2 x d sums: 16 wavefronts each add every 16th partial row, then the 16
+// slice sums are added in order.
+__global__ __launch_bounds__(1024) void ln_param_reduce_kernel(const float *partial, int n_parts, int d, float *dgamma, float *dbeta) {
+  __shared__ float red[16][64];
+  const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
+  const int idx = blockIdx.x * 64 + lane;  // position in [gamma sums | beta sums]
   float s = 0.f;
-  for (int w = 0; w < n_waves; ++w) s += partial[((size_t)w * 2 + which) * d + c];
-  float *dst = which == 0 ? dgamma : dbeta;
-  dst[c] += s;
+  if (idx < 2 * d) {
+#pragma unroll 8
+    for (int w = slice; w < n_parts; w += 16) s += partial[(size_t)w * 2 * d + idx];
+  }
+  red[slice][lane] = s;
+  __syncthreads();
+  if (slice == 0 && idx < 2 * d) {
+    float t = red[0][lane];
+#pragma unroll
+    for (int q = 1; q < 16; ++q) t += red[q][lane];
+    float *dst = idx < d ? dgamma + idx : dbeta + (idx - d);
+    *dst += t;
+  }
 }
 
 __global__ __launch_bounds__(256) void copy_rows_kernel(const void *src, int src_ld, void *dst, int dst_ld, int64_t M, int d, int dtype) {
@@ -205,7 +229,7 @@ int launch_ln_relu_backward(const void *x, int x_dtype, int x_ld, const float *g
 #undef LN_BWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return (int)e;
-  hipLaunchKernelGGL(ln_param_reduce_kernel, dim3((unsigned)((2 * d + 255) / 256)), dim3(256), 0, s, partial, waves, d, dgamma, dbeta);
+  hipLaunchKernelGGL(ln_param_reduce_kernel, dim3((unsigned)((2 * d + 63) / 64)), dim3(1024), 0, s, partial, waves / 4, d, dgamma, dbeta);
   return (int)hipGetLastError();
 }
 

@@ -29,6 +29,7 @@ class Workload:
     gcnii_first_layer: int = 1  # global 1-based index of the stage's first layer
     relabel: bool = True
     rmat_abc: tuple = (0.57, 0.19, 0.19)
+    first_stage: Optional[bool] = None  # None: GCN-type stages are first stages (features in, no input gradient)
     note: str = ""
 
     @property
@@ -60,6 +61,13 @@ CONFIGS = {
     # configs[4]: large, HBM-bound
     "c4": Workload("c4", "rmat", 10_000_000, 2308100874, [256] * 5, 32,
                    dtype="bf16", n_candidates=133_400_000, rmat_abc=(0.54, 0.19, 0.19)),
+    # c1's graph under a middle stage (bf16 level 0, input gradient wanted) of each layer type, same width
+    "c1_mid": Workload("c1_mid", "rmat", 232_965, 2308100871, [256] * 5, 8, dtype="bf16", n_candidates=92_300_000,
+                       first_stage=False),
+    "c1_sage": Workload("c1_sage", "rmat", 232_965, 2308100871, [256] * 5, 8, variant="sage", dtype="bf16",
+                        n_candidates=92_300_000, first_stage=False),
+    "c1_res": Workload("c1_res", "rmat", 232_965, 2308100871, [256] * 5, 8, variant="resgcn", dtype="bf16",
+                       n_candidates=92_300_000, first_stage=False),
     # shrunk versions for element-by-element parity against the oracle
     "c1_s": Workload("c1_s", "rmat", 6_007, 2308100881, [602, 256, 256, 256, 256], 8,
                      dtype="bf16", level0_f32=True, n_candidates=260_000),
