@@ -33,6 +33,10 @@
  *     gamma * (x - mean) / sqrt(var + eps) + beta with the biased variance.  The current-vs-historical
  *     choice applies to h_u; the normalisation is this layer's own, so its parameters also receive
  *     gradient through the historical rows (oracle_backward_finish).
+ *     Dropout (Section 5 trains with rate 0.5; DeepGCNs' block is Norm -> ReLU -> Dropout -> conv):
+ *     r_u = m_u * ReLU(LayerNorm(h_u)), m in {0, 1/(1-p)} per (layer, vertex, feature), the same for every
+ *     reader of u in a pass and for u's current and historical row alike.  The mask is a counter-based
+ *     draw: SplitMix64 of a per-layer key plus the element's index (oracle_dropout_keep).
  *
  * Precision: arrays are fp32 storage, every sum runs in fp64.  With quant == 1 the
  * values the GPU path keeps in bf16 (saved aggregation, levels, gradient rows) are
@@ -103,6 +107,8 @@ typedef struct {
   double ln_eps;
   int32_t *fwd_pos;     /* K entries: position of every chunk in this pass's forward order */
   int32_t n_fwd;
+  double dropout_p;     /* 0: no dropout */
+  uint64_t dropout_seed; /* of this pass */
 } oracle_stage;
 
 void oracle_set_threads(int n) {
@@ -198,6 +204,23 @@ void oracle_begin_pass(oracle_stage *s) {
   s->n_fwd = 0;
 }
 
+/* SplitMix64 output function (Steele, Lea, Flood 2014) */
+static uint64_t splitmix64(uint64_t z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+/* 1 if feature c of vertex u survives the dropout of layer j in the pass with this seed.  The layer's key is
+ * the generator's output for state seed + (j + 1) * golden; the element's draw is the output for state
+ * key + (u * d + c + 1) * golden; its top 24 bits, as a fraction of 2^24, are compared with p. */
+int32_t oracle_dropout_keep(uint64_t seed, int32_t j, int64_t u, int32_t d, int32_t c, double p) {
+  const uint64_t golden = 0x9E3779B97F4A7C15ull;
+  const uint64_t key = splitmix64(seed + (uint64_t)(j + 1) * golden);
+  const uint64_t r = splitmix64(key + (uint64_t)(u * d + c + 1) * golden);
+  return (double)(r >> 40) >= p * 16777216.0;
+}
+
 /* LayerNorm statistics of one row: mean and 1/sqrt(biased variance + eps) */
 static void ln_stats(const real_t *x, int32_t d, double eps, double *mean, double *rstd) {
   double m = 0.0;
@@ -210,27 +233,32 @@ static void ln_stats(const real_t *x, int32_t d, double eps, double *mean, doubl
   *rstd = 1.0 / sqrt(var + eps);
 }
 
-/* r = ReLU(LayerNorm(x)), stored like every other row the GPU path keeps */
-static void ln_relu_row(const oracle_stage *s, int32_t j, const real_t *x, int32_t d, real_t *r) {
+/* r = Dropout(ReLU(LayerNorm(x))) of vertex u, stored like every other row the GPU path keeps */
+static void ln_relu_row(const oracle_stage *s, int32_t j, int64_t u, const real_t *x, int32_t d, real_t *r) {
   double mean, rstd;
   ln_stats(x, d, s->ln_eps, &mean, &rstd);
+  const double keep_scale = 1.0 / (1.0 - s->dropout_p);
   for (int32_t i = 0; i < d; ++i) {
-    const double y = (double)s->ln_g[j][i] * (((double)x[i] - mean) * rstd) + (double)s->ln_b[j][i];
-    r[i] = store(s, y > 0.0 ? y : 0.0);
+    double y = (double)s->ln_g[j][i] * (((double)x[i] - mean) * rstd) + (double)s->ln_b[j][i];
+    y = y > 0.0 ? y : 0.0;
+    if (s->dropout_p > 0.0) y = oracle_dropout_keep(s->dropout_seed, j, u, d, i, s->dropout_p) ? y * keep_scale : 0.0;
+    r[i] = store(s, y);
   }
 }
 
 /* Backward of r = ReLU(LayerNorm(x)) for one row: dr -> dx (may be NULL), and the parameter gradients. */
-static void ln_relu_row_backward(const oracle_stage *s, int32_t j, const real_t *x, int32_t d, const double *dr,
+static void ln_relu_row_backward(const oracle_stage *s, int32_t j, int64_t u, const real_t *x, int32_t d, const double *dr,
                                  double *dx, double *dg, double *db) {
   double mean, rstd;
   ln_stats(x, d, s->ln_eps, &mean, &rstd);
   double m1 = 0.0, m2 = 0.0;
   double *dxh = (double *)malloc(sizeof(double) * (size_t)d);
+  const double keep_scale = 1.0 / (1.0 - s->dropout_p);
   for (int32_t i = 0; i < d; ++i) {
     const double xh = ((double)x[i] - mean) * rstd;
     const double y = (double)s->ln_g[j][i] * xh + (double)s->ln_b[j][i];
-    const double dn = y > 0.0 ? dr[i] : 0.0; /* ReLU derivative, strict */
+    double dn = y > 0.0 ? dr[i] : 0.0; /* ReLU derivative, strict */
+    if (s->dropout_p > 0.0) dn = oracle_dropout_keep(s->dropout_seed, j, u, d, i, s->dropout_p) ? dn * keep_scale : 0.0;
     dg[i] += dn * xh;
     db[i] += dn;
     dxh[i] = dn * (double)s->ln_g[j][i];
@@ -286,7 +314,7 @@ void oracle_forward_chunk(oracle_stage *s, int32_t k) {
           const double w = (double)s->val[e];
           const real_t *hu = src + u * din;
           if (s->variant == 3) { /* ResGCN+: the neighbour enters normalised and activated */
-            ln_relu_row(s, j, hu, din, ru);
+            ln_relu_row(s, j, u, hu, din, ru);
             hu = ru;
           }
           for (int32_t i = 0; i < din; ++i) z[i] += w * (double)hu[i];
@@ -449,7 +477,7 @@ void oracle_backward_chunk(oracle_stage *s, int32_t k, const real_t *grad_out, i
           double *dx = dr + din;
           for (int32_t i = 0; i < din; ++i) dr[i] = (double)store(s, acc[i]);
           double *dg = (double *)calloc((size_t)din * 2, sizeof(double));
-          ln_relu_row_backward(s, j, s->cur[j] + u * din, din, dr, dx, dg, dg + din);
+          ln_relu_row_backward(s, j, u, s->cur[j] + u * din, din, dr, dx, dg, dg + din);
 #pragma omp critical
           for (int32_t i = 0; i < din; ++i) {
             s->d_ln_g[j][i] += dg[i];
@@ -496,7 +524,7 @@ void oracle_backward_finish(oracle_stage *s) {
         for (int32_t i = 0; i < d; ++i) acc[i] += w * (double)dz[i];
       }
       for (int32_t i = 0; i < d; ++i) dr[i] = (double)store(s, acc[i]);
-      ln_relu_row_backward(s, j, s->hist[j] + u * d, d, dr, NULL, s->d_ln_g[j], s->d_ln_b[j]);
+      ln_relu_row_backward(s, j, u, s->hist[j] + u * d, d, dr, NULL, s->d_ln_g[j], s->d_ln_b[j]);
     }
     free(acc);
   }

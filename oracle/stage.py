@@ -46,6 +46,7 @@ class _CStage(C.Structure):
         ("g0", C.c_void_p), ("g1", C.c_void_p),
         ("ln_g", C.c_void_p), ("ln_b", C.c_void_p), ("d_ln_g", C.c_void_p), ("d_ln_b", C.c_void_p),
         ("ln_eps", C.c_double), ("fwd_pos", C.c_void_p), ("n_fwd", C.c_int32),
+        ("dropout_p", C.c_double), ("dropout_seed", C.c_uint64),
     ]
 
 
@@ -64,6 +65,8 @@ def _lib(f64: bool):
         lib.oracle_update_history.argtypes = [C.c_void_p]
         lib.oracle_backward_finish.argtypes = [C.c_void_p]
         lib.oracle_backward_finish.restype = None
+        lib.oracle_dropout_keep.argtypes = [C.c_uint64, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_double]
+        lib.oracle_dropout_keep.restype = C.c_int32
         lib.oracle_set_threads.argtypes = [C.c_int]
         lib.oracle_max_threads.restype = C.c_int
         for f in ("oracle_gcn_norm", "oracle_chunk_of", "oracle_build_transpose", "oracle_begin_pass",
@@ -107,7 +110,7 @@ class OracleStage:
 
     def __init__(self, row_ptr, col, val, chunk_ptr, dims, W, b=None, *, variant="gcn", a=0.0,
                  beta=None, h0=None, quant=False, level0_f32=False, f64=False, ln_gamma=None, ln_beta=None,
-                 ln_eps=1e-5):
+                 ln_eps=1e-5, dropout_p=0.0):
         self.f64 = f64
         self.rt = rt = np.float64 if f64 else np.float32
         self.lib = _lib(f64)
@@ -145,6 +148,8 @@ class OracleStage:
         self.grad_in = np.zeros((n, d[0]), dtype=rt)
         # ResGCN+: LayerNorm parameters of every layer and their gradients
         self.ln_eps = float(ln_eps)
+        self.dropout_p = float(dropout_p)   # ResGCN+ only: rate of the dropout between ReLU and the convolution
+        self.dropout_seed = 0               # per pass, see set_dropout_seed
         self.ln_g = [np.ascontiguousarray(ln_gamma[j] if ln_gamma is not None else np.ones(d[j]), dtype=rt) for j in range(L)]
         self.ln_b = [np.ascontiguousarray(ln_beta[j] if ln_beta is not None else np.zeros(d[j]), dtype=rt) for j in range(L)]
         self.d_ln_g = [np.zeros(d[j], dtype=np.float64) for j in range(L)]
@@ -191,11 +196,26 @@ class OracleStage:
         cs.g0, cs.g1 = self._g0.ctypes.data, self._g1.ctypes.data
         cs.ln_g, cs.ln_b, cs.d_ln_g, cs.d_ln_b = vp(plg), vp(plb), vp(pdlg), vp(pdlb)
         cs.ln_eps, cs.fwd_pos, cs.n_fwd = self.ln_eps, self.fwd_pos.ctypes.data, 0
+        cs.dropout_p, cs.dropout_seed = self.dropout_p, self.dropout_seed
         self._cs = cs
 
     # ---- Algorithm 1 driver pieces -------------------------------------------------
     def rows(self, k: int) -> slice:
         return slice(int(self.chunk_ptr[k]), int(self.chunk_ptr[k + 1]))
+
+    def set_dropout_seed(self, seed: int) -> None:
+        """Seed of the dropout masks of the next pass (forward and backward use the same)."""
+        self.dropout_seed = int(seed) & ((1 << 64) - 1)
+        self._cs.dropout_seed = self.dropout_seed
+
+    def dropout_keep_mask(self, j: int) -> np.ndarray:
+        """The 0/1 keep decisions of layer j for the current seed, element by element (for dense references)."""
+        d = int(self.dims[j])
+        out = np.zeros((self.n, d), dtype=np.float64)
+        for u in range(self.n):
+            for c in range(d):
+                out[u, c] = self.lib.oracle_dropout_keep(self.dropout_seed, j, u, d, c, self.dropout_p)
+        return out
 
     def begin_pass(self) -> None:
         self.lib.oracle_begin_pass(C.byref(self._cs))

@@ -52,6 +52,8 @@ class Problem:
     level0_f32: bool = False
     ln_gamma: Optional[List[np.ndarray]] = None   # ResGCN+ only
     ln_beta: Optional[List[np.ndarray]] = None
+    dropout_p: float = 0.0                        # ResGCN+ only
+    dropout_seed: int = 0
 
     @property
     def n(self):
@@ -67,7 +69,8 @@ class Problem:
                                 self.chunk_ptr, self.dims, self.W, self.b,
                                 variant=self.w.variant, a=self.a, beta=self.beta, h0=self.h0,
                                 quant=self.quant and not f64, level0_f32=self.level0_f32, f64=f64,
-                                ln_gamma=self.ln_gamma, ln_beta=self.ln_beta)
+                                ln_gamma=self.ln_gamma, ln_beta=self.ln_beta, dropout_p=self.dropout_p)
+        st.set_dropout_seed(self.dropout_seed)
         st.cur[0][...] = self.x0
         for j in range(self.L):
             st.hist[j][...] = self.hist[j]
@@ -81,7 +84,7 @@ def gcnii_beta(first_layer: int, n_layers: int) -> np.ndarray:
 
 def make_problem(w: Workload, *, graph=None, chunk_ptr=None, order=None, bias_std: float = 0.1,
                  first_stage: Optional[bool] = None, shuffle: bool = True, noise_std: float = 0.01,
-                 history: str = "clean") -> Problem:
+                 history: str = "clean", dropout_p: float = 0.0, dropout_seed: int = 0) -> Problem:
     row_ptr, col = graph if graph is not None else make_graph(w)
     n = row_ptr.shape[0] - 1
     val = edge_weights(w.variant, row_ptr, col)
@@ -136,7 +139,8 @@ def make_problem(w: Workload, *, graph=None, chunk_ptr=None, order=None, bias_st
             hist.append(g0(hj) if j == 0 else g(hj))
     return Problem(w, row_ptr, col, val, np.asarray(chunk_ptr, dtype=np.int64), dims, W, b, x0, hist, grad_out,
                    np.asarray(order, dtype=np.int32), h0=h0, a=a, beta=beta, quant=quant,
-                   level0_f32=w.level0_f32 and quant, ln_gamma=ln_gamma, ln_beta=ln_beta)
+                   level0_f32=w.level0_f32 and quant, ln_gamma=ln_gamma, ln_beta=ln_beta,
+                   dropout_p=dropout_p, dropout_seed=dropout_seed)
 
 
 def run_oracle(p: Problem, need_input_grad: bool = True, f64: bool = False):

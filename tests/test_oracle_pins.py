@@ -65,7 +65,7 @@ def dense_full_graph_levels(A, x0, W, b, variant="gcn", a=0.0, beta=None, h0=Non
     return levels
 
 
-def torch_dense_chunked(p, A, order, x0_t, W_t, b_t, h0_t=None, ln_t=None):
+def torch_dense_chunked(p, A, order, x0_t, W_t, b_t, h0_t=None, ln_t=None, drop=None):
     """Independent dense formulation of Algorithm 1's forward for autograd: per chunk and
     layer, split the dense adjacency columns into processed / unprocessed blocks."""
     n, L, K = p.n, p.L, p.chunk_ptr.shape[0] - 1
@@ -89,6 +89,8 @@ def torch_dense_chunked(p, A, order, x0_t, W_t, b_t, h0_t=None, ln_t=None):
                 src = cur_rows[j][c] if c in done else hist[j][cols]
                 if p.w.variant == "resgcn":  # a library LayerNorm, then ReLU, on whichever row is read
                     src = torch.relu(torch.nn.functional.layer_norm(src, (p.dims[j],), ln_t[0][j], ln_t[1][j], 1e-5))
+                    if drop is not None:  # keep decisions are an input here; 1 / (1 - p) rescales the survivors
+                        src = src * drop[j][cols] / (1.0 - p.dropout_p)
                 z = z + A_t[rows, cols] @ src
             if p.w.variant == "gcn":
                 y = z @ W_t[j] + b_t[j]
@@ -401,6 +403,63 @@ def test_resgcn_parameter_gradients_do_not_depend_on_asking_for_the_input_gradie
     c = run_oracle(p)
     assert np.array_equal(c.cur[p.L], p.x0)
     assert np.abs(c.grad_in - p.grad_out).max() <= 1e-6 * np.abs(p.grad_out).max()
+
+
+def test_resgcn_dropout():
+    """Dropout between ReLU and the convolution of the ResGCN+ block: counter-based keep decisions per
+    (layer, vertex, feature), survivors scaled by 1 / (1 - p)."""
+    w = tiny_workload(n=31, k=4, dims=(6, 6, 6, 6), variant="resgcn", seed=21)
+    chunks = graphs.ragged_chunks(31, 4, 3)
+    p0 = make_problem(w, chunk_ptr=chunks, first_stage=False, noise_std=0.3)
+    pz = make_problem(w, chunk_ptr=chunks, first_stage=False, noise_std=0.3, dropout_p=0.0, dropout_seed=99)
+    a, b = run_oracle(p0), run_oracle(pz)
+    assert np.array_equal(a.cur[p0.L], b.cur[p0.L]) and np.array_equal(a.grad_in, b.grad_in)   # rate 0 is no dropout
+    # keep decisions: a fair, repeatable coin per element that depends on seed and layer
+    big = oracle.OracleStage(p0.row_ptr, p0.col, p0.val, p0.chunk_ptr, [64, 64, 64], [np.zeros((64, 64))] * 2,
+                             variant="resgcn", dropout_p=0.4)
+    masks = {}
+    for seed in (1, 2):
+        big.set_dropout_seed(seed)
+        for j in range(2):
+            masks[seed, j] = big.dropout_keep_mask(j)
+    m = masks[1, 0]
+    assert set(np.unique(m)) == {0.0, 1.0} and abs(m.mean() - 0.6) < 4 * np.sqrt(0.24 / m.size)
+    assert abs(np.corrcoef(m[:, :-1].ravel(), m[:, 1:].ravel())[0, 1]) < 0.08
+    big.set_dropout_seed(1)
+    assert np.array_equal(big.dropout_keep_mask(0), m)
+    for other in ((1, 1), (2, 0)):
+        assert 0.3 < np.mean(masks[other] != m) < 0.7
+    # forward and every gradient against autograd on the dense chunked model, the keep decisions as an input
+    p = make_problem(w, chunk_ptr=chunks, first_stage=False, noise_std=0.3, dropout_p=0.5, dropout_seed=7)
+    st = p.new_oracle(f64=True)
+    st.forward_pass(p.order)
+    st.backward_pass(p.grad_out)
+    drop = [torch.from_numpy(st.dropout_keep_mask(j)) for j in range(p.L)]
+    assert 0.3 < float(drop[0].mean()) < 0.7
+    A = dense_adj(p.row_ptr, p.col, edge_weights("resgcn", p.row_ptr, p.col, f64=True), p.n)
+    x0_t = torch.from_numpy(p.x0.astype(np.float64)).requires_grad_(True)
+    W_t = [torch.from_numpy(x.astype(np.float64)).requires_grad_(True) for x in p.W]
+    b_t = [torch.from_numpy(x.astype(np.float64)).requires_grad_(True) for x in p.b]
+    ln_t = ([torch.from_numpy(x.astype(np.float64)).requires_grad_(True) for x in p.ln_gamma],
+            [torch.from_numpy(x.astype(np.float64)).requires_grad_(True) for x in p.ln_beta])
+    out = torch_dense_chunked(p, A, p.order, x0_t, W_t, b_t, None, ln_t, drop)
+    assert np.allclose(out.detach().numpy(), st.cur[p.L], rtol=1e-11, atol=1e-12)
+    (out * torch.from_numpy(p.grad_out.astype(np.float64))).sum().backward()
+    for j in range(p.L):
+        assert np.allclose(st.dW[j], W_t[j].grad.numpy(), rtol=1e-9, atol=1e-11)
+        assert np.allclose(st.d_ln_g[j], ln_t[0][j].grad.numpy(), rtol=1e-9, atol=1e-11)
+        assert np.allclose(st.d_ln_b[j], ln_t[1][j].grad.numpy(), rtol=1e-9, atol=1e-11)
+    assert np.allclose(st.grad_in, x0_t.grad.numpy(), rtol=1e-9, atol=1e-11)
+    # the decisions belong to (vertex, feature), not to the chunking: with the full-graph levels as history
+    # every chunking of the same seed gives the full-graph result
+    full = make_problem(w, chunk_ptr=np.array([0, 31]), first_stage=False, dropout_p=0.5, dropout_seed=7)
+    sf = full.new_oracle(f64=True)
+    sf.forward_pass([0])
+    for j in range(p.L):
+        p.hist[j] = sf.cur[j].copy()
+    sc = p.new_oracle(f64=True)
+    sc.forward_pass(p.order)
+    assert np.allclose(sc.cur[p.L], sf.cur[p.L], rtol=1e-12, atol=1e-12)
 
 
 def test_transposed_index_round_trip_and_push_pull():
