@@ -66,6 +66,10 @@ enum { GNNSTAGE_F32 = 0, GNNSTAGE_BF16 = 1 };
  *     variance.  The current-vs-historical choice applies to h_u.  All widths equal (at most 1024), no fp32
  *     level 0.  d_ln_gamma / d_ln_beta are complete after the last backward call of a pass: the normalisation
  *     is the layer's own, so its parameters also receive gradient through the historical rows.
+ *     With dropout_p > 0 (Section 5 trains with rate 0.5) the block is Norm -> ReLU -> Dropout -> convolution:
+ *     r_u is zeroed or scaled by 1 / (1 - p) per (layer, vertex, feature), the same decision for every reader
+ *     of u in a pass and for u's current and historical row; decisions are counter-based draws from the seed
+ *     given by gnnstage_set_dropout_seed.
  *
  * dtype GNNSTAGE_F32 : levels, weights, gradients rows are fp32; fp32 arithmetic.
  * dtype GNNSTAGE_BF16: levels, weights, gradient rows are bf16 (bias and all accumulators
@@ -113,6 +117,7 @@ typedef struct {
   float *const *d_ln_gamma; /* "+=" over the backward calls; caller zeroes */
   float *const *d_ln_beta;
   float ln_eps;
+  float dropout_p; /* GNNSTAGE_RESGCN only, in [0, 1): dropout between ReLU and the convolution (0 = none) */
 } gnnstage_desc;
 
 /* Device bytes the stage needs inside desc->workspace (graph tables, transposed index,
@@ -148,6 +153,11 @@ int stage_backward_chunk(gnnstage_t *st, int32_t chunk_id, const void *grad_out_
 /* hist[j] <- cur[j] for j < L, all rows (Section 3.4, second technique: when to call it, i.e.
  * the refresh period, is caller policy).  Levels whose hist pointer aliases cur are skipped. */
 int update_history(gnnstage_t *st, void *hip_stream);
+
+/* Seed of the dropout decisions of the next pass (forward and backward of a pass use the same one).  Feature c
+ * of vertex u survives in layer j when the top 24 bits of SplitMix64(key_j + (u * d + c + 1) * G) are at least
+ * dropout_p * 2^24, key_j = SplitMix64(seed + (j + 1) * G), G = 0x9E3779B97F4A7C15.  EORDER inside a forward pass. */
+int gnnstage_set_dropout_seed(gnnstage_t *st, uint64_t seed);
 
 /* Synchronises the device and frees the handle (the workspace stays with the caller). */
 int gnnstage_destroy(gnnstage_t *st);

@@ -61,7 +61,8 @@ typedef struct {
   int32_t optimizer;            /* GNNTRAIN_SGD: p -= lr (g + wd p);  GNNTRAIN_ADAM: Kingma & Ba, Algorithm 1 */
   float lr, beta1, beta2, eps, weight_decay;
   int32_t shuffle;    /* 0: chunks in index order every epoch */
-  uint64_t seed;      /* of the chunk shuffling */
+  uint64_t seed;      /* of the chunk shuffling, and of the dropout decisions of stages that have dropout: stage s
+                         gets gnnstage_set_dropout_seed(SplitMix64(seed + (epoch + 1) * 0x9E3779B97F4A7C15) + s) */
   int32_t alpha_hist; /* refresh period of the historical embeddings, >= 1 */
   void *workspace;    /* DEVICE, 256-byte aligned, >= gnntrain_workspace_size() bytes */
   size_t workspace_bytes;

@@ -183,8 +183,9 @@ class OracleTrainer:
         last = self.stages[-1]
         top = last.cur[last.L]
         C = self.head_W.shape[1]
-        for st in self.stages:
+        for si, st in enumerate(self.stages):
             st.zero_grads()
+            st.set_dropout_seed(splitmix64(self.seed + (t + 1) * _GOLDEN) + si)  # this epoch's dropout decisions
             st.begin_pass()
         self.head_dW[...] = 0
         self.head_db[...] = 0

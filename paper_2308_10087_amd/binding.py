@@ -39,7 +39,7 @@ class gnnstage_desc(C.Structure):
         ("grad_in", C.c_void_p), ("grad_h0", C.c_void_p), ("need_input_grad", C.c_int32),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
         ("ln_gamma", C.c_void_p), ("ln_beta", C.c_void_p), ("d_ln_gamma", C.c_void_p), ("d_ln_beta", C.c_void_p),
-        ("ln_eps", C.c_float),
+        ("ln_eps", C.c_float), ("dropout_p", C.c_float),
     ]
 
 
@@ -117,6 +117,8 @@ def _load():
     lib.gnnstage_profile_read.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     lib.gnnstage_profile_reset.restype = C.c_int
     lib.gnnstage_profile_reset.argtypes = [C.c_void_p]
+    lib.gnnstage_set_dropout_seed.restype = C.c_int
+    lib.gnnstage_set_dropout_seed.argtypes = [C.c_void_p, C.c_uint64]
     lib.gnnstage_query.restype = C.c_int64
     lib.gnnstage_query.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
     lib.gnnstage_buffer.restype = C.c_void_p
@@ -269,7 +271,7 @@ class GnnStage:
     def __init__(self, row_ptr, col_idx, chunk_ptr, dims, *, W, cur, hist, dW, bias=None, dbias=None,
                  edge_val=None, variant=GNNSTAGE_GCN, alpha=0.0, beta=None, h0=None, grad_h0=None,
                  dtype=GNNSTAGE_F32, level0_f32=False, grad_in=None, device="cuda:0", ln_gamma=None, ln_beta=None,
-                 d_ln_gamma=None, d_ln_beta=None, ln_eps=1e-5):
+                 d_ln_gamma=None, d_ln_beta=None, ln_eps=1e-5, dropout_p=0.0):
         import torch
 
         self._torch = torch
@@ -308,6 +310,7 @@ class GnnStage:
         d.need_input_grad = int(grad_in is not None)
         d.ln_gamma, d.ln_beta, d.d_ln_gamma, d.d_ln_beta = (vp(x) for x in self._keep_ln)
         d.ln_eps = float(ln_eps)
+        d.dropout_p = float(dropout_p)
         size = int(lib.gnnstage_workspace_size(C.byref(d)))
         if size == 0:
             raise GnnStageError(-1, lib.gnnstage_last_error(None).decode())
@@ -337,6 +340,9 @@ class GnnStage:
     def stage_backward_chunk(self, chunk_id: int, grad_out_rows, stream=None) -> None:
         ptr = None if grad_out_rows is None else grad_out_rows.data_ptr()
         self._check(lib.stage_backward_chunk(self._h, int(chunk_id), ptr, self._stream(stream)))
+
+    def gnnstage_set_dropout_seed(self, seed: int) -> None:
+        self._check(lib.gnnstage_set_dropout_seed(self._h, int(seed) & ((1 << 64) - 1)))
 
     def update_history(self, stream=None) -> None:
         self._check(lib.update_history(self._h, self._stream(stream)))

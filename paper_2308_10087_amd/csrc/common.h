@@ -216,15 +216,24 @@ int launch_colsum_add(const void *B, int dtype, int ldb, int M, int O, float *pa
 constexpr int kLnMaxWidth = 1024;  // a row lives in the registers of one wavefront
 constexpr int kLnMaxWaves = 8192;  // wavefronts of one backward launch; the parameter-gradient scratch holds one
                                    // 2 x d block of sums per workgroup of four
-// out[r][c] = ReLU(gamma[c] * (x[r][c] - mean_r) / sqrt(var_r + eps) + beta[c]), c < d; zeros up to out_ld
+// Dropout behind the activation: threshold = ceil(rate * 2^24) (0: none), scale = 1 / (1 - rate), key = the
+// layer's key of this pass, u0 = vertex id of the launch's first row.
+struct LnDropout {
+  uint32_t threshold;
+  float scale;
+  uint64_t key;
+  int64_t u0;
+};
+// out[r][c] = Dropout(ReLU(gamma[c] * (x[r][c] - mean_r) / sqrt(var_r + eps) + beta[c])), c < d; zeros up to out_ld
 int launch_ln_relu(const void *x, int x_dtype, int x_ld, const float *gamma, const float *beta, float eps, int64_t M, int d, void *out,
-                   int out_dtype, int out_ld, hipStream_t s);
+                   int out_dtype, int out_ld, const LnDropout &dp, hipStream_t s);
 // Backward of the same for M rows: dr is the gradient of the activated rows.  out (may be NULL) receives the
 // gradient of x plus, when res is not NULL, the rows of res (the residual branch); dgamma / dbeta get "+=" of
 // the column sums in a fixed order (partial: fp32 scratch, kLnMaxWaves / 4 * 2 * d).
 int launch_ln_relu_backward(const void *x, int x_dtype, int x_ld, const float *gamma, const float *beta, float eps, const void *dr,
                             int dr_dtype, int dr_ld, const void *res, int res_dtype, int res_ld, int64_t M, int d, void *out,
-                            int out_dtype, int out_ld, float *partial, float *dgamma, float *dbeta, hipStream_t s);
+                            int out_dtype, int out_ld, float *partial, float *dgamma, float *dbeta, const LnDropout &dp,
+                            hipStream_t s);
 // dst[r][c] = src[r][c] for c < d, zero for d <= c < dst_ld
 int launch_copy_rows(const void *src, int src_ld, void *dst, int dst_ld, int64_t M, int d, int dtype, hipStream_t s);
 

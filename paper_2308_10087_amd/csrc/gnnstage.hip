@@ -540,6 +540,22 @@ struct gnnstage {
   std::vector<const float *> ln_g, ln_b;  // ResGCN+: LayerNorm parameters and their gradients
   std::vector<float *> d_ln_g, d_ln_b;
   float ln_eps = 1e-5f;
+  float dropout_p = 0.f;      // ResGCN+: rate of the dropout between ReLU and the convolution
+  uint64_t dropout_seed = 0;  // of the current pass (gnnstage_set_dropout_seed)
+  // the dropout of layer j for a launch whose first row is vertex u0
+  LnDropout dropout(int j, int64_t u0) const {
+    LnDropout dp{};
+    if (dropout_p > 0.f) {
+      uint64_t z = dropout_seed + (uint64_t)(j + 1) * 0x9E3779B97F4A7C15ull;  // SplitMix64 output for that state
+      z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+      z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+      dp.key = z ^ (z >> 31);
+      dp.threshold = (uint32_t)std::ceil((double)dropout_p * 16777216.0);
+      dp.scale = (float)(1.0 / (1.0 - (double)dropout_p));
+      dp.u0 = u0;
+    }
+    return dp;
+  }
   void *grad_in = nullptr;
   float *grad_h0 = nullptr;
   char *ws = nullptr;
@@ -830,7 +846,7 @@ int res_pass_start(gnnstage *st, hipStream_t stream) {
   for (int j = 0; j < s.L; ++j) {
     Timed t(st, stream, 1, j);
     HIP_TRY(st, launch_ln_relu(st->hist[j], st->level_dtype(j), s.dims[j], st->ln_g[j], st->ln_b[j], st->ln_eps, s.n, s.dims[j],
-                               st->at<char>(st->lay.Th[j]), cd, s.ld[j], stream));
+                               st->at<char>(st->lay.Th[j]), cd, s.ld[j], st->dropout(j, 0), stream));
   }
   return GNNSTAGE_OK;
 }
@@ -848,7 +864,7 @@ int res_forward_chunk(gnnstage *st, int k, hipStream_t stream) {
     if (!shared) {
       Timed t(st, stream, 1, j);
       HIP_TRY(st, launch_ln_relu(xrows, st->level_dtype(j), s.dims[j], st->ln_g[j], st->ln_b[j], st->ln_eps, M, s.dims[j],
-                                 Rc + (size_t)row0 * s.ld[j] * celt, cd, s.ld[j], stream));
+                                 Rc + (size_t)row0 * s.ld[j] * celt, cd, s.ld[j], st->dropout(j, row0), stream));
     }
     char *Zj = st->at<char>(st->lay.Z[j]);
     {
@@ -919,7 +935,7 @@ int res_backward_finish(gnnstage *st, hipStream_t stream) {
         const char *xrows = static_cast<const char *>(st->hist[j]) + (size_t)row0 * s.dims[j] * st->level_elt(j);
         HIP_TRY(st, launch_ln_relu_backward(xrows, st->level_dtype(j), s.dims[j], st->ln_g[j], st->ln_b[j], st->ln_eps, dR, cd, s.ld[j],
                                             nullptr, cd, 0, M, s.dims[j], nullptr, cd, 0, st->at<float>(st->lay.ln_partial),
-                                            st->d_ln_g[j], st->d_ln_b[j], stream));
+                                            st->d_ln_g[j], st->d_ln_b[j], st->dropout(j, row0), stream));
       }
     }
     mask_set(earlier, c);
@@ -1015,7 +1031,7 @@ int res_backward_chunk(gnnstage *st, int k, const void *grad_out_rows, hipStream
       }
       HIP_TRY(st, launch_ln_relu_backward(xrows, st->level_dtype(j), s.dims[j], st->ln_g[j], st->ln_b[j], st->ln_eps, dR, cd, s.ld[j], dY,
                                           cd, s.ld[j + 1], M, s.dims[j], out, st->level_dtype(j), out_ld,
-                                          st->at<float>(st->lay.ln_partial), st->d_ln_g[j], st->d_ln_b[j], stream));
+                                          st->at<float>(st->lay.ln_partial), st->d_ln_g[j], st->d_ln_b[j], st->dropout(j, row0), stream));
     }
     gi ^= 1;
   }
@@ -1125,6 +1141,7 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
       if (!d->ln_gamma[j] || !d->ln_beta[j] || !d->d_ln_gamma[j] || !d->d_ln_beta[j])
         return fail(nullptr, GNNSTAGE_EINVAL, "a LayerNorm parameter pointer is NULL");
     if (!(d->ln_eps > 0.f)) return fail(nullptr, GNNSTAGE_EINVAL, "ln_eps must be positive");
+    if (!(d->dropout_p >= 0.f && d->dropout_p < 1.f)) return fail(nullptr, GNNSTAGE_EINVAL, "dropout_p must be in [0, 1)");
   }
   if (s.need_input_grad && !d->grad_in) return fail(nullptr, GNNSTAGE_EINVAL, "need_input_grad set but grad_in is NULL");
   if (!d->workspace || (reinterpret_cast<uintptr_t>(d->workspace) & (kAlign - 1)))
@@ -1175,6 +1192,7 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
       st->d_ln_b.push_back(d->d_ln_beta[j]);
     }
     st->ln_eps = d->ln_eps;
+    st->dropout_p = d->dropout_p;
   }
   if (d->beta) st->beta.assign(d->beta, d->beta + s.L); else st->beta.assign(s.L, 0.f);
   st->W.assign(d->W, d->W + s.L);
@@ -1862,6 +1880,14 @@ extern "C" int gnnstage_debug_select_counts(gnnstage_t *st, int32_t k, int32_t *
 extern "C" int gnnstage_layer_order(const gnnstage_t *st, int32_t layer) {
   if (!st || layer < 0 || layer >= st->s.L) return GNNSTAGE_EINVAL;
   return st->s.tf[layer] ? 1 : 0;
+}
+
+extern "C" int gnnstage_set_dropout_seed(gnnstage_t *st, uint64_t seed) {
+  if (!st) return GNNSTAGE_EINVAL;
+  if (!st->order.empty() && (int)st->order.size() < st->s.K)
+    return fail(st, GNNSTAGE_EORDER, "the dropout seed cannot change inside a forward pass");
+  st->dropout_seed = seed;
+  return GNNSTAGE_OK;
 }
 
 extern "C" int64_t gnnstage_query(const gnnstage_t *st, int32_t what, int32_t index) {

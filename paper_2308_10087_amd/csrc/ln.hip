@@ -20,6 +20,18 @@ __device__ inline void st_elt(void *p, int dtype, size_t i, float v) {
   else
     static_cast<float *>(p)[i] = v;
 }
+// Dropout between the activation and the aggregation: feature c of vertex u survives when the top 24 bits of
+// SplitMix64(key + (u * d + c + 1) * golden) reach the threshold rate * 2^24 (key: the layer's key of this pass).
+__device__ inline uint64_t splitmix64_dev(uint64_t z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+__device__ inline bool dropout_keep(const LnDropout &dp, int64_t u, int d, int c) {
+  const uint64_t r = splitmix64_dev(dp.key + (uint64_t)(u * d + c + 1) * 0x9E3779B97F4A7C15ull);
+  return (uint32_t)(r >> 40) >= dp.threshold;
+}
+
 __device__ inline float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
@@ -29,7 +41,8 @@ __device__ inline float wave_sum(float v) {
 // NI = columns per lane (lane, lane + 64, ...): the row lives in registers between the passes
 template <int NI>
 __global__ __launch_bounds__(256) void ln_relu_kernel(const void *x, int x_dtype, int x_ld, const float *gamma, const float *beta,
-                                                      float eps, int64_t M, int d, void *out, int out_dtype, int out_ld) {
+                                                      float eps, int64_t M, int d, void *out, int out_dtype, int out_ld,
+                                                      const LnDropout dp) {
   const int lane = threadIdx.x & 63;
   const int64_t w0 = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6), nw = (int64_t)gridDim.x * 4;
   for (int64_t r = w0; r < M; r += nw) {
@@ -58,6 +71,7 @@ __global__ __launch_bounds__(256) void ln_relu_kernel(const void *x, int x_dtype
         if (c < d) {
           y = gamma[c] * ((v[i] - mean) * rstd) + beta[c];
           y = y > 0.f ? y : 0.f;
+          if (dp.threshold > 0) y = dropout_keep(dp, dp.u0 + r, d, c) ? y * dp.scale : 0.f;
         }
         st_elt(out, out_dtype, (size_t)r * out_ld + c, y);
       }
@@ -72,7 +86,8 @@ template <int NI>
 __global__ __launch_bounds__(256) void ln_relu_backward_kernel(const void *x, int x_dtype, int x_ld, const float *gamma,
                                                                const float *beta, float eps, const void *dr, int dr_dtype, int dr_ld,
                                                                const void *res, int res_dtype, int res_ld, int64_t M, int d,
-                                                               void *out, int out_dtype, int out_ld, float *partial) {
+                                                               void *out, int out_dtype, int out_ld, float *partial,
+                                                               const LnDropout dp) {
   __shared__ float red[3][2][NI * 64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t w0 = (int64_t)blockIdx.x * 4 + wave, nw = (int64_t)gridDim.x * 4;
@@ -111,6 +126,7 @@ __global__ __launch_bounds__(256) void ln_relu_backward_kernel(const void *x, in
       if (c < d) {
         const float y = gam[i] * xh[i] + bet[i];
         dn = y > 0.f ? ld_elt(dr, dr_dtype, (size_t)r * dr_ld + c) : 0.f;  // ReLU derivative, strict
+        if (dp.threshold > 0) dn = dropout_keep(dp, dp.u0 + r, d, c) ? dn * dp.scale : 0.f;
       }
       dg[i] += dn * xh[i];
       db[i] += dn;
@@ -195,12 +211,12 @@ int waves_for(int64_t M, int max_waves) {
 }  // namespace
 
 int launch_ln_relu(const void *x, int x_dtype, int x_ld, const float *gamma, const float *beta, float eps, int64_t M, int d, void *out,
-                   int out_dtype, int out_ld, hipStream_t s) {
+                   int out_dtype, int out_ld, const LnDropout &dp, hipStream_t s) {
   if (M <= 0) return hipSuccess;
   if (d > kLnMaxWidth || out_ld > kLnMaxWidth) return hipErrorInvalidValue;
   const int ni = (std::max(d, out_ld) + 63) / 64;
   dim3 grid((unsigned)(waves_for(M, 16384) / 4));
-#define LN_FWD(NI) hipLaunchKernelGGL(ln_relu_kernel<NI>, grid, dim3(256), 0, s, x, x_dtype, x_ld, gamma, beta, eps, M, d, out, out_dtype, out_ld)
+#define LN_FWD(NI) hipLaunchKernelGGL(ln_relu_kernel<NI>, grid, dim3(256), 0, s, x, x_dtype, x_ld, gamma, beta, eps, M, d, out, out_dtype, out_ld, dp)
   if (ni <= 1) LN_FWD(1);
   else if (ni <= 2) LN_FWD(2);
   else if (ni <= 4) LN_FWD(4);
@@ -212,7 +228,8 @@ int launch_ln_relu(const void *x, int x_dtype, int x_ld, const float *gamma, con
 
 int launch_ln_relu_backward(const void *x, int x_dtype, int x_ld, const float *gamma, const float *beta, float eps, const void *dr,
                             int dr_dtype, int dr_ld, const void *res, int res_dtype, int res_ld, int64_t M, int d, void *out,
-                            int out_dtype, int out_ld, float *partial, float *dgamma, float *dbeta, hipStream_t s) {
+                            int out_dtype, int out_ld, float *partial, float *dgamma, float *dbeta, const LnDropout &dp,
+                            hipStream_t s) {
   if (M <= 0) return hipSuccess;
   if (d > kLnMaxWidth || (out && out_ld > kLnMaxWidth)) return hipErrorInvalidValue;
   const int ni = (std::max(d, out ? out_ld : d) + 63) / 64;
@@ -220,7 +237,7 @@ int launch_ln_relu_backward(const void *x, int x_dtype, int x_ld, const float *g
   dim3 grid((unsigned)(waves / 4));
 #define LN_BWD(NI)                                                                                                              \
   hipLaunchKernelGGL(ln_relu_backward_kernel<NI>, grid, dim3(256), 0, s, x, x_dtype, x_ld, gamma, beta, eps, dr, dr_dtype, dr_ld, res, \
-                     res_dtype, res_ld, M, d, out, out_dtype, out_ld, partial)
+                     res_dtype, res_ld, M, d, out, out_dtype, out_ld, partial, dp)
   if (ni <= 1) LN_BWD(1);
   else if (ni <= 2) LN_BWD(2);
   else if (ni <= 4) LN_BWD(4);

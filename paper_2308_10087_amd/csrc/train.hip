@@ -431,6 +431,10 @@ extern "C" int gnntrain_epoch(gnntrain_t *tr, int64_t epoch, float *loss, void *
   const int cd = x.dtype;
   const int S = (int)tr->stages.size();
   gnntrain_chunk_order(tr->seed, epoch, x.K, tr->shuffle, tr->order.data());
+  // dropout decisions of this epoch (stages without dropout ignore the seed): the epoch's SplitMix64 output, plus
+  // the stage's index
+  for (int s = 0; s < S; ++s)
+    TRAIN_STAGE(tr, s, gnnstage_set_dropout_seed(tr->stages[(size_t)s], splitmix64(tr->seed + (uint64_t)(epoch + 1) * kGolden) + (uint64_t)s));
 
   for (const gnntrain_param &p : tr->params) TRAIN_HIP(tr, launch_fill_zero(p.grad, sizeof(float) * (size_t)p.count, stream));
   // the head's weights, staged like a layer's: transposed for the logits, plain for the input gradient

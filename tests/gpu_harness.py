@@ -44,11 +44,14 @@ class GpuRun:
             variant={"gcn": g.GNNSTAGE_GCN, "gcnii": g.GNNSTAGE_GCNII, "sage": g.GNNSTAGE_SAGE,
                      "resgcn": g.GNNSTAGE_RESGCN}[p.w.variant], alpha=p.a,
             ln_gamma=self.ln_gamma, ln_beta=self.ln_beta, d_ln_gamma=self.d_ln_gamma, d_ln_beta=self.d_ln_beta,
+            dropout_p=p.dropout_p,
             beta=None if gcn else p.beta.astype(np.float32), h0=self.h0, grad_h0=self.grad_h0,
             dtype=g.GNNSTAGE_BF16 if bf else g.GNNSTAGE_F32, level0_f32=p.level0_f32, grad_in=self.grad_in,
             device=device)
 
     def forward(self, order=None):
+        if self.p.dropout_p > 0:
+            self.stage.gnnstage_set_dropout_seed(self.p.dropout_seed)
         self.stage.forward_pass(self.p.order if order is None else order)
 
     def backward(self, order=None):
@@ -102,7 +105,8 @@ class GpuTrainRun:
                             edge_val=tp.val, dtype=g.GNNSTAGE_BF16 if bf else g.GNNSTAGE_F32,
                             level0_f32=first and bf and not res, grad_in=grad_in, device=device,
                             variant={"gcn": g.GNNSTAGE_GCN, "sage": g.GNNSTAGE_SAGE, "resgcn": g.GNNSTAGE_RESGCN}[var],
-                            ln_gamma=ln_g, ln_beta=ln_b, d_ln_gamma=d_ln_g, d_ln_beta=d_ln_b)
+                            ln_gamma=ln_g, ln_beta=ln_b, d_ln_gamma=d_ln_g, d_ln_beta=d_ln_b,
+                            dropout_p=tp.dropout_p if res else 0.0)
             self.stages.append(st)
             for j in range(L):
                 self.params.append((master_W[j], W[j] if bf else None, dW[j]))

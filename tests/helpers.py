@@ -181,6 +181,7 @@ class TrainProblem:
     variants: Optional[List[str]] = None        # per stage: "gcn" (default), "sage", "resgcn"
     ln_gamma: Optional[List[List[np.ndarray]]] = None
     ln_beta: Optional[List[List[np.ndarray]]] = None
+    dropout_p: float = 0.0                      # of the ResGCN+ stages
 
     @property
     def n(self):
@@ -231,7 +232,8 @@ def new_oracle_trainer(tp: TrainProblem, f64: bool = False, **opt):
         st = oracle.OracleStage(tp.row_ptr, tp.col, val, tp.chunk_ptr, dims, tp.W[si], tp.b[si], variant=var,
                                 quant=tp.quant and not f64,
                                 level0_f32=(si == 0 and tp.quant and not f64 and var != "resgcn"), f64=f64,
-                                ln_gamma=tp.ln_gamma[si], ln_beta=tp.ln_beta[si])
+                                ln_gamma=tp.ln_gamma[si], ln_beta=tp.ln_beta[si],
+                                dropout_p=tp.dropout_p if var == "resgcn" else 0.0)
         if si == 0:
             st.cur[0][...] = tp.x0
             st.hist[0][...] = tp.x0

@@ -502,3 +502,37 @@ def test_resgcn_bf16_dense_blocks(monkeypatch):
     probe = _gpu(p)
     assert probe.stage.gnnstage_dense_entries(False) > 0 and probe.stage.gnnstage_dense_entries(True) > 0
     _parity(p, TOL_BF16)
+
+
+@pytest.mark.parametrize("rate,seed", [(0.5, 7), (0.3, 2**63 + 12345), (0.9, 1)])
+def test_resgcn_dropout(rate, seed):
+    """Same keep decisions on both sides (an integer comparison of counter-based draws), so the usual
+    tolerances hold element by element; the rate crosses the C ABI as a float and the oracle gets that float."""
+    rate = float(np.float32(rate))
+    w = small(dims=(40,) * 4, n=911, k=6, variant="resgcn")
+    p = make_problem(w, chunk_ptr=graphs.ragged_chunks(911, 6, 4), first_stage=False, noise_std=0.3,
+                     dropout_p=rate, dropout_seed=seed)
+    worst = _parity(p, TOL_F32)
+    ref = run_oracle(p)
+    keep = ref.dropout_keep_mask(0)
+    assert abs(keep.mean() - (1 - rate)) < 0.02
+    wb = Workload("res_drop", "rmat", 5003, 2308100894, [128] * 4, 6, variant="resgcn", dtype="bf16", n_candidates=60_000)
+    _parity(make_problem(wb, first_stage=False, dropout_p=rate, dropout_seed=seed), TOL_BF16)
+
+
+def test_resgcn_dropout_seed_changes_the_pass_and_is_locked_inside_one():
+    import paper_2308_10087_amd as g
+    w = small(dims=(24,) * 3, n=500, k=4, variant="resgcn")
+    p = make_problem(w, first_stage=False, dropout_p=0.5, dropout_seed=3)
+    run = _gpu(p)
+    run.forward()
+    a = run.cur[p.L].clone()
+    run.forward()
+    assert torch.equal(run.cur[p.L], a)                 # same seed, same pass
+    run.stage.gnnstage_set_dropout_seed(4)
+    run.stage.forward_pass(p.order)
+    assert not torch.equal(run.cur[p.L], a)
+    run.stage.stage_forward_chunk(int(p.order[0]), 0)
+    with pytest.raises(g.GnnStageError) as e:
+        run.stage.gnnstage_set_dropout_seed(5)
+    assert e.value.code == -3
