@@ -156,7 +156,8 @@ int update_history(gnnstage_t *st, void *hip_stream);
 
 /* Seed of the dropout decisions of the next pass (forward and backward of a pass use the same one).  Feature c
  * of vertex u survives in layer j when the top 24 bits of SplitMix64(key_j + (u * d + c + 1) * G) are at least
- * dropout_p * 2^24, key_j = SplitMix64(seed + (j + 1) * G), G = 0x9E3779B97F4A7C15.  EORDER inside a forward pass. */
+ * dropout_p * 2^24, key_j = SplitMix64(seed + (j + 1) * G), G = 0x9E3779B97F4A7C15.  EORDER inside a forward or a
+ * backward pass. */
 int gnnstage_set_dropout_seed(gnnstage_t *st, uint64_t seed);
 
 /* Synchronises the device and frees the handle (the workspace stays with the caller). */

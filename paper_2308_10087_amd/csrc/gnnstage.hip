@@ -1884,8 +1884,8 @@ extern "C" int gnnstage_layer_order(const gnnstage_t *st, int32_t layer) {
 
 extern "C" int gnnstage_set_dropout_seed(gnnstage_t *st, uint64_t seed) {
   if (!st) return GNNSTAGE_EINVAL;
-  if (!st->order.empty() && (int)st->order.size() < st->s.K)
-    return fail(st, GNNSTAGE_EORDER, "the dropout seed cannot change inside a forward pass");
+  if ((!st->order.empty() && (int)st->order.size() < st->s.K) || (st->n_bwd > 0 && st->n_bwd < st->s.K))
+    return fail(st, GNNSTAGE_EORDER, "the dropout seed cannot change inside a forward or a backward pass");
   st->dropout_seed = seed;
   return GNNSTAGE_OK;
 }

@@ -536,3 +536,9 @@ def test_resgcn_dropout_seed_changes_the_pass_and_is_locked_inside_one():
     with pytest.raises(g.GnnStageError) as e:
         run.stage.gnnstage_set_dropout_seed(5)
     assert e.value.code == -3
+    for pos, k in enumerate(p.order[1:], start=1):
+        run.stage.stage_forward_chunk(int(k), pos)
+    run.stage.stage_backward_chunk(int(p.order[-1]), run.grad_out[run.stage.rows(int(p.order[-1]))])
+    with pytest.raises(g.GnnStageError) as e:
+        run.stage.gnnstage_set_dropout_seed(6)      # the backward pass must see the forward pass's decisions
+    assert e.value.code == -3
