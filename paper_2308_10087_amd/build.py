@@ -13,7 +13,8 @@ LIB = os.path.join(HERE, "libgnnstage.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 SOURCES = ["gnnstage.hip", "spmm.hip", "dense.hip", "gemm.hip", "misc.hip", "ln.hip", "train.hip", "plan.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
-         # packed-fp32 VALU forms are switched off on purpose (build flags)
+         # packed-fp32 VALU forms are switched off on purpose: hipcc -O3 would form them by itself from ordinary
+         # float code, and some of those forms have given wrong results on this hardware
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-Wno-pass-failed"]
 
