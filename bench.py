@@ -240,7 +240,7 @@ def main():
     gemm_ms = sum(prof_all[k][0] for k in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad")) / n_extra
     gemm = {"tflops": round(gemm_flops / max(gemm_ms * 1e-3, 1e-12) / 1e12, 1), "ms_per_step": round(gemm_ms, 3),
             "frac_of_mfma_peak": round(gemm_flops / max(gemm_ms * 1e-3, 1e-12) / (2.5e15 if bf else 157.3e12), 4),
-            "bound": "hbm (128 flop/B at width 256 against a machine balance of 312)"}
+            "bound": f"hbm ({max(dims[1:]) // 2} flop/B at width {max(dims[1:])} against a machine balance of 312)"}
 
     # ---- optional: epochs of the whole training loop around the same stage ------------------
     trainer = None
@@ -277,7 +277,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf else "f32", "data": "synthetic",
-        "config": {"workload": f"configs[{args.workload[1:]}] {w.name}: R-MAT n={n} nnz={nnz} dims={dims} chunks={K} "
+        "config": {"workload": f"configs[{args.workload[1:]}] {w.name}: {'R-MAT' if w.kind == 'rmat' else 'Erdos-Renyi'} n={n} nnz={nnz} dims={dims} chunks={K} "
                                f"{w.variant} {'bf16 levels, fp32 level 0' if w.level0_f32 else w.dtype}",
                    "max_degree": stats["max_degree"], "step": "forward all chunks + backward all chunks + update_history"},
         "kernel_ms_per_step": kernels_ms,
