@@ -542,3 +542,34 @@ def test_resgcn_dropout_seed_changes_the_pass_and_is_locked_inside_one():
     with pytest.raises(g.GnnStageError) as e:
         run.stage.gnnstage_set_dropout_seed(6)      # the backward pass must see the forward pass's decisions
     assert e.value.code == -3
+
+
+# ----------------------------------------------------------------------------- size limits and degenerate inputs
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_maximum_chunk_count_with_tiny_chunks(dtype):
+    """256 chunks (the most the packed index word's chunk field is sized for here), most of one to four
+    vertices, shuffled order."""
+    n = 700
+    w = small(n=n, k=256, dims=(16, 24, 16), dtype=dtype, deg=5.0)
+    chunk_ptr = graphs.ragged_chunks(n, 256, 11)
+    assert np.diff(chunk_ptr).min() == 1
+    p = make_problem(w, chunk_ptr=chunk_ptr, first_stage=False, noise_std=0.2)
+    _parity(p, TOL_BF16 if dtype == "bf16" else TOL_F32)
+
+
+def test_rows_without_entries_and_a_single_vertex_graph():
+    """Vertices nobody points at (empty rows: the aggregation is zero, the layer output ReLU(b)), given weights;
+    and the smallest graph there is."""
+    rng = np.random.default_rng(3)
+    n = 300
+    dst = rng.integers(0, n // 2, 2500)          # rows n/2 .. n-1 stay empty
+    src = rng.integers(0, n, 2500)
+    row_ptr, col = graphs.from_directed_pairs(n, dst, src)
+    assert np.diff(row_ptr)[n // 2:].max() == 0
+    w = small(n=n, k=4, dims=(12, 20, 8))
+    p = make_problem(w, graph=(row_ptr, col), first_stage=False, noise_std=0.2)
+    p.val[...] = rng.uniform(0.1, 1.0, size=p.val.shape).astype(np.float32)   # D = 0 has no normalisation: weights are given
+    _parity(p, TOL_F32)
+    one = small(n=1, k=1, dims=(4, 4, 4))
+    g1 = (np.array([0, 1], dtype=np.int64), np.array([0], dtype=np.int32))
+    _parity(make_problem(one, graph=g1), TOL_F32)
