@@ -1,0 +1,102 @@
+"""Pins of the chunk partitioner's oracle (oracle/partition.py): what a locality-aware partition must
+deliver whatever heuristic produces it, on graphs whose best partition is known."""
+from __future__ import annotations
+
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle.partition import edge_cut, partition_chunks, permute_csr
+from synth import graphs
+
+
+def _check_shape(row_ptr, part, perm, chunk_ptr, K, nu=1.1):
+    n = len(row_ptr) - 1
+    assert part.min() >= 0 and part.max() < K
+    assert sorted(perm.tolist()) == list(range(n))                      # a renumbering
+    assert chunk_ptr[0] == 0 and chunk_ptr[-1] == n and np.all(np.diff(chunk_ptr) >= 0)
+    assert np.diff(chunk_ptr).max() <= int(np.ceil(nu * n / K))           # balance
+    for v in range(n):                                                    # part i is the id range of chunk i
+        assert chunk_ptr[part[v]] <= perm[v] < chunk_ptr[part[v] + 1]
+    inv = np.argsort(perm)
+    for i in range(K):                                                    # index order is kept inside a part
+        ids = inv[chunk_ptr[i]:chunk_ptr[i + 1]]
+        assert np.all(np.diff(ids) > 0)
+
+
+def test_disconnected_cliques_are_not_cut():
+    K, size = 4, 12
+    iu, ju = [], []
+    for c in range(K):
+        for a, b in itertools.combinations(range(c * size, (c + 1) * size), 2):
+            iu.append(a); ju.append(b)
+    rng = np.random.default_rng(0)
+    relabel = rng.permutation(K * size)
+    row_ptr, col = graphs.from_undirected_pairs(K * size, relabel[iu], relabel[ju])
+    part, perm, chunk_ptr = partition_chunks(row_ptr, col, K, passes=3)
+    _check_shape(row_ptr, part, perm, chunk_ptr, K)
+    assert edge_cut(row_ptr, col, part) == 0.0
+    assert np.array_equal(np.diff(chunk_ptr), [size] * K)
+
+
+def test_two_cliques_and_a_bridge_brute_force():
+    """n = 10, K = 2: the best balanced cut (enumerated) is the single bridge, and the heuristic finds it once a
+    part may hold one vertex more than its share (with no slack at all, restreaming cannot move anything: the
+    vertex that was taken out is the only one that fits back)."""
+    pairs = list(itertools.combinations(range(5), 2)) + list(itertools.combinations(range(5, 10), 2)) + [(4, 5)]
+    relabel = np.array([3, 8, 0, 6, 1, 9, 2, 7, 5, 4])
+    iu = relabel[[a for a, _ in pairs]]
+    ju = relabel[[b for _, b in pairs]]
+    row_ptr, col = graphs.from_undirected_pairs(10, iu, ju)
+    best = None
+    for subset in itertools.combinations(range(10), 5):
+        p = np.zeros(10, dtype=np.int32)
+        p[list(subset)] = 1
+        c = edge_cut(row_ptr, col, p)
+        best = c if best is None else min(best, c)
+    part, perm, chunk_ptr = partition_chunks(row_ptr, col, 2, passes=3, nu=1.1)
+    _check_shape(row_ptr, part, perm, chunk_ptr, 2, nu=1.1)
+    assert edge_cut(row_ptr, col, part) == best == pytest.approx(2 / 42)
+    stuck = partition_chunks(row_ptr, col, 2, passes=3, nu=1.0)
+    assert np.array_equal(np.diff(stuck[2]), [5, 5])
+
+
+def test_planted_partition_is_recovered():
+    n, K = 4000, 8
+    row_ptr, col, group = graphs.planted_partition(n, K, 12.0, 1.5, 5)
+    part, perm, chunk_ptr = partition_chunks(row_ptr, col, K)
+    _check_shape(row_ptr, part, perm, chunk_ptr, K)
+    planted = edge_cut(row_ptr, col, group)
+    assert edge_cut(row_ptr, col, part) <= 1.05 * planted
+    purity = np.mean([np.bincount(group[part == i], minlength=K).max() / max((part == i).sum(), 1) for i in range(K)])
+    assert purity > 0.99
+    # an index-range split of the (randomly numbered) vertices cuts (K - 1) / K of the edges
+    blind = (np.arange(n) * K // n).astype(np.int32)
+    assert edge_cut(row_ptr, col, blind) > 0.8
+
+
+def test_one_chunk_and_repeatability():
+    row_ptr, col = graphs.erdos_renyi(300, 6.0, 3)
+    part, perm, chunk_ptr = partition_chunks(row_ptr, col, 1)
+    assert np.all(part == 0) and np.array_equal(perm, np.arange(300)) and chunk_ptr.tolist() == [0, 300]
+    a = partition_chunks(row_ptr, col, 5, passes=2)
+    b = partition_chunks(row_ptr, col, 5, passes=2)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    more = partition_chunks(row_ptr, col, 5, passes=4)
+    assert edge_cut(row_ptr, col, more[0]) <= edge_cut(row_ptr, col, a[0]) + 0.02   # further passes do not hurt
+
+
+def test_renumbered_graph_is_the_same_graph():
+    row_ptr, col = graphs.erdos_renyi(200, 5.0, 9)
+    part, perm, chunk_ptr = partition_chunks(row_ptr, col, 4)
+    p2, c2 = permute_csr(row_ptr, col, perm)
+    assert p2[-1] == row_ptr[-1]
+    old = {(int(v), int(u)) for v in range(200) for u in col[row_ptr[v]:row_ptr[v + 1]]}
+    new = {(int(v), int(u)) for v in range(200) for u in c2[p2[v]:p2[v + 1]]}
+    assert new == {(int(perm[v]), int(perm[u])) for v, u in old}
+    for v in range(200):
+        assert np.all(np.diff(c2[p2[v]:p2[v + 1]]) > 0)
+    # after the renumbering, part i is exactly chunk i
+    chunk_of = np.searchsorted(chunk_ptr, np.arange(200), side="right") - 1
+    assert np.array_equal(chunk_of[perm], part)
