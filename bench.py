@@ -53,6 +53,8 @@ def main():
     ap.add_argument("--workload", default="c1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=131072)
+    ap.add_argument("--partition", action="store_true",
+                    help="chunks from the library's locality-aware partitioner instead of index ranges (not the benchmark configuration)")
     ap.add_argument("--train-epochs", type=int, default=0,
                     help="also time this many epochs of the whole training loop (head + Adam) around the same stage")
     args = ap.parse_args()
@@ -72,6 +74,19 @@ def main():
     row_ptr, col = make_graph(w)
     n, nnz = len(row_ptr) - 1, int(row_ptr[-1])
     chunk_ptr = equal_chunks(n, w.n_chunks)
+    cut_note = ""
+    if args.partition:
+        t_p = time.time()
+        part, perm, chunk_ptr = g.gnnstage_partition_chunks(row_ptr, col, w.n_chunks)
+        rows_all = np.repeat(np.arange(n, dtype=np.int64), np.diff(row_ptr))
+        off = rows_all != col
+        blind = (np.arange(n, dtype=np.int64) * w.n_chunks // n)
+        cut_before = float(np.mean(blind[rows_all[off]] != blind[col[off]]))
+        cut_after = float(np.mean(part[rows_all[off]] != part[col[off]]))
+        del rows_all, off
+        row_ptr, col = g.gnnstage_permute_csr(row_ptr, col, perm)
+        cut_note = f" partitioned chunks (neighbours in other chunks {cut_before:.3f} -> {cut_after:.3f}, sizes {np.diff(chunk_ptr).min()}..{np.diff(chunk_ptr).max()})"
+        log(f"[bench] partitioner: {time.time() - t_p:.1f}s,{cut_note}")
     K, L, dims = w.n_chunks, w.n_layers, list(w.dims)
     stats = degree_stats(row_ptr)
     log(f"[bench] graph {w.name}: {stats} built in {time.time() - t0:.1f}s")
@@ -278,7 +293,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf else "f32", "data": "synthetic",
         "config": {"workload": f"configs[{args.workload[1:]}] {w.name}: {'R-MAT' if w.kind == 'rmat' else 'Erdos-Renyi'} n={n} nnz={nnz} dims={dims} chunks={K} "
-                               f"{w.variant} {'bf16 levels, fp32 level 0' if w.level0_f32 else w.dtype}",
+                               f"{w.variant} {'bf16 levels, fp32 level 0' if w.level0_f32 else w.dtype}{cut_note}",
                    "max_degree": stats["max_degree"], "step": "forward all chunks + backward all chunks + update_history"},
         "kernel_ms_per_step": kernels_ms,
         "gemm": gemm,

@@ -228,6 +228,24 @@ int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, int64_t n_ve
                             int64_t *task_e0, int32_t *task_ne, int32_t *task_slot, int64_t *n_slots,
                             int64_t *class_off, uint8_t *slot_class);
 
+/*
+ * Chunk partitioner (host only): Algorithm 1's first step, "partition V into K chunks", locality-aware as
+ * Section 3.2 asks.  Restreaming FENNEL (Tsourakakis et al., WSDM 2014; Nishimura and Ugander, KDD 2013):
+ * `passes` streams over the vertices in index order; a vertex leaves its part, then joins the part i that
+ * maximises  |N(v) in P_i| - alpha * 1.5 * sqrt(|P_i|)  among the parts with fewer than ceil(slack * n / K)
+ * vertices, alpha = balance * sqrt(K) * m / n^1.5 with m the number of undirected edges (balance = 1 is the
+ * published weight, 4 keeps the capacity from binding while the parts form); ties go to the lowest part;
+ * self-loops are ignored.  The index must be symmetric for the edge count to mean what it says.
+ * part (n): part of every vertex.  perm (n): perm[old id] = new id, part by part, index order kept inside a
+ * part.  chunk_ptr (K + 1): the id ranges of the chunks after the renumbering.  gnnstage_permute_csr applies a
+ * renumbering to an index (columns ascending inside every row).
+ */
+int gnnstage_partition_chunks(int64_t n, const int64_t *row_ptr, const int32_t *col_idx, int32_t n_chunks,
+                              int32_t passes, double slack, double balance, int32_t *part, int32_t *perm,
+                              int64_t *chunk_ptr);
+int gnnstage_permute_csr(int64_t n, const int64_t *row_ptr, const int32_t *col_idx, const int32_t *perm,
+                         int64_t *out_ptr, int32_t *out_idx);
+
 /* Dense-block plan of one aggregation direction (host only).  Power-law graphs keep most of their
  * entries in a small, dense corner once rows and columns are ordered by degree: inside every chunk the
  * rows are ordered by length, the vertices of every chunk by how often they occur as a column, and the

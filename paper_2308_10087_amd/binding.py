@@ -119,6 +119,11 @@ def _load():
     lib.gnnstage_profile_reset.argtypes = [C.c_void_p]
     lib.gnnstage_set_dropout_seed.restype = C.c_int
     lib.gnnstage_set_dropout_seed.argtypes = [C.c_void_p, C.c_uint64]
+    lib.gnnstage_partition_chunks.restype = C.c_int
+    lib.gnnstage_partition_chunks.argtypes = [C.c_int64, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_double,
+                                              C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.gnnstage_permute_csr.restype = C.c_int
+    lib.gnnstage_permute_csr.argtypes = [C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.gnnstage_query.restype = C.c_int64
     lib.gnnstage_query.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
     lib.gnnstage_buffer.restype = C.c_void_p
@@ -219,6 +224,35 @@ def gnnstage_plan_tasks(ptr: np.ndarray, row_begin: int, row_end: int, split_edg
     if return_classes:
         return row, e0, ne, slot, int(ns.value), class_off, slot_class[:int(ns.value)]
     return row, e0, ne, slot, int(ns.value)
+
+
+def gnnstage_partition_chunks(row_ptr: np.ndarray, col_idx: np.ndarray, n_chunks: int, passes: int = 6, slack: float = 1.1,
+                              balance: float = 4.0):
+    """Locality-aware chunks: returns (part, perm with perm[old id] = new id, chunk_ptr)."""
+    row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int64)
+    col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
+    n = row_ptr.shape[0] - 1
+    part, perm = np.zeros(n, dtype=np.int32), np.zeros(n, dtype=np.int32)
+    chunk_ptr = np.zeros(n_chunks + 1, dtype=np.int64)
+    rc = lib.gnnstage_partition_chunks(n, row_ptr.ctypes.data, col_idx.ctypes.data, int(n_chunks), int(passes), float(slack),
+                                       float(balance), part.ctypes.data, perm.ctypes.data, chunk_ptr.ctypes.data)
+    if rc != 0:
+        raise GnnStageError(rc, "gnnstage_partition_chunks")
+    return part, perm, chunk_ptr
+
+
+def gnnstage_permute_csr(row_ptr: np.ndarray, col_idx: np.ndarray, perm: np.ndarray):
+    """The same graph with vertex ``old`` renamed ``perm[old]`` (columns ascending inside every row)."""
+    row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int64)
+    col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
+    perm = np.ascontiguousarray(perm, dtype=np.int32)
+    n = row_ptr.shape[0] - 1
+    out_ptr, out_idx = np.zeros(n + 1, dtype=np.int64), np.zeros(col_idx.shape[0], dtype=np.int32)
+    rc = lib.gnnstage_permute_csr(n, row_ptr.ctypes.data, col_idx.ctypes.data, perm.ctypes.data, out_ptr.ctypes.data,
+                                  out_idx.ctypes.data)
+    if rc != 0:
+        raise GnnStageError(rc, "gnnstage_permute_csr")
+    return out_ptr, out_idx
 
 
 _DENSE_FIELDS = [("rem_ptr", np.int64), ("rem_idx", np.int32), ("rem_orig", np.int64), ("row_perm", np.int32),

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgnnstage.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-SOURCES = ["gnnstage.hip", "spmm.hip", "dense.hip", "gemm.hip", "misc.hip", "ln.hip", "train.hip", "plan.cpp"]
+SOURCES = ["gnnstage.hip", "spmm.hip", "dense.hip", "gemm.hip", "misc.hip", "ln.hip", "train.hip", "plan.cpp", "partition.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed-fp32 VALU forms are switched off on purpose: hipcc -O3 would form them by itself from ordinary
          # float code, and some of those forms have given wrong results on this hardware
@@ -23,7 +23,8 @@ def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
     cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     if src.endswith(".cpp"):
-        cmd = [HIPCC, "-O2", "-std=c++17", "-fPIC", "-c", os.path.join(CSRC, src), "-o", obj]
+        # host code; no fused multiply-adds, so that its floating-point scores are the plain IEEE operations
+        cmd = [HIPCC, "-O2", "-std=c++17", "-fPIC", "-ffp-contract=off", "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

@@ -34,6 +34,8 @@ def main() -> None:
     ap.add_argument("--lr", type=float, default=0.005)
     ap.add_argument("--dropout", type=float, default=0.0, help="inside ResGCN+ blocks")
     ap.add_argument("--bf16", action="store_true")
+    ap.add_argument("--partition", action="store_true",
+                    help="chunks from the locality-aware partitioner (Algorithm 1's first step) instead of index ranges")
     ap.add_argument("--seed", type=int, default=1)
     args = ap.parse_args()
 
@@ -47,6 +49,14 @@ def main() -> None:
     x0 = values.group_features(args.seed, 1, group, args.features, 0.4)
     train_mask = values.bernoulli_mask(args.seed, 2, n, 0.3)
     chunk_ptr = graphs.equal_chunks(n, K)
+    if args.partition:  # renumber the vertices chunk by chunk; features, labels and mask follow
+        part, perm, chunk_ptr = g.gnnstage_partition_chunks(row_ptr, col, K)
+        rows_all = np.repeat(np.arange(n), np.diff(row_ptr))
+        print(f"neighbours in other chunks: {np.mean((rows_all * K // n) != (col.astype(np.int64) * K // n)):.3f} with index ranges, "
+              f"{np.mean(part[rows_all] != part[col]):.3f} with the partitioner", flush=True)
+        row_ptr, col = g.gnnstage_permute_csr(row_ptr, col, perm)
+        inverse = np.argsort(perm)
+        x0, group, train_mask = x0[inverse], group[inverse], train_mask[inverse]
     sdt = torch.bfloat16 if args.bf16 else torch.float32
     kinds = args.layers.split(",")
     variant = {"gcn": g.GNNSTAGE_GCN, "sage": g.GNNSTAGE_SAGE, "resgcn": g.GNNSTAGE_RESGCN}

@@ -32,7 +32,8 @@ def test_library_exports_every_declared_symbol():
     declared = sorted({n for n in names if n.startswith(("gnnstage_", "gnntrain_", "stage_", "update_history"))})
     assert {"gnnstage_create", "stage_forward_chunk", "stage_backward_chunk", "update_history",
             "gnnstage_destroy", "gnntrain_create", "gnntrain_epoch", "gnntrain_chunk_order", "gnntrain_softmax_xent",
-            "gnntrain_adam_step", "gnntrain_sgd_step", "gnntrain_sum", "gnnstage_query", "gnnstage_buffer"} <= set(declared)
+            "gnntrain_adam_step", "gnntrain_sgd_step", "gnntrain_sum", "gnnstage_query", "gnnstage_buffer",
+            "gnnstage_partition_chunks", "gnnstage_permute_csr", "gnnstage_set_dropout_seed"} <= set(declared)
     for name in declared:
         assert hasattr(g.lib, name), name
     assert g.gnnstage_version() >= 100
@@ -47,6 +48,39 @@ def test_chunk_order_matches_the_oracle_bit_for_bit():
             for epoch in (0, 1, 2, 77, 10**6):
                 assert np.array_equal(g.gnntrain_chunk_order(seed, epoch, K), chunk_order(seed, epoch, K)), (seed, K, epoch)
     assert np.array_equal(g.gnntrain_chunk_order(5, 3, 9, shuffle=False), np.arange(9))
+
+
+def test_chunk_partitioner_matches_the_oracle_bit_for_bit():
+    """Algorithm 1's first step on the host: the library's restreaming-FENNEL partitioner and the oracle's make the
+    same decision for every vertex (integer parts; the scores are plain IEEE operations on both sides)."""
+    from oracle.partition import edge_cut, partition_chunks, permute_csr
+    from synth.configs import CONFIGS, make_graph
+    g = _lib()
+    cases = [
+        (graphs.planted_partition(3000, 8, 10.0, 2.0, 3)[:2], 8, dict()),
+        (graphs.erdos_renyi(1500, 7.0, 4), 5, dict(passes=2, slack=1.05, balance=1.0)),
+        (make_graph(CONFIGS["c1_s"]), 8, dict(passes=3)),
+        (make_graph(CONFIGS["c3_s"]), 16, dict(passes=4, slack=1.3)),
+        (graphs.erdos_renyi(200, 4.0, 5), 1, dict()),
+        (graphs.erdos_renyi(97, 3.0, 6), 97, dict(passes=2, slack=1.0)),    # one vertex per chunk
+    ]
+    for (row_ptr, col), K, kw in cases:
+        part, perm, chunk_ptr = g.gnnstage_partition_chunks(row_ptr, col, K, **kw)
+        okw = dict(kw)
+        if "slack" in okw:
+            okw["nu"] = okw.pop("slack")
+        rpart, rperm, rchunk = partition_chunks(row_ptr, col, K, **okw)
+        assert np.array_equal(part, rpart) and np.array_equal(perm, rperm) and np.array_equal(chunk_ptr, rchunk), K
+        p2, c2 = g.gnnstage_permute_csr(row_ptr, col, perm)
+        q2, d2 = permute_csr(row_ptr, col, perm)
+        assert np.array_equal(p2, q2) and np.array_equal(c2, d2)
+    # what it is for: far fewer neighbours in other chunks than index ranges of randomly numbered vertices
+    (row_ptr, col), K, _ = cases[0]
+    part, perm, chunk_ptr = g.gnnstage_partition_chunks(row_ptr, col, K)
+    blind = (np.arange(3000) * K // 3000).astype(np.int32)
+    assert edge_cut(row_ptr, col, part) < 0.3 * edge_cut(row_ptr, col, blind)
+    with pytest.raises(g.GnnStageError):
+        g.gnnstage_permute_csr(row_ptr, col, np.zeros(3000, dtype=np.int32))     # not a permutation
 
 
 def test_transposed_index_is_the_exact_transpose():
