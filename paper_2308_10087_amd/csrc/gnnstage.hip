@@ -76,6 +76,36 @@ std::vector<int64_t> class_bounds(int64_t n, int classes, const std::vector<int6
   return lo;
 }
 
+// Class bounds for the rows [r0, r1) of an index (one chunk's launch): equal shares of those rows' ENTRIES rather than
+// of the id range, so that a chunk whose neighbours cluster in a few id ranges (chunks from a locality-aware
+// partitioner: about half of a chunk's neighbours are its own vertices) still spreads over all classes, its heavy
+// range cut into slices that fit an L2.  A bound moves to a chunk boundary that lies within a quarter of a class share
+// (in entries): classes made of whole chunks are skipped as a whole by launches that drop those chunks.  On a
+// uniformly numbered graph this gives the equal, chunk-aligned id ranges of class_bounds.
+std::vector<int64_t> class_bounds_by_entries(const int64_t *ptr, const int32_t *idx, int64_t n, int64_t r0, int64_t r1, int classes,
+                                             const std::vector<int64_t> &chunk_ptr) {
+  if (classes <= 1 || idx == nullptr || ptr[r1] == ptr[r0]) return class_bounds(n, classes, chunk_ptr);
+  std::vector<int64_t> mass((size_t)n + 1, 0);  // mass[u + 1] = entries of these rows whose source is u, then prefix sums
+  for (int64_t e = ptr[r0]; e < ptr[r1]; ++e) mass[(size_t)idx[e] + 1] += 1;
+  for (int64_t u = 0; u < n; ++u) mass[(size_t)u + 1] += mass[(size_t)u];
+  const int64_t total = mass[(size_t)n];
+  const int64_t tol = total / (4 * (int64_t)classes);
+  std::vector<int64_t> lo((size_t)classes + 1, 0);
+  lo[(size_t)classes] = n;
+  for (int q = 1; q < classes; ++q) {
+    const int64_t target = total / classes * q + total % classes * q / classes;
+    int64_t b = std::lower_bound(mass.begin(), mass.end(), target) - mass.begin();
+    int64_t best = -1;
+    for (const int64_t cb : chunk_ptr) {
+      const int64_t dist = std::llabs(mass[(size_t)cb] - target);
+      if (cb > 0 && cb < n && dist <= tol && (best < 0 || dist < std::llabs(mass[(size_t)best] - target))) best = cb;
+    }
+    if (best >= 0) b = best;
+    lo[(size_t)q] = std::min<int64_t>(std::max<int64_t>(b, lo[(size_t)q - 1]), n);
+  }
+  return lo;
+}
+
 // Dense blocks: switched on for bf16 stages whose aggregations all gather rows of width 128 or 256.
 // GNNSTAGE_DENSE=0 switches them off; GNNSTAGE_DENSE_MIN_NNZ (entries a 128 x 64 block needs, default 5 %
 // of its cells), GNNSTAGE_DENSE_MIN_SHARE (share of all entries that must fall into such blocks,
@@ -1207,7 +1237,6 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
   st->ws = static_cast<char *>(d->workspace);
   st->prof.init(s.L);
   st->n_classes = s.classes();
-  const std::vector<int64_t> cls_lo = class_bounds(s.n, st->n_classes, s.chunk_ptr);
   st->h_row_ptr.assign(d->row_ptr, d->row_ptr + s.n + 1);
   if (hp.f.dense()) {  // the diagnostics walk the whole index, not the remainder
     st->h_pcol.resize((size_t)s.nnz);
@@ -1255,6 +1284,7 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
       int64_t ns = 0;
       std::vector<int64_t> coff(classes + 1, 0);
       std::vector<uint8_t> sclass((size_t)std::max<int64_t>(pc.slots[c], 1), 255);
+      const std::vector<int64_t> cls_lo = class_bounds_by_entries(ptr, idx, s.n, s.chunk_ptr[c], s.chunk_ptr[c + 1], classes, s.chunk_ptr);
       const int64_t got = gnnstage_plan_tasks(ptr, idx, s.n, s.chunk_ptr[c], s.chunk_ptr[c + 1], pc.split[c], classes,
                                               cls_lo.data(), min_row, h.force_ptr(), cap, row.data(), e0.data(),
                                               ne.data(), slot.data(), &ns, coff.data(), sclass.data());

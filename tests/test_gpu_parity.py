@@ -573,3 +573,21 @@ def test_rows_without_entries_and_a_single_vertex_graph():
     one = small(n=1, k=1, dims=(4, 4, 4))
     g1 = (np.array([0, 1], dtype=np.int64), np.array([0], dtype=np.int32))
     _parity(make_problem(one, graph=g1), TOL_F32)
+
+
+@pytest.mark.parametrize("name", ["c1_s", "c2_s"])
+def test_chunks_from_the_partitioner(monkeypatch, name):
+    """Locality-aware chunks: about half of a chunk's neighbours are its own vertices, so the source classes of a
+    launch are far from equal id ranges, and the chunks differ in their entry counts."""
+    import paper_2308_10087_amd as g
+    from synth.configs import make_graph
+    monkeypatch.setenv("GNNSTAGE_XCD_CLASSES", "8")
+    monkeypatch.setenv("GNNSTAGE_CLASS_MIN_ROW", "16")
+    w = CONFIGS[name]
+    row_ptr, col = make_graph(w)
+    part, perm, chunk_ptr = g.gnnstage_partition_chunks(row_ptr, col, w.n_chunks)
+    graph = g.gnnstage_permute_csr(row_ptr, col, perm)
+    rows = np.repeat(np.arange(len(row_ptr) - 1), np.diff(row_ptr))
+    assert np.mean(part[rows] != part[col]) < 0.8 * (1 - 1 / w.n_chunks)
+    p = make_problem(w, graph=graph, chunk_ptr=chunk_ptr)
+    _parity(p, TOL_BF16)
