@@ -55,6 +55,7 @@ def main():
     ap.add_argument("--cpu-sample-rows", type=int, default=131072)
     ap.add_argument("--partition", action="store_true",
                     help="chunks from the library's locality-aware partitioner instead of index ranges (not the benchmark configuration)")
+    ap.add_argument("--partition-by-entries", action="store_true", help="with --partition: balance the chunks by entries")
     ap.add_argument("--train-epochs", type=int, default=0,
                     help="also time this many epochs of the whole training loop (head + Adam) around the same stage")
     args = ap.parse_args()
@@ -77,7 +78,7 @@ def main():
     cut_note = ""
     if args.partition:
         t_p = time.time()
-        part, perm, chunk_ptr = g.gnnstage_partition_chunks(row_ptr, col, w.n_chunks)
+        part, perm, chunk_ptr = g.gnnstage_partition_chunks(row_ptr, col, w.n_chunks, by_entries=args.partition_by_entries)
         rows_all = np.repeat(np.arange(n, dtype=np.int64), np.diff(row_ptr))
         off = rows_all != col
         blind = (np.arange(n, dtype=np.int64) * w.n_chunks // n)

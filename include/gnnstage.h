@@ -236,13 +236,16 @@ int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, int64_t n_ve
  * vertices, alpha = balance * sqrt(K) * m / n^1.5 with m the number of undirected edges (balance = 1 is the
  * published weight, 4 keeps the capacity from binding while the parts form); ties go to the lowest part;
  * self-loops are ignored.  The index must be symmetric for the edge count to mean what it says.
+ * by_entries != 0 counts balance in entries of the index (what a chunk costs to aggregate) instead of vertices:
+ * vertex v weighs its row length, n becomes the total weight in alpha and in the capacity, and v's balance term
+ * is multiplied by its weight; a part is open while it is below the capacity.
  * part (n): part of every vertex.  perm (n): perm[old id] = new id, part by part, index order kept inside a
  * part.  chunk_ptr (K + 1): the id ranges of the chunks after the renumbering.  gnnstage_permute_csr applies a
  * renumbering to an index (columns ascending inside every row).
  */
 int gnnstage_partition_chunks(int64_t n, const int64_t *row_ptr, const int32_t *col_idx, int32_t n_chunks,
-                              int32_t passes, double slack, double balance, int32_t *part, int32_t *perm,
-                              int64_t *chunk_ptr);
+                              int32_t passes, double slack, double balance, int32_t by_entries, int32_t *part,
+                              int32_t *perm, int64_t *chunk_ptr);
 int gnnstage_permute_csr(int64_t n, const int64_t *row_ptr, const int32_t *col_idx, const int32_t *perm,
                          int64_t *out_ptr, int32_t *out_idx);
 

@@ -17,6 +17,12 @@ here).  The stand-in is a published streaming heuristic, written out step by ste
 
 Ties go to the lowest part index; vertices arrive in index order; self-loops are ignored.  The parts
 become the chunks: vertices are renumbered part by part, in index order inside a part.
+
+Balance is counted in vertices, or (by_entries) in entries of the index, which is what a chunk costs to
+aggregate: vertex v then weighs w_v = its row length, a part's size is the sum of its weights, n becomes the
+total weight W in alpha and in the capacity ceil(nu * W / K), and the balance term of v is multiplied by w_v
+(the marginal cost of adding w_v to the part).  A part is open while its size is below the capacity, so the
+last vertex may overshoot by its own weight.
 """
 from __future__ import annotations
 
@@ -25,24 +31,29 @@ import math
 import numpy as np
 
 
-def partition_chunks(row_ptr: np.ndarray, col: np.ndarray, K: int, passes: int = 6, nu: float = 1.1, balance: float = 4.0):
+def partition_chunks(row_ptr: np.ndarray, col: np.ndarray, K: int, passes: int = 6, nu: float = 1.1, balance: float = 4.0,
+                     by_entries: bool = False):
     """Returns (part [n] int32, perm [n] int32 with perm[old id] = new id, chunk_ptr [K+1] int64)."""
     n = len(row_ptr) - 1
+    weight = [int(row_ptr[v + 1] - row_ptr[v]) if by_entries else 1 for v in range(n)]
+    total_w = sum(weight)
     deg_no_loops = 0
     for v in range(n):
         for e in range(row_ptr[v], row_ptr[v + 1]):
             if col[e] != v:
                 deg_no_loops += 1
     m = deg_no_loops / 2.0                       # a symmetric index lists every edge twice
-    alpha = balance * (math.sqrt(float(K)) * m / (float(n) * math.sqrt(float(n)))) if n > 0 else 0.0
-    cap = int(math.ceil(nu * n / K)) if n > 0 else 0
+    alpha = balance * (math.sqrt(float(K)) * m / (float(total_w) * math.sqrt(float(total_w)))) if total_w > 0 else 0.0
+    cap = int(math.ceil(nu * total_w / K)) if total_w > 0 else 0
     part = np.full(n, -1, dtype=np.int32)
-    size = [0] * K
+    size = [0] * K      # in weight units
+    count = [0] * K     # in vertices
     cnt = [0] * K
     for p in range(passes):
         for v in range(n):
             if part[v] >= 0:                     # restreaming: v leaves its part before it is scored
-                size[part[v]] -= 1
+                size[part[v]] -= weight[v]
+                count[part[v]] -= 1
                 part[v] = -1
             touched = []
             for e in range(row_ptr[v], row_ptr[v + 1]):
@@ -55,16 +66,17 @@ def partition_chunks(row_ptr: np.ndarray, col: np.ndarray, K: int, passes: int =
             for i in range(K):
                 if size[i] >= cap:
                     continue
-                score = float(cnt[i]) - alpha * 1.5 * math.sqrt(float(size[i]))
+                score = float(cnt[i]) - alpha * 1.5 * math.sqrt(float(size[i])) * float(weight[v])
                 if best < 0 or score > best_score:
                     best, best_score = i, score
             for i in touched:
                 cnt[i] = 0
             part[v] = best
-            size[best] += 1
+            size[best] += weight[v]
+            count[best] += 1
     chunk_ptr = np.zeros(K + 1, dtype=np.int64)
     for i in range(K):
-        chunk_ptr[i + 1] = chunk_ptr[i] + size[i]
+        chunk_ptr[i + 1] = chunk_ptr[i] + count[i]
     nxt = chunk_ptr[:-1].copy()
     perm = np.zeros(n, dtype=np.int32)
     for v in range(n):

@@ -121,7 +121,7 @@ def _load():
     lib.gnnstage_set_dropout_seed.argtypes = [C.c_void_p, C.c_uint64]
     lib.gnnstage_partition_chunks.restype = C.c_int
     lib.gnnstage_partition_chunks.argtypes = [C.c_int64, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_double,
-                                              C.c_void_p, C.c_void_p, C.c_void_p]
+                                              C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.gnnstage_permute_csr.restype = C.c_int
     lib.gnnstage_permute_csr.argtypes = [C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.gnnstage_query.restype = C.c_int64
@@ -227,7 +227,7 @@ def gnnstage_plan_tasks(ptr: np.ndarray, row_begin: int, row_end: int, split_edg
 
 
 def gnnstage_partition_chunks(row_ptr: np.ndarray, col_idx: np.ndarray, n_chunks: int, passes: int = 6, slack: float = 1.1,
-                              balance: float = 4.0):
+                              balance: float = 4.0, by_entries: bool = False):
     """Locality-aware chunks: returns (part, perm with perm[old id] = new id, chunk_ptr)."""
     row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int64)
     col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
@@ -235,7 +235,8 @@ def gnnstage_partition_chunks(row_ptr: np.ndarray, col_idx: np.ndarray, n_chunks
     part, perm = np.zeros(n, dtype=np.int32), np.zeros(n, dtype=np.int32)
     chunk_ptr = np.zeros(n_chunks + 1, dtype=np.int64)
     rc = lib.gnnstage_partition_chunks(n, row_ptr.ctypes.data, col_idx.ctypes.data, int(n_chunks), int(passes), float(slack),
-                                       float(balance), part.ctypes.data, perm.ctypes.data, chunk_ptr.ctypes.data)
+                                       float(balance), int(bool(by_entries)), part.ctypes.data, perm.ctypes.data,
+                                       chunk_ptr.ctypes.data)
     if rc != 0:
         raise GnnStageError(rc, "gnnstage_partition_chunks")
     return part, perm, chunk_ptr

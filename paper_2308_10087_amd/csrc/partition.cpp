@@ -5,6 +5,9 @@
 // each one leaving its part before it is scored against the parts as they stand.  Ties go to the lowest part,
 // vertices arrive in index order, self-loops are ignored.  The parts become the chunks: vertices are renumbered
 // part by part, keeping the index order inside a part.
+// Balance is counted in vertices or (by_entries) in entries of the index, which is what a chunk costs to aggregate:
+// vertex v then weighs its row length, n becomes the total weight W in alpha and in the capacity, and the balance
+// term of v is multiplied by its weight.  A part is open while it is below the capacity.
 #include <stdint.h>
 
 #include <cmath>
@@ -13,8 +16,8 @@
 #include "../../include/gnnstage.h"
 
 extern "C" int gnnstage_partition_chunks(int64_t n, const int64_t *row_ptr, const int32_t *col_idx, int32_t n_chunks,
-                                         int32_t passes, double slack, double balance, int32_t *part, int32_t *perm,
-                                         int64_t *chunk_ptr) {
+                                         int32_t passes, double slack, double balance, int32_t by_entries, int32_t *part,
+                                         int32_t *perm, int64_t *chunk_ptr) {
   if (n <= 0 || !row_ptr || n_chunks <= 0 || passes <= 0 || !part || !perm || !chunk_ptr) return GNNSTAGE_EINVAL;
   if (!(slack >= 1.0) || !(balance >= 0.0) || n > INT32_MAX) return GNNSTAGE_EINVAL;
   const int64_t nnz = row_ptr[n];
@@ -29,15 +32,19 @@ extern "C" int gnnstage_partition_chunks(int64_t n, const int64_t *row_ptr, cons
     }
   }
   const double m = (double)off_diagonal / 2.0;  // a symmetric index lists every edge twice
-  const double alpha = balance * (std::sqrt((double)K) * m / ((double)n * std::sqrt((double)n)));
-  const int64_t cap = (int64_t)std::ceil(slack * (double)n / (double)K);
-  std::vector<int64_t> size((size_t)K, 0);
+  const int64_t total_w = by_entries ? nnz : n;
+  if (total_w <= 0) return GNNSTAGE_EINVAL;
+  const double alpha = balance * (std::sqrt((double)K) * m / ((double)total_w * std::sqrt((double)total_w)));
+  const int64_t cap = (int64_t)std::ceil(slack * (double)total_w / (double)K);
+  std::vector<int64_t> size((size_t)K, 0), count((size_t)K, 0);
   std::vector<int32_t> cnt((size_t)K, 0), touched;
   for (int64_t v = 0; v < n; ++v) part[v] = -1;
   for (int p = 0; p < passes; ++p) {
     for (int64_t v = 0; v < n; ++v) {
+      const int64_t w = by_entries ? row_ptr[v + 1] - row_ptr[v] : 1;
       if (part[v] >= 0) {  // restreaming: v leaves its part before it is scored
-        size[(size_t)part[v]] -= 1;
+        size[(size_t)part[v]] -= w;
+        count[(size_t)part[v]] -= 1;
         part[v] = -1;
       }
       touched.clear();
@@ -50,19 +57,20 @@ extern "C" int gnnstage_partition_chunks(int64_t n, const int64_t *row_ptr, cons
       double best_score = 0.0;
       for (int i = 0; i < K; ++i) {
         if (size[(size_t)i] >= cap) continue;
-        const double score = (double)cnt[(size_t)i] - alpha * 1.5 * std::sqrt((double)size[(size_t)i]);
+        const double score = (double)cnt[(size_t)i] - alpha * 1.5 * std::sqrt((double)size[(size_t)i]) * (double)w;
         if (best < 0 || score > best_score) {
           best = i;
           best_score = score;
         }
       }
       for (int32_t i : touched) cnt[(size_t)i] = 0;
-      part[v] = best;  // the capacities add up to at least n, so some part always has room
-      size[(size_t)best] += 1;
+      part[v] = best;  // the capacities add up to at least the total weight, so some part is always open
+      size[(size_t)best] += w;
+      count[(size_t)best] += 1;
     }
   }
   chunk_ptr[0] = 0;
-  for (int i = 0; i < K; ++i) chunk_ptr[i + 1] = chunk_ptr[i] + size[(size_t)i];
+  for (int i = 0; i < K; ++i) chunk_ptr[i + 1] = chunk_ptr[i] + count[(size_t)i];
   std::vector<int64_t> next(chunk_ptr, chunk_ptr + K);
   for (int64_t v = 0; v < n; ++v) perm[v] = (int32_t)next[(size_t)part[v]]++;
   return GNNSTAGE_OK;

@@ -63,6 +63,8 @@ def test_chunk_partitioner_matches_the_oracle_bit_for_bit():
         (make_graph(CONFIGS["c3_s"]), 16, dict(passes=4, slack=1.3)),
         (graphs.erdos_renyi(200, 4.0, 5), 1, dict()),
         (graphs.erdos_renyi(97, 3.0, 6), 97, dict(passes=2, slack=1.0)),    # one vertex per chunk
+        (make_graph(CONFIGS["c1_s"]), 8, dict(by_entries=True)),
+        (make_graph(CONFIGS["c2_s"]), 16, dict(by_entries=True, passes=3, slack=1.05, balance=2.0)),
     ]
     for (row_ptr, col), K, kw in cases:
         part, perm, chunk_ptr = g.gnnstage_partition_chunks(row_ptr, col, K, **kw)

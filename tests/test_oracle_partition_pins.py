@@ -76,6 +76,27 @@ def test_planted_partition_is_recovered():
     assert edge_cut(row_ptr, col, blind) > 0.8
 
 
+def test_balance_counted_in_entries():
+    """Chunks that cost the same to aggregate: balance by the entries of the rows instead of by vertices."""
+    from synth.configs import CONFIGS, make_graph
+    row_ptr, col = make_graph(CONFIGS["c1_s"])         # power law: a vertex-balanced split is far from entry-balanced
+    K, nu = 8, 1.1
+    deg = np.diff(row_ptr)
+    by_v = partition_chunks(row_ptr, col, K, nu=nu)
+    by_e = partition_chunks(row_ptr, col, K, nu=nu, by_entries=True)
+    w_v = np.bincount(by_v[0], weights=deg, minlength=K)
+    w_e = np.bincount(by_e[0], weights=deg, minlength=K)
+    assert w_v.max() > 2.5 * w_v.mean()                # hubs cluster when only vertices are counted
+    assert w_e.max() <= np.ceil(nu * deg.sum() / K) + deg.max()   # a part is open below the capacity: one row may overshoot
+    assert w_e.max() < 1.15 * w_e.mean()
+    _check_shape(row_ptr, by_e[0], by_e[1], by_e[2], K, nu=10.0)  # a valid renumbering (vertex counts are free here)
+    assert edge_cut(row_ptr, col, by_e[0]) < 0.95 * (1 - 1 / K)    # still better than index ranges of random numbers
+    # on a graph of even degrees the two notions agree: the planted partition is recovered either way
+    rp, c, group = graphs.planted_partition(4000, 8, 12.0, 1.5, 5)
+    pe = partition_chunks(rp, c, 8, by_entries=True)
+    assert edge_cut(rp, c, pe[0]) <= 1.05 * edge_cut(rp, c, group)
+
+
 def test_one_chunk_and_repeatability():
     row_ptr, col = graphs.erdos_renyi(300, 6.0, 3)
     part, perm, chunk_ptr = partition_chunks(row_ptr, col, 1)
