@@ -232,7 +232,7 @@ def main():
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
     traffic = None  # HBM-side bytes per launch from the committed rocprofv3 counter summary, if it covers this kernel
     tpath = os.path.join(ROOT, "profiles", f"stage_{w.name}_pmc_traffic.md")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and not args.partition:  # the counters were read on the benchmark configuration only
         for line in open(tpath):
             parts = [x.strip() for x in line.split("|")]
             if len(parts) == 3 and parts[0] == f"traffic {w.name}" and parts[1] == dom_name:
