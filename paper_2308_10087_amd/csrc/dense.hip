@@ -23,10 +23,12 @@ namespace {
 typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int A_PITCH = 72;  // bf16 elements per weight-tile row in LDS: 144 bytes keep 16-byte fragment reads conflict-free
 constexpr int DH = 128;      // columns one workgroup owns
 constexpr int TILE_ELEMS = kDenseRB * kDenseCB;  // one weight tile in memory (row-major, no padding)
+constexpr int HQ_BUF = (kDenseCB / 8) * DH;      // 16-byte words of one source-row buffer of the pattern kernel
 
 __device__ inline bool masks_meet(const ChunkMask &x, const ChunkMask &y) {
   return ((x.w[0] & y.w[0]) | (x.w[1] & y.w[1]) | (x.w[2] & y.w[2]) | (x.w[3] & y.w[3])) != 0;
@@ -189,55 +191,68 @@ __global__ __launch_bounds__(256, 2) void spmm_dense_kernel(const DenseArgs a) {
 }
 
 // The same product for weights of the form w(v, u) = s(v) * s(u) (the normalisation of Section 2.1 computed
-// by the library itself).  A block is then a 0/1 pattern, kept as 128 x 64 bits; the weight tiles are made
-// in LDS from the pattern and the 64 column scales (each split into the nearest bf16 and the bf16 of the
-// remainder), and the accumulator rows are scaled by s(v) at the end:
+// by the library itself).  A block is then a 0/1 pattern, kept as 128 x 64 bits, and
 //     out[v] = s(v) * sum_u P(v, u) * s(u) * h(u).
-// Per item everything that does not depend on the block's data is resolved once: the column slots become
-// (vertex | selected << 31), padding slots and - in a backward launch - unselected sources become 0xffffffff
-// (their rows count as zero), and the column scales of all its blocks sit in LDS as ready-made bf16 pairs.
+// What this kernel has to save is vector instructions: a matrix instruction keeps a SIMD's vector port busy
+// for about half of its 32 cycles, so a loop with more than four vector instructions per matrix instruction
+// is bound by instruction issue, not by the matrix cores.
+//  * A wave owns 32 rows x 128 columns of the accumulator tile, so the A operand of its products is private
+//    to it and never goes through LDS: a lane keeps the 64 pattern bits of its row in two registers and
+//    makes each A fragment of v_mfma_f32_32x32x16_bf16 (its row, eight consecutive columns) by masking the
+//    packed column scales (nearest bf16 and the bf16 of the remainder, one broadcast 16-byte LDS word each)
+//    with the masks of the pattern byte, which come from a 256-entry table in LDS.
+//  * The 64 source rows of a block are loaded row-wise: a wave takes 16 of them, a lane two columns of each
+//    (one 256-byte request per row; the row's address is a broadcast LDS read of a table resolved once per
+//    item: current or historical buffer by the source's chunk, a row of zeros for padding slots and - in a
+//    backward launch - unselected sources).  A lane then holds its columns of eight consecutive source pairs,
+//    i.e. two complete B fragments per column, and stores them as 16-byte words [quad of pairs][column]; a B
+//    fragment is one 16-byte read.
+//  * The source rows alternate between two LDS buffers, which leaves one barrier per block.
 __global__ __launch_bounds__(256, 2) void spmm_dense_r1_kernel(const DenseArgs a) {
-  constexpr int NI = 2;
-  constexpr int GROUPS = DH / 8;
-  constexpr int SETS = 64 / GROUPS;
-  constexpr int PPL = 8 / SETS;
-  constexpr int S = 3;  // blocks whose loads are in flight (register slots)
+  constexpr int NI = DH / 32;
+  constexpr int S = 3;              // blocks whose loads are in flight (register slots)
+  constexpr int CP = kDenseCB / 2;  // column pairs of a block
+  constexpr int WR = kDenseCB / 4;  // source rows one wave loads
+  static_assert(DH == 128 && kDenseCB == 64 && kDenseRB == 128, "lane mapping below");
   extern __shared__ __attribute__((aligned(16))) unsigned char dense_smem[];
-  bf16_t *A_hi = reinterpret_cast<bf16_t *>(dense_smem);                   // [128][A_PITCH]
-  bf16_t *A_lo = A_hi + kDenseRB * A_PITCH;
-  uint32_t *Hp = reinterpret_cast<uint32_t *>(A_lo + kDenseRB * A_PITCH);  // [32 source pairs][DH] interleaved pairs
-  uint32_t *ids = Hp + 32 * DH;                                           // [blocks][64] resolved column slots
-  uint32_t *cs = ids + kDenseMaxItemBlocks * kDenseCB;                    // [blocks][32 column pairs][2]: upper parts, lower parts
-  int32_t *m_cb = reinterpret_cast<int32_t *>(cs + kDenseMaxItemBlocks * kDenseCB);
-  int32_t *act = m_cb + kDenseMaxItemBlocks;                              // the item's selected blocks, in order
+  u32x4 *Hq = reinterpret_cast<u32x4 *>(dense_smem);                    // [2 buffers][8 quads][DH]: pairs 4q .. 4q+3 of one column
+  uint64_t *rows = reinterpret_cast<uint64_t *>(Hq + 2 * HQ_BUF);       // [blocks][64] address of every source row (at column col0)
+  uint32_t *cs_hi = reinterpret_cast<uint32_t *>(rows + kDenseMaxItemBlocks * kDenseCB);  // [blocks][32 column pairs]: nearest bf16 of the two scales
+  uint32_t *cs_lo = cs_hi + kDenseMaxItemBlocks * CP;                   // the same for the remainders
+  uint32_t *lut = cs_lo + kDenseMaxItemBlocks * CP;                     // [256][4]: pattern byte -> 16-bit masks of its eight cells
+  int32_t *m_cb = reinterpret_cast<int32_t *>(lut + 256 * 4);
+  int32_t *act = m_cb + kDenseMaxItemBlocks;                            // the item's selected blocks, in order
 
   const int item = blockIdx.x;
   const int col0 = blockIdx.y * DH;
   const bool drop = a.src_unsel == nullptr;
   if (drop && !masks_meet(a.item_chunks[item], a.mask)) return;  // whole workgroup
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  const int wm = wave * 32, g = lane >> 5, r32 = lane & 31;
   const uint32_t vmask = (1u << a.vbits) - 1u;
   const int64_t b0 = a.item_b0[item];
   const int nb = a.item_nb[item];
   const bf16_t *src_sel = static_cast<const bf16_t *>(a.src_sel) + col0;
   const bf16_t *src_unsel = drop ? src_sel : static_cast<const bf16_t *>(a.src_unsel) + col0;
   const size_t ld = (size_t)a.src_ld;
-  const bf16_t *zrow = static_cast<const bf16_t *>(a.zero_row);  // 128 zeros are enough for any column half
+  const uint64_t zrow = reinterpret_cast<uint64_t>(a.zero_row);  // 128 zeros are enough for any column half
 
   if (tid < nb) m_cb[tid] = a.blk_cb[b0 + tid];
+#pragma unroll
+  for (int t = 0; t < 4; ++t)  // cells 2t (lower half-word) and 2t + 1 of pattern byte tid
+    lut[tid * 4 + t] = ((((uint32_t)tid >> (2 * t)) & 1u) ? 0xffffu : 0u) | ((((uint32_t)tid >> (2 * t + 1)) & 1u) ? 0xffff0000u : 0u);
   __syncthreads();
   for (int i = tid; i < nb * kDenseCB; i += 256) {
     const int64_t slot = (int64_t)m_cb[i >> 6] * kDenseCB + (i & 63);
     const uint32_t pc = a.colslot[slot];
-    uint32_t id = 0xffffffffu;
+    uint64_t addr = zrow;
     if (pc != 0xffffffffu) {
       const bool sel = mask_test(a.mask, pc >> a.vbits);
-      if (sel || !drop) id = (pc & vmask) | (sel ? 0x80000000u : 0u);
+      if (sel || !drop) addr = reinterpret_cast<uint64_t>((sel ? src_sel : src_unsel) + (size_t)(pc & vmask) * ld);
     }
-    ids[i] = id;
+    rows[i] = addr;
   }
-  for (int i = tid; i < nb * (kDenseCB / 2); i += 256) {  // column pair (2i, 2i + 1) of a block
+  for (int i = tid; i < nb * CP; i += 256) {  // column pair (2i, 2i + 1) of a block
     const int64_t slot = (int64_t)m_cb[i >> 5] * kDenseCB + 2 * (i & 31);
     uint32_t part[2][2];  // [column of the pair][upper, lower]
 #pragma unroll
@@ -248,12 +263,12 @@ __global__ __launch_bounds__(256, 2) void spmm_dense_r1_kernel(const DenseArgs a
       part[c][0] = __builtin_bit_cast(uint16_t, h);
       part[c][1] = __builtin_bit_cast(uint16_t, l);
     }
-    cs[2 * i] = part[0][0] | (part[1][0] << 16);
-    cs[2 * i + 1] = part[0][1] | (part[1][1] << 16);
+    cs_hi[i] = part[0][0] | (part[1][0] << 16);
+    cs_lo[i] = part[0][1] | (part[1][1] << 16);
   }
   __syncthreads();
-  if (wave == 0) {  // a block whose first slot resolved to "zero row" in a backward launch has no selected source
-    const bool on = lane < nb && (!drop || ids[(lane < nb ? lane : 0) * kDenseCB] != 0xffffffffu);
+  if (wave == 0) {  // a block whose first slot resolved to the row of zeros in a backward launch has no selected source
+    const bool on = lane < nb && (!drop || rows[(lane < nb ? lane : 0) * kDenseCB] != zrow);
     const uint64_t bal = __ballot(on);
     if (on) act[__popcll(bal & ((1ull << lane) - 1ull))] = lane;
     if (lane == 0) act[kDenseMaxItemBlocks] = __popcll(bal);
@@ -261,116 +276,72 @@ __global__ __launch_bounds__(256, 2) void spmm_dense_r1_kernel(const DenseArgs a
   __syncthreads();
   const int na = act[kDenseMaxItemBlocks];
 
-  f32x16 acc[2][NI];
+  f32x16 acc[NI];
 #pragma unroll
-  for (int mi = 0; mi < 2; ++mi)
+  for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-      for (int t = 0; t < 16; ++t) acc[mi][ni][t] = 0.f;
+    for (int t = 0; t < 16; ++t) acc[ni][t] = 0.f;
 
-  const int ng = lane % GROUPS, set = lane / GROUPS;
-  // register slots: slot u carries the active block i with i % S == u from its loads to LDS.  Every load is
-  // unconditional (a zero row reads a row of zeros), so the number of younger loads at every
-  // wait is a compile-time constant.
-  u32x4 x0[S][PPL], x1[S][PPL];
-  uint32_t bits[S];  // this thread's 32 cells of the pattern: row tid / 2, columns 32 * (tid % 2) ..
+  // register slots: slot u carries the active block i with i % S == u from its loads to its products.  Every
+  // load is unconditional, so the number of younger loads at every wait is a compile-time constant.
+  uint32_t x[S][WR];  // columns 2 lane, 2 lane + 1 of the wave's source rows
+  u32x2 bits[S];      // the pattern of this lane's row: columns 0..31, 32..63
   auto issue = [&](int bi, int u) {
-    bits[u] = a.bits[(size_t)(b0 + bi) * 256 + tid];
+    bits[u] = *reinterpret_cast<const u32x2 *>(a.bits + (size_t)(b0 + bi) * 256 + 2 * (wm + r32));
+    const uint64_t *rp = rows + bi * kDenseCB + wave * WR;  // the same for all lanes: broadcast reads
 #pragma unroll
-    for (int j = 0; j < PPL; ++j) {
-      const int kp = wave * 8 + j * SETS + set;
-      const uint32_t i0 = ids[bi * kDenseCB + 2 * kp], i1 = ids[bi * kDenseCB + 2 * kp + 1];
-      const bool z0 = i0 == 0xffffffffu, z1 = i1 == 0xffffffffu;  // zero rows are read from a row of zeros
-      const bf16_t *r0 = z0 ? zrow : ((i0 >> 31) ? src_sel : src_unsel) + (size_t)(i0 & 0x7fffffffu) * ld;
-      const bf16_t *r1 = z1 ? zrow : ((i1 >> 31) ? src_sel : src_unsel) + (size_t)(i1 & 0x7fffffffu) * ld;
-      x0[u][j] = *reinterpret_cast<const u32x4 *>(r0 + ng * 8);
-      x1[u][j] = *reinterpret_cast<const u32x4 *>(r1 + ng * 8);
-    }
+    for (int r = 0; r < WR; ++r)  // device memory, said so: a generic load would also count as an LDS access in the waits
+      x[u][r] = *reinterpret_cast<const __attribute__((address_space(1))) uint32_t *>(rp[r] + 4u * (uint32_t)lane);
     __builtin_amdgcn_sched_barrier(0);  // keep the slots' loads in program order (the waits count younger loads)
   };
-  auto consume = [&](int bi, int u) {
-    __syncthreads();  // the previous block's fragment reads are done
-    {  // weight tiles from the pattern: cell (r, c) = bit ? scale part of column c : 0
-      const uint32_t w = bits[u];
-      const u32x4 *cp = reinterpret_cast<const u32x4 *>(cs + (size_t)bi * kDenseCB + (tid & 1) * 32);
-      u32x4 *dh = reinterpret_cast<u32x4 *>(A_hi + (tid >> 1) * A_PITCH + (tid & 1) * 32);
-      u32x4 *dl = reinterpret_cast<u32x4 *>(A_lo + (tid >> 1) * A_PITCH + (tid & 1) * 32);
-      u32x4 cw[8];  // all reads first: one LDS latency instead of four
+  // source rows of slot u -> buffer H: the wave's rows are pairs 8 wave .. 8 wave + 7, i.e. quads 2 wave, 2 wave + 1
+  auto stage = [&](int u, u32x4 *H) {
 #pragma unroll
-      for (int q = 0; q < 8; ++q) cw[q] = cp[q];
+    for (int q = 0; q < 2; ++q) {
+      u32x4 even, odd;  // columns 2 lane and 2 lane + 1: (row 2p | row 2p + 1 << 16) for the quad's four pairs p
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {  // 8 columns = 4 pairs
-        const u32x4 c0 = cw[2 * q], c1 = cw[2 * q + 1];  // pairs 4q, 4q+1 | 4q+2, 4q+3: (upper, lower) each
-        u32x4 vh, vl;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const int m0 = __builtin_amdgcn_sbfe(w, 8 * q + 2 * t, 1), m1 = __builtin_amdgcn_sbfe(w, 8 * q + 2 * t + 1, 1);
-          const uint32_t mask = ((uint32_t)m0 & 0xffffu) | ((uint32_t)m1 & 0xffff0000u);
-          const uint32_t up = t < 2 ? c0[2 * t] : c1[2 * (t - 2)], lw = t < 2 ? c0[2 * t + 1] : c1[2 * (t - 2) + 1];
-          vh[t] = up & mask;
-          vl[t] = lw & mask;
-        }
-        dh[q] = vh;
-        dl[q] = vl;
+      for (int t = 0; t < 4; ++t) {
+        const uint32_t p0 = x[u][8 * q + 2 * t], p1 = x[u][8 * q + 2 * t + 1];
+        even[t] = __builtin_amdgcn_perm(p1, p0, 0x05040100u);
+        odd[t] = __builtin_amdgcn_perm(p1, p0, 0x07060302u);
       }
+      u32x4 *dst = H + (2 * wave + q) * DH + 2 * lane;
+      dst[0] = even;
+      dst[1] = odd;
     }
-    // source rows: word n of pair kp holds (row 2kp, row 2kp+1) at column n
-#pragma unroll
-    for (int j = 0; j < PPL; ++j) {
-      const int kp = wave * 8 + j * SETS + set;
-      u32x4 lo4, hi4;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const uint32_t p0 = x0[u][j][q], p1 = x1[u][j][q];
-        const uint32_t even = __builtin_amdgcn_perm(p1, p0, 0x05040100u), odd = __builtin_amdgcn_perm(p1, p0, 0x07060302u);
-        if (q < 2) {
-          lo4[2 * q] = even;
-          lo4[2 * q + 1] = odd;
-        } else {
-          hi4[2 * (q - 2)] = even;
-          hi4[2 * (q - 2) + 1] = odd;
-        }
-      }
-      u32x4 *dst = reinterpret_cast<u32x4 *>(Hp + (size_t)kp * DH + ng * 8);
-      dst[0] = lo4;
-      dst[1] = hi4;
-    }
-    __syncthreads();  // weights and source rows are in place
   };
-  // fragments of the next k-step are read from LDS while the current one is multiplied
-  auto multiply = [&]() {
-    bf16x8 fh[2][2], fl[2][2], fb[2][NI];
+  // acc += (pattern . upper scales) H + (pattern . lower scales) H; the operands of the next k-step are read
+  // from LDS while the current one is multiplied
+  auto multiply = [&](int bi, u32x2 w, const u32x4 *H) {
+    const uint32_t wsh[2] = {w[0] >> (8 * g), w[1] >> (8 * g)};  // this lane's eight columns of a k-step start at bit 0 / 16
+    const u32x4 *ch = reinterpret_cast<const u32x4 *>(cs_hi + bi * CP + g * 4);
+    const u32x4 *cl = reinterpret_cast<const u32x4 *>(cs_lo + bi * CP + g * 4);
+    u32x4 fb[2][NI], sh[2], sl[2], m4[2];
     auto frags = [&](int ks, int f) {
-      const int koff = ks * 16 + (lane >> 5) * 8;
+      const uint32_t byte = __builtin_amdgcn_ubfe(wsh[ks >> 1], (ks & 1) * 16, 8);  // this lane's eight cells
+      m4[f] = *reinterpret_cast<const u32x4 *>(lut + byte * 4);
+      sh[f] = ch[2 * ks];
+      sl[f] = cl[2 * ks];
 #pragma unroll
-      for (int mi = 0; mi < 2; ++mi) {
-        fh[f][mi] = *reinterpret_cast<const bf16x8 *>(&A_hi[(wm + mi * 32 + (lane & 31)) * A_PITCH + koff]);
-        fl[f][mi] = *reinterpret_cast<const bf16x8 *>(&A_lo[(wm + mi * 32 + (lane & 31)) * A_PITCH + koff]);
-      }
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni) {
-        u32x4 w4;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) w4[j] = Hp[(size_t)(ks * 8 + (lane >> 5) * 4 + j) * DH + wn + ni * 32 + (lane & 31)];
-        fb[f][ni] = __builtin_bit_cast(bf16x8, w4);
-      }
+      for (int ni = 0; ni < NI; ++ni) fb[f][ni] = H[(2 * ks + g) * DH + ni * 32 + r32];
     };
     frags(0, 0);
 #pragma unroll
     for (int ks = 0; ks < kDenseCB / 16; ++ks) {
       const int f = ks & 1;
       if (ks + 1 < kDenseCB / 16) frags(ks + 1, f ^ 1);
+      const bf16x8 fh = __builtin_bit_cast(bf16x8, sh[f] & m4[f]), fl = __builtin_bit_cast(bf16x8, sl[f] & m4[f]);
 #pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
+      for (int ni = 0; ni < NI; ++ni)
+        acc[ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fh, __builtin_bit_cast(bf16x8, fb[f][ni]), acc[ni], 0, 0, 0);
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fh[f][mi], fb[f][ni], acc[mi][ni], 0, 0, 0);
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni) acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fl[f][mi], fb[f][ni], acc[mi][ni], 0, 0, 0);
+      for (int ni = 0; ni < NI; ++ni)
+        acc[ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fl, __builtin_bit_cast(bf16x8, fb[f][ni]), acc[ni], 0, 0, 0);
     }
   };
+  // Block number idx of the item uses buffer idx % 2.  A wave that stores block idx + 2 has passed the barrier of
+  // block idx + 1, which every wave reaches only after its products of block idx: one barrier per block is enough.
+  auto buffer = [&](int idx) { return Hq + (idx & 1) * HQ_BUF; };
 
   // prologue, steady groups of S blocks (every refill unconditional), tail
   int i = 0;
@@ -380,9 +351,11 @@ __global__ __launch_bounds__(256, 2) void spmm_dense_r1_kernel(const DenseArgs a
     for (; i + 2 * S <= na; i += S) {
 #pragma unroll
       for (int u = 0; u < S; ++u) {
-        consume(act[i + u], u);
+        const u32x2 w = bits[u];
+        stage(u, buffer(i + u));
+        __syncthreads();  // the source rows are in place
         issue(act[i + S + u], u);
-        multiply();
+        multiply(act[i + u], w, buffer(i + u));
       }
     }
   } else {
@@ -394,23 +367,26 @@ __global__ __launch_bounds__(256, 2) void spmm_dense_r1_kernel(const DenseArgs a
 #pragma unroll
     for (int u = 0; u < S; ++u) {
       if (i + u < na) {
-        consume(act[i + u], u);
+        const u32x2 w = bits[u];
+        stage(u, buffer(i + u));
+        __syncthreads();
         if (i + S + u < na) issue(act[i + S + u], u);
-        multiply();
+        multiply(act[i + u], w, buffer(i + u));
       }
     }
   }
   float *P = a.partial + (size_t)item * kDenseRB * a.d + col0;
   const float *rs = a.rowscale + (size_t)a.item_rb[item] * kDenseRB;  // zero past the last row of the chunk
+  float rsv[16];  // all loads before the first store: the stores may alias them for all the compiler knows
 #pragma unroll
-  for (int mi = 0; mi < 2; ++mi)
+  for (int t = 0; t < 16; ++t) rsv[t] = rs[wm + 8 * (t >> 2) + 4 * g + (t & 3)];
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
+  for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-      for (int t = 0; t < 16; ++t) {
-        const int r = wm + mi * 32 + 8 * (t >> 2) + 4 * (lane >> 5) + (t & 3);
-        P[(size_t)r * a.d + wn + ni * 32 + (lane & 31)] = acc[mi][ni][t] * rs[r];
-      }
+    for (int t = 0; t < 16; ++t) {
+      const int r = wm + 8 * (t >> 2) + 4 * g + (t & 3);
+      P[(size_t)r * a.d + ni * 32 + r32] = acc[ni][t] * rsv[t];
+    }
 }
 
 }  // namespace
@@ -427,8 +403,8 @@ int launch_spmm_dense(const DenseArgs &a, hipStream_t s) {
     attr_done = true;
   }
   if (a.bits) {
-    const size_t smem1 = (size_t)2 * kDenseRB * A_PITCH * sizeof(bf16_t) + (size_t)32 * DH * sizeof(uint32_t) +
-                         (size_t)2 * kDenseMaxItemBlocks * kDenseCB * sizeof(uint32_t) + (2 * kDenseMaxItemBlocks + 1) * sizeof(int32_t);
+    const size_t smem1 = (size_t)2 * HQ_BUF * 16 + (size_t)kDenseMaxItemBlocks * kDenseCB * (sizeof(uint64_t) + sizeof(uint32_t)) +
+                         (size_t)256 * 4 * sizeof(uint32_t) + (2 * kDenseMaxItemBlocks + 1) * sizeof(int32_t);
     static bool attr1_done = false;
     if (!attr1_done) {
       (void)hipFuncSetAttribute(reinterpret_cast<const void *>(spmm_dense_r1_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
