@@ -242,29 +242,48 @@ __global__ __launch_bounds__(256, 2) void spmm_dense_r1_kernel(const DenseArgs a
   for (int t = 0; t < 4; ++t)  // cells 2t (lower half-word) and 2t + 1 of pattern byte tid
     lut[tid * 4 + t] = ((((uint32_t)tid >> (2 * t)) & 1u) ? 0xffffu : 0u) | ((((uint32_t)tid >> (2 * t + 1)) & 1u) ? 0xffff0000u : 0u);
   __syncthreads();
-  for (int i = tid; i < nb * kDenseCB; i += 256) {
-    const int64_t slot = (int64_t)m_cb[i >> 6] * kDenseCB + (i & 63);
-    const uint32_t pc = a.colslot[slot];
-    uint64_t addr = zrow;
-    if (pc != 0xffffffffu) {
-      const bool sel = mask_test(a.mask, pc >> a.vbits);
-      if (sel || !drop) addr = reinterpret_cast<uint64_t>((sel ? src_sel : src_unsel) + (size_t)(pc & vmask) * ld);
-    }
-    rows[i] = addr;
-  }
-  for (int i = tid; i < nb * CP; i += 256) {  // column pair (2i, 2i + 1) of a block
-    const int64_t slot = (int64_t)m_cb[i >> 5] * kDenseCB + 2 * (i & 31);
-    uint32_t part[2][2];  // [column of the pair][upper, lower]
+  {  // all loads of the two tables first, in one round trip: up to 8 column slots and 4 column pairs per thread
+    constexpr int NQ = kDenseMaxItemBlocks * kDenseCB / 256, NP = kDenseMaxItemBlocks * CP / 256;
+    uint32_t pc[NQ];
+    float sc[NP][2];
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
-      const float sc = a.colscale[slot + c];  // zero for padding slots
-      const bf16_t h = (bf16_t)sc;
-      const bf16_t l = (bf16_t)(sc - (float)h);
-      part[c][0] = __builtin_bit_cast(uint16_t, h);
-      part[c][1] = __builtin_bit_cast(uint16_t, l);
+    for (int q = 0; q < NQ; ++q) {
+      const int i = tid + 256 * q;
+      pc[q] = i < nb * kDenseCB ? a.colslot[(int64_t)m_cb[i >> 6] * kDenseCB + (i & 63)] : 0xffffffffu;
     }
-    cs_hi[i] = part[0][0] | (part[1][0] << 16);
-    cs_lo[i] = part[0][1] | (part[1][1] << 16);
+#pragma unroll
+    for (int q = 0; q < NP; ++q) {  // column pair (2i, 2i + 1) of a block; the scale of a padding slot is zero
+      const int i = tid + 256 * q;
+      const int64_t slot = i < nb * CP ? (int64_t)m_cb[i >> 5] * kDenseCB + 2 * (i & 31) : 0;
+      sc[q][0] = a.colscale[slot];
+      sc[q][1] = a.colscale[slot + 1];
+    }
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+      const int i = tid + 256 * q;
+      uint64_t addr = zrow;
+      if (pc[q] != 0xffffffffu) {
+        const bool sel = mask_test(a.mask, pc[q] >> a.vbits);
+        if (sel || !drop) addr = reinterpret_cast<uint64_t>((sel ? src_sel : src_unsel) + (size_t)(pc[q] & vmask) * ld);
+      }
+      if (i < nb * kDenseCB) rows[i] = addr;
+    }
+#pragma unroll
+    for (int q = 0; q < NP; ++q) {
+      const int i = tid + 256 * q;
+      uint32_t part[2][2];  // [column of the pair][upper, lower]
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const bf16_t h = (bf16_t)sc[q][c];
+        const bf16_t l = (bf16_t)(sc[q][c] - (float)h);
+        part[c][0] = __builtin_bit_cast(uint16_t, h);
+        part[c][1] = __builtin_bit_cast(uint16_t, l);
+      }
+      if (i < nb * CP) {
+        cs_hi[i] = part[0][0] | (part[1][0] << 16);
+        cs_lo[i] = part[0][1] | (part[1][1] << 16);
+      }
+    }
   }
   __syncthreads();
   if (wave == 0) {  // a block whose first slot resolved to the row of zeros in a backward launch has no selected source
