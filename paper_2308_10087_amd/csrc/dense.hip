@@ -24,6 +24,7 @@ typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int A_PITCH = 72;  // bf16 elements per weight-tile row in LDS: 144 bytes keep 16-byte fragment reads conflict-free
 constexpr int DH = 128;      // columns one workgroup owns
@@ -205,8 +206,10 @@ __global__ __launch_bounds__(256, 2) void spmm_dense_kernel(const DenseArgs a) {
 //    (one 256-byte request per row; the row's address is a broadcast LDS read of a table resolved once per
 //    item: current or historical buffer by the source's chunk, a row of zeros for padding slots and - in a
 //    backward launch - unselected sources).  A lane then holds its columns of eight consecutive source pairs,
-//    i.e. two complete B fragments per column, and stores them as 16-byte words [quad of pairs][column]; a B
-//    fragment is one 16-byte read.
+//    i.e. two complete B fragments per column, and stores them as 16-byte words [quad of pairs][column slot]; a
+//    B fragment is one 16-byte read.  Column slot s holds column 2s (s < 64) or 2(s - 64) + 1, so that the lanes
+//    of a store and of a read touch consecutive words (no bank conflicts); the accumulator tiles inherit that
+//    order and tiles ni, ni + 2 leave as pairs of neighbouring columns.
 //  * The source rows alternate between two LDS buffers, which leaves one barrier per block.
 __global__ __launch_bounds__(256, 2) void spmm_dense_r1_kernel(const DenseArgs a) {
   constexpr int NI = DH / 32;
@@ -324,9 +327,9 @@ __global__ __launch_bounds__(256, 2) void spmm_dense_r1_kernel(const DenseArgs a
         even[t] = __builtin_amdgcn_perm(p1, p0, 0x05040100u);
         odd[t] = __builtin_amdgcn_perm(p1, p0, 0x07060302u);
       }
-      u32x4 *dst = H + (2 * wave + q) * DH + 2 * lane;
+      u32x4 *dst = H + (2 * wave + q) * DH + lane;  // column slots: the even columns first, then the odd ones
       dst[0] = even;
-      dst[1] = odd;
+      dst[DH / 2] = odd;
     }
   };
   // acc += (pattern . upper scales) H + (pattern . lower scales) H; the operands of the next k-step are read
@@ -400,11 +403,11 @@ __global__ __launch_bounds__(256, 2) void spmm_dense_r1_kernel(const DenseArgs a
 #pragma unroll
   for (int t = 0; t < 16; ++t) rsv[t] = rs[wm + 8 * (t >> 2) + 4 * g + (t & 3)];
 #pragma unroll
-  for (int ni = 0; ni < NI; ++ni)
+  for (int ni = 0; ni < NI / 2; ++ni)  // tile ni holds the even columns 2 (32 ni + lane), tile ni + 2 the odd ones next to them
 #pragma unroll
     for (int t = 0; t < 16; ++t) {
       const int r = wm + 8 * (t >> 2) + 4 * g + (t & 3);
-      P[(size_t)r * a.d + ni * 32 + r32] = acc[ni][t] * rsv[t];
+      *reinterpret_cast<f32x2 *>(&P[(size_t)r * a.d + 2 * (ni * 32 + r32)]) = f32x2{acc[ni][t] * rsv[t], acc[ni + 2][t] * rsv[t]};
     }
 }
 
