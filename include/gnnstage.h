@@ -242,6 +242,9 @@ int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, int64_t n_ve
  * part (n): part of every vertex.  perm (n): perm[old id] = new id, part by part, index order kept inside a
  * part.  chunk_ptr (K + 1): the id ranges of the chunks after the renumbering.  gnnstage_permute_csr applies a
  * renumbering to an index (columns ascending inside every row).
+ * All arrays are HOST memory owned by the caller.  GNNSTAGE_EINVAL for NULL arrays, n < 1, n_chunks < 1, passes < 1,
+ * slack < 1, balance < 0, an index entry outside [0, n), or by_entries on an index without entries.  Parts may stay
+ * empty (chunks of no vertices), e.g. when n_chunks > n.
  */
 int gnnstage_partition_chunks(int64_t n, const int64_t *row_ptr, const int32_t *col_idx, int32_t n_chunks,
                               int32_t passes, double slack, double balance, int32_t by_entries, int32_t *part,

@@ -37,14 +37,16 @@ def partition_chunks(row_ptr: np.ndarray, col: np.ndarray, K: int, passes: int =
     n = len(row_ptr) - 1
     weight = [int(row_ptr[v + 1] - row_ptr[v]) if by_entries else 1 for v in range(n)]
     total_w = sum(weight)
+    if total_w <= 0:
+        raise ValueError("nothing to balance: the index has no entries")
     deg_no_loops = 0
     for v in range(n):
         for e in range(row_ptr[v], row_ptr[v + 1]):
             if col[e] != v:
                 deg_no_loops += 1
     m = deg_no_loops / 2.0                       # a symmetric index lists every edge twice
-    alpha = balance * (math.sqrt(float(K)) * m / (float(total_w) * math.sqrt(float(total_w)))) if total_w > 0 else 0.0
-    cap = int(math.ceil(nu * total_w / K)) if total_w > 0 else 0
+    alpha = balance * (math.sqrt(float(K)) * m / (float(total_w) * math.sqrt(float(total_w))))
+    cap = int(math.ceil(nu * total_w / K))
     part = np.full(n, -1, dtype=np.int32)
     size = [0] * K      # in weight units
     count = [0] * K     # in vertices

@@ -83,6 +83,16 @@ def test_chunk_partitioner_matches_the_oracle_bit_for_bit():
     assert edge_cut(row_ptr, col, part) < 0.3 * edge_cut(row_ptr, col, blind)
     with pytest.raises(g.GnnStageError):
         g.gnnstage_permute_csr(row_ptr, col, np.zeros(3000, dtype=np.int32))     # not a permutation
+    empty = np.zeros(8, dtype=np.int64)                 # seven vertices, no entries: nothing to balance by entries
+    none = np.zeros(0, dtype=np.int32)
+    with pytest.raises(g.GnnStageError):
+        g.gnnstage_partition_chunks(empty, none, 2, by_entries=True)
+    with pytest.raises(ValueError):
+        partition_chunks(empty, none, 2, by_entries=True)
+    part, perm, chunk_ptr = g.gnnstage_partition_chunks(empty, none, 9)          # more chunks than vertices
+    rpart, rperm, rchunk = partition_chunks(empty, none, 9)
+    assert np.array_equal(part, rpart) and np.array_equal(perm, rperm) and np.array_equal(chunk_ptr, rchunk)
+    assert chunk_ptr[-1] == 7 and sorted(perm.tolist()) == list(range(7))
 
 
 def test_transposed_index_is_the_exact_transpose():
