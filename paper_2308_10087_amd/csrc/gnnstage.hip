@@ -1136,7 +1136,7 @@ extern "C" size_t gnnstage_workspace_size(const gnnstage_desc *desc) {
     g_create_error = err;
     return 0;
   }
-  return make_layout(s, hp.f, hp.b, desc->edge_val == nullptr && !s.sage()).total;
+  return make_layout(s, hp.f, hp.b, desc->edge_val == nullptr).total;
 }
 
 extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
@@ -1145,8 +1145,10 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
   Shape s;
   std::string err;
   if (!read_shape(d, s, err)) return fail(nullptr, GNNSTAGE_EINVAL, err);
-  // GraphSage without weights: the mean aggregator, 1 / |N(v)| on every entry of row v, handled from here on
-  // like weights the caller gave
+  // The library computes the weights itself: w(v, u) = s_row(v) s_col(u), which the dense blocks keep as patterns.
+  const bool rank1 = d->edge_val == nullptr;
+  // GraphSage without weights: the mean aggregator, 1 / |N(v)| on every entry of row v; the sparse kernels take
+  // it from here on like weights the caller gave
   std::vector<float> mean_val;
   gnnstage_desc with_mean;
   if (s.sage() && !d->edge_val && d->row_ptr) {
@@ -1201,7 +1203,6 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
   rc = gnnstage_plan_pack(s.n, hp.b.nnz, hp.b.idx, s.K, s.chunk_ptr.data(), prow.data(), &vbits);
   if (rc != GNNSTAGE_OK) return fail(nullptr, rc, "cannot pack row indices");
 
-  const bool rank1 = d->edge_val == nullptr;  // the library computes w(v, u) = s(v) s(u) itself
   Layout lay = make_layout(s, hp.f, hp.b, rank1);
   if (d->workspace_bytes < lay.total) {
     char buf[160];
@@ -1397,8 +1398,14 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
         hipMemcpy(st->at<ChunkMask>(lay.d_item_chunks[dir]), h.item_chunks.data(), sizeof(ChunkMask) * ni, hipMemcpyHostToDevice) != hipSuccess)
       return bail(GNNSTAGE_EHIP, std::string("uploading the dense blocks failed: ") + hipGetErrorString(hipGetLastError()));
     if (rank1) {
-      // patterns and the two scale vectors; s(v) = 1 / sqrt(row length of v in A + I)
-      auto scale_of = [&](int64_t v) { return (float)(1.0 / sqrt((double)(d->row_ptr[v + 1] - d->row_ptr[v]))); };
+      // patterns and the two scale vectors.  GCN normalisation: s_row = s_col = 1 / sqrt(row length in A + I).
+      // Mean aggregator: 1 / |N(v)| belongs to the destination v, which is the row of a forward block and the
+      // column of a block of the transposed index.
+      auto row_len = [&](int64_t v) { return d->row_ptr[v + 1] - d->row_ptr[v]; };
+      auto inv_sqrt = [&](int64_t v) { return (float)(1.0 / sqrt((double)row_len(v))); };
+      auto inv_len = [&](int64_t v) { return row_len(v) > 0 ? 1.f / (float)row_len(v) : 0.f; };
+      auto row_scale = [&](int64_t v) { return !s.sage() ? inv_sqrt(v) : dir == 0 ? inv_len(v) : 1.f; };
+      auto col_scale = [&](int64_t v) { return !s.sage() ? inv_sqrt(v) : dir == 0 ? 1.f : inv_len(v); };
       std::vector<uint32_t> bits(nb * 256, 0u);
       for (size_t b = 0; b < nb; ++b)
         for (int64_t e = dp.blk_e0[b]; e < dp.blk_e0[b + 1]; ++e) {
@@ -1407,10 +1414,10 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
         }
       std::vector<float> colscale(colslot.size(), 0.f), rowscale((size_t)h.rowscale_off.back(), 0.f);
       for (size_t i = 0; i < colslot.size(); ++i)
-        if (dp.colslot_vertex[i] >= 0) colscale[i] = scale_of(dp.colslot_vertex[i]);
+        if (dp.colslot_vertex[i] >= 0) colscale[i] = col_scale(dp.colslot_vertex[i]);
       for (int k = 0; k < s.K; ++k)
         for (int64_t pp = 0; pp < s.chunk_ptr[k + 1] - s.chunk_ptr[k]; ++pp)
-          rowscale[(size_t)(h.rowscale_off[(size_t)k] + pp)] = scale_of(dp.row_perm[(size_t)(s.chunk_ptr[k] + pp)]);
+          rowscale[(size_t)(h.rowscale_off[(size_t)k] + pp)] = row_scale(dp.row_perm[(size_t)(s.chunk_ptr[k] + pp)]);
       if (hipMemcpy(st->at<uint32_t>(lay.d_bits[dir]), bits.data(), sizeof(uint32_t) * bits.size(), hipMemcpyHostToDevice) != hipSuccess ||
           hipMemcpy(st->at<float>(lay.d_colscale[dir]), colscale.data(), sizeof(float) * colscale.size(), hipMemcpyHostToDevice) != hipSuccess ||
           hipMemcpy(st->at<float>(lay.d_rowscale[dir]), rowscale.data(), sizeof(float) * rowscale.size(), hipMemcpyHostToDevice) != hipSuccess)

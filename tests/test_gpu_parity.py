@@ -466,15 +466,18 @@ def test_sage_bf16(dims, level0_f32):
     _parity(p, TOL_BF16)
 
 
-def test_sage_bf16_dense_blocks(monkeypatch):
+@pytest.mark.parametrize("weights", ["given", "computed"])
+def test_sage_bf16_dense_blocks(monkeypatch, weights):
+    """Given weights go through the tile kernel; the mean aggregator computed by the library is a pattern with
+    1 / |N(v)| as the row scale of a forward block and as the column scale of a block of the transposed index."""
     monkeypatch.setenv("GNNSTAGE_DENSE_MIN_ENTRIES", "0")
     monkeypatch.setenv("GNNSTAGE_DENSE_MIN_NNZ", "64")
     monkeypatch.setenv("GNNSTAGE_DENSE_MIN_SHARE", "0.05")
     w = Workload("sage_d", "rmat", 6007, 2308100891, [128, 128, 128], 4, variant="sage", dtype="bf16", n_candidates=260_000)
     p = make_problem(w, first_stage=False)
-    probe = _gpu(p)
+    probe = _gpu(p, edge_val=weights)
     assert probe.stage.gnnstage_dense_entries(False) > 0 and probe.stage.gnnstage_dense_entries(True) > 0
-    _parity(p, TOL_BF16)
+    _parity(p, TOL_BF16, edge_val=weights)
 
 
 # ----------------------------------------------------------------------------- ResGCN+ variant
