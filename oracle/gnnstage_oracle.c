@@ -37,6 +37,12 @@
  *     r_u = m_u * ReLU(LayerNorm(h_u)), m in {0, 1/(1-p)} per (layer, vertex, feature), the same for every
  *     reader of u in a pass and for u's current and historical row alike.  The mask is a counter-based
  *     draw: SplitMix64 of a per-layer key plus the element's index (oracle_dropout_keep).
+ *   - Dropout in GCN and GraphSage layers (Section 5 trains with rate 0.5; the paper does not say where it
+ *     sits): on the layer's output, h' = m * ReLU(...), m in {0, 1/(1-p)} per (layer, vertex, feature) with
+ *     the same draw.  What is stored - and later read as current or historical embedding - is the value after
+ *     dropout, so every reader of a vertex sees the same mask, and it equals dropout on the next layer's
+ *     input.  Backward: a positive stored output passed both ReLU and dropout, its gradient is scaled by
+ *     1/(1-p).  GCNII layers have no dropout here.
  *
  * Precision: arrays are fp32 storage, every sum runs in fp64.  With quant == 1 the
  * values the GPU path keeps in bf16 (saved aggregation, levels, gradient rows) are
@@ -350,9 +356,13 @@ void oracle_forward_chunk(oracle_stage *s, int32_t k) {
           for (int32_t o = 0; o < dout; ++o) hn[o] = store(s, (double)hv[o] + y[o] + (double)b[o]);
         } else if (s->variant != 1) {
           const real_t *b = s->b[j];
+          const double keep_scale = 1.0 / (1.0 - s->dropout_p);
           for (int32_t o = 0; o < dout; ++o) {
             double t = y[o] + (double)b[o];
-            hn[o] = store(s, t > 0.0 ? t : 0.0);
+            t = t > 0.0 ? t : 0.0;
+            /* GCN, GraphSage: dropout on the layer's output, i.e. on the embedding every later reader sees */
+            if (s->dropout_p > 0.0) t = oracle_dropout_keep(s->dropout_seed, j, v, dout, o, s->dropout_p) ? t * keep_scale : 0.0;
+            hn[o] = store(s, t);
           }
         } else { /* GCNII identity mapping: (1-beta) p + beta p W */
           const double be = s->beta[j];
@@ -382,10 +392,15 @@ void oracle_backward_chunk(oracle_stage *s, int32_t k, const real_t *grad_out, i
     const real_t *hn = s->cur[j + 1];
     /* dy = g where the layer's output is positive (ReLU derivative, strict); ResGCN+ has no activation there */
     if (s->variant != 3) {
+      /* a positive stored output passed the ReLU and, with dropout, survived it: its gradient carries 1 / (1 - p) */
+      const int scaled = s->dropout_p > 0.0 && s->variant != 1;
+      const double keep_scale = 1.0 / (1.0 - s->dropout_p);
 #pragma omp parallel for schedule(static)
       for (int64_t r = 0; r < m; ++r)
-        for (int32_t o = 0; o < dout; ++o)
+        for (int32_t o = 0; o < dout; ++o) {
           if (!(hn[(v0 + r) * dout + o] > (real_t)0)) g[r * dout + o] = (real_t)0;
+          else if (scaled) g[r * dout + o] = store(s, (double)g[r * dout + o] * keep_scale);
+        }
     }
     const double wscale = s->variant == 1 ? s->beta[j] : 1.0;
     const int64_t zoff = s->variant == 2 ? (int64_t)din * dout : 0; /* GraphSage: W_neigh is the lower half */

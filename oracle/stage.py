@@ -148,7 +148,9 @@ class OracleStage:
         self.grad_in = np.zeros((n, d[0]), dtype=rt)
         # ResGCN+: LayerNorm parameters of every layer and their gradients
         self.ln_eps = float(ln_eps)
-        self.dropout_p = float(dropout_p)   # ResGCN+ only: rate of the dropout between ReLU and the convolution
+        # ResGCN+: rate of the dropout between ReLU and the convolution; GCN, GraphSage: on the layer's output
+        assert dropout_p == 0.0 or self.variant != 1, "no dropout in GCNII layers"
+        self.dropout_p = float(dropout_p)
         self.dropout_seed = 0               # per pass, see set_dropout_seed
         self.ln_g = [np.ascontiguousarray(ln_gamma[j] if ln_gamma is not None else np.ones(d[j]), dtype=rt) for j in range(L)]
         self.ln_b = [np.ascontiguousarray(ln_beta[j] if ln_beta is not None else np.zeros(d[j]), dtype=rt) for j in range(L)]
@@ -209,8 +211,9 @@ class OracleStage:
         self._cs.dropout_seed = self.dropout_seed
 
     def dropout_keep_mask(self, j: int) -> np.ndarray:
-        """The 0/1 keep decisions of layer j for the current seed, element by element (for dense references)."""
-        d = int(self.dims[j])
+        """The 0/1 keep decisions of layer j for the current seed, element by element (for dense references):
+        over the layer's input rows for ResGCN+, over its output rows for GCN and GraphSage."""
+        d = int(self.dims[j] if self.variant == 3 else self.dims[j + 1])
         out = np.zeros((self.n, d), dtype=np.float64)
         for u in range(self.n):
             for c in range(d):

@@ -104,6 +104,8 @@ def torch_dense_chunked(p, A, order, x0_t, W_t, b_t, h0_t=None, ln_t=None, drop=
                 pm = (1 - p.a) * z + p.a * h0_t[rows]
                 y = (1 - p.beta[j]) * pm + p.beta[j] * (pm @ W_t[j])
             cur_rows[j + 1][k] = torch.relu(y)
+            if drop is not None:  # GCN, GraphSage: dropout on the layer's output; keep decisions are an input here
+                cur_rows[j + 1][k] = cur_rows[j + 1][k] * drop[j][rows] / (1.0 - p.dropout_p)
     return torch.cat([cur_rows[L][c] for c in range(K)], dim=0)
 
 
@@ -460,6 +462,47 @@ def test_resgcn_dropout():
     sc = p.new_oracle(f64=True)
     sc.forward_pass(p.order)
     assert np.allclose(sc.cur[p.L], sf.cur[p.L], rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("variant", ["gcn", "sage"])
+def test_output_dropout_of_gcn_and_sage_layers(variant):
+    """Dropout on the output of a GCN / GraphSage layer: what is stored, and read later as current or historical
+    embedding, is the value after dropout; the gradient of a surviving element carries 1 / (1 - p)."""
+    w = tiny_workload(n=31, k=4, dims=(6, 5, 7, 4), variant=variant, seed=23)
+    chunks = graphs.ragged_chunks(31, 4, 3)
+    p0 = make_problem(w, chunk_ptr=chunks, first_stage=False, noise_std=0.3)
+    pz = make_problem(w, chunk_ptr=chunks, first_stage=False, noise_std=0.3, dropout_p=0.0, dropout_seed=99)
+    a, b = run_oracle(p0), run_oracle(pz)
+    assert np.array_equal(a.cur[p0.L], b.cur[p0.L]) and np.array_equal(a.grad_in, b.grad_in)   # rate 0 is no dropout
+    # forward and every gradient against autograd on the dense chunked model, the keep decisions as an input
+    p = make_problem(w, chunk_ptr=chunks, first_stage=False, noise_std=0.3, dropout_p=0.5, dropout_seed=11)
+    st = p.new_oracle(f64=True)
+    st.forward_pass(p.order)
+    st.backward_pass(p.grad_out)
+    drop = [torch.from_numpy(st.dropout_keep_mask(j)) for j in range(p.L)]
+    assert [tuple(m.shape) for m in drop] == [(p.n, d) for d in p.dims[1:]] and 0.3 < float(drop[0].mean()) < 0.7
+    for j in range(p.L):  # dropped elements are stored as zeros, survivors are positive or were zero before
+        assert np.all(st.cur[j + 1][drop[j].numpy() == 0] == 0)
+    A = dense_adj(p.row_ptr, p.col, edge_weights(variant, p.row_ptr, p.col, f64=True), p.n)
+    x0_t = torch.from_numpy(p.x0.astype(np.float64)).requires_grad_(True)
+    W_t = [torch.from_numpy(x.astype(np.float64)).requires_grad_(True) for x in p.W]
+    b_t = [torch.from_numpy(x.astype(np.float64)).requires_grad_(True) for x in p.b]
+    out = torch_dense_chunked(p, A, p.order, x0_t, W_t, b_t, None, None, drop)
+    assert np.allclose(out.detach().numpy(), st.cur[p.L], rtol=1e-11, atol=1e-12)
+    (out * torch.from_numpy(p.grad_out.astype(np.float64))).sum().backward()
+    for j in range(p.L):
+        assert np.allclose(st.dW[j], W_t[j].grad.numpy(), rtol=1e-9, atol=1e-11)
+        assert np.allclose(st.db[j], b_t[j].grad.numpy(), rtol=1e-9, atol=1e-11)
+    assert np.allclose(st.grad_in, x0_t.grad.numpy(), rtol=1e-9, atol=1e-11)
+    # unbiased: over many seeds the mean of one layer's output is the output without dropout
+    one = tiny_workload(n=31, k=1, dims=(6, 5), variant=variant, seed=23)
+    base = run_oracle(make_problem(one, first_stage=False, noise_std=0.3)).cur[1].astype(np.float64)
+    acc = np.zeros_like(base)
+    seeds = 400
+    for seed in range(seeds):
+        acc += run_oracle(make_problem(one, first_stage=False, noise_std=0.3, dropout_p=0.5, dropout_seed=seed)).cur[1]
+    err = np.abs(acc / seeds - base)
+    assert np.all(err <= 5.0 * base / np.sqrt(seeds) + 1e-6)   # survivors are 2 x base with probability 1/2: std = base
 
 
 def test_transposed_index_round_trip_and_push_pull():
