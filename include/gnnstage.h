@@ -70,6 +70,13 @@ enum { GNNSTAGE_F32 = 0, GNNSTAGE_BF16 = 1 };
  *     r_u is zeroed or scaled by 1 / (1 - p) per (layer, vertex, feature), the same decision for every reader
  *     of u in a pass and for u's current and historical row; decisions are counter-based draws from the seed
  *     given by gnnstage_set_dropout_seed.
+ * Dropout in GNNSTAGE_GCN and GNNSTAGE_SAGE stages (dropout_p > 0; Section 5 trains with rate 0.5, the paper does
+ *     not say where it sits): on the output of every layer of the stage, h' = m * ReLU(...), m in {0, 1/(1-p)}
+ *     per (layer, vertex, feature) from the same draws.  What the level buffers hold - and what later readers
+ *     gather as current or historical embedding - is the value after dropout, which equals dropout on the next
+ *     layer's input with one mask for all readers of a vertex.  Backward: a positive stored output passed ReLU and
+ *     dropout, its gradient is scaled by 1 / (1 - p).  A stage whose last layer is the model's output layer should
+ *     be created with dropout_p = 0.  GNNSTAGE_GCNII takes no dropout (EINVAL).
  *
  * dtype GNNSTAGE_F32 : levels, weights, gradients rows are fp32; fp32 arithmetic.
  * dtype GNNSTAGE_BF16: levels, weights, gradient rows are bf16 (bias and all accumulators
@@ -117,7 +124,8 @@ typedef struct {
   float *const *d_ln_gamma; /* "+=" over the backward calls; caller zeroes */
   float *const *d_ln_beta;
   float ln_eps;
-  float dropout_p; /* GNNSTAGE_RESGCN only, in [0, 1): dropout between ReLU and the convolution (0 = none) */
+  float dropout_p; /* in [0, 1), 0 = none.  GNNSTAGE_RESGCN: between ReLU and the convolution; GNNSTAGE_GCN,
+                      GNNSTAGE_SAGE: on every layer's output; GNNSTAGE_GCNII: must be 0 */
 } gnnstage_desc;
 
 /* Device bytes the stage needs inside desc->workspace (graph tables, transposed index,
@@ -156,7 +164,8 @@ int update_history(gnnstage_t *st, void *hip_stream);
 
 /* Seed of the dropout decisions of the next pass (forward and backward of a pass use the same one).  Feature c
  * of vertex u survives in layer j when the top 24 bits of SplitMix64(key_j + (u * d + c + 1) * G) are at least
- * dropout_p * 2^24, key_j = SplitMix64(seed + (j + 1) * G), G = 0x9E3779B97F4A7C15.  EORDER inside a forward or a
+ * dropout_p * 2^24, key_j = SplitMix64(seed + (j + 1) * G), G = 0x9E3779B97F4A7C15, d the width of the rows the
+ * dropout acts on (the layer's input for GNNSTAGE_RESGCN, its output for GNNSTAGE_GCN / GNNSTAGE_SAGE).  EORDER inside a forward or a
  * backward pass. */
 int gnnstage_set_dropout_seed(gnnstage_t *st, uint64_t seed);
 

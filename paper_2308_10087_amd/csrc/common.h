@@ -33,6 +33,25 @@ enum SpmmEpilogue : int {
 __host__ __device__ inline bool spmm_reads_aux(int e) { return e == SPMM_MIX || e == SPMM_MASK || e == SPMM_ADD_MASK; }
 __host__ __device__ inline bool spmm_reads_add(int e) { return e == SPMM_ADD || e == SPMM_ADD_MASK; }
 
+// Dropout behind an activation: threshold = ceil(rate * 2^24) (0: none), scale = 1 / (1 - rate), key = the
+// layer's key of this pass, u0 = vertex id of the launch's first row.  Feature c of vertex u (rows of d features)
+// survives when the top 24 bits of SplitMix64(key + (u * d + c + 1) * golden) reach the threshold.
+struct LnDropout {
+  uint32_t threshold;
+  float scale;
+  uint64_t key;
+  int64_t u0;
+};
+__host__ __device__ inline uint64_t splitmix64_dev(uint64_t z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+__host__ __device__ inline bool dropout_keep(const LnDropout &dp, int64_t u, int d, int c) {
+  const uint64_t r = splitmix64_dev(dp.key + (uint64_t)(u * d + c + 1) * 0x9E3779B97F4A7C15ull);
+  return (uint32_t)(r >> 40) >= dp.threshold;
+}
+
 struct SpmmArgs {
   // sparse structure: packed index words (vertex | chunk << vbits) and weights
   const uint32_t *pidx;
@@ -89,6 +108,8 @@ struct SpmmArgs {
   const void *add;    // SPMM_ADD / SPMM_ADD_MASK: rows indexed by row - add_row0, same dtype as src
   int32_t add_ld;
   int64_t add_row0;
+  LnDropout drop{};        // SPMM_BIAS_RELU: dropout on the activated output (rows are absolute: u0 = 0)
+  float mask_scale = 1.f;  // SPMM_MASK / SPMM_ADD_MASK: what passes the mask is scaled (1 / (1 - rate) of that dropout)
 };
 
 // which task the wave `wave` of workgroup `b` runs (-1: none)
@@ -188,6 +209,8 @@ struct GemmNtArgs {
   int32_t out_ld;
   int32_t out_pad;  // columns [N, out_pad) of every output row are written as zeros (0: none)
   int32_t vec_epi;  // set by the launcher: the epilogue may use 16-byte accesses
+  LnDropout drop{};        // EPI_FWD_GCN / EPI_FWD_ADD: dropout on the activated output (u0 = vertex of row 0)
+  float mask_scale = 1.f;  // EPI_MASK: what passes the mask is scaled (1 / (1 - rate) of that dropout)
 };
 int launch_gemm_nt(const GemmNtArgs &a, int compute_dtype, hipStream_t s);
 
@@ -216,14 +239,6 @@ int launch_colsum_add(const void *B, int dtype, int ldb, int M, int O, float *pa
 constexpr int kLnMaxWidth = 1024;  // a row lives in the registers of one wavefront
 constexpr int kLnMaxWaves = 8192;  // wavefronts of one backward launch; the parameter-gradient scratch holds one
                                    // 2 x d block of sums per workgroup of four
-// Dropout behind the activation: threshold = ceil(rate * 2^24) (0: none), scale = 1 / (1 - rate), key = the
-// layer's key of this pass, u0 = vertex id of the launch's first row.
-struct LnDropout {
-  uint32_t threshold;
-  float scale;
-  uint64_t key;
-  int64_t u0;
-};
 // out[r][c] = Dropout(ReLU(gamma[c] * (x[r][c] - mean_r) / sqrt(var_r + eps) + beta[c])), c < d; zeros up to out_ld
 int launch_ln_relu(const void *x, int x_dtype, int x_ld, const float *gamma, const float *beta, float eps, int64_t M, int d, void *out,
                    int out_dtype, int out_ld, const LnDropout &dp, hipStream_t s);
@@ -242,7 +257,8 @@ int launch_copy_rows(const void *src, int src_ld, void *dst, int dst_ld, int64_t
 int launch_stage_weights(const void *W, int w_dtype, int K, int N, void *Wt, int Kp, void *Wn, int Np,
                          hipStream_t s);
 // dY[m][c] = level[m][c] > 0 ? g[m][c] : 0 for c < d, zeros up to out_ld
-int launch_relu_mask(const void *g, const void *level, int dtype, int64_t M, int d, void *out, int out_ld,
+// out = level > 0 ? g * scale : 0 (the ReLU derivative on the way back; scale = 1 / (1 - rate) of a dropout behind it)
+int launch_relu_mask(const void *g, const void *level, int dtype, int64_t M, int d, void *out, int out_ld, float scale,
                      hipStream_t s);
 int launch_copy(const void *src, void *dst, size_t bytes, hipStream_t s);
 int launch_fill_zero(void *dst, size_t bytes, hipStream_t s);

@@ -43,6 +43,7 @@ __device__ inline void epilogue_store(const GemmNtArgs &a, int m, int n, float a
     case EPI_FWD_GCN: {
       r = acc + a.bias[n];
       r = r > 0.f ? r : 0.f;
+      if (a.drop.threshold > 0) r = dropout_keep(a.drop, a.drop.u0 + m, a.N, n) ? r * a.drop.scale : 0.f;
       break;
     }
     case EPI_FWD_GCNII: {
@@ -58,6 +59,7 @@ __device__ inline void epilogue_store(const GemmNtArgs &a, int m, int n, float a
     case EPI_FWD_ADD: {
       r = acc + a.bias[n] + load_f32(a.aux, a.aux_dtype, (size_t)m * a.aux_ld + n);
       r = r > 0.f ? r : 0.f;
+      if (a.drop.threshold > 0) r = dropout_keep(a.drop, a.drop.u0 + m, a.N, n) ? r * a.drop.scale : 0.f;
       break;
     }
     case EPI_RES: {
@@ -65,7 +67,7 @@ __device__ inline void epilogue_store(const GemmNtArgs &a, int m, int n, float a
       break;
     }
     case EPI_MASK: {
-      r = load_f32(a.aux, a.aux_dtype, (size_t)m * a.aux_ld + n) > 0.f ? acc : 0.f;
+      r = load_f32(a.aux, a.aux_dtype, (size_t)m * a.aux_ld + n) > 0.f ? acc * a.mask_scale : 0.f;
       break;
     }
     default: {  // EPI_DGRAD_GCNII
@@ -124,6 +126,10 @@ __device__ inline void epilogue_store8(const GemmNtArgs &a, int m, int n0, const
         const float y = acc[t] + x[t];
         r[t] = y > 0.f ? y : 0.f;
       }
+      if (a.drop.threshold > 0) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) r[t] = dropout_keep(a.drop, a.drop.u0 + m, a.N, n0 + t) ? r[t] * a.drop.scale : 0.f;
+      }
       break;
     }
     case EPI_FWD_GCNII: {
@@ -150,12 +156,16 @@ __device__ inline void epilogue_store8(const GemmNtArgs &a, int m, int n0, const
         const float y = acc[t] + b8[t] + x[t];
         r[t] = (a.epilogue == EPI_RES || y > 0.f) ? y : 0.f;
       }
+      if (a.epilogue == EPI_FWD_ADD && a.drop.threshold > 0) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) r[t] = dropout_keep(a.drop, a.drop.u0 + m, a.N, n0 + t) ? r[t] * a.drop.scale : 0.f;
+      }
       break;
     }
     case EPI_MASK: {
       load8_f32(a.aux, a.aux_dtype, (size_t)m * a.aux_ld + n0, x);
 #pragma unroll
-      for (int t = 0; t < 8; ++t) r[t] = x[t] > 0.f ? acc[t] : 0.f;
+      for (int t = 0; t < 8; ++t) r[t] = x[t] > 0.f ? acc[t] * a.mask_scale : 0.f;
       break;
     }
     default: {  // EPI_DGRAD_GCNII

@@ -570,8 +570,13 @@ struct gnnstage {
   std::vector<const float *> ln_g, ln_b;  // ResGCN+: LayerNorm parameters and their gradients
   std::vector<float *> d_ln_g, d_ln_b;
   float ln_eps = 1e-5f;
-  float dropout_p = 0.f;      // ResGCN+: rate of the dropout between ReLU and the convolution
+  float dropout_p = 0.f;      // ResGCN+: between ReLU and the convolution; GCN, GraphSage: on every layer's output
   uint64_t dropout_seed = 0;  // of the current pass (gnnstage_set_dropout_seed)
+  // GCN, GraphSage: the stored output of a layer is the value after dropout; a positive one passed ReLU and dropout,
+  // so every ReLU mask of the backward pass also scales by 1 / (1 - rate)
+  bool output_dropout() const { return dropout_p > 0.f && (s.variant == GNNSTAGE_GCN || s.variant == GNNSTAGE_SAGE); }
+  LnDropout output_dropout(int j, int64_t u0) const { return output_dropout() ? dropout(j, u0) : LnDropout{}; }
+  float mask_scale() const { return output_dropout() ? (float)(1.0 / (1.0 - (double)dropout_p)) : 1.f; }
   // the dropout of layer j for a launch whose first row is vertex u0
   LnDropout dropout(int j, int64_t u0) const {
     LnDropout dp{};
@@ -1173,8 +1178,9 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
       if (!d->ln_gamma[j] || !d->ln_beta[j] || !d->d_ln_gamma[j] || !d->d_ln_beta[j])
         return fail(nullptr, GNNSTAGE_EINVAL, "a LayerNorm parameter pointer is NULL");
     if (!(d->ln_eps > 0.f)) return fail(nullptr, GNNSTAGE_EINVAL, "ln_eps must be positive");
-    if (!(d->dropout_p >= 0.f && d->dropout_p < 1.f)) return fail(nullptr, GNNSTAGE_EINVAL, "dropout_p must be in [0, 1)");
   }
+  if (!(d->dropout_p >= 0.f && d->dropout_p < 1.f)) return fail(nullptr, GNNSTAGE_EINVAL, "dropout_p must be in [0, 1)");
+  if (d->dropout_p > 0.f && s.variant == GNNSTAGE_GCNII) return fail(nullptr, GNNSTAGE_EINVAL, "no dropout in GCNII layers");
   if (s.need_input_grad && !d->grad_in) return fail(nullptr, GNNSTAGE_EINVAL, "need_input_grad set but grad_in is NULL");
   if (!d->workspace || (reinterpret_cast<uintptr_t>(d->workspace) & (kAlign - 1)))
     return fail(nullptr, GNNSTAGE_EINVAL, "workspace must be a 256-byte aligned device pointer");
@@ -1223,8 +1229,8 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
       st->d_ln_b.push_back(d->d_ln_beta[j]);
     }
     st->ln_eps = d->ln_eps;
-    st->dropout_p = d->dropout_p;
   }
+  st->dropout_p = d->dropout_p;
   if (d->beta) st->beta.assign(d->beta, d->beta + s.L); else st->beta.assign(s.L, 0.f);
   st->W.assign(d->W, d->W + s.L);
   st->cur.assign(d->cur, d->cur + s.L + 1);
@@ -1584,6 +1590,7 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
       a.out_row0 = 0;
       a.epilogue = SPMM_BIAS_RELU;
       a.bias = static_cast<const float *>(st->bias[j]);
+      a.drop = st->output_dropout(j, 0);
       HIP_TRY(st, run_spmm(st, a, false, k, cd, cd, stream, 0, j));
       continue;
     }
@@ -1647,6 +1654,7 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
       } else {
         g.epilogue = EPI_FWD_GCN;
         g.bias = static_cast<const float *>(st->bias[j]);
+        g.drop = st->output_dropout(j, row0);
         if (s.sage()) {
           g.epilogue = EPI_FWD_ADD;
           g.aux = st->at<float>(st->lay.self_fwd);
@@ -1687,7 +1695,7 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
   {
     Timed t(st, stream, 6);
     const char *top = static_cast<const char *>(st->cur[s.L]) + (size_t)row0 * s.dims[s.L] * celt;
-    HIP_TRY(st, launch_relu_mask(grad_out_rows, top, cd, M, s.dims[s.L], G[gi], s.ld[s.L], stream));
+    HIP_TRY(st, launch_relu_mask(grad_out_rows, top, cd, M, s.dims[s.L], G[gi], s.ld[s.L], st->mask_scale(), stream));
   }
   // invariant at the top of every iteration: G[gi] holds dY_j = dL/d(pre-activation of layer j) for the
   // rows of the chunk, [M x ld_{j+1}], zero in the padding columns
@@ -1763,6 +1771,7 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
         g.Kp = s.ld[j + 1];
         if (j > 0) {
           g.epilogue = EPI_MASK;
+          g.mask_scale = st->mask_scale();
           g.aux = static_cast<const char *>(st->cur[j]) + (size_t)row0 * s.dims[j] * celt;
           g.aux_dtype = cd;
           g.aux_ld = s.dims[j];
@@ -1870,6 +1879,7 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
         a.out_ld = s.ld[j];
         a.out_row0 = row0;
         a.epilogue = s.sage() ? SPMM_ADD_MASK : SPMM_MASK;
+        a.mask_scale = st->mask_scale();
         a.aux = st->cur[j];
         a.aux_ld = s.dims[j];
         HIP_TRY(st, run_spmm(st, a, true, k, cd, cd, stream, 2, j));

@@ -20,17 +20,6 @@ __device__ inline void st_elt(void *p, int dtype, size_t i, float v) {
   else
     static_cast<float *>(p)[i] = v;
 }
-// Dropout between the activation and the aggregation: feature c of vertex u survives when the top 24 bits of
-// SplitMix64(key + (u * d + c + 1) * golden) reach the threshold rate * 2^24 (key: the layer's key of this pass).
-__device__ inline uint64_t splitmix64_dev(uint64_t z) {
-  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-  return z ^ (z >> 31);
-}
-__device__ inline bool dropout_keep(const LnDropout &dp, int64_t u, int d, int c) {
-  const uint64_t r = splitmix64_dev(dp.key + (uint64_t)(u * d + c + 1) * 0x9E3779B97F4A7C15ull);
-  return (uint32_t)(r >> 40) >= dp.threshold;
-}
 
 __device__ inline float wave_sum(float v) {
 #pragma unroll

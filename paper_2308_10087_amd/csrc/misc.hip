@@ -30,7 +30,7 @@ __global__ __launch_bounds__(256) void stage_weights_kernel(const Tw *W, int K, 
 
 // 8 elements per thread with 16-byte accesses (d and out_ld multiples of 8, aligned pointers)
 template <typename T>
-__global__ __launch_bounds__(256) void relu_mask_vec_kernel(const T *g, const T *level, int64_t M, int d, T *out) {
+__global__ __launch_bounds__(256) void relu_mask_vec_kernel(const T *g, const T *level, int64_t M, int d, T *out, float scale) {
   typedef T vec_t __attribute__((ext_vector_type(8)));
   const int64_t idx = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
   if (idx >= M * d) return;
@@ -40,7 +40,7 @@ __global__ __launch_bounds__(256) void relu_mask_vec_kernel(const T *g, const T 
     const vec_t x = *reinterpret_cast<const vec_t *>(gp), l = *reinterpret_cast<const vec_t *>(lp);
     vec_t r;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) r[t] = to_f32(l[t]) > 0.f ? x[t] : from_f32<T>(0.f);
+    for (int t = 0; t < 8; ++t) r[t] = to_f32(l[t]) > 0.f ? from_f32<T>(to_f32(x[t]) * scale) : from_f32<T>(0.f);
     *reinterpret_cast<vec_t *>(op) = r;
   } else {
     typedef T half_t __attribute__((ext_vector_type(4)));
@@ -49,20 +49,20 @@ __global__ __launch_bounds__(256) void relu_mask_vec_kernel(const T *g, const T 
       const half_t x = *reinterpret_cast<const half_t *>(gp + 4 * h), l = *reinterpret_cast<const half_t *>(lp + 4 * h);
       half_t r;
 #pragma unroll
-      for (int t = 0; t < 4; ++t) r[t] = to_f32(l[t]) > 0.f ? x[t] : from_f32<T>(0.f);
+      for (int t = 0; t < 4; ++t) r[t] = to_f32(l[t]) > 0.f ? from_f32<T>(to_f32(x[t]) * scale) : from_f32<T>(0.f);
       *reinterpret_cast<half_t *>(op + 4 * h) = r;
     }
   }
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void relu_mask_kernel(const T *g, const T *level, int64_t M, int d, T *out, int out_ld) {
+__global__ __launch_bounds__(256) void relu_mask_kernel(const T *g, const T *level, int64_t M, int d, T *out, int out_ld, float scale) {
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= M * out_ld) return;
   const int64_t m = idx / out_ld;
   const int c = (int)(idx % out_ld);
   float r = 0.f;
-  if (c < d && to_f32(level[m * d + c]) > 0.f) r = to_f32(g[m * d + c]);
+  if (c < d && to_f32(level[m * d + c]) > 0.f) r = to_f32(g[m * d + c]) * scale;
   out[idx] = from_f32<T>(r);
 }
 
@@ -113,27 +113,28 @@ int launch_stage_weights(const void *W, int w_dtype, int K, int N, void *Wt, int
   return (int)hipGetLastError();
 }
 
-int launch_relu_mask(const void *g, const void *level, int dtype, int64_t M, int d, void *out, int out_ld, hipStream_t s) {
+int launch_relu_mask(const void *g, const void *level, int dtype, int64_t M, int d, void *out, int out_ld, float scale,
+                     hipStream_t s) {
   if (M <= 0) return hipSuccess;
   const auto al = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
   if (d % 8 == 0 && out_ld == d && al(g) && al(level) && al(out)) {
     dim3 gv((unsigned)((M * d / 8 + 255) / 256));
     if (dtype == DT_BF16)
       hipLaunchKernelGGL(relu_mask_vec_kernel<bf16_t>, gv, dim3(256), 0, s, static_cast<const bf16_t *>(g),
-                         static_cast<const bf16_t *>(level), M, d, static_cast<bf16_t *>(out));
+                         static_cast<const bf16_t *>(level), M, d, static_cast<bf16_t *>(out), scale);
     else
       hipLaunchKernelGGL(relu_mask_vec_kernel<float>, gv, dim3(256), 0, s, static_cast<const float *>(g),
-                         static_cast<const float *>(level), M, d, static_cast<float *>(out));
+                         static_cast<const float *>(level), M, d, static_cast<float *>(out), scale);
     return (int)hipGetLastError();
   }
   const int64_t total = M * out_ld;
   dim3 grid((unsigned)((total + 255) / 256));
   if (dtype == DT_BF16)
     hipLaunchKernelGGL(relu_mask_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t *>(g),
-                       static_cast<const bf16_t *>(level), M, d, static_cast<bf16_t *>(out), out_ld);
+                       static_cast<const bf16_t *>(level), M, d, static_cast<bf16_t *>(out), out_ld, scale);
   else
     hipLaunchKernelGGL(relu_mask_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(g),
-                       static_cast<const float *>(level), M, d, static_cast<float *>(out), out_ld);
+                       static_cast<const float *>(level), M, d, static_cast<float *>(out), out_ld, scale);
   return (int)hipGetLastError();
 }
 

@@ -57,13 +57,17 @@ __device__ inline void finish_cols(const SpmmArgs &a, int64_t row, int c, const 
       const float y = acc[t] + a.bias[c + t];
       r[t] = y > 0.f ? y : 0.f;
     }
+    if (a.drop.threshold > 0) {
+#pragma unroll
+      for (int t = 0; t < VEC; ++t) r[t] = dropout_keep(a.drop, a.drop.u0 + row, a.d, c + t) ? r[t] * a.drop.scale : 0.f;
+    }
   } else if (spmm_reads_add(a.epilogue)) {
     const Pack<Tin, VEC> y = *reinterpret_cast<const Pack<Tin, VEC> *>(
         static_cast<const Tin *>(a.add) + (size_t)(row - a.add_row0) * a.add_ld + c);
 #pragma unroll
     for (int t = 0; t < VEC; ++t) {
       const float sum = acc[t] + to_f32(y.v[t]);
-      r[t] = (a.epilogue == SPMM_ADD || to_f32(x.v[t]) > 0.f) ? sum : 0.f;
+      r[t] = a.epilogue == SPMM_ADD ? sum : to_f32(x.v[t]) > 0.f ? sum * a.mask_scale : 0.f;
     }
   } else if (a.epilogue == SPMM_MIX) {
 #pragma unroll
@@ -73,7 +77,7 @@ __device__ inline void finish_cols(const SpmmArgs &a, int64_t row, int c, const 
     for (int t = 0; t < VEC; ++t) r[t] = __builtin_fmaf(a.s_acc, acc[t], a.s_aux * to_f32(x.v[t]));
   } else {
 #pragma unroll
-    for (int t = 0; t < VEC; ++t) r[t] = to_f32(x.v[t]) > 0.f ? acc[t] : 0.f;
+    for (int t = 0; t < VEC; ++t) r[t] = to_f32(x.v[t]) > 0.f ? acc[t] * a.mask_scale : 0.f;
   }
   Pack<Tout, VEC> o;
 #pragma unroll

@@ -32,7 +32,8 @@ def main() -> None:
     ap.add_argument("--epochs", type=int, default=60)
     ap.add_argument("--alpha-hist", type=int, default=2)
     ap.add_argument("--lr", type=float, default=0.005)
-    ap.add_argument("--dropout", type=float, default=0.0, help="inside ResGCN+ blocks")
+    ap.add_argument("--dropout", type=float, default=0.0,
+                    help="inside ResGCN+ blocks and on the layer outputs of gcn / sage stages (not of the last stage, which feeds the head)")
     ap.add_argument("--bf16", action="store_true")
     ap.add_argument("--partition", action="store_true",
                     help="chunks from the locality-aware partitioner (Algorithm 1's first step) instead of index ranges")
@@ -87,7 +88,7 @@ def main() -> None:
         st = g.GnnStage(row_ptr, col, chunk_ptr, dims, W=W, cur=cur, hist=hist, dW=dW, bias=bias, dbias=dbias, variant=variant[kind],
                         dtype=g.GNNSTAGE_BF16 if args.bf16 else g.GNNSTAGE_F32, level0_f32=(l0 == torch.float32 and args.bf16),
                         grad_in=grad_in, device=dev, ln_gamma=ln[0], ln_beta=ln[1], d_ln_gamma=ln[2], d_ln_beta=ln[3],
-                        dropout_p=args.dropout if kind == "resgcn" else 0.0)
+                        dropout_p=args.dropout if (kind == "resgcn" or si < len(kinds) - 1) else 0.0)
         stages.append(st)
         params += [(master[j], W[j] if args.bf16 else None, dW[j]) for j in range(2)]
         params += [(bias[j], None, dbias[j]) for j in range(2)]

@@ -106,7 +106,7 @@ class GpuTrainRun:
                             level0_f32=first and bf and not res, grad_in=grad_in, device=device,
                             variant={"gcn": g.GNNSTAGE_GCN, "sage": g.GNNSTAGE_SAGE, "resgcn": g.GNNSTAGE_RESGCN}[var],
                             ln_gamma=ln_g, ln_beta=ln_b, d_ln_gamma=d_ln_g, d_ln_beta=d_ln_b,
-                            dropout_p=tp.dropout_p if res else 0.0)
+                            dropout_p=tp.stage_dropout(si))
             self.stages.append(st)
             for j in range(L):
                 self.params.append((master_W[j], W[j] if bf else None, dW[j]))

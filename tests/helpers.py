@@ -52,7 +52,7 @@ class Problem:
     level0_f32: bool = False
     ln_gamma: Optional[List[np.ndarray]] = None   # ResGCN+ only
     ln_beta: Optional[List[np.ndarray]] = None
-    dropout_p: float = 0.0                        # ResGCN+ only
+    dropout_p: float = 0.0                        # ResGCN+: inside the block; GCN, GraphSage: on every layer's output
     dropout_seed: int = 0
 
     @property
@@ -181,7 +181,13 @@ class TrainProblem:
     variants: Optional[List[str]] = None        # per stage: "gcn" (default), "sage", "resgcn"
     ln_gamma: Optional[List[List[np.ndarray]]] = None
     ln_beta: Optional[List[List[np.ndarray]]] = None
-    dropout_p: float = 0.0                      # of the ResGCN+ stages
+    dropout_p: float = 0.0                      # of the ResGCN+ stages, and ...
+    dropout_everywhere: bool = False            # ... of the GCN / GraphSage stages too, except the last stage
+
+    def stage_dropout(self, si: int) -> float:
+        if self.variant(si) == "resgcn":
+            return self.dropout_p
+        return self.dropout_p if self.dropout_everywhere and si < len(self.stage_dims) - 1 else 0.0
 
     @property
     def n(self):
@@ -233,7 +239,7 @@ def new_oracle_trainer(tp: TrainProblem, f64: bool = False, **opt):
                                 quant=tp.quant and not f64,
                                 level0_f32=(si == 0 and tp.quant and not f64 and var != "resgcn"), f64=f64,
                                 ln_gamma=tp.ln_gamma[si], ln_beta=tp.ln_beta[si],
-                                dropout_p=tp.dropout_p if var == "resgcn" else 0.0)
+                                dropout_p=tp.stage_dropout(si))
         if si == 0:
             st.cur[0][...] = tp.x0
             st.hist[0][...] = tp.x0

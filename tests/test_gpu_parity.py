@@ -523,6 +523,37 @@ def test_resgcn_dropout(rate, seed):
     _parity(make_problem(wb, first_stage=False, dropout_p=rate, dropout_seed=seed), TOL_BF16)
 
 
+@pytest.mark.parametrize("order", ["aggregate", "transform"])
+@pytest.mark.parametrize("variant", ["gcn", "sage"])
+@pytest.mark.parametrize("rate,seed", [(0.5, 7), (0.3, 2**63 + 12345)])
+def test_output_dropout_of_gcn_and_sage_layers(monkeypatch, rate, seed, variant, order):
+    """Dropout on every layer's output, fused into the epilogue that writes the level (the transform's when the
+    layer aggregates first, the aggregation's when it transforms first); the backward masks carry 1 / (1 - p)."""
+    monkeypatch.setenv("GNNSTAGE_ORDER", order)
+    rate = float(np.float32(rate))
+    w = small(dims=(40, 24, 32, 16), n=911, k=6, variant=variant)
+    p = make_problem(w, chunk_ptr=graphs.ragged_chunks(911, 6, 4), first_stage=False, noise_std=0.3,
+                     dropout_p=rate, dropout_seed=seed)
+    _parity(p, TOL_F32)
+    ref = run_oracle(p)
+    keep = ref.dropout_keep_mask(0)
+    assert keep.shape == (911, 24) and abs(keep.mean() - (1 - rate)) < 0.02
+    assert np.all(ref.cur[1][keep == 0] == 0)
+    wb = Workload("out_drop", "rmat", 5003, 2308100895, [100, 128, 256, 128], 6, variant=variant, dtype="bf16",
+                  level0_f32=True, n_candidates=60_000)
+    _parity(make_problem(wb, dropout_p=rate, dropout_seed=seed), TOL_BF16)
+    _parity(make_problem(wb, dropout_p=rate, dropout_seed=seed), TOL_BF16, need_input_grad=False)
+
+
+def test_no_dropout_in_gcnii_layers():
+    import paper_2308_10087_amd as g
+    p = make_problem(small(dims=(16,) * 3, n=300, k=3, variant="gcnii"))
+    p.dropout_p = 0.5
+    with pytest.raises(g.GnnStageError) as e:
+        _gpu(p)
+    assert e.value.code == -1
+
+
 def test_resgcn_dropout_seed_changes_the_pass_and_is_locked_inside_one():
     import paper_2308_10087_amd as g
     w = small(dims=(24,) * 3, n=500, k=4, variant="resgcn")

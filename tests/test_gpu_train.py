@@ -187,6 +187,26 @@ def test_sgd_epochs_with_dropout_in_the_resgcn_stage():
     assert abs(ref0.epoch(0) - out[0][1]) > 1e-3       # dropout really changed the pass
 
 
+def test_sgd_epochs_with_dropout_in_every_stage_but_the_last():
+    """GCN and GraphSage stages drop on their layers' outputs, the ResGCN+ stage inside its block; the last stage feeds
+    the loss head and is created without dropout."""
+    tp = make_train_problem(n=1500, n_classes=5, stage_dims=((24, 16, 16), (16, 16, 16), (16, 16), (16, 8)), K=4, ragged=True,
+                            variants=("sage", "resgcn", "gcn", "gcn"))
+    tp.dropout_p = 0.5
+    tp.dropout_everywhere = True
+    assert [tp.stage_dropout(si) for si in range(4)] == [0.5, 0.5, 0.5, 0.0]
+    ref, run, out = _run_pair(tp, 3, optimizer="sgd", lr=0.05, shuffle=True, seed=13, alpha_hist=2)
+    for lg, lr_ in out:
+        assert abs(lg - lr_) <= 1e-4 * lr_
+    for a, b in zip(run.grads(), ref.grads()):
+        assert max_rel(a.reshape(b.shape), b) <= 1e-4
+    only_res = make_train_problem(n=1500, n_classes=5, stage_dims=((24, 16, 16), (16, 16, 16), (16, 16), (16, 8)), K=4,
+                                  ragged=True, variants=("sage", "resgcn", "gcn", "gcn"))
+    only_res.dropout_p = 0.5
+    ref0 = new_oracle_trainer(only_res, optimizer="sgd", lr=F(0.05), shuffle=True, seed=13, alpha_hist=2)
+    assert abs(ref0.epoch(0) - out[0][1]) > 1e-3       # the other stages' dropout really changed the pass
+
+
 @pytest.mark.parametrize("stage_dims", [((24, 16, 16),), ((24, 16), (16, 16, 8))])
 def test_one_sgd_epoch_bf16(stage_dims):
     """bf16 levels: the oracle rounds at the same points.  A pre-activation that sits within rounding noise of
