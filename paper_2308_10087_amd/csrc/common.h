@@ -108,7 +108,6 @@ struct SpmmArgs {
   const void *add;    // SPMM_ADD / SPMM_ADD_MASK: rows indexed by row - add_row0, same dtype as src
   int32_t add_ld;
   int64_t add_row0;
-  LnDropout drop{};        // SPMM_BIAS_RELU: dropout on the activated output (rows are absolute: u0 = 0)
   float mask_scale = 1.f;  // SPMM_MASK / SPMM_ADD_MASK: what passes the mask is scaled (1 / (1 - rate) of that dropout)
 };
 
@@ -209,7 +208,6 @@ struct GemmNtArgs {
   int32_t out_ld;
   int32_t out_pad;  // columns [N, out_pad) of every output row are written as zeros (0: none)
   int32_t vec_epi;  // set by the launcher: the epilogue may use 16-byte accesses
-  LnDropout drop{};        // EPI_FWD_GCN / EPI_FWD_ADD: dropout on the activated output (u0 = vertex of row 0)
   float mask_scale = 1.f;  // EPI_MASK: what passes the mask is scaled (1 / (1 - rate) of that dropout)
 };
 int launch_gemm_nt(const GemmNtArgs &a, int compute_dtype, hipStream_t s);
@@ -257,6 +255,8 @@ int launch_copy_rows(const void *src, int src_ld, void *dst, int dst_ld, int64_t
 int launch_stage_weights(const void *W, int w_dtype, int K, int N, void *Wt, int Kp, void *Wn, int Np,
                          hipStream_t s);
 // dY[m][c] = level[m][c] > 0 ? g[m][c] : 0 for c < d, zeros up to out_ld
+// x[r][c] <- survives ? x[r][c] * scale : 0 in place, r < M, c < d (rows of leading dimension ld; dp.u0 = vertex of row 0)
+int launch_dropout_rows(void *x, int dtype, int64_t M, int d, int ld, const LnDropout &dp, hipStream_t s);
 // out = level > 0 ? g * scale : 0 (the ReLU derivative on the way back; scale = 1 / (1 - rate) of a dropout behind it)
 int launch_relu_mask(const void *g, const void *level, int dtype, int64_t M, int d, void *out, int out_ld, float scale,
                      hipStream_t s);

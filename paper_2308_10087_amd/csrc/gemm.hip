@@ -43,7 +43,6 @@ __device__ inline void epilogue_store(const GemmNtArgs &a, int m, int n, float a
     case EPI_FWD_GCN: {
       r = acc + a.bias[n];
       r = r > 0.f ? r : 0.f;
-      if (a.drop.threshold > 0) r = dropout_keep(a.drop, a.drop.u0 + m, a.N, n) ? r * a.drop.scale : 0.f;
       break;
     }
     case EPI_FWD_GCNII: {
@@ -59,7 +58,6 @@ __device__ inline void epilogue_store(const GemmNtArgs &a, int m, int n, float a
     case EPI_FWD_ADD: {
       r = acc + a.bias[n] + load_f32(a.aux, a.aux_dtype, (size_t)m * a.aux_ld + n);
       r = r > 0.f ? r : 0.f;
-      if (a.drop.threshold > 0) r = dropout_keep(a.drop, a.drop.u0 + m, a.N, n) ? r * a.drop.scale : 0.f;
       break;
     }
     case EPI_RES: {
@@ -126,10 +124,6 @@ __device__ inline void epilogue_store8(const GemmNtArgs &a, int m, int n0, const
         const float y = acc[t] + x[t];
         r[t] = y > 0.f ? y : 0.f;
       }
-      if (a.drop.threshold > 0) {
-#pragma unroll
-        for (int t = 0; t < 8; ++t) r[t] = dropout_keep(a.drop, a.drop.u0 + m, a.N, n0 + t) ? r[t] * a.drop.scale : 0.f;
-      }
       break;
     }
     case EPI_FWD_GCNII: {
@@ -155,10 +149,6 @@ __device__ inline void epilogue_store8(const GemmNtArgs &a, int m, int n0, const
       for (int t = 0; t < 8; ++t) {
         const float y = acc[t] + b8[t] + x[t];
         r[t] = (a.epilogue == EPI_RES || y > 0.f) ? y : 0.f;
-      }
-      if (a.epilogue == EPI_FWD_ADD && a.drop.threshold > 0) {
-#pragma unroll
-        for (int t = 0; t < 8; ++t) r[t] = dropout_keep(a.drop, a.drop.u0 + m, a.N, n0 + t) ? r[t] * a.drop.scale : 0.f;
       }
       break;
     }

@@ -575,7 +575,6 @@ struct gnnstage {
   // GCN, GraphSage: the stored output of a layer is the value after dropout; a positive one passed ReLU and dropout,
   // so every ReLU mask of the backward pass also scales by 1 / (1 - rate)
   bool output_dropout() const { return dropout_p > 0.f && (s.variant == GNNSTAGE_GCN || s.variant == GNNSTAGE_SAGE); }
-  LnDropout output_dropout(int j, int64_t u0) const { return output_dropout() ? dropout(j, u0) : LnDropout{}; }
   float mask_scale() const { return output_dropout() ? (float)(1.0 / (1.0 - (double)dropout_p)) : 1.f; }
   // the dropout of layer j for a launch whose first row is vertex u0
   LnDropout dropout(int j, int64_t u0) const {
@@ -1590,8 +1589,10 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
       a.out_row0 = 0;
       a.epilogue = SPMM_BIAS_RELU;
       a.bias = static_cast<const float *>(st->bias[j]);
-      a.drop = st->output_dropout(j, 0);
       HIP_TRY(st, run_spmm(st, a, false, k, cd, cd, stream, 0, j));
+      if (st->output_dropout())  // on the rows just written, in place
+        HIP_TRY(st, launch_dropout_rows(static_cast<char *>(st->cur[j + 1]) + (size_t)row0 * s.dims[j + 1] * celt, cd, M, s.dims[j + 1],
+                                        s.dims[j + 1], st->dropout(j, row0), stream));
       continue;
     }
     char *Zj = st->at<char>(st->lay.Z[j]);
@@ -1654,7 +1655,6 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
       } else {
         g.epilogue = EPI_FWD_GCN;
         g.bias = static_cast<const float *>(st->bias[j]);
-        g.drop = st->output_dropout(j, row0);
         if (s.sage()) {
           g.epilogue = EPI_FWD_ADD;
           g.aux = st->at<float>(st->lay.self_fwd);
@@ -1666,6 +1666,8 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
       g.out_dtype = cd;
       g.out_ld = s.dims[j + 1];
       HIP_TRY(st, launch_gemm_nt(g, cd, stream));
+      if (st->output_dropout())  // on the rows just written, in place
+        HIP_TRY(st, launch_dropout_rows(g.out, cd, M, s.dims[j + 1], s.dims[j + 1], st->dropout(j, row0), stream));
     }
   }
   return GNNSTAGE_OK;

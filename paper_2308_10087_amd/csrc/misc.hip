@@ -55,6 +55,22 @@ __global__ __launch_bounds__(256) void relu_mask_vec_kernel(const T *g, const T 
   }
 }
 
+// Dropout on rows that a layer has just written: 8 consecutive columns per thread when the row allows it.
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void dropout_rows_kernel(T *x, int64_t M, int d, int ld, LnDropout dp) {
+  const int per_row = d / VEC;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= M * per_row) return;
+  const int64_t r = idx / per_row;
+  const int c = (int)(idx % per_row) * VEC;
+  typedef T vec_t __attribute__((ext_vector_type(VEC)));
+  vec_t *p = reinterpret_cast<vec_t *>(x + r * ld + c);
+  vec_t v = *p;
+#pragma unroll
+  for (int t = 0; t < VEC; ++t) v[t] = dropout_keep(dp, dp.u0 + r, d, c + t) ? from_f32<T>(to_f32(v[t]) * dp.scale) : from_f32<T>(0.f);
+  *p = v;
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void relu_mask_kernel(const T *g, const T *level, int64_t M, int d, T *out, int out_ld, float scale) {
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -110,6 +126,22 @@ int launch_stage_weights(const void *W, int w_dtype, int K, int N, void *Wt, int
   else
     hipLaunchKernelGGL((stage_weights_kernel<float, float>), grid, dim3(256), 0, s, static_cast<const float *>(W), K, N,
                        static_cast<float *>(Wt), Kp, static_cast<float *>(Wn), Np);
+  return (int)hipGetLastError();
+}
+
+int launch_dropout_rows(void *x, int dtype, int64_t M, int d, int ld, const LnDropout &dp, hipStream_t s) {
+  if (M <= 0 || d <= 0 || dp.threshold == 0) return hipSuccess;
+  const bool vec = d % 8 == 0 && ld % 8 == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0 && dtype == DT_BF16;
+  const int64_t threads = vec ? M * (d / 8) : M * d;
+  dim3 grid((unsigned)((threads + 255) / 256));
+  if (dtype == DT_BF16) {
+    if (vec)
+      hipLaunchKernelGGL((dropout_rows_kernel<bf16_t, 8>), grid, dim3(256), 0, s, static_cast<bf16_t *>(x), M, d, ld, dp);
+    else
+      hipLaunchKernelGGL((dropout_rows_kernel<bf16_t, 1>), grid, dim3(256), 0, s, static_cast<bf16_t *>(x), M, d, ld, dp);
+  } else {
+    hipLaunchKernelGGL((dropout_rows_kernel<float, 1>), grid, dim3(256), 0, s, static_cast<float *>(x), M, d, ld, dp);
+  }
   return (int)hipGetLastError();
 }
 

@@ -57,10 +57,6 @@ __device__ inline void finish_cols(const SpmmArgs &a, int64_t row, int c, const 
       const float y = acc[t] + a.bias[c + t];
       r[t] = y > 0.f ? y : 0.f;
     }
-    if (a.drop.threshold > 0) {
-#pragma unroll
-      for (int t = 0; t < VEC; ++t) r[t] = dropout_keep(a.drop, a.drop.u0 + row, a.d, c + t) ? r[t] * a.drop.scale : 0.f;
-    }
   } else if (spmm_reads_add(a.epilogue)) {
     const Pack<Tin, VEC> y = *reinterpret_cast<const Pack<Tin, VEC> *>(
         static_cast<const Tin *>(a.add) + (size_t)(row - a.add_row0) * a.add_ld + c);

@@ -527,8 +527,9 @@ def test_resgcn_dropout(rate, seed):
 @pytest.mark.parametrize("variant", ["gcn", "sage"])
 @pytest.mark.parametrize("rate,seed", [(0.5, 7), (0.3, 2**63 + 12345)])
 def test_output_dropout_of_gcn_and_sage_layers(monkeypatch, rate, seed, variant, order):
-    """Dropout on every layer's output, fused into the epilogue that writes the level (the transform's when the
-    layer aggregates first, the aggregation's when it transforms first); the backward masks carry 1 / (1 - p)."""
+    """Dropout on every layer's output, applied to the chunk's rows right behind the kernel that writes the level (the
+    transform when the layer aggregates first, the aggregation when it transforms first); the backward masks carry
+    1 / (1 - p)."""
     monkeypatch.setenv("GNNSTAGE_ORDER", order)
     rate = float(np.float32(rate))
     w = small(dims=(40, 24, 32, 16), n=911, k=6, variant=variant)
