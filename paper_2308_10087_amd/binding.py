@@ -101,6 +101,9 @@ def _load():
     lib.gnnstage_dense_plan_create.restype = C.c_int
     lib.gnnstage_dense_plan_create.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32,
                                                C.c_double, C.POINTER(C.c_void_p)]
+    lib.gnnstage_dense_plan_create_capped.restype = C.c_int
+    lib.gnnstage_dense_plan_create_capped.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32,
+                                                      C.c_double, C.c_int32, C.c_int64, C.POINTER(C.c_void_p)]
     lib.gnnstage_dense_plan_get.restype = C.c_int64
     lib.gnnstage_dense_plan_get.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_void_p)]
     lib.gnnstage_dense_plan_destroy.restype = C.c_int
@@ -258,18 +261,26 @@ def gnnstage_permute_csr(row_ptr: np.ndarray, col_idx: np.ndarray, perm: np.ndar
 
 _DENSE_FIELDS = [("rem_ptr", np.int64), ("rem_idx", np.int32), ("rem_orig", np.int64), ("row_perm", np.int32),
                  ("cb_off", np.int64), ("colslot_vertex", np.int32), ("chunk_blk_off", np.int64), ("blk_rb", np.int32),
-                 ("blk_cb", np.int32), ("blk_e0", np.int64), ("ent_pos", np.uint16), ("ent_orig", np.int64)]
+                 ("blk_cb", np.int32), ("blk_e0", np.int64), ("ent_pos", np.uint16), ("ent_orig", np.int64),
+                 ("min_nnz_used", np.int32)]
 
 
-def gnnstage_dense_plan(ptr: np.ndarray, idx: np.ndarray, chunk_ptr: np.ndarray, min_nnz: int, min_share: float) -> dict:
-    """Dense-block plan of one aggregation direction as a dict of numpy arrays (copies); every array is
-    empty when the plan is inactive."""
+def gnnstage_dense_plan(ptr: np.ndarray, idx: np.ndarray, chunk_ptr: np.ndarray, min_nnz: int, min_share: float,
+                        item_blocks: int = 0, max_items: int = 0) -> dict:
+    """Dense-block plan of one aggregation direction as a dict of numpy arrays (copies); every array but
+    min_nnz_used is empty when the plan is inactive.  With item_blocks and max_items the threshold is raised
+    until no chunk has more than max_items items (gnnstage_dense_plan_create_capped)."""
     ptr = np.ascontiguousarray(ptr, dtype=np.int64)
     idx = np.ascontiguousarray(idx, dtype=np.int32)
     chunk_ptr = np.ascontiguousarray(chunk_ptr, dtype=np.int64)
     h = C.c_void_p(None)
-    rc = lib.gnnstage_dense_plan_create(ptr.ctypes.data, idx.ctypes.data, ptr.shape[0] - 1, chunk_ptr.shape[0] - 1,
-                                        chunk_ptr.ctypes.data, int(min_nnz), float(min_share), C.byref(h))
+    if item_blocks or max_items:
+        rc = lib.gnnstage_dense_plan_create_capped(ptr.ctypes.data, idx.ctypes.data, ptr.shape[0] - 1, chunk_ptr.shape[0] - 1,
+                                                   chunk_ptr.ctypes.data, int(min_nnz), float(min_share), int(item_blocks),
+                                                   int(max_items), C.byref(h))
+    else:
+        rc = lib.gnnstage_dense_plan_create(ptr.ctypes.data, idx.ctypes.data, ptr.shape[0] - 1, chunk_ptr.shape[0] - 1,
+                                            chunk_ptr.ctypes.data, int(min_nnz), float(min_share), C.byref(h))
     if rc != 0:
         raise GnnStageError(rc, "gnnstage_dense_plan_create")
     out = {}

@@ -107,8 +107,9 @@ std::vector<int64_t> class_bounds_by_entries(const int64_t *ptr, const int32_t *
 }
 
 // Dense blocks: switched on for bf16 stages whose aggregations all gather rows of width 128 or 256.
-// GNNSTAGE_DENSE=0 switches them off; GNNSTAGE_DENSE_MIN_NNZ (entries a 128 x 64 block needs, default 5 %
-// of its cells), GNNSTAGE_DENSE_MIN_SHARE (share of all entries that must fall into such blocks,
+// GNNSTAGE_DENSE=0 switches them off; GNNSTAGE_DENSE_MIN_NNZ (entries a 128 x 64 block needs, default 3.4 %
+// of its cells: about where a block costs the dense kernel what its entries cost the sparse one; the plan raises
+// it until a launch fits one round of workgroups, see dense_max_items), GNNSTAGE_DENSE_MIN_SHARE (share of all entries that must fall into such blocks,
 // default 0.2) and GNNSTAGE_DENSE_MIN_ENTRIES (see below) let tests force them on small graphs.
 bool dense_enabled() {
   const char *e = getenv("GNNSTAGE_DENSE");
@@ -117,8 +118,12 @@ bool dense_enabled() {
 int dense_min_nnz() {
   const char *e = getenv("GNNSTAGE_DENSE_MIN_NNZ");
   if (e && atoi(e) >= 1) return atoi(e);
-  return kDenseRB * kDenseCB / 20;
+  return kDenseRB * kDenseCB * 34 / 1000;
 }
+// Items (runs of at most 32 blocks of one row block) a chunk may have: one workgroup per item and 128-column
+// half, two workgroups per CU, 256 CUs; a tenth more is harmless because short items end early, beyond that
+// the extra workgroups wait for a second round and the launch takes twice as long.
+int64_t dense_max_items(int widest) { return (int64_t)(2 * 256 * 11 / 10) / std::max(1, widest / 128); }
 double dense_min_share() {
   const char *e = getenv("GNNSTAGE_DENSE_MIN_SHARE");
   return e ? atof(e) : 0.2;
@@ -220,7 +225,7 @@ struct HostDir {
 void host_mask_set(ChunkMask &m, int c) { m.w[c >> 6] |= 1ull << (c & 63); }
 
 bool make_host_dir(const int64_t *ptr, const int32_t *idx, int64_t n, const std::vector<int64_t> &chunk_ptr,
-                   int classes, bool try_dense, HostDir &h) {
+                   int classes, bool try_dense, int dense_width, HostDir &h) {
   const int K = (int)chunk_ptr.size() - 1;
   h.ptr = ptr;
   h.idx = idx;
@@ -233,7 +238,8 @@ bool make_host_dir(const int64_t *ptr, const int32_t *idx, int64_t n, const std:
     // share of all entries that must be dense: the relative threshold, or the absolute one if that asks for more
     const double nnz = (double)ptr[n];
     const double share = std::max(dense_min_share(), nnz > 0 ? dense_min_entries_per_chunk() * K / nnz : 0.0);
-    if (!build_dense_plan(ptr, idx, n, K, chunk_ptr.data(), dense_min_nnz(), share, h.dp)) return false;
+    if (!build_dense_plan(ptr, idx, n, K, chunk_ptr.data(), dense_min_nnz(), share, h.dp, kDenseItemBlocks, dense_max_items(dense_width)))
+      return false;
   }
   if (h.dp.active) {
     const DensePlan &dp = h.dp;
@@ -326,6 +332,11 @@ struct Shape {
   }
   // dense blocks serve the matrix-core aggregation only: every aggregation of the stage must gather bf16 rows
   // of width 128 or 256
+  int dense_width() const {  // the widest rows the dense kernel gathers (one workgroup per 128 columns)
+    int wdt = 128;
+    for (int j = 0; j < L; ++j) wdt = std::max(wdt, tf[j] ? dims[j + 1] : dims[j]);
+    return wdt;
+  }
   bool dense_ok() const {
     if (dtype != GNNSTAGE_BF16 || !dense_enabled()) return false;
     for (int j = 0; j < L; ++j) {
@@ -1106,8 +1117,8 @@ int make_host_plan(const gnnstage_desc *d, const Shape &s, bool want_edge, HostP
     return GNNSTAGE_EINVAL;
   }
   const bool dense = s.dense_ok();
-  if (!make_host_dir(d->row_ptr, d->col_idx, s.n, s.chunk_ptr, s.classes(), dense, hp.f) ||
-      !make_host_dir(hp.t_ptr.data(), hp.t_row.data(), s.n, s.chunk_ptr, s.classes(), dense, hp.b)) {
+  if (!make_host_dir(d->row_ptr, d->col_idx, s.n, s.chunk_ptr, s.classes(), dense, s.dense_width(), hp.f) ||
+      !make_host_dir(hp.t_ptr.data(), hp.t_row.data(), s.n, s.chunk_ptr, s.classes(), dense, s.dense_width(), hp.b)) {
     err = "cannot plan the aggregation";
     return GNNSTAGE_EINVAL;
   }

@@ -254,7 +254,43 @@ def test_dense_plan_partitions_the_entries(name, min_nnz):
         assert np.all(np.diff(key) > 0)
     # an unreachable share leaves the plan inactive
     off = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, min_nnz, 1.1)
-    assert all(len(v) == 0 for v in off.values())
+    assert all(len(v) == 0 for k, v in off.items() if k != "min_nnz_used")
+
+
+def _items_per_chunk(d, K, item_blocks):
+    """Items of every chunk: runs of at most item_blocks consecutive blocks of one row block."""
+    out = []
+    for k in range(K):
+        rb = d["blk_rb"][d["chunk_blk_off"][k]:d["chunk_blk_off"][k + 1]]
+        out.append(int(sum(-(-c // item_blocks) for c in np.bincount(rb) if c > 0)) if len(rb) else 0)
+    return out
+
+
+def test_dense_plan_raises_the_threshold_until_a_launch_fits_one_round():
+    """With a limit on the items of a chunk the threshold goes up in steps of 5 % until every chunk fits; the blocks
+    that remain are exactly those of an uncapped plan built with the raised threshold."""
+    g = _lib()
+    row_ptr, col = make_graph(CONFIGS["c1_s"])
+    n = len(row_ptr) - 1
+    chunk_ptr = graphs.ragged_chunks(n, 5, 3)
+    free = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, 6, 0.0)
+    assert int(free["min_nnz_used"][0]) == 6
+    worst = max(_items_per_chunk(free, 5, 4))
+    assert worst > 8, "graph too small for this test"
+    same = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, 6, 0.0, item_blocks=4, max_items=worst)   # already fits
+    assert int(same["min_nnz_used"][0]) == 6 and np.array_equal(same["blk_e0"], free["blk_e0"])
+    capped = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, 6, 0.0, item_blocks=4, max_items=worst // 2)
+    t = int(capped["min_nnz_used"][0])
+    assert t > 6 and max(_items_per_chunk(capped, 5, 4)) <= worst // 2
+    ladder = [6]
+    while ladder[-1] < t:
+        ladder.append(max(ladder[-1] + 1, int(ladder[-1] * 1.05)))
+    assert ladder[-1] == t                                                    # a rung of the 5 % ladder ...
+    below = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, ladder[-2], 0.0)
+    assert max(_items_per_chunk(below, 5, 4)) > worst // 2                    # ... and the first one that fits
+    ref = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, t, 0.0)
+    for key in ("blk_rb", "blk_cb", "blk_e0", "ent_pos", "ent_orig", "rem_ptr", "rem_idx", "chunk_blk_off"):
+        assert np.array_equal(capped[key], ref[key]), key
 
 
 def _desc(g, **over):
