@@ -754,11 +754,22 @@ __global__ __launch_bounds__(256) void gemm_tn_f32_kernel(const GemmTnArgs a, in
 
 // dst[e] += scale * sum_s partial[s][e].  Fixed summation order => reproducible.  64 outputs per block,
 // four phases of splits summed in parallel (8 independent loads in flight each), then combined in LDS.
+// A second sum over the same splits (the bias gradient next to a weight gradient) rides in the same launch:
+// blocks from blocks1 on serve (partial2, count2, dst2) with scale 1.
 __global__ __launch_bounds__(256) void reduce_add_kernel(const float *partial, int splits, size_t count, float scale,
-                                                         float *dst) {
+                                                         float *dst, unsigned blocks1, const float *partial2, size_t count2,
+                                                         float *dst2) {
   __shared__ float red[4][64];
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  const size_t e = (size_t)blockIdx.x * 64 + tx;
+  unsigned block = blockIdx.x;
+  if (block >= blocks1) {  // whole workgroup
+    block -= blocks1;
+    partial = partial2;
+    count = count2;
+    scale = 1.0f;
+    dst = dst2;
+  }
+  const size_t e = (size_t)block * 64 + tx;
   float s = 0.f;
   if (e < count) {
     const int per = (splits + 3) / 4;
@@ -918,17 +929,11 @@ int launch_gemm_tn(const GemmTnArgs &a, int compute_dtype, hipStream_t s) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return (int)e;
   const size_t count = (size_t)a.I * a.O;
-  hipLaunchKernelGGL(reduce_add_kernel, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, s, a.partial, splits, count,
-                     a.scale, a.dW);
-  e = hipGetLastError();
-  if (e != hipSuccess) return (int)e;
-  if (a.dbias != nullptr) {
-    if (compute_dtype != DT_BF16) return hipErrorInvalidValue;  // the fp32 stage sums columns separately
-    hipLaunchKernelGGL(reduce_add_kernel, dim3((unsigned)((a.O + 63) / 64)), dim3(256), 0, s, a.bias_partial, splits,
-                       (size_t)a.O, 1.0f, a.dbias);
-    e = hipGetLastError();
-  }
-  return (int)e;
+  if (a.dbias != nullptr && compute_dtype != DT_BF16) return hipErrorInvalidValue;  // the fp32 stage sums columns separately
+  const unsigned blocks1 = (unsigned)((count + 63) / 64), blocks2 = a.dbias != nullptr ? (unsigned)((a.O + 63) / 64) : 0u;
+  hipLaunchKernelGGL(reduce_add_kernel, dim3(blocks1 + blocks2), dim3(256), 0, s, a.partial, splits, count, a.scale, a.dW, blocks1,
+                     a.bias_partial, (size_t)a.O, a.dbias);
+  return (int)hipGetLastError();
 }
 
 int launch_colsum_add(const void *B, int dtype, int ldb, int M, int O, float *partial, int max_splits, float *dst,
@@ -948,6 +953,7 @@ int launch_colsum_add(const void *B, int dtype, int ldb, int M, int O, float *pa
     hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, s, static_cast<const float *>(B), ldb, M, O, rows_per, partial);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return (int)e;
-  hipLaunchKernelGGL(reduce_add_kernel, dim3((unsigned)((O + 63) / 64)), dim3(256), 0, s, partial, splits, (size_t)O, 1.0f, dst);
+  hipLaunchKernelGGL(reduce_add_kernel, dim3((unsigned)((O + 63) / 64)), dim3(256), 0, s, partial, splits, (size_t)O, 1.0f, dst,
+                     (unsigned)((O + 63) / 64), static_cast<const float *>(nullptr), (size_t)0, static_cast<float *>(nullptr));
   return (int)hipGetLastError();
 }
