@@ -899,9 +899,10 @@ int launch_gemm_tn(const GemmTnArgs &a, int compute_dtype, hipStream_t s) {
   const int step = compute_dtype == DT_BF16 ? TR : 16;
   const int ti = (a.I + tile - 1) / tile, to = (a.O + tile - 1) / tile;
   int splits = 1024 / (ti * to);  // about four blocks per compute unit ...
-  // ... but the fp32 partials (write + read, 8 bytes per output element and split) should not outweigh
-  // the operands themselves (2 bytes per element of A and B)
-  const long long cap = (long long)a.M * (a.I + a.O) / (4LL * a.I * a.O);
+  // ... but the fp32 partials (write + read, 8 bytes per output element and split) should not move more than
+  // twice the operands themselves (2 bytes per element of A and B); below that the kernel is latency-bound and
+  // more blocks win
+  const long long cap = (long long)a.M * (a.I + a.O) / (2LL * a.I * a.O);
   if (splits > cap) splits = (int)cap;
   if (splits < 1) splits = 1;
   if (splits > a.max_splits) splits = a.max_splits;
