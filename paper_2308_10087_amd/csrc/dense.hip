@@ -1,9 +1,12 @@
 // Dense blocks of the neighbour aggregation on the matrix cores (Algorithm 1, the AGGREGATE line, for
 // the part of a power-law graph that is dense once rows and columns are ordered by degree).
 //
-// Every dense block is kept in memory as two 128 x 64 bf16 tiles: the nearest bf16 of every weight and
-// the bf16 of the remainder (weights keep 16 mantissa bits, as in the sparse kernel); an expand kernel
-// writes them once from the block's entry list when the stage is created.
+// Two kernels.  When the library computes the weights itself, w(v, u) = s_row(v) s_col(u), a block is a
+// 128 x 64 bit pattern plus scales (spmm_dense_r1_kernel, described there; the benchmark configurations).
+// Weights given by the caller (spmm_dense_kernel, described here): every dense block is kept in memory as two
+// 128 x 64 bf16 tiles, the nearest bf16 of every weight and the bf16 of the remainder (weights keep 16 mantissa
+// bits, as in the sparse kernel); an expand kernel writes them once from the block's entry list when the stage
+// is created.
 //
 // One workgroup per (item, 128-column half of the rows' width).  An item owns the 128 x 128 fp32
 // accumulator tile of one row block (in registers) and walks over its dense blocks.  For every block it
