@@ -274,18 +274,19 @@ int gnnstage_permute_csr(int64_t n, const int64_t *row_ptr, const int32_t *col_i
  *   4 cb_off (int64, K+1: column blocks of chunk c)   5 colslot_vertex (int32, 64 per column block, -1 = padding)
  *   6 chunk_blk_off (int64, K+1: dense blocks whose rows are in chunk k)   7 blk_rb (int32, row block in its chunk)
  *   8 blk_cb (int32, column block)   9 blk_e0 (int64, n_blocks+1)   10 ent_pos (uint16, row_in_block << 8 | col_in_block)
- *   11 ent_orig (int64, position in the original index)   12 min_nnz_used (int32, one entry)
+ *   11 ent_orig (int64, position in the original index)   12 min_nnz_used (int32, K: threshold of every row chunk)
  * gnnstage_dense_plan_create_capped: the dense kernel serves the blocks of a row block in items of at most
- * item_blocks blocks, one workgroup per item and column half, and a launch should fit one round of workgroups:
- * the threshold is raised from min_nnz in steps of 5 % until no chunk has more than max_items items; array 12
- * says where it ended.                                                                                     */
+ * item_blocks blocks, one workgroup per item and column half.  A row chunk whose items at min_nnz fit one round of
+ * workgroups (at most max_items items) keeps min_nnz: its launch takes as long as its longest item however many
+ * blocks it has.  A chunk with more items needs several rounds, every block costs time, and its blocks are
+ * selected with min_nnz_many (>= min_nnz) instead.                                                          */
 typedef struct gnnstage_dense_plan gnnstage_dense_plan;
 int gnnstage_dense_plan_create(const int64_t *ptr, const int32_t *idx, int64_t n_vertices, int32_t n_chunks,
                                const int64_t *chunk_ptr, int32_t min_nnz, double min_share,
                                gnnstage_dense_plan **out);
 int gnnstage_dense_plan_create_capped(const int64_t *ptr, const int32_t *idx, int64_t n_vertices, int32_t n_chunks,
                                       const int64_t *chunk_ptr, int32_t min_nnz, double min_share, int32_t item_blocks,
-                                      int64_t max_items, gnnstage_dense_plan **out);
+                                      int64_t max_items, int32_t min_nnz_many, gnnstage_dense_plan **out);
 int64_t gnnstage_dense_plan_get(const gnnstage_dense_plan *plan, int32_t what, const void **data);
 int gnnstage_dense_plan_destroy(gnnstage_dense_plan *plan);
 

@@ -103,7 +103,7 @@ def _load():
                                                C.c_double, C.POINTER(C.c_void_p)]
     lib.gnnstage_dense_plan_create_capped.restype = C.c_int
     lib.gnnstage_dense_plan_create_capped.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32,
-                                                      C.c_double, C.c_int32, C.c_int64, C.POINTER(C.c_void_p)]
+                                                      C.c_double, C.c_int32, C.c_int64, C.c_int32, C.POINTER(C.c_void_p)]
     lib.gnnstage_dense_plan_get.restype = C.c_int64
     lib.gnnstage_dense_plan_get.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_void_p)]
     lib.gnnstage_dense_plan_destroy.restype = C.c_int
@@ -266,10 +266,10 @@ _DENSE_FIELDS = [("rem_ptr", np.int64), ("rem_idx", np.int32), ("rem_orig", np.i
 
 
 def gnnstage_dense_plan(ptr: np.ndarray, idx: np.ndarray, chunk_ptr: np.ndarray, min_nnz: int, min_share: float,
-                        item_blocks: int = 0, max_items: int = 0) -> dict:
+                        item_blocks: int = 0, max_items: int = 0, min_nnz_many: int = 0) -> dict:
     """Dense-block plan of one aggregation direction as a dict of numpy arrays (copies); every array but
-    min_nnz_used is empty when the plan is inactive.  With item_blocks and max_items the threshold is raised
-    until no chunk has more than max_items items (gnnstage_dense_plan_create_capped)."""
+    min_nnz_used is empty when the plan is inactive.  With item_blocks, max_items and min_nnz_many a row chunk
+    with more than max_items items at min_nnz takes min_nnz_many instead (gnnstage_dense_plan_create_capped)."""
     ptr = np.ascontiguousarray(ptr, dtype=np.int64)
     idx = np.ascontiguousarray(idx, dtype=np.int32)
     chunk_ptr = np.ascontiguousarray(chunk_ptr, dtype=np.int64)
@@ -277,7 +277,7 @@ def gnnstage_dense_plan(ptr: np.ndarray, idx: np.ndarray, chunk_ptr: np.ndarray,
     if item_blocks or max_items:
         rc = lib.gnnstage_dense_plan_create_capped(ptr.ctypes.data, idx.ctypes.data, ptr.shape[0] - 1, chunk_ptr.shape[0] - 1,
                                                    chunk_ptr.ctypes.data, int(min_nnz), float(min_share), int(item_blocks),
-                                                   int(max_items), C.byref(h))
+                                                   int(max_items), int(min_nnz_many), C.byref(h))
     else:
         rc = lib.gnnstage_dense_plan_create(ptr.ctypes.data, idx.ctypes.data, ptr.shape[0] - 1, chunk_ptr.shape[0] - 1,
                                             chunk_ptr.ctypes.data, int(min_nnz), float(min_share), C.byref(h))

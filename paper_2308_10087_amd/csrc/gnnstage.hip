@@ -107,9 +107,9 @@ std::vector<int64_t> class_bounds_by_entries(const int64_t *ptr, const int32_t *
 }
 
 // Dense blocks: switched on for bf16 stages whose aggregations all gather rows of width 128 or 256.
-// GNNSTAGE_DENSE=0 switches them off; GNNSTAGE_DENSE_MIN_NNZ (entries a 128 x 64 block needs, default 3.4 %
-// of its cells: about where a block costs the dense kernel what its entries cost the sparse one; the plan raises
-// it until a launch fits one round of workgroups, see dense_max_items), GNNSTAGE_DENSE_MIN_SHARE (share of all entries that must fall into such blocks,
+// GNNSTAGE_DENSE=0 switches them off; GNNSTAGE_DENSE_MIN_NNZ (entries a 128 x 64 block needs; default: 3.4 % of
+// its cells for a chunk whose launch fits one round of workgroups, 5 % for a chunk that needs several, see
+// dense_max_items), GNNSTAGE_DENSE_MIN_SHARE (share of all entries that must fall into such blocks,
 // default 0.2) and GNNSTAGE_DENSE_MIN_ENTRIES (see below) let tests force them on small graphs.
 bool dense_enabled() {
   const char *e = getenv("GNNSTAGE_DENSE");
@@ -120,9 +120,15 @@ int dense_min_nnz() {
   if (e && atoi(e) >= 1) return atoi(e);
   return kDenseRB * kDenseCB * 34 / 1000;
 }
-// Items (runs of at most 32 blocks of one row block) a chunk may have: one workgroup per item and 128-column
-// half, two workgroups per CU, 256 CUs; a tenth more is harmless because short items end early, beyond that
-// the extra workgroups wait for a second round and the launch takes twice as long.
+int dense_min_nnz_many() {  // for a chunk whose launch needs several rounds of workgroups: every block costs time there
+  const char *e = getenv("GNNSTAGE_DENSE_MIN_NNZ");
+  if (e && atoi(e) >= 1) return atoi(e);
+  return kDenseRB * kDenseCB / 20;
+}
+// Items (runs of at most 32 blocks of one row block) of a launch that fits one round of workgroups: one workgroup
+// per item and 128-column half, two workgroups per CU, 256 CUs; a tenth more is harmless because short items end
+// early.  Such a launch takes as long as its longest item, so blocks down to the low threshold are free; beyond it
+// the extra workgroups wait for a second round.
 int64_t dense_max_items(int widest) { return (int64_t)(2 * 256 * 11 / 10) / std::max(1, widest / 128); }
 double dense_min_share() {
   const char *e = getenv("GNNSTAGE_DENSE_MIN_SHARE");
@@ -238,7 +244,8 @@ bool make_host_dir(const int64_t *ptr, const int32_t *idx, int64_t n, const std:
     // share of all entries that must be dense: the relative threshold, or the absolute one if that asks for more
     const double nnz = (double)ptr[n];
     const double share = std::max(dense_min_share(), nnz > 0 ? dense_min_entries_per_chunk() * K / nnz : 0.0);
-    if (!build_dense_plan(ptr, idx, n, K, chunk_ptr.data(), dense_min_nnz(), share, h.dp, kDenseItemBlocks, dense_max_items(dense_width)))
+    if (!build_dense_plan(ptr, idx, n, K, chunk_ptr.data(), dense_min_nnz(), share, h.dp, kDenseItemBlocks, dense_max_items(dense_width),
+                          dense_min_nnz_many()))
       return false;
   }
   if (h.dp.active) {

@@ -175,7 +175,7 @@ extern "C" int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, i
 
 // ---- dense blocks ------------------------------------------------------------------------------
 bool build_dense_plan(const int64_t *ptr, const int32_t *idx, int64_t n, int K, const int64_t *chunk_ptr,
-                      int min_nnz, double min_share, DensePlan &out, int item_blocks, int64_t max_items) {
+                      int min_nnz, double min_share, DensePlan &out, int item_blocks, int64_t max_items, int min_nnz_many) {
   constexpr int RB = DensePlan::RB, CB = DensePlan::CB;
   out = DensePlan();
   out.n = n;
@@ -244,51 +244,41 @@ bool build_dense_plan(const int64_t *ptr, const int32_t *idx, int64_t n, int K, 
       }
     chunk_blk_off[(size_t)c + 1] = (int64_t)blk_rb.size();
   }
-  // One round of workgroups: raise the threshold until every chunk's items fit (blocks are sorted by chunk, then
-  // row block, so the items of a chunk are runs of equal row block cut every item_blocks blocks).
-  int threshold = min_nnz;
-  if (max_items > 0 && item_blocks > 0) {
-    auto worst_items = [&](int t) {
-      int64_t worst = 0;
-      for (int c = 0; c < K; ++c) {
-        int64_t items = 0, run = 0;
-        int32_t rb = -1;
-        for (int64_t i = chunk_blk_off[(size_t)c]; i < chunk_blk_off[(size_t)c + 1]; ++i) {
-          if (blk_cnt[(size_t)i] < t) continue;
-          if (blk_rb[(size_t)i] != rb || run == item_blocks) {
-            ++items;
-            run = 0;
-            rb = blk_rb[(size_t)i];
-          }
-          ++run;
+  // Threshold per row chunk: the low one while the chunk's items fit one round of workgroups (blocks are sorted by
+  // chunk, then row block, so the items of a chunk are runs of equal row block cut every item_blocks blocks).
+  out.min_nnz_used.assign((size_t)K, min_nnz);
+  if (max_items > 0 && item_blocks > 0 && min_nnz_many > min_nnz) {
+    std::vector<int64_t> off((size_t)K + 1, 0);
+    size_t w = 0;
+    dense_entries = 0;
+    for (int c = 0; c < K; ++c) {
+      int64_t items = 0, run = 0;
+      int32_t rb = -1;
+      for (int64_t i = chunk_blk_off[(size_t)c]; i < chunk_blk_off[(size_t)c + 1]; ++i) {
+        if (blk_rb[(size_t)i] != rb || run == item_blocks) {
+          ++items;
+          run = 0;
+          rb = blk_rb[(size_t)i];
         }
-        worst = std::max(worst, items);
+        ++run;
       }
-      return worst;
-    };
-    while (worst_items(threshold) > max_items && threshold < RB * CB) threshold = std::max(threshold + 1, (int)(threshold * 1.05));
-    if (threshold != min_nnz) {  // drop the blocks below the raised threshold
-      std::vector<int64_t> off((size_t)K + 1, 0);
-      size_t w = 0;
-      dense_entries = 0;
-      for (int c = 0; c < K; ++c) {
-        for (int64_t i = chunk_blk_off[(size_t)c]; i < chunk_blk_off[(size_t)c + 1]; ++i)
-          if (blk_cnt[(size_t)i] >= threshold) {
-            blk_rb[w] = blk_rb[(size_t)i];
-            blk_cb[w] = blk_cb[(size_t)i];
-            blk_cnt[w] = blk_cnt[(size_t)i];
-            dense_entries += blk_cnt[w];
-            ++w;
-          }
-        off[(size_t)c + 1] = (int64_t)w;
-      }
-      blk_rb.resize(w);
-      blk_cb.resize(w);
-      blk_cnt.resize(w);
-      chunk_blk_off.swap(off);
+      const int threshold = items > max_items ? min_nnz_many : min_nnz;
+      out.min_nnz_used[(size_t)c] = threshold;
+      for (int64_t i = chunk_blk_off[(size_t)c]; i < chunk_blk_off[(size_t)c + 1]; ++i)
+        if (blk_cnt[(size_t)i] >= threshold) {
+          blk_rb[w] = blk_rb[(size_t)i];
+          blk_cb[w] = blk_cb[(size_t)i];
+          blk_cnt[w] = blk_cnt[(size_t)i];
+          dense_entries += blk_cnt[w];
+          ++w;
+        }
+      off[(size_t)c + 1] = (int64_t)w;
     }
+    blk_rb.resize(w);
+    blk_cb.resize(w);
+    blk_cnt.resize(w);
+    chunk_blk_off.swap(off);
   }
-  out.min_nnz_used.assign(1, threshold);
   if (blk_rb.empty() || (double)dense_entries < min_share * (double)nnz) return true;
   // pass 2: split the entries
   const int64_t nb = (int64_t)blk_rb.size();
@@ -339,13 +329,14 @@ struct gnnstage_dense_plan {
 };
 
 static int create_dense_plan(const int64_t *ptr, const int32_t *idx, int64_t n_vertices, int32_t n_chunks, const int64_t *chunk_ptr,
-                             int32_t min_nnz, double min_share, int32_t item_blocks, int64_t max_items, gnnstage_dense_plan **out) {
+                             int32_t min_nnz, double min_share, int32_t item_blocks, int64_t max_items, int32_t min_nnz_many,
+                             gnnstage_dense_plan **out) {
   if (!ptr || !chunk_ptr || !out || n_vertices <= 0 || n_chunks <= 0 || (ptr[n_vertices] > 0 && !idx)) return GNNSTAGE_EINVAL;
   if (chunk_ptr[0] != 0 || chunk_ptr[n_chunks] != n_vertices) return GNNSTAGE_EINVAL;
   for (int c = 0; c < n_chunks; ++c)
     if (chunk_ptr[c] > chunk_ptr[c + 1]) return GNNSTAGE_EINVAL;
   gnnstage_dense_plan *h = new gnnstage_dense_plan();
-  if (!build_dense_plan(ptr, idx, n_vertices, n_chunks, chunk_ptr, min_nnz, min_share, h->p, item_blocks, max_items)) {
+  if (!build_dense_plan(ptr, idx, n_vertices, n_chunks, chunk_ptr, min_nnz, min_share, h->p, item_blocks, max_items, min_nnz_many)) {
     delete h;
     return GNNSTAGE_EINVAL;
   }
@@ -356,14 +347,14 @@ static int create_dense_plan(const int64_t *ptr, const int32_t *idx, int64_t n_v
 extern "C" int gnnstage_dense_plan_create(const int64_t *ptr, const int32_t *idx, int64_t n_vertices, int32_t n_chunks,
                                           const int64_t *chunk_ptr, int32_t min_nnz, double min_share,
                                           gnnstage_dense_plan **out) {
-  return create_dense_plan(ptr, idx, n_vertices, n_chunks, chunk_ptr, min_nnz, min_share, 0, 0, out);
+  return create_dense_plan(ptr, idx, n_vertices, n_chunks, chunk_ptr, min_nnz, min_share, 0, 0, 0, out);
 }
 
 extern "C" int gnnstage_dense_plan_create_capped(const int64_t *ptr, const int32_t *idx, int64_t n_vertices, int32_t n_chunks,
                                                  const int64_t *chunk_ptr, int32_t min_nnz, double min_share, int32_t item_blocks,
-                                                 int64_t max_items, gnnstage_dense_plan **out) {
-  if (item_blocks <= 0 || max_items <= 0) return GNNSTAGE_EINVAL;
-  return create_dense_plan(ptr, idx, n_vertices, n_chunks, chunk_ptr, min_nnz, min_share, item_blocks, max_items, out);
+                                                 int64_t max_items, int32_t min_nnz_many, gnnstage_dense_plan **out) {
+  if (item_blocks <= 0 || max_items <= 0 || min_nnz_many < min_nnz) return GNNSTAGE_EINVAL;
+  return create_dense_plan(ptr, idx, n_vertices, n_chunks, chunk_ptr, min_nnz, min_share, item_blocks, max_items, min_nnz_many, out);
 }
 
 extern "C" int64_t gnnstage_dense_plan_get(const gnnstage_dense_plan *h, int32_t what, const void **data) {

@@ -29,14 +29,16 @@ struct DensePlan {
   std::vector<int64_t> blk_e0;          // n_blocks + 1: entries of a block
   std::vector<uint16_t> ent_pos;        // (row inside the block) << 8 | column inside the block
   std::vector<int64_t> ent_orig;        // position in the original index
-  std::vector<int32_t> min_nnz_used;    // one entry: the threshold the blocks were selected with (see max_items)
+  std::vector<int32_t> min_nnz_used;    // K entries: the threshold the blocks of every row chunk were selected with
   int64_t n_blocks() const { return (int64_t)blk_rb.size(); }
 };
 
 // min_share: the plan is only activated when at least this share of all entries falls into dense blocks.
 // max_items > 0: the dense kernel serves the blocks of a row block in items of at most item_blocks blocks, one
-// workgroup per item and column half, and a launch should not need a second round of workgroups; the threshold
-// is raised from min_nnz in steps of 5 % until no chunk has more than max_items items.
+// workgroup per item and column half.  A launch (one row chunk) that fits one round of workgroups can afford the low
+// threshold min_nnz: its time is set by its longest item whatever the number of blocks.  A chunk with more than
+// max_items items at min_nnz needs several rounds, every block then costs time, and it takes min_nnz_many instead.
 // Returns false on invalid input (an index entry outside [0, n)).
 bool build_dense_plan(const int64_t *ptr, const int32_t *idx, int64_t n, int K, const int64_t *chunk_ptr,
-                      int min_nnz, double min_share, DensePlan &out, int item_blocks = 0, int64_t max_items = 0);
+                      int min_nnz, double min_share, DensePlan &out, int item_blocks = 0, int64_t max_items = 0,
+                      int min_nnz_many = 0);

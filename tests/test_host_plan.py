@@ -266,31 +266,40 @@ def _items_per_chunk(d, K, item_blocks):
     return out
 
 
-def test_dense_plan_raises_the_threshold_until_a_launch_fits_one_round():
-    """With a limit on the items of a chunk the threshold goes up in steps of 5 % until every chunk fits; the blocks
-    that remain are exactly those of an uncapped plan built with the raised threshold."""
+def test_dense_plan_threshold_per_chunk_by_rounds_of_workgroups():
+    """A chunk whose items at the low threshold fit one round keeps it; a chunk with more items takes the other
+    threshold; the blocks of every chunk are exactly those of an uncapped plan built with that chunk's threshold."""
     g = _lib()
     row_ptr, col = make_graph(CONFIGS["c1_s"])
     n = len(row_ptr) - 1
-    chunk_ptr = graphs.ragged_chunks(n, 5, 3)
-    free = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, 6, 0.0)
-    assert int(free["min_nnz_used"][0]) == 6
-    worst = max(_items_per_chunk(free, 5, 4))
-    assert worst > 8, "graph too small for this test"
-    same = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, 6, 0.0, item_blocks=4, max_items=worst)   # already fits
-    assert int(same["min_nnz_used"][0]) == 6 and np.array_equal(same["blk_e0"], free["blk_e0"])
-    capped = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, 6, 0.0, item_blocks=4, max_items=worst // 2)
-    t = int(capped["min_nnz_used"][0])
-    assert t > 6 and max(_items_per_chunk(capped, 5, 4)) <= worst // 2
-    ladder = [6]
-    while ladder[-1] < t:
-        ladder.append(max(ladder[-1] + 1, int(ladder[-1] * 1.05)))
-    assert ladder[-1] == t                                                    # a rung of the 5 % ladder ...
-    below = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, ladder[-2], 0.0)
-    assert max(_items_per_chunk(below, 5, 4)) > worst // 2                    # ... and the first one that fits
-    ref = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, t, 0.0)
-    for key in ("blk_rb", "blk_cb", "blk_e0", "ent_pos", "ent_orig", "rem_ptr", "rem_idx", "chunk_blk_off"):
-        assert np.array_equal(capped[key], ref[key]), key
+    K = 5
+    chunk_ptr = np.array([0, n // 2, n // 2 + n // 8, n // 2 + n // 4, n // 2 + 3 * n // 8, n], dtype=np.int64)  # one heavy chunk
+    low, high = 6, 30
+    free = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, low, 0.0)
+    assert list(free["min_nnz_used"]) == [low] * K
+    items = _items_per_chunk(free, K, 4)
+    limit = sorted(items)[-2]                 # all chunks but the heaviest fit
+    assert items[0] == max(items) > limit > 0
+    capped = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, low, 0.0, item_blocks=4, max_items=limit, min_nnz_many=high)
+    assert list(capped["min_nnz_used"]) == [high] + [low] * (K - 1)
+    strict = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, high, 0.0)
+    for k in range(K):
+        ref = strict if k == 0 else free
+        a0, a1 = capped["chunk_blk_off"][k], capped["chunk_blk_off"][k + 1]
+        r0, r1 = ref["chunk_blk_off"][k], ref["chunk_blk_off"][k + 1]
+        assert a1 - a0 == r1 - r0
+        assert np.array_equal(capped["blk_rb"][a0:a1], ref["blk_rb"][r0:r1]) and np.array_equal(capped["blk_cb"][a0:a1], ref["blk_cb"][r0:r1])
+        ea, er = capped["blk_e0"], ref["blk_e0"]
+        assert np.array_equal(np.diff(ea[a0:a1 + 1]), np.diff(er[r0:r1 + 1]))
+        assert np.array_equal(capped["ent_orig"][ea[a0]:ea[a1]], ref["ent_orig"][er[r0]:er[r1]])
+        assert np.array_equal(capped["ent_pos"][ea[a0]:ea[a1]], ref["ent_pos"][er[r0]:er[r1]])
+    # every entry still exactly once: dense entries + remainder
+    seen = np.zeros(row_ptr[-1], dtype=np.int32)
+    seen[capped["rem_orig"]] += 1
+    seen[capped["ent_orig"]] += 1
+    assert np.all(seen == 1)
+    same = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, low, 0.0, item_blocks=4, max_items=max(items), min_nnz_many=high)
+    assert list(same["min_nnz_used"]) == [low] * K and np.array_equal(same["blk_e0"], free["blk_e0"])
 
 
 def _desc(g, **over):
