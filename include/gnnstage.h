@@ -226,8 +226,8 @@ int gnnstage_plan_pack(int64_t n, int64_t nnz, const int32_t *idx, int32_t n_chu
  * table.  Every piece carries the index of the fp32 partial-sum slot it writes (consecutive per row).
  * force_slot (one byte per vertex, may be NULL) marks rows whose sum has parts outside this index: such a row
  * always writes partial sums (never the finished row), and gets no task at all when it is empty here.
- * Tasks are emitted class-major: the pieces of class 0, ..., class n_classes-1, then pieces without a
- * class, then whole rows; class_off (n_classes + 1 entries, may be NULL) receives where each class
+ * Tasks are emitted class-major: the pieces of class 0, ..., class n_classes-1 (inside a class the longest
+ * piece first, ties in row order), then pieces without a class, then whole rows (both in row order); class_off (n_classes + 1 entries, may be NULL) receives where each class
  * section starts (the last entry is the start of the class-less tail) and slot_class (one byte per slot,
  * may be NULL) the class of every slot (255 = none).  Returns the number of tasks (or a negative code);
  * with non-NULL task arrays also fills them (capacity checked).  idx may be NULL when n_classes == 1. */

@@ -144,6 +144,14 @@ extern "C" int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, i
   // workgroups serve which class is decided at launch time (one class per XCD when all are active).
   std::vector<Task> out;
   out.reserve(pieces.size() + whole.size() + (size_t)slots);
+  if (classes) {
+    // Inside a class the longest pieces go first: the waves of an XCD then work on pieces of similar length at any
+    // time, and since every piece walks its class's source range upwards they sweep that range together (what one
+    // wave brings into the L2 the others find there); it is also the better packing order for the tail.  Pieces
+    // without a class and whole rows stay in row order: their output rows and metadata are then neighbours.
+    auto longer = [](const Task &x, const Task &y) { return x.ne > y.ne; };
+    for (auto &v : by_class) std::stable_sort(v.begin(), v.end(), longer);
+  }
   for (size_t c = 0; c < by_class.size(); ++c) {
     if (class_off) class_off[c] = (int64_t)out.size();
     out.insert(out.end(), by_class[c].begin(), by_class[c].end());
