@@ -169,6 +169,12 @@ int update_history(gnnstage_t *st, void *hip_stream);
  * backward pass. */
 int gnnstage_set_dropout_seed(gnnstage_t *st, uint64_t seed);
 
+/* Changes dropout_p for the passes that follow (Section 5 evaluates the trained model: a forward pass with
+ * rate 0, then training goes on with the old rate).  A forward pass and the backward pass that belongs to it must
+ * run with the same rate.  EORDER inside a forward or a backward pass, EINVAL outside [0, 1) or for a positive
+ * rate on a GNNSTAGE_GCNII stage. */
+int gnnstage_set_dropout_rate(gnnstage_t *st, float dropout_p);
+
 /* Synchronises the device and frees the handle (the workspace stays with the caller). */
 int gnnstage_destroy(gnnstage_t *st);
 

@@ -120,6 +120,8 @@ def _load():
     lib.gnnstage_profile_read.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     lib.gnnstage_profile_reset.restype = C.c_int
     lib.gnnstage_profile_reset.argtypes = [C.c_void_p]
+    lib.gnnstage_set_dropout_rate.restype = C.c_int
+    lib.gnnstage_set_dropout_rate.argtypes = [C.c_void_p, C.c_float]
     lib.gnnstage_set_dropout_seed.restype = C.c_int
     lib.gnnstage_set_dropout_seed.argtypes = [C.c_void_p, C.c_uint64]
     lib.gnnstage_partition_chunks.restype = C.c_int
@@ -389,6 +391,9 @@ class GnnStage:
 
     def gnnstage_set_dropout_seed(self, seed: int) -> None:
         self._check(lib.gnnstage_set_dropout_seed(self._h, int(seed) & ((1 << 64) - 1)))
+
+    def gnnstage_set_dropout_rate(self, dropout_p: float) -> None:
+        self._check(lib.gnnstage_set_dropout_rate(self._h, float(dropout_p)))
 
     def update_history(self, stream=None) -> None:
         self._check(lib.update_history(self._h, self._stream(stream)))

@@ -1949,6 +1949,16 @@ extern "C" int gnnstage_layer_order(const gnnstage_t *st, int32_t layer) {
   return st->s.tf[layer] ? 1 : 0;
 }
 
+extern "C" int gnnstage_set_dropout_rate(gnnstage_t *st, float dropout_p) {
+  if (!st) return GNNSTAGE_EINVAL;
+  if ((!st->order.empty() && (int)st->order.size() < st->s.K) || (st->n_bwd > 0 && st->n_bwd < st->s.K))
+    return fail(st, GNNSTAGE_EORDER, "the dropout rate cannot change inside a forward or a backward pass");
+  if (!(dropout_p >= 0.f && dropout_p < 1.f)) return fail(st, GNNSTAGE_EINVAL, "dropout_p must be in [0, 1)");
+  if (dropout_p > 0.f && st->s.variant == GNNSTAGE_GCNII) return fail(st, GNNSTAGE_EINVAL, "no dropout in GCNII layers");
+  st->dropout_p = dropout_p;
+  return GNNSTAGE_OK;
+}
+
 extern "C" int gnnstage_set_dropout_seed(gnnstage_t *st, uint64_t seed) {
   if (!st) return GNNSTAGE_EINVAL;
   if ((!st->order.empty() && (int)st->order.size() < st->s.K) || (st->n_bwd > 0 && st->n_bwd < st->s.K))

@@ -546,6 +546,34 @@ def test_output_dropout_of_gcn_and_sage_layers(monkeypatch, rate, seed, variant,
     _parity(make_problem(wb, dropout_p=rate, dropout_seed=seed), TOL_BF16, need_input_grad=False)
 
 
+@pytest.mark.parametrize("variant", ["gcn", "resgcn"])
+def test_dropout_rate_switched_off_for_an_evaluation_pass_and_on_again(variant):
+    import paper_2308_10087_amd as g
+    dims = (24, 24, 24)
+    p = make_problem(small(dims=dims, n=500, k=4, variant=variant), first_stage=False, dropout_p=0.5, dropout_seed=3)
+    p0 = make_problem(small(dims=dims, n=500, k=4, variant=variant), first_stage=False)
+    plain = _gpu(p0).run()
+    run = _gpu(p)
+    run.forward()
+    dropped = run.cur[p.L].clone()
+    assert not torch.equal(dropped, plain.cur[p.L])
+    run.stage.gnnstage_set_dropout_rate(0.0)
+    run.stage.forward_pass(p.order)
+    assert torch.equal(run.cur[p.L], plain.cur[p.L])            # the evaluation pass is the stage without dropout
+    run.stage.stage_forward_chunk(int(p.order[0]), 0)
+    with pytest.raises(g.GnnStageError) as e:
+        run.stage.gnnstage_set_dropout_rate(0.5)                # not inside a pass
+    assert e.value.code == -3
+    for pos, k in enumerate(p.order[1:], start=1):
+        run.stage.stage_forward_chunk(int(k), pos)
+    run.stage.gnnstage_set_dropout_rate(0.5)
+    run.forward()
+    assert torch.equal(run.cur[p.L], dropped)                   # and training goes on as before
+    with pytest.raises(g.GnnStageError) as e:
+        run.stage.gnnstage_set_dropout_rate(1.0)
+    assert e.value.code == -1
+
+
 def test_no_dropout_in_gcnii_layers():
     import paper_2308_10087_amd as g
     p = make_problem(small(dims=(16,) * 3, n=300, k=3, variant="gcnii"))

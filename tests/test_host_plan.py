@@ -33,7 +33,8 @@ def test_library_exports_every_declared_symbol():
     assert {"gnnstage_create", "stage_forward_chunk", "stage_backward_chunk", "update_history",
             "gnnstage_destroy", "gnntrain_create", "gnntrain_epoch", "gnntrain_chunk_order", "gnntrain_softmax_xent",
             "gnntrain_adam_step", "gnntrain_sgd_step", "gnntrain_sum", "gnnstage_query", "gnnstage_buffer",
-            "gnnstage_partition_chunks", "gnnstage_permute_csr", "gnnstage_set_dropout_seed"} <= set(declared)
+            "gnnstage_partition_chunks", "gnnstage_permute_csr", "gnnstage_set_dropout_seed",
+            "gnnstage_set_dropout_rate"} <= set(declared)
     for name in declared:
         assert hasattr(g.lib, name), name
     assert g.gnnstage_version() >= 100
