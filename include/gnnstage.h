@@ -282,10 +282,11 @@ int gnnstage_permute_csr(int64_t n, const int64_t *row_ptr, const int32_t *col_i
  *   8 blk_cb (int32, column block)   9 blk_e0 (int64, n_blocks+1)   10 ent_pos (uint16, row_in_block << 8 | col_in_block)
  *   11 ent_orig (int64, position in the original index)   12 min_nnz_used (int32, K: threshold of every row chunk)
  * gnnstage_dense_plan_create_capped: the dense kernel serves the blocks of a row block in items of at most
- * item_blocks blocks, one workgroup per item and column half.  A row chunk whose items at min_nnz fit one round of
- * workgroups (at most max_items items) keeps min_nnz: its launch takes as long as its longest item however many
- * blocks it has.  A chunk with more items needs several rounds, every block costs time, and its blocks are
- * selected with min_nnz_many (>= min_nnz) instead.                                                          */
+ * item_blocks blocks, one workgroup per item and column half.  A launch (one row chunk) that fits one round of
+ * workgroups takes as long as its longest item however many blocks it has, so every chunk takes the lowest rung of
+ * a 5 % ladder from min_nnz (t -> max(t + 1, floor(1.05 t))) at which it has at most max_items items; a chunk that
+ * does not get there below min_nnz_many (>= min_nnz) needs several rounds, every block costs time, and it takes
+ * min_nnz_many.                                                                                              */
 typedef struct gnnstage_dense_plan gnnstage_dense_plan;
 int gnnstage_dense_plan_create(const int64_t *ptr, const int32_t *idx, int64_t n_vertices, int32_t n_chunks,
                                const int64_t *chunk_ptr, int32_t min_nnz, double min_share,

@@ -107,9 +107,9 @@ std::vector<int64_t> class_bounds_by_entries(const int64_t *ptr, const int32_t *
 }
 
 // Dense blocks: switched on for bf16 stages whose aggregations all gather rows of width 128 or 256.
-// GNNSTAGE_DENSE=0 switches them off; GNNSTAGE_DENSE_MIN_NNZ (entries a 128 x 64 block needs; default: 3.4 % of
-// its cells for a chunk whose launch fits one round of workgroups, 5 % for a chunk that needs several, see
-// dense_max_items), GNNSTAGE_DENSE_MIN_SHARE (share of all entries that must fall into such blocks,
+// GNNSTAGE_DENSE=0 switches them off; GNNSTAGE_DENSE_MIN_NNZ (entries a 128 x 64 block needs; default: from 3.4 %
+// of its cells upwards, as low as the chunk's launch still fits one round of workgroups, 5 % for a chunk that needs
+// several, see dense_max_items), GNNSTAGE_DENSE_MIN_SHARE (share of all entries that must fall into such blocks,
 // default 0.2) and GNNSTAGE_DENSE_MIN_ENTRIES (see below) let tests force them on small graphs.
 bool dense_enabled() {
   const char *e = getenv("GNNSTAGE_DENSE");

@@ -260,17 +260,24 @@ bool build_dense_plan(const int64_t *ptr, const int32_t *idx, int64_t n, int K, 
     size_t w = 0;
     dense_entries = 0;
     for (int c = 0; c < K; ++c) {
-      int64_t items = 0, run = 0;
-      int32_t rb = -1;
-      for (int64_t i = chunk_blk_off[(size_t)c]; i < chunk_blk_off[(size_t)c + 1]; ++i) {
-        if (blk_rb[(size_t)i] != rb || run == item_blocks) {
-          ++items;
-          run = 0;
-          rb = blk_rb[(size_t)i];
+      auto items_at = [&](int t) {
+        int64_t items = 0, run = 0;
+        int32_t rb = -1;
+        for (int64_t i = chunk_blk_off[(size_t)c]; i < chunk_blk_off[(size_t)c + 1]; ++i) {
+          if (blk_cnt[(size_t)i] < t) continue;
+          if (blk_rb[(size_t)i] != rb || run == item_blocks) {
+            ++items;
+            run = 0;
+            rb = blk_rb[(size_t)i];
+          }
+          ++run;
         }
-        ++run;
-      }
-      const int threshold = items > max_items ? min_nnz_many : min_nnz;
+        return items;
+      };
+      // the lowest rung of a 5 % ladder from min_nnz at which the chunk fits one round; min_nnz_many if none below it does
+      int threshold = min_nnz;
+      while (threshold < min_nnz_many && items_at(threshold) > max_items) threshold = std::max(threshold + 1, (int)(threshold * 1.05));
+      if (threshold > min_nnz_many) threshold = min_nnz_many;
       out.min_nnz_used[(size_t)c] = threshold;
       for (int64_t i = chunk_blk_off[(size_t)c]; i < chunk_blk_off[(size_t)c + 1]; ++i)
         if (blk_cnt[(size_t)i] >= threshold) {

@@ -35,9 +35,10 @@ struct DensePlan {
 
 // min_share: the plan is only activated when at least this share of all entries falls into dense blocks.
 // max_items > 0: the dense kernel serves the blocks of a row block in items of at most item_blocks blocks, one
-// workgroup per item and column half.  A launch (one row chunk) that fits one round of workgroups can afford the low
-// threshold min_nnz: its time is set by its longest item whatever the number of blocks.  A chunk with more than
-// max_items items at min_nnz needs several rounds, every block then costs time, and it takes min_nnz_many instead.
+// workgroup per item and column half.  A launch (one row chunk) that fits one round of workgroups can afford a low
+// threshold: its time is set by its longest item whatever the number of blocks.  Every chunk takes the lowest rung
+// of a 5 % ladder from min_nnz at which it has at most max_items items; a chunk that does not get there below
+// min_nnz_many needs several rounds, every block then costs time, and it takes min_nnz_many.
 // Returns false on invalid input (an index entry outside [0, n)).
 bool build_dense_plan(const int64_t *ptr, const int32_t *idx, int64_t n, int K, const int64_t *chunk_ptr,
                       int min_nnz, double min_share, DensePlan &out, int item_blocks = 0, int64_t max_items = 0,

@@ -268,8 +268,9 @@ def _items_per_chunk(d, K, item_blocks):
 
 
 def test_dense_plan_threshold_per_chunk_by_rounds_of_workgroups():
-    """A chunk whose items at the low threshold fit one round keeps it; a chunk with more items takes the other
-    threshold; the blocks of every chunk are exactly those of an uncapped plan built with that chunk's threshold."""
+    """A chunk whose items at the low threshold fit one round keeps it; a chunk with more items climbs a 5 % ladder
+    until it fits, at most to the other threshold; the blocks of every chunk are exactly those of an uncapped plan
+    built with that chunk's threshold."""
     g = _lib()
     row_ptr, col = make_graph(CONFIGS["c1_s"])
     n = len(row_ptr) - 1
@@ -282,8 +283,18 @@ def test_dense_plan_threshold_per_chunk_by_rounds_of_workgroups():
     limit = sorted(items)[-2]                 # all chunks but the heaviest fit
     assert items[0] == max(items) > limit > 0
     capped = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, low, 0.0, item_blocks=4, max_items=limit, min_nnz_many=high)
-    assert list(capped["min_nnz_used"]) == [high] + [low] * (K - 1)
-    strict = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, high, 0.0)
+    t0 = int(capped["min_nnz_used"][0])
+    assert list(capped["min_nnz_used"][1:]) == [low] * (K - 1) and low < t0 <= high
+    ladder = [low]
+    while ladder[-1] < t0:
+        ladder.append(max(ladder[-1] + 1, int(ladder[-1] * 1.05)))
+    assert ladder[-1] == t0 or t0 == high                                     # a rung of the ladder, or its end
+    strict = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, t0, 0.0)
+    if t0 < high:                                                             # the first rung that fits
+        assert _items_per_chunk(strict, K, 4)[0] <= limit
+        assert _items_per_chunk(g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, ladder[-2], 0.0), K, 4)[0] > limit
+    never = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, low, 0.0, item_blocks=4, max_items=1, min_nnz_many=high)
+    assert list(never["min_nnz_used"]) == [high] * K                          # nothing fits: the other threshold
     for k in range(K):
         ref = strict if k == 0 else free
         a0, a1 = capped["chunk_blk_off"][k], capped["chunk_blk_off"][k + 1]
@@ -301,6 +312,23 @@ def test_dense_plan_threshold_per_chunk_by_rounds_of_workgroups():
     assert np.all(seen == 1)
     same = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, low, 0.0, item_blocks=4, max_items=max(items), min_nnz_many=high)
     assert list(same["min_nnz_used"]) == [low] * K and np.array_equal(same["blk_e0"], free["blk_e0"])
+
+
+def test_benchmark_graph_stays_near_the_low_threshold_in_every_chunk():
+    """configs[1] with the stage's own settings (3.4 % of a block's cells, items of 32 blocks, 1.1 x 512 workgroups of
+    two column halves): every chunk's launch fits one round, two thirds of the entries are dense."""
+    g = _lib()
+    w = CONFIGS["c1"]
+    row_ptr, col = make_graph(w)
+    n = len(row_ptr) - 1
+    K = w.n_chunks
+    chunk_ptr = (np.arange(K + 1, dtype=np.int64) * n) // K
+    low, high, max_items = 128 * 64 * 34 // 1000, 128 * 64 // 20, 2 * 256 * 11 // 10 // 2
+    d = g.gnnstage_dense_plan(row_ptr, col, chunk_ptr, low, 0.2, item_blocks=32, max_items=max_items, min_nnz_many=high)
+    assert all(low <= t <= 1.1 * low for t in d["min_nnz_used"]) and low in d["min_nnz_used"]
+    items = _items_per_chunk(d, K, 32)
+    assert max(items) <= max_items and min(items) > 0.8 * max_items      # one round, and a full one
+    assert 0.6 < d["blk_e0"][-1] / len(col) < 0.75
 
 
 def _desc(g, **over):
