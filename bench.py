@@ -56,6 +56,9 @@ def main():
     ap.add_argument("--partition", action="store_true",
                     help="chunks from the library's locality-aware partitioner instead of index ranges (not the benchmark configuration)")
     ap.add_argument("--partition-by-entries", action="store_true", help="with --partition: balance the chunks by entries")
+    ap.add_argument("--caller-weights", action="store_true",
+                    help="hand the edge weights to the library (edge_val) instead of letting it compute the normalisation: "
+                         "dense blocks then run from stored weight tiles instead of bit patterns")
     ap.add_argument("--train-epochs", type=int, default=0,
                     help="also time this many epochs of the whole training loop (head + Adam) around the same stage")
     args = ap.parse_args()
@@ -117,8 +120,13 @@ def main():
     if not gcn:
         import math
         beta = np.array([math.log(0.5 / l + 1.0) for l in range(w.gcnii_first_layer, w.gcnii_first_layer + L)], np.float32)
+    edge_val = None
+    if args.caller_weights:  # the weights the library would compute itself: 1 / sqrt(D_v D_u), or 1 / D_v for the mean aggregator
+        deg = np.diff(row_ptr).astype(np.float64)
+        inv = 1.0 / np.maximum(deg, 1.0) if sage else 1.0 / np.sqrt(np.maximum(deg, 1.0))
+        edge_val = (np.repeat(inv, np.diff(row_ptr)) * (1.0 if sage else inv[col])).astype(np.float32)
     t1 = time.time()
-    st = g.GnnStage(row_ptr, col, chunk_ptr, dims, W=W, cur=cur, hist=hist, dW=dW, bias=bias, dbias=dbias,
+    st = g.GnnStage(row_ptr, col, chunk_ptr, dims, W=W, cur=cur, hist=hist, dW=dW, bias=bias, dbias=dbias, edge_val=edge_val,
                     variant={"gcn": g.GNNSTAGE_GCN, "gcnii": g.GNNSTAGE_GCNII, "sage": g.GNNSTAGE_SAGE,
                              "resgcn": g.GNNSTAGE_RESGCN}[w.variant], alpha=w.gcnii_alpha, beta=beta, h0=h0,
                     grad_h0=grad_h0, dtype=g.GNNSTAGE_BF16 if bf else g.GNNSTAGE_F32, level0_f32=w.level0_f32,
@@ -232,7 +240,7 @@ def main():
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
     traffic = None  # HBM-side bytes per launch from the committed rocprofv3 counter summary, if it covers this kernel
     tpath = os.path.join(ROOT, "profiles", f"stage_{w.name}_pmc_traffic.md")
-    if os.path.exists(tpath) and not args.partition:  # the counters were read on the benchmark configuration only
+    if os.path.exists(tpath) and not args.partition and not args.caller_weights:  # the counters were read on the benchmark configuration only
         for line in open(tpath):
             parts = [x.strip() for x in line.split("|")]
             if len(parts) == 3 and parts[0] == f"traffic {w.name}" and parts[1] == dom_name:
@@ -294,7 +302,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf else "f32", "data": "synthetic",
         "config": {"workload": f"configs[{args.workload[1:]}] {w.name}: {'R-MAT' if w.kind == 'rmat' else 'Erdos-Renyi'} n={n} nnz={nnz} dims={dims} chunks={K} "
-                               f"{w.variant} {'bf16 levels, fp32 level 0' if w.level0_f32 else w.dtype}{cut_note}",
+                               f"{w.variant} {'bf16 levels, fp32 level 0' if w.level0_f32 else w.dtype}{cut_note}{' edge weights given by the caller' if args.caller_weights else ''}",
                    "max_degree": stats["max_degree"], "step": "forward all chunks + backward all chunks + update_history"},
         "kernel_ms_per_step": kernels_ms,
         "gemm": gemm,

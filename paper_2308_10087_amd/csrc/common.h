@@ -146,7 +146,8 @@ struct DenseArgs {
   const ChunkMask *item_chunks;   // chunks its blocks' columns come from
   int32_t n_items;
   const int32_t *blk_cb;          // column block of every block: column slots 64 * cb ...
-  const bf16_t *tiles;            // per block two row-major 128 x 64 weight tiles: nearest bf16, then the remainder's bf16
+  const bf16_t *tiles;            // per block two 128 x 64 weight tiles (nearest bf16, then the remainder's bf16) as
+                                  // launch_dense_expand writes them: [32-row group][16-column step][lane][8 values]
   // weights of the form s(row) * s(column) instead (bits != nullptr): per block 256 words of pattern bits
   // (word t: row t / 2, columns 32 * (t % 2) ..), s per column slot (0 = padding) and per row position of the chunk
   const uint32_t *bits;

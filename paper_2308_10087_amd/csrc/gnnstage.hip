@@ -818,10 +818,10 @@ int run_spmm(gnnstage *st, const SpmmArgs &a_in, bool transposed, int chunk, int
         da.bits = st->at<uint32_t>(lay.d_bits[dir]);
         da.colscale = st->at<float>(lay.d_colscale[dir]);
         da.rowscale = st->at<float>(lay.d_rowscale[dir]) + st->rowscale_off[dir][(size_t)chunk];
-        da.zero_row = st->at<char>(lay.zero_row);
       } else {
         da.tiles = st->at<bf16_t>(lay.d_tiles[dir]);
       }
+      da.zero_row = st->at<char>(lay.zero_row);
       da.colslot = st->at<uint32_t>(lay.d_colslot[dir]);
       da.src_sel = a.src_sel;
       da.src_unsel = a.src_unsel;
