@@ -27,7 +27,7 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int DH = 128;      // columns one workgroup owns
 constexpr int TILE_ELEMS = kDenseRB * kDenseCB;  // one weight tile in memory
-constexpr int HQ_BUF = (kDenseCB / 8) * DH;      // 16-byte words of one source-row buffer of the pattern kernel
+constexpr int HQ_BUF = (kDenseCB / 8) * DH;      // 16-byte words of one source-row buffer in LDS
 
 __device__ inline bool masks_meet(const ChunkMask &x, const ChunkMask &y) {
   return ((x.w[0] & y.w[0]) | (x.w[1] & y.w[1]) | (x.w[2] & y.w[2]) | (x.w[3] & y.w[3])) != 0;
@@ -57,10 +57,11 @@ __global__ __launch_bounds__(256) void dense_expand_kernel(const int64_t *blk_e0
 // for about half of its 32 cycles, so a loop with more than four vector instructions per matrix instruction
 // is bound by instruction issue, not by the matrix cores.
 //  * A wave owns 32 rows x 128 columns of the accumulator tile, so the A operand of its products is private
-//    to it and never goes through LDS.  Pattern blocks: a lane keeps the 64 pattern bits of its row in two registers and
-//    makes each A fragment of v_mfma_f32_32x32x16_bf16 (its row, eight consecutive columns) by masking the
-//    packed column scales (nearest bf16 and the bf16 of the remainder, one broadcast 16-byte LDS word each)
-//    with the masks of the pattern byte, which come from a 256-entry table in LDS.
+//    to it and never goes through LDS.  Pattern blocks: a lane keeps the 64 pattern bits of its row in two
+//    registers and makes each A fragment of v_mfma_f32_32x32x16_bf16 (its row, eight consecutive columns) by
+//    masking the packed column scales (nearest bf16 and the bf16 of the remainder, one broadcast 16-byte LDS
+//    word each) with the masks of the pattern byte, which come from a 256-entry table in LDS.  Tile blocks:
+//    the eight fragments of a block (four k-steps, upper and lower part) are eight 16-byte loads per lane.
 //  * The 64 source rows of a block are loaded row-wise: a wave takes 16 of them, a lane two columns of each
 //    (one 256-byte request per row; the row's address is a broadcast LDS read of a table resolved once per
 //    item: current or historical buffer by the source's chunk, a row of zeros for padding slots and - in a
