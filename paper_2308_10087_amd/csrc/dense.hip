@@ -89,15 +89,14 @@ __global__ __launch_bounds__(256, 2) void spmm_dense_blocks_kernel(const DenseAr
   int32_t *act = m_cb + kDenseMaxItemBlocks;                            // the item's selected blocks, in order
 
   int item = blockIdx.x, half = blockIdx.y;
-  if constexpr (TILES) {
-    // Both halves of an item read the same 32 KB of weight tiles per block.  Workgroups go to the eight XCDs in
-    // turn, so in a one-dimensional grid the pairs (item, half 0) and (item, half 1) are put eight apart: same
-    // XCD, started together, and the second one finds the tiles in that XCD's L2.
-    if (a.d > DH) {
-      item = (int)(blockIdx.x >> 4) * 8 + (int)(blockIdx.x & 7u);
-      half = (int)(blockIdx.x >> 3) & 1;
-      if (item >= a.n_items) return;  // whole workgroup: the grid is rounded up to groups of eight items
-    }
+  // Both halves of an item read the same weights (32 KB of tiles per block; little for pattern blocks, which
+  // lose nothing by it).  Workgroups go to the eight XCDs in turn, so in a one-dimensional grid the pairs
+  // (item, half 0) and (item, half 1) are put eight apart: same XCD, started together, and the second one finds
+  // the weights in that XCD's L2.
+  if (a.d > DH) {
+    item = (int)(blockIdx.x >> 4) * 8 + (int)(blockIdx.x & 7u);
+    half = (int)(blockIdx.x >> 3) & 1;
+    if (item >= a.n_items) return;  // whole workgroup: the grid is rounded up to groups of eight items
   }
   const int col0 = half * DH;
   const bool drop = a.src_unsel == nullptr;
@@ -341,7 +340,7 @@ int launch_spmm_dense(const DenseArgs &a, hipStream_t s) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     attr_done[a.bits ? 0 : 1] = true;
   }
-  const bool paired = !a.bits && a.d > DH;  // see the kernel: one-dimensional grid, halves of an item on one XCD
+  const bool paired = a.d > DH;  // see the kernel: one-dimensional grid, the halves of an item on one XCD
   const dim3 grid = paired ? dim3((unsigned)((a.n_items + 7) / 8 * 16)) : dim3((unsigned)a.n_items, (unsigned)(a.d / DH));
   hipLaunchKernelGGL(kernel, grid, dim3(256), smem, s, a);
   return (int)hipGetLastError();
