@@ -109,23 +109,22 @@ std::vector<int64_t> class_bounds_by_entries(const int64_t *ptr, const int32_t *
 // Dense blocks: switched on for bf16 stages whose aggregations all gather rows of width 128 or 256.
 // GNNSTAGE_DENSE=0 switches them off; GNNSTAGE_DENSE_MIN_NNZ (entries a 128 x 64 block needs; default: from 3.4 %
 // of its cells upwards, as low as the chunk's launch still fits one round of workgroups, 5 % for a chunk that needs
-// several, see dense_max_items; 5 % and 6.25 % for blocks kept as weight tiles, which read 32 KB each where a
-// pattern block reads 2 KB: c1 with the caller's weights, threshold -> ms per step: 278 -> 19.6, 340 -> 19.5,
-// 500 -> 19.2, 700 -> 19.7; flat, these defaults give 19.5), GNNSTAGE_DENSE_MIN_SHARE (share of all entries that must fall into such blocks,
+// several, see dense_max_items; the same for blocks kept as weight tiles, whose curve is flat from 278 to 500:
+// 18.7 - 18.9 ms per c1 step with the caller's weights), GNNSTAGE_DENSE_MIN_SHARE (share of all entries that must fall into such blocks,
 // default 0.2) and GNNSTAGE_DENSE_MIN_ENTRIES (see below) let tests force them on small graphs.
 bool dense_enabled() {
   const char *e = getenv("GNNSTAGE_DENSE");
   return !(e && atoi(e) == 0);
 }
-int dense_min_nnz(bool stored_tiles) {
+int dense_min_nnz() {
   const char *e = getenv("GNNSTAGE_DENSE_MIN_NNZ");
   if (e && atoi(e) >= 1) return atoi(e);
-  return stored_tiles ? kDenseRB * kDenseCB / 20 : kDenseRB * kDenseCB * 34 / 1000;
+  return kDenseRB * kDenseCB * 34 / 1000;
 }
-int dense_min_nnz_many(bool stored_tiles) {  // for a chunk whose launch needs several rounds of workgroups: every block costs time there
+int dense_min_nnz_many() {  // for a chunk whose launch needs several rounds of workgroups: every block costs time there
   const char *e = getenv("GNNSTAGE_DENSE_MIN_NNZ");
   if (e && atoi(e) >= 1) return atoi(e);
-  return stored_tiles ? kDenseRB * kDenseCB / 16 : kDenseRB * kDenseCB / 20;
+  return kDenseRB * kDenseCB / 20;
 }
 // Items (runs of at most 32 blocks of one row block) of a launch that fits one round of workgroups: one workgroup
 // per item and 128-column half, two workgroups per CU, 256 CUs; a tenth more is harmless because short items end
@@ -233,7 +232,7 @@ struct HostDir {
 void host_mask_set(ChunkMask &m, int c) { m.w[c >> 6] |= 1ull << (c & 63); }
 
 bool make_host_dir(const int64_t *ptr, const int32_t *idx, int64_t n, const std::vector<int64_t> &chunk_ptr,
-                   int classes, bool try_dense, int dense_width, bool stored_tiles, HostDir &h) {
+                   int classes, bool try_dense, int dense_width, HostDir &h) {
   const int K = (int)chunk_ptr.size() - 1;
   h.ptr = ptr;
   h.idx = idx;
@@ -246,8 +245,8 @@ bool make_host_dir(const int64_t *ptr, const int32_t *idx, int64_t n, const std:
     // share of all entries that must be dense: the relative threshold, or the absolute one if that asks for more
     const double nnz = (double)ptr[n];
     const double share = std::max(dense_min_share(), nnz > 0 ? dense_min_entries_per_chunk() * K / nnz : 0.0);
-    if (!build_dense_plan(ptr, idx, n, K, chunk_ptr.data(), dense_min_nnz(stored_tiles), share, h.dp, kDenseItemBlocks,
-                          dense_max_items(dense_width), dense_min_nnz_many(stored_tiles)))
+    if (!build_dense_plan(ptr, idx, n, K, chunk_ptr.data(), dense_min_nnz(), share, h.dp, kDenseItemBlocks, dense_max_items(dense_width),
+                          dense_min_nnz_many()))
       return false;
   }
   if (h.dp.active) {
@@ -1112,7 +1111,7 @@ struct HostPlan {
   HostDir f, b;
 };
 
-int make_host_plan(const gnnstage_desc *d, const Shape &s, bool want_edge, bool stored_tiles, HostPlan &hp, std::string &err) {
+int make_host_plan(const gnnstage_desc *d, const Shape &s, bool want_edge, HostPlan &hp, std::string &err) {
   if (s.nnz > 0 && !d->col_idx) {
     err = "col_idx is NULL";
     return GNNSTAGE_EINVAL;
@@ -1126,8 +1125,8 @@ int make_host_plan(const gnnstage_desc *d, const Shape &s, bool want_edge, bool 
     return GNNSTAGE_EINVAL;
   }
   const bool dense = s.dense_ok();
-  if (!make_host_dir(d->row_ptr, d->col_idx, s.n, s.chunk_ptr, s.classes(), dense, s.dense_width(), stored_tiles, hp.f) ||
-      !make_host_dir(hp.t_ptr.data(), hp.t_row.data(), s.n, s.chunk_ptr, s.classes(), dense, s.dense_width(), stored_tiles, hp.b)) {
+  if (!make_host_dir(d->row_ptr, d->col_idx, s.n, s.chunk_ptr, s.classes(), dense, s.dense_width(), hp.f) ||
+      !make_host_dir(hp.t_ptr.data(), hp.t_row.data(), s.n, s.chunk_ptr, s.classes(), dense, s.dense_width(), hp.b)) {
     err = "cannot plan the aggregation";
     return GNNSTAGE_EINVAL;
   }
@@ -1156,7 +1155,7 @@ extern "C" size_t gnnstage_workspace_size(const gnnstage_desc *desc) {
     return 0;
   }
   HostPlan hp;
-  if (make_host_plan(desc, s, false, desc->edge_val != nullptr, hp, err) != GNNSTAGE_OK) {
+  if (make_host_plan(desc, s, false, hp, err) != GNNSTAGE_OK) {
     g_create_error = err;
     return 0;
   }
@@ -1216,7 +1215,7 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
 
   // ---- host planning -------------------------------------------------------------------
   HostPlan hp;
-  int rc = make_host_plan(d, s, d->edge_val != nullptr, !rank1, hp, err);
+  int rc = make_host_plan(d, s, d->edge_val != nullptr, hp, err);
   if (rc != GNNSTAGE_OK) return fail(nullptr, rc, err);
   const std::vector<int64_t> &t_ptr = hp.t_ptr, &t_edge = hp.t_edge;
   int vbits = 0;
