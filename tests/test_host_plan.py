@@ -382,3 +382,13 @@ def test_generated_graphs_are_symmetric_sorted_and_reproducible():
     has_loop = np.zeros(n, dtype=bool)
     has_loop[rows[rows == a_col]] = True
     assert has_loop.all()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The build covers one pipeline stage on one GPU: asking the benchmark for more ends with a message, before any GPU work."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and "--gpus must be 1" in r.stderr
+    assert r.stdout.strip() == ""  # no result line
