@@ -162,17 +162,19 @@ int stage_backward_chunk(gnnstage_t *st, int32_t chunk_id, const void *grad_out_
  * the refresh period, is caller policy).  Levels whose hist pointer aliases cur are skipped. */
 int update_history(gnnstage_t *st, void *hip_stream);
 
-/* Seed of the dropout decisions of the next pass (forward and backward of a pass use the same one).  Feature c
- * of vertex u survives in layer j when the top 24 bits of SplitMix64(key_j + (u * d + c + 1) * G) are at least
- * dropout_p * 2^24, key_j = SplitMix64(seed + (j + 1) * G), G = 0x9E3779B97F4A7C15, d the width of the rows the
- * dropout acts on (the layer's input for GNNSTAGE_RESGCN, its output for GNNSTAGE_GCN / GNNSTAGE_SAGE).  EORDER inside a forward or a
- * backward pass. */
+/* Seed of the dropout decisions of the passes that follow.  Feature c of vertex u survives in layer j when the
+ * top 24 bits of SplitMix64(key_j + (u * d + c + 1) * G) are at least dropout_p * 2^24, key_j = SplitMix64(seed +
+ * (j + 1) * G), G = 0x9E3779B97F4A7C15, d the width of the rows the dropout acts on (the layer's input for
+ * GNNSTAGE_RESGCN, its output for GNNSTAGE_GCN / GNNSTAGE_SAGE).  A pass takes the seed (and the rate) that are
+ * set when its first forward call arrives and keeps them until its last backward call, so the backward pass
+ * redraws the decisions of its own forward pass even if the caller sets a new seed in between.  EORDER inside a
+ * forward or a backward pass. */
 int gnnstage_set_dropout_seed(gnnstage_t *st, uint64_t seed);
 
 /* Changes dropout_p for the passes that follow (Section 5 evaluates the trained model: a forward pass with
- * rate 0, then training goes on with the old rate).  A forward pass and the backward pass that belongs to it must
- * run with the same rate.  EORDER inside a forward or a backward pass, EINVAL outside [0, 1) or for a positive
- * rate on a GNNSTAGE_GCNII stage. */
+ * rate 0, then training goes on with the old rate).  Taken by a pass at its first forward call, like the seed.
+ * EORDER inside a forward or a backward pass, EINVAL outside [0, 1) or for a positive rate on a GNNSTAGE_GCNII
+ * stage. */
 int gnnstage_set_dropout_rate(gnnstage_t *st, float dropout_p);
 
 /* Synchronises the device and frees the handle (the workspace stays with the caller). */
@@ -245,7 +247,7 @@ int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, int64_t n_ve
 
 /*
  * Chunk partitioner (host only): Algorithm 1's first step, "partition V into K chunks", locality-aware as
- * Section 3.2 asks.  Restreaming FENNEL (Tsourakakis et al., WSDM 2014; Nishimura and Ugander, KDD 2013):
+ * Section 3.3 asks.  Restreaming FENNEL (Tsourakakis et al., WSDM 2014; Nishimura and Ugander, KDD 2013):
  * `passes` streams over the vertices in index order; a vertex leaves its part, then joins the part i that
  * maximises  |N(v) in P_i| - alpha * 1.5 * sqrt(|P_i|)  among the parts with fewer than ceil(slack * n / K)
  * vertices, alpha = balance * sqrt(K) * m / n^1.5 with m the number of undirected edges (balance = 1 is the

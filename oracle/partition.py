@@ -1,6 +1,6 @@
 """CPU oracle of the chunk partitioner (TEST INFRASTRUCTURE ONLY).
 
-Algorithm 1 starts by partitioning the vertex set into K chunks, and Section 3.2 says the partitioner is
+Algorithm 1 starts by partitioning the vertex set into K chunks, and Section 3.3 says the partitioner is
 locality-aware (the paper uses one built on a third-party multilevel partitioner that is not available
 here).  The stand-in is a published streaming heuristic, written out step by step:
 

@@ -109,6 +109,9 @@ struct SpmmArgs {
   int32_t add_ld;
   int64_t add_row0;
   float mask_scale = 1.f;  // SPMM_MASK / SPMM_ADD_MASK: what passes the mask is scaled (1 / (1 - rate) of that dropout)
+  // kernel choice (measurement and test switches, set by the stage from what it read at create)
+  int32_t force_valu = 0;  // vector-ALU aggregation for bf16 rows too
+  int32_t unroll = 2;      // gather slots per wave of the matrix-core aggregation: 2, 4 or 8
 };
 
 // which task the wave `wave` of workgroup `b` runs (-1: none)
@@ -210,6 +213,7 @@ struct GemmNtArgs {
   int32_t out_pad;  // columns [N, out_pad) of every output row are written as zeros (0: none)
   int32_t vec_epi;  // set by the launcher: the epilogue may use 16-byte accesses
   float mask_scale = 1.f;  // EPI_MASK: what passes the mask is scaled (1 / (1 - rate) of that dropout)
+  int32_t ws_min_rows = 65536;  // rows from which the weight-stationary kernel is used (tests force it on small inputs)
 };
 int launch_gemm_nt(const GemmNtArgs &a, int compute_dtype, hipStream_t s);
 

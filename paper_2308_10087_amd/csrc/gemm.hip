@@ -458,12 +458,6 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_bf16_ws_kernel(const GemmNtArg
   }
 }
 
-// GNNSTAGE_GEMM_WS_MIN_ROWS overrides the row count from which the persistent kernel is used (tests force it)
-static int ws_min_rows() {
-  const char *e = getenv("GNNSTAGE_GEMM_WS_MIN_ROWS");
-  return e ? atoi(e) : 65536;
-}
-
 template <int WN, int KS>
 static int launch_ws(const GemmNtArgs &a, hipStream_t s) {
   constexpr int TM = 64 * (4 / WN), LDK = KS * 16 + 8;
@@ -871,7 +865,7 @@ int launch_gemm_nt(const GemmNtArgs &a_in, int compute_dtype, hipStream_t s) {
       hipLaunchKernelGGL((gemm_nt_bf16_kernel<float, false, true>), grid, dim3(256), 0, s, a);
     else if (a.a_dtype == DT_F32)
       hipLaunchKernelGGL((gemm_nt_bf16_kernel<float, false>), grid, dim3(256), 0, s, a);
-    else if (vec && vec_ok(a.Bt, a.ldb, 8) && a.Kp <= 256 && a.N <= 256 && a.M >= ws_min_rows()) {
+    else if (vec && vec_ok(a.Bt, a.ldb, 8) && a.Kp <= 256 && a.N <= 256 && a.M >= a.ws_min_rows) {
       // long operands: persistent weight-stationary kernel (needs a few row tiles per workgroup to pay
       // for loading its panel of Bt into registers)
       if (a.N <= 128 && a.Kp <= 128) return launch_ws<2, 8>(a, s);

@@ -21,16 +21,60 @@ constexpr size_t kAlign = 256;
 
 std::string g_create_error;
 
+// Measurement and test switches.  Defaults are the product path.  The environment is read ONCE per
+// gnnstage_workspace_size / gnnstage_create call (both must see the same values) and the result is kept in
+// the handle; nothing on the launch path looks at the environment.
+//   GNNSTAGE_SPLIT_EDGES (>= 64)      fixed length of the pieces long rows are cut into
+//   GNNSTAGE_XCD_CLASSES (1..32)      source-id classes (1 = off)
+//   GNNSTAGE_CLASS_MIN_ROW            rows from this length on are cut by class
+//   GNNSTAGE_DENSE=0                  no dense blocks
+//   GNNSTAGE_DENSE_MIN_NNZ            entries a 128 x 64 block needs to be multiplied as a dense block
+//   GNNSTAGE_DENSE_MIN_SHARE          share of all entries that must fall into such blocks
+//   GNNSTAGE_DENSE_MIN_ENTRIES        dense entries per chunk below which the plan stays off
+//   GNNSTAGE_ORDER=aggregate|transform  one layer order for every GCN layer
+//   GNNSTAGE_SPMM_VALU                vector-ALU aggregation for bf16 rows too
+//   GNNSTAGE_SPMM_UNROLL (2, 4, 8)    gather slots per wave of the matrix-core aggregation
+//   GNNSTAGE_GEMM_WS_MIN_ROWS         rows from which the weight-stationary product is used
+//   GNNSTAGE_WGRAD_DEFER=0            weight gradients per chunk instead of one product per layer at the end of the pass
+//   GNNSTAGE_HOT_SOURCES (0 = off)    hottest sources whose rows are gathered from a compact copy
+struct Tuning {
+  int split_edges = 0;          // 0: from the launch size
+  int xcd_classes = 0;          // 0: from the size of the gathered table
+  int class_min_row = 128;      // measured: shorter rows than this cost more in partial sums than their locality gains
+  bool dense = true;
+  int dense_min_nnz = 0;        // 0: the defaults below
+  double dense_min_share = 0.2;
+  double dense_min_entries = 2e6;
+  int order = 0;                // 0 auto, 1 aggregate first, 2 transform first
+  bool spmm_valu = false;
+  int spmm_unroll = 2;          // two slots leave room for eight waves per SIMD, which measured best on every workload
+  int gemm_ws_min_rows = 65536;
+  bool wgrad_defer = true;
+};
+
+Tuning read_tuning() {
+  Tuning t;
+  const char *e;
+  if ((e = getenv("GNNSTAGE_SPLIT_EDGES")) && atoi(e) >= 64) t.split_edges = atoi(e);
+  if ((e = getenv("GNNSTAGE_XCD_CLASSES")) && atoi(e) >= 1 && atoi(e) <= kMaxClasses) t.xcd_classes = atoi(e);
+  if ((e = getenv("GNNSTAGE_CLASS_MIN_ROW")) && atoi(e) >= 1) t.class_min_row = atoi(e);
+  if ((e = getenv("GNNSTAGE_DENSE")) && atoi(e) == 0) t.dense = false;
+  if ((e = getenv("GNNSTAGE_DENSE_MIN_NNZ")) && atoi(e) >= 1) t.dense_min_nnz = atoi(e);
+  if ((e = getenv("GNNSTAGE_DENSE_MIN_SHARE"))) t.dense_min_share = atof(e);
+  if ((e = getenv("GNNSTAGE_DENSE_MIN_ENTRIES"))) t.dense_min_entries = atof(e);
+  if ((e = getenv("GNNSTAGE_ORDER"))) t.order = !strcmp(e, "aggregate") ? 1 : !strcmp(e, "transform") ? 2 : 0;
+  if (getenv("GNNSTAGE_SPMM_VALU")) t.spmm_valu = true;
+  if ((e = getenv("GNNSTAGE_SPMM_UNROLL"))) t.spmm_unroll = atoi(e);
+  if ((e = getenv("GNNSTAGE_GEMM_WS_MIN_ROWS"))) t.gemm_ws_min_rows = atoi(e);
+  if ((e = getenv("GNNSTAGE_WGRAD_DEFER")) && atoi(e) == 0) t.wgrad_defer = false;
+  return t;
+}
+
 // Longest piece of a row that one wavefront handles in an aggregation over `entries` entries.  A wave
 // streams roughly 16 entries per microsecond, so the longest task bounds the tail of the launch: pieces
 // shrink with the launch (about 16k pieces' worth of work per launch), within [256, 4096].
-// GNNSTAGE_SPLIT_EDGES overrides (tests force tiny pieces).
-int split_edges_for(int64_t entries) {
-  const char *e = getenv("GNNSTAGE_SPLIT_EDGES");
-  if (e) {
-    const int v = atoi(e);
-    if (v >= 64) return v;
-  }
+int split_edges_for(const Tuning &t, int64_t entries) {
+  if (t.split_edges >= 64) return t.split_edges;
   int64_t s = (entries / 16384 + 63) / 64 * 64;
   if (s < 256) s = 256;
   if (s > 4096) s = 4096;
@@ -39,23 +83,9 @@ int split_edges_for(int64_t entries) {
 
 // Source-id classes (one per XCD) pay when one class's slice of the gathered table has a chance to
 // live in an XCD's L2 and the memory-side cache; for tables far beyond that they only add partial sums.
-// GNNSTAGE_XCD_CLASSES=1 switches them off, =8 forces them on.
-int xcd_classes_setting(int64_t table_bytes) {
-  const char *e = getenv("GNNSTAGE_XCD_CLASSES");
-  if (e) {
-    const int v = atoi(e);
-    if (v >= 1 && v <= kMaxClasses) return v;
-  }
+int xcd_classes_setting(const Tuning &t, int64_t table_bytes) {
+  if (t.xcd_classes >= 1) return t.xcd_classes;
   return table_bytes <= (int64_t)256 << 20 ? 8 : 1;
-}
-
-int class_min_row_setting() {
-  const char *e = getenv("GNNSTAGE_CLASS_MIN_ROW");
-  if (e) {
-    const int v = atoi(e);
-    if (v >= 1) return v;
-  }
-  return 128;  // measured: shorter rows than this cost more in partial sums than their locality gains
 }
 
 // Lower bounds of the source-id classes: equal id ranges, except that a bound moves onto a chunk boundary
@@ -107,41 +137,20 @@ std::vector<int64_t> class_bounds_by_entries(const int64_t *ptr, const int32_t *
 }
 
 // Dense blocks: switched on for bf16 stages whose aggregations all gather rows of width 128 or 256.
-// GNNSTAGE_DENSE=0 switches them off; GNNSTAGE_DENSE_MIN_NNZ (entries a 128 x 64 block needs; default: from 3.4 %
-// of its cells upwards, as low as the chunk's launch still fits one round of workgroups, 5 % for a chunk that needs
-// several, see dense_max_items; the same for blocks kept as weight tiles, whose curve is flat from 278 to 500:
-// 18.7 - 18.9 ms per c1 step with the caller's weights), GNNSTAGE_DENSE_MIN_SHARE (share of all entries that must fall into such blocks,
-// default 0.2) and GNNSTAGE_DENSE_MIN_ENTRIES (see below) let tests force them on small graphs.
-bool dense_enabled() {
-  const char *e = getenv("GNNSTAGE_DENSE");
-  return !(e && atoi(e) == 0);
-}
-int dense_min_nnz() {
-  const char *e = getenv("GNNSTAGE_DENSE_MIN_NNZ");
-  if (e && atoi(e) >= 1) return atoi(e);
-  return kDenseRB * kDenseCB * 34 / 1000;
-}
-int dense_min_nnz_many() {  // for a chunk whose launch needs several rounds of workgroups: every block costs time there
-  const char *e = getenv("GNNSTAGE_DENSE_MIN_NNZ");
-  if (e && atoi(e) >= 1) return atoi(e);
-  return kDenseRB * kDenseCB / 20;
-}
+// Threshold: entries a 128 x 64 block needs; default: from 3.4 % of its cells upwards, as low as the chunk's launch
+// still fits one round of workgroups, 5 % for a chunk that needs several (see dense_max_items); the same for blocks
+// kept as weight tiles, whose curve is flat from 278 to 500: 18.7 - 18.9 ms per c1 step with the caller's weights.
+int dense_min_nnz(const Tuning &t) { return t.dense_min_nnz >= 1 ? t.dense_min_nnz : kDenseRB * kDenseCB * 34 / 1000; }
+// for a chunk whose launch needs several rounds of workgroups: every block costs time there
+int dense_min_nnz_many(const Tuning &t) { return t.dense_min_nnz >= 1 ? t.dense_min_nnz : kDenseRB * kDenseCB / 20; }
 // Items (runs of at most 32 blocks of one row block) of a launch that fits one round of workgroups: one workgroup
 // per item and 128-column half, two workgroups per CU, 256 CUs; a tenth more is harmless because short items end
 // early.  Such a launch takes as long as its longest item, so blocks down to the low threshold are free; beyond it
 // the extra workgroups wait for a second round.
 int64_t dense_max_items(int widest) { return (int64_t)(2 * 256 * 11 / 10) / std::max(1, widest / 128); }
-double dense_min_share() {
-  const char *e = getenv("GNNSTAGE_DENSE_MIN_SHARE");
-  return e ? atof(e) : 0.2;
-}
 // A dense launch has a fixed cost (its longest item runs 32 blocks one after the other, some tens of
-// microseconds); it only pays when it takes a lot of entries off the sparse kernel: at least this many per
-// chunk on average (GNNSTAGE_DENSE_MIN_ENTRIES; the sparse kernel gathers about 40 entries per nanosecond).
-double dense_min_entries_per_chunk() {
-  const char *e = getenv("GNNSTAGE_DENSE_MIN_ENTRIES");
-  return e ? atof(e) : 2e6;
-}
+// microseconds); it only pays when it takes a lot of entries off the sparse kernel: at least
+// Tuning::dense_min_entries per chunk on average (the sparse kernel gathers about 40 entries per nanosecond).
 constexpr int kDenseItemBlocks = kDenseMaxItemBlocks;
 
 struct TaskList {
@@ -174,17 +183,17 @@ struct PlanCounts {
 
 // Upper bounds (from row lengths alone) on tasks / cut rows / slots of every chunk: a row cut by
 // source class adds at most one extra piece per class.
-PlanCounts count_plan(const int64_t *ptr, const std::vector<int64_t> &chunk_ptr, int classes,
+PlanCounts count_plan(const Tuning &tune, const int64_t *ptr, const std::vector<int64_t> &chunk_ptr, int classes,
                       const uint8_t *force = nullptr) {
   PlanCounts pc;
   const int K = (int)chunk_ptr.size() - 1;
-  const int min_row = class_min_row_setting();
+  const int min_row = tune.class_min_row;
   pc.tasks.assign(K, 0);
   pc.longs.assign(K, 0);
   pc.slots.assign(K, 0);
   pc.split.assign(K, 0);
   for (int c = 0; c < K; ++c) {
-    const int split = split_edges_for(ptr[chunk_ptr[c + 1]] - ptr[chunk_ptr[c]]);
+    const int split = split_edges_for(tune, ptr[chunk_ptr[c + 1]] - ptr[chunk_ptr[c]]);
     pc.split[c] = split;
     for (int64_t r = chunk_ptr[c]; r < chunk_ptr[c + 1]; ++r) {
       const int64_t len = ptr[r + 1] - ptr[r];
@@ -231,7 +240,7 @@ struct HostDir {
 
 void host_mask_set(ChunkMask &m, int c) { m.w[c >> 6] |= 1ull << (c & 63); }
 
-bool make_host_dir(const int64_t *ptr, const int32_t *idx, int64_t n, const std::vector<int64_t> &chunk_ptr,
+bool make_host_dir(const Tuning &tune, const int64_t *ptr, const int32_t *idx, int64_t n, const std::vector<int64_t> &chunk_ptr,
                    int classes, bool try_dense, int dense_width, HostDir &h) {
   const int K = (int)chunk_ptr.size() - 1;
   h.ptr = ptr;
@@ -244,9 +253,9 @@ bool make_host_dir(const int64_t *ptr, const int32_t *idx, int64_t n, const std:
   if (try_dense) {
     // share of all entries that must be dense: the relative threshold, or the absolute one if that asks for more
     const double nnz = (double)ptr[n];
-    const double share = std::max(dense_min_share(), nnz > 0 ? dense_min_entries_per_chunk() * K / nnz : 0.0);
-    if (!build_dense_plan(ptr, idx, n, K, chunk_ptr.data(), dense_min_nnz(), share, h.dp, kDenseItemBlocks, dense_max_items(dense_width),
-                          dense_min_nnz_many()))
+    const double share = std::max(tune.dense_min_share, nnz > 0 ? tune.dense_min_entries * K / nnz : 0.0);
+    if (!build_dense_plan(ptr, idx, n, K, chunk_ptr.data(), dense_min_nnz(tune), share, h.dp, kDenseItemBlocks, dense_max_items(dense_width),
+                          dense_min_nnz_many(tune)))
       return false;
   }
   if (h.dp.active) {
@@ -281,7 +290,7 @@ bool make_host_dir(const int64_t *ptr, const int32_t *idx, int64_t n, const std:
       h.max_items = std::max(h.max_items, h.chunk_item_off[(size_t)k + 1] - h.chunk_item_off[(size_t)k]);
     }
   }
-  h.pc = count_plan(h.ptr, chunk_ptr, classes, h.force_ptr());
+  h.pc = count_plan(tune, h.ptr, chunk_ptr, classes, h.force_ptr());
   return true;
 }
 
@@ -323,6 +332,7 @@ struct Shape {
   std::vector<int> dims, ld;
   std::vector<char> tf;  // per layer: 1 = transform first (gather rows of width d_{j+1}), 0 = aggregate first
   int dtype = 0, level0_f32 = 0, variant = 0, need_input_grad = 0;
+  Tuning tune;
   bool has_bias() const { return variant != GNNSTAGE_GCNII; }
   bool sage() const { return variant == GNNSTAGE_SAGE; }
   bool res() const { return variant == GNNSTAGE_RESGCN; }
@@ -336,7 +346,7 @@ struct Shape {
     for (int j = 0; j < L; ++j)
       widest = std::max<int64_t>(widest, tf[j] ? (int64_t)dims[j + 1] * elt()
                                                : std::max<int64_t>((int64_t)dims[j] * level_elt(j), (int64_t)dims[j] * elt()));
-    return xcd_classes_setting(n * widest);
+    return xcd_classes_setting(tune, n * widest);
   }
   // dense blocks serve the matrix-core aggregation only: every aggregation of the stage must gather bf16 rows
   // of width 128 or 256
@@ -346,7 +356,7 @@ struct Shape {
     return wdt;
   }
   bool dense_ok() const {
-    if (dtype != GNNSTAGE_BF16 || !dense_enabled()) return false;
+    if (dtype != GNNSTAGE_BF16 || !tune.dense) return false;
     for (int j = 0; j < L; ++j) {
       const int wdt = tf[j] ? dims[j + 1] : dims[j];
       if (wdt != 128 && wdt != 256) return false;
@@ -403,14 +413,14 @@ bool read_shape(const gnnstage_desc *d, Shape &s, std::string &err) {
   }
   // Layer order.  (A_hat H) W == A_hat (H W) and the select is per edge, so a GCN layer may apply W
   // before the aggregation; that pays when it narrows the rows the gather has to move.
-  const char *ord = getenv("GNNSTAGE_ORDER");
+  s.tune = read_tuning();
   s.tf.assign(s.L, 0);
   for (int j = 0; j < s.L; ++j) {
     if (s.variant != GNNSTAGE_GCN) continue;
     const bool narrower = (size_t)s.dims[j + 1] * s.elt() < (size_t)s.dims[j] * s.level_elt(j);
     s.tf[j] = narrower ? 1 : 0;
-    if (ord && !strcmp(ord, "aggregate")) s.tf[j] = 0;
-    if (ord && !strcmp(ord, "transform")) s.tf[j] = 1;
+    if (s.tune.order == 1) s.tf[j] = 0;
+    if (s.tune.order == 2) s.tf[j] = 1;
   }
   if (d->row_ptr[0] != 0 || d->row_ptr[s.n] != s.nnz) { err = "row_ptr must start at 0 and end at nnz"; return false; }
   for (int64_t v = 0; v < s.n; ++v)
@@ -590,7 +600,12 @@ struct gnnstage {
   std::vector<float *> d_ln_g, d_ln_b;
   float ln_eps = 1e-5f;
   float dropout_p = 0.f;      // ResGCN+: between ReLU and the convolution; GCN, GraphSage: on every layer's output
-  uint64_t dropout_seed = 0;  // of the current pass (gnnstage_set_dropout_seed)
+  uint64_t dropout_seed = 0;  // of the current pass
+  // What the setters wrote.  A pass latches both at its first forward call and keeps them until its last backward
+  // call, so that the backward pass redraws exactly the decisions of its forward pass whatever the caller sets
+  // in between.
+  float next_dropout_p = 0.f;
+  uint64_t next_dropout_seed = 0;
   // GCN, GraphSage: the stored output of a layer is the value after dropout; a positive one passed ReLU and dropout,
   // so every ReLU mask of the backward pass also scales by 1 / (1 - rate)
   bool output_dropout() const { return dropout_p > 0.f && (s.variant == GNNSTAGE_GCN || s.variant == GNNSTAGE_SAGE); }
@@ -782,6 +797,8 @@ SpmmArgs base_spmm(const gnnstage *st, bool transposed, int chunk) {
   a.n_long = t.n_long;
   a.partial = st->at<float>(st->lay.partial);
   a.vbits = st->vbits;
+  a.force_valu = st->s.tune.spmm_valu ? 1 : 0;
+  a.unroll = st->s.tune.spmm_unroll;
   a.mask = transposed ? st->bmask : st->fmask;
   const int dir = transposed ? 1 : 0;
   if (st->dense_on[dir]) {
@@ -935,6 +952,7 @@ int res_forward_chunk(gnnstage *st, int k, hipStream_t stream) {
     {
       Timed t(st, stream, 1, j);
       GemmNtArgs g{};
+      g.ws_min_rows = st->s.tune.gemm_ws_min_rows;
       g.A = Zj + (size_t)row0 * s.ld[j] * celt;
       g.a_dtype = cd;
       g.lda = s.ld[j];
@@ -1042,6 +1060,7 @@ int res_backward_chunk(gnnstage *st, int k, const void *grad_out_rows, hipStream
     {
       Timed t(st, stream, 3, j);
       GemmNtArgs g{};
+      g.ws_min_rows = st->s.tune.gemm_ws_min_rows;
       g.A = dY;
       g.a_dtype = cd;
       g.lda = s.ld[j + 1];
@@ -1125,8 +1144,8 @@ int make_host_plan(const gnnstage_desc *d, const Shape &s, bool want_edge, HostP
     return GNNSTAGE_EINVAL;
   }
   const bool dense = s.dense_ok();
-  if (!make_host_dir(d->row_ptr, d->col_idx, s.n, s.chunk_ptr, s.classes(), dense, s.dense_width(), hp.f) ||
-      !make_host_dir(hp.t_ptr.data(), hp.t_row.data(), s.n, s.chunk_ptr, s.classes(), dense, s.dense_width(), hp.b)) {
+  if (!make_host_dir(s.tune, d->row_ptr, d->col_idx, s.n, s.chunk_ptr, s.classes(), dense, s.dense_width(), hp.f) ||
+      !make_host_dir(s.tune, hp.t_ptr.data(), hp.t_row.data(), s.n, s.chunk_ptr, s.classes(), dense, s.dense_width(), hp.b)) {
     err = "cannot plan the aggregation";
     return GNNSTAGE_EINVAL;
   }
@@ -1248,7 +1267,7 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
     }
     st->ln_eps = d->ln_eps;
   }
-  st->dropout_p = d->dropout_p;
+  st->dropout_p = st->next_dropout_p = d->dropout_p;
   if (d->beta) st->beta.assign(d->beta, d->beta + s.L); else st->beta.assign(s.L, 0.f);
   st->W.assign(d->W, d->W + s.L);
   st->cur.assign(d->cur, d->cur + s.L + 1);
@@ -1274,7 +1293,7 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
   }
 
   // schedules: build on the host chunk by chunk, upload into the preallocated arrays
-  const int classes = s.classes(), min_row = class_min_row_setting();
+  const int classes = s.classes(), min_row = s.tune.class_min_row;
   auto build = [&](const HostDir &h, const uint32_t *packed, bool transposed, std::vector<TaskList> &lists) -> int {
     const int64_t *ptr = h.ptr;
     const int32_t *idx = h.idx;
@@ -1529,6 +1548,8 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
     st->fmask = ChunkMask{};
     st->bmask = ChunkMask{};
     st->n_bwd = 0;
+    st->dropout_p = st->next_dropout_p;
+    st->dropout_seed = st->next_dropout_seed;
     {
       Timed t(st, stream, 6);
       for (int j = 0; j < s.L; ++j) {
@@ -1550,6 +1571,7 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
       if (!s.tf[j]) continue;
       Timed t(st, stream, 1, j);
       GemmNtArgs g{};
+      g.ws_min_rows = st->s.tune.gemm_ws_min_rows;
       g.A = st->hist[j];
       g.a_dtype = st->level_dtype(j);
       g.lda = s.dims[j];
@@ -1583,6 +1605,7 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
       if (!shared) {
         Timed t(st, stream, 1, j);
         GemmNtArgs g{};
+        g.ws_min_rows = st->s.tune.gemm_ws_min_rows;
         g.A = static_cast<const char *>(st->cur[j]) + (size_t)row0 * s.dims[j] * st->level_elt(j);
         g.a_dtype = st->level_dtype(j);
         g.lda = s.dims[j];
@@ -1638,6 +1661,7 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
     if (s.sage()) {  // the vertex's own row through W_self, kept in fp32 until the layer's epilogue adds it
       Timed t(st, stream, 1, j);
       GemmNtArgs g{};
+      g.ws_min_rows = st->s.tune.gemm_ws_min_rows;
       g.A = static_cast<const char *>(st->cur[j]) + (size_t)row0 * s.dims[j] * st->level_elt(j);
       g.a_dtype = st->level_dtype(j);
       g.lda = s.dims[j];
@@ -1656,6 +1680,7 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
     {
       Timed t(st, stream, 1, j);
       GemmNtArgs g{};
+      g.ws_min_rows = st->s.tune.gemm_ws_min_rows;
       g.A = Zj + (size_t)row0 * s.ld[j] * celt;
       g.a_dtype = cd;
       g.lda = s.ld[j];
@@ -1705,7 +1730,8 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
   st->n_bwd += 1;
   mask_set(st->bmask, k);
   if (s.res()) return res_backward_chunk(st, k, grad_out_rows, stream);
-  if (M == 0) return GNNSTAGE_OK;
+  // an empty chunk has no rows of its own, but the end-of-pass work still runs when it is the last call of the pass
+  if (M == 0) return st->n_bwd == s.K ? finish_transform_first(st, stream) : GNNSTAGE_OK;
 
   const int cd = st->cdtype();
   const size_t celt = s.elt();
@@ -1781,6 +1807,7 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
       {
         Timed t(st, stream, 3, j);
         GemmNtArgs g{};
+        g.ws_min_rows = st->s.tune.gemm_ws_min_rows;
         g.A = dT;
         g.a_dtype = cd;
         g.lda = s.ld[j + 1];
@@ -1853,6 +1880,7 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
     {
       Timed t(st, stream, 3, j);
       GemmNtArgs g{};
+      g.ws_min_rows = st->s.tune.gemm_ws_min_rows;
       g.A = dY;
       g.a_dtype = cd;
       g.lda = s.ld[j + 1];
@@ -1956,7 +1984,7 @@ extern "C" int gnnstage_set_dropout_rate(gnnstage_t *st, float dropout_p) {
     return fail(st, GNNSTAGE_EORDER, "the dropout rate cannot change inside a forward or a backward pass");
   if (!(dropout_p >= 0.f && dropout_p < 1.f)) return fail(st, GNNSTAGE_EINVAL, "dropout_p must be in [0, 1)");
   if (dropout_p > 0.f && st->s.variant == GNNSTAGE_GCNII) return fail(st, GNNSTAGE_EINVAL, "no dropout in GCNII layers");
-  st->dropout_p = dropout_p;
+  st->next_dropout_p = dropout_p;  // latched by the next pass's first forward call
   return GNNSTAGE_OK;
 }
 
@@ -1964,7 +1992,7 @@ extern "C" int gnnstage_set_dropout_seed(gnnstage_t *st, uint64_t seed) {
   if (!st) return GNNSTAGE_EINVAL;
   if ((!st->order.empty() && (int)st->order.size() < st->s.K) || (st->n_bwd > 0 && st->n_bwd < st->s.K))
     return fail(st, GNNSTAGE_EORDER, "the dropout seed cannot change inside a forward or a backward pass");
-  st->dropout_seed = seed;
+  st->next_dropout_seed = seed;  // latched by the next pass's first forward call
   return GNNSTAGE_OK;
 }
 

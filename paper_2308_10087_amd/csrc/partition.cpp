@@ -1,4 +1,4 @@
-// Chunk partitioner: Algorithm 1's first step ("partition V into K chunks"), locality-aware as Section 3.2 asks.
+// Chunk partitioner: Algorithm 1's first step ("partition V into K chunks"), locality-aware as Section 3.3 asks.
 // Host only.  The heuristic is restreaming FENNEL: Tsourakakis et al. (WSDM 2014) place the vertices one by one
 // into the part that maximises  |N(v) in P_i| - alpha * gamma * |P_i|^(gamma - 1)  among the parts with room,
 // gamma = 3/2, alpha = balance * sqrt(K) * m / n^(3/2); Nishimura and Ugander (KDD 2013) stream the vertices again,

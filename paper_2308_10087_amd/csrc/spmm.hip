@@ -12,8 +12,6 @@
 //    broadcast through lane permutes; dropped entries are first compacted inside the wave.
 //  * spmm_ring_kernel, for bf16 rows whose width is a multiple of 8: entries become address
 //    records in a wave-private LDS ring and the weighted sum runs on the matrix cores.
-#include <stdlib.h>
-
 #include "common.h"
 
 namespace {
@@ -544,7 +542,7 @@ static const Shape *pick_shape(const SpmmArgs &a, int src_dtype, int out_dtype) 
 }
 
 static bool mfma_path(const SpmmArgs &a, int src_dtype) {
-  static const bool off = getenv("GNNSTAGE_SPMM_VALU") != nullptr;  // measurement switch
+  const bool off = a.force_valu != 0;  // measurement switch
   const bool has_aux = spmm_reads_aux(a.epilogue);
   return !off && src_dtype == DT_BF16 && a.d % 8 == 0 && a.src_ld % 8 == 0 && a.out_ld % 8 == 0 &&
          (!has_aux || a.aux_ld % 8 == 0) && (!spmm_reads_add(a.epilogue) || a.add_ld % 8 == 0);
@@ -565,18 +563,11 @@ static void launch_ring(const SpmmArgs &a, hipStream_t s, dim3 grid, int unroll)
   }
 }
 
-// Gather slots per wave.  Two slots leave room for eight waves per SIMD, which measured best on every
-// workload; GNNSTAGE_SPMM_UNROLL = 4 or 8 trades waves for deeper per-wave queues (tests run all three).
-static int ring_slots() {
-  const char *e = getenv("GNNSTAGE_SPMM_UNROLL");
-  return e ? atoi(e) : 2;
-}
-
 template <typename Tout>
 static int launch_mfma(const SpmmArgs &a, hipStream_t s) {
   const unsigned gx = (unsigned)(a.n_class_blocks + (a.n_tasks - a.tail_task0 + 3) / 4);
   if (gx == 0) return hipSuccess;  // only class pieces, none of them active
-  const int unroll = ring_slots();
+  const int unroll = a.unroll;  // 4 or 8 trade waves per SIMD for deeper per-wave queues (tests run all three)
   if (a.d <= 128)
     launch_ring<Tout, 1>(a, s, dim3(gx, 1), unroll);
   else if (a.d <= 256)

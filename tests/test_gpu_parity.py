@@ -107,6 +107,24 @@ def test_fp32_directed_graph_and_empty_chunks():
     _parity(p, TOL_F32)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("empty_at", ["first", "last", "middle"])
+def test_empty_chunk_at_either_end_of_the_order_with_a_transform_first_layer(dtype, empty_at):
+    """The backward pass walks the forward order in reverse, so an empty chunk that is FIRST in the forward
+    order is the last backward call - the call after which the history-side weight gradient of a
+    transform-first layer (24 -> 8 narrows the gathered rows) is taken.  That work must run although the
+    call itself has no rows."""
+    n = 600
+    w = small(n=n, k=5, dims=(24, 8, 16), dtype=dtype)
+    chunk_ptr = np.array([0, 0, 200, 200, 420, n], dtype=np.int64)   # chunks 0 and 2 are empty
+    order = {"first": [0, 3, 2, 1, 4], "last": [4, 1, 3, 0, 2], "middle": [1, 0, 4, 2, 3]}[empty_at]
+    p = make_problem(w, chunk_ptr=chunk_ptr, order=order, first_stage=False)
+    run = _gpu(p)
+    assert run.stage.gnnstage_layer_order(0) == 1
+    del run
+    _parity(p, TOL_F32 if dtype == "f32" else TOL_BF16)
+
+
 def test_fp32_long_rows_are_split(monkeypatch):
     monkeypatch.setenv("GNNSTAGE_SPLIT_EDGES", "64")
     w = CONFIGS["c2_s"]
@@ -285,30 +303,6 @@ def test_full_size_c3_gcnii_stage():
     """configs[3] at full size: 16 GCNII layers over the 169k-vertex power-law graph, bf16."""
     p = make_problem(CONFIGS["c3"], bias_std=0.0)
     _parity(p, TOL_BF16)
-
-
-def test_full_size_c2_first_chunks_of_a_pass():
-    """configs[2] at full size (2.45 M vertices, 16 chunks, 8 layers of width 128, no source classes: the
-    gathered table is beyond the memory-side cache): the first two chunks of a forward pass, every level of
-    their rows against the oracle.  The second chunk reads the first one's current rows, everything else
-    comes from (random) history.  The backward pass needs a complete forward pass on both sides and is left
-    to the shrunk configuration."""
-    p = make_problem(CONFIGS["c2"], bias_std=0.05, history="random")
-    order = [int(k) for k in p.order[:2]]
-    st = p.new_oracle()
-    st.forward_pass(order)
-    run = _gpu(p, need_input_grad=False, alias_hist0=True, edge_val="computed")
-    run.forward(order)
-    torch.cuda.synchronize()
-    for k in order:
-        rows = st.rows(k)
-        for j in range(1, p.L + 1):
-            a, b = run.np(run.cur[j][rows]), st.cur[j][rows]
-            assert max_rel(a, b) <= TOL_BF16, (k, j, max_rel(a, b))
-            flips = (a > 0) != (b > 0)
-            assert flips.mean() <= 1e-2
-            if flips.any():
-                assert np.maximum(np.abs(a[flips]), np.abs(b[flips])).max() <= TOL_BF16 * np.abs(b).max()
 
 
 # ----------------------------------------------------------------------------- select mask, bit-exact
@@ -605,6 +599,26 @@ def test_resgcn_dropout_seed_changes_the_pass_and_is_locked_inside_one():
     with pytest.raises(g.GnnStageError) as e:
         run.stage.gnnstage_set_dropout_seed(6)      # the backward pass must see the forward pass's decisions
     assert e.value.code == -3
+
+
+def test_seed_set_between_forward_and_backward_belongs_to_the_next_pass():
+    """A pass keeps the seed and the rate it started with: a new seed (or rate) set after the forward pass is
+    taken by the NEXT pass, and the backward pass still redraws the masks of its own forward pass."""
+    w = small(dims=(24,) * 3, n=500, k=4, variant="resgcn")
+    p = make_problem(w, first_stage=False, dropout_p=0.5, dropout_seed=3)
+    ref = _gpu(p).run()
+    run = _gpu(p)
+    run.forward()
+    run.stage.gnnstage_set_dropout_seed(99)
+    run.stage.gnnstage_set_dropout_rate(0.25)
+    run.backward()
+    torch.cuda.synchronize()
+    for j in range(p.L):
+        assert torch.equal(run.dW[j], ref.dW[j]) and torch.equal(run.d_ln_gamma[j], ref.d_ln_gamma[j])
+    assert torch.equal(run.grad_in, ref.grad_in)
+    run.stage.forward_pass(p.order)                      # the next pass runs with seed 99 and rate 0.25
+    torch.cuda.synchronize()
+    assert not torch.equal(run.cur[p.L], ref.cur[p.L])
 
 
 # ----------------------------------------------------------------------------- size limits and degenerate inputs

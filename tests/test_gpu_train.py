@@ -171,6 +171,28 @@ def test_one_sgd_epoch_fp32_other_layer_types(variants, stage_dims):
     assert out[-1][0] < out[0][0]
 
 
+def test_sgd_epochs_with_empty_chunks_and_shuffling():
+    """Chunks without vertices take part in the shuffled order like any other.  With seed 5 an empty chunk
+    comes first in the forward order of epochs 0 to 3, i.e. last in their backward pass, where the stage still
+    owes the history-side weight gradient of its transform-first layer (24 -> 8)."""
+    tp = make_train_problem(n=1500, n_classes=5, stage_dims=((24, 8, 16),), K=5)
+    tp.chunk_ptr = np.array([0, 0, 400, 400, 900, 1500], dtype=np.int64)
+    from gpu_harness import GpuTrainRun
+    opt = dict(optimizer="sgd", lr=0.05, shuffle=True, seed=5, alpha_hist=1)
+    ref = new_oracle_trainer(tp, **{k: (F(v) if isinstance(v, float) else v) for k, v in opt.items()})
+    run = GpuTrainRun(tp, **opt)
+    assert run.stages[0].gnnstage_layer_order(0) == 1
+    firsts = []
+    for e in range(4):
+        lr_, lg = ref.epoch(e), run.epoch(e)
+        assert np.array_equal(run.trainer.gnntrain_last_order(), ref.last_order)
+        firsts.append(int(ref.last_order[0]))
+        assert abs(lg - lr_) <= 1e-4 * lr_
+        for a, b in zip(run.grads(), ref.grads()):
+            assert max_rel(a.reshape(b.shape), b) <= 1e-4, e
+    assert set(firsts) <= {0, 2}, firsts
+
+
 def test_sgd_epochs_with_dropout_in_the_resgcn_stage():
     """A fresh set of dropout decisions every epoch, the same on both sides."""
     tp = make_train_problem(n=1500, n_classes=5, stage_dims=((24, 16), (16, 16, 16), (16, 8)), K=4, ragged=True,
