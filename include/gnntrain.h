@@ -109,6 +109,17 @@ int gnntrain_softmax_xent(const float *logits, int32_t ld, const float *bias, co
 /* out[0] = scale * sum of x[0 .. n), added in a fixed order (reproducible).  scratch: DEVICE, 1024 floats. */
 int gnntrain_sum(const float *x, int64_t n, float scale, float *scratch, float *out, void *hip_stream);
 
+/* gnntrain_sum for callers that cannot allocate or bring a scratch buffer: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation.  Same kernels, same order of additions, same result bit for
+ * bit; the 1024 block sums go to an array that lives inside the library's device image (4 KB on every GPU the
+ * library runs on, held until the process ends).  Calls no allocating routine.  Its address on the current device
+ * is looked up at the first call on that device.  n may be at most GNNTRAIN_SUM_STATIC_MAX_N, beyond that the
+ * call returns GNNSTAGE_ENOTSUP (gnntrain_last_error(NULL) says why; also for EINVAL and EHIP).  Nothing in the
+ * array has to be cleared between calls (the first launch writes every slot the second reads), but every call on
+ * one GPU uses the same array: calls that overlap in time on one GPU (two streams) race.  x, out: DEVICE. */
+#define GNNTRAIN_SUM_STATIC_MAX_N 2147483647LL
+int gnntrain_sum_static(const float *x, int64_t n, float scale, float *out, void *hip_stream);
+
 /* One optimiser step on one tensor (t = 1, 2, ... for Adam's bias correction).  compute may be NULL. */
 int gnntrain_adam_step(float *p, const float *g, float *m, float *v, void *compute, int32_t compute_dtype,
                        int64_t count, float lr, float beta1, float beta2, float eps, float weight_decay, int64_t t,

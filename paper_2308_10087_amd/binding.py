@@ -153,6 +153,8 @@ def _load():
                                           C.c_float, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.gnntrain_sum.restype = C.c_int
     lib.gnntrain_sum.argtypes = [C.c_void_p, C.c_int64, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.gnntrain_sum_static.restype = C.c_int
+    lib.gnntrain_sum_static.argtypes = [C.c_void_p, C.c_int64, C.c_float, C.c_void_p, C.c_void_p]
     lib.gnntrain_adam_step.restype = C.c_int
     lib.gnntrain_adam_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64,
                                        C.c_float, C.c_float, C.c_float, C.c_float, C.c_float, C.c_int64, C.c_void_p]
@@ -495,6 +497,13 @@ def gnntrain_sum(x, scale: float, scratch, out) -> None:
     rc = lib.gnntrain_sum(x.data_ptr(), x.numel(), float(scale), scratch.data_ptr(), out.data_ptr(), _cur_stream())
     if rc != 0:
         raise GnnStageError(rc, "gnntrain_sum")
+
+
+def gnntrain_sum_static(x, scale: float, out, n: Optional[int] = None) -> None:
+    """gnntrain_sum without a scratch argument (the block sums go to an array inside the library)."""
+    rc = lib.gnntrain_sum_static(x.data_ptr(), x.numel() if n is None else int(n), float(scale), out.data_ptr(), _cur_stream())
+    if rc != 0:
+        raise GnnStageError(rc, lib.gnntrain_last_error(None).decode())
 
 
 def _compute_args(compute):

@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -275,6 +276,63 @@ extern "C" int gnntrain_softmax_xent(const float *logits, int32_t ld, const floa
 extern "C" int gnntrain_sum(const float *x, int64_t n, float scale, float *scratch, float *out, void *hip_stream) {
   if (n < 0 || !scratch || !out || (n > 0 && !x)) return GNNSTAGE_EINVAL;
   return launch_sum(x, n, scale, scratch, out, static_cast<hipStream_t>(hip_stream)) == 0 ? GNNSTAGE_OK : GNNSTAGE_EHIP;
+}
+
+// ---- the same sum for callers that cannot allocate -----------------------------------------------------
+// The block sums go to a file-scope device array instead of a buffer the caller brings.  Every GPU holds its own
+// copy of the array at its own address; host code never uses the array's name (a host-side stand-in, not a
+// device address) but the address hipGetSymbolAddress reports for the device that is current, looked up once per
+// device and kept.
+constexpr int kSumStaticSlots = 1024;  // block sums of one call: the kernels never use more blocks than this
+static __device__ __align__(256) float scratch[kSumStaticSlots];
+namespace {
+constexpr int kMaxDevices = 64;
+float *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// device address of `scratch` on the current device; nullptr (with err set) when it cannot be had
+float *static_scratch(std::string &err) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) {
+    err = std::string("hipGetDevice: ") + hipGetErrorString(e);
+    return nullptr;
+  }
+  if (dev < 0 || dev >= kMaxDevices) {
+    err = "device index beyond the per-device table of the static scratch array";
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void *ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || ptr == nullptr) {
+      err = std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e);
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = static_cast<float *>(ptr);
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" int gnntrain_sum_static(const float *x, int64_t n, float scale, float *out, void *hip_stream) {
+  if (n < 0 || !out || (n > 0 && !x)) {
+    g_create_error = "gnntrain_sum_static: n is negative or a pointer is NULL";
+    return GNNSTAGE_EINVAL;
+  }
+  if (n > GNNTRAIN_SUM_STATIC_MAX_N) {
+    g_create_error = "gnntrain_sum_static: n exceeds GNNTRAIN_SUM_STATIC_MAX_N (2^31 - 1 elements)";
+    return GNNSTAGE_ENOTSUP;
+  }
+  std::string err;
+  float *ptr = static_scratch(err);
+  if (ptr == nullptr) {
+    g_create_error = err;
+    return GNNSTAGE_EHIP;
+  }
+  // Nothing in the array has to start at zero: the first launch writes every slot the second one reads.
+  return launch_sum(x, n, scale, ptr, out, static_cast<hipStream_t>(hip_stream)) == 0 ? GNNSTAGE_OK : GNNSTAGE_EHIP;
 }
 
 extern "C" int gnntrain_adam_step(float *p, const float *g, float *m, float *v, void *compute, int32_t compute_dtype, int64_t count,
