@@ -2,14 +2,17 @@
 """Benchmark of one pipeline stage on one MI355X.
 
 A step = one epoch's work of the stage: forward over all chunks (shuffled order), backward over
-the chunks in reverse, then update_history.  The workload is configuration 1 of the benchmark
-definition (Reddit-shaped R-MAT graph, 4 GCN layers 602->256x4, bf16 transforms, 8 chunks); inputs
-are synthetic and resident in HBM before the timed region.  Prints one JSON line.
+the chunks in reverse, then update_history.  The headline workload is configuration 4 of the
+benchmark definition, the largest one that fits a GPU (R-MAT graph, 10 M vertices, 210 M entries,
+4 GCN layers of width 256 in bf16, 32 chunks); configurations 1 to 3 are timed in the same run and
+reported under "per_config".  Inputs are synthetic and resident in HBM before the timed region.
+Prints one JSON line.
 """
 from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -20,6 +23,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+BF16_MFMA_PEAK = 2.5e15
+FP32_VALU_PEAK = 157.3e12
+HEADLINE = "c4"
+SECONDARY = ("c1", "c2", "c3")
 
 
 def log(*a):
@@ -45,35 +52,35 @@ def pair_counts(row_ptr, col, chunk_ptr):
     return E, D
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c1")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-rows", type=int, default=131072)
-    ap.add_argument("--partition", action="store_true",
-                    help="chunks from the library's locality-aware partitioner instead of index ranges (not the benchmark configuration)")
-    ap.add_argument("--partition-by-entries", action="store_true", help="with --partition: balance the chunks by entries")
-    ap.add_argument("--caller-weights", action="store_true",
-                    help="hand the edge weights to the library (edge_val) instead of letting it compute the normalisation: "
-                         "dense blocks then run from stored weight tiles instead of bit patterns")
-    ap.add_argument("--train-epochs", type=int, default=0,
-                    help="also time this many epochs of the whole training loop (head + Adam) around the same stage")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py measures one pipeline stage on ONE GPU; this build has no multi-GPU path (--gpus must be 1)")
+def copy_bandwidth(torch, dev, nbytes=2 << 30, reps=5):
+    """What this machine's memory system gives a plain device-to-device copy (torch's copy kernel), read + written
+    bytes per second: the yardstick for update_history."""
+    a = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    b = torch.empty_like(a)
+    b.copy_(a)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(reps):
+        b.copy_(a)
+    ev1.record()
+    torch.cuda.synchronize()
+    ms = ev0.elapsed_time(ev1) / reps
+    del a, b
+    torch.cuda.empty_cache()
+    return 2.0 * nbytes / (ms * 1e-3) / 1e9
 
+
+def run_config(name, args, steps, warmup, with_cpu, copy_gbs):
+    """Builds the workload, times `steps` steps and returns the result object of that configuration."""
     import torch
     import paper_2308_10087_amd as g
     from synth import values
     from synth.configs import CONFIGS, make_graph
     from synth.graphs import degree_stats, equal_chunks
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
-    w = CONFIGS[args.workload]
+    w = CONFIGS[name]
     t0 = time.time()
     row_ptr, col = make_graph(w)
     n, nnz = len(row_ptr) - 1, int(row_ptr[-1])
@@ -100,25 +107,33 @@ def main():
     l0 = torch.float32 if (w.level0_f32 or not bf) else torch.bfloat16
     gcn = w.variant != "gcnii"  # layer types with a bias vector and no GCNII inputs
     sage, res = w.variant == "sage", w.variant == "resgcn"
-    x0_np = values.normal(w.seed, 1, (n, dims[0])) if gcn else values.half_normal(w.seed, 1, (n, dims[0]))
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed)
+
+    def dev_normal(shape, dtype, absolute=False):
+        # drawn on the device: the 10 M x 256 tables of the largest configuration take minutes on the host
+        x = torch.randn(shape, generator=gen, device=dev)
+        if absolute:
+            x.abs_()
+        return x.to(dtype)
+
     wrows = 2 if sage else 1  # GraphSage stacks [W_self ; W_neigh]
     W = [torch.from_numpy(np.concatenate([values.glorot_uniform(w.seed, 100 + 50 * h + j, dims[j], dims[j + 1]) for h in range(wrows)]))
          .to(dev, sdt) for j in range(L)]
     bias = [torch.zeros(dims[j + 1], device=dev) for j in range(L)] if gcn else None
-    cur = [torch.from_numpy(x0_np).to(dev, l0)] + [torch.zeros((n, dims[j]), dtype=sdt, device=dev) for j in range(1, L + 1)]
+    cur = [dev_normal((n, dims[0]), l0, absolute=not gcn)] + [torch.zeros((n, dims[j]), dtype=sdt, device=dev) for j in range(1, L + 1)]
     first_stage = (w.variant == "gcn") if w.first_stage is None else w.first_stage
     ln = [[torch.ones(dims[j], device=dev) for j in range(L)], [torch.zeros(dims[j], device=dev) for j in range(L)],
           [torch.zeros(dims[j], device=dev) for j in range(L)], [torch.zeros(dims[j], device=dev) for j in range(L)]] if res else [None] * 4
     hist = [cur[0] if first_stage else cur[0].clone()] + [torch.zeros((n, dims[j]), dtype=sdt, device=dev) for j in range(1, L)]
     dW = [torch.zeros((wrows * dims[j], dims[j + 1]), device=dev) for j in range(L)]
     dbias = [torch.zeros(dims[j + 1], device=dev) for j in range(L)] if gcn else None
-    h0 = None if gcn else torch.from_numpy(values.normal(w.seed, 2, (n, dims[0]))).to(dev, sdt)
+    h0 = None if gcn else dev_normal((n, dims[0]), sdt)
     grad_h0 = None if gcn else torch.zeros((n, dims[0]), device=dev)
     grad_in = None if first_stage else torch.zeros((n, dims[0]), dtype=l0, device=dev)
-    grad_out = torch.from_numpy(values.normal(w.seed, 3, (n, dims[-1]))).to(dev, sdt)
+    grad_out = dev_normal((n, dims[-1]), sdt)
     beta = None
     if not gcn:
-        import math
         beta = np.array([math.log(0.5 / l + 1.0) for l in range(w.gcnii_first_layer, w.gcnii_first_layer + L)], np.float32)
     edge_val = None
     if args.caller_weights:  # the weights the library would compute itself: 1 / sqrt(D_v D_u), or 1 / D_v for the mean aggregator
@@ -149,25 +164,27 @@ def main():
 
     # historical buffers: one untimed epoch from zero history, refresh, then N(0, 0.01^2) noise
     one_step(-1)
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(w.seed)
     for j in range(L):
         if hist[j].data_ptr() != cur[j].data_ptr():
-            hist[j].add_((0.01 * torch.randn(hist[j].shape, generator=gen, device=dev)).to(hist[j].dtype))
-    for i in range(args.warmup):
+            rows_per = max(1, (1 << 28) // max(dims[j], 1))  # in slices: the noise of a whole 10 M x 256 level is 10 GB of fp32
+            for r0 in range(0, n, rows_per):
+                sl = hist[j][r0:r0 + rows_per]
+                sl.add_((0.01 * torch.randn(sl.shape, generator=gen, device=dev)).to(sl.dtype))
+    for i in range(warmup):
         one_step(i)
     torch.cuda.synchronize()
 
-    # Inside the timed region only the aggregation launches (the dominant kernel) carry HIP events: two
-    # event records per launch on the launch stream.  The per-kind breakdown of a whole step comes from two
-    # further, untimed steps with every kind switched on (events around ~350 launches cost ~1 ms per step).
+    # Inside the timed region only the launches of an aggregation (the dominant operation: gather kernels and
+    # the reduce kernel that adds the partial rows of cut rows) carry HIP events: two event records per launch on
+    # the launch stream.  The per-kind breakdown of a whole step comes from two further, untimed steps with every
+    # kind switched on (events around all launches of a step cost about a millisecond).
     st.gnnstage_profile_reset()
-    st.gnnstage_profile_select(["spmm_fwd", "spmm_bwd"])
+    st.gnnstage_profile_select(["spmm_fwd", "spmm_bwd", "spmm_reduce"])
     orders = []
     torch.cuda.synchronize()
     t_start = time.perf_counter()
-    for i in range(args.steps):
-        orders.append(one_step(args.warmup + i))
+    for i in range(steps):
+        orders.append(one_step(warmup + i))
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     st.gnnstage_profile_enable(False)
@@ -176,20 +193,22 @@ def main():
     st.gnnstage_profile_enable(True)
     n_extra = 2
     for i in range(n_extra):
-        one_step(args.warmup + args.steps + i)
+        one_step(warmup + steps + i)
     torch.cuda.synchronize()
     st.gnnstage_profile_enable(False)
     prof_all = st.gnnstage_profile_read(-1)
 
-    ms_per_step = 1e3 * elapsed / args.steps
-    value = L * nnz / (elapsed / args.steps)
+    ms_per_step = 1e3 * elapsed / steps
+    value = L * nnz / (elapsed / steps)
 
-    # ---- roofline of the dominant kernel -------------------------------------------------
-    # Aggregation launches are grouped by the rows they gather (width, element type): one kernel
-    # instantiation and launch shape per group, the same grouping rocprofv3 shows by kernel name.
-    # Algorithmic bytes of a launch over chunk k: every entry's packed index + weight (8 B), the chunk's
-    # row pointers, each DISTINCT gathered source row once, the output rows (+ the level rows a masking
-    # epilogue reads).  Backward launches gather only entries whose reader chunk is already processed.
+    # ---- roofline of the dominant operation ------------------------------------------------
+    # Aggregations are grouped by the rows they gather (width, element type): one kernel instantiation and
+    # launch shape per group, the same grouping rocprofv3 shows by kernel name.  One aggregation = the gather
+    # kernels (dense blocks, sparse remainder) plus the reduce kernel; its duration is the sum of the three.
+    # Algorithmic bytes of an aggregation over chunk k: every entry's packed index word (4 B) plus its weight
+    # (4 B) when the caller gave weights - 0 B when the library computes the normalisation itself, as here -,
+    # the chunk's row pointers, each DISTINCT gathered source row once, the output rows (+ the level rows a
+    # masking epilogue reads).  Backward launches gather only entries whose reader chunk is already processed.
     E, D = pair_counts(row_ptr, col, chunk_ptr)
     rows = np.diff(chunk_ptr)
     elt = 2 if bf else 4
@@ -207,13 +226,19 @@ def main():
     def gname(d, e):
         return f"spmm gather width {d} {'f32' if e == 4 else 'bf16'}"
 
-    struct = [E[k].sum() * 8 + 8 * (rows[k] + 1) for k in range(K)]
+    entry_bytes = 8 if edge_val is not None else 4
+    struct = [E[k].sum() * entry_bytes + 8 * (rows[k] + 1) for k in range(K)]
     for j in range(L):
         lvl_e = 4 if (j == 0 and l0 == torch.float32) else elt
         dg, eg = (dims[j + 1], elt) if tf[j] else (dims[j], lvl_e)       # what the forward gathers
         fb = sum(struct[k] + D[k].sum() * dg * eg + rows[k] * (dims[j + 1] if tf[j] else dims[j]) * elt
                  for k in range(K)) * len(orders)
-        add(gname(dg, eg), fb, E.sum() * dg * eg * len(orders), *prof_layer[j]["spmm_fwd"])
+        f_ms, f_n = prof_layer[j]["spmm_fwd"]
+        b_ms, b_n = prof_layer[j]["spmm_bwd"]
+        r_ms = prof_layer[j]["spmm_reduce"][0]
+        # the reduce launches of a layer belong to its forward and backward aggregations alike: by launch count
+        f_red = r_ms * f_n / max(f_n + b_n, 1)
+        add(gname(dg, eg), fb, E.sum() * dg * eg * len(orders), f_ms + f_red, f_n)
         db_, eb = (dims[j + 1], elt) if tf[j] else (dims[j], elt)        # what the backward gathers
         bb = gb = 0.0
         masked = (j > 0 or grad_in is not None or res) and not (tf[j] and j == 0 and shared0 and grad_in is None)
@@ -234,11 +259,11 @@ def main():
                         bb += struct[k] + D[k][earlier].sum() * db_ * eb + rows[k] * db_ * elt
                         gb += E[k][earlier].sum() * db_ * eb
                     earlier[k] = True
-        if prof_layer[j]["spmm_bwd"][1] > 0:
-            add(gname(db_, eb), bb, gb, *prof_layer[j]["spmm_bwd"])
+        if b_n > 0:
+            add(gname(db_, eb), bb, gb, b_ms + (r_ms - f_red), b_n)
     dom_name, (dom_bytes, dom_gather, dom_ms, dom_launches) = max(groups.items(), key=lambda kv: kv[1][2])
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
-    traffic = None  # HBM-side bytes per launch from the committed rocprofv3 counter summary, if it covers this kernel
+    traffic = None  # HBM-side bytes per aggregation from the committed rocprofv3 counter summary, if it covers this kernel
     tpath = os.path.join(ROOT, "profiles", f"stage_{w.name}_pmc_traffic.md")
     if os.path.exists(tpath) and not args.partition and not args.caller_weights:  # the counters were read on the benchmark configuration only
         for line in open(tpath):
@@ -248,6 +273,7 @@ def main():
     roofline = {
         "bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+        "one_launch": "one aggregation over a chunk: gather kernels (dense blocks, sparse rows) + the reduce of cut rows",
         "algorithmic_bytes_per_launch": round(dom_bytes / max(dom_launches, 1)),
         "avg_launch_ms": round(dom_ms / max(dom_launches, 1), 4), "launches": dom_launches,
         "gathered_bytes_per_launch": round(dom_gather / max(dom_launches, 1)),
@@ -256,15 +282,34 @@ def main():
     }
     kernels_ms = {k: round(v[0] / n_extra, 3) for k, v in prof_all.items()}
 
-    # ---- gemm side of the metric: achieved rate of the dense products against the bf16 matrix-core peak
-    gemm_flops = 0.0
+    # ---- gemm side of the metric: achieved rate of the dense products against the matrix-core peak and against
+    # the ceiling of their own shape, min(peak, arithmetic intensity x HBM bandwidth), operands from HBM once
+    gemm_flops = gemm_bytes = 0.0
     for j in range(L):
         per = 2.0 * n * dims[j] * dims[j + 1]
-        gemm_flops += per * (3 if (j > 0 or not first_stage) else 2)  # forward, weight gradient, input gradient
+        products = 3 if (j > 0 or not first_stage) else 2   # forward, weight gradient, input gradient
+        gemm_flops += per * products
+        in_e = 4 if (j == 0 and l0 == torch.float32) else elt
+        gemm_bytes += products * (n * (dims[j] * in_e + dims[j + 1] * elt) + dims[j] * dims[j + 1] * elt)
     gemm_ms = sum(prof_all[k][0] for k in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad")) / n_extra
-    gemm = {"tflops": round(gemm_flops / max(gemm_ms * 1e-3, 1e-12) / 1e12, 1), "ms_per_step": round(gemm_ms, 3),
-            "frac_of_mfma_peak": round(gemm_flops / max(gemm_ms * 1e-3, 1e-12) / (2.5e15 if bf else 157.3e12), 4),
-            "bound": f"hbm ({max(dims[1:]) // 2} flop/B at width {max(dims[1:])} against a machine balance of 312)"}
+    peak = BF16_MFMA_PEAK if bf else FP32_VALU_PEAK
+    rate = gemm_flops / max(gemm_ms * 1e-3, 1e-12)
+    ai = gemm_flops / gemm_bytes
+    ceiling = min(peak, ai * HBM_PEAK_GBS * 1e9)
+    gemm = {"tflops": round(rate / 1e12, 1), "ms_per_step": round(gemm_ms, 3),
+            "frac_of_mfma_peak": round(rate / peak, 4),
+            "flop_per_byte": round(ai, 1), "shape_ceiling_tflops": round(ceiling / 1e12, 1),
+            "frac_of_shape_ceiling": round(rate / ceiling, 4),
+            "bound": "hbm" if ceiling < peak else "mfma"}
+
+    # ---- update_history against this box's plain copy bandwidth
+    hist_bytes = sum(2.0 * n * dims[j] * (4 if (j == 0 and l0 == torch.float32) else elt)
+                     for j in range(L) if hist[j].data_ptr() != cur[j].data_ptr())
+    hms = kernels_ms.get("history_copy", 0.0)
+    history = {"bytes_per_step": round(hist_bytes), "ms_per_step": hms,
+               "GBps": round(hist_bytes / max(hms * 1e-3, 1e-12) / 1e9, 1) if hms > 0 else None,
+               "box_copy_GBps": round(copy_gbs, 1),
+               "frac_of_box_copy": round(hist_bytes / max(hms * 1e-3, 1e-12) / 1e9 / copy_gbs, 3) if hms > 0 else None}
 
     # ---- optional: epochs of the whole training loop around the same stage ------------------
     trainer = None
@@ -290,38 +335,42 @@ def main():
         trainer = {"ms_per_epoch": round(1e3 * (time.perf_counter() - t_tr) / args.train_epochs, 3), "epochs": args.train_epochs,
                    "head_classes": n_classes, "optimizer": "adam", "loss": last_loss,
                    "step": "stage step + linear softmax cross-entropy head + Adam update of all weights"}
+        del tr
 
     # ---- CPU baseline: the oracle on a bounded sample ---------------------------------------
     cpu = None
-    if not args.no_cpu_baseline and w.variant in ("gcn", "gcnii"):
-        cpu = cpu_baseline(w, row_ptr, col, x0_np, dims, args.cpu_sample_rows)
+    if with_cpu and w.variant in ("gcn", "gcnii"):
+        # level tables of a realistic range, drawn afresh (inputs, not what the library computed); this leg is timed, not compared
+        tables = [cur[0]] + [dev_normal((n, dims[j]), sdt, absolute=True) for j in range(1, L)]
+        cpu = cpu_baseline(w, row_ptr, col, tables, h0, dims, args.cpu_sample_rows if args.cpu_sample_rows > 0 else None)
 
     out = {
-        "metric": "layer-stage fwd+bwd edges/sec per MI355X", "value": value, "unit": "edges/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if bf else "f32", "data": "synthetic",
-        "config": {"workload": f"configs[{args.workload[1:]}] {w.name}: {'R-MAT' if w.kind == 'rmat' else 'Erdos-Renyi'} n={n} nnz={nnz} dims={dims} chunks={K} "
-                               f"{w.variant} {'bf16 levels, fp32 level 0' if w.level0_f32 else w.dtype}{cut_note}{' edge weights given by the caller' if args.caller_weights else ''}",
-                   "max_degree": stats["max_degree"], "step": "forward all chunks + backward all chunks + update_history"},
-        "kernel_ms_per_step": kernels_ms,
-        "gemm": gemm,
-        "roofline": roofline,
-        "cpu_baseline": cpu,
+        "workload": f"configs[{name[1:]}] {w.name}: {'R-MAT' if w.kind == 'rmat' else 'Erdos-Renyi'} n={n} nnz={nnz} dims={dims} chunks={K} "
+                    f"{w.variant} {'bf16 levels, fp32 level 0' if w.level0_f32 else w.dtype}{cut_note}{' edge weights given by the caller' if args.caller_weights else ''}",
+        "max_degree": stats["max_degree"], "value": value, "unit": "edges/s", "ms_per_step": ms_per_step, "steps": steps,
+        "dtype": "bf16" if bf else "f32",
+        "kernel_ms_per_step": kernels_ms, "gemm": gemm, "roofline": roofline, "update_history": history, "cpu_baseline": cpu,
     }
     if trainer is not None:
         out["trainer"] = trainer
-    print(json.dumps(out), flush=True)
+    st.gnnstage_destroy()
+    del st, cur, hist, W, dW, grad_out, h0, grad_h0, grad_in
+    torch.cuda.empty_cache()
+    return out
 
 
-def cpu_baseline(w, row_ptr, col, x0_np, dims, sample_rows):
+def cpu_baseline(w, row_ptr, col, tables, h0, dims, sample_rows):
     """Times the CPU oracle (as it stands) on the first `sample_rows` destination rows of the same
     workload: all layers, forward + backward, half of the remaining vertices marked processed."""
+    import ctypes
+
     import oracle
     from synth import values
 
     n = len(row_ptr) - 1
     L = len(dims) - 1
+    if sample_rows is None:  # about 10 to 30 seconds of oracle time on the box's cores
+        sample_rows = {"c1": 131072, "c2": 306250, "c3": n // 2, "c4": 312500}.get(w.name, 131072)
     s = min(sample_rows, n // 2)
     chunk_ptr = np.array([0, s, (s + n) // 2, n], dtype=np.int64)
     t0 = time.time()
@@ -331,34 +380,85 @@ def cpu_baseline(w, row_ptr, col, x0_np, dims, sample_rows):
     Wn = [values.glorot_uniform(w.seed, 100 + j, dims[j], dims[j + 1]) for j in range(L)]
     beta = None
     if not gcn:
-        import math
         beta = np.array([math.log(0.5 / l + 1.0) for l in range(w.gcnii_first_layer, w.gcnii_first_layer + L)])
-    h0 = None if gcn else values.normal(w.seed, 2, (n, dims[0]))
+    h0n = None if h0 is None else h0.float().cpu().numpy()
     st = oracle.OracleStage(row_ptr, col, val, chunk_ptr, dims, Wn, None, variant=w.variant, a=w.gcnii_alpha,
-                            beta=beta, h0=h0, quant=quant, level0_f32=w.level0_f32)
-    st.cur[0][...] = x0_np
-    st.hist[0][...] = x0_np
-    for j in range(1, L):
-        # values only need a realistic range here (this leg is timed, not compared)
-        st.hist[j][...] = values.half_normal(w.seed, 400 + j, (n, dims[j]))
-        st.cur[j][...] = st.hist[j]
+                            beta=beta, h0=h0n, quant=quant, level0_f32=w.level0_f32)
+    for j in range(L):  # one host array as current and historical level: nothing is compared here
+        a = tables[j].float().cpu().numpy()
+        st.cur[j] = a
+        st.hist[j] = a
+    st._refresh()
     log(f"[bench] oracle set-up {time.time() - t0:.1f}s")
     edges = int(row_ptr[s] - row_ptr[0])
     gout = values.normal(w.seed, 3, (s, dims[-1]))
     st.begin_pass()
     st.processed[2] = 1   # half of the other vertices count as already processed (read from cur)
     t1 = time.perf_counter()
-    st.lib.oracle_forward_chunk(__import__("ctypes").byref(st._cs), 0)
+    st.lib.oracle_forward_chunk(ctypes.byref(st._cs), 0)
     t_f = time.perf_counter() - t1
     st.bprocessed[2] = 1
     t2 = time.perf_counter()
-    st.lib.oracle_backward_chunk(__import__("ctypes").byref(st._cs), 0, np.ascontiguousarray(gout).ctypes.data, 1)
+    st.lib.oracle_backward_chunk(ctypes.byref(st._cs), 0, np.ascontiguousarray(gout).ctypes.data, 1)
     t_b = time.perf_counter() - t2
     total = t_f + t_b
     return {"value": L * edges / total, "unit": "edges/s", "cores": oracle.max_threads(), "kind": "oracle",
             "sample": f"first {s} destination rows ({edges} entries) of the same graph, all {L} layers, forward "
                       f"{t_f:.2f}s + backward {t_b:.2f}s, half of the other vertices marked processed",
             "seconds": round(total, 2)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default=HEADLINE, help="headline configuration (default: the largest one, c4)")
+    ap.add_argument("--only", action="store_true", help="time the headline configuration only (no per_config object)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-rows", type=int, default=0, help="0: a sample sized to about 10-30 s of oracle time")
+    ap.add_argument("--partition", action="store_true",
+                    help="chunks from the library's locality-aware partitioner instead of index ranges (not the benchmark configuration)")
+    ap.add_argument("--partition-by-entries", action="store_true", help="with --partition: balance the chunks by entries")
+    ap.add_argument("--caller-weights", action="store_true",
+                    help="hand the edge weights to the library (edge_val) instead of letting it compute the normalisation: "
+                         "dense blocks then run from stored weight tiles instead of bit patterns")
+    ap.add_argument("--train-epochs", type=int, default=0,
+                    help="also time this many epochs of the whole training loop (head + Adam) around the same stage")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one pipeline stage on ONE GPU; this build has no multi-GPU path (--gpus must be 1)")
+
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    copy_gbs = copy_bandwidth(torch, "cuda:0")
+    log(f"[bench] plain device copy on this box: {copy_gbs:.0f} GB/s (read + written)")
+
+    head = run_config(args.workload, args, args.steps, args.warmup, not args.no_cpu_baseline, copy_gbs)
+    per_config = {}
+    if not args.only and args.workload == HEADLINE and not (args.partition or args.caller_weights or args.train_epochs):
+        for name in SECONDARY:
+            r = run_config(name, args, args.steps, args.warmup, False, copy_gbs)
+            per_config[name] = {k: r[k] for k in ("workload", "value", "unit", "ms_per_step", "steps", "dtype", "kernel_ms_per_step",
+                                                  "gemm", "roofline", "update_history")}
+    out = {
+        "metric": "layer-stage fwd+bwd edges/sec per MI355X", "value": head["value"], "unit": "edges/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": head["dtype"], "data": "synthetic",
+        "config": {"workload": head["workload"], "max_degree": head["max_degree"],
+                   "step": "forward all chunks + backward all chunks + update_history"},
+        "kernel_ms_per_step": head["kernel_ms_per_step"],
+        "gemm": head["gemm"],
+        "update_history": head["update_history"],
+        "roofline": head["roofline"],
+        "cpu_baseline": head["cpu_baseline"],
+    }
+    if per_config:
+        out["per_config"] = per_config
+    if "trainer" in head:
+        out["trainer"] = head["trainer"]
+    print(json.dumps(out), flush=True)
 
 
 if __name__ == "__main__":
