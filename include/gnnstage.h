@@ -154,9 +154,17 @@ int stage_forward_chunk(gnnstage_t *st, int32_t chunk_id, int32_t pos_in_pass, v
  * order of a completed forward pass (otherwise EORDER): then a vertex is "processed" in the
  * backward pass exactly when it read current values in the forward pass, and the zero rule of
  * Section 3.4 yields the gradient of the chunked forward with history held constant.
- * Accumulates dW, dbias (and grad_h0), writes grad_in rows of the chunk when requested.
+ * Accumulates dW, dbias (and grad_h0), writes grad_in rows of the chunk when requested.  dW and dbias are complete
+ * after the last backward call of the pass (see gnnstage_flush_weight_gradients).
  */
 int stage_backward_chunk(gnnstage_t *st, int32_t chunk_id, const void *grad_out_rows, void *hip_stream);
+
+/* The library takes the weight gradient of a layer in ONE product over all rows once the backward pass is complete
+ * (the last stage_backward_chunk call of a pass does it), not chunk by chunk.  A caller that stops a backward pass
+ * early calls this to have dW / dbias hold the contributions of the backward calls made so far; it is a no-op when
+ * nothing is owed.  (Layers that run transform-first owe a further term that needs every chunk's gradient rows;
+ * their dW is complete only after the last backward call.)  Asynchronous on hip_stream. */
+int gnnstage_flush_weight_gradients(gnnstage_t *st, void *hip_stream);
 
 /* hist[j] <- cur[j] for j < L, all rows (Section 3.4, second technique: when to call it, i.e.
  * the refresh period, is caller policy).  Levels whose hist pointer aliases cur are skipped. */
@@ -229,9 +237,11 @@ int gnnstage_plan_pack(int64_t n, int64_t nnz, const int32_t *idx, int32_t n_chu
  * A task is what one wavefront does.  Rows with at most split_edges entries are one task each
  * (task_slot = -1).  Longer rows are cut into pieces of at most split_edges entries; with n_classes > 1
  * rows of at least class_min_row entries are first cut where the source id changes its range class
- * (class q = source ids [class_lo[q], class_lo[q + 1]), n_classes + 1 ascending bounds from 0 to n_vertices;
- * class_lo == NULL means equal id ranges), so that each piece gathers from one slice of the source
- * table.  Every piece carries the index of the fp32 partial-sum slot it writes (consecutive per row).
+ * (class q = source ids [class_lo[q], class_lo[q + 1]), n_classes + 1 ascending bounds from 0 to at most
+ * n_vertices - ids from class_lo[n_classes] on belong to no class and their run is cut into class-less pieces;
+ * class_lo == NULL means equal id ranges up to n_vertices), so that each piece gathers from one slice of the
+ * source table.  (The stage also calls this with `idx` holding, instead of ids, the hotness RANK of every
+ * entry's source, ascending inside a row: classes are then slices of the most often gathered sources.)  Every piece carries the index of the fp32 partial-sum slot it writes (consecutive per row).
  * force_slot (one byte per vertex, may be NULL) marks rows whose sum has parts outside this index: such a row
  * always writes partial sums (never the finished row), and gets no task at all when it is empty here.
  * Tasks are emitted class-major: the pieces of class 0, ..., class n_classes-1 (inside a class the longest
@@ -315,6 +325,19 @@ int gnnstage_profile_enable(gnnstage_t *st, int32_t on);
 int gnnstage_profile_select(gnnstage_t *st, uint32_t kind_mask);
 int gnnstage_profile_read(gnnstage_t *st, int32_t kind, int32_t layer, double *ms, int64_t *launches);
 int gnnstage_profile_reset(gnnstage_t *st);
+
+/*
+ * Diagnostic: what this GPU's memory system gives the access pattern of the aggregation (Algorithm 1's AGGREGATE
+ * line reads one embedding row per neighbour), with no arithmetic and no index traffic around it.  Every 16-lane
+ * group reads whole rows of row_bytes (a multiple of 256, at most 4096) at pseudo-random row numbers, eight rows in
+ * flight per group, 2048 workgroups; a share hot_share of the draws goes to rows [0, hot_rows), the rest is uniform
+ * over the n_rows rows of the table.  One warm-up launch, then n_launches timed with HIP events on hip_stream;
+ * synchronises.  table: DEVICE, n_rows * row_bytes bytes, 16-byte aligned; sink: DEVICE, 4 bytes.
+ * bytes_per_second (HOST) receives gathered bytes per second.  Returns 0, GNNSTAGE_EINVAL or GNNSTAGE_EHIP.
+ */
+int gnnstage_debug_gather_rate(const void *table, int64_t n_rows, int32_t row_bytes, int64_t gathers_per_launch,
+                               int32_t n_launches, int64_t hot_rows, double hot_share, uint32_t seed, void *sink,
+                               void *hip_stream, double *bytes_per_second);
 
 /* Library version, e.g. 100 = 0.1.0 */
 int gnnstage_version(void);

@@ -9,4 +9,5 @@ from .binding import (  # noqa: F401
     gnnstage_dense_plan, gnnstage_plan_pack, gnnstage_plan_tasks, gnnstage_plan_transpose, gnnstage_version, lib,
     GNNTRAIN_ADAM, GNNTRAIN_SGD, GnnTrainer, gnntrain_adam_step, gnntrain_chunk_order, gnntrain_sgd_step,
     gnntrain_softmax_xent, gnntrain_sum, gnntrain_sum_static, gnnstage_partition_chunks, gnnstage_permute_csr,
+    gnnstage_debug_gather_rate,
 )

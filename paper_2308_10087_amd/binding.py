@@ -81,6 +81,8 @@ def _load():
     lib.stage_forward_chunk.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
     lib.stage_backward_chunk.restype = C.c_int
     lib.stage_backward_chunk.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.gnnstage_flush_weight_gradients.restype = C.c_int
+    lib.gnnstage_flush_weight_gradients.argtypes = [C.c_void_p, C.c_void_p]
     lib.update_history.restype = C.c_int
     lib.update_history.argtypes = [C.c_void_p, C.c_void_p]
     lib.gnnstage_destroy.restype = C.c_int
@@ -153,6 +155,9 @@ def _load():
                                           C.c_float, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.gnntrain_sum.restype = C.c_int
     lib.gnntrain_sum.argtypes = [C.c_void_p, C.c_int64, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.gnnstage_debug_gather_rate.restype = C.c_int
+    lib.gnnstage_debug_gather_rate.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int64, C.c_int32, C.c_int64, C.c_double,
+                                               C.c_uint32, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
     lib.gnntrain_sum_static.restype = C.c_int
     lib.gnntrain_sum_static.argtypes = [C.c_void_p, C.c_int64, C.c_float, C.c_void_p, C.c_void_p]
     lib.gnntrain_adam_step.restype = C.c_int
@@ -231,6 +236,21 @@ def gnnstage_plan_tasks(ptr: np.ndarray, row_begin: int, row_end: int, split_edg
     if return_classes:
         return row, e0, ne, slot, int(ns.value), class_off, slot_class[:int(ns.value)]
     return row, e0, ne, slot, int(ns.value)
+
+
+def gnnstage_debug_gather_rate(table, n_rows: int, row_bytes: int, gathers_per_launch: int, n_launches: int = 3,
+                               hot_rows: int = 0, hot_share: float = 0.0, seed: int = 1) -> float:
+    """Gathered bytes per second of random whole-row reads from ``table`` (a device tensor of at least
+    n_rows * row_bytes bytes); see include/gnnstage.h."""
+    import torch
+    sink = torch.zeros(1, dtype=torch.int32, device=table.device)
+    out = C.c_double(0.0)
+    rc = lib.gnnstage_debug_gather_rate(table.data_ptr(), int(n_rows), int(row_bytes), int(gathers_per_launch), int(n_launches),
+                                        int(hot_rows), float(hot_share), int(seed) & 0xffffffff, sink.data_ptr(),
+                                        C.c_void_p(torch.cuda.current_stream().cuda_stream), C.byref(out))
+    if rc != 0:
+        raise GnnStageError(rc, "gnnstage_debug_gather_rate")
+    return float(out.value)
 
 
 def gnnstage_partition_chunks(row_ptr: np.ndarray, col_idx: np.ndarray, n_chunks: int, passes: int = 6, slack: float = 1.1,
@@ -396,6 +416,9 @@ class GnnStage:
 
     def gnnstage_set_dropout_rate(self, dropout_p: float) -> None:
         self._check(lib.gnnstage_set_dropout_rate(self._h, float(dropout_p)))
+
+    def gnnstage_flush_weight_gradients(self, stream=None) -> None:
+        self._check(lib.gnnstage_flush_weight_gradients(self._h, self._stream(stream)))
 
     def update_history(self, stream=None) -> None:
         self._check(lib.update_history(self._h, self._stream(stream)))

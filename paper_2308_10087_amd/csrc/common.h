@@ -62,6 +62,12 @@ struct SpmmArgs {
   const int32_t *task_ne;
   const int32_t *task_slot;
   int64_t n_tasks;
+  // The last n_short tasks are whole rows of at most a few entries (no partial slot).  The matrix-core kernel gives
+  // them to extra workgroups of the same launch in which every 16-lane group owns a row of its own: a wave per
+  // row would spend its life waiting for three dependent round trips to move a kilobyte or two.  The launcher
+  // takes them off n_tasks; the vector-ALU kernel ignores the field and serves them like any other task.
+  int64_t n_short;
+  int64_t n_main_blocks;  // set by the launcher: workgroups from this index on serve the short rows
   // XCD-aware serving order.  Tasks [0, tail_task0) are pieces grouped by source-id class (class c at
   // cls_task0[c], cls_ntasks[c] of them).  Workgroups are dealt round-robin to the 8 XCDs; XCD x
   // (workgroups with index % 8 == x) serves up to kMaxSegs segments, segment s being the groups of four tasks

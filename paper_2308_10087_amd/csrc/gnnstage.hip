@@ -36,7 +36,10 @@ std::string g_create_error;
 //   GNNSTAGE_SPMM_UNROLL (2, 4, 8)    gather slots per wave of the matrix-core aggregation
 //   GNNSTAGE_GEMM_WS_MIN_ROWS         rows from which the weight-stationary product is used
 //   GNNSTAGE_WGRAD_DEFER=0            weight gradients per chunk instead of one product per layer at the end of the pass
-//   GNNSTAGE_HOT_SOURCES (0 = off)    hottest sources whose rows are gathered from a compact copy
+//   GNNSTAGE_HOT_CLASSES (0 = off, 2..32: on whatever the table size)   classes of the hottest sources
+//   GNNSTAGE_HOT_ROWS                 sources per such class
+//   GNNSTAGE_HOT_MIN_ROW              rows from this length on are cut by hotness class
+//   GNNSTAGE_SHORT_ROW (0 = off)      whole rows of at most this many entries are served a row per 16-lane group
 struct Tuning {
   int split_edges = 0;          // 0: from the launch size
   int xcd_classes = 0;          // 0: from the size of the gathered table
@@ -50,6 +53,12 @@ struct Tuning {
   int spmm_unroll = 2;          // two slots leave room for eight waves per SIMD, which measured best on every workload
   int gemm_ws_min_rows = 65536;
   bool wgrad_defer = true;
+  int hot_classes = -1;         // -1: 16 for gathered tables beyond 256 MB, none below
+  int hot_rows = 0;             // 0: as many rows as fit an XCD's 4 MB L2
+  int hot_min_row = 2048;       // measured on the 10 M vertex graph: 512 -> 142.8, 1024 -> 140.6, 2048 -> 140.4 ms per step (off: 143.2)
+  int short_row = -1;           // whole rows of at most this many entries are served a row per 16-lane group (0: none;
+                                // -1: 4 for gathered tables beyond 256 MB, none below: 141.2 against 143.2 ms per step there,
+                                // nothing or a small loss on tables that sit in a cache)
 };
 
 Tuning read_tuning() {
@@ -67,6 +76,10 @@ Tuning read_tuning() {
   if ((e = getenv("GNNSTAGE_SPMM_UNROLL"))) t.spmm_unroll = atoi(e);
   if ((e = getenv("GNNSTAGE_GEMM_WS_MIN_ROWS"))) t.gemm_ws_min_rows = atoi(e);
   if ((e = getenv("GNNSTAGE_WGRAD_DEFER")) && atoi(e) == 0) t.wgrad_defer = false;
+  if ((e = getenv("GNNSTAGE_HOT_CLASSES")) && atoi(e) >= 0 && atoi(e) <= kMaxClasses) t.hot_classes = atoi(e);
+  if ((e = getenv("GNNSTAGE_HOT_ROWS")) && atoi(e) >= 1) t.hot_rows = atoi(e);
+  if ((e = getenv("GNNSTAGE_HOT_MIN_ROW")) && atoi(e) >= 1) t.hot_min_row = atoi(e);
+  if ((e = getenv("GNNSTAGE_SHORT_ROW")) && atoi(e) >= 0) t.short_row = atoi(e);
   return t;
 }
 
@@ -86,6 +99,23 @@ int split_edges_for(const Tuning &t, int64_t entries) {
 int xcd_classes_setting(const Tuning &t, int64_t table_bytes) {
   if (t.xcd_classes >= 1) return t.xcd_classes;
   return table_bytes <= (int64_t)256 << 20 ? 8 : 1;
+}
+
+// Hotness classes, for tables that fit no cache.  On a power-law graph a small set of sources takes a large share
+// of all gathers (10 M vertices, 21 entries per row: the 130 k most frequent sources are 45 % of the entries), but
+// between two uses of such a row an XCD streams far more than its 4 MB L2 holds.  So the hottest sources are cut
+// into classes of as many rows as fit one L2, long rows get their entries ordered by hotness and are cut at the
+// class bounds, and the pieces of a class run together on one XCD (the class machinery above): a hot row is
+// fetched once per launch and XCD instead of once per use.  The rest of every row, and all short rows, gather
+// as before.  Off when id-range classes are forced (GNNSTAGE_XCD_CLASSES).
+int hot_classes_setting(const Tuning &t, int64_t table_bytes) {
+  if (t.xcd_classes >= 1) return 0;
+  if (t.hot_classes >= 0) return t.hot_classes >= 2 ? t.hot_classes : 0;
+  return table_bytes > (int64_t)256 << 20 ? 16 : 0;
+}
+int64_t hot_rows_setting(const Tuning &t, int64_t row_bytes) {
+  if (t.hot_rows >= 1) return t.hot_rows;
+  return std::max<int64_t>(64, ((int64_t)4 << 20) / std::max<int64_t>(row_bytes, 1));
 }
 
 // Lower bounds of the source-id classes: equal id ranges, except that a bound moves onto a chunk boundary
@@ -155,6 +185,7 @@ constexpr int kDenseItemBlocks = kDenseMaxItemBlocks;
 
 struct TaskList {
   int64_t n_tasks = 0, n_long = 0, n_slots = 0;
+  int64_t n_short = 0;  // the last n_short tasks are whole rows of at most Tuning::short_row entries
   int32_t *task_row = nullptr;
   int64_t *task_e0 = nullptr;
   int32_t *task_ne = nullptr;
@@ -183,11 +214,10 @@ struct PlanCounts {
 
 // Upper bounds (from row lengths alone) on tasks / cut rows / slots of every chunk: a row cut by
 // source class adds at most one extra piece per class.
-PlanCounts count_plan(const Tuning &tune, const int64_t *ptr, const std::vector<int64_t> &chunk_ptr, int classes,
+PlanCounts count_plan(const Tuning &tune, const int64_t *ptr, const std::vector<int64_t> &chunk_ptr, int classes, int min_row,
                       const uint8_t *force = nullptr) {
   PlanCounts pc;
   const int K = (int)chunk_ptr.size() - 1;
-  const int min_row = tune.class_min_row;
   pc.tasks.assign(K, 0);
   pc.longs.assign(K, 0);
   pc.slots.assign(K, 0);
@@ -199,7 +229,7 @@ PlanCounts count_plan(const Tuning &tune, const int64_t *ptr, const std::vector<
       const int64_t len = ptr[r + 1] - ptr[r];
       const bool by_src = classes > 1 && len >= min_row;
       if (by_src || len > split || (force && force[r])) {
-        const int64_t pieces = (len + split - 1) / split + (by_src ? classes : 0);
+        const int64_t pieces = (len + split - 1) / split + (by_src ? classes + 1 : 0);  // + 1: the run beyond the classes
         pc.tasks[c] += pieces;
         pc.slots[c] += pieces;
         pc.longs[c] += 1;
@@ -222,6 +252,8 @@ struct HostDir {
   const int32_t *idx = nullptr;
   int64_t nnz = 0;
   std::vector<uint8_t> force;     // rows with dense parts (they always write partial sums)
+  HotOrder hot;                   // active: idx is hot.idx (long rows ordered by hotness), hot.rank the ranks in that order
+  int min_row = 128;              // rows from this length on are cut by class
   PlanCounts pc;
   std::vector<int32_t> item_rb, item_nb;
   std::vector<int64_t> item_b0;
@@ -241,7 +273,7 @@ struct HostDir {
 void host_mask_set(ChunkMask &m, int c) { m.w[c >> 6] |= 1ull << (c & 63); }
 
 bool make_host_dir(const Tuning &tune, const int64_t *ptr, const int32_t *idx, int64_t n, const std::vector<int64_t> &chunk_ptr,
-                   int classes, bool try_dense, int dense_width, HostDir &h) {
+                   int classes, bool hot, bool want_orig, bool try_dense, int dense_width, HostDir &h) {
   const int K = (int)chunk_ptr.size() - 1;
   h.ptr = ptr;
   h.idx = idx;
@@ -290,7 +322,12 @@ bool make_host_dir(const Tuning &tune, const int64_t *ptr, const int32_t *idx, i
       h.max_items = std::max(h.max_items, h.chunk_item_off[(size_t)k + 1] - h.chunk_item_off[(size_t)k]);
     }
   }
-  h.pc = count_plan(tune, h.ptr, chunk_ptr, classes, h.force_ptr());
+  h.min_row = hot ? tune.hot_min_row : tune.class_min_row;
+  if (hot && classes > 1) {  // on the index the sparse kernels see (the dense plan's remainder, if there is one)
+    if (!build_hot_order(h.ptr, h.idx, n, h.min_row, want_orig, h.hot)) return false;
+    h.idx = h.hot.idx.data();
+  }
+  h.pc = count_plan(tune, h.ptr, chunk_ptr, classes, h.min_row, h.force_ptr());
   return true;
 }
 
@@ -317,6 +354,7 @@ struct Layout {
   size_t dense_partial, zero_row;
   size_t partial;
   std::vector<size_t> Z, dZ, Wt, Wn, Tc, Th;
+  std::vector<size_t> dY;  // deferred weight gradients: dL/d(pre-activation) of every aggregate-first layer, all n rows
   std::vector<size_t> Wt_self, Wn_self;  // GraphSage: staged copies of W_self (Wt / Wn then hold W_neigh)
   size_t self_fwd = 0, self_bwd = 0;      // GraphSage: h_v W_self of a chunk (fp32), dY W_self^T of a chunk
   size_t res_dr = 0, ln_partial = 0;      // ResGCN+: gradient of the activated rows of a chunk; parameter-gradient scratch
@@ -334,6 +372,10 @@ struct Shape {
   int dtype = 0, level0_f32 = 0, variant = 0, need_input_grad = 0;
   Tuning tune;
   bool has_bias() const { return variant != GNNSTAGE_GCNII; }
+  // One weight-gradient product per layer over all rows at the end of the backward pass instead of one per chunk
+  // (the rows of dL/d(pre-activation) are kept for the whole pass): a per-chunk product of a few ten thousand rows
+  // runs at its launch and latency floor.  Not for ResGCN+ stages (their backward is a path of its own).
+  bool defer_wgrad() const { return tune.wgrad_defer && variant != GNNSTAGE_RESGCN; }
   bool sage() const { return variant == GNNSTAGE_SAGE; }
   bool res() const { return variant == GNNSTAGE_RESGCN; }
   // elements of one weight matrix: GraphSage stacks [W_self ; W_neigh]
@@ -341,12 +383,20 @@ struct Shape {
   int elt() const { return dtype == GNNSTAGE_BF16 ? 2 : 4; }
   int level_elt(int j) const { return (j == 0 && level0_f32) ? 4 : elt(); }
   // source classes for the aggregation schedule, decided by the widest bf16/fp32 table that is gathered
-  int classes() const {
-    int64_t widest = 0;  // bytes of the widest row any aggregation of the stage gathers
+  int64_t widest_row_bytes() const {  // of the widest row any aggregation of the stage gathers
+    int64_t widest = 0;
     for (int j = 0; j < L; ++j)
       widest = std::max<int64_t>(widest, tf[j] ? (int64_t)dims[j + 1] * elt()
                                                : std::max<int64_t>((int64_t)dims[j] * level_elt(j), (int64_t)dims[j] * elt()));
-    return xcd_classes_setting(tune, n * widest);
+    return widest;
+  }
+  // classes of the hottest sources instead of id-range classes (tables that fit no cache)
+  bool hot() const { return hot_classes_setting(tune, n * widest_row_bytes()) >= 2; }
+  int64_t hot_rows() const { return hot_rows_setting(tune, widest_row_bytes()); }
+  int short_row() const { return tune.short_row >= 0 ? tune.short_row : (n * widest_row_bytes() > ((int64_t)256 << 20) ? 4 : 0); }
+  int classes() const {
+    if (hot()) return hot_classes_setting(tune, n * widest_row_bytes());
+    return xcd_classes_setting(tune, n * widest_row_bytes());
   }
   // dense blocks serve the matrix-core aggregation only: every aggregation of the stage must gather bf16 rows
   // of width 128 or 256
@@ -496,6 +546,7 @@ Layout make_layout(const Shape &s, const HostDir &hf, const HostDir &hb, bool ra
   l.Wn.resize(s.L);
   l.Tc.assign(s.L, 0);
   l.Th.assign(s.L, 0);
+  l.dY.assign(s.L, 0);
   for (int j = 0; j < s.L && s.res(); ++j) {
     // ResGCN+: ReLU(LayerNorm(.)) of the current and of the historical rows, the saved aggregation, and the
     // gradient of the aggregation for ALL rows (the parameter gradient through historical rows needs it)
@@ -518,6 +569,7 @@ Layout make_layout(const Shape &s, const HostDir &hf, const HostDir &hb, bool ra
     } else {
       l.Z[j] = w.take((size_t)s.n * s.ld[j] * elt);
       l.dZ[j] = (j == 0 && !s.need_input_grad) ? 0 : w.take((size_t)s.n * s.ld[j] * elt);
+      if (s.defer_wgrad()) l.dY[j] = w.take((size_t)s.n * s.ld[j + 1] * elt);
     }
   }
   for (int j = 0; j < s.L; ++j) {
@@ -641,6 +693,7 @@ struct gnnstage {
   std::vector<int32_t> order;
   ChunkMask fmask{}, bmask{};
   int n_bwd = 0;
+  std::vector<char> wgrad_pending;  // per chunk: its backward call ran, its rows' weight-gradient products are still owed
   std::string err;
   Profiler prof;
 
@@ -791,6 +844,7 @@ SpmmArgs base_spmm(const gnnstage *st, bool transposed, int chunk) {
   a.task_ne = t.task_ne;
   a.task_slot = t.task_slot;
   a.n_tasks = t.n_tasks;
+  a.n_short = t.n_short;
   a.lr_row = t.lr_row;
   a.lr_slot0 = t.lr_slot0;
   a.lr_nslots = t.lr_nslots;
@@ -1144,8 +1198,8 @@ int make_host_plan(const gnnstage_desc *d, const Shape &s, bool want_edge, HostP
     return GNNSTAGE_EINVAL;
   }
   const bool dense = s.dense_ok();
-  if (!make_host_dir(s.tune, d->row_ptr, d->col_idx, s.n, s.chunk_ptr, s.classes(), dense, s.dense_width(), hp.f) ||
-      !make_host_dir(s.tune, hp.t_ptr.data(), hp.t_row.data(), s.n, s.chunk_ptr, s.classes(), dense, s.dense_width(), hp.b)) {
+  if (!make_host_dir(s.tune, d->row_ptr, d->col_idx, s.n, s.chunk_ptr, s.classes(), s.hot(), want_edge, dense, s.dense_width(), hp.f) ||
+      !make_host_dir(s.tune, hp.t_ptr.data(), hp.t_row.data(), s.n, s.chunk_ptr, s.classes(), s.hot(), want_edge, dense, s.dense_width(), hp.b)) {
     err = "cannot plan the aggregation";
     return GNNSTAGE_EINVAL;
   }
@@ -1293,7 +1347,7 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
   }
 
   // schedules: build on the host chunk by chunk, upload into the preallocated arrays
-  const int classes = s.classes(), min_row = s.tune.class_min_row;
+  const int classes = s.classes();
   auto build = [&](const HostDir &h, const uint32_t *packed, bool transposed, std::vector<TaskList> &lists) -> int {
     const int64_t *ptr = h.ptr;
     const int32_t *idx = h.idx;
@@ -1328,10 +1382,18 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
       int64_t ns = 0;
       std::vector<int64_t> coff(classes + 1, 0);
       std::vector<uint8_t> sclass((size_t)std::max<int64_t>(pc.slots[c], 1), 255);
-      const std::vector<int64_t> cls_lo = class_bounds_by_entries(ptr, idx, s.n, s.chunk_ptr[c], s.chunk_ptr[c + 1], classes, s.chunk_ptr);
-      const int64_t got = gnnstage_plan_tasks(ptr, idx, s.n, s.chunk_ptr[c], s.chunk_ptr[c + 1], pc.split[c], classes,
-                                              cls_lo.data(), min_row, h.force_ptr(), cap, row.data(), e0.data(),
-                                              ne.data(), slot.data(), &ns, coff.data(), sclass.data());
+      // class bounds: equal shares of the chunk's entries over the id range, or (hotness classes) slices of
+      // hot_rows ranks each, the ranks beyond the last slice belonging to no class
+      std::vector<int64_t> cls_lo;
+      if (h.hot.active) {
+        cls_lo.resize((size_t)classes + 1);
+        for (int q = 0; q <= classes; ++q) cls_lo[(size_t)q] = std::min<int64_t>((int64_t)q * s.hot_rows(), s.n);
+      } else {
+        cls_lo = class_bounds_by_entries(ptr, idx, s.n, s.chunk_ptr[c], s.chunk_ptr[c + 1], classes, s.chunk_ptr);
+      }
+      const int64_t got = gnnstage_plan_tasks(ptr, h.hot.active ? h.hot.rank.data() : idx, s.n, s.chunk_ptr[c], s.chunk_ptr[c + 1],
+                                              pc.split[c], classes, cls_lo.data(), h.min_row, h.force_ptr(), cap, row.data(),
+                                              e0.data(), ne.data(), slot.data(), &ns, coff.data(), sclass.data());
       if (got < 0 || got > cap || ns > pc.slots[c]) return GNNSTAGE_EINVAL;
       tl.n_classes = classes > 1 ? classes : 0;
       for (int q = 0; q <= tl.n_classes; ++q) tl.cls_off[q] = coff[q];
@@ -1343,6 +1405,32 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
         return GNNSTAGE_EHIP;
       tl.n_tasks = got;
       tl.n_slots = ns;
+      // whole rows come last in the list: move the short ones behind the others (both parts keep their row order)
+      const int short_row = s.short_row();
+      if (short_row > 0) {
+        int64_t first_whole = got;
+        while (first_whole > 0 && slot[(size_t)first_whole - 1] < 0) --first_whole;
+        std::vector<int64_t> ord;
+        ord.reserve((size_t)(got - first_whole));
+        for (int64_t t = first_whole; t < got; ++t)
+          if (ne[(size_t)t] > short_row) ord.push_back(t);
+        const int64_t n_other = (int64_t)ord.size();
+        for (int64_t t = first_whole; t < got; ++t)
+          if (ne[(size_t)t] <= short_row) ord.push_back(t);
+        tl.n_short = (int64_t)ord.size() - n_other;
+        if (tl.n_short > 0 && n_other > 0) {
+          std::vector<int32_t> r2(ord.size()), n2(ord.size());
+          std::vector<int64_t> e2(ord.size());
+          for (size_t i = 0; i < ord.size(); ++i) {
+            r2[i] = row[(size_t)ord[i]];
+            n2[i] = ne[(size_t)ord[i]];
+            e2[i] = e0[(size_t)ord[i]];
+          }
+          std::copy(r2.begin(), r2.end(), row.begin() + first_whole);
+          std::copy(n2.begin(), n2.end(), ne.begin() + first_whole);
+          std::copy(e2.begin(), e2.end(), e0.begin() + first_whole);
+        }
+      }
       // cut rows: their slots are consecutive, so sorting the pieces by slot groups them by row
       std::vector<std::pair<int32_t, int32_t>> sr;
       for (int64_t t = 0; t < got; ++t)
@@ -1501,13 +1589,18 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
   if (d->edge_val) {
     std::vector<float> fval, tval((size_t)hp.b.nnz);
     const float *fv = d->edge_val;
-    if (hp.f.dense()) {
+    // entry i of the index a direction's sparse kernels see -> its position in that direction's full index:
+    // through the hotness order (if any), then through the dense plan's remainder (if any)
+    auto full_pos = [](const HostDir &h, int64_t i) {
+      if (h.hot.active) i = h.hot.orig[(size_t)i];
+      return h.dense() ? h.dp.rem_orig[(size_t)i] : i;
+    };
+    if (hp.f.dense() || hp.f.hot.active) {
       fval.resize((size_t)hp.f.nnz);
-      for (int64_t i = 0; i < hp.f.nnz; ++i) fval[(size_t)i] = d->edge_val[hp.f.dp.rem_orig[(size_t)i]];
+      for (int64_t i = 0; i < hp.f.nnz; ++i) fval[(size_t)i] = d->edge_val[full_pos(hp.f, i)];
       fv = fval.data();
     }
-    for (int64_t i = 0; i < hp.b.nnz; ++i)
-      tval[(size_t)i] = d->edge_val[t_edge[(size_t)(hp.b.dense() ? hp.b.dp.rem_orig[(size_t)i] : i)]];
+    for (int64_t i = 0; i < hp.b.nnz; ++i) tval[(size_t)i] = d->edge_val[t_edge[(size_t)full_pos(hp.b, i)]];
     if ((hp.f.nnz > 0 && hipMemcpy(st->at<float>(lay.val), fv, sizeof(float) * hp.f.nnz, hipMemcpyHostToDevice) != hipSuccess) ||
         (hp.b.nnz > 0 && hipMemcpy(st->at<float>(lay.tval), tval.data(), sizeof(float) * hp.b.nnz, hipMemcpyHostToDevice) != hipSuccess))
       return bail(GNNSTAGE_EHIP, "uploading edge values failed");
@@ -1548,6 +1641,7 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
     st->fmask = ChunkMask{};
     st->bmask = ChunkMask{};
     st->n_bwd = 0;
+    st->wgrad_pending.assign((size_t)s.K, 0);  // what an abandoned backward pass still owed is dropped with it
     st->dropout_p = st->next_dropout_p;
     st->dropout_seed = st->next_dropout_seed;
     {
@@ -1717,6 +1811,81 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
   return GNNSTAGE_OK;
 }
 
+namespace {
+// Weight (and bias) gradients of the aggregate-first layers that the backward calls made so far still owe:
+// dW_j += scale * Z_j^T dY_j over the rows of every maximal run of chunks whose backward call has run.  A complete
+// pass is one run, i.e. one product per layer over all n rows.
+int flush_deferred_wgrad(gnnstage *st, hipStream_t stream) {
+  const Shape &s = st->s;
+  if (!s.defer_wgrad() || st->wgrad_pending.empty()) return GNNSTAGE_OK;
+  const int cd = st->cdtype();
+  const size_t celt = s.elt();
+  float *gemm_partial = st->at<float>(st->lay.gemm_partial);
+  float *bias_partial = st->at<float>(st->lay.bias_partial);
+  int c = 0;
+  while (c < s.K) {
+    if (!st->wgrad_pending[(size_t)c]) {
+      ++c;
+      continue;
+    }
+    int c1 = c;
+    while (c1 < s.K && st->wgrad_pending[(size_t)c1]) st->wgrad_pending[(size_t)c1++] = 0;
+    const int64_t r0 = s.chunk_ptr[c], M = s.chunk_ptr[c1] - r0;
+    c = c1;
+    if (M <= 0) continue;
+    if (M > 0x7fffffff) return fail(st, GNNSTAGE_ENOTSUP, "more than 2^31 - 1 rows in one weight-gradient product");
+    for (int j = s.L - 1; j >= 0; --j) {
+      if (s.tf[j]) continue;  // transform-first layers: finish_transform_first
+      const char *dY = st->at<char>(st->lay.dY[j]) + (size_t)r0 * s.ld[j + 1] * celt;
+      const bool fuse_bias = s.has_bias() && cd == DT_BF16;
+      Timed t(st, stream, 4, j);
+      if (s.has_bias() && !fuse_bias)
+        HIP_TRY(st, launch_colsum_add(dY, cd, s.ld[j + 1], (int)M, s.dims[j + 1], bias_partial, kMaxSplits, st->dbias[j], stream));
+      GemmTnArgs w{};
+      w.A = st->at<char>(st->lay.Z[j]) + (size_t)r0 * s.ld[j] * celt;
+      w.a_dtype = cd;
+      w.lda = s.ld[j];
+      w.B = dY;
+      w.ldb = s.ld[j + 1];
+      w.M = (int)M;
+      w.I = s.dims[j];
+      w.O = s.dims[j + 1];
+      w.scale = s.variant == GNNSTAGE_GCNII ? st->beta[j] : 1.f;
+      w.dW = st->dW[j] + (s.sage() ? s.w_half(j) : 0);  // GraphSage: W_neigh is the lower half
+      w.partial = gemm_partial;
+      w.max_splits = kMaxSplits;
+      if (fuse_bias) {
+        w.dbias = st->dbias[j];
+        w.bias_partial = bias_partial;
+      }
+      HIP_TRY(st, launch_gemm_tn(w, cd, stream));
+      if (s.sage()) {  // dW_self += h_v^T dY over the rows' own (current) level-j values
+        GemmTnArgs ws{};
+        ws.A = static_cast<const char *>(st->cur[j]) + (size_t)r0 * s.dims[j] * st->level_elt(j);
+        ws.a_dtype = st->level_dtype(j);
+        ws.lda = s.dims[j];
+        ws.B = dY;
+        ws.ldb = s.ld[j + 1];
+        ws.M = (int)M;
+        ws.I = s.dims[j];
+        ws.O = s.dims[j + 1];
+        ws.scale = 1.f;
+        ws.dW = st->dW[j];
+        ws.partial = gemm_partial;
+        ws.max_splits = kMaxSplits;
+        HIP_TRY(st, launch_gemm_tn(ws, cd, stream));
+      }
+    }
+  }
+  return GNNSTAGE_OK;
+}
+}  // namespace
+
+extern "C" int gnnstage_flush_weight_gradients(gnnstage_t *st, void *hip_stream) {
+  if (!st) return GNNSTAGE_EINVAL;
+  return flush_deferred_wgrad(st, static_cast<hipStream_t>(hip_stream));
+}
+
 extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_out_rows, void *hip_stream) {
   if (!st) return GNNSTAGE_EINVAL;
   const Shape &s = st->s;
@@ -1730,28 +1899,42 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
   st->n_bwd += 1;
   mask_set(st->bmask, k);
   if (s.res()) return res_backward_chunk(st, k, grad_out_rows, stream);
+  // what the last call of a pass owes beyond its own rows: the deferred weight-gradient products, then the
+  // history-side weight gradient of the transform-first layers
+  auto end_of_pass = [&]() -> int {
+    if (st->n_bwd != s.K) return GNNSTAGE_OK;
+    const int rc = flush_deferred_wgrad(st, stream);
+    return rc != GNNSTAGE_OK ? rc : finish_transform_first(st, stream);
+  };
   // an empty chunk has no rows of its own, but the end-of-pass work still runs when it is the last call of the pass
-  if (M == 0) return st->n_bwd == s.K ? finish_transform_first(st, stream) : GNNSTAGE_OK;
+  if (M == 0) return end_of_pass();
 
   const int cd = st->cdtype();
   const size_t celt = s.elt();
+  const bool defer = s.defer_wgrad();
   char *G[2] = {st->at<char>(st->lay.G[0]), st->at<char>(st->lay.G[1])};
   float *gemm_partial = st->at<float>(st->lay.gemm_partial);
   float *bias_partial = st->at<float>(st->lay.bias_partial);
+  // Where dY_j = dL/d(pre-activation of layer j) of the chunk's rows lives, [M x ld_{j+1}], zero in the padding
+  // columns.  With deferred weight gradients: the chunk's rows of a matrix over all n rows (transform-first layers
+  // keep that matrix anyway, it is what later chunks' transposed aggregations gather); otherwise one of two
+  // chunk-sized scratch matrices, used alternately.
   int gi = 0;
+  auto full_dY = [&](int j) { return st->at<char>(s.tf[j] ? st->lay.dZ[j] : st->lay.dY[j]); };
+  auto dY_rows = [&](int j) -> char * { return defer ? full_dY(j) + (size_t)row0 * s.ld[j + 1] * celt : G[gi]; };
+  if (defer) st->wgrad_pending[(size_t)k] = 1;
   {
     Timed t(st, stream, 6);
     const char *top = static_cast<const char *>(st->cur[s.L]) + (size_t)row0 * s.dims[s.L] * celt;
-    HIP_TRY(st, launch_relu_mask(grad_out_rows, top, cd, M, s.dims[s.L], G[gi], s.ld[s.L], st->mask_scale(), stream));
+    HIP_TRY(st, launch_relu_mask(grad_out_rows, top, cd, M, s.dims[s.L], dY_rows(s.L - 1), s.ld[s.L], st->mask_scale(), stream));
   }
-  // invariant at the top of every iteration: G[gi] holds dY_j = dL/d(pre-activation of layer j) for the
-  // rows of the chunk, [M x ld_{j+1}], zero in the padding columns
   for (int j = s.L - 1; j >= 0; --j) {
-    const char *dY = G[gi];
+    const char *dY = dY_rows(j);
     // bias gradient = column sums of dY: fused into the weight-gradient product where that product reads dY
-    // (aggregate-first layers of the bf16 stage), a kernel of its own otherwise
+    // (aggregate-first layers of the bf16 stage), a kernel of its own otherwise; aggregate-first layers with
+    // deferred weight gradients take it with the deferred product
     const bool fuse_bias = s.has_bias() && !s.tf[j] && cd == DT_BF16;
-    if (s.has_bias() && !fuse_bias) {
+    if (s.has_bias() && !fuse_bias && !(defer && !s.tf[j])) {
       Timed t(st, stream, 4, j);
       HIP_TRY(st, launch_colsum_add(dY, cd, s.ld[j + 1], (int)M, s.dims[j + 1], bias_partial, kMaxSplits, st->dbias[j], stream));
     }
@@ -1765,12 +1948,12 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
       //   dW += hist^T (A_hat^T dY)                after the last chunk (finish_transform_first).
       const bool shared = st->hist[j] == st->cur[j];
       char *dYfull = st->at<char>(st->lay.dZ[j]);
-      {
+      if (!defer) {
         Timed t(st, stream, 6);
         HIP_TRY(st, launch_copy(dY, dYfull + (size_t)row0 * s.ld[j + 1] * celt, (size_t)M * s.ld[j + 1] * celt, stream));
       }
-      if (shared && !need_prev) continue;  // nothing else depends on dT_cur; G[gi] is not needed below
-      char *dT = G[gi ^ 1];
+      if (shared && !need_prev) continue;  // nothing else depends on dT_cur
+      char *dT = defer ? G[0] : G[gi ^ 1];
       {
         SpmmArgs a = base_spmm(st, true, k);
         a.src_sel = dYfull;
@@ -1823,7 +2006,7 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
           g.aux = static_cast<const char *>(st->cur[j]) + (size_t)row0 * s.dims[j] * celt;
           g.aux_dtype = cd;
           g.aux_ld = s.dims[j];
-          g.out = G[gi];  // dY_j is dead by now
+          g.out = defer ? dY_rows(j - 1) : G[gi];  // without deferral dY_j is dead by now and its scratch is reused
           g.out_dtype = cd;
           g.out_ld = s.ld[j];
           g.out_pad = s.ld[j];
@@ -1835,10 +2018,10 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
         }
         HIP_TRY(st, launch_gemm_nt(g, cd, stream));
       }
-      continue;  // the next dY sits in G[gi] again
+      continue;  // without deferral the next dY sits in G[gi] again
     }
-    const char *Zrows = st->at<char>(st->lay.Z[j]) + (size_t)row0 * s.ld[j] * celt;
-    {
+    if (!defer) {
+      const char *Zrows = st->at<char>(st->lay.Z[j]) + (size_t)row0 * s.ld[j] * celt;
       Timed t(st, stream, 4, j);
       GemmTnArgs w{};
       w.A = Zrows;
@@ -1924,9 +2107,14 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
         a.add_row0 = row0;
       }
       if (j > 0) {
-        a.out = G[gi ^ 1];
+        if (defer) {  // straight into the chunk's rows of dY_{j-1}
+          a.out = full_dY(j - 1);
+          a.out_row0 = 0;
+        } else {
+          a.out = G[gi ^ 1];
+          a.out_row0 = row0;
+        }
         a.out_ld = s.ld[j];
-        a.out_row0 = row0;
         a.epilogue = s.sage() ? SPMM_ADD_MASK : SPMM_MASK;
         a.mask_scale = st->mask_scale();
         a.aux = st->cur[j];
@@ -1942,8 +2130,7 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
     }
     gi ^= 1;
   }
-  if (st->n_bwd == s.K) return finish_transform_first(st, stream);
-  return GNNSTAGE_OK;
+  return end_of_pass();
 }
 
 extern "C" int update_history(gnnstage_t *st, void *hip_stream) {

@@ -1,6 +1,10 @@
 // Small kernels around the two hot operations: weight staging, the ReLU-derivative mask on
 // the upstream gradient, the history copy (Section 3.4, second technique), zero fill, and the
 // symmetric normalisation weights of Section 2.1.
+#include <stdlib.h>
+
+#include <algorithm>
+
 #include "common.h"
 
 namespace {
@@ -175,6 +179,90 @@ static unsigned stream_grid(size_t n16) {
   if (blocks > 256 * 16) blocks = 256 * 16;  // 16 blocks per CU, grid-stride beyond that
   if (blocks == 0) blocks = 1;
   return (unsigned)blocks;
+}
+
+// ---- what the memory system gives a row gather (diagnostic) --------------------------------------------
+// Every 16-lane group reads whole rows of row_bytes (16 bytes per lane and step) at pseudo-random row numbers,
+// eight rows in flight per group, and folds what it read into one word so that no load can be dropped.  A share
+// of the draws goes to the first hot_rows rows (a power-law graph's hubs); the others are uniform over the table.
+namespace {
+__device__ inline uint32_t mix32(uint32_t x) {
+  x ^= x >> 16;
+  x *= 0x7feb352du;
+  x ^= x >> 15;
+  x *= 0x846ca68bu;
+  return x ^ (x >> 16);
+}
+
+template <int MODE>  // 0: plain loads, 1: non-temporal loads, 2: plain loads, hot rows scattered
+__global__ __launch_bounds__(256) void gather_probe_kernel(const u32x4 *table, uint32_t n_rows, int row_vecs, int rows_per_group,
+                                                           uint32_t hot_rows, uint32_t hot_threshold, uint32_t seed, uint32_t *sink) {
+  const uint32_t group = (blockIdx.x * 256u + threadIdx.x) >> 4;
+  const int lig = threadIdx.x & 15;
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  for (int i = 0; i < rows_per_group; i += 8) {
+    u32x4 x[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const uint32_t h = mix32(seed + group * 0x9e3779b9u + (uint32_t)(i + u));
+      const uint32_t pick = mix32(h ^ 0x85ebca6bu);
+      uint32_t row = (pick < hot_threshold) ? h % hot_rows : h % n_rows;
+      if (MODE == 2 && pick < hot_threshold) row *= n_rows / hot_rows;  // the hot rows spread evenly over the table
+      const u32x4 *p = table + (size_t)row * row_vecs + lig;
+      x[u] = MODE == 1 ? __builtin_nontemporal_load(p) : p[0];
+      for (int v = 16; v < row_vecs; v += 16) {
+        const u32x4 y = MODE == 1 ? __builtin_nontemporal_load(p + v) : p[v];
+        x[u] ^= y;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= x[u];
+  }
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x12345677u) sink[0] = group;  // practically never true; keeps the loads alive
+}
+
+}  // namespace
+
+// Times n_launches launches of the probe on `stream` with HIP events and reports bytes gathered per second.
+// table: DEVICE, n_rows rows of row_bytes (a multiple of 256, at most 4096); sink: DEVICE, 4 bytes.
+extern "C" int gnnstage_debug_gather_rate(const void *table, int64_t n_rows, int32_t row_bytes, int64_t gathers_per_launch,
+                                          int32_t n_launches, int64_t hot_rows, double hot_share, uint32_t seed, void *sink,
+                                          void *hip_stream, double *bytes_per_second) {
+  if (!table || !sink || !bytes_per_second || n_rows < 1 || n_rows > 0xffffffffll || row_bytes < 256 || row_bytes > 4096 ||
+      row_bytes % 256 != 0 || gathers_per_launch < 1 || n_launches < 1 || hot_rows < 0 || hot_rows > n_rows ||
+      !(hot_share >= 0.0 && hot_share <= 1.0) || (hot_share > 0.0 && hot_rows < 1))
+    return -1;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int blocks = 256 * 8;  // eight workgroups of four waves per compute unit: full occupancy
+  const int64_t groups = (int64_t)blocks * 16;
+  int64_t per_group = (gathers_per_launch + groups - 1) / groups;
+  per_group = (per_group + 7) / 8 * 8;
+  if (per_group > (1 << 24)) return -1;
+  const uint32_t thr = hot_share >= 1.0 ? 0xffffffffu : (uint32_t)(hot_share * 4294967296.0);
+  hipEvent_t a = nullptr, b = nullptr;
+  if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return -5;
+  auto launch = [&](uint32_t sd) {
+    if (getenv("GNNSTAGE_PROBE_SCATTER"))
+      hipLaunchKernelGGL(gather_probe_kernel<2>, dim3(blocks), dim3(256), 0, s, static_cast<const u32x4 *>(table), (uint32_t)n_rows,
+                         row_bytes / 16, (int)per_group, (uint32_t)std::max<int64_t>(hot_rows, 1), thr, sd, static_cast<uint32_t *>(sink));
+    else if (getenv("GNNSTAGE_PROBE_NT"))
+      hipLaunchKernelGGL(gather_probe_kernel<1>, dim3(blocks), dim3(256), 0, s, static_cast<const u32x4 *>(table), (uint32_t)n_rows,
+                         row_bytes / 16, (int)per_group, (uint32_t)std::max<int64_t>(hot_rows, 1), thr, sd, static_cast<uint32_t *>(sink));
+    else
+    hipLaunchKernelGGL(gather_probe_kernel<0>, dim3(blocks), dim3(256), 0, s, static_cast<const u32x4 *>(table), (uint32_t)n_rows,
+                       row_bytes / 16, (int)per_group, (uint32_t)std::max<int64_t>(hot_rows, 1), thr, sd, static_cast<uint32_t *>(sink));
+  };
+  launch(seed);  // warm-up
+  (void)hipEventRecord(a, s);
+  for (int i = 0; i < n_launches; ++i) launch(seed + 1u + (uint32_t)i);
+  (void)hipEventRecord(b, s);
+  float ms = 0.f;
+  const bool ok = hipEventSynchronize(b) == hipSuccess && hipEventElapsedTime(&ms, a, b) == hipSuccess && hipGetLastError() == hipSuccess;
+  (void)hipEventDestroy(a);
+  (void)hipEventDestroy(b);
+  if (!ok || !(ms > 0.f)) return -5;
+  *bytes_per_second = (double)per_group * (double)groups * (double)row_bytes * n_launches / ((double)ms * 1e-3);
+  return 0;
 }
 
 int launch_copy(const void *src, void *dst, size_t bytes, hipStream_t s) {

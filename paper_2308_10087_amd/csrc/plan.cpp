@@ -6,6 +6,8 @@
 
 #include <algorithm>
 #include <numeric>
+#include <thread>
+#include <utility>
 
 #include "../../include/gnnstage.h"
 #include "plan.h"
@@ -85,7 +87,9 @@ extern "C" int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, i
   std::vector<int64_t> lo((size_t)n_classes + 1);
   for (int q = 0; q <= n_classes; ++q)
     lo[(size_t)q] = class_lo ? class_lo[q] : ((int64_t)q * n_vertices + n_classes - 1) / n_classes;
-  if (lo[0] != 0 || lo[(size_t)n_classes] != n_vertices) return GNNSTAGE_EINVAL;
+  // With explicit bounds the classes may end before n_vertices: ids from lo[n_classes] on belong to no class
+  const int64_t cls_end = lo[(size_t)n_classes];
+  if (lo[0] != 0 || cls_end > n_vertices || (!class_lo && cls_end != n_vertices)) return GNNSTAGE_EINVAL;
   for (int q = 0; q < n_classes; ++q)
     if (lo[(size_t)q] > lo[(size_t)q + 1]) return GNNSTAGE_EINVAL;
   auto cls_of = [&](int64_t u) {  // last q with lo[q] <= u
@@ -120,23 +124,28 @@ extern "C" int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, i
       continue;
     }
     // maximal runs of entries whose source falls in the same id range (contiguous when the row is sorted);
-    // a row whose columns are so unsorted that it has more runs than classes is cut without classes
-    int64_t runs = 1, prev = cls_of(idx[b]);
-    for (int64_t x = b + 1; x < e && runs <= n_classes; ++x) {
-      const int64_t q = (idx[x] >= lo[(size_t)prev] && idx[x] < lo[(size_t)prev + 1]) ? prev : cls_of(idx[x]);
+    // a row whose columns are so unsorted that it has more runs than classes is cut without classes.
+    // Ids beyond the last class form one more run (class index n_classes) whose pieces carry no class.
+    auto cls_or_none = [&](int64_t u) { return u >= cls_end ? (int64_t)n_classes : cls_of(u); };
+    auto in_run = [&](int64_t u, int64_t q) {
+      return q == n_classes ? u >= cls_end : (u >= lo[(size_t)q] && u < lo[(size_t)q + 1]);
+    };
+    int64_t runs = 1, prev = cls_or_none(idx[b]);
+    for (int64_t x = b + 1; x < e && runs <= n_classes + 1; ++x) {
+      const int64_t q = in_run(idx[x], prev) ? prev : cls_or_none(idx[x]);
       if (q != prev) ++runs;
       prev = q;
     }
-    if (runs > n_classes) {
+    if (runs > n_classes + 1) {
       cut(pieces, r, b, e);
       continue;
     }
     int64_t s0 = b;
     while (s0 < e) {
-      const int64_t cls = cls_of(idx[s0]);
+      const int64_t cls = cls_or_none(idx[s0]);
       int64_t s1 = s0 + 1;
-      while (s1 < e && idx[s1] >= lo[(size_t)cls] && idx[s1] < lo[(size_t)cls + 1]) ++s1;
-      cut(by_class[(size_t)cls], r, s0, s1);
+      while (s1 < e && in_run(idx[s1], cls)) ++s1;
+      cut(cls == n_classes ? pieces : by_class[(size_t)cls], r, s0, s1);
       s0 = s1;
     }
   }
@@ -403,4 +412,68 @@ extern "C" int gnnstage_dense_plan_destroy(gnnstage_dense_plan *h) {
   if (!h) return GNNSTAGE_EINVAL;
   delete h;
   return GNNSTAGE_OK;
+}
+
+// ---- hotness order -------------------------------------------------------------------------------
+bool build_hot_order(const int64_t *ptr, const int32_t *idx, int64_t n, int min_row, bool want_orig, HotOrder &out) {
+  out = HotOrder();
+  const int64_t nnz = ptr[n];
+  std::vector<int64_t> count((size_t)n, 0);
+  int64_t most = 0;
+  for (int64_t e = 0; e < nnz; ++e) {
+    const int64_t u = idx[e];
+    if (u < 0 || u >= n) return false;
+    most = std::max(most, ++count[(size_t)u]);
+  }
+  // rank by descending count, ties by ascending id: a bucket per count value, filled in id order
+  std::vector<int64_t> start((size_t)most + 2, 0);  // start[c] = first rank of the vertices that occur c times
+  for (int64_t u = 0; u < n; ++u) start[(size_t)count[(size_t)u]] += 1;
+  int64_t at = 0;
+  for (int64_t c = most; c >= 0; --c) {
+    const int64_t k = start[(size_t)c];
+    start[(size_t)c] = at;
+    at += k;
+  }
+  std::vector<int32_t> rank_of((size_t)n);
+  for (int64_t u = 0; u < n; ++u) rank_of[(size_t)u] = (int32_t)start[(size_t)count[(size_t)u]]++;
+  out.idx.assign(idx, idx + nnz);
+  out.rank.resize((size_t)nnz);
+  if (want_orig) out.orig.resize((size_t)nnz);
+  const unsigned hw = std::thread::hardware_concurrency();
+  const int n_threads = (int)std::max(1u, std::min(16u, hw ? hw : 1u));
+  auto work = [&](int t) {
+    // contiguous row ranges of about equal entry counts
+    const int64_t e_lo = nnz * t / n_threads, e_hi = nnz * (t + 1) / n_threads;
+    int64_t r0 = std::lower_bound(ptr, ptr + n + 1, e_lo) - ptr, r1 = std::lower_bound(ptr, ptr + n + 1, e_hi) - ptr;
+    if (t == 0) r0 = 0;
+    if (t == n_threads - 1) r1 = n;
+    std::vector<std::pair<int32_t, int64_t>> tmp;
+    for (int64_t r = r0; r < r1; ++r) {
+      const int64_t b = ptr[r], e = ptr[r + 1];
+      if (e - b < min_row) {
+        for (int64_t x = b; x < e; ++x) {
+          out.rank[(size_t)x] = rank_of[(size_t)idx[x]];
+          if (want_orig) out.orig[(size_t)x] = x;
+        }
+        continue;
+      }
+      tmp.clear();
+      for (int64_t x = b; x < e; ++x) tmp.emplace_back(rank_of[(size_t)idx[x]], x);
+      std::sort(tmp.begin(), tmp.end());  // ranks are distinct per vertex; equal ranks (a repeated entry) fall back on position
+      for (int64_t x = b; x < e; ++x) {
+        const auto &p = tmp[(size_t)(x - b)];
+        out.rank[(size_t)x] = p.first;
+        out.idx[(size_t)x] = idx[p.second];
+        if (want_orig) out.orig[(size_t)x] = p.second;
+      }
+    }
+  };
+  // lower_bound on ptr may put a row that straddles a boundary into either neighbour, never into both or none:
+  // thread t takes rows [first row starting at or after e_lo, first row starting at or after e_hi)
+  std::vector<std::thread> pool;
+  for (int t = 1; t < n_threads; ++t) pool.emplace_back(work, t);
+  work(0);
+  for (auto &th : pool) th.join();
+  out.active = true;
+  return true;
 }

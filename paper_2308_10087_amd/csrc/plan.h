@@ -43,3 +43,16 @@ struct DensePlan {
 bool build_dense_plan(const int64_t *ptr, const int32_t *idx, int64_t n, int K, const int64_t *chunk_ptr,
                       int min_nnz, double min_share, DensePlan &out, int item_blocks = 0, int64_t max_items = 0,
                       int min_nnz_many = 0);
+
+// Hotness order of one aggregation direction.  A source's hotness is how often it occurs in the index; rank 0 is
+// the most often gathered vertex (ties: lower id first).  Rows with at least min_row entries get their entries
+// re-ordered by ascending rank, so that the entries whose sources belong to one slice of the hottest vertices are
+// one contiguous run of the row; shorter rows keep their order.  idx / rank / orig describe the index after the
+// re-ordering: source id, its rank, and the entry's position in the index the order was built from.
+struct HotOrder {
+  bool active = false;
+  std::vector<int32_t> idx, rank;
+  std::vector<int64_t> orig;  // empty unless asked for
+};
+// Returns false on an index entry outside [0, n).
+bool build_hot_order(const int64_t *ptr, const int32_t *idx, int64_t n, int min_row, bool want_orig, HotOrder &out);

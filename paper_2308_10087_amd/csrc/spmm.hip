@@ -264,6 +264,68 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(1))) bf16x8_t global_bf16x8_t;  // a load through it is a global load
 
+// Short rows (at most a few entries: the bulk of a power-law graph's rows, a few percent of its entries).  A wave
+// per row would spend its life waiting for three dependent round trips to move a kilobyte or two, and a launch
+// would need several rounds of waves.  Here every 16-lane group owns one row: a lane keeps 8 columns of each
+// 128-column tile in fp32 registers and the sum runs on the vector ALU; two to four of the row's entries are in
+// flight per lane.  Entries that a backward launch drops are not loaded at all.  `first` = index of the first row
+// of this workgroup among the launch's short rows.
+template <typename Tout, int NT, bool FULL>
+__device__ __forceinline__ void spmm_short_rows(const SpmmArgs &a, int64_t first) {
+  const int lane = threadIdx.x & 63, lig = lane & 15;
+  const int64_t t = first + (threadIdx.x >> 4);
+  if (t >= a.n_short) return;
+  const int64_t task = a.n_tasks + t;  // the short rows follow the tasks of the main part
+  const uint32_t vmask = (1u << a.vbits) - 1u;
+  const bool drop_unsel = a.src_unsel == nullptr;
+  const char *base_sel = static_cast<const char *>(a.src_sel);
+  const char *base_unsel = drop_unsel ? base_sel : static_cast<const char *>(a.src_unsel);
+  const size_t row_bytes = (size_t)a.src_ld * 2u;
+  const int d = a.d;
+  const int64_t row = a.task_row[task];
+  const int64_t e0 = a.task_e0[task];
+  const int ne = a.task_ne[task];
+  float acc[NT][8];
+#pragma unroll
+  for (int h = 0; h < NT; ++h)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[h][c] = 0.f;
+  constexpr int SU = NT == 1 ? 4 : 2;  // entries in flight per lane (16 bytes x NT each)
+  for (int i = 0; i < ne; i += SU) {
+    bf16x8_t x[SU][NT];
+    float w[SU];
+#pragma unroll
+    for (int u = 0; u < SU; ++u) {
+      w[u] = 0.f;
+#pragma unroll
+      for (int h = 0; h < NT; ++h) x[u][h] = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+      if (i + u < ne) {
+        const uint32_t pc = a.pidx[e0 + i + u];
+        const bool sel = mask_test(a.mask, pc >> a.vbits);
+        if (sel || !drop_unsel) {
+          w[u] = a.val[e0 + i + u];
+          const char *p = (sel ? base_sel : base_unsel) + (size_t)(pc & vmask) * row_bytes + (size_t)lig * 16u;
+#pragma unroll
+          for (int h = 0; h < NT; ++h)
+            if (FULL || h * 128 + lig * 8 < d) x[u][h] = *reinterpret_cast<const bf16x8_t *>(p + h * 256);
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < SU; ++u)
+#pragma unroll
+      for (int h = 0; h < NT; ++h)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[h][c] = __builtin_fmaf(w[u], (float)x[u][h][c], acc[h][c]);
+  }
+#pragma unroll
+  for (int h = 0; h < NT; ++h) {
+    const int c = h * 128 + lig * 8;
+    if (FULL || c < d) finish_cols<bf16_t, Tout, 8>(a, row, c, acc[h]);
+  }
+  zero_pad_cols<Tout>(a, row, lig);
+}
+
 // Entry metadata is turned, once per entry, into a 16-byte record {row address, packed weight halves}
 // and appended to a wave-private ring in LDS; unselected entries of a backward launch are simply not
 // appended, so the gather loop sees one dense stream of kept entries across the 64-entry metadata
@@ -282,6 +344,10 @@ __global__ __launch_bounds__(256, (NT * U <= 8) ? 7 : 1) void spmm_ring_kernel(c
   static_assert(TILE_W * sizeof(float) <= R * sizeof(u32x4_t), "the output row reuses the ring's memory");
   static_assert((U & (U - 1)) == 0 && U <= 8, "slot count");
   __shared__ u32x4_t ring_all[4][R];
+  if ((int64_t)blockIdx.x >= a.n_main_blocks) {  // the workgroups behind the main part serve the short rows, 16 each
+    if constexpr (NT <= 2) spmm_short_rows<Tout, NT, FULL>(a, ((int64_t)blockIdx.x - a.n_main_blocks) * 16);
+    return;
+  }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t task = spmm_task_index(a, blockIdx.x, wave);
   if (task < 0) return;  // whole wave leaves together (no block-wide barrier below)
@@ -564,8 +630,15 @@ static void launch_ring(const SpmmArgs &a, hipStream_t s, dim3 grid, int unroll)
 }
 
 template <typename Tout>
-static int launch_mfma(const SpmmArgs &a, hipStream_t s) {
-  const unsigned gx = (unsigned)(a.n_class_blocks + (a.n_tasks - a.tail_task0 + 3) / 4);
+static int launch_mfma(const SpmmArgs &a_in, hipStream_t s) {
+  SpmmArgs a = a_in;
+  // short whole rows (the tail of the task list) are served a row per 16-lane group, by extra workgroups of the
+  // same launch, when a row fits the registers of such a group
+  const int64_t n_short = (a.d <= 256 && a.n_short > 0 && a.n_short <= a.n_tasks - a.tail_task0) ? a.n_short : 0;
+  a.n_tasks -= n_short;
+  a.n_short = n_short;
+  a.n_main_blocks = a.n_class_blocks + (a.n_tasks - a.tail_task0 + 3) / 4;
+  const unsigned gx = (unsigned)(a.n_main_blocks + (n_short + 15) / 16);
   if (gx == 0) return hipSuccess;  // only class pieces, none of them active
   const int unroll = a.unroll;  // 4 or 8 trade waves per SIMD for deeper per-wave queues (tests run all three)
   if (a.d <= 128)

@@ -201,6 +201,9 @@ def test_full_size_c4_chunks_at_both_ends_of_a_pass():
         g_host = np.ascontiguousarray(g_dev.to(torch.float32).cpu().numpy())
         st.lib.oracle_backward_chunk(ctypes.byref(st._cs), k, g_host.ctypes.data, 0)
         c.stage.stage_backward_chunk(k, g_dev)
+        # the pass stops here: have the weight gradients of the calls made so far now (the library would take
+        # them in one product per layer after the last call of the pass)
+        c.stage.gnnstage_flush_weight_gradients()
         torch.cuda.synchronize()
         c.check_grads(f"backward call of chunk {k}")
     assert order[-2:] == [before_last, last]

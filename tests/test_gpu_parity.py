@@ -190,6 +190,103 @@ def test_source_class_schedules(monkeypatch, classes, min_row, split, name):
     _parity(p, TOL_BF16)
 
 
+@pytest.mark.parametrize("weights", ["given", "computed"])
+@pytest.mark.parametrize("classes,rows,min_row,split,dense", [(4, 32, 8, 64, False), (16, 8, 4, 128, False),
+                                                              (32, 3, 2, 4096, False), (8, 24, 8, 64, True)])
+@pytest.mark.parametrize("name", ["c2_s", "c4_s", "c3_s"])
+def test_hotness_class_schedules(monkeypatch, classes, rows, min_row, split, dense, name, weights):
+    """For tables beyond every cache the schedule cuts long rows by classes of the most often gathered sources
+    (their entries re-ordered by hotness first) and runs a class's pieces together on one XCD.  Forced on the
+    shrunk graphs with tiny classes, tiny rows cut, ragged chunks, forward and backward; with the caller's
+    weights (which must follow their entries through the re-ordering) and with weights the library computes;
+    also on top of dense blocks (the re-ordering then acts on what the dense plan leaves)."""
+    monkeypatch.setenv("GNNSTAGE_HOT_CLASSES", str(classes))
+    monkeypatch.setenv("GNNSTAGE_HOT_ROWS", str(rows))
+    monkeypatch.setenv("GNNSTAGE_HOT_MIN_ROW", str(min_row))
+    monkeypatch.setenv("GNNSTAGE_SPLIT_EDGES", str(split))
+    if dense:
+        monkeypatch.setenv("GNNSTAGE_DENSE_MIN_NNZ", "6")
+        monkeypatch.setenv("GNNSTAGE_DENSE_MIN_SHARE", "0")
+        monkeypatch.setenv("GNNSTAGE_DENSE_MIN_ENTRIES", "0")
+    w = CONFIGS[name]
+    row_ptr, col = __import__("synth").make_graph(w)
+    n = len(row_ptr) - 1
+    p = make_problem(w, graph=(row_ptr, col), chunk_ptr=graphs.ragged_chunks(n, w.n_chunks, 17), bias_std=0.05)
+    _parity(p, TOL_BF16, edge_val=weights)
+
+
+def test_hotness_class_schedule_fp32_probe(monkeypatch):
+    """Exact-integer check of the hotness-class path: unit weights, ones, W = I - every level-1 value is a count
+    of selected neighbours, every input gradient a count of processed readers."""
+    monkeypatch.setenv("GNNSTAGE_HOT_CLASSES", "8")
+    monkeypatch.setenv("GNNSTAGE_HOT_ROWS", "16")
+    monkeypatch.setenv("GNNSTAGE_HOT_MIN_ROW", "4")
+    monkeypatch.setenv("GNNSTAGE_SPLIT_EDGES", "64")
+    w = small(n=1200, k=6, dims=(8, 8), deg=10.0, seed=33)
+    p = make_problem(w, chunk_ptr=graphs.ragged_chunks(1200, 6, 5), bias_std=0.0)
+    p.val = np.ones_like(p.val)
+    p.W = [np.eye(8, dtype=np.float32)]
+    p.x0 = np.ones_like(p.x0)
+    p.hist = [np.zeros_like(p.hist[0])]
+    p.grad_out = np.ones_like(p.grad_out)
+    ref = run_oracle(p)
+    run = _gpu(p).run()
+    assert np.array_equal(run.np(run.cur[1]), ref.cur[1])
+    assert np.array_equal(run.np(run.grad_in), ref.grad_in)
+
+
+@pytest.mark.parametrize("short", [2, 8, 40])
+@pytest.mark.parametrize("name,dims", [("c2_s", None), ("c3_s", None), ("c4_s", None), ("c4_s", (40, 72, 136)), ("c4_s", (64, 256, 200))])
+def test_short_rows_served_a_row_per_lane_group(monkeypatch, short, name, dims):
+    """Whole rows of at most a few entries can be served by 16-lane groups (a row each, vector-ALU sums) instead
+    of a wavefront per row; forced here for several thresholds, full and ragged tile widths, forward and backward."""
+    monkeypatch.setenv("GNNSTAGE_SHORT_ROW", str(short))
+    w = CONFIGS[name]
+    if dims is not None:
+        w = Workload(w.name + "_w", "rmat", w.n, w.seed, list(dims), w.n_chunks, dtype="bf16", n_candidates=w.n_candidates,
+                     rmat_abc=w.rmat_abc)
+    p = make_problem(w, bias_std=0.05)
+    _parity(p, TOL_BF16)
+
+
+@pytest.mark.parametrize("name", ["c0", "c1_s", "c3_s"])
+def test_weight_gradients_per_chunk_instead_of_one_product_per_layer(monkeypatch, name):
+    """By default the stage keeps the gradient rows of a pass and takes every layer's weight gradient in one
+    product after the last backward call; the per-chunk form must give the same gradients."""
+    monkeypatch.setenv("GNNSTAGE_WGRAD_DEFER", "0")
+    p = make_problem(CONFIGS[name], bias_std=0.05)
+    _parity(p, TOL_F32 if name == "c0" else TOL_BF16)
+
+
+@pytest.mark.parametrize("variant,dtype", [("gcn", "f32"), ("gcn", "bf16"), ("sage", "bf16"), ("gcnii", "bf16")])
+def test_flushing_the_weight_gradients_of_a_backward_pass_that_stops_early(variant, dtype):
+    """gnnstage_flush_weight_gradients after every backward call: the gradients then hold exactly the
+    contributions of the calls made so far (compared with the oracle after each call), nothing is added twice,
+    and the last call of the pass leaves the same totals."""
+    dims = (16, 16, 16) if variant == "gcnii" else (24, 40, 16)
+    w = small(n=900, k=5, dims=dims, variant=variant, dtype=dtype)
+    p = make_problem(w, chunk_ptr=graphs.ragged_chunks(900, 5, 9), first_stage=False)
+    tol = TOL_F32 if dtype == "f32" else TOL_BF16
+    ref = p.new_oracle()
+    ref.forward_pass(p.order)
+    run = _gpu(p)
+    assert all(run.stage.gnnstage_layer_order(j) == 0 for j in range(p.L))   # no transform-first layer here
+    run.forward()
+    torch.cuda.synchronize()
+    for j in range(1, p.L + 1):
+        run.cur[j].copy_(torch.from_numpy(ref.cur[j]).to(run.cur[j].dtype))
+    for k in reversed([int(x) for x in p.order]):
+        ref.backward_chunk(k, p.grad_out[ref.rows(k)])
+        run.stage.stage_backward_chunk(k, run.grad_out[run.stage.rows(k)])
+        run.stage.gnnstage_flush_weight_gradients()
+        run.stage.gnnstage_flush_weight_gradients()          # nothing is owed any more: a no-op
+        torch.cuda.synchronize()
+        for j in range(p.L):
+            assert max_rel(run.np(run.dW[j]), ref.dW[j]) <= tol, (k, j)
+            if variant != "gcnii":
+                assert max_rel(run.np(run.dbias[j]), ref.db[j]) <= tol, (k, j)
+
+
 @pytest.mark.parametrize("slots", [4, 8])
 @pytest.mark.parametrize("name", ["c1_s", "c3_s"])
 def test_deeper_gather_queues(monkeypatch, slots, name):

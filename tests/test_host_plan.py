@@ -206,6 +206,58 @@ def test_launch_schedule_with_explicit_class_bounds():
                               class_lo=np.array([0, 5, 3, 9, n]))  # not ascending
 
 
+def test_launch_schedule_with_classes_that_end_before_the_last_id():
+    """Hotness classes: the index handed to the planner holds, per entry, the RANK of its source (0 = most
+    often gathered), ascending inside every row; classes are slices of the first ranks only, and the run of a
+    row beyond the last class is cut into pieces without a class."""
+    g = _lib()
+    w = CONFIGS["c4_s"]
+    row_ptr, col = make_graph(w)
+    n = len(row_ptr) - 1
+    count = np.bincount(col, minlength=n)
+    by_hotness = np.lexsort((np.arange(n), -count))          # descending count, ties by id
+    rank_of = np.empty(n, dtype=np.int64)
+    rank_of[by_hotness] = np.arange(n)
+    ranks = rank_of[col]
+    for v in range(n):                                        # every row ascending in rank
+        ranks[row_ptr[v]:row_ptr[v + 1]].sort()
+    ranks = ranks.astype(np.int32)
+    R, classes, min_row, split = 40, 4, 16, 64
+    lo = np.arange(classes + 1, dtype=np.int64) * R           # ends at rank 160 of 30,011
+    row, e0, ne, slot, n_slots, class_off, slot_class = g.gnnstage_plan_tasks(
+        row_ptr, 0, n, split, idx=ranks, n_vertices=n, n_classes=classes, class_min_row=min_row, return_classes=True,
+        class_lo=lo)
+    covered = np.zeros(row_ptr[-1], dtype=np.int32)
+    for r, a, m in zip(row, e0, ne):
+        assert row_ptr[r] <= a and a + m <= row_ptr[r + 1] and m <= split
+        covered[a:a + m] += 1
+    assert np.all(covered == 1)
+    assert class_off[classes] > 0
+    for q in range(classes):
+        for i in range(class_off[q], class_off[q + 1]):
+            u = ranks[e0[i]:e0[i] + ne[i]]
+            assert ne[i] > 0 and u.min() >= lo[q] and u.max() < lo[q + 1] and slot_class[slot[i]] == q
+    deg = np.diff(row_ptr)
+    n_pieces = int((slot >= 0).sum())
+    tail_pieces = [i for i in range(class_off[classes], n_pieces)]
+    assert tail_pieces, "some long row must have a run beyond the classes"
+    for i in tail_pieces:                                     # class-less pieces: only ranks beyond the classes,
+        u = ranks[e0[i]:e0[i] + ne[i]]                        # or rows too short to be cut by class at all
+        assert slot_class[slot[i]] == 255
+        assert u.min() >= lo[classes] or deg[row[i]] < min_row
+    # a long row's sections appear in rank order: its class pieces cover exactly its entries below the last bound
+    long_rows = np.flatnonzero(deg >= min_row)
+    in_class = np.zeros(row_ptr[-1], dtype=bool)
+    for i in range(class_off[classes]):
+        in_class[e0[i]:e0[i] + ne[i]] = True
+    for v in long_rows[:200]:
+        seg = slice(row_ptr[v], row_ptr[v + 1])
+        assert np.array_equal(in_class[seg], ranks[seg] < lo[classes])
+    with pytest.raises(g.GnnStageError):
+        g.gnnstage_plan_tasks(row_ptr, 0, n, split, idx=ranks, n_vertices=n, n_classes=classes, class_min_row=min_row,
+                              class_lo=np.array([0, 5, 9, 12, n + 1]))  # beyond the id range
+
+
 @pytest.mark.parametrize("name,min_nnz", [("c1_s", 40), ("c3_s", 12), ("c0", 3)])
 def test_dense_plan_partitions_the_entries(name, min_nnz):
     """Dense blocks + remainder hold every entry exactly once, at the right (row, column); rows and columns
