@@ -263,7 +263,7 @@ def test_flushing_the_weight_gradients_of_a_backward_pass_that_stops_early(varia
     """gnnstage_flush_weight_gradients after every backward call: the gradients then hold exactly the
     contributions of the calls made so far (compared with the oracle after each call), nothing is added twice,
     and the last call of the pass leaves the same totals."""
-    dims = (16, 16, 16) if variant == "gcnii" else (24, 40, 16)
+    dims = (16, 16, 16) if variant == "gcnii" else (24, 40, 48)
     w = small(n=900, k=5, dims=dims, variant=variant, dtype=dtype)
     p = make_problem(w, chunk_ptr=graphs.ragged_chunks(900, 5, 9), first_stage=False)
     tol = TOL_F32 if dtype == "f32" else TOL_BF16
