@@ -211,6 +211,8 @@ void oracle_begin_pass(oracle_stage *s) {
 }
 
 /* SplitMix64 output function (Steele, Lea, Flood 2014) */
+/* exported so that the test suite can pin this copy of the generator's output function to the published vector */
+uint64_t oracle_splitmix64(uint64_t z);
 static uint64_t splitmix64(uint64_t z) {
   z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
   z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
@@ -220,6 +222,8 @@ static uint64_t splitmix64(uint64_t z) {
 /* 1 if feature c of vertex u survives the dropout of layer j in the pass with this seed.  The layer's key is
  * the generator's output for state seed + (j + 1) * golden; the element's draw is the output for state
  * key + (u * d + c + 1) * golden; its top 24 bits, as a fraction of 2^24, are compared with p. */
+uint64_t oracle_splitmix64(uint64_t z) { return splitmix64(z); }
+
 int32_t oracle_dropout_keep(uint64_t seed, int32_t j, int64_t u, int32_t d, int32_t c, double p) {
   const uint64_t golden = 0x9E3779B97F4A7C15ull;
   const uint64_t key = splitmix64(seed + (uint64_t)(j + 1) * golden);

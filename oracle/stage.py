@@ -67,6 +67,8 @@ def _lib(f64: bool):
         lib.oracle_backward_finish.restype = None
         lib.oracle_dropout_keep.argtypes = [C.c_uint64, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_double]
         lib.oracle_dropout_keep.restype = C.c_int32
+        lib.oracle_splitmix64.argtypes = [C.c_uint64]
+        lib.oracle_splitmix64.restype = C.c_uint64
         lib.oracle_set_threads.argtypes = [C.c_int]
         lib.oracle_max_threads.restype = C.c_int
         for f in ("oracle_gcn_norm", "oracle_chunk_of", "oracle_build_transpose", "oracle_begin_pass",
@@ -85,6 +87,11 @@ def set_threads(n: int) -> None:
 
 def max_threads() -> int:
     return int(_lib(False).oracle_max_threads())
+
+
+def splitmix64_c(z: int, f64: bool = False) -> int:
+    """Output function of SplitMix64 as the C oracle's dropout draws use it (state in, output out)."""
+    return int(_lib(f64).oracle_splitmix64(int(z) & ((1 << 64) - 1)))
 
 
 def gcn_norm(row_ptr: np.ndarray, col: np.ndarray, f64: bool = False) -> np.ndarray:

@@ -1,6 +1,7 @@
 """GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element,
 on the same seeded inputs.  Tolerances (per tensor, max|x - ref| / max|ref|):
 1e-5 for the fp32 stage, 1e-2 for the bf16 / matrix-core stage; integer bookkeeping bit-exact."""
+import math
 import os
 
 import numpy as np
@@ -19,6 +20,24 @@ TOL_F32 = 1e-5
 TOL_BF16 = 1e-2
 
 
+# Share of a level's elements whose ReLU decision may differ between the two sides (each of them a near-tie, see
+# _check_forward).  How many elements sit that close to zero is a property of the data, not of either side's
+# arithmetic.  Measured over this file: at most 9.3e-4 (and 7 of 4,800 elements = 1.5e-3 in one 600-vertex case);
+# at full size 7.8e-4 on configs[2] and 1.5e-5 on configs[4].
+FLIP_SHARE = 2e-3
+
+
+def _note_flip_share(level, share, count, size):
+    """One line per level with differing ReLU decisions into gpurun_out/ (what the bound above is judged by)."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    try:
+        os.makedirs(os.path.join(root, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(root, "gpurun_out", "flip_shares.log"), "a") as f:
+            f.write(f"{share:.3e} {count} of {size} level {level} {os.environ.get('PYTEST_CURRENT_TEST', '')}\n")
+    except OSError:
+        pass
+
+
 def _gpu(p, **kw):
     from gpu_harness import GpuRun
     return GpuRun(p, **kw)
@@ -27,14 +46,16 @@ def _gpu(p, **kw):
 def _check_forward(run, ref, p, tol):
     """Levels within tolerance; ReLU on/off decisions may differ only at near-ties: the side that is
     non-zero holds a value no larger than the tolerance itself (tol * max).  How many elements sit that
-    close to zero is a property of the data, so the share of such flips is only sanity-bounded (1%)."""
+    close to zero is a property of the data; the share of such elements is bounded by FLIP_SHARE (measured
+    values beside its definition)."""
     worst = {}
     for j in range(1, p.L + 1):
         a, b = run.np(run.cur[j]), ref.cur[j]
         worst[f"level{j}"] = max_rel(a, b)
         flips = (a > 0) != (b > 0)
         if flips.any():
-            assert flips.mean() <= 1e-2, (j, flips.sum())
+            _note_flip_share(j, float(flips.mean()), int(flips.sum()), a.size)
+            assert flips.mean() <= FLIP_SHARE, (j, flips.sum())
             assert np.maximum(np.abs(a[flips]), np.abs(b[flips])).max() <= tol * np.abs(b).max(), j
     bad = {k: v for k, v in worst.items() if not (v <= tol)}
     assert not bad, f"over tolerance {tol}: {bad} (all: {worst})"
@@ -75,6 +96,54 @@ def _compare(run, ref, p, tol, need_input_grad=True):
     bad = {k: v for k, v in worst.items() if not (v <= tol)}
     assert not bad, f"over tolerance {tol}: {bad} (all: {worst})"
     return worst
+
+
+@pytest.mark.parametrize("name", ["c1_s", "c2_s", "c3_s", "c4_s"])
+def test_bf16_backward_on_the_gpus_own_levels(name):
+    """The one comparison in which nothing is forced: the GPU's backward pass runs on the levels and saved
+    aggregations of its OWN forward pass, and every gradient is compared with the oracle's own pass.
+
+    Beyond the arithmetic of the two sides (1e-2, as everywhere) the two passes now differ in ReLU decisions:
+    where a pre-activation lies within rounding distance of zero (|y| <= 1e-2 max|y|, checked by the forward
+    comparison) one side passes the upstream gradient of that element and the other replaces it by zero.  If a
+    share s of a layer's elements is decided differently, dY of that layer differs by about sqrt(s) of its
+    Frobenius norm; everything below that layer is linear in dY once the masks are fixed, so the relative errors
+    of the L layers add at most.  Hence the bound on the relative Frobenius error of every gradient:
+        1e-2 + L * sqrt(s),   s = largest share of differing decisions over the levels (measured in the test).
+    Measured (error / bound): c1_s 0.083 / 0.116, c2_s 0.176 / 0.233, c3_s 0.0037 / 0.045, c4_s 0.013 / 0.039.
+    The max-norm used elsewhere is not bounded here: one flipped element moves single gradient rows by their
+    full size (c3_s: about 100 flipped elements in 2 * 10^7 put max|x - ref| / max|ref| of grad_in at 0.24)."""
+    p = make_problem(CONFIGS[name], bias_std=0.05)
+    ref = run_oracle(p)
+    run = _gpu(p)
+    run.forward()
+    torch.cuda.synchronize()
+    _check_forward(run, ref, p, TOL_BF16)
+    share = max(float(((run.np(run.cur[j]) > 0) != (ref.cur[j] > 0)).mean()) for j in range(1, p.L + 1))
+    assert share <= 2e-3, share
+    run.backward()
+    torch.cuda.synchronize()
+    def fro(x, r):
+        r = np.asarray(r, dtype=np.float64)
+        return float(np.linalg.norm(np.asarray(x, dtype=np.float64) - r) / max(np.linalg.norm(r), 1e-300))
+
+    worst = {}
+    for j in range(p.L):
+        worst[f"dW{j}"] = fro(run.np(run.dW[j]), ref.dW[j])
+        if p.w.variant == "gcn":
+            worst[f"db{j}"] = fro(run.np(run.dbias[j]), ref.db[j])
+    worst["grad_in"] = fro(run.np(run.grad_in), ref.grad_in)
+    if p.w.variant == "gcnii":
+        worst["grad_h0"] = fro(run.np(run.grad_h0), ref.dH0)
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    try:
+        with open(os.path.join(root, "gpurun_out", "unforced.log"), "a") as f:
+            f.write(f"{name} flip share {share:.2e} worst {max(worst.values()):.3e} {worst}\n")
+    except OSError:
+        pass
+    bound = TOL_BF16 + p.L * math.sqrt(share)
+    bad = {k: v for k, v in worst.items() if not (v <= bound)}
+    assert not bad, f"over {bound}: {bad} (all: {worst})"
 
 
 def small(n=700, k=5, dims=(24, 40, 16, 32), variant="gcn", dtype="f32", seed=5, deg=6.0, level0_f32=False):

@@ -10,6 +10,7 @@
   +   normalisation closed forms / eigenvector invariant, transposed index round trip,
       select counts by brute force, bf16 rounding against torch, update_history.
 """
+import math
 import os
 
 import numpy as np
@@ -405,6 +406,39 @@ def test_resgcn_parameter_gradients_do_not_depend_on_asking_for_the_input_gradie
     c = run_oracle(p)
     assert np.array_equal(c.cur[p.L], p.x0)
     assert np.abs(c.grad_in - p.grad_out).max() <= 1e-6 * np.abs(p.grad_out).max()
+
+
+@pytest.mark.parametrize("f64", [False, True])
+def test_the_c_oracles_splitmix64_and_keep_rule_against_the_published_vector(f64):
+    """The dropout decisions of the C oracle come from its own copy of SplitMix64's output function.  Pinned to
+    the test vector published with the reference implementation (seed 1234567: the state advances by the golden
+    gamma, the outputs are the file's values), and the keep rule is pinned to its definition written out with
+    Python integers: key_j = out(seed + (j + 1) G), draw = out(key_j + (u d + c + 1) G), keep iff the draw's top
+    24 bits reach ceil(p 2^24).  A mistyped mixing constant or shift, a wrong counter or threshold fails here."""
+    from oracle.stage import _lib, splitmix64_c
+    golden = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "splitmix64_seed1234567.txt")
+    want = [int(x) for x in open(golden).read().split("\n") if x and not x.startswith("#")]
+    G, M = 0x9E3779B97F4A7C15, (1 << 64) - 1
+    got = [splitmix64_c((1234567 + (i + 1) * G) & M, f64=f64) for i in range(len(want))]
+    assert got == want
+
+    def out(z):  # the published output function, in Python integers
+        z &= M
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & M
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & M
+        return z ^ (z >> 31)
+
+    assert [out(1234567 + (i + 1) * G) for i in range(len(want))] == want   # the definition above is the published one
+    lib = _lib(f64)
+    rng = np.random.default_rng(3)
+    for seed, p in ((7, 0.5), (2**63 + 12345, 0.3), (0, 0.9), (M, 0.125)):
+        thr = math.ceil(p * (1 << 24))
+        for _ in range(200):
+            j, u, d = int(rng.integers(0, 40)), int(rng.integers(0, 10**7)), int(rng.integers(1, 1025))
+            c = int(rng.integers(0, d))
+            key = out(seed + (j + 1) * G)
+            keep = (out(key + (u * d + c + 1) * G) >> 40) >= thr
+            assert bool(lib.oracle_dropout_keep(seed, j, u, d, c, p)) == keep, (seed, p, j, u, d, c)
 
 
 def test_resgcn_dropout():
