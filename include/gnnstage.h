@@ -331,13 +331,15 @@ int gnnstage_profile_reset(gnnstage_t *st);
  * line reads one embedding row per neighbour), with no arithmetic and no index traffic around it.  Every 16-lane
  * group reads whole rows of row_bytes (a multiple of 256, at most 4096) at pseudo-random row numbers, eight rows in
  * flight per group, 2048 workgroups; a share hot_share of the draws goes to rows [0, hot_rows), the rest is uniform
- * over the n_rows rows of the table.  One warm-up launch, then n_launches timed with HIP events on hip_stream;
+ * over the n_rows rows of the table.  mode 0: plain loads, hot rows are the first rows of the table; 1: the same with
+ * non-temporal loads; 2: plain loads, the hot rows spread evenly over the table (the case of a graph whose hubs
+ * carry arbitrary ids).  One warm-up launch, then n_launches timed with HIP events on hip_stream;
  * synchronises.  table: DEVICE, n_rows * row_bytes bytes, 16-byte aligned; sink: DEVICE, 4 bytes.
  * bytes_per_second (HOST) receives gathered bytes per second.  Returns 0, GNNSTAGE_EINVAL or GNNSTAGE_EHIP.
  */
 int gnnstage_debug_gather_rate(const void *table, int64_t n_rows, int32_t row_bytes, int64_t gathers_per_launch,
-                               int32_t n_launches, int64_t hot_rows, double hot_share, uint32_t seed, void *sink,
-                               void *hip_stream, double *bytes_per_second);
+                               int32_t n_launches, int64_t hot_rows, double hot_share, int32_t mode, uint32_t seed,
+                               void *sink, void *hip_stream, double *bytes_per_second);
 
 /* Library version, e.g. 100 = 0.1.0 */
 int gnnstage_version(void);

@@ -157,7 +157,7 @@ def _load():
     lib.gnntrain_sum.argtypes = [C.c_void_p, C.c_int64, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.gnnstage_debug_gather_rate.restype = C.c_int
     lib.gnnstage_debug_gather_rate.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int64, C.c_int32, C.c_int64, C.c_double,
-                                               C.c_uint32, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
+                                               C.c_int32, C.c_uint32, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
     lib.gnntrain_sum_static.restype = C.c_int
     lib.gnntrain_sum_static.argtypes = [C.c_void_p, C.c_int64, C.c_float, C.c_void_p, C.c_void_p]
     lib.gnntrain_adam_step.restype = C.c_int
@@ -239,14 +239,14 @@ def gnnstage_plan_tasks(ptr: np.ndarray, row_begin: int, row_end: int, split_edg
 
 
 def gnnstage_debug_gather_rate(table, n_rows: int, row_bytes: int, gathers_per_launch: int, n_launches: int = 3,
-                               hot_rows: int = 0, hot_share: float = 0.0, seed: int = 1) -> float:
+                               hot_rows: int = 0, hot_share: float = 0.0, mode: int = 0, seed: int = 1) -> float:
     """Gathered bytes per second of random whole-row reads from ``table`` (a device tensor of at least
     n_rows * row_bytes bytes); see include/gnnstage.h."""
     import torch
     sink = torch.zeros(1, dtype=torch.int32, device=table.device)
     out = C.c_double(0.0)
     rc = lib.gnnstage_debug_gather_rate(table.data_ptr(), int(n_rows), int(row_bytes), int(gathers_per_launch), int(n_launches),
-                                        int(hot_rows), float(hot_share), int(seed) & 0xffffffff, sink.data_ptr(),
+                                        int(hot_rows), float(hot_share), int(mode), int(seed) & 0xffffffff, sink.data_ptr(),
                                         C.c_void_p(torch.cuda.current_stream().cuda_stream), C.byref(out))
     if rc != 0:
         raise GnnStageError(rc, "gnnstage_debug_gather_rate")

@@ -1,8 +1,6 @@
 // Small kernels around the two hot operations: weight staging, the ReLU-derivative mask on
 // the upstream gradient, the history copy (Section 3.4, second technique), zero fill, and the
 // symmetric normalisation weights of Section 2.1.
-#include <stdlib.h>
-
 #include <algorithm>
 
 #include "common.h"
@@ -226,11 +224,11 @@ __global__ __launch_bounds__(256) void gather_probe_kernel(const u32x4 *table, u
 // Times n_launches launches of the probe on `stream` with HIP events and reports bytes gathered per second.
 // table: DEVICE, n_rows rows of row_bytes (a multiple of 256, at most 4096); sink: DEVICE, 4 bytes.
 extern "C" int gnnstage_debug_gather_rate(const void *table, int64_t n_rows, int32_t row_bytes, int64_t gathers_per_launch,
-                                          int32_t n_launches, int64_t hot_rows, double hot_share, uint32_t seed, void *sink,
-                                          void *hip_stream, double *bytes_per_second) {
+                                          int32_t n_launches, int64_t hot_rows, double hot_share, int32_t mode, uint32_t seed,
+                                          void *sink, void *hip_stream, double *bytes_per_second) {
   if (!table || !sink || !bytes_per_second || n_rows < 1 || n_rows > 0xffffffffll || row_bytes < 256 || row_bytes > 4096 ||
       row_bytes % 256 != 0 || gathers_per_launch < 1 || n_launches < 1 || hot_rows < 0 || hot_rows > n_rows ||
-      !(hot_share >= 0.0 && hot_share <= 1.0) || (hot_share > 0.0 && hot_rows < 1))
+      !(hot_share >= 0.0 && hot_share <= 1.0) || (hot_share > 0.0 && hot_rows < 1) || mode < 0 || mode > 2)
     return -1;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int blocks = 256 * 8;  // eight workgroups of four waves per compute unit: full occupancy
@@ -242,15 +240,15 @@ extern "C" int gnnstage_debug_gather_rate(const void *table, int64_t n_rows, int
   hipEvent_t a = nullptr, b = nullptr;
   if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return -5;
   auto launch = [&](uint32_t sd) {
-    if (getenv("GNNSTAGE_PROBE_SCATTER"))
-      hipLaunchKernelGGL(gather_probe_kernel<2>, dim3(blocks), dim3(256), 0, s, static_cast<const u32x4 *>(table), (uint32_t)n_rows,
-                         row_bytes / 16, (int)per_group, (uint32_t)std::max<int64_t>(hot_rows, 1), thr, sd, static_cast<uint32_t *>(sink));
-    else if (getenv("GNNSTAGE_PROBE_NT"))
-      hipLaunchKernelGGL(gather_probe_kernel<1>, dim3(blocks), dim3(256), 0, s, static_cast<const u32x4 *>(table), (uint32_t)n_rows,
-                         row_bytes / 16, (int)per_group, (uint32_t)std::max<int64_t>(hot_rows, 1), thr, sd, static_cast<uint32_t *>(sink));
+    const u32x4 *t = static_cast<const u32x4 *>(table);
+    const uint32_t hr = (uint32_t)std::max<int64_t>(hot_rows, 1);
+    uint32_t *sk = static_cast<uint32_t *>(sink);
+    if (mode == 2)
+      hipLaunchKernelGGL(gather_probe_kernel<2>, dim3(blocks), dim3(256), 0, s, t, (uint32_t)n_rows, row_bytes / 16, (int)per_group, hr, thr, sd, sk);
+    else if (mode == 1)
+      hipLaunchKernelGGL(gather_probe_kernel<1>, dim3(blocks), dim3(256), 0, s, t, (uint32_t)n_rows, row_bytes / 16, (int)per_group, hr, thr, sd, sk);
     else
-    hipLaunchKernelGGL(gather_probe_kernel<0>, dim3(blocks), dim3(256), 0, s, static_cast<const u32x4 *>(table), (uint32_t)n_rows,
-                       row_bytes / 16, (int)per_group, (uint32_t)std::max<int64_t>(hot_rows, 1), thr, sd, static_cast<uint32_t *>(sink));
+      hipLaunchKernelGGL(gather_probe_kernel<0>, dim3(blocks), dim3(256), 0, s, t, (uint32_t)n_rows, row_bytes / 16, (int)per_group, hr, thr, sd, sk);
   };
   launch(seed);  // warm-up
   (void)hipEventRecord(a, s);
