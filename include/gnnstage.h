@@ -341,6 +341,12 @@ int gnnstage_debug_gather_rate(const void *table, int64_t n_rows, int32_t row_by
                                int32_t n_launches, int64_t hot_rows, double hot_share, int32_t mode, uint32_t seed,
                                void *sink, void *hip_stream, double *bytes_per_second);
 
+/* Diagnostic (host only, launches nothing): 1 when the dense-block launcher refuses a launch whose operand `missing` is
+ * absent (0 zero row, 1 column slots, 2 selected source table, 3 partial tiles, 4 column scales / weight tiles,
+ * 5 row scales; pattern_blocks != 0: blocks kept as bit patterns, else as weight tiles), 0 when it would launch,
+ * -1 for an operand that the block kind does not have.  The kernel reads every operand without a test of its own. */
+int gnnstage_debug_dense_rejects(int32_t missing, int32_t pattern_blocks);
+
 /* Library version, e.g. 100 = 0.1.0 */
 int gnnstage_version(void);
 

@@ -346,6 +346,38 @@ int launch_spmm_dense(const DenseArgs &a, hipStream_t s) {
   return (int)hipGetLastError();
 }
 
+// Diagnostic for CPU tests of the check above: 1 when the launcher refuses a launch whose operand `missing` is absent
+// (0 zero row, 1 column slots, 2 selected source table, 3 partial tiles, 4 column scales (pattern blocks) or weight
+// tiles, 5 row scales (pattern blocks only)), 0 when it would launch, -1 for an unknown operand.  Nothing is launched:
+// the other operands are placeholder addresses that a refused launch never reads.
+extern "C" int gnnstage_debug_dense_rejects(int32_t missing, int32_t pattern_blocks) {
+  if (missing < 0 || missing > 5 || (missing == 5 && !pattern_blocks)) return -1;
+  static char placeholder[16];
+  DenseArgs a{};
+  a.n_items = 1;
+  a.d = 128;
+  a.zero_row = placeholder;
+  a.colslot = reinterpret_cast<const uint32_t *>(placeholder);
+  a.src_sel = placeholder;
+  a.partial = reinterpret_cast<float *>(placeholder);
+  if (pattern_blocks) {
+    a.bits = reinterpret_cast<const uint32_t *>(placeholder);
+    a.colscale = reinterpret_cast<const float *>(placeholder);
+    a.rowscale = reinterpret_cast<const float *>(placeholder);
+  } else {
+    a.tiles = reinterpret_cast<const bf16_t *>(placeholder);
+  }
+  switch (missing) {
+    case 0: a.zero_row = nullptr; break;
+    case 1: a.colslot = nullptr; break;
+    case 2: a.src_sel = nullptr; break;
+    case 3: a.partial = nullptr; break;
+    case 4: if (pattern_blocks) a.colscale = nullptr; else a.tiles = nullptr; break;
+    default: a.rowscale = nullptr; break;
+  }
+  return launch_spmm_dense(a, nullptr) == (int)hipErrorInvalidValue ? 1 : 0;
+}
+
 int launch_dense_expand(const int64_t *blk_e0, const uint16_t *ent_pos, const uint32_t *ent_w, void *tiles, int64_t n_blocks,
                         hipStream_t s) {
   if (n_blocks <= 0) return hipSuccess;

@@ -40,6 +40,18 @@ def test_library_exports_every_declared_symbol():
     assert g.gnnstage_version() >= 100
 
 
+def test_dense_block_launcher_refuses_a_launch_with_a_missing_operand():
+    """The dense-block kernel reads all of its operand tables without a test of its own (a null table is a memory
+    fault on the device), so the launcher must refuse - on the host, before anything is launched."""
+    g = _lib()
+    g.lib.gnnstage_debug_dense_rejects.restype = C.c_int
+    g.lib.gnnstage_debug_dense_rejects.argtypes = [C.c_int32, C.c_int32]
+    for pattern in (0, 1):
+        for missing in range(6 if pattern else 5):
+            assert g.lib.gnnstage_debug_dense_rejects(missing, pattern) == 1, (missing, pattern)
+    assert g.lib.gnnstage_debug_dense_rejects(5, 0) == -1 and g.lib.gnnstage_debug_dense_rejects(9, 1) == -1
+
+
 def test_chunk_order_matches_the_oracle_bit_for_bit():
     """Section 3.4, technique 1: the library's host-side shuffle and the oracle's draw the same orders."""
     from oracle.train import chunk_order
