@@ -333,7 +333,7 @@ int gnnstage_profile_reset(gnnstage_t *st);
  * flight per group, 2048 workgroups; a share hot_share of the draws goes to rows [0, hot_rows), the rest is uniform
  * over the n_rows rows of the table.  mode 0: plain loads, hot rows are the first rows of the table; 1: the same with
  * non-temporal loads; 2: plain loads, the hot rows spread evenly over the table (the case of a graph whose hubs
- * carry arbitrary ids).  One warm-up launch, then n_launches timed with HIP events on hip_stream;
+ * carry arbitrary ids); 3: non-temporal loads for the draws outside the hot rows only.  One warm-up launch, then n_launches timed with HIP events on hip_stream;
  * synchronises.  table: DEVICE, n_rows * row_bytes bytes, 16-byte aligned; sink: DEVICE, 4 bytes.
  * bytes_per_second (HOST) receives gathered bytes per second.  Returns 0, GNNSTAGE_EINVAL or GNNSTAGE_EHIP.
  */

@@ -192,7 +192,7 @@ __device__ inline uint32_t mix32(uint32_t x) {
   return x ^ (x >> 16);
 }
 
-template <int MODE>  // 0: plain loads, 1: non-temporal loads, 2: plain loads, hot rows scattered
+template <int MODE>  // 0: plain loads, 1: non-temporal loads, 2: plain loads, hot rows scattered, 3: non-temporal loads for the cold draws only
 __global__ __launch_bounds__(256) void gather_probe_kernel(const u32x4 *table, uint32_t n_rows, int row_vecs, int rows_per_group,
                                                            uint32_t hot_rows, uint32_t hot_threshold, uint32_t seed, uint32_t *sink) {
   const uint32_t group = (blockIdx.x * 256u + threadIdx.x) >> 4;
@@ -207,9 +207,10 @@ __global__ __launch_bounds__(256) void gather_probe_kernel(const u32x4 *table, u
       uint32_t row = (pick < hot_threshold) ? h % hot_rows : h % n_rows;
       if (MODE == 2 && pick < hot_threshold) row *= n_rows / hot_rows;  // the hot rows spread evenly over the table
       const u32x4 *p = table + (size_t)row * row_vecs + lig;
-      x[u] = MODE == 1 ? __builtin_nontemporal_load(p) : p[0];
+      const bool nt = MODE == 1 || (MODE == 3 && pick >= hot_threshold);
+      x[u] = nt ? __builtin_nontemporal_load(p) : p[0];
       for (int v = 16; v < row_vecs; v += 16) {
-        const u32x4 y = MODE == 1 ? __builtin_nontemporal_load(p + v) : p[v];
+        const u32x4 y = nt ? __builtin_nontemporal_load(p + v) : p[v];
         x[u] ^= y;
       }
     }
@@ -228,7 +229,7 @@ extern "C" int gnnstage_debug_gather_rate(const void *table, int64_t n_rows, int
                                           void *sink, void *hip_stream, double *bytes_per_second) {
   if (!table || !sink || !bytes_per_second || n_rows < 1 || n_rows > 0xffffffffll || row_bytes < 256 || row_bytes > 4096 ||
       row_bytes % 256 != 0 || gathers_per_launch < 1 || n_launches < 1 || hot_rows < 0 || hot_rows > n_rows ||
-      !(hot_share >= 0.0 && hot_share <= 1.0) || (hot_share > 0.0 && hot_rows < 1) || mode < 0 || mode > 2)
+      !(hot_share >= 0.0 && hot_share <= 1.0) || (hot_share > 0.0 && hot_rows < 1) || mode < 0 || mode > 3)
     return -1;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int blocks = 256 * 8;  // eight workgroups of four waves per compute unit: full occupancy
@@ -243,7 +244,9 @@ extern "C" int gnnstage_debug_gather_rate(const void *table, int64_t n_rows, int
     const u32x4 *t = static_cast<const u32x4 *>(table);
     const uint32_t hr = (uint32_t)std::max<int64_t>(hot_rows, 1);
     uint32_t *sk = static_cast<uint32_t *>(sink);
-    if (mode == 2)
+    if (mode == 3)
+      hipLaunchKernelGGL(gather_probe_kernel<3>, dim3(blocks), dim3(256), 0, s, t, (uint32_t)n_rows, row_bytes / 16, (int)per_group, hr, thr, sd, sk);
+    else if (mode == 2)
       hipLaunchKernelGGL(gather_probe_kernel<2>, dim3(blocks), dim3(256), 0, s, t, (uint32_t)n_rows, row_bytes / 16, (int)per_group, hr, thr, sd, sk);
     else if (mode == 1)
       hipLaunchKernelGGL(gather_probe_kernel<1>, dim3(blocks), dim3(256), 0, s, t, (uint32_t)n_rows, row_bytes / 16, (int)per_group, hr, thr, sd, sk);
