@@ -238,6 +238,8 @@ struct GemmTnArgs {
   int32_t max_splits;
   float *dbias;         // optional (bf16 product only): dbias[o] += column sums of B, fused into the product
   float *bias_partial;  // fp32 scratch [splits][O]
+  int32_t wide_min_rows = 65536;  // bf16 operands from this many rows on, with more than one 128 x 128 output tile: one
+                                  // workgroup per row split computes the whole output (tests force it on small inputs)
 };
 int launch_gemm_tn(const GemmTnArgs &a, int compute_dtype, hipStream_t s);
 // dst[o] += sum over the M rows of B[.][o]; partial: fp32 scratch [max_splits][O]

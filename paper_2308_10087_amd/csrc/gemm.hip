@@ -630,6 +630,120 @@ __global__ __launch_bounds__(256) void gemm_tn_bf16_kernel(const GemmTnArgs a, i
       }
 }
 
+// The same product for long operands of up to 256 x 256 outputs (one weight-gradient product per layer over all rows
+// of a pass): ONE workgroup of eight waves owns a row split and the whole I x O output, so every operand row is read
+// from memory once.  With 128 x 128 tiles the four tiles of a split each stream half of both operands and share them
+// only in part through their XCD's L2 (measured on 10 M rows: 16.1 GB fetched for 10.2 GB of operands).  A wave owns
+// 64 rows x 128 columns of the output (eight 32 x 32 accumulators); both operands are bf16 with 16-byte aligned rows.
+constexpr int LDS_PW = 260;  // padded stride, in words, of one row pair of a 256-column LDS tile
+__global__ __launch_bounds__(512) void gemm_tn_bf16_wide_kernel(const GemmTnArgs a, int rows_per_split, int splits) {
+  __shared__ __attribute__((aligned(16))) uint32_t As[TR / 2 * LDS_PW];
+  __shared__ __attribute__((aligned(16))) uint32_t Bs[TR / 2 * LDS_PW];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int split = blockIdx.x;
+  if (split >= splits) return;
+  const int wi = (wave >> 1) * 64, wo = (wave & 1) * 128;
+  const int r_begin = split * rows_per_split;
+  const int r_end = min(a.M, r_begin + rows_per_split);
+  const bf16_t *A = static_cast<const bf16_t *>(a.A);
+  const bf16_t *B = static_cast<const bf16_t *>(a.B);
+  const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int t = 0; t < 16; ++t) acc[i][j][t] = 0.f;
+  // bias gradient on the side: every thread adds up the B rows it stages (its 8 columns, 4 rows per tile); the 16
+  // threads that share a column group are added in a fixed order at the end.  (The all-ones matrix product of the
+  // 128 x 128 kernel would cost 64 more accumulator registers here.)
+  const bool do_bias = a.bias_partial != nullptr;
+  float bsum[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) bsum[t] = 0.f;
+  constexpr int NVT = TR * 32 / 512;  // 16-byte vectors per thread and operand tile
+  bf16x8 ra[NVT], rb[NVT];
+  const int c = (tid & 31) * 8;
+  auto gload = [&](int r0) {
+#pragma unroll
+    for (int i = 0; i < NVT; ++i) {
+      const int r = 2 * ((tid >> 5) + 16 * (i >> 1)) + (i & 1);  // slots 2h, 2h+1: one row pair
+      const bool rv = r0 + r < r_end;
+      ra[i] = (rv && c < a.lda) ? *reinterpret_cast<const bf16x8 *>(A + (size_t)(r0 + r) * a.lda + c) : zero8;
+      rb[i] = (rv && c < a.ldb) ? *reinterpret_cast<const bf16x8 *>(B + (size_t)(r0 + r) * a.ldb + c) : zero8;
+    }
+  };
+  if (r_begin < r_end) gload(r_begin);
+  for (int r0 = r_begin; r0 < r_end; r0 += TR) {
+    __syncthreads();  // previous step's fragment reads are done
+#pragma unroll
+    for (int h = 0; h < NVT / 2; ++h) {
+      const int p = (tid >> 5) + 16 * h;
+      store_row_pair(&As[p * LDS_PW + c], ra[2 * h], ra[2 * h + 1]);
+      store_row_pair(&Bs[p * LDS_PW + c], rb[2 * h], rb[2 * h + 1]);
+    }
+    if (do_bias) {
+#pragma unroll
+      for (int i = 0; i < NVT; ++i)
+#pragma unroll
+        for (int t = 0; t < 8; ++t) bsum[t] += (float)rb[i][t];
+    }
+    __syncthreads();
+    if (r0 + TR < r_end) gload(r0 + TR);  // next tile's loads fly while this one is multiplied
+#pragma unroll
+    for (int kk = 0; kk < TR / 16; ++kk) {
+      const int poff = kk * 8 + (lane >> 5) * 4;  // first of the fragment's four row pairs
+      bf16x8 fa[2], fb[4];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        u32x4 w;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) w[t] = As[(poff + t) * LDS_PW + wi + i * 32 + (lane & 31)];
+        fa[i] = __builtin_bit_cast(bf16x8, w);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        u32x4 w;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) w[t] = Bs[(poff + t) * LDS_PW + wo + j * 32 + (lane & 31)];
+        fb[j] = __builtin_bit_cast(bf16x8, w);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+  }
+  if (do_bias) {
+    __syncthreads();  // the operand tiles are done with; As is reused for the threads' column sums
+    float *cs = reinterpret_cast<float *>(As);
+    static_assert(512 * 8 * sizeof(float) <= sizeof(As), "the column sums must fit the A tile");
+#pragma unroll
+    for (int t = 0; t < 8; ++t) cs[tid * 8 + t] = bsum[t];
+    __syncthreads();
+    if (tid < 256 && tid < a.O) {  // column tid: the threads (g * 32 + tid / 8), g = 0 .. 15, element tid % 8
+      float sum = 0.f;
+#pragma unroll
+      for (int g = 0; g < 16; ++g) sum += cs[(g * 32 + (tid >> 3)) * 8 + (tid & 7)];
+      a.bias_partial[(size_t)split * a.O + tid] = sum;
+    }
+  }
+  float *P = a.partial + (size_t)split * a.I * a.O;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int t = 0; t < 16; ++t) {
+        const int ii = wi + i * 32 + 8 * (t >> 2) + 4 * (lane >> 5) + (t & 3);
+        const int oo = wo + j * 32 + (lane & 31);
+        if (ii < a.I && oo < a.O) P[(size_t)ii * a.O + oo] = acc[i][j][t];
+      }
+}
+
 // ------------------------------------------------------------------------------------ fp32 NT
 template <bool VEC>
 __global__ __launch_bounds__(256) void gemm_nt_f32_kernel(const GemmNtArgs a) {
@@ -904,7 +1018,16 @@ int launch_gemm_tn(const GemmTnArgs &a, int compute_dtype, hipStream_t s) {
   rows_per = (rows_per + step - 1) / step * step;
   splits = (a.M + rows_per - 1) / rows_per;
   dim3 grid(ti, to, splits);
-  if (compute_dtype == DT_BF16) {
+  // long operands with more than one 128 x 128 output tile: one workgroup per row split computes all of the output
+  const bool wide = compute_dtype == DT_BF16 && a.a_dtype == DT_BF16 && a.M >= a.wide_min_rows && ti * to > 1 && a.I <= 256 &&
+                    a.O <= 256 && vec_ok(a.A, a.lda, 8) && vec_ok(a.B, a.ldb, 8);
+  if (wide) {
+    splits = a.max_splits < 256 ? a.max_splits : 256;  // one workgroup per compute unit
+    rows_per = (a.M + splits - 1) / splits;
+    rows_per = (rows_per + step - 1) / step * step;
+    splits = (a.M + rows_per - 1) / rows_per;
+    hipLaunchKernelGGL(gemm_tn_bf16_wide_kernel, dim3((unsigned)splits), dim3(512), 0, s, a, rows_per, splits);
+  } else if (compute_dtype == DT_BF16) {
     dim3 g1((unsigned)(((splits + 7) / 8) * 8 * ti * to));
     if (a.a_dtype == DT_F32 && pair_ok(a.A, a.lda))
       hipLaunchKernelGGL((gemm_tn_bf16_kernel<float, false, true>), g1, dim3(256), 0, s, a, rows_per, splits);

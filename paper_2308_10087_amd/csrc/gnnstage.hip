@@ -35,6 +35,7 @@ std::string g_create_error;
 //   GNNSTAGE_SPMM_VALU                vector-ALU aggregation for bf16 rows too
 //   GNNSTAGE_SPMM_UNROLL (2, 4, 8)    gather slots per wave of the matrix-core aggregation
 //   GNNSTAGE_GEMM_WS_MIN_ROWS         rows from which the weight-stationary product is used
+//   GNNSTAGE_GEMM_WIDE_MIN_ROWS       rows from which a weight-gradient product of up to 256 x 256 outputs is one workgroup per split
 //   GNNSTAGE_WGRAD_DEFER=0            weight gradients per chunk instead of one product per layer at the end of the pass
 //   GNNSTAGE_HOT_CLASSES (0 = off, 2..32: on whatever the table size)   classes of the hottest sources
 //   GNNSTAGE_HOT_ROWS                 sources per such class
@@ -52,6 +53,7 @@ struct Tuning {
   bool spmm_valu = false;
   int spmm_unroll = 2;          // two slots leave room for eight waves per SIMD, which measured best on every workload
   int gemm_ws_min_rows = 65536;
+  int gemm_wide_min_rows = 65536;  // weight-gradient products from this many rows on read each operand once (one workgroup per split)
   bool wgrad_defer = true;
   int hot_classes = -1;         // -1: 16 for gathered tables beyond 256 MB, none below
   int hot_rows = 0;             // 0: as many rows as fit an XCD's 4 MB L2
@@ -75,6 +77,7 @@ Tuning read_tuning() {
   if (getenv("GNNSTAGE_SPMM_VALU")) t.spmm_valu = true;
   if ((e = getenv("GNNSTAGE_SPMM_UNROLL"))) t.spmm_unroll = atoi(e);
   if ((e = getenv("GNNSTAGE_GEMM_WS_MIN_ROWS"))) t.gemm_ws_min_rows = atoi(e);
+  if ((e = getenv("GNNSTAGE_GEMM_WIDE_MIN_ROWS"))) t.gemm_wide_min_rows = atoi(e);
   if ((e = getenv("GNNSTAGE_WGRAD_DEFER")) && atoi(e) == 0) t.wgrad_defer = false;
   if ((e = getenv("GNNSTAGE_HOT_CLASSES")) && atoi(e) >= 0 && atoi(e) <= kMaxClasses) t.hot_classes = atoi(e);
   if ((e = getenv("GNNSTAGE_HOT_ROWS")) && atoi(e) >= 1) t.hot_rows = atoi(e);
@@ -942,6 +945,7 @@ int finish_transform_first(gnnstage *st, hipStream_t stream) {
       HIP_TRY(st, run_spmm(st, a, true, c, cd, cd, stream, 2, j));
       Timed t(st, stream, 4, j);
       GemmTnArgs w{};
+      w.wide_min_rows = st->s.tune.gemm_wide_min_rows;
       w.A = static_cast<const char *>(st->hist[j]) + (size_t)row0 * s.dims[j] * st->level_elt(j);
       w.a_dtype = st->level_dtype(j);
       w.lda = s.dims[j];
@@ -1092,6 +1096,7 @@ int res_backward_chunk(gnnstage *st, int k, const void *grad_out_rows, hipStream
     {
       Timed t(st, stream, 4, j);
       GemmTnArgs w{};
+      w.wide_min_rows = st->s.tune.gemm_wide_min_rows;
       w.A = st->at<char>(st->lay.Z[j]) + (size_t)row0 * s.ld[j] * celt;
       w.a_dtype = cd;
       w.lda = s.ld[j];
@@ -1842,6 +1847,7 @@ int flush_deferred_wgrad(gnnstage *st, hipStream_t stream) {
       if (s.has_bias() && !fuse_bias)
         HIP_TRY(st, launch_colsum_add(dY, cd, s.ld[j + 1], (int)M, s.dims[j + 1], bias_partial, kMaxSplits, st->dbias[j], stream));
       GemmTnArgs w{};
+      w.wide_min_rows = st->s.tune.gemm_wide_min_rows;
       w.A = st->at<char>(st->lay.Z[j]) + (size_t)r0 * s.ld[j] * celt;
       w.a_dtype = cd;
       w.lda = s.ld[j];
@@ -1861,6 +1867,7 @@ int flush_deferred_wgrad(gnnstage *st, hipStream_t stream) {
       HIP_TRY(st, launch_gemm_tn(w, cd, stream));
       if (s.sage()) {  // dW_self += h_v^T dY over the rows' own (current) level-j values
         GemmTnArgs ws{};
+        ws.wide_min_rows = st->s.tune.gemm_wide_min_rows;
         ws.A = static_cast<const char *>(st->cur[j]) + (size_t)r0 * s.dims[j] * st->level_elt(j);
         ws.a_dtype = st->level_dtype(j);
         ws.lda = s.dims[j];
@@ -1969,6 +1976,7 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
       if (!shared) {
         Timed t(st, stream, 4, j);
         GemmTnArgs w{};
+        w.wide_min_rows = st->s.tune.gemm_wide_min_rows;
         w.a_dtype = st->level_dtype(j);
         w.lda = s.dims[j];
         w.B = dT;
@@ -2024,6 +2032,7 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
       const char *Zrows = st->at<char>(st->lay.Z[j]) + (size_t)row0 * s.ld[j] * celt;
       Timed t(st, stream, 4, j);
       GemmTnArgs w{};
+      w.wide_min_rows = st->s.tune.gemm_wide_min_rows;
       w.A = Zrows;
       w.a_dtype = cd;
       w.lda = s.ld[j];
@@ -2043,6 +2052,7 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
       HIP_TRY(st, launch_gemm_tn(w, cd, stream));
       if (s.sage()) {  // dW_self += h_v^T dY over the chunk's own (current) rows
         GemmTnArgs ws{};
+        ws.wide_min_rows = st->s.tune.gemm_wide_min_rows;
         ws.A = static_cast<const char *>(st->cur[j]) + (size_t)row0 * s.dims[j] * st->level_elt(j);
         ws.a_dtype = st->level_dtype(j);
         ws.lda = s.dims[j];

@@ -405,6 +405,22 @@ def test_dense_blocks_switched_off_give_the_same_levels(monkeypatch):
         assert max_rel(a.np(a.cur[j]), b.np(b.cur[j])) <= 1e-2
 
 
+@pytest.mark.parametrize("defer", ["1", "0"])
+@pytest.mark.parametrize("name,dims", [("c1_s", None), ("c3_s", None), ("c4_s", None), ("c4_s", (200, 256, 136, 256))])
+def test_one_workgroup_per_split_weight_gradient_on_small_inputs(monkeypatch, name, dims, defer):
+    """Long weight-gradient products of up to 256 x 256 outputs run as one workgroup per row split that reads every
+    operand row once (fused bias gradient as per-thread column sums); forced here on small inputs, ragged widths
+    (200, 136: partial tiles, padded operand columns) and both the deferred and the per-chunk form."""
+    monkeypatch.setenv("GNNSTAGE_GEMM_WIDE_MIN_ROWS", "1")
+    monkeypatch.setenv("GNNSTAGE_WGRAD_DEFER", defer)
+    w = CONFIGS[name]
+    if dims is not None:
+        w = Workload(w.name + "_w", "rmat", w.n, w.seed, list(dims), w.n_chunks, dtype="bf16", n_candidates=w.n_candidates,
+                     rmat_abc=w.rmat_abc)
+    p = make_problem(w, bias_std=0.05)
+    _parity(p, TOL_BF16)
+
+
 @pytest.mark.parametrize("name", ["c1_s", "c2_s", "c3_s", "c4_s"])
 def test_persistent_gemm_on_small_inputs(monkeypatch, name):
     """The weight-stationary persistent GEMM normally serves only long operands; force it everywhere."""
