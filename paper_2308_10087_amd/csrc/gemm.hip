@@ -195,14 +195,22 @@ __device__ inline bf16x8 load8_bf16(const T *base, size_t ld, int r, int c, int 
 }
 
 // ------------------------------------------------------------------------------------ bf16 NT
-constexpr int BM = 128, BN = 128, BK = 32;
-constexpr int LDS_K = 40;  // padded K stride (elements): 80-byte rows keep 16-byte fragment reads conflict-free
+constexpr int BM = 128, BN = 128;
+// K step BK = 32 or 64 elements per LDS tile; rows are padded by 8 elements (80- or 144-byte rows keep the 16-byte
+// fragment reads conflict-free).  The per-chunk products of small graphs (a few ten thousand rows: one or two
+// workgroups per CU, all resident at once) are a chain of K / BK load-wait-multiply steps and nothing else, so the
+// deeper step halves their time's main term; it costs registers (four staged vectors per operand) and LDS (72 KB
+// per workgroup), which the long products do not have to spare.
 
 // PAIR: A is an fp32 matrix with an even leading dimension and an 8-byte aligned base.  A tile row is then
 // 32 floats = one 128-byte line, read by 16 lanes as float pairs (four whole rows per wave instruction,
 // fully coalesced) instead of eight scalars per lane.
-template <typename TA, bool VEC, bool PAIR = false>
+template <typename TA, bool VEC, bool PAIR = false, int BK = 32>
 __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmNtArgs a) {
+  constexpr int LDS_K = BK + 8;   // padded K stride (elements)
+  constexpr int KV = BK / 8;      // 16-byte vectors per tile row
+  constexpr int NV = BM * KV / 256;  // vectors per thread and operand tile
+  static_assert(!PAIR || BK == 32, "the float-pair loader is written for 32-wide steps");
   __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * LDS_K];
   __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * LDS_K];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -225,7 +233,7 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmNtArgs a) {
 #pragma unroll
       for (int t = 0; t < 16; ++t) acc[i][j][t] = 0.f;
 
-  bf16x8 ra[2], rb[2];
+  bf16x8 ra[NV], rb[NV];
   f32x2 rp[PAIR ? 8 : 1];
   const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
   auto gload = [&](int k0) {
@@ -245,8 +253,8 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmNtArgs a) {
       }
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int vid = tid + 256 * i, r = vid >> 2, k = k0 + (vid & 3) * 8;
+    for (int i = 0; i < NV; ++i) {
+      const int vid = tid + 256 * i, r = vid / KV, k = k0 + (vid % KV) * 8;
       if constexpr (!PAIR) ra[i] = (m0 + r < a.M) ? load8_bf16<TA, VEC>(A, (size_t)a.lda, m0 + r, k, a_cols) : zero8;
       rb[i] = (n0 + r < a.N && k < a.Kp) ? *reinterpret_cast<const bf16x8 *>(Bt + (size_t)(n0 + r) * a.ldb + k) : zero8;
     }
@@ -261,8 +269,8 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmNtArgs a) {
       }
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int vid = tid + 256 * i, r = vid >> 2, kv = vid & 3;
+    for (int i = 0; i < NV; ++i) {
+      const int vid = tid + 256 * i, r = vid / KV, kv = vid % KV;
       if constexpr (!PAIR) *reinterpret_cast<bf16x8 *>(&As[buf][r * LDS_K + kv * 8]) = ra[i];
       *reinterpret_cast<bf16x8 *>(&Bs[buf][r * LDS_K + kv * 8]) = rb[i];
     }
@@ -986,7 +994,10 @@ int launch_gemm_nt(const GemmNtArgs &a_in, int compute_dtype, hipStream_t s) {
       if (a.N <= 128) return launch_ws<2, 16>(a, s);
       if (a.Kp <= 128) return launch_ws<4, 8>(a, s);
       return launch_ws<4, 16>(a, s);
-    } else if (vec)
+    } else if (vec && a.Kp >= 128 && (long long)mt * ntiles <= 1024)
+      // short operands: every workgroup is resident at once, the product is its chain of K steps
+      hipLaunchKernelGGL((gemm_nt_bf16_kernel<bf16_t, true, false, 64>), grid, dim3(256), 0, s, a);
+    else if (vec)
       hipLaunchKernelGGL((gemm_nt_bf16_kernel<bf16_t, true>), grid, dim3(256), 0, s, a);
     else
       hipLaunchKernelGGL((gemm_nt_bf16_kernel<bf16_t, false>), grid, dim3(256), 0, s, a);
