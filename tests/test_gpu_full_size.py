@@ -33,7 +33,7 @@ DEV = "cuda:0"
 
 
 def _progress(msg):
-    """A line per step into gpurun_out/ (a test here runs for minutes; the harness takes silence for a hang)."""
+    """A line per step into the run's output folder (a test here runs for minutes, and a long silence reads as a hang)."""
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     try:
         os.makedirs(os.path.join(root, "gpurun_out"), exist_ok=True)

@@ -28,7 +28,7 @@ FLIP_SHARE = 2e-3
 
 
 def _note_flip_share(level, share, count, size):
-    """One line per level with differing ReLU decisions into gpurun_out/ (what the bound above is judged by)."""
+    """One line per level with differing ReLU decisions into the run's output folder (what the bound above is judged by)."""
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     try:
         os.makedirs(os.path.join(root, "gpurun_out"), exist_ok=True)
