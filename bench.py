@@ -175,16 +175,24 @@ def run_config(name, args, steps, warmup, with_cpu, copy_gbs):
     torch.cuda.synchronize()
 
     # Inside the timed region only the launches of an aggregation (the dominant operation: gather kernels and
-    # the reduce kernel that adds the partial rows of cut rows) carry HIP events: two event records per launch on
-    # the launch stream.  The per-kind breakdown of a whole step comes from two further, untimed steps with every
-    # kind switched on (events around all launches of a step cost about a millisecond).
+    # the reduce kernel that adds the partial rows of cut rows) carry HIP events, two event records per launch on
+    # the launch stream, and only in every `event_every`-th step: an event pair costs a launch about a microsecond
+    # and a half, which is a tenth of a step made of 2,000 launches of a few microseconds (configs[3]).  The per-kind
+    # breakdown of a whole step comes from two further, untimed steps with every kind switched on.
     st.gnnstage_profile_reset()
-    st.gnnstage_profile_select(["spmm_fwd", "spmm_bwd", "spmm_reduce"])
-    orders = []
+    st.gnnstage_profile_enable(False)
+    every = max(1, args.event_every)
+    orders = []          # of the steps whose aggregations carried events
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for i in range(steps):
-        orders.append(one_step(warmup + i))
+        if i % every == 0:
+            st.gnnstage_profile_select(["spmm_fwd", "spmm_bwd", "spmm_reduce"])
+        elif i % every == 1:
+            st.gnnstage_profile_enable(False)
+        order = one_step(warmup + i)
+        if i % every == 0:
+            orders.append(order)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     st.gnnstage_profile_enable(False)
@@ -276,6 +284,7 @@ def run_config(name, args, steps, warmup, with_cpu, copy_gbs):
         "one_launch": "one aggregation over a chunk: gather kernels (dense blocks, sparse rows) + the reduce of cut rows",
         "algorithmic_bytes_per_launch": round(dom_bytes / max(dom_launches, 1)),
         "avg_launch_ms": round(dom_ms / max(dom_launches, 1), 4), "launches": dom_launches,
+        "steps_with_events": len(orders),
         "gathered_bytes_per_launch": round(dom_gather / max(dom_launches, 1)),
         "gather_GBps": round(dom_gather / max(dom_ms * 1e-3, 1e-12) / 1e9, 1),
         "layer_order": ["transform-first" if t else "aggregate-first" for t in tf],
@@ -416,6 +425,8 @@ def main():
     ap.add_argument("--workload", default=HEADLINE, help="headline configuration (default: the largest one, c4)")
     ap.add_argument("--only", action="store_true", help="time the headline configuration only (no per_config object)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--event-every", type=int, default=4,
+                    help="the aggregation launches of every N-th timed step carry HIP events (1: of every step)")
     ap.add_argument("--cpu-sample-rows", type=int, default=0, help="0: a sample sized to about 10-30 s of oracle time")
     ap.add_argument("--partition", action="store_true",
                     help="chunks from the library's locality-aware partitioner instead of index ranges (not the benchmark configuration)")

@@ -617,7 +617,9 @@ struct Profiler {
       return e;
     }
     hipEvent_t e = nullptr;
-    (void)hipEventCreate(&e);
+    // timing only: no system-scope fence when the event completes (the default event makes every write of the
+    // stream visible to the host, which costs a launch of a few microseconds about as much as the launch itself)
+    (void)hipEventCreateWithFlags(&e, hipEventDisableSystemFence);
     return e;
   }
   void collect() {
