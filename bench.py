@@ -417,6 +417,53 @@ def cpu_baseline(w, row_ptr, col, tables, h0, dims, sample_rows):
             "seconds": round(total, 2)}
 
 
+def cpu_full(name, threads):
+    """Times the CPU oracle as it stands on ONE WHOLE configuration: a complete forward pass over all chunks (shuffled
+    order) and the complete backward pass, at the configuration's own size, with `threads` host threads.  Level tables
+    are random (the time does not depend on their values); nothing is compared here."""
+    import oracle
+    from synth import values
+    from synth.configs import CONFIGS, make_graph
+    from synth.graphs import equal_chunks
+
+    w = CONFIGS[name]
+    row_ptr, col = make_graph(w)
+    n, nnz = len(row_ptr) - 1, int(row_ptr[-1])
+    K, L, dims = w.n_chunks, w.n_layers, list(w.dims)
+    chunk_ptr = equal_chunks(n, K)
+    gcn = w.variant == "gcn"
+    val = oracle.gcn_norm(row_ptr, col)
+    Wn = [values.glorot_uniform(w.seed, 100 + j, dims[j], dims[j + 1]) for j in range(L)]
+    beta = None if gcn else np.array([math.log(0.5 / l + 1.0) for l in range(w.gcnii_first_layer, w.gcnii_first_layer + L)])
+    rng = np.random.default_rng(w.seed)
+    h0 = None if gcn else rng.standard_normal((n, dims[0]), dtype=np.float32)
+    if threads > 0:
+        oracle.set_threads(threads)
+    st = oracle.OracleStage(row_ptr, col, val, chunk_ptr, dims, Wn, None, variant=w.variant, a=w.gcnii_alpha, beta=beta,
+                            h0=h0, quant=w.dtype == "bf16", level0_f32=w.level0_f32)
+    for j in range(L):  # one host array as current and historical level
+        a = np.abs(rng.standard_normal((n, dims[j]), dtype=np.float32))
+        st.cur[j] = a
+        st.hist[j] = a
+    st._refresh()
+    order = [int(k) for k in values.permutation(w.seed, 1000, K)]
+    gout = rng.standard_normal((n, dims[-1]), dtype=np.float32)
+    first_stage = gcn if w.first_stage is None else w.first_stage
+    t0 = time.perf_counter()
+    st.begin_pass()
+    for k in order:  # a line per chunk: a whole pass takes minutes on the larger configurations
+        st.forward_chunk(k)
+        log(f"[bench]   {name} forward chunk {k} done at {time.perf_counter() - t0:.1f}s")
+    t_f = time.perf_counter() - t0
+    t1 = time.perf_counter()
+    for k in reversed(order):
+        st.backward_chunk(k, np.ascontiguousarray(gout[st.rows(k)]), need_input_grad=not first_stage)
+        log(f"[bench]   {name} backward chunk {k} done at {time.perf_counter() - t1:.1f}s")
+    t_b = time.perf_counter() - t1
+    return {"workload": name, "n": n, "nnz": nnz, "layers": L, "chunks": K, "threads": oracle.max_threads(),
+            "forward_s": round(t_f, 2), "backward_s": round(t_b, 2), "edges_per_s": L * nnz / (t_f + t_b), "kind": "oracle"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -436,7 +483,21 @@ def main():
                          "dense blocks then run from stored weight tiles instead of bit patterns")
     ap.add_argument("--train-epochs", type=int, default=0,
                     help="also time this many epochs of the whole training loop (head + Adam) around the same stage")
+    ap.add_argument("--cpu-full", default="",
+                    help="no GPU work: time the CPU oracle on whole configurations instead (comma-separated names, "
+                         "e.g. c0,c1,c2,c3; a name with ':1' appended runs on one thread) and print one JSON line")
     args = ap.parse_args()
+    if args.cpu_full:
+        import oracle
+        all_threads = oracle.max_threads()
+        res = []
+        for item in args.cpu_full.split(","):
+            nm, _, th = item.partition(":")
+            log(f"[bench] CPU oracle on all of {nm} ...")
+            res.append(cpu_full(nm, int(th) if th else all_threads))
+            log(f"[bench] {res[-1]}")
+        print(json.dumps({"cpu_baseline_full": res}))
+        return
     if args.gpus != 1:
         sys.exit("bench.py measures one pipeline stage on ONE GPU; this build has no multi-GPU path (--gpus must be 1)")
 
