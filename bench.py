@@ -159,16 +159,19 @@ def run_config(name, args, steps, warmup, with_cpu, copy_gbs):
             grad_h0.zero_()
         st.forward_pass(order)
         st.backward_pass(order, grad_out)
-        st.update_history()
+        if args.history_swap:
+            st.gnnstage_update_history_swap()
+        else:
+            st.update_history()
         return order
 
     # historical buffers: one untimed epoch from zero history, refresh, then N(0, 0.01^2) noise
     one_step(-1)
     for j in range(L):
-        if hist[j].data_ptr() != cur[j].data_ptr():
+        if st.hist[j].data_ptr() != st.cur[j].data_ptr():  # the stage's lists: with --history-swap the buffers trade places
             rows_per = max(1, (1 << 28) // max(dims[j], 1))  # in slices: the noise of a whole 10 M x 256 level is 10 GB of fp32
             for r0 in range(0, n, rows_per):
-                sl = hist[j][r0:r0 + rows_per]
+                sl = st.hist[j][r0:r0 + rows_per]
                 sl.add_((0.01 * torch.randn(sl.shape, generator=gen, device=dev)).to(sl.dtype))
     for i in range(warmup):
         one_step(i)
@@ -315,7 +318,9 @@ def run_config(name, args, steps, warmup, with_cpu, copy_gbs):
     hist_bytes = sum(2.0 * n * dims[j] * (4 if (j == 0 and l0 == torch.float32) else elt)
                      for j in range(L) if hist[j].data_ptr() != cur[j].data_ptr())
     hms = kernels_ms.get("history_copy", 0.0)
-    history = {"bytes_per_step": round(hist_bytes), "ms_per_step": hms,
+    if args.history_swap:  # nothing is copied (but a level 0 with a history buffer of its own)
+        hist_bytes = 2.0 * n * dims[0] * (4 if l0 == torch.float32 else elt) if hist[0].data_ptr() != cur[0].data_ptr() else 0.0
+    history = {"mode": "swap" if args.history_swap else "copy", "bytes_per_step": round(hist_bytes), "ms_per_step": hms,
                "GBps": round(hist_bytes / max(hms * 1e-3, 1e-12) / 1e9, 1) if hms > 0 else None,
                "box_copy_GBps": round(copy_gbs, 1),
                "frac_of_box_copy": round(hist_bytes / max(hms * 1e-3, 1e-12) / 1e9 / copy_gbs, 3) if hms > 0 else None}
@@ -483,6 +488,9 @@ def main():
                          "dense blocks then run from stored weight tiles instead of bit patterns")
     ap.add_argument("--train-epochs", type=int, default=0,
                     help="also time this many epochs of the whole training loop (head + Adam) around the same stage")
+    ap.add_argument("--history-swap", action="store_true",
+                    help="refresh the history with gnnstage_update_history_swap (levels trade buffers, nothing is copied) "
+                         "instead of update_history; not the default line")
     ap.add_argument("--cpu-full", default="",
                     help="no GPU work: time the CPU oracle on whole configurations instead (comma-separated names, "
                          "e.g. c0,c1,c2,c3; a name with ':1' appended runs on one thread) and print one JSON line")
@@ -508,7 +516,7 @@ def main():
 
     head = run_config(args.workload, args, args.steps, args.warmup, not args.no_cpu_baseline, copy_gbs)
     per_config = {}
-    if not args.only and args.workload == HEADLINE and not (args.partition or args.caller_weights or args.train_epochs):
+    if not args.only and args.workload == HEADLINE and not (args.partition or args.caller_weights or args.train_epochs or args.history_swap):
         for name in SECONDARY:
             r = run_config(name, args, args.steps, args.warmup, False, copy_gbs)
             per_config[name] = {k: r[k] for k in ("workload", "value", "unit", "ms_per_step", "steps", "dtype", "kernel_ms_per_step",
@@ -519,7 +527,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": head["dtype"], "data": "synthetic",
         "config": {"workload": head["workload"], "max_degree": head["max_degree"],
-                   "step": "forward all chunks + backward all chunks + update_history"},
+                   "step": "forward all chunks + backward all chunks + " +
+                           ("gnnstage_update_history_swap (levels trade buffers)" if args.history_swap else "update_history")},
         "kernel_ms_per_step": head["kernel_ms_per_step"],
         "gemm": head["gemm"],
         "update_history": head["update_history"],

@@ -170,6 +170,21 @@ int gnnstage_flush_weight_gradients(gnnstage_t *st, void *hip_stream);
  * the refresh period, is caller policy).  Levels whose hist pointer aliases cur are skipped. */
 int update_history(gnnstage_t *st, void *hip_stream);
 
+/* The same refresh without moving a byte, for callers that let the library say which buffer is which (Section 3.4,
+ * second technique, at a refresh period of one epoch).  For every level j in [1, L) whose hist pointer differs from
+ * its cur pointer the two buffers trade places INSIDE the library: the buffer that held the current level becomes
+ * the historical one, and the next pass writes its current rows into the other buffer.  That is the state
+ * update_history leaves, except that the new "current" buffer holds stale rows: harmless, because a pass reads a
+ * current row only after it has written it (rows of processed chunks), and everything else from history.  Level 0 is
+ * caller-filled and keeps its buffers: it is copied as in update_history when hist[0] differs from cur[0].
+ * Needs a complete pass behind it (every chunk forwarded; no backward pass half-way), otherwise EORDER.
+ * After the call gnnstage_level_buffers tells where the levels are; the desc's pointers no longer do. */
+int gnnstage_update_history_swap(gnnstage_t *st, void *hip_stream);
+
+/* Where level `level` lives now: *cur (levels 0 .. L) and *hist (levels 0 .. L-1, NULL for level L), DEVICE pointers
+ * among those the caller passed at create.  Either output may be NULL.  EINVAL for a level outside [0, L]. */
+int gnnstage_level_buffers(const gnnstage_t *st, int32_t level, void **cur, void **hist);
+
 /* Seed of the dropout decisions of the passes that follow.  Feature c of vertex u survives in layer j when the
  * top 24 bits of SplitMix64(key_j + (u * d + c + 1) * G) are at least dropout_p * 2^24, key_j = SplitMix64(seed +
  * (j + 1) * G), G = 0x9E3779B97F4A7C15, d the width of the rows the dropout acts on (the layer's input for

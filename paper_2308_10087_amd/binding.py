@@ -85,6 +85,10 @@ def _load():
     lib.gnnstage_flush_weight_gradients.argtypes = [C.c_void_p, C.c_void_p]
     lib.update_history.restype = C.c_int
     lib.update_history.argtypes = [C.c_void_p, C.c_void_p]
+    lib.gnnstage_update_history_swap.restype = C.c_int
+    lib.gnnstage_update_history_swap.argtypes = [C.c_void_p, C.c_void_p]
+    lib.gnnstage_level_buffers.restype = C.c_int
+    lib.gnnstage_level_buffers.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]
     lib.gnnstage_destroy.restype = C.c_int
     lib.gnnstage_destroy.argtypes = [C.c_void_p]
     lib.gnnstage_last_error.restype = C.c_char_p
@@ -422,6 +426,21 @@ class GnnStage:
 
     def update_history(self, stream=None) -> None:
         self._check(lib.update_history(self._h, self._stream(stream)))
+
+    def gnnstage_update_history_swap(self, stream=None) -> None:
+        """The refresh without a copy: levels 1 .. L-1 trade their current and historical buffers inside the
+        library.  ``self.cur`` / ``self.hist`` are re-ordered to match (same tensors, other places)."""
+        self._check(lib.gnnstage_update_history_swap(self._h, self._stream(stream)))
+        by_ptr = {t.data_ptr(): t for t in self.cur + self.hist}
+        for j in range(self.L):
+            c, h = self.gnnstage_level_buffers(j)
+            self.cur[j], self.hist[j] = by_ptr[c], by_ptr[h]
+
+    def gnnstage_level_buffers(self, level: int):
+        """(device address of the current level, of the historical level or None for level L)."""
+        c, h = C.c_void_p(None), C.c_void_p(None)
+        self._check(lib.gnnstage_level_buffers(self._h, int(level), C.byref(c), C.byref(h)))
+        return c.value, h.value
 
     def gnnstage_debug_select_counts(self, chunk_id: int) -> np.ndarray:
         rows = max(int(self.chunk_ptr[chunk_id + 1] - self.chunk_ptr[chunk_id]), 0) if 0 <= chunk_id < self.K else 0

@@ -698,6 +698,7 @@ struct gnnstage {
   std::vector<int32_t> order;
   ChunkMask fmask{}, bmask{};
   int n_bwd = 0;
+  bool cur_stale = false;  // the levels traded places and no complete pass has rewritten the current ones yet
   std::vector<char> wgrad_pending;  // per chunk: its backward call ran, its rows' weight-gradient products are still owed
   std::string err;
   Profiler prof;
@@ -1693,6 +1694,7 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
   if (mask_test(st->fmask, (uint32_t)k)) return fail(st, GNNSTAGE_EORDER, "chunk already processed in this pass");
   st->order.push_back(k);
   mask_set(st->fmask, k);  // C_k joins V_processed before its layers run
+  if ((int)st->order.size() == s.K) st->cur_stale = false;  // after this call every current row is of this pass
 
   const int64_t row0 = s.chunk_ptr[k], M = s.chunk_ptr[k + 1] - row0;
   if (M == 0) return GNNSTAGE_OK;
@@ -2149,11 +2151,37 @@ extern "C" int update_history(gnnstage_t *st, void *hip_stream) {
   if (!st) return GNNSTAGE_EINVAL;
   const Shape &s = st->s;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (st->cur_stale)
+    return fail(st, GNNSTAGE_EORDER, "the current levels hold stale rows until a complete pass follows gnnstage_update_history_swap");
   Timed t(st, stream, 5);
   for (int j = 0; j < s.L; ++j) {
     if (st->hist[j] == st->cur[j]) continue;
     HIP_TRY(st, launch_copy(st->cur[j], st->hist[j], (size_t)s.n * s.dims[j] * st->level_elt(j), stream));
   }
+  return GNNSTAGE_OK;
+}
+
+extern "C" int gnnstage_update_history_swap(gnnstage_t *st, void *hip_stream) {
+  if (!st) return GNNSTAGE_EINVAL;
+  const Shape &s = st->s;
+  if ((int)st->order.size() != s.K || (st->n_bwd > 0 && st->n_bwd < s.K) || st->cur_stale)
+    return fail(st, GNNSTAGE_EORDER, "the levels trade places only behind a complete pass");
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  Timed t(st, stream, 5);
+  if (st->hist[0] != st->cur[0])  // level 0 is written by the caller: it keeps its buffers
+    HIP_TRY(st, launch_copy(st->cur[0], st->hist[0], (size_t)s.n * s.dims[0] * st->level_elt(0), stream));
+  for (int j = 1; j < s.L; ++j)
+    if (st->hist[j] != st->cur[j]) {
+      std::swap(st->hist[j], st->cur[j]);
+      st->cur_stale = true;
+    }
+  return GNNSTAGE_OK;
+}
+
+extern "C" int gnnstage_level_buffers(const gnnstage_t *st, int32_t level, void **cur, void **hist) {
+  if (!st || level < 0 || level > st->s.L) return GNNSTAGE_EINVAL;
+  if (cur) *cur = st->cur[(size_t)level];
+  if (hist) *hist = level < st->s.L ? st->hist[(size_t)level] : nullptr;
   return GNNSTAGE_OK;
 }
 

@@ -581,6 +581,69 @@ def test_update_history_and_second_epoch():
     _compare(run, ref, p, TOL_F32)
 
 
+@pytest.mark.parametrize("variant,dtype,first_stage", [("gcn", "f32", False), ("gcn", "f32", True), ("gcnii", "bf16", False),
+                                                        ("sage", "bf16", False), ("resgcn", "f32", False)])
+def test_history_refreshed_by_trading_buffers(variant, dtype, first_stage):
+    """gnnstage_update_history_swap: after a complete pass the buffers of levels 1 .. L-1 trade places inside the
+    library instead of being copied (level 0 is copied).  The historical levels then hold exactly what the current
+    ones held, and three further epochs (each refreshed the same way, new chunk order every epoch) match the oracle,
+    which copies.  Guards: no second trade, and no copying refresh, before another complete pass."""
+    import paper_2308_10087_amd as g
+    dims = (16, 16, 16, 16) if variant in ("gcnii", "resgcn") else (24, 40, 16, 32)
+    w = small(n=800, k=4, dims=dims, variant=variant, dtype=dtype)
+    p = make_problem(w, first_stage=first_stage, bias_std=0.05)
+    tol = TOL_F32 if dtype == "f32" else TOL_BF16
+    ref = run_oracle(p)
+    run = _gpu(p, alias_hist0=first_stage).run()
+    st = run.stage
+    order0 = [int(k) for k in p.order]
+    st.stage_forward_chunk(order0[0], 0)               # a new pass, one chunk in: no trade now
+    with pytest.raises(g.GnnStageError) as e:
+        st.gnnstage_update_history_swap()
+    assert e.value.code == -3
+    for pos, k in enumerate(order0[1:], start=1):      # complete it (same order, same inputs: same levels)
+        st.stage_forward_chunk(k, pos)
+    run.backward()
+    torch.cuda.synchronize()
+    for epoch in range(1, 4):
+        before = [st.cur[j].clone() for j in range(p.L)]
+        ptrs = [(st.cur[j].data_ptr(), st.hist[j].data_ptr()) for j in range(p.L)]
+        ref.update_history()
+        st.gnnstage_update_history_swap()
+        torch.cuda.synchronize()
+        for j in range(p.L):
+            assert torch.equal(st.hist[j], before[j]), (epoch, j)
+            now = st.gnnstage_level_buffers(j)
+            if j >= 1 and ptrs[j][0] != ptrs[j][1]:
+                assert now == (ptrs[j][1], ptrs[j][0]), (epoch, j)      # traded places
+            else:
+                assert now == ptrs[j], (epoch, j)                        # level 0 keeps its buffers
+        assert st.gnnstage_level_buffers(p.L) == (st.cur[p.L].data_ptr(), None)
+        with pytest.raises(g.GnnStageError) as e:
+            st.gnnstage_update_history_swap()
+        assert e.value.code == -3
+        if any(a != b for a, b in ptrs[1:]):
+            with pytest.raises(g.GnnStageError) as e:
+                st.update_history()
+            assert e.value.code == -3
+        run.cur, run.hist = st.cur, st.hist    # the harness reads results through these lists
+        order = [int(k) for k in values.permutation(77, epoch, len(p.chunk_ptr) - 1)]
+        ref.zero_grads()
+        for t in run.dW + (run.dbias or []) + ([run.grad_h0] if run.grad_h0 is not None else []) + \
+                (run.d_ln_gamma or []) + (run.d_ln_beta or []):
+            t.zero_()
+        ref.forward_pass(order)
+        run.forward(order)
+        torch.cuda.synchronize()
+        _check_forward(run, ref, p, tol)
+        for j in range(1, p.L + 1):
+            run.cur[j].copy_(torch.from_numpy(ref.cur[j]).to(run.cur[j].dtype))
+        ref.backward_pass(p.grad_out)
+        run.backward(order)
+        torch.cuda.synchronize()
+        _compare(run, ref, p, tol)
+
+
 def test_protocol_errors():
     import paper_2308_10087_amd as g
     p = make_problem(small(k=3))
