@@ -148,7 +148,7 @@ def run_config(name, args, steps, warmup, with_cpu, copy_gbs):
                     grad_in=grad_in, device=dev, ln_gamma=ln[0], ln_beta=ln[1], d_ln_gamma=ln[2], d_ln_beta=ln[3])
     log(f"[bench] gnnstage_create: {time.time() - t1:.1f}s, workspace {st.workspace_bytes / 2**30:.2f} GiB")
 
-    def one_step(step_idx: int):
+    def one_step(step_idx: int, swap: bool = args.history_swap):
         order = values.permutation(w.seed, 1000 + step_idx, K)
         for t in dW:
             t.zero_()
@@ -159,7 +159,7 @@ def run_config(name, args, steps, warmup, with_cpu, copy_gbs):
             grad_h0.zero_()
         st.forward_pass(order)
         st.backward_pass(order, grad_out)
-        if args.history_swap:
+        if swap:
             st.gnnstage_update_history_swap()
         else:
             st.update_history()
@@ -208,6 +208,17 @@ def run_config(name, args, steps, warmup, with_cpu, copy_gbs):
     torch.cuda.synchronize()
     st.gnnstage_profile_enable(False)
     prof_all = st.gnnstage_profile_read(-1)
+    # for comparison, not part of the line's value: the same steps with the history refreshed by trading buffers
+    swap_ms = None
+    if not args.history_swap and L > 1:
+        n_swap = min(steps, 5)
+        one_step(warmup + steps + n_extra, swap=True)
+        torch.cuda.synchronize()
+        t_sw = time.perf_counter()
+        for i in range(n_swap):
+            one_step(warmup + steps + n_extra + 1 + i, swap=True)
+        torch.cuda.synchronize()
+        swap_ms = round(1e3 * (time.perf_counter() - t_sw) / n_swap, 3)
 
     ms_per_step = 1e3 * elapsed / steps
     value = L * nnz / (elapsed / steps)
@@ -320,7 +331,8 @@ def run_config(name, args, steps, warmup, with_cpu, copy_gbs):
     hms = kernels_ms.get("history_copy", 0.0)
     if args.history_swap:  # nothing is copied (but a level 0 with a history buffer of its own)
         hist_bytes = 2.0 * n * dims[0] * (4 if l0 == torch.float32 else elt) if hist[0].data_ptr() != cur[0].data_ptr() else 0.0
-    history = {"mode": "swap" if args.history_swap else "copy", "bytes_per_step": round(hist_bytes), "ms_per_step": hms,
+    history = {"mode": "swap" if args.history_swap else "copy", "step_ms_with_buffers_traded_instead": swap_ms,
+               "bytes_per_step": round(hist_bytes), "ms_per_step": hms,
                "GBps": round(hist_bytes / max(hms * 1e-3, 1e-12) / 1e9, 1) if hms > 0 else None,
                "box_copy_GBps": round(copy_gbs, 1),
                "frac_of_box_copy": round(hist_bytes / max(hms * 1e-3, 1e-12) / 1e9 / copy_gbs, 3) if hms > 0 else None}
