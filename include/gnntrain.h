@@ -64,6 +64,9 @@ typedef struct {
   uint64_t seed;      /* of the chunk shuffling, and of the dropout decisions of stages that have dropout: stage s
                          gets gnnstage_set_dropout_seed(SplitMix64(seed + (epoch + 1) * 0x9E3779B97F4A7C15) + s) */
   int32_t alpha_hist; /* refresh period of the historical embeddings, >= 1 */
+  int32_t history_swap; /* non-zero: refresh with gnnstage_update_history_swap (the level buffers of a stage trade places,
+                           nothing but level 0 is copied) instead of update_history; the stages' level pointers then
+                           come from gnnstage_level_buffers */
   void *workspace;    /* DEVICE, 256-byte aligned, >= gnntrain_workspace_size() bytes */
   size_t workspace_bytes;
 } gnntrain_desc;

@@ -56,7 +56,7 @@ class gnntrain_desc(C.Structure):
         ("n_params", C.c_int32), ("params", C.c_void_p),
         ("optimizer", C.c_int32), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
         ("weight_decay", C.c_float),
-        ("shuffle", C.c_int32), ("seed", C.c_uint64), ("alpha_hist", C.c_int32),
+        ("shuffle", C.c_int32), ("seed", C.c_uint64), ("alpha_hist", C.c_int32), ("history_swap", C.c_int32),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
     ]
 
@@ -431,6 +431,10 @@ class GnnStage:
         """The refresh without a copy: levels 1 .. L-1 trade their current and historical buffers inside the
         library.  ``self.cur`` / ``self.hist`` are re-ordered to match (same tensors, other places)."""
         self._check(lib.gnnstage_update_history_swap(self._h, self._stream(stream)))
+        self.sync_level_lists()
+
+    def sync_level_lists(self) -> None:
+        """Re-orders ``self.cur`` / ``self.hist`` after the library's view of which buffer holds which level."""
         by_ptr = {t.data_ptr(): t for t in self.cur + self.hist}
         for j in range(self.L):
             c, h = self.gnnstage_level_buffers(j)
@@ -576,10 +580,11 @@ class GnnTrainer:
 
     def __init__(self, stages: Sequence["GnnStage"], *, head_W, head_b, head_dW, head_db, labels, train_mask, params,
                  optimizer=GNNTRAIN_ADAM, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, shuffle=True,
-                 seed=0, alpha_hist=1, device="cuda:0"):
+                 seed=0, alpha_hist=1, history_swap=False, device="cuda:0"):
         import torch
 
         self._torch = torch
+        self.history_swap = bool(history_swap)
         self.stages = list(stages)
         self._tensors = [head_W, head_b, head_dW, head_db, labels, train_mask, params]
         hs = (C.c_void_p * len(self.stages))(*[st._h for st in self.stages])
@@ -600,6 +605,7 @@ class GnnTrainer:
         d.optimizer, d.lr, d.beta1, d.beta2, d.eps = int(optimizer), float(lr), float(beta1), float(beta2), float(eps)
         d.weight_decay = float(weight_decay)
         d.shuffle, d.seed, d.alpha_hist = int(bool(shuffle)), int(seed), int(alpha_hist)
+        d.history_swap = int(bool(history_swap))
         size = int(lib.gnntrain_workspace_size(C.byref(d)))
         if size == 0:
             raise GnnStageError(-1, "gnntrain_workspace_size: invalid descriptor")
@@ -619,6 +625,9 @@ class GnnTrainer:
         rc = lib.gnntrain_epoch(self._h, int(epoch), C.byref(loss) if want_loss else None, _cur_stream())
         if rc != 0:
             raise GnnStageError(rc, lib.gnntrain_last_error(self._h).decode())
+        if self.history_swap:  # the stages' level buffers may have traded places
+            for st in self.stages:
+                st.sync_level_lists()
         return float(loss.value) if want_loss else None
 
     def gnntrain_last_order(self) -> np.ndarray:

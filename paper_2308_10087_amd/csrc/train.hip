@@ -202,7 +202,7 @@ struct gnntrain {
   const int32_t *labels = nullptr;
   const uint8_t *mask = nullptr;
   int64_t n_train = 0;
-  int optimizer = 0, shuffle = 0, alpha_hist = 1;
+  int optimizer = 0, shuffle = 0, alpha_hist = 1, history_swap = 0;
   float lr = 0, beta1 = 0, beta2 = 0, eps = 0, wd = 0;
   uint64_t seed = 0;
   int64_t step = 0;
@@ -447,6 +447,7 @@ extern "C" int gnntrain_create(const gnntrain_desc *d, gnntrain_t **out) {
   tr->optimizer = d->optimizer;
   tr->shuffle = d->shuffle;
   tr->alpha_hist = d->alpha_hist;
+  tr->history_swap = d->history_swap;
   tr->lr = d->lr;
   tr->beta1 = d->beta1;
   tr->beta2 = d->beta2;
@@ -596,7 +597,10 @@ extern "C" int gnntrain_epoch(gnntrain_t *tr, int64_t epoch, float *loss, void *
   }
   // ---- Section 3.4, second technique: the history of epoch alpha * floor((t - 1) / alpha)
   if ((epoch + 1) % tr->alpha_hist == 0)
-    for (int s = 0; s < S; ++s) TRAIN_STAGE(tr, s, update_history(tr->stages[(size_t)s], stream));
+    for (int s = 0; s < S; ++s) {
+      if (tr->history_swap) TRAIN_STAGE(tr, s, gnnstage_update_history_swap(tr->stages[(size_t)s], stream));
+      else TRAIN_STAGE(tr, s, update_history(tr->stages[(size_t)s], stream));
+    }
   if (loss) {
     TRAIN_HIP(tr, hipMemcpyAsync(loss, tr->at<float>(lay.loss), sizeof(float), hipMemcpyDeviceToHost, stream));
     TRAIN_HIP(tr, hipStreamSynchronize(stream));

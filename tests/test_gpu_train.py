@@ -288,6 +288,29 @@ def test_adam_epochs_learn_bf16():
     assert out[-1][0] < 0.7 * out[0][0]
 
 
+@pytest.mark.parametrize("dtype,alpha,variants", [("f32", 1, ("sage", "resgcn", "gcn")), ("f32", 2, None), ("bf16", 1, None)])
+def test_epochs_with_the_history_refreshed_by_trading_buffers(dtype, alpha, variants):
+    """history_swap: the loop refreshes with gnnstage_update_history_swap.  The historical levels hold the same
+    values as after a copy, so losses and parameters are bit-identical to a run that copies, epoch after epoch."""
+    from gpu_harness import GpuTrainRun
+    dims = ((24, 16, 16), (16, 16, 16), (16, 16, 12)) if variants else ((24, 16, 16), (16, 16, 12))
+    tp = make_train_problem(n=1200, n_classes=5, stage_dims=dims, K=4, dtype=dtype, ragged=True, variants=variants)
+    a = GpuTrainRun(tp, optimizer="adam", lr=0.01, shuffle=True, seed=5, alpha_hist=alpha)
+    b = GpuTrainRun(tp, optimizer="adam", lr=0.01, shuffle=True, seed=5, alpha_hist=alpha, history_swap=True)
+    for e in range(6):
+        la, lb = a.epoch(e), b.epoch(e)
+        assert la == lb, (e, la, lb)
+    for x, y in zip(a.master_values(), b.master_values()):
+        assert np.array_equal(x, y)
+    traded = False
+    for sa, sb in zip(a.stages, b.stages):
+        for j in range(sa.L):
+            assert sb.gnnstage_level_buffers(j) == (sb.cur[j].data_ptr(), sb.hist[j].data_ptr())
+            assert torch.equal(sa.hist[j], sb.hist[j]), j       # epoch 6 refreshed (alpha 1 or 2)
+        traded = traded or any(sb.cur[j].data_ptr() != b.cur[b.stages.index(sb)][j].data_ptr() for j in range(1, sb.L))
+    assert traded == (6 // alpha % 2 == 1)   # an odd number of trades leaves the buffers in the other places
+
+
 def test_splitting_layers_into_stages_changes_nothing_on_the_gpu():
     from gpu_harness import GpuTrainRun
     losses = []
