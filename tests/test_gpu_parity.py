@@ -481,6 +481,15 @@ def test_full_size_c1_in_the_benchmark_configuration():
     _parity(p, TOL_BF16, need_input_grad=False, alias_hist0=True, edge_val="computed")
 
 
+@pytest.mark.parametrize("name", ["c1_sage", "c1_res"])
+def test_full_size_c1_graph_under_the_other_layer_types(name):
+    """The 233 k vertex graph of configs[1] as a middle stage (256 -> 256 x 4, bf16, input gradient wanted) of GraphSage
+    layers (mean aggregator computed by the library: dense blocks run as bit patterns with row / column scales) and
+    of ResGCN+ layers (LayerNorm tables, end-of-pass aggregations for the LayerNorm parameters), at full size."""
+    p = make_problem(CONFIGS[name], bias_std=0.05)
+    _parity(p, TOL_BF16, edge_val="computed")
+
+
 def test_full_size_c3_gcnii_stage():
     """configs[3] at full size: 16 GCNII layers over the 169k-vertex power-law graph, bf16."""
     p = make_problem(CONFIGS["c3"], bias_std=0.0)
