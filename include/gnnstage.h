@@ -21,6 +21,12 @@
  *
  * Every function returns GNNSTAGE_OK (0) or a negative GNNSTAGE_E* code and never throws
  * or aborts; gnnstage_last_error gives a message for the last failure.
+ *
+ * stage_forward_chunk, stage_backward_chunk, update_history and gnnstage_flush_weight_gradients do nothing on the
+ * device but launch kernels on the given stream (no allocation, no synchronisation, no memset or copy call), so with
+ * the gnnstage_profile_* timers off a sequence of them may be recorded under HIP stream capture and replayed; the
+ * protocol state they keep on the host (which chunks are processed) advances at capture time, so a replay repeats
+ * exactly the recorded calls.
  */
 #ifndef GNNSTAGE_H
 #define GNNSTAGE_H
