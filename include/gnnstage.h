@@ -45,7 +45,7 @@ enum {
   GNNSTAGE_EINVAL = -1,  /* null pointer, bad shape / dtype / variant, malformed CSR or chunks */
   GNNSTAGE_ERANGE = -2,  /* chunk id outside [0, n_chunks) */
   GNNSTAGE_EORDER = -3,  /* call sequence violates the pass protocol (see below) */
-  GNNSTAGE_ENOMEM = -4,  /* workspace smaller than gnnstage_workspace_size() */
+  GNNSTAGE_ENOMEM = -4,  /* workspace smaller than gnnstage_workspace_size(), or the host ran out of memory */
   GNNSTAGE_EHIP = -5,    /* a HIP runtime call failed */
   GNNSTAGE_ENOTSUP = -6  /* sizes beyond what the index packing supports */
 };

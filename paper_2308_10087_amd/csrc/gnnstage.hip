@@ -2,6 +2,7 @@
 // planning at create time, and the per-chunk launch sequences (Algorithm 1's inner loops and
 // the matching backward pass).  All device work is issued on the caller's stream.
 #include <stdio.h>
+#include "guard.h"
 #include <stdlib.h>
 #include <string.h>
 
@@ -1228,7 +1229,7 @@ float bf16_bits_to_f32(uint16_t h) {
 }
 }  // namespace
 
-extern "C" size_t gnnstage_workspace_size(const gnnstage_desc *desc) {
+extern "C" size_t gnnstage_workspace_size(const gnnstage_desc *desc) try {
   Shape s;
   std::string err;
   if (!read_shape(desc, s, err)) {
@@ -1242,8 +1243,9 @@ extern "C" size_t gnnstage_workspace_size(const gnnstage_desc *desc) {
   }
   return make_layout(s, hp.f, hp.b, desc->edge_val == nullptr).total;
 }
+GNNSTAGE_GUARD_SIZE
 
-extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
+extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) try {
   if (!out) return fail(nullptr, GNNSTAGE_EINVAL, "out is NULL");
   *out = nullptr;
   Shape s;
@@ -1628,16 +1630,18 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) {
   *out = st;
   return GNNSTAGE_OK;
 }
+GNNSTAGE_GUARD_INT
 
-extern "C" int gnnstage_destroy(gnnstage_t *st) {
+extern "C" int gnnstage_destroy(gnnstage_t *st) try {
   if (!st) return GNNSTAGE_EINVAL;
   const hipError_t e = hipDeviceSynchronize();
   st->prof.destroy();
   delete st;
   return e == hipSuccess ? GNNSTAGE_OK : GNNSTAGE_EHIP;
 }
+GNNSTAGE_GUARD_INT
 
-extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void *hip_stream) {
+extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void *hip_stream) try {
   if (!st) return GNNSTAGE_EINVAL;
   const Shape &s = st->s;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -1819,6 +1823,7 @@ extern "C" int stage_forward_chunk(gnnstage_t *st, int32_t k, int32_t pos, void 
   }
   return GNNSTAGE_OK;
 }
+GNNSTAGE_GUARD_INT
 
 namespace {
 // Weight (and bias) gradients of the aggregate-first layers that the backward calls made so far still owe:
@@ -1892,12 +1897,13 @@ int flush_deferred_wgrad(gnnstage *st, hipStream_t stream) {
 }
 }  // namespace
 
-extern "C" int gnnstage_flush_weight_gradients(gnnstage_t *st, void *hip_stream) {
+extern "C" int gnnstage_flush_weight_gradients(gnnstage_t *st, void *hip_stream) try {
   if (!st) return GNNSTAGE_EINVAL;
   return flush_deferred_wgrad(st, static_cast<hipStream_t>(hip_stream));
 }
+GNNSTAGE_GUARD_INT
 
-extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_out_rows, void *hip_stream) {
+extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_out_rows, void *hip_stream) try {
   if (!st) return GNNSTAGE_EINVAL;
   const Shape &s = st->s;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -2146,8 +2152,9 @@ extern "C" int stage_backward_chunk(gnnstage_t *st, int32_t k, const void *grad_
   }
   return end_of_pass();
 }
+GNNSTAGE_GUARD_INT
 
-extern "C" int update_history(gnnstage_t *st, void *hip_stream) {
+extern "C" int update_history(gnnstage_t *st, void *hip_stream) try {
   if (!st) return GNNSTAGE_EINVAL;
   const Shape &s = st->s;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -2160,8 +2167,9 @@ extern "C" int update_history(gnnstage_t *st, void *hip_stream) {
   }
   return GNNSTAGE_OK;
 }
+GNNSTAGE_GUARD_INT
 
-extern "C" int gnnstage_update_history_swap(gnnstage_t *st, void *hip_stream) {
+extern "C" int gnnstage_update_history_swap(gnnstage_t *st, void *hip_stream) try {
   if (!st) return GNNSTAGE_EINVAL;
   const Shape &s = st->s;
   if ((int)st->order.size() != s.K || (st->n_bwd > 0 && st->n_bwd < s.K) || st->cur_stale)
@@ -2177,6 +2185,7 @@ extern "C" int gnnstage_update_history_swap(gnnstage_t *st, void *hip_stream) {
     }
   return GNNSTAGE_OK;
 }
+GNNSTAGE_GUARD_INT
 
 extern "C" int gnnstage_level_buffers(const gnnstage_t *st, int32_t level, void **cur, void **hist) {
   if (!st || level < 0 || level > st->s.L) return GNNSTAGE_EINVAL;
@@ -2185,7 +2194,7 @@ extern "C" int gnnstage_level_buffers(const gnnstage_t *st, int32_t level, void 
   return GNNSTAGE_OK;
 }
 
-extern "C" int gnnstage_debug_select_counts(gnnstage_t *st, int32_t k, int32_t *out) {
+extern "C" int gnnstage_debug_select_counts(gnnstage_t *st, int32_t k, int32_t *out) try {
   if (!st || !out) return GNNSTAGE_EINVAL;
   const Shape &s = st->s;
   if (k < 0 || k >= s.K) return fail(st, GNNSTAGE_ERANGE, "chunk id out of range");
@@ -2199,6 +2208,7 @@ extern "C" int gnnstage_debug_select_counts(gnnstage_t *st, int32_t k, int32_t *
   }
   return GNNSTAGE_OK;
 }
+GNNSTAGE_GUARD_INT
 
 extern "C" int gnnstage_layer_order(const gnnstage_t *st, int32_t layer) {
   if (!st || layer < 0 || layer >= st->s.L) return GNNSTAGE_EINVAL;
@@ -2262,7 +2272,7 @@ extern "C" int gnnstage_profile_select(gnnstage_t *st, uint32_t kind_mask) {
   return GNNSTAGE_OK;
 }
 
-extern "C" int gnnstage_profile_read(gnnstage_t *st, int32_t kind, int32_t layer, double *ms, int64_t *launches) {
+extern "C" int gnnstage_profile_read(gnnstage_t *st, int32_t kind, int32_t layer, double *ms, int64_t *launches) try {
   if (!st || kind < 0 || kind >= GNNSTAGE_NKINDS || layer >= st->s.L) return GNNSTAGE_EINVAL;
   if (hipDeviceSynchronize() != hipSuccess) return fail(st, GNNSTAGE_EHIP, "device synchronisation failed");
   st->prof.collect();
@@ -2278,11 +2288,13 @@ extern "C" int gnnstage_profile_read(gnnstage_t *st, int32_t kind, int32_t layer
   if (launches) *launches = n;
   return GNNSTAGE_OK;
 }
+GNNSTAGE_GUARD_INT
 
-extern "C" int gnnstage_profile_reset(gnnstage_t *st) {
+extern "C" int gnnstage_profile_reset(gnnstage_t *st) try {
   if (!st) return GNNSTAGE_EINVAL;
   if (hipDeviceSynchronize() != hipSuccess) return fail(st, GNNSTAGE_EHIP, "device synchronisation failed");
   st->prof.collect();
   st->prof.init(st->s.L);
   return GNNSTAGE_OK;
 }
+GNNSTAGE_GUARD_INT

@@ -9,6 +9,7 @@
 // vertex v then weighs its row length, n becomes the total weight W in alpha and in the capacity, and the balance
 // term of v is multiplied by its weight.  A part is open while it is below the capacity.
 #include <stdint.h>
+#include "guard.h"
 
 #include <cmath>
 #include <vector>
@@ -17,7 +18,7 @@
 
 extern "C" int gnnstage_partition_chunks(int64_t n, const int64_t *row_ptr, const int32_t *col_idx, int32_t n_chunks,
                                          int32_t passes, double slack, double balance, int32_t by_entries, int32_t *part,
-                                         int32_t *perm, int64_t *chunk_ptr) {
+                                         int32_t *perm, int64_t *chunk_ptr) try {
   if (n <= 0 || !row_ptr || n_chunks <= 0 || passes <= 0 || !part || !perm || !chunk_ptr) return GNNSTAGE_EINVAL;
   if (!(slack >= 1.0) || !(balance >= 0.0) || n > INT32_MAX) return GNNSTAGE_EINVAL;
   const int64_t nnz = row_ptr[n];
@@ -75,11 +76,12 @@ extern "C" int gnnstage_partition_chunks(int64_t n, const int64_t *row_ptr, cons
   for (int64_t v = 0; v < n; ++v) perm[v] = (int32_t)next[(size_t)part[v]]++;
   return GNNSTAGE_OK;
 }
+GNNSTAGE_GUARD_INT
 
 // The same graph with vertex `old` renamed perm[old]; columns ascending inside every row.  Row v of the output
 // is row inverse(v) of the input.  out_ptr: n + 1, out_idx: nnz.
 extern "C" int gnnstage_permute_csr(int64_t n, const int64_t *row_ptr, const int32_t *col_idx, const int32_t *perm,
-                                    int64_t *out_ptr, int32_t *out_idx) {
+                                    int64_t *out_ptr, int32_t *out_idx) try {
   if (n <= 0 || !row_ptr || !perm || !out_ptr || (row_ptr[n] > 0 && (!col_idx || !out_idx))) return GNNSTAGE_EINVAL;
   std::vector<int32_t> inverse((size_t)n, -1);
   for (int64_t v = 0; v < n; ++v) {
@@ -106,3 +108,4 @@ extern "C" int gnnstage_permute_csr(int64_t n, const int64_t *row_ptr, const int
   }
   return GNNSTAGE_OK;
 }
+GNNSTAGE_GUARD_INT

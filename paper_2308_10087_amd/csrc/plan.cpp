@@ -1,6 +1,7 @@
 // Host-only integer bookkeeping of the stage: transposed index, packed index words and the
 // launch schedule of an aggregation.  No GPU calls here, so all of it can be checked on a CPU.
 #include <stdint.h>
+#include "guard.h"
 
 #include <vector>
 
@@ -13,7 +14,7 @@
 #include "plan.h"
 
 extern "C" int gnnstage_plan_transpose(int64_t n, const int64_t *row_ptr, const int32_t *col_idx, int64_t *t_ptr,
-                                       int32_t *t_row, int64_t *t_edge) {
+                                       int32_t *t_row, int64_t *t_edge) try {
   if (n < 0 || !row_ptr || !t_ptr || (row_ptr[n] > 0 && (!col_idx || !t_row))) return GNNSTAGE_EINVAL;
   const int64_t nnz = row_ptr[n];
   for (int64_t i = 0; i <= n; ++i) t_ptr[i] = 0;
@@ -34,6 +35,7 @@ extern "C" int gnnstage_plan_transpose(int64_t n, const int64_t *row_ptr, const 
   }
   return GNNSTAGE_OK;
 }
+GNNSTAGE_GUARD_INT
 
 static int bits_for(int64_t count) {  // bits needed to represent ids 0 .. count-1
   int b = 0;
@@ -42,7 +44,7 @@ static int bits_for(int64_t count) {  // bits needed to represent ids 0 .. count
 }
 
 extern "C" int gnnstage_plan_pack(int64_t n, int64_t nnz, const int32_t *idx, int32_t n_chunks,
-                                  const int64_t *chunk_ptr, uint32_t *packed, int32_t *vbits_out) {
+                                  const int64_t *chunk_ptr, uint32_t *packed, int32_t *vbits_out) try {
   if (n <= 0 || nnz < 0 || n_chunks <= 0 || !chunk_ptr || !vbits_out) return GNNSTAGE_EINVAL;
   int vbits = bits_for(n);
   if (vbits < 1) vbits = 1;
@@ -64,6 +66,7 @@ extern "C" int gnnstage_plan_pack(int64_t n, int64_t nnz, const int32_t *idx, in
   }
   return GNNSTAGE_OK;
 }
+GNNSTAGE_GUARD_INT
 
 namespace {
 struct Task {
@@ -79,7 +82,7 @@ extern "C" int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, i
                                        const int64_t *class_lo, int32_t class_min_row, const uint8_t *force_slot,
                                        int64_t capacity, int32_t *task_row, int64_t *task_e0, int32_t *task_ne,
                                        int32_t *task_slot, int64_t *n_slots_out, int64_t *class_off,
-                                       uint8_t *slot_class) {
+                                       uint8_t *slot_class) try {
   if (!ptr || row_begin > row_end || split_edges <= 0 || n_classes < 1 || n_classes > 64 || n_vertices <= 0)
     return GNNSTAGE_EINVAL;
   const bool classes = n_classes > 1 && idx != nullptr;
@@ -189,6 +192,7 @@ extern "C" int64_t gnnstage_plan_tasks(const int64_t *ptr, const int32_t *idx, i
   }
   return t;
 }
+GNNSTAGE_GUARD_INT64
 
 // ---- dense blocks ------------------------------------------------------------------------------
 bool build_dense_plan(const int64_t *ptr, const int32_t *idx, int64_t n, int K, const int64_t *chunk_ptr,
@@ -370,18 +374,20 @@ static int create_dense_plan(const int64_t *ptr, const int32_t *idx, int64_t n_v
 
 extern "C" int gnnstage_dense_plan_create(const int64_t *ptr, const int32_t *idx, int64_t n_vertices, int32_t n_chunks,
                                           const int64_t *chunk_ptr, int32_t min_nnz, double min_share,
-                                          gnnstage_dense_plan **out) {
+                                          gnnstage_dense_plan **out) try {
   return create_dense_plan(ptr, idx, n_vertices, n_chunks, chunk_ptr, min_nnz, min_share, 0, 0, 0, out);
 }
+GNNSTAGE_GUARD_INT
 
 extern "C" int gnnstage_dense_plan_create_capped(const int64_t *ptr, const int32_t *idx, int64_t n_vertices, int32_t n_chunks,
                                                  const int64_t *chunk_ptr, int32_t min_nnz, double min_share, int32_t item_blocks,
-                                                 int64_t max_items, int32_t min_nnz_many, gnnstage_dense_plan **out) {
+                                                 int64_t max_items, int32_t min_nnz_many, gnnstage_dense_plan **out) try {
   if (item_blocks <= 0 || max_items <= 0 || min_nnz_many < min_nnz) return GNNSTAGE_EINVAL;
   return create_dense_plan(ptr, idx, n_vertices, n_chunks, chunk_ptr, min_nnz, min_share, item_blocks, max_items, min_nnz_many, out);
 }
+GNNSTAGE_GUARD_INT
 
-extern "C" int64_t gnnstage_dense_plan_get(const gnnstage_dense_plan *h, int32_t what, const void **data) {
+extern "C" int64_t gnnstage_dense_plan_get(const gnnstage_dense_plan *h, int32_t what, const void **data) try {
   if (!h || !data) return GNNSTAGE_EINVAL;
   const DensePlan &p = h->p;
 #define GIVE(v)                 \
@@ -407,12 +413,14 @@ extern "C" int64_t gnnstage_dense_plan_get(const gnnstage_dense_plan *h, int32_t
   }
 #undef GIVE
 }
+GNNSTAGE_GUARD_INT64
 
-extern "C" int gnnstage_dense_plan_destroy(gnnstage_dense_plan *h) {
+extern "C" int gnnstage_dense_plan_destroy(gnnstage_dense_plan *h) try {
   if (!h) return GNNSTAGE_EINVAL;
   delete h;
   return GNNSTAGE_OK;
 }
+GNNSTAGE_GUARD_INT
 
 // ---- hotness order -------------------------------------------------------------------------------
 bool build_hot_order(const int64_t *ptr, const int32_t *idx, int64_t n, int min_row, bool want_orig, HotOrder &out) {

@@ -3,6 +3,7 @@
 // last line, or Adam as in Section 5).  The stages do the heavy work through their public entry points; the
 // head reuses the library's dense products.
 #include <hip/hip_runtime.h>
+#include "guard.h"
 
 #include <algorithm>
 #include <cmath>
@@ -244,7 +245,7 @@ int launch_sum(const float *x, int64_t n, float scale, float *scratch, float *ou
 
 }  // namespace
 
-extern "C" int gnntrain_chunk_order(uint64_t seed, int64_t epoch, int32_t n_chunks, int32_t shuffle, int32_t *order) {
+extern "C" int gnntrain_chunk_order(uint64_t seed, int64_t epoch, int32_t n_chunks, int32_t shuffle, int32_t *order) try {
   if (!order || n_chunks <= 0 || epoch < 0) return GNNSTAGE_EINVAL;
   for (int i = 0; i < n_chunks; ++i) order[i] = i;
   if (!shuffle) return GNNSTAGE_OK;
@@ -260,6 +261,7 @@ extern "C" int gnntrain_chunk_order(uint64_t seed, int64_t epoch, int32_t n_chun
   }
   return GNNSTAGE_OK;
 }
+GNNSTAGE_GUARD_INT
 
 extern "C" int gnntrain_softmax_xent(const float *logits, int32_t ld, const float *bias, const int32_t *labels, const uint8_t *mask,
                                      int64_t rows, int32_t n_classes, float inv_n_train, void *dlogits, int32_t dl_dtype,
@@ -362,16 +364,17 @@ extern "C" int gnntrain_sgd_step(float *p, const float *g, void *compute, int32_
   return hipGetLastError() == hipSuccess ? GNNSTAGE_OK : GNNSTAGE_EHIP;
 }
 
-extern "C" size_t gnntrain_workspace_size(const gnntrain_desc *desc) {
+extern "C" size_t gnntrain_workspace_size(const gnntrain_desc *desc) try {
   Dims x;
   std::string err;
   if (!read_dims(desc, x, err)) return 0;
   return make_layout(desc, x).total;
 }
+GNNSTAGE_GUARD_SIZE
 
 extern "C" const char *gnntrain_last_error(const gnntrain_t *tr) { return tr ? tr->err.c_str() : g_create_error.c_str(); }
 
-extern "C" int gnntrain_create(const gnntrain_desc *d, gnntrain_t **out) {
+extern "C" int gnntrain_create(const gnntrain_desc *d, gnntrain_t **out) try {
   if (out) *out = nullptr;
   auto bad = [&](int code, const std::string &msg) {
     g_create_error = msg;
@@ -467,13 +470,15 @@ extern "C" int gnntrain_create(const gnntrain_desc *d, gnntrain_t **out) {
   *out = tr;
   return GNNSTAGE_OK;
 }
+GNNSTAGE_GUARD_INT
 
-extern "C" int gnntrain_destroy(gnntrain_t *tr) {
+extern "C" int gnntrain_destroy(gnntrain_t *tr) try {
   if (!tr) return GNNSTAGE_EINVAL;
   (void)hipDeviceSynchronize();
   delete tr;
   return GNNSTAGE_OK;
 }
+GNNSTAGE_GUARD_INT
 
 extern "C" int gnntrain_last_order(const gnntrain_t *tr, int32_t *order) {
   if (!tr || !order) return GNNSTAGE_EINVAL;
@@ -481,7 +486,7 @@ extern "C" int gnntrain_last_order(const gnntrain_t *tr, int32_t *order) {
   return GNNSTAGE_OK;
 }
 
-extern "C" int gnntrain_epoch(gnntrain_t *tr, int64_t epoch, float *loss, void *hip_stream) {
+extern "C" int gnntrain_epoch(gnntrain_t *tr, int64_t epoch, float *loss, void *hip_stream) try {
   if (!tr) return GNNSTAGE_EINVAL;
   if (epoch < 0) return fail(tr, GNNSTAGE_EINVAL, "epoch must not be negative");
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -607,3 +612,4 @@ extern "C" int gnntrain_epoch(gnntrain_t *tr, int64_t epoch, float *loss, void *
   }
   return GNNSTAGE_OK;
 }
+GNNSTAGE_GUARD_INT
