@@ -3,6 +3,7 @@
 // the matching backward pass).  All device work is issued on the caller's stream.
 #include <stdio.h>
 #include "guard.h"
+#include <memory>
 #include <stdlib.h>
 #include <string.h>
 
@@ -1317,7 +1318,8 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) try {
     return fail(nullptr, GNNSTAGE_ENOMEM, buf);
   }
 
-  gnnstage *st = new gnnstage();
+  std::unique_ptr<gnnstage> holder(new gnnstage());  // freed on every early return, and when something below throws
+  gnnstage *st = holder.get();
   st->s = s;
   st->lay = lay;
   st->vbits = vbits;
@@ -1348,10 +1350,8 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) try {
   st->h_row_ptr.assign(d->row_ptr, d->row_ptr + s.n + 1);
   if (hp.f.dense()) {  // the diagnostics walk the whole index, not the remainder
     st->h_pcol.resize((size_t)s.nnz);
-    if (gnnstage_plan_pack(s.n, s.nnz, d->col_idx, s.K, s.chunk_ptr.data(), st->h_pcol.data(), &vbits) != GNNSTAGE_OK) {
-      delete st;
+    if (gnnstage_plan_pack(s.n, s.nnz, d->col_idx, s.K, s.chunk_ptr.data(), st->h_pcol.data(), &vbits) != GNNSTAGE_OK)
       return fail(nullptr, GNNSTAGE_EINVAL, "cannot pack column indices");
-    }
   } else {
     st->h_pcol = pcol;
   }
@@ -1508,10 +1508,7 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) try {
     return GNNSTAGE_OK;
   };
 
-  auto bail = [&](int code, const std::string &msg) {
-    delete st;
-    return fail(nullptr, code, msg);
-  };
+  auto bail = [&](int code, const std::string &msg) { return fail(nullptr, code, msg); };
   if (hipMemcpy(st->at<int64_t>(lay.row_ptr), d->row_ptr, sizeof(int64_t) * (s.n + 1), hipMemcpyHostToDevice) != hipSuccess ||
       hipMemcpy(st->at<int64_t>(lay.t_ptr), t_ptr.data(), sizeof(int64_t) * (s.n + 1), hipMemcpyHostToDevice) != hipSuccess ||
       (hp.f.nnz > 0 && hipMemcpy(st->at<uint32_t>(lay.pcol), pcol.data(), sizeof(uint32_t) * hp.f.nnz, hipMemcpyHostToDevice) != hipSuccess) ||
@@ -1627,7 +1624,7 @@ extern "C" int gnnstage_create(const gnnstage_desc *d, gnnstage_t **out) try {
   if (rc == GNNSTAGE_OK) rc = build(hp.b, prow.data(), true, st->btasks);
   if (rc != GNNSTAGE_OK) return bail(rc, "building the launch schedule failed");
   if (hipDeviceSynchronize() != hipSuccess) return bail(GNNSTAGE_EHIP, "device synchronisation failed after create");
-  *out = st;
+  *out = holder.release();
   return GNNSTAGE_OK;
 }
 GNNSTAGE_GUARD_INT
