@@ -4,6 +4,7 @@
 // head reuses the library's dense products.
 #include <hip/hip_runtime.h>
 #include "guard.h"
+#include <memory>
 
 #include <algorithm>
 #include <cmath>
@@ -426,7 +427,8 @@ extern "C" int gnntrain_create(const gnntrain_desc *d, gnntrain_t **out) try {
   }
   if (n_train <= 0) return bad(GNNSTAGE_EINVAL, "no labelled vertex");
 
-  gnntrain *tr = new gnntrain();
+  std::unique_ptr<gnntrain> holder(new gnntrain());  // freed on an early return, and when something below throws
+  gnntrain *tr = holder.get();
   tr->x = x;
   tr->lay = lay;
   tr->stages.assign(d->stages, d->stages + d->n_stages);
@@ -462,12 +464,10 @@ extern "C" int gnntrain_create(const gnntrain_desc *d, gnntrain_t **out) try {
   if (tr->optimizer == GNNTRAIN_ADAM && x.n_param_elems > 0) {
     const size_t bytes = sizeof(float) * (size_t)x.n_param_elems;
     if (launch_fill_zero(tr->at<char>(lay.m), bytes, nullptr) != 0 || launch_fill_zero(tr->at<char>(lay.v), bytes, nullptr) != 0 ||
-        hipDeviceSynchronize() != hipSuccess) {
-      delete tr;
+        hipDeviceSynchronize() != hipSuccess)
       return bad(GNNSTAGE_EHIP, "clearing the optimiser state failed");
-    }
   }
-  *out = tr;
+  *out = holder.release();
   return GNNSTAGE_OK;
 }
 GNNSTAGE_GUARD_INT
