@@ -114,9 +114,10 @@ __device__ inline void store8_f32(void *p, int dtype, size_t idx, const float (&
 
 // Eight consecutive output columns n0..n0+7 of row m (all inside [0, N), every pointer involved
 // 16-byte aligned at that position: checked on the host, a.vec_epi).
-__device__ inline void epilogue_store8(const GemmNtArgs &a, int m, int n0, const float (&acc)[8]) {
+// epi: the epilogue to apply (a.epilogue, or EPI_PLAIN where the caller has applied it to the accumulators already)
+__device__ inline void epilogue_store8(const GemmNtArgs &a, int m, int n0, const float (&acc)[8], int epi) {
   float r[8], x[8];
-  switch (a.epilogue) {
+  switch (epi) {
     case EPI_FWD_GCN: {
       load8_f32(a.bias, DT_F32, (size_t)n0, x);
 #pragma unroll
@@ -148,7 +149,7 @@ __device__ inline void epilogue_store8(const GemmNtArgs &a, int m, int n0, const
 #pragma unroll
       for (int t = 0; t < 8; ++t) {
         const float y = acc[t] + b8[t] + x[t];
-        r[t] = (a.epilogue == EPI_RES || y > 0.f) ? y : 0.f;
+        r[t] = (epi == EPI_RES || y > 0.f) ? y : 0.f;
       }
       break;
     }
@@ -311,6 +312,18 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmNtArgs a) {
   constexpr int PS = 36;  // padded row stride (floats) of the 32x32 patch
   float *patch = reinterpret_cast<float *>(&As[0][0]) + wave * (32 * PS);
   static_assert(4 * 32 * PS * sizeof(float) <= sizeof(As), "staging patch must fit the A tiles");
+  // GCN forward epilogue: bias + ReLU on the accumulators, where a lane holds one column of a sub-tile (two bias
+  // values per lane), instead of a bias load in front of each of the lane's eight row-wise pieces
+  const bool gcn_fwd = a.vec_epi && a.epilogue == EPI_FWD_GCN;
+  float bias_col[2] = {0.f, 0.f};
+  if (gcn_fwd) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int n = n0 + wn + j * 32 + (lane & 31);
+      if (n < a.N) bias_col[j] = a.bias[n];
+    }
+  }
+  const int store_epi = gcn_fwd ? (int)EPI_PLAIN : (int)a.epilogue;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -318,6 +331,13 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmNtArgs a) {
       const int mt = m0 + wm + i * 32, nt = n0 + wn + j * 32;
       if (mt >= a.M || nt >= (a.out_pad > a.N ? a.out_pad : a.N)) continue;  // wave-uniform
       if (a.vec_epi) {
+        if (gcn_fwd) {
+#pragma unroll
+          for (int t = 0; t < 16; ++t) {
+            const float y = acc[i][j][t] + bias_col[j];
+            acc[i][j][t] = y > 0.f ? y : 0.f;
+          }
+        }
 #pragma unroll
         for (int t = 0; t < 16; ++t) patch[(8 * (t >> 2) + 4 * (lane >> 5) + (t & 3)) * PS + (lane & 31)] = acc[i][j][t];
         __builtin_amdgcn_wave_barrier();
@@ -332,7 +352,7 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmNtArgs a) {
             v[t] = v0[t];
             v[4 + t] = v1[t];
           }
-          if (mt + r < a.M && nt + c < a.N) epilogue_store8(a, mt + r, nt + c, v);
+          if (mt + r < a.M && nt + c < a.N) epilogue_store8(a, mt + r, nt + c, v, store_epi);
         }
         __builtin_amdgcn_wave_barrier();
       } else {
@@ -356,7 +376,8 @@ __global__ __launch_bounds__(256) void gemm_nt_bf16_kernel(const GemmNtArgs a) {
 // and walk over row tiles, and the loads of the next A tile are in flight while the current one is
 // multiplied and stored.  WN = column panels per workgroup (4: N <= 256 with 64-row tiles, 2: N <= 128
 // with 128-row tiles); KS = number of 16-wide k-steps held (Kp <= 16 * KS).
-template <int WN, int KS>
+// GCNF: the instance for the GCN forward epilogue (bias + ReLU applied to the accumulators, see below).
+template <int WN, int KS, bool GCNF>
 __global__ __launch_bounds__(256, 2) void gemm_nt_bf16_ws_kernel(const GemmNtArgs a) {
   constexpr int WR = 4 / WN, TM = 64 * WR;  // row groups, rows per tile
   constexpr int LDK = KS * 16 + 8;          // LDS row stride (elements): conflict-free 16-byte fragment reads
@@ -383,6 +404,22 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_bf16_ws_kernel(const GemmNtArg
       bfr[ks][j] = (n < a.N && k < a.Kp) ? *reinterpret_cast<const bf16x8 *>(Bt + (size_t)n * a.ldb + k) : zero8;
     }
 
+  // GCN forward epilogue (bias + ReLU): in the accumulator layout a lane holds ONE column of a 32 x 32 sub-tile, so
+  // the bias is two values per lane for the whole kernel, added (and clamped) before the sub-tile goes through the
+  // LDS patch; the store that follows is the plain one.  Loading the bias piece by piece in the row-wise layout after
+  // the patch cost a dependent load per piece: 11.2 against 9.5 ms per c4 step for the forward products.
+  // An instance of its own, so that the other epilogues do not carry its registers (with one kernel for both, the plain
+  // input-gradient products went from 7.0 to 7.5 ms per c4 step).
+  constexpr bool gcn_fwd = GCNF;
+  float bias_col[2] = {0.f, 0.f};
+  if constexpr (gcn_fwd) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int n = n_wave + j * 32 + (lane & 31);
+      if (n < a.N) bias_col[j] = a.bias[n];
+    }
+  }
+  const int store_epi = gcn_fwd ? (int)EPI_PLAIN : (int)a.epilogue;  // what the store path still has to apply
   const int n_tiles = (a.M + TM - 1) / TM;
   bf16x8 stage[NV];
   auto gload = [&](int tile) {
@@ -430,6 +467,13 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_bf16_ws_kernel(const GemmNtArg
         const int mt = m_wave + i * 32, ntc = n_wave + j * 32;
         if (mt >= a.M || ntc >= (a.out_pad > a.N ? a.out_pad : a.N)) continue;  // wave-uniform
         if (a.vec_epi) {
+          if constexpr (gcn_fwd) {
+#pragma unroll
+            for (int t = 0; t < 16; ++t) {
+              const float y = acc[t] + bias_col[j];
+              acc[t] = y > 0.f ? y : 0.f;
+            }
+          }
 #pragma unroll
           for (int hf = 0; hf < 2; ++hf) {  // accumulator elements 8*hf .. 8*hf+7 are rows 16*hf .. 16*hf+15
 #pragma unroll
@@ -445,7 +489,7 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_bf16_ws_kernel(const GemmNtArg
               v[t] = v0[t];
               v[4 + t] = v1[t];
             }
-            if (mt + 16 * hf + r < a.M && ntc + c < a.N) epilogue_store8(a, mt + 16 * hf + r, ntc + c, v);
+            if (mt + 16 * hf + r < a.M && ntc + c < a.N) epilogue_store8(a, mt + 16 * hf + r, ntc + c, v, store_epi);
             __builtin_amdgcn_wave_barrier();
           }
         } else {
@@ -466,20 +510,26 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_bf16_ws_kernel(const GemmNtArg
   }
 }
 
-template <int WN, int KS>
-static int launch_ws(const GemmNtArgs &a, hipStream_t s) {
+template <int WN, int KS, bool GCNF>
+static int launch_ws_k(const GemmNtArgs &a, hipStream_t s) {
   constexpr int TM = 64 * (4 / WN), LDK = KS * 16 + 8;
   const size_t smem = (size_t)2 * TM * LDK * sizeof(bf16_t) + (size_t)4 * 16 * 36 * sizeof(float);
   static bool attr_done = false;
   if (!attr_done) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_nt_bf16_ws_kernel<WN, KS>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_nt_bf16_ws_kernel<WN, KS, GCNF>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     attr_done = true;
   }
   const int n_tiles = (a.M + TM - 1) / TM;
   const int blocks = n_tiles < 512 ? n_tiles : 512;  // two persistent workgroups per compute unit
-  hipLaunchKernelGGL((gemm_nt_bf16_ws_kernel<WN, KS>), dim3(blocks), dim3(256), smem, s, a);
+  hipLaunchKernelGGL((gemm_nt_bf16_ws_kernel<WN, KS, GCNF>), dim3(blocks), dim3(256), smem, s, a);
   return (int)hipGetLastError();
+}
+
+template <int WN, int KS>
+static int launch_ws(const GemmNtArgs &a, hipStream_t s) {
+  if (a.epilogue == EPI_FWD_GCN && a.vec_epi) return launch_ws_k<WN, KS, true>(a, s);
+  return launch_ws_k<WN, KS, false>(a, s);
 }
 
 // ------------------------------------------------------------------------------------ bf16 TN
