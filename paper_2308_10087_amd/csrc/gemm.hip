@@ -382,7 +382,9 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_bf16_ws_kernel(const GemmNtArg
   constexpr int WR = 4 / WN, TM = 64 * WR;  // row groups, rows per tile
   constexpr int LDK = KS * 16 + 8;          // LDS row stride (elements): conflict-free 16-byte fragment reads
   constexpr int NV = TM * (KS * 2) / 256;   // 16-byte vectors of an A tile per thread
-  constexpr int PS = 36;                    // padded row stride (floats) of a 16x32 staging patch
+  constexpr int PS = 40;                    // padded row stride (floats) of a 16x32 staging patch
+  constexpr int PB = 40;                    // padded row stride (bf16) of the 32x32 patch of the plain bf16 store
+  static_assert(32 * PB * sizeof(bf16_t) <= 16 * PS * sizeof(float), "the bf16 patch reuses the fp32 patch's memory");
   extern __shared__ __attribute__((aligned(16))) unsigned char ws_smem[];
   bf16_t *As = reinterpret_cast<bf16_t *>(ws_smem);                                 // [2][TM * LDK]
   float *patches = reinterpret_cast<float *>(ws_smem + (size_t)2 * TM * LDK * 2);  // [4][16 * PS]
@@ -420,6 +422,12 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_bf16_ws_kernel(const GemmNtArg
     }
   }
   const int store_epi = gcn_fwd ? (int)EPI_PLAIN : (int)a.epilogue;  // what the store path still has to apply
+  // Plain bf16 stores (the GCN forward product after the lines above, the GCN input-gradient product): the sub-tile is
+  // rounded to bf16 in the accumulator layout and passes through LDS whole, as 2-byte elements; a lane then reads and
+  // stores two 16-byte row pieces.  Half as many write - wait - read round trips per tile as the general path below,
+  // which was the largest part of a tile's time (clock reads in an instrumented build: of 5.2 us per 64-row tile 1.75
+  // were the matrix chains, 2.8 the stores, 0.7 barriers and staging).
+  const bool plain_bf16 = a.vec_epi && store_epi == EPI_PLAIN && a.out_dtype == DT_BF16;
   const int n_tiles = (a.M + TM - 1) / TM;
   bf16x8 stage[NV];
   auto gload = [&](int tile) {
@@ -474,6 +482,21 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_bf16_ws_kernel(const GemmNtArg
               acc[t] = y > 0.f ? y : 0.f;
             }
           }
+          if (plain_bf16) {
+            bf16_t *bp = reinterpret_cast<bf16_t *>(patch);
+#pragma unroll
+            for (int t = 0; t < 16; ++t) bp[(8 * (t >> 2) + 4 * (lane >> 5) + (t & 3)) * PB + (lane & 31)] = (bf16_t)acc[t];
+            __builtin_amdgcn_wave_barrier();
+            bf16_t *outp = static_cast<bf16_t *>(a.out);
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+              const int r = (lane >> 2) + 16 * hf, c = (lane & 3) * 8;
+              const bf16x8 v = *reinterpret_cast<const bf16x8 *>(&bp[r * PB + c]);
+              if (mt + r < a.M && ntc + c < a.N) *reinterpret_cast<bf16x8 *>(outp + (size_t)(mt + r) * a.out_ld + ntc + c) = v;
+            }
+            __builtin_amdgcn_wave_barrier();
+            continue;
+          }
 #pragma unroll
           for (int hf = 0; hf < 2; ++hf) {  // accumulator elements 8*hf .. 8*hf+7 are rows 16*hf .. 16*hf+15
 #pragma unroll
@@ -513,7 +536,7 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_bf16_ws_kernel(const GemmNtArg
 template <int WN, int KS, bool GCNF>
 static int launch_ws_k(const GemmNtArgs &a, hipStream_t s) {
   constexpr int TM = 64 * (4 / WN), LDK = KS * 16 + 8;
-  const size_t smem = (size_t)2 * TM * LDK * sizeof(bf16_t) + (size_t)4 * 16 * 36 * sizeof(float);
+  const size_t smem = (size_t)2 * TM * LDK * sizeof(bf16_t) + (size_t)4 * 16 * 40 * sizeof(float);
   static bool attr_done = false;
   if (!attr_done) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_nt_bf16_ws_kernel<WN, KS, GCNF>),
