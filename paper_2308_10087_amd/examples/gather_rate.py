@@ -29,6 +29,8 @@ def main():
         # the benchmark's largest graph: 10 M rows, 37 % of the gathers to the 65,536 hottest, 58 % to the 262,144 hottest
         for hot_rows, share in ((65536, 0.37), (262144, 0.58), (524288, 0.71)):
             mb = max(sizes)
+            if hot_rows >= (mb << 20) // rb:  # the table given on the command line is smaller than this hot set
+                continue
             r = g.gnnstage_debug_gather_rate(table, (mb << 20) // rb, rb, int(args.gather_gb * 1e9 / rb), hot_rows=hot_rows, hot_share=share, mode=args.mode)
             print(f"{mb:8d} | {rb:9d} | {hot_rows:8d} | {share:9.2f} | {r / 1e9:10.0f}", flush=True)
 
